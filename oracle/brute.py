@@ -1,0 +1,143 @@
+"""Brute-force twin of the oracle for tiny inputs.  TEST INFRASTRUCTURE ONLY.
+
+Everything is recomputed from the raw problem arrays by literal summation over operators and
+literal enumeration of all ways to cut the operator sequence (no tables, no recurrence, nothing
+shared with `harp_oracle.c`), in Python's unbounded integers.  It exists to pin the C oracle.
+
+Stage cost, transfer cost and memory rule follow the paper's section 5.2.2 / 5.2.3 constraints
+(i)-(iii) under the integer readings stated at the top of `harp_oracle.c`.
+"""
+from __future__ import annotations
+
+from itertools import combinations
+
+INF = (1 << 63) - 1
+
+
+def _cdiv(a: int, b: int) -> int:
+    return -((-a) // b)
+
+
+def stage_time(p, g: int, tp: int, j: int, i: int) -> int:
+    t = int(p.group_type[g])
+    work = sum(int(p.fwd_us[t][l]) + int(p.bwd_us[t][l]) for l in range(j, i))
+    ar = 0
+    if tp > 1:
+        for l in range(j, i):
+            ar += _cdiv(int(p.ar_count) * 2 * (tp - 1) * int(p.act_bytes[l]), tp * int(p.bw[g][g]))
+    return _cdiv(work, tp) + ar
+
+
+def cut_time(p, g: int, h: int, i: int) -> int:
+    return _cdiv(int(p.act_bytes[i - 1]), int(p.bw[g][h]))
+
+
+def memory_fits(p, g: int, tp: int, n: int, j: int, i: int) -> bool:
+    par = sum(int(p.param_bytes[l]) for l in range(j, i))
+    sta = sum(int(p.stash_bytes[l]) for l in range(j, i))
+    return par + n * sta <= tp * int(p.type_mem_bytes[int(p.group_type[g])])
+
+
+def stage_cost(p, S: int, grp, tp, s: int, j: int, i: int) -> int:
+    """w(s; j, i): INF if the stage does not fit, else max(stage time, transfer after it)."""
+    n = min(S - s, int(p.M))
+    if not memory_fits(p, int(grp[s]), int(tp[s]), n, j, i):
+        return INF
+    c = 0 if s == S - 1 else cut_time(p, int(grp[s]), int(grp[s + 1]), i)
+    return max(stage_time(p, int(grp[s]), int(tp[s]), j, i), c)
+
+
+def valid(p, S: int, S_max: int, grp, tp) -> bool:
+    if not 1 <= S <= S_max:
+        return False
+    allowed = set(int(x) for x in p.tp_degrees)
+    used, order = {}, []
+    for s in range(S):
+        g, d = int(grp[s]), int(tp[s])
+        if not (0 <= g < p.G) or d not in allowed:
+            return False
+        if order and order[-1] != g and g in order:
+            return False
+        order.append(g)
+        used[g] = used.get(g, 0) + d
+        if used[g] > int(p.group_ndev[g]):
+            return False
+    return True
+
+
+def partitions(n_items: int, n_parts: int):
+    """All cut vectors (0, b_1, ..., n_items) with n_parts non-empty parts."""
+    for mids in combinations(range(1, n_items), n_parts - 1):
+        yield (0,) + mids + (n_items,)
+
+
+def opt(p, S: int, grp, tp, s: int, i: int) -> int:
+    """Smallest bottleneck of the first i operators on slots 0..s-1, by enumeration."""
+    if s == 0:
+        return 0 if i == 0 else INF
+    if i < s:
+        return INF
+    best = INF
+    for b in partitions(i, s):
+        worst = 0
+        for q in range(s):
+            w = stage_cost(p, S, grp, tp, q, b[q], b[q + 1])
+            worst = max(worst, w)
+            if worst == INF:
+                break
+        best = min(best, worst)
+    return best
+
+
+def score(p, S: int, grp, tp, b):
+    """(bottleneck, iteration time) of a feasible partition: sum(t + 2c) + (M - 1) bottleneck."""
+    worst, single = 0, 0
+    for s in range(S):
+        t = stage_time(p, int(grp[s]), int(tp[s]), b[s], b[s + 1])
+        c = 0 if s == S - 1 else cut_time(p, int(grp[s]), int(grp[s + 1]), b[s + 1])
+        worst = max(worst, t, c)
+        single += t + 2 * c
+    return worst, single + (int(p.M) - 1) * worst
+
+
+def plan(p, S: int, S_max: int, grp, tp):
+    """Status, cut vector, bottleneck, iteration time of the reported plan.
+
+    Reported plan: b_S = L; going down, b_s is the smallest j for which the best bottleneck of
+    the first j operators on s slots, combined with stage s over [j, b_{s+1}), attains the best
+    bottleneck of the first b_{s+1} operators on s+1 slots.
+    """
+    L = int(p.L)
+    if not valid(p, S, S_max, grp, tp):
+        return 2, None, INF, INF
+    if S > L or opt(p, S, grp, tp, S, L) == INF:
+        return 1, None, INF, INF
+    b = [0] * (S + 1)
+    b[S] = L
+    for s in range(S - 1, -1, -1):
+        target = opt(p, S, grp, tp, s + 1, b[s + 1])
+        for j in range(s, b[s + 1]):
+            left = opt(p, S, grp, tp, s, j)
+            if left == INF:
+                continue
+            if max(left, stage_cost(p, S, grp, tp, s, j, b[s + 1])) == target:
+                b[s] = j
+                break
+        else:
+            raise AssertionError("no predecessor attains the optimum")
+    bott, it = score(p, S, grp, tp, b)
+    assert bott == opt(p, S, grp, tp, S, L)
+    return 0, b, bott, it
+
+
+def best_iteration_time(p, S: int, S_max: int, grp, tp):
+    """Exhaustive optimum of eq. gpipe_cost_model over every feasible partition (T* of the
+    candidate), with t_max taken as the partition's own max over stage and transfer times."""
+    if not valid(p, S, S_max, grp, tp) or S > int(p.L):
+        return INF
+    best = INF
+    for b in partitions(int(p.L), S):
+        if any(stage_cost(p, S, grp, tp, s, b[s], b[s + 1]) == INF for s in range(S)):
+            continue
+        best = min(best, score(p, S, grp, tp, b)[1])
+    return best

@@ -1,0 +1,346 @@
+/*
+ * CPU oracle for the inter-operator planner search of HARP (paper section 5.2).
+ *
+ * TEST INFRASTRUCTURE ONLY.  Plain, slow, single-threaded C written from the paper's statement of
+ * the planning problem.  It shares no code with the HIP library and must never be reachable from
+ * the product path: only the tests, the smoke check and the benchmark's cpu_baseline leg call it.
+ *
+ * What is computed, for every candidate (an ordered list of S slots, slot s = tp_s devices of
+ * device group g_s):
+ *
+ *   - the stage partition 0 = b_0 < b_1 < ... < b_S = L of the operator sequence that minimises
+ *     the largest per-stage cost  max_s max(time_s, comm_s)  subject to the per-device memory
+ *     limit.  This is the smallest feasible bottleneck t_max of section 5.2.4 (2) for the DP of
+ *     section 5.2.3 (eq. dp_general) with the submesh of each stage fixed by the candidate, and
+ *     with constraints (i) stage time <= t_max, (ii) C(j) <= t_max and (iii) eq. mem_cons.
+ *   - the iteration time of that plan under the cost model of section 5.2.2
+ *     (eq. gpipe_cost_model):  sum_s (t_s + 2 c_s) + (B - 1) t_max,  B = number of microbatches.
+ *
+ * Readings where the paper leaves the model open (all integer, microseconds and bytes):
+ *   t_s   = ceil(sum of (fwd+bwd) over the stage's operators on the group's GPU type / tp)
+ *           + sum over the stage's operators of the tensor-parallel all-reduce time
+ *             ceil(ar_count * 2 (tp-1) * act_bytes[l] / (tp * bw[g][g]))      (0 when tp == 1)
+ *   c_s   = ceil(act_bytes[b_{s+1}-1] / bw[g_s][g_{s+1}])   for s < S-1, 0 for the last stage
+ *   mem   : sum(param_bytes) + N_s * sum(stash_bytes) <= tp * type_mem_bytes, with the classic
+ *           1F1B in-flight count N_s = min(S - s, B)  (section 2.1: stage i of S keeps S-i+1)
+ *   ties  : the recurrence scans the previous cut j in increasing order and keeps the first j that
+ *           attains the minimum, so the lowest j wins.
+ *
+ * Every loop below is the definition written out: no blocking, no pruning, no reordering.
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define ORACLE_INF INT64_MAX
+
+enum { ORACLE_OK = 0, ORACLE_BAD_ARG = -1, ORACLE_OVERFLOW = -5 };
+enum { CAND_OK = 0, CAND_INFEASIBLE = 1, CAND_INVALID = 2 };
+
+typedef struct {
+    int32_t L, T, G, M, ar_count, n_tp;
+    const int32_t *tp_degrees;      /* [n_tp] ascending, first is 1 */
+    const int64_t *fwd_us, *bwd_us; /* [T][L] */
+    const int64_t *param_bytes, *stash_bytes, *act_bytes; /* [L] */
+    const int32_t *group_type, *group_ndev;               /* [G] */
+    const int64_t *type_mem_bytes;                        /* [T] */
+    const int64_t *bw;                                    /* [G][G] bytes per microsecond */
+} oracle_problem;
+
+typedef __int128 wide;
+
+static const wide LIMIT63 = (((wide)1) << 63) - 1;
+static const wide LIMIT47 = (((wide)1) << 47);
+
+static int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+static int64_t max64(int64_t a, int64_t b) { return a > b ? a : b; }
+
+/* Tables of running sums, index i = 0..L, entry 0 is 0.
+ *   PF[t][i]      sum_{l<i} fwd_us[t][l] + bwd_us[t][l]
+ *   PP[i], PS[i]  sum_{l<i} param_bytes[l], stash_bytes[l]
+ *   PR[g][k][i]   sum_{l<i} all-reduce time of operator l at degree tp_degrees[k] inside group g
+ * Returns ORACLE_OVERFLOW when the inputs leave the range in which every later quantity is known
+ * to fit in int64 (magnitude preconditions of the library), ORACLE_BAD_ARG for malformed input. */
+int oracle_build_tables(const oracle_problem *p, int64_t *PF, int64_t *PP, int64_t *PS, int64_t *PR)
+{
+    const int L = p->L, T = p->T, G = p->G, K = p->n_tp;
+    if (L < 1 || L > 65535 || T < 1 || G < 1 || p->M < 1 || K < 1 || K > 8 || p->ar_count < 0)
+        return ORACLE_BAD_ARG;
+    if (p->tp_degrees[0] != 1) return ORACLE_BAD_ARG;
+    for (int k = 1; k < K; ++k)
+        if (p->tp_degrees[k] <= p->tp_degrees[k - 1]) return ORACLE_BAD_ARG;
+    for (int g = 0; g < G; ++g) {
+        if (p->group_type[g] < 0 || p->group_type[g] >= T || p->group_ndev[g] < 1) return ORACLE_BAD_ARG;
+        for (int h = 0; h < G; ++h)
+            if (p->bw[g * G + h] < 1) return ORACLE_BAD_ARG;
+    }
+    for (int t = 0; t < T; ++t) {
+        if (p->type_mem_bytes[t] < 0) return ORACLE_BAD_ARG;
+        for (int l = 0; l < L; ++l)
+            if (p->fwd_us[t * L + l] < 0 || p->bwd_us[t * L + l] < 0) return ORACLE_BAD_ARG;
+    }
+    for (int l = 0; l < L; ++l)
+        if (p->param_bytes[l] < 0 || p->stash_bytes[l] < 0 || p->act_bytes[l] < 0) return ORACLE_BAD_ARG;
+
+    const int64_t tp_max = p->tp_degrees[K - 1];
+    wide worst = 0; /* largest stage time or transfer time any plan can see */
+
+    for (int t = 0; t < T; ++t) {
+        wide acc = 0;
+        PF[t * (L + 1)] = 0;
+        for (int l = 0; l < L; ++l) {
+            acc += (wide)p->fwd_us[t * L + l] + (wide)p->bwd_us[t * L + l];
+            if (acc > LIMIT63) return ORACLE_OVERFLOW;
+            PF[t * (L + 1) + l + 1] = (int64_t)acc;
+        }
+    }
+    {
+        wide ap = 0, as = 0;
+        PP[0] = 0; PS[0] = 0;
+        for (int l = 0; l < L; ++l) {
+            ap += p->param_bytes[l];
+            as += p->stash_bytes[l];
+            if (ap > LIMIT63 || as > LIMIT63) return ORACLE_OVERFLOW;
+            PP[l + 1] = (int64_t)ap;
+            PS[l + 1] = (int64_t)as;
+        }
+        /* memory need of any segment with any in-flight count, and the limit it is compared to */
+        int64_t n_max = p->M < L ? p->M : L;
+        if (ap + (wide)n_max * as > LIMIT63) return ORACLE_OVERFLOW;
+        for (int t = 0; t < T; ++t)
+            if ((wide)tp_max * p->type_mem_bytes[t] > LIMIT63) return ORACLE_OVERFLOW;
+    }
+    for (int g = 0; g < G; ++g) {
+        const int64_t b = p->bw[g * G + g];
+        for (int k = 0; k < K; ++k) {
+            const int64_t tp = p->tp_degrees[k];
+            int64_t *row = PR + ((size_t)(g * K + k)) * (L + 1);
+            wide acc = 0;
+            row[0] = 0;
+            for (int l = 0; l < L; ++l) {
+                if (tp > 1) {
+                    wide num = (wide)p->ar_count * 2 * (tp - 1) * p->act_bytes[l];
+                    wide den = (wide)tp * b;
+                    if (num > LIMIT63 || den > LIMIT63) return ORACLE_OVERFLOW;
+                    acc += (num + den - 1) / den;
+                }
+                if (acc > LIMIT63) return ORACLE_OVERFLOW;
+                row[l + 1] = (int64_t)acc;
+            }
+            wide whole = (wide)PF[p->group_type[g] * (L + 1) + L] + acc;
+            if (whole > worst) worst = whole;
+        }
+    }
+    for (int l = 0; l < L; ++l)
+        for (int gh = 0; gh < G * G; ++gh) {
+            wide c = ((wide)p->act_bytes[l] + p->bw[gh] - 1) / p->bw[gh];
+            if (c > worst) worst = c;
+        }
+    if (worst >= LIMIT47) return ORACLE_OVERFLOW;
+    /* iteration time: at most L stage times, 2 (L-1) transfers and (M-1) bottlenecks */
+    if (worst * ((wide)3 * L + p->M) > LIMIT63) return ORACLE_OVERFLOW;
+    return ORACLE_OK;
+}
+
+typedef struct {
+    const oracle_problem *p;
+    const int64_t *PF, *PP, *PS, *PR;
+} tables_view;
+
+static int tp_index(const oracle_problem *p, int tp)
+{
+    for (int k = 0; k < p->n_tp; ++k)
+        if (p->tp_degrees[k] == tp) return k;
+    return -1;
+}
+
+/* Candidate well-formedness: stage count in range, groups in range, degrees allowed, slots of a
+ * group adjacent, no group over-subscribed. */
+static int candidate_valid(const oracle_problem *p, int S, int S_max, const int32_t *grp, const int32_t *tp)
+{
+    if (S < 1 || S > S_max) return 0;
+    int ok = 1;
+    int64_t *used = (int64_t *)calloc((size_t)p->G, sizeof(int64_t));
+    char *closed = (char *)calloc((size_t)p->G, 1);
+    for (int s = 0; s < S && ok; ++s) {
+        int g = grp[s];
+        if (g < 0 || g >= p->G || tp[s] < 1 || tp_index(p, tp[s]) < 0) { ok = 0; break; }
+        if (closed[g]) { ok = 0; break; }
+        used[g] += tp[s];
+        if (used[g] > p->group_ndev[g]) { ok = 0; break; }
+        if (s + 1 < S && grp[s + 1] != g) closed[g] = 1;
+    }
+    free(used);
+    free(closed);
+    return ok;
+}
+
+/* Stage time t_s of operators [j, i) on slot (g, tp). */
+static int64_t stage_time(const tables_view *v, int g, int tp, int j, int i)
+{
+    const oracle_problem *p = v->p;
+    const int L = p->L;
+    const int64_t *pf = v->PF + (size_t)p->group_type[g] * (L + 1);
+    const int64_t *pr = v->PR + ((size_t)(g * p->n_tp + tp_index(p, tp))) * (L + 1);
+    return ceil_div(pf[i] - pf[j], tp) + (pr[i] - pr[j]);
+}
+
+/* Transfer time c_s of the cut placed before operator i, from group g to group h. */
+static int64_t cut_time(const oracle_problem *p, int g, int h, int i)
+{
+    return ceil_div(p->act_bytes[i - 1], p->bw[g * p->G + h]);
+}
+
+/* eq. mem_cons with parameters and activations sharded evenly over the tp devices of the slot:
+ * (params + n * stash) / tp <= device memory, compared without dividing. */
+static int memory_fits(const tables_view *v, int g, int tp, int64_t n_inflight, int j, int i)
+{
+    const oracle_problem *p = v->p;
+    int64_t need = (v->PP[i] - v->PP[j]) + n_inflight * (v->PS[i] - v->PS[j]);
+    return need <= (int64_t)tp * p->type_mem_bytes[p->group_type[g]];
+}
+
+static void fill_failed(int S_max, int32_t *splits, int32_t *dev_first, int64_t *bott, int64_t *iter)
+{
+    for (int s = 0; s <= S_max; ++s) splits[s] = -1;
+    for (int s = 0; s < S_max; ++s) dev_first[s] = -1;
+    *bott = ORACLE_INF;
+    *iter = ORACLE_INF;
+}
+
+/* First global device id of every slot: groups are numbered consecutively in group-id order and a
+ * group's slots take its devices in slot order. */
+static void slot_devices(const oracle_problem *p, int S, int S_max, const int32_t *grp, const int32_t *tp,
+                         int32_t *dev_first)
+{
+    for (int s = 0; s < S_max; ++s) dev_first[s] = -1;
+    for (int s = 0; s < S; ++s) {
+        int32_t base = 0;
+        for (int g = 0; g < grp[s]; ++g) base += p->group_ndev[g];
+        for (int q = 0; q < s; ++q)
+            if (grp[q] == grp[s]) base += tp[q];
+        dev_first[s] = base;
+    }
+}
+
+/* Cost model of section 5.2.2 for a given partition.  Returns the candidate status. */
+static int score_partition(const tables_view *v, int S, const int32_t *grp, const int32_t *tp,
+                           const int32_t *b, int64_t *bott, int64_t *iter)
+{
+    const oracle_problem *p = v->p;
+    if (b[0] != 0 || b[S] != p->L) return CAND_INVALID;
+    for (int s = 0; s < S; ++s)
+        if (b[s + 1] <= b[s]) return CAND_INVALID;
+    int64_t worst = 0, single = 0;
+    for (int s = 0; s < S; ++s) {
+        int64_t n = (S - s) < p->M ? (S - s) : p->M;
+        if (!memory_fits(v, grp[s], tp[s], n, b[s], b[s + 1])) return CAND_INFEASIBLE;
+        int64_t t = stage_time(v, grp[s], tp[s], b[s], b[s + 1]);
+        int64_t c = (s == S - 1) ? 0 : cut_time(p, grp[s], grp[s + 1], b[s + 1]);
+        worst = max64(worst, max64(t, c));
+        single += t + 2 * c;
+    }
+    *bott = worst;
+    *iter = single + (int64_t)(p->M - 1) * worst;
+    return CAND_OK;
+}
+
+/* One candidate: min-max recurrence over stages, back-pointers, backtrack, score. */
+static int plan_one(const tables_view *v, int S, int S_max, const int32_t *grp, const int32_t *tp,
+                    int64_t *D_prev, int64_t *D_next, int32_t *arg,
+                    int32_t *splits, int32_t *dev_first, int64_t *bott, int64_t *iter)
+{
+    const oracle_problem *p = v->p;
+    const int L = p->L;
+    fill_failed(S_max, splits, dev_first, bott, iter);
+    if (!candidate_valid(p, S, S_max, grp, tp)) return CAND_INVALID;
+    if (S > L) return CAND_INFEASIBLE;
+
+    for (int i = 0; i <= L; ++i) D_prev[i] = ORACLE_INF;
+    D_prev[0] = 0;
+    for (int s = 0; s < S; ++s) {
+        const int64_t n = (S - s) < p->M ? (S - s) : p->M;
+        int32_t *arg_row = arg + (size_t)(s + 1) * (L + 1);
+        for (int i = 0; i <= L; ++i) { D_next[i] = ORACLE_INF; arg_row[i] = -1; }
+        /* stage s ends at cut i; the S-1-s later stages each need one operator */
+        for (int i = s + 1; i <= L - (S - 1 - s); ++i) {
+            if (s == S - 1 && i != L) continue;
+            const int64_t c = (s == S - 1) ? 0 : cut_time(p, grp[s], grp[s + 1], i);
+            int64_t best = ORACLE_INF;
+            int32_t best_j = -1;
+            for (int j = s; j < i; ++j) {
+                if (D_prev[j] == ORACLE_INF) continue;
+                if (!memory_fits(v, grp[s], tp[s], n, j, i)) continue;
+                int64_t val = max64(D_prev[j], max64(stage_time(v, grp[s], tp[s], j, i), c));
+                if (val < best) { best = val; best_j = j; }
+            }
+            D_next[i] = best;
+            arg_row[i] = best_j;
+        }
+        int64_t *tmp = D_prev; D_prev = D_next; D_next = tmp;
+    }
+    if (D_prev[L] == ORACLE_INF) return CAND_INFEASIBLE;
+
+    splits[S] = L;
+    for (int s = S - 1; s >= 0; --s)
+        splits[s] = arg[(size_t)(s + 1) * (L + 1) + splits[s + 1]];
+    slot_devices(p, S, S_max, grp, tp, dev_first);
+    int st = score_partition(v, S, grp, tp, splits, bott, iter);
+    if (st != CAND_OK || *bott != D_prev[L]) abort(); /* the plan found must score to the DP value */
+    return CAND_OK;
+}
+
+/* Plans candidates c_begin..c_end-1 of a batch; outputs are indexed by absolute candidate. */
+int oracle_plan_batch(const oracle_problem *p, const int64_t *PF, const int64_t *PP, const int64_t *PS,
+                      const int64_t *PR, int32_t C, int32_t S_max, const int32_t *cand_S,
+                      const int32_t *cand_group, const int32_t *cand_tp, int32_t c_begin, int32_t c_end,
+                      int32_t *splits, int32_t *dev_first, int64_t *bottleneck, int64_t *iter_time,
+                      int32_t *status)
+{
+    if (C < 0 || S_max < 1 || c_begin < 0 || c_end > C || c_begin > c_end) return ORACLE_BAD_ARG;
+    const int L = p->L;
+    tables_view v = { p, PF, PP, PS, PR };
+    int64_t *D0 = (int64_t *)malloc(sizeof(int64_t) * (size_t)(L + 1));
+    int64_t *D1 = (int64_t *)malloc(sizeof(int64_t) * (size_t)(L + 1));
+    int32_t *arg = (int32_t *)malloc(sizeof(int32_t) * (size_t)(S_max + 1) * (size_t)(L + 1));
+    if (!D0 || !D1 || !arg) { free(D0); free(D1); free(arg); return ORACLE_BAD_ARG; }
+    for (int32_t c = c_begin; c < c_end; ++c) {
+        status[c] = plan_one(&v, cand_S[c], S_max, cand_group + (size_t)c * S_max, cand_tp + (size_t)c * S_max,
+                             D0, D1, arg, splits + (size_t)c * (S_max + 1), dev_first + (size_t)c * S_max,
+                             bottleneck + c, iter_time + c);
+    }
+    free(D0); free(D1); free(arg);
+    return ORACLE_OK;
+}
+
+/* Scores caller-chosen partitions (eq. gpipe_cost_model); splits[c] holds b_0..b_S. */
+int oracle_score_1f1b(const oracle_problem *p, const int64_t *PF, const int64_t *PP, const int64_t *PS,
+                      const int64_t *PR, int32_t C, int32_t S_max, const int32_t *cand_S,
+                      const int32_t *cand_group, const int32_t *cand_tp, const int32_t *splits,
+                      int64_t *bottleneck, int64_t *iter_time, int32_t *status)
+{
+    if (C < 0 || S_max < 1) return ORACLE_BAD_ARG;
+    tables_view v = { p, PF, PP, PS, PR };
+    for (int32_t c = 0; c < C; ++c) {
+        const int32_t *grp = cand_group + (size_t)c * S_max, *tp = cand_tp + (size_t)c * S_max;
+        bottleneck[c] = ORACLE_INF;
+        iter_time[c] = ORACLE_INF;
+        if (!candidate_valid(p, cand_S[c], S_max, grp, tp)) { status[c] = CAND_INVALID; continue; }
+        int64_t b = ORACLE_INF, t = ORACLE_INF;
+        status[c] = score_partition(&v, cand_S[c], grp, tp, splits + (size_t)c * (S_max + 1), &b, &t);
+        if (status[c] == CAND_OK) { bottleneck[c] = b; iter_time[c] = t; }
+    }
+    return ORACLE_OK;
+}
+
+/* Final selection over the batch: smallest iteration time among feasible candidates, lowest
+ * candidate index on ties; index -1 and time INF when none is feasible. */
+int oracle_argmin_batch(int32_t C, const int64_t *iter_time, const int32_t *status,
+                        int64_t *best_time, int32_t *best_index)
+{
+    *best_time = ORACLE_INF;
+    *best_index = -1;
+    for (int32_t c = 0; c < C; ++c)
+        if (status[c] == CAND_OK && iter_time[c] < *best_time) { *best_time = iter_time[c]; *best_index = c; }
+    return ORACLE_OK;
+}

@@ -1,0 +1,56 @@
+"""Small constructors shared by the tests (inputs only, no planner arithmetic)."""
+import numpy as np
+
+from paper_2509_24859_amd.workloads import Candidates, Problem
+
+BIG = 1 << 40
+
+
+def simple_problem(costs, M=1, T=1, G=1, ndev=(1,), tp=(1,), act=None, params=None, stash=None,
+                   mem=None, bw=None, gtype=None, fwd=None, bwd=None, ar_count=4):
+    """Problem whose operator l costs costs[l] (forward+backward, all in the forward entry)."""
+    costs = np.asarray(costs, dtype=np.int64)
+    L = costs.shape[-1]
+    if fwd is None:
+        fwd = np.tile(costs, (T, 1)) if costs.ndim == 1 else costs
+        bwd = np.zeros_like(fwd)
+    z = np.zeros(L, dtype=np.int64)
+    return Problem(
+        L=L, T=T, G=G, M=M, ar_count=ar_count, tp_degrees=np.asarray(tp, dtype=np.int32),
+        fwd_us=np.ascontiguousarray(fwd, dtype=np.int64),
+        bwd_us=np.ascontiguousarray(bwd, dtype=np.int64),
+        param_bytes=z.copy() if params is None else np.asarray(params, dtype=np.int64),
+        stash_bytes=z.copy() if stash is None else np.asarray(stash, dtype=np.int64),
+        act_bytes=z.copy() if act is None else np.asarray(act, dtype=np.int64),
+        group_type=np.zeros(G, dtype=np.int32) if gtype is None else np.asarray(gtype, np.int32),
+        group_ndev=np.asarray(ndev, dtype=np.int32),
+        type_mem_bytes=np.full(T, BIG, dtype=np.int64) if mem is None else np.asarray(mem, np.int64),
+        bw=np.full((G, G), 1, dtype=np.int64) if bw is None else np.asarray(bw, dtype=np.int64))
+
+
+def cands_from_lists(slot_lists, S_max=None):
+    """slot_lists: per candidate a list of (group, tp)."""
+    S_max = max(len(s) for s in slot_lists) if S_max is None else S_max
+    C = len(slot_lists)
+    cg = np.full((C, S_max), -1, dtype=np.int32)
+    ct = np.zeros((C, S_max), dtype=np.int32)
+    cs = np.zeros(C, dtype=np.int32)
+    for c, sl in enumerate(slot_lists):
+        cs[c] = len(sl)
+        for s, (g, t) in enumerate(sl[:S_max]):
+            cg[c, s], ct[c, s] = g, t
+    return Candidates(C, S_max, cs, cg, ct)
+
+
+def same_slot(S, g=0, tp=1):
+    return [(g, tp)] * S
+
+
+def read_golden(path):
+    rows = []
+    with open(path) as f:
+        for line in f:
+            line = line.strip()
+            if line and not line.startswith("#"):
+                rows.append(line)
+    return rows

@@ -1,0 +1,450 @@
+"""Pins of the CPU oracle against things other than itself (CPU only).
+
+The oracle (oracle/harp_oracle.c) is checked against: hand-worked fixtures, brute-force
+enumeration of every partition from the raw inputs, an independent algorithm for the textbook
+linear-partition special case, closed forms for uniform operators, and invariants of the model.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from oracle import brute
+from paper_2509_24859_amd import workloads as W
+
+from helpers import BIG, cands_from_lists, read_golden, same_slot, simple_problem
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def plan(problem, cands):
+    return oracle.plan_batch(oracle.build_tables(problem), cands)
+
+
+# ---------------------------------------------------------------- fixtures worked by hand
+
+def test_hand_examples():
+    for row in read_golden(os.path.join(GOLD, "hand_examples.txt")):
+        costs, S, M, splits, bott, it = [f.strip() for f in row.split("|")]
+        costs = [int(x) for x in costs.split()]
+        S, M = int(S), int(M)
+        p = simple_problem(costs, M=M, ndev=(S,))
+        out = plan(p, cands_from_lists([same_slot(S)]))
+        assert out.status[0] == oracle.OK
+        assert list(out.splits[0, :S + 1]) == [int(x) for x in splits.split()]
+        assert out.bottleneck[0] == int(bott)
+        assert out.iter_time[0] == int(it)
+
+
+def test_classic_1f1b_inflight_counts():
+    """Memory rule holds N_s = S - s stashes (paper section 2.1): with one operator per stage,
+    zero parameters and unit stash, stage s fits exactly when the device holds N_s units."""
+    for row in read_golden(os.path.join(GOLD, "classic_1f1b_inflight.txt")):
+        S, counts = row.split(":")
+        S, counts = int(S), [int(x) for x in counts.split()]
+        # one GPU type per stage so that every stage has its own limit
+        for slack, want in ((0, oracle.OK), (-1, oracle.INFEASIBLE)):
+            for tight in range(S):
+                mem = [c + (slack if s == tight else 0) for s, c in enumerate(counts)]
+                p = simple_problem([1] * S, M=64, T=S, G=S, ndev=[1] * S, gtype=list(range(S)),
+                                   stash=[1] * S, mem=mem, bw=np.ones((S, S)))
+                out = plan(p, cands_from_lists([[(g, 1) for g in range(S)]]))
+                assert out.status[0] == want, (S, tight, slack)
+
+
+def test_inflight_count_capped_by_microbatches():
+    # M = 1: every stage holds one stash only, so memory 1 suffices everywhere
+    S = 3
+    p = simple_problem([1] * S, M=1, ndev=(S,), stash=[1] * S, mem=[1])
+    assert plan(p, cands_from_lists([same_slot(S)])).status[0] == oracle.OK
+    p = simple_problem([1] * S, M=2, ndev=(S,), stash=[1] * S, mem=[1])
+    assert plan(p, cands_from_lists([same_slot(S)])).status[0] == oracle.INFEASIBLE
+
+
+# ---------------------------------------------------------------- brute force
+
+def _check_against_brute(w, cands):
+    out = plan(w.problem, cands)
+    n_ok = 0
+    for c in range(cands.C):
+        S = int(cands.cand_S[c])
+        st, b, bott, it = brute.plan(w.problem, S, cands.S_max, cands.cand_group[c], cands.cand_tp[c])
+        assert st == out.status[c], (w.seed, c)
+        if st == oracle.OK:
+            n_ok += 1
+            assert list(out.splits[c, :S + 1]) == b, (w.seed, c)
+            assert (out.splits[c, S + 1:] == -1).all()
+            assert out.bottleneck[c] == bott and out.iter_time[c] == it, (w.seed, c)
+        else:
+            assert (out.splits[c] == -1).all() and (out.dev_first[c] == -1).all()
+            assert out.bottleneck[c] == oracle.INF and out.iter_time[c] == oracle.INF
+    return n_ok
+
+
+def test_brute_force_tiny_config():
+    w = W.make("tiny")
+    assert _check_against_brute(w, w.candidates()) == 16
+
+
+def test_brute_force_random_small():
+    n_ok = n_all = 0
+    for seed in range(1500):
+        w = W.random_small(seed)
+        cands = w.candidates()
+        n_ok += _check_against_brute(w, cands)
+        n_all += cands.C
+    # the sample must exercise both outcomes
+    assert 0.5 * n_all < n_ok < 0.95 * n_all
+
+
+def test_score_matches_brute_on_arbitrary_partitions():
+    rng = np.random.default_rng(5)
+    for seed in range(300):
+        w = W.random_small(seed)
+        cands = w.candidates()
+        L = w.problem.L
+        splits = np.full((cands.C, cands.S_max + 1), -1, dtype=np.int32)
+        for c in range(cands.C):
+            S = int(cands.cand_S[c])
+            if S <= L:
+                cut = np.sort(rng.choice(np.arange(1, L), size=S - 1, replace=False)) if S > 1 else []
+                splits[c, :S + 1] = [0, *cut, L]
+        bott, it, st = oracle.score_1f1b(oracle.build_tables(w.problem), cands, splits)
+        for c in range(cands.C):
+            S = int(cands.cand_S[c])
+            g, t = cands.cand_group[c], cands.cand_tp[c]
+            if S > L:
+                assert st[c] == oracle.INVALID
+                continue
+            b = [int(x) for x in splits[c, :S + 1]]
+            fits = all(brute.stage_cost(w.problem, S, g, t, s, b[s], b[s + 1]) != brute.INF
+                       for s in range(S))
+            if not fits:
+                assert st[c] == oracle.INFEASIBLE and bott[c] == oracle.INF and it[c] == oracle.INF
+            else:
+                assert st[c] == oracle.OK
+                assert (bott[c], it[c]) == brute.score(w.problem, S, g, t, b)
+
+
+# ---------------------------------------------------------------- textbook special case
+
+def _linear_partition_value(costs, S):
+    """Smallest possible largest part sum when cutting costs into exactly S non-empty parts
+    (all costs >= 0): bisection on the answer with greedy packing."""
+    def parts_needed(limit):
+        n, acc = 1, 0
+        for c in costs:
+            if c > limit:
+                return len(costs) + 1
+            if acc + c > limit:
+                n, acc = n + 1, c
+            else:
+                acc += c
+        return n
+    lo, hi = 0, sum(costs)
+    while lo < hi:
+        mid = (lo + hi) // 2
+        if parts_needed(mid) <= S:
+            hi = mid
+        else:
+            lo = mid + 1
+    return lo
+
+
+def test_reduces_to_linear_partition():
+    rng = np.random.default_rng(11)
+    for _ in range(200):
+        L = int(rng.integers(1, 40))
+        S = int(rng.integers(1, min(L, 9) + 1))
+        costs = [int(x) for x in rng.integers(0, 1000, size=L)]
+        p = simple_problem(costs, M=3, ndev=(S,))
+        out = plan(p, cands_from_lists([same_slot(S)]))
+        assert out.status[0] == oracle.OK
+        # with non-negative costs "at most S parts" and "exactly S parts" have the same optimum
+        assert out.bottleneck[0] == _linear_partition_value(costs, S)
+
+
+# ---------------------------------------------------------------- closed forms
+
+def test_uniform_operators_closed_form():
+    for L in range(1, 25):
+        for S in range(1, min(L, 8) + 1):
+            for a, M in ((7, 1), (3, 5), (1000, 32)):
+                p = simple_problem([a] * L, M=M, ndev=(S,))
+                out = plan(p, cands_from_lists([same_slot(S)]))
+                big = math.ceil(L / S) * a
+                assert out.bottleneck[0] == big
+                assert out.iter_time[0] == L * a + (M - 1) * big
+                if L % S == 0:
+                    assert out.iter_time[0] == (M + S - 1) * (L // S) * a
+                sizes, left = [], L
+                for s in range(S, 0, -1):       # stage sizes are fixed from the back
+                    sizes.append(math.ceil(left / s))
+                    left -= sizes[-1]
+                want = [0]
+                for z in reversed(sizes):
+                    want.append(want[-1] + z)
+                assert list(out.splits[0, :S + 1]) == want
+
+
+def test_single_stage():
+    rng = np.random.default_rng(3)
+    for _ in range(50):
+        L, M = int(rng.integers(1, 20)), int(rng.integers(1, 9))
+        fwd = rng.integers(1, 100, size=(1, L))
+        bwd = rng.integers(1, 100, size=(1, L))
+        params = rng.integers(0, 50, size=L)
+        stash = rng.integers(0, 50, size=L)
+        need = int(params.sum() + min(1, M) * stash.sum())
+        for mem, want in ((need, oracle.OK), (need - 1, oracle.INFEASIBLE)):
+            p = simple_problem(np.zeros(L), M=M, fwd=fwd, bwd=bwd, params=params, stash=stash,
+                               mem=[mem])
+            out = plan(p, cands_from_lists([same_slot(1)]))
+            if need == 0 and mem < 0:
+                continue
+            assert out.status[0] == want
+            if want == oracle.OK:
+                t = int(fwd.sum() + bwd.sum())
+                assert out.bottleneck[0] == t and out.iter_time[0] == M * t
+                assert list(out.splits[0]) == [0, L]
+
+
+def test_tensor_parallel_time_model():
+    # degree 1: no all-reduce term; degree tp: ceil(work / tp) + per-operator rounded all-reduce
+    work = [10, 11, 12]
+    act = [100, 250, 7]
+    bwv = 7
+    for tp in (1, 2, 3, 4, 8):
+        p = simple_problem(work, ndev=(8,), tp=sorted({1, tp}), act=act, bw=[[bwv]], ar_count=4)
+        out = plan(p, cands_from_lists([[(0, tp)]]))
+        ar = 0 if tp == 1 else sum(-(-(4 * 2 * (tp - 1) * a) // (tp * bwv)) for a in act)
+        assert out.bottleneck[0] == -(-sum(work) // tp) + ar
+        if tp in (2, 4, 8):
+            assert -(-sum(work) // tp) == (sum(work) + tp - 1) >> (tp.bit_length() - 1)
+
+
+def test_faster_intra_group_link_never_slows_a_stage():
+    for seed in range(100):
+        w = W.random_small(seed)
+        p = w.problem
+        cands = w.candidates()
+        a = plan(p, cands)
+        for g in range(p.G):
+            p.bw[g, g] *= 2
+        b = plan(p, cands)
+        ok = (a.status == oracle.OK)
+        assert (b.status == a.status).all()          # memory does not depend on bandwidth
+        assert (b.bottleneck[ok] <= a.bottleneck[ok]).all()
+
+
+def test_huge_bandwidth_makes_every_transfer_one_microsecond():
+    for seed in range(60):
+        w = W.random_small(seed)
+        p = w.problem
+        p.act_bytes[:] = np.maximum(p.act_bytes, 1)
+        p.bw[:] = 1 << 40
+        p.tp_degrees = np.asarray([1], dtype=np.int32)
+        cands = w.candidates()
+        cands.cand_tp[cands.cand_tp > 0] = 1
+        out = plan(p, cands)
+        for c in np.nonzero(out.status == oracle.OK)[0]:
+            S = int(cands.cand_S[c])
+            b = out.splits[c]
+            t = [int(p.fwd_us[p.group_type[cands.cand_group[c, s]], b[s]:b[s + 1]].sum()
+                     + p.bwd_us[p.group_type[cands.cand_group[c, s]], b[s]:b[s + 1]].sum())
+                 for s in range(S)]
+            assert out.iter_time[c] == sum(t) + 2 * (S - 1) + (p.M - 1) * max(t + [1] * (S > 1))
+
+
+def test_slow_link_forces_the_cheapest_cut():
+    # two groups joined by a link so slow that the transfer dominates every stage time: the plan
+    # must cut where the fewest bytes cross (joint optimisation of section 5.2 / ablation 6.6)
+    act = [900, 500, 100, 700, 800, 1]
+    p = simple_problem([5] * 6, M=4, G=2, ndev=(1, 1), act=act, bw=[[1000, 1], [1, 1000]])
+    out = plan(p, cands_from_lists([[(0, 1), (1, 1)]]))
+    assert list(out.splits[0]) == [0, 3, 6]
+    assert out.bottleneck[0] == 100
+    assert out.iter_time[0] == 30 + 2 * 100 + 3 * 100
+
+
+# ---------------------------------------------------------------- invariants
+
+def test_score_of_own_plan_reproduces_it():
+    for name in ("tiny", "llama7b"):
+        w = W.make(name)
+        cands = w.candidates(0, min(w.C, 128))
+        tables = oracle.build_tables(w.problem)
+        out = oracle.plan_batch(tables, cands)
+        bott, it, st = oracle.score_1f1b(tables, cands, out.splits)
+        ok = out.status == oracle.OK
+        assert (st[ok] == oracle.OK).all() and (st[~ok] == oracle.INVALID).all()
+        assert (bott == out.bottleneck).all() and (it == out.iter_time).all()
+
+
+def test_one_more_microbatch_costs_one_bottleneck():
+    for seed in range(80):
+        w = W.random_small(seed)
+        p = w.problem
+        p.type_mem_bytes[:] = BIG
+        p.M = 8
+        cands = w.candidates()
+        a = plan(p, cands)
+        p.M = 9
+        b = plan(p, cands)
+        ok = cands.cand_S <= p.L
+        assert (a.status[ok] == oracle.OK).all() and (a.status[~ok] == oracle.INFEASIBLE).all()
+        assert (a.splits == b.splits).all()
+        assert (b.iter_time[ok] - a.iter_time[ok] == a.bottleneck[ok]).all()
+
+
+def test_bottleneck_monotone_as_memory_shrinks():
+    """Feasible sets are nested, so per candidate the bottleneck can only grow and feasibility can
+    only be lost when any device memory shrinks.  The exhaustive optimum of the iteration time
+    (not the min-max plan's own time) is monotone too; brute force checks that."""
+    for seed in range(120):
+        w = W.random_small(seed, L_max=8, S_cap=4)
+        p = w.problem
+        cands = w.candidates()
+        prev = None
+        prev_best = None
+        start = p.type_mem_bytes.copy()
+        for step in range(5):
+            p.type_mem_bytes[:] = start * (5 - step) // 5
+            out = plan(p, cands)
+            best = [brute.best_iteration_time(p, int(cands.cand_S[c]), cands.S_max,
+                                              cands.cand_group[c], cands.cand_tp[c])
+                    for c in range(cands.C)] if seed < 40 else None
+            if prev is not None:
+                assert (out.bottleneck >= prev.bottleneck).all()
+                assert ((out.status != oracle.OK) | (prev.status == oracle.OK)).all()
+                if best is not None:
+                    assert all(x >= y for x, y in zip(best, prev_best))
+            if best is not None:
+                for c in range(cands.C):
+                    if out.status[c] == oracle.OK:
+                        assert out.iter_time[c] >= best[c]
+                    else:
+                        assert best[c] == brute.INF
+            prev, prev_best = out, best
+
+
+def test_lower_bounds():
+    for name, n in (("llama7b", 256), ("llama70b", 128), ("finegrained", 32)):
+        w = W.make(name)
+        p = w.problem
+        cands = w.candidates(0, n)
+        out = plan(p, cands)
+        work = (p.fwd_us + p.bwd_us)
+        for c in np.nonzero(out.status == oracle.OK)[0]:
+            S = int(cands.cand_S[c])
+            tps = cands.cand_tp[c, :S].astype(np.int64)
+            types = p.group_type[cands.cand_group[c, :S]]
+            # all work must be done by somebody: total device-time covers the fastest-type work
+            assert out.bottleneck[c] * int(tps.sum()) >= int(work[types].min(axis=0).sum())
+            # every operator sits in some stage
+            per_op = np.min(-(-work[types] // tps[:, None]), axis=0)
+            assert out.bottleneck[c] >= int(per_op.max())
+
+
+def test_batch_independence_and_determinism():
+    w = W.make("llama70b")
+    cands = w.candidates(0, 96)
+    tables = oracle.build_tables(w.problem)
+    a = oracle.plan_batch(tables, cands)
+    perm = np.random.default_rng(0).permutation(cands.C)
+    shuffled = cands.take(np.concatenate([perm, perm[:7]]))
+    b = oracle.plan_batch(tables, shuffled)
+    for k, c in enumerate(np.concatenate([perm, perm[:7]])):
+        assert (a.splits[c] == b.splits[k]).all() and a.iter_time[c] == b.iter_time[k]
+        assert a.status[c] == b.status[k] and (a.dev_first[c] == b.dev_first[k]).all()
+
+
+def test_device_assignment():
+    p = simple_problem([1] * 6, G=3, ndev=(4, 2, 8), tp=(1, 2, 4), bw=np.ones((3, 3)))
+    out = plan(p, cands_from_lists([[(2, 4), (2, 2), (0, 1), (0, 2), (1, 2)]]))
+    assert list(out.dev_first[0]) == [6, 10, 0, 1, 4]
+
+
+def test_invalid_candidates():
+    p = simple_problem([1] * 6, G=2, ndev=(2, 2), tp=(1, 2), bw=np.ones((2, 2)))
+    bad = [
+        [(0, 1), (1, 1), (0, 1)],       # group 0 revisited
+        [(0, 2), (0, 1)],               # group 0 over-subscribed
+        [(0, 3)],                       # degree not allowed
+        [(2, 1)],                       # no such group
+        [(0, 0)],                       # degree below 1
+        [],                             # no stage
+    ]
+    cands = cands_from_lists(bad, S_max=3)
+    out = plan(p, cands)
+    assert (out.status == oracle.INVALID).all()
+    cands = cands_from_lists([[(0, 1), (1, 1)]], S_max=3)
+    cands.cand_S[0] = 4                 # more stages than S_max
+    assert plan(p, cands).status[0] == oracle.INVALID
+
+
+def test_more_stages_than_operators_is_infeasible():
+    p = simple_problem([1, 1], ndev=(4,))
+    out = plan(p, cands_from_lists([same_slot(3)]))
+    assert out.status[0] == oracle.INFEASIBLE
+
+
+def test_argmin_batch():
+    it = np.array([9, 5, 5, 3, 7], dtype=np.int64)
+    st = np.array([0, 0, 0, 1, 0], dtype=np.int32)
+    assert oracle.argmin_batch(it, st) == (5, 1)
+    assert oracle.argmin_batch(it, np.ones(5, dtype=np.int32)) == (oracle.INF, -1)
+    assert oracle.argmin_batch(it[:0], st[:0]) == (oracle.INF, -1)
+
+
+def test_magnitude_guard():
+    p = simple_problem([1 << 46, 1 << 46], ndev=(2,))
+    assert oracle.Tables(p).rc == oracle.ERR_OVERFLOW
+    p = simple_problem([1 << 45, 1 << 45], M=1 << 17, ndev=(2,))
+    assert oracle.Tables(p).rc == oracle.ERR_OVERFLOW      # 2^46 * (3 L + M) overflows the sum
+    p = simple_problem([1 << 45, 1 << 45], M=1 << 10, ndev=(2,))
+    assert oracle.Tables(p).rc == 0
+    p = simple_problem([1 << 40, 1 << 40], ndev=(2,))
+    assert oracle.Tables(p).rc == 0
+    p = simple_problem([1, -1], ndev=(2,))
+    assert oracle.Tables(p).rc == oracle.ERR_BAD_ARG
+    p = simple_problem([1, 1], ndev=(2,), bw=[[0]])
+    assert oracle.Tables(p).rc == oracle.ERR_BAD_ARG
+
+
+# ---------------------------------------------------------------- the workloads themselves
+
+def test_workload_shapes_and_determinism():
+    import hashlib
+    for name in W.ORDER:
+        w1, w2 = W.make(name), W.make(name)
+        c1, c2 = w1.candidates(0, min(w1.C, 512)), w2.candidates(0, min(w2.C, 512))
+        h = lambda w, c: hashlib.sha256(b"".join(np.ascontiguousarray(a).tobytes() for a in (
+            w.problem.fwd_us, w.problem.bwd_us, w.problem.param_bytes, w.problem.stash_bytes,
+            w.problem.act_bytes, w.problem.bw, w.problem.type_mem_bytes, c.cand_S, c.cand_group,
+            c.cand_tp))).hexdigest()
+        assert h(w1, c1) == h(w2, c2)
+        p = w1.problem
+        assert (p.bwd_us == 2 * p.fwd_us).all() and (p.bw == p.bw.T).all() and (p.bw >= 1).all()
+    shapes = {n: (W.make(n).problem.L, W.make(n).C, W.make(n).S_max, W.make(n).problem.M)
+              for n in W.ORDER}
+    assert shapes == {"tiny": (8, 16, 4, 4), "llama7b": (32, 1024, 8, 32),
+                      "llama70b": (82, 16384, 16, 64), "finegrained": (160, 65536, 32, 128),
+                      "stress": (512, 262144, 64, 256)}
+
+
+def test_candidate_slices_are_independent_of_batching():
+    w = W.make("finegrained")
+    a, b = w.candidates(1000, 1100), w.candidates(900, 1300)
+    assert (a.cand_group == b.cand_group[100:200]).all() and (a.cand_tp == b.cand_tp[100:200]).all()
+    assert (a.cand_S == b.cand_S[100:200]).all()
+
+
+def test_stress_workload_is_memory_tight():
+    w = W.make("stress")
+    cands = w.candidates(0, 96)
+    out = plan(w.problem, cands)
+    frac = float((out.status == oracle.INFEASIBLE).mean())
+    assert 0.15 < frac < 0.45        # about 30% over the first 4096 candidates
