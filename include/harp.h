@@ -1,0 +1,203 @@
+/*
+ * harp.h - C ABI of the MI355X planner-search library.
+ *
+ * The library evaluates, on one GPU, a batch of candidate pipeline layouts for the inter-operator
+ * planner of HARP (paper section 5.2).  A planning problem is an ordered sequence of L operators
+ * with profiled per-GPU-type compute times and byte sizes, and a cluster of G homogeneous device
+ * groups with intra- and inter-group link bandwidths (section 5.2.1, 5.2.3).  A candidate is an
+ * ordered list of S stage slots; slot s is a submesh of tp_s devices of group g_s (the ordered
+ * subclusters of section 5.2.1 together with the submesh choice of section 5.2.2, hoisted out of
+ * the DP into the batch dimension).  For every candidate the library finds the partition of the
+ * operators into S contiguous non-empty stages with the smallest feasible bottleneck t_max
+ * (section 5.2.3, constraints (i)-(iii); section 5.2.4 (2), "smallest feasible value t_S") and
+ * scores it with the iteration-time model of section 5.2.2 (eq. gpipe_cost_model).
+ *
+ * All quantities are integers: times in microseconds, sizes in bytes, bandwidths in bytes per
+ * microsecond.  With segment [j, i) of operators on slot s = (g, tp), t = group_type[g]:
+ *
+ *   time(s; j, i) = ceil(sum_{j<=l<i} (fwd_us[t][l] + bwd_us[t][l]) / tp)
+ *                   + sum_{j<=l<i} ceil(ar_count * 2 (tp-1) * act_bytes[l] / (tp * bw[g][g]))
+ *                                                                   (second term 0 when tp == 1)
+ *   comm(s; i)    = ceil(act_bytes[i-1] / bw[g_s][g_{s+1}])  for s < S-1,   0 for s == S-1
+ *   fits(s; j, i) = sum param_bytes + N_s * sum stash_bytes <= tp * type_mem_bytes[t],
+ *                   N_s = min(S - s, M)     (classic 1F1B in-flight microbatches, section 2.1;
+ *                                            eq. mem_cons of section 5.2.3)
+ *   bottleneck    = min over partitions with every stage fitting of
+ *                   max_s max(time_s, comm_s)
+ *   iter_time     = sum_s time_s + 2 sum_{s<S-1} comm_s + (M - 1) * bottleneck
+ *
+ * Among partitions of equal bottleneck the reported one is fixed by the recurrence
+ *   D[s+1][i] = min_j max(D[s][j], time(s;j,i), comm(s;i))  over fitting j, lowest j on ties,
+ * followed back from (S, L).
+ *
+ * Conventions.  Pointers marked DEVICE are device memory of the context's GPU, pointers marked
+ * HOST are ordinary host memory.  The caller owns every buffer; the library allocates no device
+ * memory.  Calls enqueue work on the given HIP stream (NULL = the default stream) and return
+ * without waiting unless stated; outputs are valid once the stream has been synchronised.  Every
+ * function returning int returns HARP_OK or a negative error code; harp_last_error gives the
+ * message.  A context must not be used from two host threads at once.  No call falls back to the
+ * CPU: without a usable GPU harp_create fails.
+ */
+#ifndef HARP_H
+#define HARP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct harp_ctx harp_ctx;       /* opaque; host-side state of one GPU */
+typedef struct harp_tables harp_tables; /* opaque host-side view of a caller-lent table buffer */
+
+enum {
+    HARP_OK = 0,
+    HARP_ERR_INVALID_ARG = -1, /* null pointer, value out of range, malformed problem */
+    HARP_ERR_SHAPE = -2,       /* sizes that do not fit together or exceed a stated limit */
+    HARP_ERR_WORKSPACE = -3,   /* lent buffer too small or misaligned */
+    HARP_ERR_HIP = -4,         /* a HIP runtime call failed */
+    HARP_ERR_OVERFLOW = -5,    /* problem magnitudes outside the range the library guarantees */
+    HARP_ERR_UNIMPLEMENTED = -6
+};
+
+/* per-candidate status written by harp_plan_batch and harp_score_1f1b */
+enum { HARP_CAND_OK = 0, HARP_CAND_INFEASIBLE = 1, HARP_CAND_INVALID = 2 };
+
+/* harp_plan_batch kernel selection (harp_set_plan_path).  Every path gives identical results. */
+enum {
+    HARP_PATH_AUTO = 0,    /* fastest path the tables allow */
+    HARP_PATH_GENERIC = 1, /* int64 dense recurrence, one wave per DP cell; any degree, any size */
+    HARP_PATH_FAST32 = 2   /* 32-bit times, bounded scan; needs harp_tables_fast32() != 0 */
+};
+
+#define HARP_INF INT64_MAX
+#define HARP_MAX_TP_DEGREES 8
+#define HARP_MAX_L_PLAN 65535
+
+/* Creates the context for GPU `hip_device_ordinal`.  HARP_ERR_HIP when the device is missing. */
+int harp_create(harp_ctx **out, int hip_device_ordinal);
+void harp_destroy(harp_ctx *ctx);
+/* Message of the last failed call on this context; owned by the context, never NULL. */
+const char *harp_last_error(const harp_ctx *ctx);
+
+/* The planning problem (paper section 5.2.2-5.2.3: layer sequence, profiled costs, subclusters).
+ * All arrays row-major and contiguous. */
+typedef struct {
+    int32_t L;        /* operators, >= 1 */
+    int32_t T;        /* GPU types, >= 1 */
+    int32_t G;        /* device groups (homogeneous subclusters), >= 1 */
+    int32_t M;        /* microbatches per iteration (the paper's B), >= 1 */
+    int32_t ar_count; /* tensor-parallel all-reduces per operator per forward+backward, >= 0 */
+    int32_t flags;    /* must be 0 */
+    int32_t n_tp;     /* 1 .. HARP_MAX_TP_DEGREES */
+    const int32_t *tp_degrees;     /* HOST   [n_tp] ascending, first == 1 */
+    const int64_t *fwd_us;         /* DEVICE [T][L] forward time per operator and GPU type */
+    const int64_t *bwd_us;         /* DEVICE [T][L] backward time */
+    const int64_t *param_bytes;    /* DEVICE [L] parameters and buffers */
+    const int64_t *stash_bytes;    /* DEVICE [L] activation kept per in-flight microbatch */
+    const int64_t *act_bytes;      /* DEVICE [L] bytes crossing a cut placed right after l */
+    const int32_t *group_type;     /* DEVICE [G] GPU type of each group */
+    const int32_t *group_ndev;     /* DEVICE [G] devices in each group, >= 1 */
+    const int64_t *type_mem_bytes; /* DEVICE [T] memory of one device */
+    const int64_t *bw_bytes_per_us;/* DEVICE [G][G] symmetric, >= 1; diagonal = link inside a group */
+} harp_problem;
+
+/* Bytes of device memory the caller must lend to harp_build_segment_costs (0 on a malformed
+ * problem).  Depends on L, T, G, n_tp only. */
+size_t harp_tables_bytes(const harp_problem *problem);
+
+/* Segment-cost tables (the stored stage costs that the search of section 5.2.3 looks up):
+ * running sums over operators of compute time per GPU type, parameter bytes, stash bytes and
+ * all-reduce time per (group, degree), so that any segment's time and memory is two lookups;
+ * plus, when magnitudes allow, the 32-bit rows and per-link cut times of the fast path.
+ * Also validates the device-resident problem (signs, ranges, magnitudes).
+ *
+ * table_buf: DEVICE, 256-byte aligned, at least harp_tables_bytes(problem) bytes; the returned
+ * view aliases it and the problem's act_bytes, group_type, group_ndev, type_mem_bytes and
+ * bw_bytes_per_us arrays, all of which must stay alive and unchanged until harp_tables_release.
+ * Enqueues on `hip_stream` and returns; the verdict on the problem's values is collected by
+ * harp_tables_finalize. */
+int harp_build_segment_costs(harp_ctx *ctx, const harp_problem *problem, void *table_buf,
+                             size_t table_bytes, harp_tables **out, void *hip_stream);
+
+/* Waits for the build on its stream and returns its verdict: HARP_OK, HARP_ERR_INVALID_ARG
+ * (negative input, bandwidth < 1, group type out of range, group without devices) or
+ * HARP_ERR_OVERFLOW (sums that could leave int64, a stage or transfer time >= 2^47 us, or an
+ * iteration time that could leave int64).  Idempotent.  harp_plan_batch and harp_score_1f1b call
+ * it themselves on first use of a view. */
+int harp_tables_finalize(harp_ctx *ctx, harp_tables *tables);
+
+/* 1 when the finalized tables allow the 32-bit fast path (all degrees powers of two, every time
+ * below 2^31 us, L <= 2048, per-link cut table within 256 MiB), else 0. */
+int harp_tables_fast32(const harp_tables *tables);
+
+/* DEVICE pointers into the table buffer, for inspection: running sums indexed [row][i],
+ * i = 0..L, row pitch in elements returned through `pitch`.  PF [T], PP [1], PS [1],
+ * PR [G * n_tp] (row g * n_tp + k for degree tp_degrees[k]). */
+const int64_t *harp_tables_pf(const harp_tables *tables, size_t *pitch);
+const int64_t *harp_tables_pp(const harp_tables *tables);
+const int64_t *harp_tables_ps(const harp_tables *tables);
+const int64_t *harp_tables_pr(const harp_tables *tables, size_t *pitch);
+
+/* Frees the host-side view only. */
+void harp_tables_release(harp_tables *tables);
+
+/* A batch of candidates. */
+typedef struct {
+    int32_t C;     /* candidates, >= 0 */
+    int32_t S_max; /* row length of the slot arrays, >= 1 */
+    const int32_t *cand_S;     /* DEVICE [C]        stages of each candidate */
+    const int32_t *cand_group; /* DEVICE [C][S_max] group of each slot (entries beyond S ignored) */
+    const int32_t *cand_tp;    /* DEVICE [C][S_max] devices of each slot */
+} harp_candidates;
+
+/* Plans, all DEVICE, caller-allocated.  For a candidate whose status is not HARP_CAND_OK:
+ * splits and dev_first all -1, bottleneck = iter_time = HARP_INF. */
+typedef struct {
+    int32_t *splits;     /* [C][S_max+1] cut positions b_0 = 0 < ... < b_S = L, rest -1 */
+    int32_t *dev_first;  /* [C][S_max]   first global device id of each stage, rest -1; groups
+                            number their devices consecutively in group order, a group's slots
+                            take its devices in slot order */
+    int64_t *bottleneck; /* [C] */
+    int64_t *iter_time;  /* [C] */
+    int32_t *status;     /* [C] HARP_CAND_* */
+} harp_plans;
+
+/* Chooses the kernel of harp_plan_batch for this context (HARP_PATH_*); for tests and
+ * measurements.  HARP_ERR_INVALID_ARG on an unknown value. */
+int harp_set_plan_path(harp_ctx *ctx, int path);
+
+/* Bytes of DEVICE workspace harp_plan_batch needs for this batch (0 on malformed arguments). */
+size_t harp_plan_workspace_bytes(harp_ctx *ctx, const harp_tables *tables,
+                                 const harp_candidates *cands);
+
+/* The search itself (section 5.2.3 recurrence per candidate, back-pointers, backtrack, and the
+ * score of section 5.2.2), one workgroup per candidate.  A candidate is HARP_CAND_INVALID when
+ * S is outside 1..S_max, a group id or degree is not allowed, a group's slots are not adjacent
+ * or use more devices than the group has; HARP_CAND_INFEASIBLE when S > L or no partition fits
+ * in memory.  workspace: DEVICE, 256-byte aligned, >= harp_plan_workspace_bytes; contents are
+ * scratch.  Needs L <= HARP_MAX_L_PLAN.  Asynchronous on `hip_stream`, except that the first use
+ * of a view finalizes it. */
+int harp_plan_batch(harp_ctx *ctx, harp_tables *tables, const harp_candidates *cands,
+                    const harp_plans *out, void *workspace, size_t workspace_bytes,
+                    void *hip_stream);
+
+/* Scores caller-chosen partitions with eq. gpipe_cost_model (section 5.2.2):
+ * splits DEVICE [C][S_max+1].  Status HARP_CAND_INVALID when the candidate is malformed or its
+ * cuts are not strictly increasing from 0 to L; HARP_CAND_INFEASIBLE when a stage does not fit
+ * in memory; times are HARP_INF unless the status is HARP_CAND_OK. */
+int harp_score_1f1b(harp_ctx *ctx, harp_tables *tables, const harp_candidates *cands,
+                    const int32_t *splits, int64_t *bottleneck, int64_t *iter_time,
+                    int32_t *status, void *hip_stream);
+
+/* Final selection over the batch (the min over evaluated candidates of section 5.2.3): smallest
+ * iter_time among candidates with status HARP_CAND_OK, lowest index on ties.  best_time and
+ * best_index are DEVICE scalars; -1 and HARP_INF when no candidate qualifies. */
+int harp_argmin_batch(harp_ctx *ctx, int32_t C, const int64_t *iter_time, const int32_t *status,
+                      int64_t *best_time, int32_t *best_index, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HARP_H */

@@ -1,0 +1,341 @@
+// Host layer of the C ABI declared in include/harp.h: argument checks, layout of the caller-lent
+// buffers, kernel selection and launches.  Allocates no device memory (one small pinned host
+// buffer per context receives the build verdict).
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+
+#include "harp_internal.h"
+
+using namespace harp;
+
+struct harp_ctx {
+    int device;
+    int n_cu;
+    int plan_path;
+    BuildHeader *pinned;   // host, pinned
+    char err[512];
+};
+
+struct harp_tables {
+    TablesDev dev;
+    BuildLimits lim;
+    hipStream_t build_stream;
+    int device;
+    bool finalized;
+    int verdict;
+    bool fast32;
+    size_t bytes;
+};
+
+namespace {
+
+int fail(harp_ctx *ctx, int code, const char *fmt, ...) {
+    if (ctx) {
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(ctx->err, sizeof(ctx->err), fmt, ap);
+        va_end(ap);
+    }
+    return code;
+}
+
+int hip_fail(harp_ctx *ctx, hipError_t e, const char *what) {
+    return fail(ctx, HARP_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+struct Layout {
+    size_t header, group_base, rows, chunk_sums, p32, cm, total;
+    int64_t pitch, pitch32;
+    int n_chunks;
+    bool fast;
+};
+
+bool problem_shape_ok(const harp_problem *p) {
+    if (!p) return false;
+    if (p->L < 1 || p->L > (1 << 24) || p->T < 1 || p->T > 4096 || p->G < 1 || p->G > 4096) return false;
+    if (p->M < 1 || p->ar_count < 0 || p->ar_count > (1 << 20) || p->flags != 0) return false;
+    if (p->n_tp < 1 || p->n_tp > kMaxTp || !p->tp_degrees) return false;
+    if (p->tp_degrees[0] != 1) return false;
+    for (int k = 1; k < p->n_tp; ++k)
+        if (p->tp_degrees[k] <= p->tp_degrees[k - 1] || p->tp_degrees[k] > 65536) return false;
+    if (int64_t(p->T) + 2 + int64_t(p->G) * p->n_tp > 65535) return false;
+    return true;
+}
+
+Layout make_layout(const harp_problem *p) {
+    Layout y;
+    const size_t L1 = size_t(p->L) + 1;
+    y.pitch = (int64_t)align_up(L1, 8);
+    y.pitch32 = (int64_t)align_up(L1, 16);
+    y.n_chunks = (p->L + kScanChunk - 1) / kScanChunk;
+    const size_t n_rows = size_t(p->T) + 2 + size_t(p->G) * p->n_tp;
+    size_t off = 0;
+    y.header = off; off += 256;
+    y.group_base = off; off += align_up(size_t(p->G) * 4, 256);
+    y.rows = off; off += align_up(n_rows * y.pitch * 8, 256);
+    y.chunk_sums = off; off += align_up(n_rows * size_t(y.n_chunks) * 8, 256);
+    bool pow2 = true;
+    for (int k = 0; k < p->n_tp; ++k) pow2 = pow2 && (p->tp_degrees[k] & (p->tp_degrees[k] - 1)) == 0;
+    const size_t cm_bytes = size_t(p->G) * p->G * y.pitch32 * 4;
+    y.fast = pow2 && p->L <= kFastMaxL && cm_bytes <= kFastCutTableLimit &&
+             size_t(p->G) * p->n_tp + size_t(p->G) * p->G <= 65535;
+    y.p32 = off;
+    if (y.fast) off += align_up(size_t(p->G) * p->n_tp * y.pitch32 * 4, 256);
+    y.cm = off;
+    if (y.fast) off += align_up(cm_bytes, 256);
+    y.total = off;
+    return y;
+}
+
+int finalize_tables(harp_ctx *ctx, harp_tables *t) {
+    if (t->finalized) return t->verdict;
+    hipError_t e = hipMemcpyAsync(ctx->pinned, t->dev.header, sizeof(BuildHeader), hipMemcpyDeviceToHost,
+                                  t->build_stream);
+    if (e != hipSuccess) return hip_fail(ctx, e, "reading the build verdict");
+    e = hipStreamSynchronize(t->build_stream);
+    if (e != hipSuccess) return hip_fail(ctx, e, "waiting for the table build");
+    t->finalized = true;
+    t->fast32 = ctx->pinned->fast32 != 0;
+    if (ctx->pinned->bad_arg)
+        t->verdict = fail(ctx, HARP_ERR_INVALID_ARG,
+                          "problem arrays hold a negative value, a bandwidth below 1, a group type out of range or an empty group");
+    else if (ctx->pinned->overflow)
+        t->verdict = fail(ctx, HARP_ERR_OVERFLOW,
+                          "problem magnitudes are outside the supported range (stage or transfer time >= 2^47 us, or sums that could leave int64)");
+    else
+        t->verdict = HARP_OK;
+    return t->verdict;
+}
+
+int check_batch(harp_ctx *ctx, harp_tables *t, const harp_candidates *cd) {
+    if (!ctx) return HARP_ERR_INVALID_ARG;
+    if (!t || !cd) return fail(ctx, HARP_ERR_INVALID_ARG, "null tables or candidates");
+    if (t->device != ctx->device) return fail(ctx, HARP_ERR_INVALID_ARG, "tables belong to another device");
+    if (cd->C < 0) return fail(ctx, HARP_ERR_INVALID_ARG, "C must be >= 0");
+    if (cd->S_max < 1 || cd->S_max > kMaxStages)
+        return fail(ctx, HARP_ERR_SHAPE, "S_max must be in 1..%d", kMaxStages);
+    if (cd->C > 0 && (!cd->cand_S || !cd->cand_group || !cd->cand_tp))
+        return fail(ctx, HARP_ERR_INVALID_ARG, "null candidate array");
+    if (t->dev.L > HARP_MAX_L_PLAN) return fail(ctx, HARP_ERR_SHAPE, "planning needs L <= %d", HARP_MAX_L_PLAN);
+    return finalize_tables(ctx, t);
+}
+
+int n_plan_groups(const harp_ctx *ctx, int C, bool fast, int L) {
+    int resident = fast ? plan_fast_groups(L, ctx->n_cu) : ctx->n_cu * 8;
+    if (resident < 1) resident = 1;
+    return C < resident ? (C < 1 ? 1 : C) : resident;
+}
+
+bool use_fast(const harp_ctx *ctx, const harp_tables *t) {
+    return t->fast32 && ctx->plan_path != HARP_PATH_GENERIC;
+}
+
+}  // namespace
+
+extern "C" {
+
+int harp_create(harp_ctx **out, int hip_device_ordinal) {
+    if (!out) return HARP_ERR_INVALID_ARG;
+    *out = nullptr;
+    int n = 0;
+    if (hipGetDeviceCount(&n) != hipSuccess || hip_device_ordinal < 0 || hip_device_ordinal >= n)
+        return HARP_ERR_HIP;
+    if (hipSetDevice(hip_device_ordinal) != hipSuccess) return HARP_ERR_HIP;
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, hip_device_ordinal) != hipSuccess) return HARP_ERR_HIP;
+    harp_ctx *ctx = new (std::nothrow) harp_ctx;
+    if (!ctx) return HARP_ERR_INVALID_ARG;
+    ctx->device = hip_device_ordinal;
+    ctx->n_cu = prop.multiProcessorCount;
+    ctx->plan_path = HARP_PATH_AUTO;
+    ctx->pinned = nullptr;
+    ctx->err[0] = 0;
+    if (hipHostMalloc(reinterpret_cast<void **>(&ctx->pinned), sizeof(BuildHeader), hipHostMallocDefault) != hipSuccess) {
+        delete ctx;
+        return HARP_ERR_HIP;
+    }
+    *out = ctx;
+    return HARP_OK;
+}
+
+void harp_destroy(harp_ctx *ctx) {
+    if (!ctx) return;
+    if (ctx->pinned) (void)hipHostFree(ctx->pinned);
+    delete ctx;
+}
+
+const char *harp_last_error(const harp_ctx *ctx) { return ctx ? ctx->err : "null context"; }
+
+size_t harp_tables_bytes(const harp_problem *problem) {
+    if (!problem_shape_ok(problem)) return 0;
+    return make_layout(problem).total;
+}
+
+int harp_build_segment_costs(harp_ctx *ctx, const harp_problem *p, void *table_buf, size_t table_bytes,
+                             harp_tables **out, void *hip_stream) {
+    if (!ctx) return HARP_ERR_INVALID_ARG;
+    if (!out) return fail(ctx, HARP_ERR_INVALID_ARG, "null output pointer");
+    *out = nullptr;
+    if (!p) return fail(ctx, HARP_ERR_INVALID_ARG, "null problem");
+    if (!problem_shape_ok(p))
+        return fail(ctx, HARP_ERR_INVALID_ARG,
+                    "malformed problem header (L, T, G, M, ar_count, flags or tp_degrees out of range)");
+    if (!p->fwd_us || !p->bwd_us || !p->param_bytes || !p->stash_bytes || !p->act_bytes || !p->group_type ||
+        !p->group_ndev || !p->type_mem_bytes || !p->bw_bytes_per_us)
+        return fail(ctx, HARP_ERR_INVALID_ARG, "null problem array");
+    const Layout y = make_layout(p);
+    if (!table_buf || (reinterpret_cast<uintptr_t>(table_buf) & 255) != 0)
+        return fail(ctx, HARP_ERR_WORKSPACE, "table buffer must be a 256-byte aligned device pointer");
+    if (table_bytes < y.total)
+        return fail(ctx, HARP_ERR_WORKSPACE, "table buffer holds %zu bytes, %zu needed", table_bytes, y.total);
+    hipError_t e = hipSetDevice(ctx->device);
+    if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
+
+    harp_tables *t = new (std::nothrow) harp_tables;
+    if (!t) return fail(ctx, HARP_ERR_INVALID_ARG, "out of host memory");
+    unsigned char *base = static_cast<unsigned char *>(table_buf);
+    TablesDev &d = t->dev;
+    d.L = p->L; d.T = p->T; d.G = p->G; d.M = p->M; d.n_tp = p->n_tp; d.ar_count = p->ar_count;
+    for (int k = 0; k < kMaxTp; ++k) { d.tp[k] = 0; d.tp_shift[k] = -1; }
+    for (int k = 0; k < p->n_tp; ++k) {
+        const int v = p->tp_degrees[k];
+        d.tp[k] = v;
+        if ((v & (v - 1)) == 0) { int s = 0; while ((1 << s) < v) ++s; d.tp_shift[k] = s; }
+    }
+    d.pitch = y.pitch; d.pitch32 = y.pitch32;
+    d.header = reinterpret_cast<BuildHeader *>(base + y.header);
+    d.group_base = reinterpret_cast<int32_t *>(base + y.group_base);
+    d.rows = reinterpret_cast<int64_t *>(base + y.rows);
+    d.chunk_sums = reinterpret_cast<int64_t *>(base + y.chunk_sums);
+    d.P32 = y.fast ? reinterpret_cast<uint32_t *>(base + y.p32) : nullptr;
+    d.CM = y.fast ? reinterpret_cast<uint32_t *>(base + y.cm) : nullptr;
+    d.fwd_us = p->fwd_us; d.bwd_us = p->bwd_us; d.param_bytes = p->param_bytes;
+    d.stash_bytes = p->stash_bytes; d.act_bytes = p->act_bytes; d.type_mem = p->type_mem_bytes;
+    d.bw = p->bw_bytes_per_us; d.group_type = p->group_type; d.group_ndev = p->group_ndev;
+
+    const int64_t tp_max = p->tp_degrees[p->n_tp - 1];
+    const int64_t num_mul = int64_t(p->ar_count) * 2 * (tp_max - 1);
+    t->lim.elem_max = ((int64_t(1) << 62) - 1) / p->L;
+    t->lim.act_max = num_mul > 0 ? INT64_MAX / num_mul : INT64_MAX;
+    t->lim.bw_max = INT64_MAX / tp_max;
+    t->lim.mem_max = INT64_MAX / tp_max;
+    t->lim.want_fast = y.fast ? 1 : 0;
+    t->build_stream = static_cast<hipStream_t>(hip_stream);
+    t->device = ctx->device;
+    t->finalized = false;
+    t->verdict = HARP_OK;
+    t->fast32 = false;
+    t->bytes = y.total;
+
+    launch_build(d, t->lim, t->build_stream);
+    e = hipGetLastError();
+    if (e != hipSuccess) { delete t; return hip_fail(ctx, e, "launching the table build"); }
+    *out = t;
+    return HARP_OK;
+}
+
+int harp_tables_finalize(harp_ctx *ctx, harp_tables *tables) {
+    if (!ctx) return HARP_ERR_INVALID_ARG;
+    if (!tables) return fail(ctx, HARP_ERR_INVALID_ARG, "null tables");
+    return finalize_tables(ctx, tables);
+}
+
+int harp_tables_fast32(const harp_tables *tables) { return tables && tables->finalized && tables->fast32; }
+
+const int64_t *harp_tables_pf(const harp_tables *t, size_t *pitch) {
+    if (!t) return nullptr;
+    if (pitch) *pitch = (size_t)t->dev.pitch;
+    return t->dev.PF(0);
+}
+const int64_t *harp_tables_pp(const harp_tables *t) { return t ? t->dev.PP() : nullptr; }
+const int64_t *harp_tables_ps(const harp_tables *t) { return t ? t->dev.PS() : nullptr; }
+const int64_t *harp_tables_pr(const harp_tables *t, size_t *pitch) {
+    if (!t) return nullptr;
+    if (pitch) *pitch = (size_t)t->dev.pitch;
+    return t->dev.PR(0, 0);
+}
+
+void harp_tables_release(harp_tables *tables) { delete tables; }
+
+int harp_set_plan_path(harp_ctx *ctx, int path) {
+    if (!ctx) return HARP_ERR_INVALID_ARG;
+    if (path != HARP_PATH_AUTO && path != HARP_PATH_GENERIC && path != HARP_PATH_FAST32)
+        return fail(ctx, HARP_ERR_INVALID_ARG, "unknown plan path %d", path);
+    ctx->plan_path = path;
+    return HARP_OK;
+}
+
+size_t harp_plan_workspace_bytes(harp_ctx *ctx, const harp_tables *t, const harp_candidates *cd) {
+    if (!ctx || !t || !cd || cd->C < 0 || cd->S_max < 1 || cd->S_max > kMaxStages) return 0;
+    if (t->dev.L > HARP_MAX_L_PLAN) return 0;
+    // sized for whichever path may run, so that the answer does not depend on the build verdict
+    const int C = cd->C;
+    size_t gen = size_t(n_plan_groups(ctx, C, false, t->dev.L)) * plan_generic_ws_per_group(t->dev.L, cd->S_max);
+    size_t fast = 0;
+    if (t->lim.want_fast)
+        fast = size_t(n_plan_groups(ctx, C, true, t->dev.L)) * plan_fast_ws_per_group(t->dev.L, cd->S_max);
+    return (gen > fast ? gen : fast) + 256;
+}
+
+int harp_plan_batch(harp_ctx *ctx, harp_tables *t, const harp_candidates *cd, const harp_plans *out,
+                    void *workspace, size_t workspace_bytes, void *hip_stream) {
+    int rc = check_batch(ctx, t, cd);
+    if (rc != HARP_OK) return rc;
+    if (!out || (cd->C > 0 && (!out->splits || !out->dev_first || !out->bottleneck || !out->iter_time || !out->status)))
+        return fail(ctx, HARP_ERR_INVALID_ARG, "null output array");
+    if (ctx->plan_path == HARP_PATH_FAST32 && !t->fast32)
+        return fail(ctx, HARP_ERR_UNIMPLEMENTED, "the 32-bit path was requested but these tables do not allow it");
+    if (cd->C == 0) return HARP_OK;
+    const size_t need = harp_plan_workspace_bytes(ctx, t, cd);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0)
+        return fail(ctx, HARP_ERR_WORKSPACE, "workspace must be a 256-byte aligned device pointer");
+    if (workspace_bytes < need)
+        return fail(ctx, HARP_ERR_WORKSPACE, "workspace holds %zu bytes, %zu needed", workspace_bytes, need);
+    hipError_t e = hipSetDevice(ctx->device);
+    if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
+    const CandDev c = { cd->C, cd->S_max, cd->cand_S, cd->cand_group, cd->cand_tp };
+    const PlansDev o = { out->splits, out->dev_first, out->bottleneck, out->iter_time, out->status };
+    const bool fast = use_fast(ctx, t);
+    const int groups = n_plan_groups(ctx, cd->C, fast, t->dev.L);
+    if (fast) launch_plan_fast(t->dev, c, o, workspace, groups, static_cast<hipStream_t>(hip_stream));
+    else launch_plan_generic(t->dev, c, o, workspace, groups, static_cast<hipStream_t>(hip_stream));
+    e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(ctx, e, "launching the planner kernel");
+    return HARP_OK;
+}
+
+int harp_score_1f1b(harp_ctx *ctx, harp_tables *t, const harp_candidates *cd, const int32_t *splits,
+                    int64_t *bottleneck, int64_t *iter_time, int32_t *status, void *hip_stream) {
+    int rc = check_batch(ctx, t, cd);
+    if (rc != HARP_OK) return rc;
+    if (cd->C == 0) return HARP_OK;
+    if (!splits || !bottleneck || !iter_time || !status) return fail(ctx, HARP_ERR_INVALID_ARG, "null array");
+    hipError_t e = hipSetDevice(ctx->device);
+    if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
+    const CandDev c = { cd->C, cd->S_max, cd->cand_S, cd->cand_group, cd->cand_tp };
+    launch_score(t->dev, c, splits, bottleneck, iter_time, status, static_cast<hipStream_t>(hip_stream));
+    e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(ctx, e, "launching the scorer kernel");
+    return HARP_OK;
+}
+
+int harp_argmin_batch(harp_ctx *ctx, int32_t C, const int64_t *iter_time, const int32_t *status,
+                      int64_t *best_time, int32_t *best_index, void *hip_stream) {
+    if (!ctx) return HARP_ERR_INVALID_ARG;
+    if (C < 0) return fail(ctx, HARP_ERR_INVALID_ARG, "C must be >= 0");
+    if (!best_time || !best_index || (C > 0 && (!iter_time || !status)))
+        return fail(ctx, HARP_ERR_INVALID_ARG, "null array");
+    hipError_t e = hipSetDevice(ctx->device);
+    if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
+    launch_argmin(C, iter_time, status, best_time, best_index, static_cast<hipStream_t>(hip_stream));
+    e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(ctx, e, "launching the selection kernel");
+    return HARP_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,92 @@
+// Internal declarations shared by the host layer and the gfx950 kernels.  Not part of the ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "harp.h"
+
+namespace harp {
+
+constexpr int kMaxTp = HARP_MAX_TP_DEGREES;
+constexpr int kMaxStages = 256;        // S_max accepted by plan/score
+constexpr int kFastMaxL = 2048;        // fast path keeps whole rows in LDS
+constexpr size_t kFastCutTableLimit = size_t(256) << 20;
+constexpr int64_t kInf = INT64_MAX;
+constexpr int64_t kTimeLimit = int64_t(1) << 47;
+
+// Device-side verdict of the table build, first bytes of the table buffer.
+struct BuildHeader {
+    unsigned int bad_arg;        // nonzero: malformed values
+    unsigned int overflow;       // nonzero: magnitudes out of range
+    unsigned int fast32;         // 1: 32-bit rows and cut table are valid
+    unsigned int pad;
+    unsigned long long max_act;  // largest act_bytes entry
+    long long worst_time;        // largest stage or transfer time any plan can see
+    long long reserved[4];
+};
+
+// Everything a kernel needs to read the tables; passed by value.
+struct TablesDev {
+    int32_t L, T, G, M, n_tp, ar_count;
+    int32_t tp[kMaxTp];
+    int32_t tp_shift[kMaxTp];    // log2(tp) when tp is a power of two, else -1
+    int64_t pitch;               // elements between int64 rows
+    int64_t pitch32;             // elements between uint32 rows
+    BuildHeader *header;
+    int64_t *rows;               // PF rows, PP, PS, PR rows, consecutive
+    int64_t *chunk_sums;         // scan scratch, [n_rows][n_chunks]
+    int32_t *group_base;         // [G] first global device id of each group
+    uint32_t *P32;               // [G*n_tp][pitch32]  PF[type g][i] + tp * PR[g][k][i]
+    uint32_t *CM;                // [G*G][pitch32]     ceil(act_bytes[i-1] / bw[g][h]), 0 at i = 0
+    const int64_t *fwd_us, *bwd_us, *param_bytes, *stash_bytes, *act_bytes;
+    const int64_t *type_mem, *bw;
+    const int32_t *group_type, *group_ndev;
+
+    __host__ __device__ const int64_t *PF(int t) const { return rows + int64_t(t) * pitch; }
+    __host__ __device__ const int64_t *PP() const { return rows + int64_t(T) * pitch; }
+    __host__ __device__ const int64_t *PS() const { return rows + int64_t(T + 1) * pitch; }
+    __host__ __device__ const int64_t *PR(int g, int k) const {
+        return rows + (int64_t(T + 2) + int64_t(g) * n_tp + k) * pitch;
+    }
+    __host__ __device__ int n_rows() const { return T + 2 + G * n_tp; }
+};
+
+struct CandDev {
+    int32_t C, S_max;
+    const int32_t *cand_S, *cand_group, *cand_tp;
+};
+
+struct PlansDev {
+    int32_t *splits, *dev_first;
+    int64_t *bottleneck, *iter_time;
+    int32_t *status;
+};
+
+// limits derived on the host for the element-wise magnitude guard
+struct BuildLimits {
+    int64_t elem_max;   // every time/byte input and every all-reduce time must be <= this
+    int64_t act_max;    // act_bytes bound so that the all-reduce numerator fits
+    int64_t bw_max;     // bandwidth bound so that tp * bw fits
+    int64_t mem_max;    // device memory bound so that tp * mem fits
+    int32_t want_fast;  // 1: the buffer has room for the 32-bit rows and the cut table
+};
+
+constexpr int kScanThreads = 256;
+constexpr int kScanItems = 4;
+constexpr int kScanChunk = kScanThreads * kScanItems;
+
+void launch_build(const TablesDev &tb, const BuildLimits &lim, hipStream_t st);
+void launch_plan_generic(const TablesDev &tb, const CandDev &cd, const PlansDev &out, void *ws,
+                         int n_groups, hipStream_t st);
+size_t plan_generic_ws_per_group(int L, int S_max);
+void launch_plan_fast(const TablesDev &tb, const CandDev &cd, const PlansDev &out, void *ws,
+                      int n_groups, hipStream_t st);
+size_t plan_fast_ws_per_group(int L, int S_max);
+int plan_fast_groups(int L, int n_cu);
+void launch_score(const TablesDev &tb, const CandDev &cd, const int32_t *splits,
+                  int64_t *bottleneck, int64_t *iter_time, int32_t *status, hipStream_t st);
+void launch_argmin(int32_t C, const int64_t *iter_time, const int32_t *status, int64_t *best_time,
+                   int32_t *best_index, hipStream_t st);
+
+}  // namespace harp

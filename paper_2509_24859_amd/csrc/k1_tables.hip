@@ -1,0 +1,305 @@
+// Segment-cost table build for gfx950: running sums over the operator sequence.
+//
+// The planner of the paper's section 5.2.3 looks up the cost of a candidate stage (a contiguous
+// operator range on a submesh) many times; section 5.1 stores those costs once.  Here the stored
+// form is one running sum per quantity, so that a segment's compute time, all-reduce time and
+// memory are each one subtraction: PF per GPU type, PP, PS, and PR per (group, degree).
+//
+// The work is a batch of independent row scans over L operators.  It is HBM-streaming work:
+// reduce-then-scan in three launches (chunk sums, scan of chunk sums per row, scan of each chunk
+// with its offset), every global access a coalesced 32-byte-per-lane run.  At L <= 1024 a row is a
+// single chunk and only the last launch runs.  The same launch validates the inputs it reads.
+#include "harp_internal.h"
+
+namespace harp {
+
+namespace {
+
+__device__ __forceinline__ int64_t ceil_div_u(int64_t a, int64_t b) {
+    return (int64_t)(((unsigned long long)a + (unsigned long long)b - 1ull) / (unsigned long long)b);
+}
+
+// Value of element l of table row r, with the checks that belong to the inputs it touches.
+struct RowSource {
+    const int64_t *a;     // first addend
+    const int64_t *b;     // second addend or nullptr
+    int64_t num_mul;      // all-reduce rows: ar_count * 2 * (tp - 1); 0 for plain rows
+    int64_t den;          // all-reduce rows: tp * bw[g][g]
+    bool is_ar;
+    bool track_act;       // this row also reports max(act_bytes)
+};
+
+__device__ __forceinline__ RowSource row_source(const TablesDev &tb, int r) {
+    RowSource s;
+    s.b = nullptr; s.num_mul = 0; s.den = 1; s.is_ar = false; s.track_act = false;
+    if (r < tb.T) {
+        s.a = tb.fwd_us + int64_t(r) * tb.L;
+        s.b = tb.bwd_us + int64_t(r) * tb.L;
+    } else if (r == tb.T) {
+        s.a = tb.param_bytes;
+    } else if (r == tb.T + 1) {
+        s.a = tb.stash_bytes;
+    } else {
+        int q = r - (tb.T + 2);
+        int g = q / tb.n_tp, k = q - g * tb.n_tp;
+        int64_t tp = tb.tp[k];
+        s.a = tb.act_bytes;
+        s.is_ar = true;
+        s.track_act = (q == 0);
+        s.num_mul = int64_t(tb.ar_count) * 2 * (tp - 1);
+        int64_t link = tb.bw[int64_t(g) * tb.G + g];
+        // a bad link value is reported by the finalize kernel; keep the division defined here
+        s.den = (link >= 1 && link <= INT64_MAX / tp) ? tp * link : 1;
+    }
+    return s;
+}
+
+__device__ __forceinline__ int64_t row_value(const RowSource &s, int64_t l, const BuildLimits &lim,
+                                             unsigned int &bad, unsigned int &ovf,
+                                             unsigned long long &act_seen) {
+    int64_t x = s.a[l];
+    if (x < 0) { bad = 1; x = 0; }
+    if (s.is_ar) {
+        if ((unsigned long long)x > act_seen) act_seen = (unsigned long long)x;
+        if (x > lim.act_max || x > lim.elem_max) { ovf = 1; x = 0; }
+        if (s.num_mul == 0) return 0;
+        int64_t v = ceil_div_u(s.num_mul * x, s.den);
+        if (v > lim.elem_max) { ovf = 1; v = 0; }
+        return v;
+    }
+    if (x > lim.elem_max) { ovf = 1; x = 0; }
+    if (s.b) {
+        int64_t y = s.b[l];
+        if (y < 0) { bad = 1; y = 0; }
+        if (y > lim.elem_max) { ovf = 1; y = 0; }
+        x += y;
+    }
+    return x;
+}
+
+__device__ __forceinline__ int64_t wave_inclusive_scan(int64_t v, int lane) {
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        int64_t up = __shfl_up(v, d, 64);
+        if (lane >= d) v += up;
+    }
+    return v;
+}
+
+__device__ __forceinline__ void report(BuildHeader *h, unsigned int bad, unsigned int ovf,
+                                       unsigned long long act_seen, bool track_act) {
+    if (__any(bad) && (threadIdx.x & 63) == 0) atomicOr(&h->bad_arg, 1u);
+    if (__any(ovf) && (threadIdx.x & 63) == 0) atomicOr(&h->overflow, 1u);
+    if (track_act) atomicMax(&h->max_act, act_seen);
+}
+
+// Launch 1 (only when a row spans several chunks): sum of every chunk.
+__global__ __launch_bounds__(kScanThreads) void k1_chunk_sums(TablesDev tb, BuildLimits lim, int n_chunks) {
+    const int r = blockIdx.y, chunk = blockIdx.x;
+    const RowSource src = row_source(tb, r);
+    unsigned int bad = 0, ovf = 0;
+    unsigned long long act_seen = 0;
+    int64_t base = int64_t(chunk) * kScanChunk + int64_t(threadIdx.x) * kScanItems;
+    int64_t sum = 0;
+#pragma unroll
+    for (int q = 0; q < kScanItems; ++q)
+        if (base + q < tb.L) sum += row_value(src, base + q, lim, bad, ovf, act_seen);
+    __shared__ int64_t part[kScanThreads / 64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int64_t inc = wave_inclusive_scan(sum, lane);
+    if (lane == 63) part[wave] = inc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int64_t t = 0;
+        for (int w = 0; w < kScanThreads / 64; ++w) t += part[w];
+        tb.chunk_sums[int64_t(r) * n_chunks + chunk] = t;
+    }
+    // values are checked again by the last launch; nothing to report here
+}
+
+// Launch 2: exclusive scan of the chunk sums of each row, in place.
+__global__ __launch_bounds__(kScanThreads) void k1_scan_chunk_sums(TablesDev tb, int n_chunks) {
+    int64_t *row = tb.chunk_sums + int64_t(blockIdx.x) * n_chunks;
+    __shared__ int64_t part[kScanThreads / 64];
+    __shared__ int64_t carry_s;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (threadIdx.x == 0) carry_s = 0;
+    __syncthreads();
+    for (int base = 0; base < n_chunks; base += kScanThreads) {
+        int idx = base + threadIdx.x;
+        int64_t v = idx < n_chunks ? row[idx] : 0;
+        int64_t inc = wave_inclusive_scan(v, lane);
+        if (lane == 63) part[wave] = inc;
+        __syncthreads();
+        int64_t off = carry_s;
+        for (int w = 0; w < wave; ++w) off += part[w];
+        if (idx < n_chunks) row[idx] = off + inc - v;
+        __syncthreads();
+        if (threadIdx.x == kScanThreads - 1) carry_s = off + inc;
+        __syncthreads();
+    }
+}
+
+// Launch 3: scan each chunk, add the chunk's offset, write the table row (entry i = l + 1).
+__global__ __launch_bounds__(kScanThreads) void k1_scan_rows(TablesDev tb, BuildLimits lim, int n_chunks) {
+    const int r = blockIdx.y, chunk = blockIdx.x;
+    const RowSource src = row_source(tb, r);
+    unsigned int bad = 0, ovf = 0;
+    unsigned long long act_seen = 0;
+    int64_t base = int64_t(chunk) * kScanChunk + int64_t(threadIdx.x) * kScanItems;
+    int64_t v[kScanItems];
+    int64_t sum = 0;
+#pragma unroll
+    for (int q = 0; q < kScanItems; ++q) {
+        v[q] = (base + q < tb.L) ? row_value(src, base + q, lim, bad, ovf, act_seen) : 0;
+        sum += v[q];
+    }
+    __shared__ int64_t part[kScanThreads / 64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int64_t inc = wave_inclusive_scan(sum, lane);
+    if (lane == 63) part[wave] = inc;
+    __syncthreads();
+    int64_t run = (n_chunks > 1) ? tb.chunk_sums[int64_t(r) * n_chunks + chunk] : 0;
+    for (int w = 0; w < wave; ++w) run += part[w];
+    run += inc - sum;
+    int64_t *out = tb.rows + int64_t(r) * tb.pitch;
+    if (chunk == 0 && threadIdx.x == 0) out[0] = 0;
+#pragma unroll
+    for (int q = 0; q < kScanItems; ++q) {
+        run += v[q];
+        if (base + q < tb.L) out[base + q + 1] = run;
+    }
+    unsigned long long wave_act = act_seen;
+    if (src.track_act) {
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) {
+            unsigned long long o = __shfl_xor(wave_act, d, 64);
+            wave_act = o > wave_act ? o : wave_act;
+        }
+    }
+    report(tb.header, bad, ovf, wave_act, src.track_act && lane == 0);
+}
+
+// Launch 4 (one workgroup): checks of the small arrays, device numbering of the groups, the
+// magnitude verdict, and whether the 32-bit fast path may be used.
+__global__ __launch_bounds__(256) void k1_finalize(TablesDev tb, BuildLimits lim) {
+    __shared__ unsigned int bad_s, ovf_s;
+    __shared__ unsigned long long min_bw_s;
+    __shared__ long long worst_s, worst32_s;
+    if (threadIdx.x == 0) { bad_s = 0; ovf_s = 0; min_bw_s = ~0ull; worst_s = 0; worst32_s = 0; }
+    __syncthreads();
+    const int L = tb.L;
+    for (int64_t e = threadIdx.x; e < int64_t(tb.G) * tb.G; e += blockDim.x) {
+        int64_t b = tb.bw[e];
+        if (b < 1) atomicOr(&bad_s, 1u);
+        else {
+            if (b > lim.bw_max) atomicOr(&ovf_s, 1u);
+            atomicMin(&min_bw_s, (unsigned long long)b);
+        }
+    }
+    for (int t = threadIdx.x; t < tb.T; t += blockDim.x) {
+        int64_t m = tb.type_mem[t];
+        if (m < 0) atomicOr(&bad_s, 1u);
+        else if (m > lim.mem_max) atomicOr(&ovf_s, 1u);
+    }
+    for (int g = threadIdx.x; g < tb.G; g += blockDim.x) {
+        int t = tb.group_type[g];
+        if (t < 0 || t >= tb.T || tb.group_ndev[g] < 1) atomicOr(&bad_s, 1u);
+    }
+    __syncthreads();
+    const bool groups_ok = (bad_s == 0);
+    if (threadIdx.x == 0) {
+        int64_t base = 0;
+        for (int g = 0; g < tb.G; ++g) {
+            tb.group_base[g] = (int32_t)base;
+            int n = tb.group_ndev[g];
+            base += n > 0 ? n : 0;
+            if (base > INT32_MAX) { atomicOr(&ovf_s, 1u); base = 0; }
+        }
+    }
+    if (groups_ok) {
+        for (int q = threadIdx.x; q < tb.G * tb.n_tp; q += blockDim.x) {
+            int g = q / tb.n_tp, k = q - g * tb.n_tp;
+            // sums are bounded by L * elem_max <= 2^62 each, so these additions cannot wrap
+            unsigned long long work = (unsigned long long)tb.PF(tb.group_type[g])[L];
+            unsigned long long ar = (unsigned long long)tb.PR(g, k)[L];
+            unsigned long long whole = work + ar;
+            long long w = whole >= (unsigned long long)kTimeLimit ? kTimeLimit : (long long)whole;
+            atomicMax(&worst_s, w);
+            unsigned long long tp = (unsigned long long)tb.tp[k];
+            unsigned long long fused = (ar < (1ull << 40)) ? work + tp * ar + tp - 1 : ~0ull;
+            long long f = fused >= (unsigned long long)kTimeLimit ? kTimeLimit : (long long)fused;
+            atomicMax(&worst32_s, f);
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        BuildHeader *h = tb.header;
+        unsigned int bad = bad_s | h->bad_arg, ovf = ovf_s | h->overflow;
+        long long worst = worst_s, cut_worst = 0;
+        if (!bad) {
+            cut_worst = (long long)((h->max_act + min_bw_s - 1ull) / min_bw_s);
+            if (cut_worst > worst) worst = cut_worst;
+            if (worst >= kTimeLimit) ovf = 1;
+            else if (worst > INT64_MAX / (3ll * L + tb.M)) ovf = 1;
+            // memory need of any segment with any in-flight count
+            long long n_max = tb.M < L ? tb.M : L;
+            long long pp = tb.PP()[L], ps = tb.PS()[L];
+            if (ps > (INT64_MAX - pp) / n_max) ovf = 1;
+        }
+        bool pow2 = true;
+        for (int k = 0; k < tb.n_tp; ++k) pow2 = pow2 && tb.tp_shift[k] >= 0;
+        const long long lim32 = 1ll << 31;
+        h->bad_arg = bad;
+        h->overflow = ovf;
+        h->worst_time = worst;
+        h->fast32 = (!bad && !ovf && lim.want_fast && pow2 && worst32_s < lim32 && cut_worst < lim32) ? 1u : 0u;
+    }
+}
+
+// Launch 5: 32-bit rows of the fast path.  Row q < G*n_tp: PF[type g][i] + tp * PR[g][k][i]
+// (so that time(j, i) = (row[i] + tp - 1 - row[j]) >> log2 tp); then G*G rows of per-link cut times.
+__global__ __launch_bounds__(256) void k1_fast_rows(TablesDev tb) {
+    if (tb.header->fast32 == 0) return;
+    const int q = blockIdx.y;
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i > tb.L) return;
+    const int n_time_rows = tb.G * tb.n_tp;
+    if (q < n_time_rows) {
+        int g = q / tb.n_tp, k = q - g * tb.n_tp;
+        int64_t v = tb.PF(tb.group_type[g])[i] + int64_t(tb.tp[k]) * tb.PR(g, k)[i];
+        tb.P32[int64_t(q) * tb.pitch32 + i] = (uint32_t)v;
+    } else {
+        int e = q - n_time_rows;
+        int64_t v = (i == 0) ? 0 : ceil_div_u(tb.act_bytes[i - 1], tb.bw[e]);
+        tb.CM[int64_t(e) * tb.pitch32 + i] = (uint32_t)v;
+    }
+}
+
+__global__ void k1_clear_header(BuildHeader *h) {
+    if (threadIdx.x == 0) {
+        h->bad_arg = 0; h->overflow = 0; h->fast32 = 0; h->pad = 0;
+        h->max_act = 0; h->worst_time = 0;
+        for (int q = 0; q < 4; ++q) h->reserved[q] = 0;
+    }
+}
+
+}  // namespace
+
+void launch_build(const TablesDev &tb, const BuildLimits &lim, hipStream_t st) {
+    const int n_chunks = (tb.L + kScanChunk - 1) / kScanChunk;
+    const int n_rows = tb.n_rows();
+    hipLaunchKernelGGL(k1_clear_header, dim3(1), dim3(64), 0, st, tb.header);
+    if (n_chunks > 1) {
+        hipLaunchKernelGGL(k1_chunk_sums, dim3(n_chunks, n_rows), dim3(kScanThreads), 0, st, tb, lim, n_chunks);
+        hipLaunchKernelGGL(k1_scan_chunk_sums, dim3(n_rows), dim3(kScanThreads), 0, st, tb, n_chunks);
+    }
+    hipLaunchKernelGGL(k1_scan_rows, dim3(n_chunks, n_rows), dim3(kScanThreads), 0, st, tb, lim, n_chunks);
+    hipLaunchKernelGGL(k1_finalize, dim3(1), dim3(256), 0, st, tb, lim);
+    if (lim.want_fast) {
+        const int q = tb.G * tb.n_tp + tb.G * tb.G;
+        hipLaunchKernelGGL(k1_fast_rows, dim3((tb.L + 256) / 256, q), dim3(256), 0, st, tb);
+    }
+}
+
+}  // namespace harp

@@ -54,3 +54,27 @@ def read_golden(path):
             if line and not line.startswith("#"):
                 rows.append(line)
     return rows
+
+
+def oracle_plan_threaded(tables, cands, threads=None, step=16):
+    """Oracle plans for a whole batch, candidates spread over host threads (ctypes drops the GIL)."""
+    import os
+    from concurrent.futures import ThreadPoolExecutor
+
+    import oracle
+    threads = threads or min(16, len(os.sched_getaffinity(0)))
+    out = oracle.Plans(cands.C, cands.S_max)
+    with ThreadPoolExecutor(threads) as ex:
+        list(ex.map(lambda lo: oracle.plan_batch(tables, cands, lo, min(lo + step, cands.C), out),
+                    range(0, cands.C, step)))
+    return out
+
+
+def assert_plans_equal(got, want, label=""):
+    """Bit-exact comparison of every output array of a batch."""
+    for name in ("status", "splits", "dev_first", "bottleneck", "iter_time"):
+        a, b = getattr(got, name), getattr(want, name)
+        if not (a == b).all():
+            bad = np.nonzero((a != b).reshape(a.shape[0], -1).any(axis=1))[0]
+            raise AssertionError("%s: %s differs at %d candidates, first %d: got %s want %s"
+                                 % (label, name, bad.size, bad[0], a[bad[0]], b[bad[0]]))

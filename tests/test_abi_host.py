@@ -1,0 +1,77 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads and exports what the header
+declares.  No compute call is made here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "harp.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(harp_[a-z0-9_]+)\s*\(", text)))
+
+
+def _library():
+    from paper_2509_24859_amd import binding, build
+    if not os.path.exists(binding.LIB_PATH):
+        build.build_library()
+    return ctypes.CDLL(binding.LIB_PATH)
+
+
+def test_every_declared_symbol_is_exported():
+    lib = _library()
+    names = _declared()
+    assert len(names) >= 12
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_binding_lists_the_same_symbols():
+    from paper_2509_24859_amd import binding
+    assert sorted(binding.EXPORTS) == _declared()
+
+
+def test_tables_bytes_rejects_malformed_headers():
+    from paper_2509_24859_amd import binding
+    lib = binding.load_library()
+    tp = (ctypes.c_int32 * 2)(1, 2)
+    good = dict(L=8, T=2, G=2, M=4, ar_count=4, flags=0, n_tp=2)
+
+    def size(**kw):
+        f = dict(good, **kw)
+        p = binding.harp_problem(f["L"], f["T"], f["G"], f["M"], f["ar_count"], f["flags"],
+                                 f["n_tp"], ctypes.addressof(tp))
+        return lib.harp_tables_bytes(ctypes.byref(p))
+
+    assert size() > 0
+    for bad in (dict(L=0), dict(T=0), dict(G=0), dict(M=0), dict(ar_count=-1), dict(flags=1),
+                dict(n_tp=0), dict(n_tp=9)):
+        assert size(**bad) == 0, bad
+    tp[0] = 2
+    assert size() == 0                  # first degree must be 1
+    tp[0], tp[1] = 1, 1
+    assert size() == 0                  # degrees must rise
+    assert lib.harp_tables_bytes(None) == 0
+
+
+def test_null_context_is_refused_without_touching_the_gpu():
+    from paper_2509_24859_amd import binding
+    lib = binding.load_library()
+    assert lib.harp_set_plan_path(None, 0) == binding.ERR_INVALID_ARG
+    assert lib.harp_tables_finalize(None, None) == binding.ERR_INVALID_ARG
+    assert lib.harp_last_error(None) == b"null context"
+    assert lib.harp_create(None, 0) == binding.ERR_INVALID_ARG
+
+
+def test_product_package_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2509_24859_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in text and "from oracle" not in text, f
+                assert "harp_oracle" not in text, f

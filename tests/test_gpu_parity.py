@@ -1,0 +1,404 @@
+"""GPU parity: the HIP library behind the C ABI against the CPU oracle, bit for bit."""
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2509_24859_amd import workloads as W
+
+from helpers import (BIG, assert_plans_equal, cands_from_lists, oracle_plan_threaded, same_slot,
+                     simple_problem)
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx(harp):
+    c = harp.Context(0)
+    yield c
+    c.close()
+
+
+def _paths(harp, tables):
+    return [harp.PATH_GENERIC] + ([harp.PATH_FAST32] if tables.fast32 else [])
+
+
+def _plan_all_paths(harp, ctx, problem, cands, want, label):
+    import torch
+    tables = harp.Tables(ctx, problem)
+    dc = harp.DeviceCandidates(ctx, cands)
+    out = harp.DevicePlans(ctx, dc.C, dc.S_max)
+    ws = harp.plan_workspace(ctx, tables, dc)
+    ran = []
+    for path in _paths(harp, tables):
+        out.poison()
+        ctx.set_plan_path(path)
+        try:
+            harp.harp_plan_batch(ctx, tables, dc, out, ws)
+            torch.cuda.synchronize()
+        finally:
+            ctx.set_plan_path(harp.PATH_AUTO)
+        assert_plans_equal(out.to_host(), want, "%s path %d" % (label, path))
+        ran.append(path)
+    return tables, ran
+
+
+# ------------------------------------------------------------------ tables (a1)
+
+@pytest.mark.parametrize("name", W.ORDER)
+def test_tables_match_oracle(harp, ctx, name):
+    w = W.make(name)
+    want = oracle.build_tables(w.problem)
+    tables = harp.Tables(ctx, w.problem)
+    PF, PP, PS, PR = tables.host_copies()
+    assert (PF == want.PF).all() and (PP == want.PP).all() and (PS == want.PS).all()
+    assert (PR == want.PR).all()
+    assert tables.fast32
+
+
+def test_tables_match_oracle_long_rows(harp, ctx):
+    """Rows spanning several scan chunks with a ragged tail (L = 5000: 4 full chunks + 904)."""
+    rng = np.random.default_rng(1)
+    L, T, G = 5000, 3, 5
+    fwd = rng.integers(0, 5000, size=(T, L))
+    bwd = rng.integers(0, 9000, size=(T, L))
+    bw = rng.integers(1, 500, size=(G, G))
+    bw = np.minimum(bw, bw.T)
+    p = simple_problem(np.zeros(L), M=7, T=T, G=G, ndev=[8] * G, tp=(1, 2, 3, 8),
+                       fwd=fwd, bwd=bwd, params=rng.integers(0, 10**9, size=L),
+                       stash=rng.integers(0, 10**8, size=L), act=rng.integers(0, 10**7, size=L),
+                       gtype=rng.integers(0, T, size=G), bw=bw)
+    want = oracle.build_tables(p)
+    tables = harp.Tables(ctx, p)
+    PF, PP, PS, PR = tables.host_copies()
+    assert (PF == want.PF).all() and (PP == want.PP).all() and (PS == want.PS).all()
+    assert (PR == want.PR).all()
+    assert not tables.fast32          # degree 3 and L > 2048
+
+
+def test_tables_random_small(harp, ctx):
+    for seed in range(60):
+        w = W.random_small(seed)
+        want = oracle.build_tables(w.problem)
+        PF, PP, PS, PR = harp.Tables(ctx, w.problem).host_copies()
+        assert (PF == want.PF).all() and (PP == want.PP).all() and (PS == want.PS).all()
+        assert (PR == want.PR).all(), seed
+
+
+def test_build_verdicts(harp, ctx):
+    cases = [
+        (simple_problem([1, -1], ndev=(2,)), harp.ERR_INVALID_ARG),
+        (simple_problem([1, 1], ndev=(2,), bw=[[0]]), harp.ERR_INVALID_ARG),
+        (simple_problem([1, 1], ndev=(0,)), harp.ERR_INVALID_ARG),
+        (simple_problem([1, 1], ndev=(2,), gtype=[3]), harp.ERR_INVALID_ARG),
+        (simple_problem([1, 1], ndev=(2,), mem=[-5]), harp.ERR_INVALID_ARG),
+        (simple_problem([1 << 46, 1 << 46], ndev=(2,)), harp.ERR_OVERFLOW),
+        (simple_problem([1 << 45, 1 << 45], M=1 << 17, ndev=(2,)), harp.ERR_OVERFLOW),
+        (simple_problem([1 << 61, 1 << 61], ndev=(2,)), harp.ERR_OVERFLOW),
+        (simple_problem([1, 1], ndev=(2,), params=[(1 << 61) - 1] * 2, stash=[(1 << 61) - 1] * 2, M=64),
+         harp.ERR_OVERFLOW),
+    ]
+    for p, code in cases:
+        assert oracle.Tables(p).rc == (oracle.ERR_BAD_ARG if code == harp.ERR_INVALID_ARG
+                                       else oracle.ERR_OVERFLOW)
+        with pytest.raises(harp.HarpError) as e:
+            harp.Tables(ctx, p)
+        assert e.value.code == code
+    ok = simple_problem([1 << 40, 1 << 40], ndev=(2,))
+    assert oracle.Tables(ok).rc == 0
+    t = harp.Tables(ctx, ok)
+    assert not t.fast32                      # times beyond 32 bits: only the int64 path
+
+
+# ------------------------------------------------------------------ planner (a2-a4)
+
+def test_plan_tiny_all_paths(harp, ctx):
+    w = W.make("tiny")
+    cands = w.candidates()
+    want = oracle.plan_batch(oracle.build_tables(w.problem), cands)
+    _, ran = _plan_all_paths(harp, ctx, w.problem, cands, want, "tiny")
+    assert harp.PATH_FAST32 in ran
+
+
+@pytest.mark.parametrize("name,n", [("llama7b", 1024), ("llama70b", 16384), ("finegrained", 4096),
+                                    ("stress", 384)])
+def test_plan_workloads_all_paths(harp, ctx, name, n):
+    w = W.make(name)
+    cands = w.candidates(0, n)
+    want = oracle_plan_threaded(oracle.build_tables(w.problem), cands)
+    assert (want.status == oracle.OK).any()
+    _, ran = _plan_all_paths(harp, ctx, w.problem, cands, want, name)
+    assert harp.PATH_FAST32 in ran
+
+
+def test_plan_random_small_all_paths(harp, ctx):
+    fast_runs = 0
+    for seed in range(400):
+        w = W.random_small(seed)
+        cands = w.candidates()
+        want = oracle.plan_batch(oracle.build_tables(w.problem), cands)
+        _, ran = _plan_all_paths(harp, ctx, w.problem, cands, want, "seed %d" % seed)
+        fast_runs += harp.PATH_FAST32 in ran
+    assert fast_runs > 200
+
+
+def test_plan_medium_random_problems(harp, ctx):
+    """Sizes that span several tiles with ragged tails: L not a multiple of 64, tight memory."""
+    rng = np.random.default_rng(21)
+    for case in range(12):
+        L = int(rng.integers(65, 700))
+        T, G = int(rng.integers(1, 4)), int(rng.integers(1, 6))
+        ndev = rng.choice([2, 4, 8], size=G)
+        fwd = rng.integers(1, 4000, size=(T, L))
+        bw = rng.integers(50, 4000, size=(G, G))
+        bw = np.minimum(bw, bw.T)
+        params = rng.integers(0, 10**6, size=L)
+        stash = rng.integers(0, 10**5, size=L)
+        S_max = int(rng.integers(G, G + 8))
+        tp = (1, 2, 4, 8)[:int(rng.integers(1, 5))]
+        per_stage = int(params.sum() + 0.5 * S_max * stash.sum()) // S_max
+        mem = (rng.uniform(0.5, 1.6, size=T) * per_stage / np.sqrt(tp[-1])).astype(np.int64)
+        p = simple_problem(np.zeros(L), M=int(rng.integers(1, 40)), T=T, G=G, ndev=ndev, tp=tp,
+                           fwd=fwd, bwd=2 * fwd, params=params, stash=stash,
+                           act=rng.integers(0, 10**6, size=L), gtype=rng.integers(0, T, size=G),
+                           mem=mem, bw=bw)
+        p.group_ndev = np.maximum(p.group_ndev, p.tp_degrees[-1]).astype(np.int32)
+        cands = W.make_candidates(p, case, 77, G, S_max, 0, 48)
+        want = oracle_plan_threaded(oracle.build_tables(p), cands)
+        _plan_all_paths(harp, ctx, p, cands, want, "medium %d (L=%d)" % (case, L))
+
+
+def test_plan_adversarial_rows(harp, ctx):
+    """Inputs built to break shortcuts: huge transfers on some cuts (non-monotone DP rows), zero
+    cost operators (long runs of ties), memory that only fits one-operator stages."""
+    rng = np.random.default_rng(4)
+    L = 200
+    fwd = rng.integers(0, 3, size=(1, L)) * rng.integers(0, 50, size=(1, L))
+    act = np.where(rng.random(L) < 0.3, 10**9, rng.integers(0, 1000, size=L))
+    p = simple_problem(np.zeros(L), M=9, G=3, ndev=(8, 8, 8), tp=(1, 2, 4), fwd=fwd, bwd=fwd,
+                       act=act, bw=[[1000, 3, 1], [3, 1000, 7], [1, 7, 1000]])
+    cands = W.make_candidates(p, 0, 78, 3, 12, 0, 64)
+    want = oracle_plan_threaded(oracle.build_tables(p), cands)
+    _plan_all_paths(harp, ctx, p, cands, want, "adversarial transfers")
+
+    L = 90
+    p = simple_problem([0] * L, M=5, ndev=(8,), tp=(1, 2))
+    cands = cands_from_lists([same_slot(S) for S in (1, 2, 7, 8)], S_max=8)
+    want = oracle.plan_batch(oracle.build_tables(p), cands)
+    _plan_all_paths(harp, ctx, p, cands, want, "all-zero costs")
+
+    L = 12
+    p = simple_problem(list(range(1, L + 1)), M=3, ndev=(16,), tp=(1,), params=[10] * L, mem=[10])
+    cands = cands_from_lists([same_slot(S) for S in (11, 12, 13)], S_max=16)
+    want = oracle.plan_batch(oracle.build_tables(p), cands)
+    assert list(want.status) == [oracle.INFEASIBLE, oracle.OK, oracle.INFEASIBLE]
+    _plan_all_paths(harp, ctx, p, cands, want, "one operator per stage")
+
+
+def test_plan_odd_degrees_use_generic_path(harp, ctx):
+    rng = np.random.default_rng(8)
+    L = 70
+    p = simple_problem(np.zeros(L), M=6, G=2, ndev=(6, 6), tp=(1, 2, 3, 6),
+                       fwd=rng.integers(1, 1000, size=(1, L)), bwd=rng.integers(1, 1000, size=(1, L)),
+                       act=rng.integers(0, 10**5, size=L), bw=[[900, 10], [10, 700]])
+    cands = W.make_candidates(p, 0, 79, 2, 6, 0, 40)
+    want = oracle.plan_batch(oracle.build_tables(p), cands)
+    tables, ran = _plan_all_paths(harp, ctx, p, cands, want, "odd degrees")
+    assert ran == [harp.PATH_GENERIC]
+    # asking for the 32-bit path on such tables is an error, not a silent switch
+    dc = harp.DeviceCandidates(ctx, cands)
+    out = harp.DevicePlans(ctx, dc.C, dc.S_max)
+    ws = harp.plan_workspace(ctx, tables, dc)
+    ctx.set_plan_path(harp.PATH_FAST32)
+    try:
+        with pytest.raises(harp.HarpError) as e:
+            harp.harp_plan_batch(ctx, tables, dc, out, ws)
+        assert e.value.code == harp.ERR_UNIMPLEMENTED
+    finally:
+        ctx.set_plan_path(harp.PATH_AUTO)
+
+
+def test_plan_wide_times_use_generic_path(harp, ctx):
+    """Times beyond 32 bits: the int64 path must carry them exactly."""
+    rng = np.random.default_rng(9)
+    L = 40
+    fwd = rng.integers(1, 1 << 36, size=(2, L))
+    p = simple_problem(np.zeros(L), M=50, T=2, G=2, ndev=(4, 4), tp=(1, 2, 4), fwd=fwd, bwd=fwd // 3,
+                       act=rng.integers(0, 1 << 40, size=L), gtype=[0, 1], bw=[[1 << 20, 5], [5, 1 << 18]])
+    cands = W.make_candidates(p, 0, 80, 2, 8, 0, 64)
+    want = oracle.plan_batch(oracle.build_tables(p), cands)
+    assert (want.status == oracle.OK).all() and want.iter_time.max() > (1 << 40)
+    _, ran = _plan_all_paths(harp, ctx, p, cands, want, "wide times")
+    assert ran == [harp.PATH_GENERIC]
+
+
+def test_invalid_and_degenerate_candidates(harp, ctx):
+    p = simple_problem([3, 1, 4, 1, 5, 9], G=2, ndev=(2, 2), tp=(1, 2), bw=np.full((2, 2), 2),
+                       act=[5] * 6)
+    lists = [
+        [(0, 1), (1, 1), (0, 1)],       # group revisited
+        [(0, 2), (0, 1)],               # over-subscribed
+        [(0, 3)],                       # degree not allowed
+        [(2, 1)],                       # no such group
+        [(-1, 1)],                      # negative group
+        [(0, 0)],                       # degree below 1
+        [],                             # no stage
+        [(0, 1), (1, 2)],               # fine
+        [(1, 1)] * 2 + [(0, 1)] * 2,    # fine, S = 4
+    ]
+    cands = cands_from_lists(lists, S_max=8)
+    extra = cands_from_lists([[(0, 1)] * 2 + [(1, 1)] * 2], S_max=8)
+    extra.cand_S[0] = 9                 # S beyond S_max
+    cands = W.Candidates(cands.C + 1, 8, np.concatenate([cands.cand_S, extra.cand_S]),
+                         np.concatenate([cands.cand_group, extra.cand_group]),
+                         np.concatenate([cands.cand_tp, extra.cand_tp]))
+    want = oracle.plan_batch(oracle.build_tables(p), cands)
+    assert list(want.status) == [2, 2, 2, 2, 2, 2, 2, 0, 0, 2]
+    _plan_all_paths(harp, ctx, p, cands, want, "invalid candidates")
+    # more stages than operators
+    p = simple_problem([1, 1], ndev=(4,))
+    cands = cands_from_lists([same_slot(3), same_slot(2), same_slot(1)])
+    want = oracle.plan_batch(oracle.build_tables(p), cands)
+    assert list(want.status) == [1, 0, 0]
+    _plan_all_paths(harp, ctx, p, cands, want, "S > L")
+
+
+def test_empty_batch_and_argument_errors(harp, ctx):
+    import torch
+    w = W.make("tiny")
+    tables = harp.Tables(ctx, w.problem)
+    empty = w.candidates(0, 0)
+    dc = harp.DeviceCandidates(ctx, empty)
+    out = harp.DevicePlans(ctx, 0, dc.S_max)
+    ws = harp.plan_workspace(ctx, tables, dc)
+    harp.harp_plan_batch(ctx, tables, dc, out, ws)          # C = 0: nothing to do, no error
+    torch.cuda.synchronize()
+    dc = harp.DeviceCandidates(ctx, w.candidates())
+    out = harp.DevicePlans(ctx, dc.C, dc.S_max)
+    small = torch.empty(256, dtype=torch.uint8, device=ctx.device)
+    with pytest.raises(harp.HarpError) as e:
+        harp.harp_plan_batch(ctx, tables, dc, out, small)
+    assert e.value.code == harp.ERR_WORKSPACE
+    ws = harp.plan_workspace(ctx, tables, dc)
+    with pytest.raises(harp.HarpError) as e:
+        harp.harp_plan_batch(ctx, tables, dc, out, ws[1:])  # misaligned
+    assert e.value.code == harp.ERR_WORKSPACE
+    dc.c.S_max = 0
+    with pytest.raises(harp.HarpError) as e:
+        harp.harp_plan_batch(ctx, tables, dc, out, ws)
+    assert e.value.code == harp.ERR_SHAPE
+    with pytest.raises(harp.HarpError) as e:
+        ctx.set_plan_path(9)
+    assert e.value.code == harp.ERR_INVALID_ARG
+
+
+# ------------------------------------------------------------------ scorer and selection
+
+def test_score_parity_on_arbitrary_partitions(harp, ctx):
+    import torch
+    rng = np.random.default_rng(2)
+    seen = set()
+    for name, n in (("tiny", 16), ("llama7b", 1024), ("llama70b", 2048), ("stress", 2048)):
+        w = W.make(name)
+        cands = w.candidates(0, n)
+        L = w.problem.L
+        splits = np.full((n, cands.S_max + 1), -1, dtype=np.int32)
+        for c in range(n):
+            S = int(cands.cand_S[c])
+            cut = np.sort(rng.choice(np.arange(1, L), size=S - 1, replace=False))
+            splits[c, :S + 1] = [0, *cut, L]
+        splits[3, 1] = splits[3, 2]                 # not strictly increasing
+        splits[5, 0] = 1                            # does not start at 0
+        splits[7, int(cands.cand_S[7])] = L - 1     # does not end at L
+        want = oracle.score_1f1b(oracle.build_tables(w.problem), cands, splits)
+        tables = harp.Tables(ctx, w.problem)
+        dc = harp.DeviceCandidates(ctx, cands)
+        sp = torch.from_numpy(splits).to(ctx.device)
+        b = torch.full((n,), -7, dtype=torch.int64, device=ctx.device)
+        t = torch.full((n,), -7, dtype=torch.int64, device=ctx.device)
+        st = torch.full((n,), -7, dtype=torch.int32, device=ctx.device)
+        harp.harp_score_1f1b(ctx, tables, dc, sp, b, t, st)
+        torch.cuda.synchronize()
+        assert (st.cpu().numpy() == want[2]).all()
+        assert (b.cpu().numpy() == want[0]).all() and (t.cpu().numpy() == want[1]).all()
+        seen |= set(int(x) for x in np.unique(want[2]))
+    assert seen == {0, 1, 2}
+
+
+def test_argmin_parity(harp, ctx):
+    import torch
+    rng = np.random.default_rng(3)
+    for n in (0, 1, 63, 64, 1000, 70001):
+        it = rng.integers(10, 50, size=n).astype(np.int64)
+        st = rng.integers(0, 3, size=n).astype(np.int32)
+        for status in (st, np.ones(n, dtype=np.int32)):
+            want = oracle.argmin_batch(it, status)
+            bt = torch.full((1,), -7, dtype=torch.int64, device=ctx.device)
+            bi = torch.full((1,), -7, dtype=torch.int32, device=ctx.device)
+            harp.harp_argmin_batch(ctx, n, torch.from_numpy(it).to(ctx.device),
+                                   torch.from_numpy(status).to(ctx.device), bt, bi)
+            torch.cuda.synchronize()
+            assert (int(bt.item()), int(bi.item())) == want
+
+
+# ------------------------------------------------------------------ full size, bench configuration
+
+def test_stress_full_batch_properties_and_samples(harp, ctx):
+    """The whole stress batch in the configuration bench.py times (auto path): sampled candidates
+    against the oracle one by one, and properties that hold at any size for all of them."""
+    import torch
+    w = W.make("stress")
+    cands = w.candidates()
+    tables = harp.Tables(ctx, w.problem)
+    assert tables.fast32
+    dc = harp.DeviceCandidates(ctx, cands)
+    out = harp.DevicePlans(ctx, dc.C, dc.S_max)
+    ws = harp.plan_workspace(ctx, tables, dc)
+    out.poison()
+    harp.harp_plan_batch(ctx, tables, dc, out, ws)
+    torch.cuda.synchronize()
+    got = out.to_host()
+    # determinism: a second launch is byte-identical (integer min/max has no order dependence)
+    out2 = harp.DevicePlans(ctx, dc.C, dc.S_max)
+    harp.harp_plan_batch(ctx, tables, dc, out2, ws)
+    torch.cuda.synchronize()
+    assert_plans_equal(out2.to_host(), got, "second launch")
+    # sampled candidates against the oracle
+    idx = np.random.default_rng(0).choice(w.C, size=320, replace=False)
+    sample = cands.take(idx)
+    want = oracle_plan_threaded(oracle.build_tables(w.problem), sample)
+    class _Sub:
+        pass
+    sub = _Sub()
+    for name in ("status", "splits", "dev_first", "bottleneck", "iter_time"):
+        setattr(sub, name, getattr(got, name)[idx])
+    assert_plans_equal(sub, want, "stress sample")
+    # properties over the whole batch
+    ok = got.status == 0
+    frac_bad = float((got.status == 1).mean())
+    assert 0.25 < frac_bad < 0.35 and (got.status != 2).all()
+    S = cands.cand_S.astype(np.int64)
+    rows = np.arange(w.C)
+    assert (got.splits[ok, 0] == 0).all() and (got.splits[rows[ok], S[ok]] == w.problem.L).all()
+    width = np.arange(cands.S_max + 1)[None, :]
+    inside = width <= S[:, None]
+    d = np.diff(got.splits.astype(np.int64), axis=1)
+    assert (d[ok][inside[ok][:, 1:]] > 0).all()
+    assert (got.splits[ok][~inside[ok]] == -1).all()
+    assert (got.splits[~ok] == -1).all() and (got.bottleneck[~ok] == oracle.INF).all()
+    # the stand-alone scorer reproduces the planner's own numbers from its cuts
+    b = torch.empty_like(out.bottleneck)
+    t = torch.empty_like(out.iter_time)
+    st = torch.empty_like(out.status)
+    harp.harp_score_1f1b(ctx, tables, dc, out.splits, b, t, st)
+    torch.cuda.synchronize()
+    assert (b.cpu().numpy()[ok] == got.bottleneck[ok]).all()
+    assert (t.cpu().numpy()[ok] == got.iter_time[ok]).all()
+    assert (st.cpu().numpy()[ok] == 0).all() and (st.cpu().numpy()[~ok] == 2).all()
+    # selection
+    bt = torch.empty(1, dtype=torch.int64, device=ctx.device)
+    bi = torch.empty(1, dtype=torch.int32, device=ctx.device)
+    harp.harp_argmin_batch(ctx, w.C, out.iter_time, out.status, bt, bi)
+    torch.cuda.synchronize()
+    assert (int(bt.item()), int(bi.item())) == oracle.argmin_batch(got.iter_time, got.status)
