@@ -1,0 +1,167 @@
+"""Benchmark of the planner-search hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic candidates, inputs resident in
+HBM: build the segment-cost tables, plan every candidate (recurrence, backtrack, fused score),
+select the best plan.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload stress] [--path auto|generic]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# int32 VALU peak of one MI355X: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz lane-operations per second
+ALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
+# accounting convention for one transition of the dense recurrence: 13 int64 operations
+# (time: 2 sub, add, shift, add; memory: 2 sub, mul, add, compare; combine: 2 max, 1 min-select),
+# each counted as two 32-bit lane-operations
+LANE_OPS_PER_TRANSITION = 26
+# HBM bytes per launch of the planner kernel on the stress workload, from rocprofv3 counters
+# (profiles/k2_fast_stress_pmc.txt); None until measured
+MEASURED_TRAFFIC_BYTES = {"stress": None}
+
+
+def cpu_baseline(w, cands, gpu_plans, budget_candidates):
+    """The oracle as it stands, timed on the host cores over the first candidates of the batch;
+    the same run checks the GPU's plans for those candidates bit for bit."""
+    from concurrent.futures import ThreadPoolExecutor
+
+    import numpy as np
+
+    import oracle
+    from paper_2509_24859_amd import workloads
+
+    cores = min(16, len(os.sched_getaffinity(0)))
+    n = min(cands.C, budget_candidates)
+    sample = cands.slice(0, n)
+    tables = oracle.build_tables(w.problem)
+    out = oracle.Plans(n, sample.S_max)
+    step = max(1, min(16, n // (cores * 4) or 1))
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(cores) as ex:
+        list(ex.map(lambda lo: oracle.plan_batch(tables, sample, lo, min(lo + step, n), out),
+                    range(0, n, step)))
+    dt = time.perf_counter() - t0
+    for name in ("status", "splits", "dev_first", "bottleneck", "iter_time"):
+        if not (getattr(out, name) == getattr(gpu_plans, name)[:n]).all():
+            raise SystemExit("GPU plans differ from the oracle in %s on the baseline sample" % name)
+    cells, trans = workloads.dense_counts(w.problem.L, sample.cand_S)
+    return {"value": n / dt, "unit": "plans/s", "cores": cores, "kind": "oracle",
+            "sample": "first %d candidates of the %s batch, %d threads over candidates, %.1f s wall; "
+                      "GPU plans for the sample verified bit-exact in the same run" % (n, w.name, cores, dt),
+            "transitions_per_s": float(trans.sum()) / dt, "cells_per_s": float(cells.sum()) / dt}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="stress")
+    ap.add_argument("--path", default="auto", choices=("auto", "generic", "fast32"))
+    ap.add_argument("--candidates", type=int, default=0, help="use only the first N candidates")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-candidates", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        raise SystemExit("bench.py measures one GPU: this build has no multi-GPU path "
+                         "(candidates would shard across GPUs with one 16-byte reduction); run with --gpus 1")
+
+    import numpy as np
+    import torch
+
+    from paper_2509_24859_amd import binding, workloads
+
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs the GPU: there is no CPU path")
+    ctx = binding.Context(0)
+    w = workloads.make(args.workload)
+    C = args.candidates or w.C
+    cands = w.candidates(0, C)
+    cells, trans = workloads.dense_counts(w.problem.L, cands.cand_S)
+    n_cells, n_trans = float(cells.sum()), float(trans.sum())
+
+    dp = binding.DeviceProblem(ctx, w.problem)
+    dc = binding.DeviceCandidates(ctx, cands)
+    out = binding.DevicePlans(ctx, dc.C, dc.S_max)
+    tables = binding.Tables(ctx, dp)
+    ws = binding.plan_workspace(ctx, tables, dc)
+    best_t = torch.empty(1, dtype=torch.int64, device=ctx.device)
+    best_i = torch.empty(1, dtype=torch.int32, device=ctx.device)
+    path = {"auto": binding.PATH_AUTO, "generic": binding.PATH_GENERIC, "fast32": binding.PATH_FAST32}[args.path]
+    ctx.set_plan_path(path)
+    kernel = "k2_fast" if (tables.fast32 and path != binding.PATH_GENERIC) else "k2_generic"
+
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+          for _ in range(args.steps)]
+
+    def step(k=None):
+        tables.rebuild()                       # a1: tables (enqueue)
+        tables.finalize()                      #     verdict on the problem's values
+        if k is not None:
+            ev[k][0].record()
+        binding.harp_plan_batch(ctx, tables, dc, out, ws)          # a2-a4
+        if k is not None:
+            ev[k][1].record()
+        binding.harp_argmin_batch(ctx, dc.C, out.iter_time, out.status, best_t, best_i)  # a5
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(k)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    kernel_ms = sum(a.elapsed_time(b) for a, b in ev) / args.steps
+    got = out.to_host()
+    achieved = n_trans * LANE_OPS_PER_TRANSITION / (kernel_ms * 1e-3)
+    traffic = MEASURED_TRAFFIC_BYTES.get(args.workload) if C == w.C and kernel == "k2_fast" else None
+    result = {
+        "metric": "candidate plans/sec (and DP cells/sec) on 1 MI355X",
+        "value": C * args.steps / elapsed,
+        "unit": "plans/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": elapsed / args.steps * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int64" if kernel == "k2_generic" else "u32 times / int64 bytes",
+        "data": "synthetic",
+        "config": {"workload": "%s: L=%d operators, %d candidates, S<=%d, M=%d, %d groups, %d GPU types"
+                               % (w.name, w.problem.L, C, w.S_max, w.problem.M, w.problem.G, w.problem.T),
+                   "plan_path": args.path, "kernel": kernel},
+        "cells_per_s": n_cells * args.steps / elapsed,
+        "dense_transitions_per_s": n_trans * args.steps / elapsed,
+        "plan_kernel_ms": kernel_ms,
+        "feasible_fraction": float((got.status == 0).mean()),
+        "best_plan": {"index": int(best_i.item()), "iter_time_us": int(best_t.item())},
+        "roofline": {
+            "bound": "alu", "kernel": kernel,
+            "achieved": achieved / 1e12, "peak": ALU_PEAK_LANE_OPS / 1e12, "unit": "T int32 lane-op/s",
+            "frac": achieved / ALU_PEAK_LANE_OPS, "traffic": traffic,
+            "note": "achieved = dense-recurrence transitions per launch x 26 lane-ops / mean kernel time "
+                    "(HIP events on the launch stream); the kernel evaluates fewer transitions than the "
+                    "dense count (bounded scans), so this is work delivered, not instructions issued",
+        },
+    }
+    if not args.no_cpu_baseline:
+        # about 20 core-seconds of oracle work at 1-5 ns per dense transition
+        budget = args.cpu_candidates or max(64, int(1.6e10 / max(1.0, n_trans / C)))
+        result["cpu_baseline"] = cpu_baseline(w, cands, got, budget)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()
