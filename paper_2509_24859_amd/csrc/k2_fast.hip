@@ -24,9 +24,12 @@
 // Mapping: one workgroup per candidate at a time (persistent workgroups stride over the batch),
 // one lane per DP cell of the current stage, lanes of a wave on consecutive cells so that LDS
 // reads of (D[j], P[j]) pairs are stride-1 or broadcast.  The previous DP row and the slot's P row
-// sit interleaved in LDS so that one 8-byte read feeds a transition.  The single cell of the last
-// stage is reduced across a wavefront with a lexicographic (value, j) minimum.  Back-pointers go
-// to a per-workgroup slice of the caller's workspace as uint16.
+// sit interleaved in LDS so that one 8-byte read feeds a transition.  Everything stage s+1 needs
+// from global memory (its slot's P row, the memory row, the link's cut times) is requested at the
+// top of stage s, lands in registers while stage s scans, and is committed to the other LDS
+// buffer before the single barrier that ends the stage.  The lone cell of the last stage is
+// reduced across a wavefront with a lexicographic (value, j) minimum.  Back-pointers go to a
+// per-workgroup slice of the caller's workspace as uint16.
 #include "harp_internal.h"
 #include "plan_common.h"
 
@@ -36,28 +39,59 @@ namespace {
 
 constexpr uint32_t kInf32 = 0xFFFFFFFFu;
 constexpr int kMaxThreads = 1024;
+constexpr int kPad = 4;
 
 struct alignas(8) Pair {
     uint32_t d;   // previous DP row
     uint32_t p;   // fused time row of the stage's slot
 };
 
+// Workgroup barrier that orders LDS traffic only.  Global loads and stores stay in flight across
+// it (the stage loop never communicates through global memory), which keeps the round trips of the
+// back-pointer stores and of the next stage's table rows off the per-stage critical path.
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 __device__ __forceinline__ uint32_t umax3(uint32_t a, uint32_t b, uint32_t c) {
     uint32_t m = a > b ? a : b;
     return m > c ? m : c;
 }
 
+// Per-slot constants of the candidate in flight, computed once per candidate so that the stage
+// loop starts from LDS and never waits on a chain of dependent global loads.
+struct StageConst {
+    int64_t cap[kMaxStages];       // tp * device memory of the slot's GPU type
+    uint32_t p_row[kMaxStages];    // element offset of the slot's fused time row
+    uint32_t cm_row[kMaxStages];   // element offset of the cut-time row of the link to the next slot
+    uint8_t shift[kMaxStages];     // log2 tp
+};
+
+// What one thread stages for the next DP stage: PER entries of the P, memory and cut rows.
+template <int PER>
+struct Staged {
+    uint32_t p[PER], c[PER];
+    int64_t pp[PER], ps[PER];
+};
+
+template <int PER>
 __global__ __launch_bounds__(kMaxThreads) void k2_fast(TablesDev tb, CandDev cd, PlansDev out,
                                                         unsigned char *ws, size_t ws_per_group,
                                                         int row_len) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     __shared__ SlotInfo slots;
-    __shared__ int fmax_s[2];
+    __shared__ StageConst sc;
+    __shared__ int fmax_s[3];
 
     const int L = tb.L, S_max = cd.S_max;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nthreads = blockDim.x;
-    int64_t *Q = reinterpret_cast<int64_t *>(lds_raw);                    // [row_len]
-    Pair *rows = reinterpret_cast<Pair *>(lds_raw + size_t(row_len) * 8); // [2][row_len]
+    // every LDS row has kPad spare entries in front, so that the group of four previous cuts
+    // ending at any j >= 0 can be read at fixed offsets without clamping
+    int64_t *Qb = reinterpret_cast<int64_t *>(lds_raw) + kPad;                        // [2][row_len]
+    Pair *rows = reinterpret_cast<Pair *>(lds_raw + size_t(row_len) * 16) + kPad;     // [2][row_len]
+    uint32_t *cutb = reinterpret_cast<uint32_t *>(lds_raw + size_t(row_len) * 32);    // [2][row_len]
     uint16_t *arg = reinterpret_cast<uint16_t *>(ws + size_t(blockIdx.x) * ws_per_group);
     const int64_t *PP = tb.PP(), *PS = tb.PS();
 
@@ -71,125 +105,184 @@ __global__ __launch_bounds__(kMaxThreads) void k2_fast(TablesDev tb, CandDev cd,
             write_failed(out, c, S_max, status);
             continue;
         }
-        if (tid == 0) { rows[0].d = 0; fmax_s[0] = 0; }
-        // fused time row of slot 0 into buffer 0
-        {
-            const uint32_t *p32 = tb.P32 + (int64_t(slots.g[0]) * tb.n_tp + slots.k[0]) * tb.pitch32;
-            for (int j = tid; j <= L; j += nthreads) rows[j].p = p32[j];
-        }
-        __syncthreads();
-
-        int cur = 0;
+        int32_t *sp = out.splits + int64_t(c) * (S_max + 1);
         bool dead = false;
-        for (int s = 0; s < S; ++s) {
-            const int g = slots.g[s], k = slots.k[s];
-            const uint32_t tp = (uint32_t)tb.tp[k];
-            const int shift = tb.tp_shift[k];
-            const int t = tb.group_type[g];
-            const int64_t n_inflight = (S - s) < tb.M ? (S - s) : tb.M;
-            const int64_t cap = int64_t(tp) * tb.type_mem[t];
-            const bool last = (s == S - 1);
-            const int i_lo = last ? L : s + 1, i_hi = L - (S - 1 - s);
-            Pair *prev = rows + size_t(cur) * row_len;
-            Pair *next = rows + size_t(cur ^ 1) * row_len;
-            const int fmax_prev = fmax_s[cur];
-            // memory row of this stage, and the next slot's time row into the other buffer
-            for (int j = s + tid; j <= i_hi; j += nthreads) Q[j] = PP[j] + n_inflight * PS[j];
-            if (!last) {
-                const uint32_t *p32 = tb.P32 + (int64_t(slots.g[s + 1]) * tb.n_tp + slots.k[s + 1]) * tb.pitch32;
-                for (int j = s + 1 + tid; j <= L; j += nthreads) next[j].p = p32[j];
+        if (S >= 2) {
+            const int R = L - S + 1;          // cells per stage; stage s touches rows s .. s+R
+            for (int s = tid; s < S; s += nthreads) {
+                const int g = slots.g[s], k = slots.k[s];
+                sc.cap[s] = int64_t(tb.tp[k]) * tb.type_mem[tb.group_type[g]];
+                sc.p_row[s] = uint32_t((int64_t(g) * tb.n_tp + k) * tb.pitch32);
+                sc.cm_row[s] = uint32_t((int64_t(g) * tb.G + (s + 1 < S ? slots.g[s + 1] : g)) * tb.pitch32);
+                sc.shift[s] = (uint8_t)tb.tp_shift[k];
             }
-            if (tid == 0) fmax_s[cur ^ 1] = -1;
             __syncthreads();
-
-            uint16_t *arg_row = arg + size_t(s) * row_len;
-            if (!last) {
-                const uint32_t *cm = tb.CM + (int64_t(g) * tb.G + slots.g[s + 1]) * tb.pitch32;
-                for (int i0 = i_lo; i0 <= i_hi; i0 += nthreads) {
-                    const int i = i0 + tid;
-                    const bool live = i <= i_hi;
-                    uint32_t best = kInf32;
-                    int best_j = 0;
-                    if (live) {
-                        // fitting cuts: j >= lo, lo = first j in [s, i] with Q[j] >= Q[i] - cap
-                        const int64_t th = Q[i] - cap;
-                        int lo = s;
-                        if (Q[s] < th) {
-                            int a = s, b = i;           // Q[a] < th <= Q[b]
-                            while (b - a > 1) {
-                                const int m = (a + b) >> 1;
-                                if (Q[m] < th) a = m; else b = m;
-                            }
-                            lo = b;
-                        }
-                        const int hi = (i - 1) < fmax_prev ? (i - 1) : fmax_prev;
-                        const uint32_t cut = cm[i];
-                        const uint32_t xi = prev[i].p + tp - 1;
-                        for (int j = hi; j >= lo; --j) {
-                            const Pair e = prev[j];
-                            const uint32_t tj = (xi - e.p) >> shift;
-                            const uint32_t v = umax3(e.d, tj, cut);
-                            if (v <= best) { best = v; best_j = j; }
-                            if (tj > best) break;
-                        }
-                        next[i].d = best;
-                        arg_row[i] = (uint16_t)best_j;
-                    }
-                    const unsigned long long finite = __ballot(live && best != kInf32);
-                    if (lane == 0 && finite) atomicMax(&fmax_s[cur ^ 1], i0 + wave * 64 + 63 - __clzll(finite));
-                }
-            } else if (wave == 0) {
-                // the last stage has the single cell i = L: lanes over j, lexicographic reduction
-                const int i = L;
-                const int64_t th = Q[i] - cap;
-                const uint32_t xi = prev[i].p + tp - 1;
-                const int hi = (i - 1) < fmax_prev ? (i - 1) : fmax_prev;
-                uint32_t best = kInf32;
-                int best_j = INT32_MAX;
-                for (int j = s + lane; j <= hi; j += 64) {
-                    if (Q[j] < th) continue;
-                    const Pair e = prev[j];
-                    const uint32_t tj = (xi - e.p) >> shift;
-                    const uint32_t v = e.d > tj ? e.d : tj;
-                    if (v < best) { best = v; best_j = j; }   // j rises within a lane
-                }
+            // global loads for stage sn into registers
+            auto fetch = [&](int sn, Staged<PER> &r) {
+                const uint32_t *p32 = tb.P32 + sc.p_row[sn];
+                const bool has_cut = sn < S - 1;
+                const uint32_t *cm = tb.CM + sc.cm_row[sn];
 #pragma unroll
-                for (int d = 32; d >= 1; d >>= 1) {
-                    const uint32_t ov = __shfl_xor(best, d, 64);
-                    const int oj = __shfl_xor(best_j, d, 64);
-                    if (ov < best || (ov == best && oj < best_j)) { best = ov; best_j = oj; }
+                for (int q = 0; q < PER; ++q) {
+                    const int j = sn + tid + q * nthreads;
+                    const bool ok = j <= sn + R;
+                    r.p[q] = ok ? p32[j] : 0u;
+                    r.pp[q] = ok ? PP[j] : 0;
+                    r.ps[q] = ok ? PS[j] : 0;
+                    r.c[q] = (ok && has_cut) ? cm[j] : 0u;
                 }
-                if (lane == 0) {
-                    next[i].d = best;
-                    arg_row[i] = (uint16_t)(best == kInf32 ? 0 : best_j);
-                    fmax_s[cur ^ 1] = best == kInf32 ? -1 : i;
+            };
+            // registers into the LDS buffer that stage sn will read
+            auto commit = [&](int sn, int buf, const Staged<PER> &r) {
+                const int64_t n_inflight = (S - sn) < tb.M ? (S - sn) : tb.M;
+#pragma unroll
+                for (int q = 0; q < PER; ++q) {
+                    const int j = sn + tid + q * nthreads;
+                    if (j <= sn + R) {
+                        rows[size_t(buf) * row_len + j].p = r.p[q];
+                        Qb[size_t(buf) * row_len + j] = r.pp[q] + n_inflight * r.ps[q];
+                        cutb[size_t(buf) * row_len + j] = r.c[q];
+                    }
                 }
+            };
+            Staged<PER> staged;
+            fetch(0, staged);
+            if (tid == 0) { rows[0].d = 0; fmax_s[0] = 0; fmax_s[1] = -1; }
+            commit(0, 0, staged);
+            lds_barrier();
+
+            int cur = 0;
+            for (int s = 0; s < S; ++s) {
+                const int shift = sc.shift[s];
+                const uint32_t tp = 1u << shift;
+                const int64_t cap = sc.cap[s];
+                const bool last = (s == S - 1);
+                const int i_hi = s + R;
+                const Pair *prev = rows + size_t(cur) * row_len;
+                Pair *next = rows + size_t(cur ^ 1) * row_len;
+                const int64_t *Q = Qb + size_t(cur) * row_len;
+                const uint32_t *cut = cutb + size_t(cur) * row_len;
+                const int fmax_prev = fmax_s[s % 3];
+                int *fmax_next = &fmax_s[(s + 1) % 3];
+                if (tid == 0) fmax_s[(s + 2) % 3] = -1;
+                if (!last) fetch(s + 1, staged);
+
+                uint16_t *arg_row = arg + size_t(s) * row_len;
+                if (!last) {
+                    // one cell per thread in all but oversized problems; the first pass keeps its
+                    // back-pointer in a register so that the global store can follow the commit
+                    int first_j = 0;
+                    for (int i0 = s + 1; i0 <= i_hi; i0 += nthreads) {
+                        const int i = i0 + tid;
+                        const bool live = i <= i_hi;
+                        uint32_t best = kInf32;
+                        int best_j = 0;
+                        if (live) {
+                            // fitting cuts are j >= lo with Q[lo] >= Q[i] - cap (memory need is
+                            // monotone in j), so the downward scan also stops at the first misfit
+                            const int64_t th = Q[i] - cap;
+                            const uint32_t xi = prev[i].p + tp - 1;
+                            const uint32_t cut_i = cut[i];
+                            // Four previous cuts per trip, read at fixed offsets below j.  An
+                            // entry counts while j >= s and it fits in memory; both conditions
+                            // are monotone in j, so they are plain predicates.  Entries below a
+                            // stop cannot update (their time exceeds the best value), so only
+                            // the last entry of a trip decides whether the lane goes on.
+                            int j = (i - 1) < fmax_prev ? (i - 1) : fmax_prev;
+                            bool more = true;
+                            while (more) {
+                                const Pair *pe = prev + (j - 3);
+                                const int64_t *pq = Q + (j - 3);
+                                const Pair e3 = pe[0], e2 = pe[1], e1 = pe[2], e0 = pe[3];
+                                const int64_t q3 = pq[0], q2 = pq[1], q1 = pq[2], q0 = pq[3];
+                                uint32_t tj;
+#define HARP_STEP(E, QV, JJ)                                                   \
+    {                                                                          \
+        tj = (xi - (E).p) >> shift;                                            \
+        const uint32_t v = umax3((E).d, tj, cut_i);                            \
+        const bool upd = ((JJ) >= s) & ((QV) >= th) & (v <= best);             \
+        best = upd ? v : best;                                                 \
+        best_j = upd ? (JJ) : best_j;                                          \
+    }
+                                HARP_STEP(e0, q0, j)
+                                HARP_STEP(e1, q1, j - 1)
+                                HARP_STEP(e2, q2, j - 2)
+                                HARP_STEP(e3, q3, j - 3)
+#undef HARP_STEP
+                                more = ((j - 3) > s) & (q3 >= th) & (tj <= best);
+                                j -= 4;
+                            }
+                            next[i].d = best;
+                            if (i0 == s + 1) first_j = best_j;
+                            else arg_row[i] = (uint16_t)best_j;
+                        }
+                        const unsigned long long finite = __ballot(live && best != kInf32);
+                        if (lane == 0 && finite) atomicMax(fmax_next, i0 + wave * 64 + 63 - __clzll(finite));
+                    }
+                    commit(s + 1, cur ^ 1, staged);
+                    if (s + 1 + tid <= i_hi) arg_row[s + 1 + tid] = (uint16_t)first_j;
+                } else if (wave == 0) {
+                    // the last stage has the single cell i = L: lanes over j, lexicographic reduction
+                    const int i = L;
+                    const int64_t th = Q[i] - cap;
+                    const uint32_t xi = prev[i].p + tp - 1;
+                    const int hi = (i - 1) < fmax_prev ? (i - 1) : fmax_prev;
+                    uint32_t best = kInf32;
+                    int best_j = INT32_MAX;
+                    for (int j = s + lane; j <= hi; j += 64) {
+                        if (Q[j] < th) continue;
+                        const Pair e = prev[j];
+                        const uint32_t tj = (xi - e.p) >> shift;
+                        const uint32_t v = e.d > tj ? e.d : tj;
+                        if (v < best) { best = v; best_j = j; }   // j rises within a lane
+                    }
+#pragma unroll
+                    for (int d = 32; d >= 1; d >>= 1) {
+                        const uint32_t ov = __shfl_xor(best, d, 64);
+                        const int oj = __shfl_xor(best_j, d, 64);
+                        if (ov < best || (ov == best && oj < best_j)) { best = ov; best_j = oj; }
+                    }
+                    if (lane == 0) {
+                        arg_row[i] = (uint16_t)(best == kInf32 ? 0 : best_j);
+                        *fmax_next = best == kInf32 ? -1 : i;
+                    }
+                }
+                lds_barrier();
+                cur ^= 1;
+                if (*fmax_next < 0) { dead = true; break; }   // uniform: no cell of this row is reachable
             }
-            __syncthreads();
-            cur ^= 1;
-            if (fmax_s[cur] < 0) { dead = true; break; }   // uniform: no cell of this row is reachable
+            __syncthreads();          // back-pointers of every wave are visible to thread 0
+            if (!dead && tid == 0) {
+                int b = L;
+                sp[S] = L;
+                for (int s = S - 1; s >= 0; --s) { b = arg[size_t(s) * row_len + b]; sp[s] = b; }
+            }
+        } else if (tid == 0) {
+            sp[0] = 0;    // one stage holds every operator; the score below checks that it fits
+            sp[1] = L;
         }
         if (dead) {
             write_failed(out, c, S_max, HARP_CAND_INFEASIBLE);
             continue;
         }
-        int32_t *sp = out.splits + int64_t(c) * (S_max + 1);
-        if (tid == 0) {
-            int b = L;
-            sp[S] = L;
-            for (int s = S - 1; s >= 0; --s) { b = arg[size_t(s) * row_len + b]; sp[s] = b; }
-        }
         for (int s = S + 1 + tid; s <= S_max; s += nthreads) sp[s] = -1;
         int32_t *df = out.dev_first + int64_t(c) * S_max;
         for (int s = tid; s < S_max; s += nthreads) df[s] = s < S ? slots.dev_first[s] : -1;
         __syncthreads();              // the cuts written by thread 0 are read by the first wave
+        int st = HARP_CAND_OK;
         if (wave == 0) {
             int64_t bott, iter;
-            const int st = wave_score_partition(tb, S, slots, sp, lane, bott, iter);
+            st = wave_score_partition(tb, S, slots, sp, lane, bott, iter);
             if (lane == 0) {
                 out.bottleneck[c] = bott;
                 out.iter_time[c] = iter;
                 out.status[c] = st;
+            }
+        }
+        if (S == 1) {                 // a single stage that does not fit: no plan to report
+            if (__syncthreads_or(wave == 0 && st != HARP_CAND_OK)) {
+                for (int s = tid; s <= S_max; s += nthreads) sp[s] = -1;
+                for (int s = tid; s < S_max; s += nthreads) df[s] = -1;
             }
         }
     }
@@ -200,9 +293,9 @@ int fast_threads(int L) {
     return t > kMaxThreads ? kMaxThreads : t;
 }
 
-int fast_row_len(int L) { return (L + 1 + 7) / 8 * 8; }
+int fast_row_len(int L) { return (L + 1 + kPad + 7) / 8 * 8; }
 
-size_t fast_lds_bytes(int L) { return size_t(fast_row_len(L)) * (8 + 2 * sizeof(Pair)); }
+size_t fast_lds_bytes(int L) { return size_t(fast_row_len(L)) * (16 + 2 * sizeof(Pair) + 8); }
 
 }  // namespace
 
@@ -224,9 +317,14 @@ int plan_fast_groups(int L, int n_cu) {
 
 void launch_plan_fast(const TablesDev &tb, const CandDev &cd, const PlansDev &out, void *ws,
                       int n_groups, hipStream_t st) {
-    hipLaunchKernelGGL(k2_fast, dim3(n_groups), dim3(fast_threads(tb.L)), fast_lds_bytes(tb.L), st, tb,
-                       cd, out, static_cast<unsigned char *>(ws), plan_fast_ws_per_group(tb.L, cd.S_max),
-                       fast_row_len(tb.L));
+    const int threads = fast_threads(tb.L);
+    const size_t per_group = plan_fast_ws_per_group(tb.L, cd.S_max);
+    if (threads >= tb.L)
+        hipLaunchKernelGGL(k2_fast<1>, dim3(n_groups), dim3(threads), fast_lds_bytes(tb.L), st, tb, cd, out,
+                           static_cast<unsigned char *>(ws), per_group, fast_row_len(tb.L));
+    else
+        hipLaunchKernelGGL(k2_fast<2>, dim3(n_groups), dim3(threads), fast_lds_bytes(tb.L), st, tb, cd, out,
+                           static_cast<unsigned char *>(ws), per_group, fast_row_len(tb.L));
 }
 
 }  // namespace harp
