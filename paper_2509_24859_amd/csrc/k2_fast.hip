@@ -77,7 +77,7 @@ struct Staged {
 };
 
 template <int PER>
-__global__ __launch_bounds__(kMaxThreads) void k2_fast(TablesDev tb, CandDev cd, PlansDev out,
+__global__ __launch_bounds__(kMaxThreads) __attribute__((amdgpu_waves_per_eu(8, 8))) void k2_fast(TablesDev tb, CandDev cd, PlansDev out,
                                                         unsigned char *ws, size_t ws_per_group,
                                                         int row_len) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
