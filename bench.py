@@ -25,8 +25,8 @@ ALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
 # each counted as two 32-bit lane-operations
 LANE_OPS_PER_TRANSITION = 26
 # HBM bytes per launch of the planner kernel on the stress workload, from rocprofv3 counters
-# (profiles/k2_fast_stress_pmc.txt); None until measured
-MEASURED_TRAFFIC_BYTES = {"stress": None}
+# (profiles/k2_fast_stress_pmc.txt: FETCH_SIZE + WRITE_SIZE, each scaled by a plain copy's reading)
+MEASURED_TRAFFIC_BYTES = {"stress": 9.56e9 + 9.96e9}
 
 
 def cpu_baseline(w, cands, gpu_plans, budget_candidates):
@@ -70,6 +70,8 @@ def main():
     ap.add_argument("--candidates", type=int, default=0, help="use only the first N candidates")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-candidates", type=int, default=0)
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
+                    help="also run one plain device copy of this many MiB (reference for HBM counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py measures one GPU: this build has no multi-GPU path "
@@ -113,6 +115,12 @@ def main():
             ev[k][1].record()
         binding.harp_argmin_batch(ctx, dc.C, out.iter_time, out.status, best_t, best_i)  # a5
 
+    if args.copy_calibration:
+        src = torch.ones(args.copy_calibration << 20, dtype=torch.uint8, device=ctx.device)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
