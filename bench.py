@@ -60,6 +60,30 @@ def cpu_baseline(w, cands, gpu_plans, budget_candidates):
             "transitions_per_s": float(trans.sum()) / dt, "cells_per_s": float(cells.sum()) / dt}
 
 
+def tables_streaming(ctx, binding, workloads, torch, L, reps=10):
+    """Table build alone on an operator-level sequence: the launch that is HBM-bound by nature but
+    moves under 3 MB at the planner's own sizes.  Algorithmic bytes: every input read once, every
+    table row written once."""
+    p = workloads.long_sequence(L)
+    tables = binding.Tables(ctx, p)
+    n_rows = p.T + 2 + p.G * len(p.tp_degrees)
+    bytes_alg = (2 * p.T + 3) * 8 * p.L + n_rows * 8 * (p.L + 1)
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    tables.rebuild()
+    torch.cuda.synchronize()
+    a.record()
+    for _ in range(reps):
+        tables.rebuild()
+    b.record()
+    torch.cuda.synchronize()
+    tables.finalize()
+    ms = a.elapsed_time(b) / reps
+    rate = bytes_alg / (ms * 1e-3)
+    return {"kernel": "k1 (chunk sums, chunk-sum scan, row scan, finalize)", "L": p.L, "rows": n_rows,
+            "algorithmic_bytes": bytes_alg, "ms_per_build": ms, "bound": "hbm",
+            "achieved": rate / 1e9, "peak": 8000.0, "unit": "GB/s", "frac": rate / 8e12}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -70,6 +94,8 @@ def main():
     ap.add_argument("--candidates", type=int, default=0, help="use only the first N candidates")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-candidates", type=int, default=0)
+    ap.add_argument("--tables-L", type=int, default=1 << 20,
+                    help="operators of the table-build streaming measurement (0 = skip)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="also run one plain device copy of this many MiB (reference for HBM counters)")
     args = ap.parse_args()
@@ -164,6 +190,8 @@ def main():
                     "dense count (bounded scans), so this is work delivered, not instructions issued",
         },
     }
+    if args.tables_L:
+        result["tables_streaming"] = tables_streaming(ctx, binding, workloads, torch, args.tables_L)
     if not args.no_cpu_baseline:
         # about 20 core-seconds of oracle work at 1-5 ns per dense transition
         budget = args.cpu_candidates or max(64, int(1.6e10 / max(1.0, n_trans / C)))

@@ -64,7 +64,9 @@ static int64_t max64(int64_t a, int64_t b) { return a > b ? a : b; }
 int oracle_build_tables(const oracle_problem *p, int64_t *PF, int64_t *PP, int64_t *PS, int64_t *PR)
 {
     const int L = p->L, T = p->T, G = p->G, K = p->n_tp;
-    if (L < 1 || L > 65535 || T < 1 || G < 1 || p->M < 1 || K < 1 || K > 8 || p->ar_count < 0)
+    /* the tables themselves have no length limit beyond int32 comfort; planning is limited to
+     * 65535 operators (see oracle_plan_batch) */
+    if (L < 1 || L > (1 << 24) || T < 1 || G < 1 || p->M < 1 || K < 1 || K > 8 || p->ar_count < 0)
         return ORACLE_BAD_ARG;
     if (p->tp_degrees[0] != 1) return ORACLE_BAD_ARG;
     for (int k = 1; k < K; ++k)
@@ -298,6 +300,7 @@ int oracle_plan_batch(const oracle_problem *p, const int64_t *PF, const int64_t 
                       int32_t *status)
 {
     if (C < 0 || S_max < 1 || c_begin < 0 || c_end > C || c_begin > c_end) return ORACLE_BAD_ARG;
+    if (p->L > 65535) return ORACLE_BAD_ARG; /* the library plans at most 65535 operators */
     const int L = p->L;
     tables_view v = { p, PF, PP, PS, PR };
     int64_t *D0 = (int64_t *)malloc(sizeof(int64_t) * (size_t)(L + 1));

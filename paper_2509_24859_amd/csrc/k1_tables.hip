@@ -19,19 +19,36 @@ __device__ __forceinline__ int64_t ceil_div_u(int64_t a, int64_t b) {
     return (int64_t)(((unsigned long long)a + (unsigned long long)b - 1ull) / (unsigned long long)b);
 }
 
+// ceil(a / b) for a row-invariant divisor b with inv = 1.0 / b precomputed.  For a, b < 2^52 the
+// double product a * inv is within 1 of the true quotient, so one exact correction step on the
+// integer remainder gives floor(a / b); larger operands take the plain 64-bit division.  Exact
+// for all inputs; the point is that a table row costs a multiply per element instead of a
+// software division, which would otherwise out-weigh the HBM traffic of the row.
+constexpr int64_t kFastDivLimit = int64_t(1) << 52;
+
+__device__ __forceinline__ int64_t ceil_div_inv(int64_t a, int64_t b, double inv) {
+    if (a >= kFastDivLimit || b >= kFastDivLimit) return ceil_div_u(a, b);
+    int64_t q = (int64_t)((double)a * inv);
+    int64_t r = a - q * b;
+    if (r < 0) { q -= 1; r += b; }
+    else if (r >= b) { q += 1; r -= b; }
+    return q + (r != 0 ? 1 : 0);
+}
+
 // Value of element l of table row r, with the checks that belong to the inputs it touches.
 struct RowSource {
     const int64_t *a;     // first addend
     const int64_t *b;     // second addend or nullptr
     int64_t num_mul;      // all-reduce rows: ar_count * 2 * (tp - 1); 0 for plain rows
     int64_t den;          // all-reduce rows: tp * bw[g][g]
+    double inv_den;       // 1.0 / den
     bool is_ar;
     bool track_act;       // this row also reports max(act_bytes)
 };
 
 __device__ __forceinline__ RowSource row_source(const TablesDev &tb, int r) {
     RowSource s;
-    s.b = nullptr; s.num_mul = 0; s.den = 1; s.is_ar = false; s.track_act = false;
+    s.b = nullptr; s.num_mul = 0; s.den = 1; s.inv_den = 1.0; s.is_ar = false; s.track_act = false;
     if (r < tb.T) {
         s.a = tb.fwd_us + int64_t(r) * tb.L;
         s.b = tb.bwd_us + int64_t(r) * tb.L;
@@ -50,6 +67,7 @@ __device__ __forceinline__ RowSource row_source(const TablesDev &tb, int r) {
         int64_t link = tb.bw[int64_t(g) * tb.G + g];
         // a bad link value is reported by the finalize kernel; keep the division defined here
         s.den = (link >= 1 && link <= INT64_MAX / tp) ? tp * link : 1;
+        s.inv_den = 1.0 / (double)s.den;
     }
     return s;
 }
@@ -63,7 +81,7 @@ __device__ __forceinline__ int64_t row_value(const RowSource &s, int64_t l, cons
         if ((unsigned long long)x > act_seen) act_seen = (unsigned long long)x;
         if (x > lim.act_max || x > lim.elem_max) { ovf = 1; x = 0; }
         if (s.num_mul == 0) return 0;
-        int64_t v = ceil_div_u(s.num_mul * x, s.den);
+        int64_t v = ceil_div_inv(s.num_mul * x, s.den, s.inv_den);
         if (v > lim.elem_max) { ovf = 1; v = 0; }
         return v;
     }
@@ -95,7 +113,7 @@ __device__ __forceinline__ void report(BuildHeader *h, unsigned int bad, unsigne
 
 // Launch 1 (only when a row spans several chunks): sum of every chunk.
 __global__ __launch_bounds__(kScanThreads) void k1_chunk_sums(TablesDev tb, BuildLimits lim, int n_chunks) {
-    const int r = blockIdx.y, chunk = blockIdx.x;
+    const int r = blockIdx.x, chunk = blockIdx.y;   // rows fastest: a chunk of act_bytes is reused across rows while in L2
     const RowSource src = row_source(tb, r);
     unsigned int bad = 0, ovf = 0;
     unsigned long long act_seen = 0;
@@ -142,7 +160,7 @@ __global__ __launch_bounds__(kScanThreads) void k1_scan_chunk_sums(TablesDev tb,
 
 // Launch 3: scan each chunk, add the chunk's offset, write the table row (entry i = l + 1).
 __global__ __launch_bounds__(kScanThreads) void k1_scan_rows(TablesDev tb, BuildLimits lim, int n_chunks) {
-    const int r = blockIdx.y, chunk = blockIdx.x;
+    const int r = blockIdx.x, chunk = blockIdx.y;   // rows fastest: a chunk of act_bytes is reused across rows while in L2
     const RowSource src = row_source(tb, r);
     unsigned int bad = 0, ovf = 0;
     unsigned long long act_seen = 0;
@@ -271,7 +289,8 @@ __global__ __launch_bounds__(256) void k1_fast_rows(TablesDev tb) {
         tb.P32[int64_t(q) * tb.pitch32 + i] = (uint32_t)v;
     } else {
         int e = q - n_time_rows;
-        int64_t v = (i == 0) ? 0 : ceil_div_u(tb.act_bytes[i - 1], tb.bw[e]);
+        const int64_t link = tb.bw[e];
+        int64_t v = (i == 0) ? 0 : ceil_div_inv(tb.act_bytes[i - 1], link, 1.0 / (double)link);
         tb.CM[int64_t(e) * tb.pitch32 + i] = (uint32_t)v;
     }
 }
@@ -291,10 +310,10 @@ void launch_build(const TablesDev &tb, const BuildLimits &lim, hipStream_t st) {
     const int n_rows = tb.n_rows();
     hipLaunchKernelGGL(k1_clear_header, dim3(1), dim3(64), 0, st, tb.header);
     if (n_chunks > 1) {
-        hipLaunchKernelGGL(k1_chunk_sums, dim3(n_chunks, n_rows), dim3(kScanThreads), 0, st, tb, lim, n_chunks);
+        hipLaunchKernelGGL(k1_chunk_sums, dim3(n_rows, n_chunks), dim3(kScanThreads), 0, st, tb, lim, n_chunks);
         hipLaunchKernelGGL(k1_scan_chunk_sums, dim3(n_rows), dim3(kScanThreads), 0, st, tb, n_chunks);
     }
-    hipLaunchKernelGGL(k1_scan_rows, dim3(n_chunks, n_rows), dim3(kScanThreads), 0, st, tb, lim, n_chunks);
+    hipLaunchKernelGGL(k1_scan_rows, dim3(n_rows, n_chunks), dim3(kScanThreads), 0, st, tb, lim, n_chunks);
     hipLaunchKernelGGL(k1_finalize, dim3(1), dim3(256), 0, st, tb, lim);
     if (lim.want_fast) {
         const int q = tb.G * tb.n_tp + tb.G * tb.G;

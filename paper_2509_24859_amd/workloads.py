@@ -318,6 +318,24 @@ def random_small(seed: int, L_max: int = 10, S_cap: int = 5, odd_degrees: bool =
     return Workload("random_small", cid, seed, p, C=8, S_max=S_max, S_min=G)
 
 
+def long_sequence(L: int = 1 << 20, seed: int = 0) -> Problem:
+    """Operator-level problem for the table build alone: the stress workload's cluster (8 GPU
+    types, 32 groups, degrees 1-8) with L operators, standing in for the 10^4-10^5 operator graphs
+    that the paper's layer construction (section 5.1) starts from.  Too long to plan; it exists to
+    show the table build streaming at HBM rate."""
+    cid, T, G = 6, 8, 32
+    base = _uniform_int(_draw_u64(seed, cid, 0, L), 200, 3000)
+    fwd = _scaled(base, (1.0, 0.85, 0.7, 0.6, 0.5, 0.4, 0.3, 0.25), divide=True)
+    params = base * 2 * MB
+    act = _uniform_int(_draw_u64(seed, cid, 2, L), 8, 64) * MB
+    x = _draw_u64(seed, cid, 3, G * (G - 1) // 2)
+    inter = np.rint(_log_uniform(x, 1.0, 100.0) * GBIT).astype(np.int64)
+    bw = _bw_matrix(G, 400 * GBYTE, inter)
+    mem = np.array([192, 141, 96, 80, 64, 48, 40, 24], dtype=np.int64) * GB
+    return _problem(L, T, G, 256, (1, 2, 4, 8), fwd, params, 4 * act, act,
+                    [g % T for g in range(G)], [8] * G, mem, bw)
+
+
 WORKLOADS = {"tiny": tiny, "llama7b": llama7b, "llama70b": llama70b,
              "finegrained": finegrained, "stress": stress}
 ORDER = ("tiny", "llama7b", "llama70b", "finegrained", "stress")

@@ -77,6 +77,37 @@ def test_tables_match_oracle_long_rows(harp, ctx):
     assert not tables.fast32          # degree 3 and L > 2048
 
 
+def test_tables_match_oracle_operator_level(harp, ctx):
+    """The long-sequence problem of the streaming measurement at a length the oracle finishes in
+    seconds: 200,001 operators = 195 full scan chunks and a ragged tail, 138 rows."""
+    p = W.long_sequence(200001)
+    want = oracle.build_tables(p)
+    tables = harp.Tables(ctx, p)
+    PF, PP, PS, PR = tables.host_copies()
+    assert (PF == want.PF).all() and (PP == want.PP).all() and (PS == want.PS).all()
+    assert (PR == want.PR).all()
+
+
+def test_tables_large_quotients(harp, ctx):
+    """All-reduce and cut times whose operands leave the range of the fast division."""
+    rng = np.random.default_rng(6)
+    L = 300
+    act = rng.integers(0, 1 << 58, size=L)
+    act[::7] = rng.integers(0, 1 << 20, size=act[::7].shape)
+    p = simple_problem([1] * L, M=2, G=2, ndev=(4, 4), tp=(1, 2, 4), act=act, ar_count=1,
+                       bw=[[3, 1 << 55], [1 << 55, (1 << 53) + 5]])
+    want = oracle.Tables(p)
+    assert want.rc == oracle.ERR_OVERFLOW          # times beyond 2^47: both sides must refuse
+    with pytest.raises(harp.HarpError):
+        harp.Tables(ctx, p)
+    act = rng.integers(0, 1 << 40, size=L)
+    p = simple_problem([1] * L, M=2, G=2, ndev=(4, 4), tp=(1, 2, 4), act=act, ar_count=3,
+                       bw=[[7, 1 << 30], [1 << 30, (1 << 33) + 5]])
+    want = oracle.build_tables(p)
+    PF, PP, PS, PR = harp.Tables(ctx, p).host_copies()
+    assert (PR == want.PR).all() and (PF == want.PF).all()
+
+
 def test_tables_random_small(harp, ctx):
     for seed in range(60):
         w = W.random_small(seed)
