@@ -129,7 +129,7 @@ int harp_build_segment_costs(harp_ctx *ctx, const harp_problem *problem, void *t
 int harp_tables_finalize(harp_ctx *ctx, harp_tables *tables);
 
 /* 1 when the finalized tables allow the 32-bit fast path (all degrees powers of two, every time
- * below 2^31 us, L <= 2048, per-link cut table within 256 MiB), else 0. */
+ * below 2^31 us, L <= 1024, per-link cut table within 256 MiB), else 0. */
 int harp_tables_fast32(const harp_tables *tables);
 
 /* DEVICE pointers into the table buffer, for inspection: running sums indexed [row][i],

@@ -22,14 +22,17 @@
 // per-link cut table built beside the rows.
 //
 // Mapping: one workgroup per candidate at a time (persistent workgroups stride over the batch),
-// one lane per DP cell of the current stage, lanes of a wave on consecutive cells so that LDS
-// reads of (D[j], P[j]) pairs are stride-1 or broadcast.  The previous DP row and the slot's P row
-// sit interleaved in LDS so that one 8-byte read feeds a transition.  Everything stage s+1 needs
-// from global memory (its slot's P row, the memory row, the link's cut times) is requested at the
-// top of stage s, lands in registers while stage s scans, and is committed to the other LDS
-// buffer before the single barrier that ends the stage.  The lone cell of the last stage is
-// reduced across a wavefront with a lexicographic (value, j) minimum.  Back-pointers go to a
-// per-workgroup slice of the caller's workspace as uint16.
+// one lane per DP cell of the current stage (thread t owns cell i = s + 1 + t, so the problem must
+// have L <= 1024), lanes of a wave on consecutive cells so that LDS reads of (D[j], P[j]) pairs
+// are stride-1 or broadcast.  The previous DP row and the slot's P row sit interleaved in LDS so
+// that one 8-byte read feeds a transition.  Everything stage s+1 needs from global memory (its
+// slot's P row, the memory row, the cell's own cut time) is requested at the top of stage s, lands
+// in registers while stage s scans, and is committed to the other LDS buffer before the single
+// LDS-only barrier that ends the stage.  Values that are the same for the whole workgroup (slot
+// constants, the reach of the previous row) are moved to scalar registers so that addressing runs
+// on the scalar unit.  The lone cell of the last stage is reduced across a wavefront with a
+// lexicographic (value, j) minimum.  Back-pointers go to a per-workgroup slice of the caller's
+// workspace as uint16.
 #include "harp_internal.h"
 #include "plan_common.h"
 
@@ -60,6 +63,14 @@ __device__ __forceinline__ uint32_t umax3(uint32_t a, uint32_t b, uint32_t c) {
     return m > c ? m : c;
 }
 
+// A value every lane of the wave holds, moved to a scalar register.
+__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ int64_t uniform64(int64_t v) {
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)((uint64_t)v >> 32));
+    return (int64_t)(((uint64_t)hi << 32) | lo);
+}
+
 // Per-slot constants of the candidate in flight, computed once per candidate so that the stage
 // loop starts from LDS and never waits on a chain of dependent global loads.
 struct StageConst {
@@ -69,17 +80,8 @@ struct StageConst {
     uint8_t shift[kMaxStages];     // log2 tp
 };
 
-// What one thread stages for the next DP stage: PER entries of the P, memory and cut rows.
-template <int PER>
-struct Staged {
-    uint32_t p[PER], c[PER];
-    int64_t pp[PER], ps[PER];
-};
-
-template <int PER>
-__global__ __launch_bounds__(kMaxThreads) __attribute__((amdgpu_waves_per_eu(8, 8))) void k2_fast(TablesDev tb, CandDev cd, PlansDev out,
-                                                        unsigned char *ws, size_t ws_per_group,
-                                                        int row_len) {
+__global__ __launch_bounds__(kMaxThreads) __attribute__((amdgpu_waves_per_eu(8, 8)))
+void k2_fast(TablesDev tb, CandDev cd, PlansDev out, unsigned char *ws, size_t ws_per_group, int row_len) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     __shared__ SlotInfo slots;
     __shared__ StageConst sc;
@@ -91,7 +93,6 @@ __global__ __launch_bounds__(kMaxThreads) __attribute__((amdgpu_waves_per_eu(8, 
     // ending at any j >= 0 can be read at fixed offsets without clamping
     int64_t *Qb = reinterpret_cast<int64_t *>(lds_raw) + kPad;                        // [2][row_len]
     Pair *rows = reinterpret_cast<Pair *>(lds_raw + size_t(row_len) * 16) + kPad;     // [2][row_len]
-    uint32_t *cutb = reinterpret_cast<uint32_t *>(lds_raw + size_t(row_len) * 32);    // [2][row_len]
     uint16_t *arg = reinterpret_cast<uint16_t *>(ws + size_t(blockIdx.x) * ws_per_group);
     const int64_t *PP = tb.PP(), *PS = tb.PS();
 
@@ -117,116 +118,119 @@ __global__ __launch_bounds__(kMaxThreads) __attribute__((amdgpu_waves_per_eu(8, 
                 sc.shift[s] = (uint8_t)tb.tp_shift[k];
             }
             __syncthreads();
-            // global loads for stage sn into registers
-            auto fetch = [&](int sn, Staged<PER> &r) {
-                const uint32_t *p32 = tb.P32 + sc.p_row[sn];
-                const bool has_cut = sn < S - 1;
-                const uint32_t *cm = tb.CM + sc.cm_row[sn];
-#pragma unroll
-                for (int q = 0; q < PER; ++q) {
-                    const int j = sn + tid + q * nthreads;
-                    const bool ok = j <= sn + R;
-                    r.p[q] = ok ? p32[j] : 0u;
-                    r.pp[q] = ok ? PP[j] : 0;
-                    r.ps[q] = ok ? PS[j] : 0;
-                    r.c[q] = (ok && has_cut) ? cm[j] : 0u;
+            const bool live = tid < R;        // this thread owns a cell in every stage but the last
+            const bool stages = tid <= R;     // this thread stages one entry of every row
+            const int64_t m_cap = tb.M;
+
+            // prologue: rows of stage 0 and the thread's own cut time of stage 0
+            uint32_t cut_i = 0;
+            {
+                const uint32_t *p32 = tb.P32 + uniform((int)sc.p_row[0]);
+                const uint32_t *cm = tb.CM + uniform((int)sc.cm_row[0]);
+                const int64_t n0 = S < m_cap ? S : m_cap;
+                if (stages) {
+                    rows[tid].p = p32[tid];
+                    Qb[tid] = PP[tid] + n0 * PS[tid];
                 }
-            };
-            // registers into the LDS buffer that stage sn will read
-            auto commit = [&](int sn, int buf, const Staged<PER> &r) {
-                const int64_t n_inflight = (S - sn) < tb.M ? (S - sn) : tb.M;
-#pragma unroll
-                for (int q = 0; q < PER; ++q) {
-                    const int j = sn + tid + q * nthreads;
-                    if (j <= sn + R) {
-                        rows[size_t(buf) * row_len + j].p = r.p[q];
-                        Qb[size_t(buf) * row_len + j] = r.pp[q] + n_inflight * r.ps[q];
-                        cutb[size_t(buf) * row_len + j] = r.c[q];
-                    }
-                }
-            };
-            Staged<PER> staged;
-            fetch(0, staged);
-            if (tid == 0) { rows[0].d = 0; fmax_s[0] = 0; fmax_s[1] = -1; }
-            commit(0, 0, staged);
+                if (live) cut_i = cm[tid + 1];
+                if (tid < 3) rows[-1 - tid].d = kInf32;   // below cut 0: never a predecessor
+                if (tid == 0) { rows[0].d = 0; fmax_s[0] = 0; fmax_s[1] = -1; }
+            }
             lds_barrier();
 
             int cur = 0;
-            for (int s = 0; s < S; ++s) {
-                const int shift = sc.shift[s];
+            for (int s = 0; s < S - 1; ++s) {
+                const int shift = uniform(sc.shift[s]);
                 const uint32_t tp = 1u << shift;
-                const int64_t cap = sc.cap[s];
-                const bool last = (s == S - 1);
-                const int i_hi = s + R;
-                const Pair *prev = rows + size_t(cur) * row_len;
-                Pair *next = rows + size_t(cur ^ 1) * row_len;
-                const int64_t *Q = Qb + size_t(cur) * row_len;
-                const uint32_t *cut = cutb + size_t(cur) * row_len;
-                const int fmax_prev = fmax_s[s % 3];
+                const int64_t cap = uniform64(sc.cap[s]);
+                const int fmax_prev = uniform(fmax_s[s % 3]);
                 int *fmax_next = &fmax_s[(s + 1) % 3];
+                const Pair *prev = rows + cur * row_len;
+                Pair *next = rows + (cur ^ 1) * row_len;
+                const int64_t *Q = Qb + cur * row_len;
+                int64_t *Qn = Qb + (cur ^ 1) * row_len;
                 if (tid == 0) fmax_s[(s + 2) % 3] = -1;
-                if (!last) fetch(s + 1, staged);
 
-                uint16_t *arg_row = arg + size_t(s) * row_len;
-                if (!last) {
-                    // one cell per thread in all but oversized problems; the first pass keeps its
-                    // back-pointer in a register so that the global store can follow the commit
-                    int first_j = 0;
-                    for (int i0 = s + 1; i0 <= i_hi; i0 += nthreads) {
-                        const int i = i0 + tid;
-                        const bool live = i <= i_hi;
-                        uint32_t best = kInf32;
-                        int best_j = 0;
-                        if (live) {
-                            // fitting cuts are j >= lo with Q[lo] >= Q[i] - cap (memory need is
-                            // monotone in j), so the downward scan also stops at the first misfit
-                            const int64_t th = Q[i] - cap;
-                            const uint32_t xi = prev[i].p + tp - 1;
-                            const uint32_t cut_i = cut[i];
-                            // Four previous cuts per trip, read at fixed offsets below j.  An
-                            // entry counts while j >= s and it fits in memory; both conditions
-                            // are monotone in j, so they are plain predicates.  Entries below a
-                            // stop cannot update (their time exceeds the best value), so only
-                            // the last entry of a trip decides whether the lane goes on.
-                            int j = (i - 1) < fmax_prev ? (i - 1) : fmax_prev;
-                            bool more = true;
-                            while (more) {
-                                const Pair *pe = prev + (j - 3);
-                                const int64_t *pq = Q + (j - 3);
-                                const Pair e3 = pe[0], e2 = pe[1], e1 = pe[2], e0 = pe[3];
-                                const int64_t q3 = pq[0], q2 = pq[1], q1 = pq[2], q0 = pq[3];
-                                uint32_t tj;
+                // requests for stage s+1: entry jn of its rows, and this thread's own cut time
+                const int jn = s + 1 + tid;
+                const bool next_has_cut = s + 2 < S;
+                uint32_t p_n = 0, cut_n = 0;
+                int64_t pp_n = 0, ps_n = 0;
+                {
+                    const uint32_t *p32 = tb.P32 + uniform((int)sc.p_row[s + 1]);
+                    const uint32_t *cm = tb.CM + uniform((int)sc.cm_row[s + 1]);
+                    if (stages) { p_n = p32[jn]; pp_n = PP[jn]; ps_n = PS[jn]; }
+                    if (live && next_has_cut) cut_n = cm[jn + 1];
+                }
+
+                const int i = s + 1 + tid;
+                uint32_t best = kInf32;
+                int best_j = 0;
+                if (live) {
+                    // fitting cuts are j >= lo with Q[lo] >= Q[i] - cap (memory need is monotone
+                    // in j), so the downward scan also stops at the first misfit
+                    const int64_t th = Q[i] - cap;
+                    const uint32_t xi = prev[i].p + tp - 1;
+                    // Four previous cuts per trip, read at fixed offsets below j.  An entry counts
+                    // while it fits in memory (monotone in j, so a plain predicate); entries below
+                    // cut s hold D = infinity and never win.  Entries below a stop cannot update
+                    // (their time exceeds the best value), so only the last entry of a trip
+                    // decides whether the lane goes on.
+                    int j = (i - 1) < fmax_prev ? (i - 1) : fmax_prev;
+                    bool more = true;
+                    while (more) {
+                        const Pair *pe = prev + (j - 3);
+                        const int64_t *pq = Q + (j - 3);
+                        const Pair e3 = pe[0], e2 = pe[1], e1 = pe[2], e0 = pe[3];
+                        const int64_t q3 = pq[0], q2 = pq[1], q1 = pq[2], q0 = pq[3];
+                        uint32_t tj;
 #define HARP_STEP(E, QV, JJ)                                                   \
     {                                                                          \
         tj = (xi - (E).p) >> shift;                                            \
         const uint32_t v = umax3((E).d, tj, cut_i);                            \
-        const bool upd = ((JJ) >= s) & ((QV) >= th) & (v <= best);             \
+        const bool upd = ((QV) >= th) & (v <= best);                           \
         best = upd ? v : best;                                                 \
         best_j = upd ? (JJ) : best_j;                                          \
     }
-                                HARP_STEP(e0, q0, j)
-                                HARP_STEP(e1, q1, j - 1)
-                                HARP_STEP(e2, q2, j - 2)
-                                HARP_STEP(e3, q3, j - 3)
+                        HARP_STEP(e0, q0, j)
+                        HARP_STEP(e1, q1, j - 1)
+                        HARP_STEP(e2, q2, j - 2)
+                        HARP_STEP(e3, q3, j - 3)
 #undef HARP_STEP
-                                more = ((j - 3) > s) & (q3 >= th) & (tj <= best);
-                                j -= 4;
-                            }
-                            next[i].d = best;
-                            if (i0 == s + 1) first_j = best_j;
-                            else arg_row[i] = (uint16_t)best_j;
-                        }
-                        const unsigned long long finite = __ballot(live && best != kInf32);
-                        if (lane == 0 && finite) atomicMax(fmax_next, i0 + wave * 64 + 63 - __clzll(finite));
+                        more = ((j - 3) > s) & (q3 >= th) & (tj <= best);
+                        j -= 4;
                     }
-                    commit(s + 1, cur ^ 1, staged);
-                    if (s + 1 + tid <= i_hi) arg_row[s + 1 + tid] = (uint16_t)first_j;
-                } else if (wave == 0) {
-                    // the last stage has the single cell i = L: lanes over j, lexicographic reduction
-                    const int i = L;
-                    const int64_t th = Q[i] - cap;
-                    const uint32_t xi = prev[i].p + tp - 1;
-                    const int hi = (i - 1) < fmax_prev ? (i - 1) : fmax_prev;
+                    next[i].d = best;
+                }
+                if (tid < 3) next[s - tid].d = kInf32;     // cuts below s+1 for the next stage
+                const unsigned long long finite = __ballot(best != kInf32);
+                if (lane == 0 && finite) atomicMax(fmax_next, s + 1 + wave * 64 + 63 - __clzll(finite));
+
+                // commit the staged entries of stage s+1, then let the back-pointer go
+                if (stages) {
+                    const int64_t n1 = (S - s - 1) < m_cap ? (S - s - 1) : m_cap;
+                    next[jn].p = p_n;
+                    Qn[jn] = pp_n + n1 * ps_n;
+                }
+                cut_i = cut_n;
+                if (live) arg[s * row_len + i] = (uint16_t)best_j;
+                lds_barrier();
+                cur ^= 1;
+                if (uniform(*fmax_next) < 0) { dead = true; break; }   // no cell of this row is reachable
+            }
+            if (!dead) {
+                // the last stage has the single cell i = L: lanes over j, lexicographic reduction
+                const int s = S - 1;
+                if (wave == 0) {
+                    const int shift = uniform(sc.shift[s]);
+                    const uint32_t tp = 1u << shift;
+                    const int64_t cap = uniform64(sc.cap[s]);
+                    const int fmax_prev = uniform(fmax_s[s % 3]);
+                    const Pair *prev = rows + cur * row_len;
+                    const int64_t *Q = Qb + cur * row_len;
+                    const int64_t th = Q[L] - cap;
+                    const uint32_t xi = prev[L].p + tp - 1;
+                    const int hi = (L - 1) < fmax_prev ? (L - 1) : fmax_prev;
                     uint32_t best = kInf32;
                     int best_j = INT32_MAX;
                     for (int j = s + lane; j <= hi; j += 64) {
@@ -243,19 +247,17 @@ __global__ __launch_bounds__(kMaxThreads) __attribute__((amdgpu_waves_per_eu(8, 
                         if (ov < best || (ov == best && oj < best_j)) { best = ov; best_j = oj; }
                     }
                     if (lane == 0) {
-                        arg_row[i] = (uint16_t)(best == kInf32 ? 0 : best_j);
-                        *fmax_next = best == kInf32 ? -1 : i;
+                        arg[s * row_len + L] = (uint16_t)(best == kInf32 ? 0 : best_j);
+                        fmax_s[(s + 1) % 3] = best == kInf32 ? -1 : L;
                     }
                 }
-                lds_barrier();
-                cur ^= 1;
-                if (*fmax_next < 0) { dead = true; break; }   // uniform: no cell of this row is reachable
+                __syncthreads();          // back-pointers of every wave are visible to thread 0
+                if (fmax_s[(s + 1) % 3] < 0) dead = true;
             }
-            __syncthreads();          // back-pointers of every wave are visible to thread 0
             if (!dead && tid == 0) {
                 int b = L;
                 sp[S] = L;
-                for (int s = S - 1; s >= 0; --s) { b = arg[size_t(s) * row_len + b]; sp[s] = b; }
+                for (int s = S - 1; s >= 0; --s) { b = arg[s * row_len + b]; sp[s] = b; }
             }
         } else if (tid == 0) {
             sp[0] = 0;    // one stage holds every operator; the score below checks that it fits
@@ -295,7 +297,7 @@ int fast_threads(int L) {
 
 int fast_row_len(int L) { return (L + 1 + kPad + 7) / 8 * 8; }
 
-size_t fast_lds_bytes(int L) { return size_t(fast_row_len(L)) * (16 + 2 * sizeof(Pair) + 8); }
+size_t fast_lds_bytes(int L) { return size_t(fast_row_len(L)) * (16 + 2 * sizeof(Pair)); }
 
 }  // namespace
 
@@ -317,14 +319,9 @@ int plan_fast_groups(int L, int n_cu) {
 
 void launch_plan_fast(const TablesDev &tb, const CandDev &cd, const PlansDev &out, void *ws,
                       int n_groups, hipStream_t st) {
-    const int threads = fast_threads(tb.L);
-    const size_t per_group = plan_fast_ws_per_group(tb.L, cd.S_max);
-    if (threads >= tb.L)
-        hipLaunchKernelGGL(k2_fast<1>, dim3(n_groups), dim3(threads), fast_lds_bytes(tb.L), st, tb, cd, out,
-                           static_cast<unsigned char *>(ws), per_group, fast_row_len(tb.L));
-    else
-        hipLaunchKernelGGL(k2_fast<2>, dim3(n_groups), dim3(threads), fast_lds_bytes(tb.L), st, tb, cd, out,
-                           static_cast<unsigned char *>(ws), per_group, fast_row_len(tb.L));
+    hipLaunchKernelGGL(k2_fast, dim3(n_groups), dim3(fast_threads(tb.L)), fast_lds_bytes(tb.L), st, tb, cd,
+                       out, static_cast<unsigned char *>(ws), plan_fast_ws_per_group(tb.L, cd.S_max),
+                       fast_row_len(tb.L));
 }
 
 }  // namespace harp

@@ -74,7 +74,7 @@ def test_tables_match_oracle_long_rows(harp, ctx):
     PF, PP, PS, PR = tables.host_copies()
     assert (PF == want.PF).all() and (PP == want.PP).all() and (PS == want.PS).all()
     assert (PR == want.PR).all()
-    assert not tables.fast32          # degree 3 and L > 2048
+    assert not tables.fast32          # degree 3 and L > 1024
 
 
 def test_tables_match_oracle_operator_level(harp, ctx):
