@@ -65,26 +65,34 @@ __device__ __forceinline__ uint32_t umax3(uint32_t a, uint32_t b, uint32_t c) {
 
 // A value every lane of the wave holds, moved to a scalar register.
 __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+template <typename T>
+__device__ __forceinline__ const T *uniform_ptr(const T *p);
 __device__ __forceinline__ int64_t uniform64(int64_t v) {
     const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
     const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)((uint64_t)v >> 32));
     return (int64_t)(((uint64_t)hi << 32) | lo);
 }
 
+template <typename T>
+__device__ __forceinline__ const T *uniform_ptr(const T *p) {
+    return reinterpret_cast<const T *>(uniform64(reinterpret_cast<int64_t>(p)));
+}
+
 // Per-slot constants of the candidate in flight, computed once per candidate so that the stage
 // loop starts from LDS and never waits on a chain of dependent global loads.
-struct StageConst {
-    int64_t cap[kMaxStages];       // tp * device memory of the slot's GPU type
-    uint32_t p_row[kMaxStages];    // element offset of the slot's fused time row
-    uint32_t cm_row[kMaxStages];   // element offset of the cut-time row of the link to the next slot
-    uint8_t shift[kMaxStages];     // log2 tp
+struct alignas(16) StageConst {
+    int64_t cap;            // tp * device memory of the slot's GPU type
+    const uint32_t *p32;    // the slot's fused time row
+    const uint32_t *cm;     // cut-time row of the link to the next slot
+    int32_t shift;          // log2 tp
+    int32_t pad;
 };
 
 __global__ __launch_bounds__(kMaxThreads) __attribute__((amdgpu_waves_per_eu(8, 8)))
 void k2_fast(TablesDev tb, CandDev cd, PlansDev out, unsigned char *ws, size_t ws_per_group, int row_len) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     __shared__ SlotInfo slots;
-    __shared__ StageConst sc;
+    __shared__ StageConst sc[kMaxStages];
     __shared__ int fmax_s[3];
 
     const int L = tb.L, S_max = cd.S_max;
@@ -112,10 +120,10 @@ void k2_fast(TablesDev tb, CandDev cd, PlansDev out, unsigned char *ws, size_t w
             const int R = L - S + 1;          // cells per stage; stage s touches rows s .. s+R
             for (int s = tid; s < S; s += nthreads) {
                 const int g = slots.g[s], k = slots.k[s];
-                sc.cap[s] = int64_t(tb.tp[k]) * tb.type_mem[tb.group_type[g]];
-                sc.p_row[s] = uint32_t((int64_t(g) * tb.n_tp + k) * tb.pitch32);
-                sc.cm_row[s] = uint32_t((int64_t(g) * tb.G + (s + 1 < S ? slots.g[s + 1] : g)) * tb.pitch32);
-                sc.shift[s] = (uint8_t)tb.tp_shift[k];
+                sc[s].cap = int64_t(tb.tp[k]) * tb.type_mem[tb.group_type[g]];
+                sc[s].p32 = tb.P32 + (int64_t(g) * tb.n_tp + k) * tb.pitch32;
+                sc[s].cm = tb.CM + (int64_t(g) * tb.G + (s + 1 < S ? slots.g[s + 1] : g)) * tb.pitch32;
+                sc[s].shift = tb.tp_shift[k];
             }
             __syncthreads();
             const bool live = tid < R;        // this thread owns a cell in every stage but the last
@@ -125,8 +133,8 @@ void k2_fast(TablesDev tb, CandDev cd, PlansDev out, unsigned char *ws, size_t w
             // prologue: rows of stage 0 and the thread's own cut time of stage 0
             uint32_t cut_i = 0;
             {
-                const uint32_t *p32 = tb.P32 + uniform((int)sc.p_row[0]);
-                const uint32_t *cm = tb.CM + uniform((int)sc.cm_row[0]);
+                const uint32_t *p32 = uniform_ptr(sc[0].p32);
+                const uint32_t *cm = uniform_ptr(sc[0].cm);
                 const int64_t n0 = S < m_cap ? S : m_cap;
                 if (stages) {
                     rows[tid].p = p32[tid];
@@ -139,17 +147,18 @@ void k2_fast(TablesDev tb, CandDev cd, PlansDev out, unsigned char *ws, size_t w
             lds_barrier();
 
             int cur = 0;
+            int fmax_prev = 0;                // reach of the previous row, carried in a register
+            int f_next = 1, f_reset = 2;      // rotating slots of fmax_s: target now, target next
             for (int s = 0; s < S - 1; ++s) {
-                const int shift = uniform(sc.shift[s]);
+                const int shift = uniform(sc[s].shift);
                 const uint32_t tp = 1u << shift;
-                const int64_t cap = uniform64(sc.cap[s]);
-                const int fmax_prev = uniform(fmax_s[s % 3]);
-                int *fmax_next = &fmax_s[(s + 1) % 3];
+                const int64_t cap = uniform64(sc[s].cap);
+                int *fmax_next = &fmax_s[f_next];
                 const Pair *prev = rows + cur * row_len;
                 Pair *next = rows + (cur ^ 1) * row_len;
                 const int64_t *Q = Qb + cur * row_len;
                 int64_t *Qn = Qb + (cur ^ 1) * row_len;
-                if (tid == 0) fmax_s[(s + 2) % 3] = -1;
+                if (tid == 0) fmax_s[f_reset] = -1;
 
                 // requests for stage s+1: entry jn of its rows, and this thread's own cut time
                 const int jn = s + 1 + tid;
@@ -157,8 +166,8 @@ void k2_fast(TablesDev tb, CandDev cd, PlansDev out, unsigned char *ws, size_t w
                 uint32_t p_n = 0, cut_n = 0;
                 int64_t pp_n = 0, ps_n = 0;
                 {
-                    const uint32_t *p32 = tb.P32 + uniform((int)sc.p_row[s + 1]);
-                    const uint32_t *cm = tb.CM + uniform((int)sc.cm_row[s + 1]);
+                    const uint32_t *p32 = uniform_ptr(sc[s + 1].p32);
+                    const uint32_t *cm = uniform_ptr(sc[s + 1].cm);
                     if (stages) { p_n = p32[jn]; pp_n = PP[jn]; ps_n = PS[jn]; }
                     if (live && next_has_cut) cut_n = cm[jn + 1];
                 }
@@ -216,16 +225,17 @@ void k2_fast(TablesDev tb, CandDev cd, PlansDev out, unsigned char *ws, size_t w
                 if (live) arg[s * row_len + i] = (uint16_t)best_j;
                 lds_barrier();
                 cur ^= 1;
-                if (uniform(*fmax_next) < 0) { dead = true; break; }   // no cell of this row is reachable
+                fmax_prev = uniform(*fmax_next);
+                { const int t = 3 - f_next - f_reset; f_next = f_reset; f_reset = t; }
+                if (fmax_prev < 0) { dead = true; break; }   // no cell of this row is reachable
             }
             if (!dead) {
                 // the last stage has the single cell i = L: lanes over j, lexicographic reduction
                 const int s = S - 1;
                 if (wave == 0) {
-                    const int shift = uniform(sc.shift[s]);
+                    const int shift = uniform(sc[s].shift);
                     const uint32_t tp = 1u << shift;
-                    const int64_t cap = uniform64(sc.cap[s]);
-                    const int fmax_prev = uniform(fmax_s[s % 3]);
+                    const int64_t cap = uniform64(sc[s].cap);
                     const Pair *prev = rows + cur * row_len;
                     const int64_t *Q = Qb + cur * row_len;
                     const int64_t th = Q[L] - cap;
@@ -248,11 +258,11 @@ void k2_fast(TablesDev tb, CandDev cd, PlansDev out, unsigned char *ws, size_t w
                     }
                     if (lane == 0) {
                         arg[s * row_len + L] = (uint16_t)(best == kInf32 ? 0 : best_j);
-                        fmax_s[(s + 1) % 3] = best == kInf32 ? -1 : L;
+                        fmax_s[f_next] = best == kInf32 ? -1 : L;
                     }
                 }
                 __syncthreads();          // back-pointers of every wave are visible to thread 0
-                if (fmax_s[(s + 1) % 3] < 0) dead = true;
+                if (fmax_s[f_next] < 0) dead = true;
             }
             if (!dead && tid == 0) {
                 int b = L;
