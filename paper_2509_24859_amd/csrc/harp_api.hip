@@ -125,8 +125,8 @@ int check_batch(harp_ctx *ctx, harp_tables *t, const harp_candidates *cd) {
     return finalize_tables(ctx, t);
 }
 
-int n_plan_groups(const harp_ctx *ctx, int C, bool fast, int L) {
-    int resident = fast ? plan_fast_groups(L, ctx->n_cu) : ctx->n_cu * 8;
+int n_plan_groups(const harp_ctx *ctx, int C, bool fast, int L, int S_max) {
+    int resident = fast ? plan_fast_groups(L, S_max, ctx->n_cu) : ctx->n_cu * 8;
     if (resident < 1) resident = 1;
     return C < resident ? (C < 1 ? 1 : C) : resident;
 }
@@ -275,10 +275,11 @@ size_t harp_plan_workspace_bytes(harp_ctx *ctx, const harp_tables *t, const harp
     if (t->dev.L > HARP_MAX_L_PLAN) return 0;
     // sized for whichever path may run, so that the answer does not depend on the build verdict
     const int C = cd->C;
-    size_t gen = size_t(n_plan_groups(ctx, C, false, t->dev.L)) * plan_generic_ws_per_group(t->dev.L, cd->S_max);
+    size_t gen = size_t(n_plan_groups(ctx, C, false, t->dev.L, cd->S_max)) *
+                 plan_generic_ws_per_group(t->dev.L, cd->S_max);
     size_t fast = 0;
     if (t->lim.want_fast)
-        fast = size_t(n_plan_groups(ctx, C, true, t->dev.L)) * plan_fast_ws_per_group(t->dev.L, cd->S_max);
+        fast = plan_fast_ws_bytes(t->dev.L, cd->S_max, C, n_plan_groups(ctx, C, true, t->dev.L, cd->S_max));
     return (gen > fast ? gen : fast) + 256;
 }
 
@@ -301,7 +302,7 @@ int harp_plan_batch(harp_ctx *ctx, harp_tables *t, const harp_candidates *cd, co
     const CandDev c = { cd->C, cd->S_max, cd->cand_S, cd->cand_group, cd->cand_tp };
     const PlansDev o = { out->splits, out->dev_first, out->bottleneck, out->iter_time, out->status };
     const bool fast = use_fast(ctx, t);
-    const int groups = n_plan_groups(ctx, cd->C, fast, t->dev.L);
+    const int groups = n_plan_groups(ctx, cd->C, fast, t->dev.L, cd->S_max);
     if (fast) launch_plan_fast(t->dev, c, o, workspace, groups, static_cast<hipStream_t>(hip_stream));
     else launch_plan_generic(t->dev, c, o, workspace, groups, static_cast<hipStream_t>(hip_stream));
     e = hipGetLastError();

@@ -1,19 +1,26 @@
-// Fast planner-search kernel for gfx950: 32-bit times, bounded scans, rows in LDS.
+// Fast planner-search kernels for gfx950: reachability bands, 32-bit times, bounded scans, rows in LDS.
 //
 // Same recurrence as the generic kernel (paper section 5.2.3, eq. dp_general with the submesh of
 // each stage fixed by the candidate; constraints (i)-(iii)), same results bit for bit, but the
-// work per DP cell is cut down with two facts that hold for every valid problem (all costs and
-// byte counts are non-negative, which the table build has verified):
+// work is cut down with facts that hold for every valid problem (all costs and byte counts are
+// non-negative, which the table build has verified):
 //
-//  * eq. mem_cons is monotone in the previous cut j: a longer stage never needs less memory.  So
-//    the fitting cuts of cell (s, i) are exactly j >= lo(s, i), and lo is found by one binary
-//    search over the running sum  Q[j] = PP[j] + N_s PS[j]  kept in LDS.
+//  * eq. mem_cons is monotone: a longer stage never needs less memory.  Hence (a) the fitting
+//    previous cuts of cell (s, i) are exactly j >= lo(s, i); (b) the largest cut any plan can reach
+//    after s stages, F[s], obeys F[s+1] <= max{ i : stage s over [F[s], i) fits }; (c) the smallest
+//    cut from which the remaining stages can still hold the remaining operators, B[s], obeys
+//    B[s] >= lo(s, B[s+1]).  Cells outside [B[s], F[s]] are either unreachable or cannot be
+//    completed, so no optimal plan passes through them and no cell that lies on a complete plan has
+//    them as a fitting predecessor: the DP is run on the band only.  A band that comes out empty,
+//    B[0] > 0, or F[S] < L proves the candidate infeasible before any DP work.  (The bands are
+//    bounds, not exact sets: a candidate whose band is non-empty can still turn out infeasible,
+//    which the DP then reports.)  k2_band computes the two chains with one thread per candidate.
 //  * the stage time time(s; j, i) never decreases when j moves down.  Scanning j downwards from
 //    i-1, once time(s; j, i) exceeds the best value found so far no lower j can match or beat it,
 //    and the scan stops.  The stop uses a strict comparison and the update a non-strict one, so
 //    the lowest j among equal values is kept, as the recurrence demands.  Nothing is assumed
 //    about the previous DP row (it is not monotone when transfer times dominate); in the worst
-//    case the scan degenerates to the dense one.
+//    case the scan covers the whole band.
 //
 // With tp a power of two and every time below 2^31 us (both checked by the table build), the
 // stage time is one subtraction and one shift on the fused 32-bit row
@@ -21,18 +28,17 @@
 // because ceil(a / tp) + b = ceil((a + tp b) / tp) for integers.  Transfer times come from the
 // per-link cut table built beside the rows.
 //
-// Mapping: one workgroup per candidate at a time (persistent workgroups stride over the batch),
-// one lane per DP cell of the current stage (thread t owns cell i = s + 1 + t, so the problem must
-// have L <= 1024), lanes of a wave on consecutive cells so that LDS reads of (D[j], P[j]) pairs
-// are stride-1 or broadcast.  The previous DP row and the slot's P row sit interleaved in LDS so
-// that one 8-byte read feeds a transition.  Everything stage s+1 needs from global memory (its
-// slot's P row, the memory row, the cell's own cut time) is requested at the top of stage s, lands
-// in registers while stage s scans, and is committed to the other LDS buffer before the single
-// LDS-only barrier that ends the stage.  Values that are the same for the whole workgroup (slot
-// constants, the reach of the previous row) are moved to scalar registers so that addressing runs
-// on the scalar unit.  The lone cell of the last stage is reduced across a wavefront with a
-// lexicographic (value, j) minimum.  Back-pointers go to a per-workgroup slice of the caller's
-// workspace as uint16.
+// Mapping of k2_fast: one workgroup per live candidate at a time (persistent workgroups stride
+// over the list k2_band compacted), one lane per DP cell of the current stage's band (more trips
+// when the band is wider than the workgroup), lanes of a wave on consecutive cells so that LDS
+// reads of (D[j], P[j]) pairs are stride-1 or broadcast.  The previous DP row and the slot's P row
+// sit interleaved in LDS so that one 8-byte read feeds a transition.  What stage s+1 needs from
+// global memory (its slot's P row, the memory row, the cell's own cut time) is requested at the
+// top of stage s, lands in registers while stage s scans, and is committed to the other LDS buffer
+// before the single LDS-only barrier that ends the stage.  Values that are the same for the whole
+// workgroup are moved to scalar registers so that addressing runs on the scalar unit.  The lone
+// cell of the last stage is reduced across a wavefront with a lexicographic (value, j) minimum.
+// Back-pointers go to a per-workgroup slice of the caller's workspace as uint16.
 #include "harp_internal.h"
 #include "plan_common.h"
 
@@ -41,8 +47,8 @@ namespace harp {
 namespace {
 
 constexpr uint32_t kInf32 = 0xFFFFFFFFu;
-constexpr int kMaxThreads = 1024;
 constexpr int kPad = 4;
+constexpr int kFastThreads = 256;
 
 struct alignas(8) Pair {
     uint32_t d;   // previous DP row
@@ -65,14 +71,11 @@ __device__ __forceinline__ uint32_t umax3(uint32_t a, uint32_t b, uint32_t c) {
 
 // A value every lane of the wave holds, moved to a scalar register.
 __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
-template <typename T>
-__device__ __forceinline__ const T *uniform_ptr(const T *p);
 __device__ __forceinline__ int64_t uniform64(int64_t v) {
     const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
     const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)((uint64_t)v >> 32));
     return (int64_t)(((uint64_t)hi << 32) | lo);
 }
-
 template <typename T>
 __device__ __forceinline__ const T *uniform_ptr(const T *p) {
     return reinterpret_cast<const T *>(uniform64(reinterpret_cast<int64_t>(p)));
@@ -88,12 +91,124 @@ struct alignas(16) StageConst {
     int32_t pad;
 };
 
-__global__ __launch_bounds__(kMaxThreads) __attribute__((amdgpu_waves_per_eu(8, 8)))
-void k2_fast(TablesDev tb, CandDev cd, PlansDev out, unsigned char *ws, size_t ws_per_group, int row_len) {
+__device__ __forceinline__ int band_lo(uint32_t w) { return int(w & 0xFFFFu); }
+__device__ __forceinline__ int band_hi(uint32_t w) { return int(w >> 16); }
+
+__device__ __forceinline__ int tp_index(const TablesDev &tb, int tp) {
+    int k = -1;
+    for (int q = 0; q < tb.n_tp; ++q)
+        if (tb.tp[q] == tp) k = q;
+    return k;
+}
+
+__device__ void thread_write_failed(const PlansDev &out, int c, int S_max, int status) {
+    int32_t *sp = out.splits + int64_t(c) * (S_max + 1);
+    int32_t *df = out.dev_first + int64_t(c) * S_max;
+    for (int s = 0; s <= S_max; ++s) sp[s] = -1;
+    for (int s = 0; s < S_max; ++s) df[s] = -1;
+    out.bottleneck[c] = kInf;
+    out.iter_time[c] = kInf;
+    out.status[c] = status;
+}
+
+// Pre-pass, one thread per candidate: checks the slot list, writes the device assignment, and
+// computes the reachability band [B[s], F[s]] of every DP row from the memory constraint alone
+// (two chains of binary searches over the running sums).  Candidates that are malformed or proven
+// infeasible get their final outputs here; the others are appended to the live list.
+__global__ __launch_bounds__(256) void k2_band(TablesDev tb, CandDev cd, PlansDev out, int *live_count,
+                                               int32_t *live_list, uint32_t *bands) {
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= cd.C) return;
+    const int L = tb.L, S_max = cd.S_max;
+    const int S = cd.cand_S[c];
+    const int32_t *grp = cd.cand_group + int64_t(c) * S_max;
+    const int32_t *tpv = cd.cand_tp + int64_t(c) * S_max;
+    int32_t *df = out.dev_first + int64_t(c) * S_max;
+
+    int status = HARP_CAND_OK;
+    if (S < 1 || S > S_max) status = HARP_CAND_INVALID;
+    int64_t used = 0;
+    for (int s = 0; status == HARP_CAND_OK && s < S; ++s) {
+        const int g = grp[s];
+        const int k = tp_index(tb, tpv[s]);
+        if (g < 0 || g >= tb.G || k < 0) { status = HARP_CAND_INVALID; break; }
+        if (s == 0 || grp[s - 1] != g) {              // first slot of a run of group g
+            for (int q = 0; q + 1 < s; ++q)
+                if (grp[q] == g) status = HARP_CAND_INVALID;   // the group was left and entered again
+            used = 0;
+        }
+        df[s] = tb.group_base[g] + (int32_t)used;
+        used += tb.tp[k];
+        if (used > tb.group_ndev[g]) status = HARP_CAND_INVALID;
+    }
+    if (status == HARP_CAND_OK && S > L) status = HARP_CAND_INFEASIBLE;
+    if (status != HARP_CAND_OK) {
+        thread_write_failed(out, c, S_max, status);
+        return;
+    }
+    for (int s = S; s < S_max; ++s) df[s] = -1;
+
+    const int64_t *PP = tb.PP(), *PS = tb.PS();
+    uint32_t *band = bands + int64_t(c) * (S_max + 1);
+    const int R = L - S + 1;
+    bool feasible = true;
+    // forward chain: F[s+1] = largest cut that stage s can reach from F[s]
+    int F = 0;
+    band[0] = 0;
+    for (int s = 0; s < S; ++s) {
+        const int g = grp[s];
+        const int64_t tp = tpv[s];
+        const int64_t n = (S - s) < tb.M ? (S - s) : tb.M;
+        const int64_t cap = tp * tb.type_mem[tb.group_type[g]];
+        const int64_t q0 = PP[F] + n * PS[F];
+        const int top = (s == S - 1) ? L : s + R;
+        int a = F, b = top;                                   // need(F, a) <= cap always holds
+        if ((PP[b] + n * PS[b]) - q0 <= cap) a = b;
+        while (b - a > 1) {
+            const int m = (a + b) >> 1;
+            if ((PP[m] + n * PS[m]) - q0 <= cap) a = m; else b = m;
+        }
+        F = a;
+        if (F < s + 1 || (s == S - 1 && F != L)) { feasible = false; break; }
+        band[s + 1] = uint32_t(F) << 16;
+    }
+    // backward chain: B[s] = smallest cut from which stage s can reach B[s+1]
+    if (feasible) {
+        int B = L;
+        band[S] |= uint32_t(L);
+        for (int s = S - 1; s >= 0; --s) {
+            const int g = grp[s];
+            const int64_t tp = tpv[s];
+            const int64_t n = (S - s) < tb.M ? (S - s) : tb.M;
+            const int64_t cap = tp * tb.type_mem[tb.group_type[g]];
+            const int64_t qb = PP[B] + n * PS[B];
+            int a = s, b = B;                                 // need(b, B) <= cap holds at b = B
+            if (qb - (PP[a] + n * PS[a]) <= cap) b = a;
+            while (b - a > 1) {
+                const int m = (a + b) >> 1;
+                if (qb - (PP[m] + n * PS[m]) <= cap) b = m; else a = m;
+            }
+            B = b;
+            const int hi = band_hi(band[s]);
+            if (hi < B || (s == 0 && B != 0)) { feasible = false; break; }
+            band[s] = uint32_t(B) | (uint32_t(hi) << 16);
+        }
+    }
+    if (!feasible) {
+        thread_write_failed(out, c, S_max, HARP_CAND_INFEASIBLE);
+        return;
+    }
+    live_list[atomicAdd(live_count, 1)] = c;
+}
+
+__global__ void k2_clear_count(int *live_count) {
+    if (threadIdx.x == 0) *live_count = 0;
+}
+
+__global__ __launch_bounds__(kFastThreads) __attribute__((amdgpu_waves_per_eu(8, 8)))
+void k2_fast(TablesDev tb, CandDev cd, PlansDev out, const int *live_count, const int32_t *live_list,
+             const uint32_t *bands, unsigned char *arg_base, size_t arg_per_group, int row_len) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
-    __shared__ SlotInfo slots;
-    __shared__ StageConst sc[kMaxStages];
-    __shared__ int fmax_s[3];
 
     const int L = tb.L, S_max = cd.S_max;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nthreads = blockDim.x;
@@ -101,92 +216,100 @@ void k2_fast(TablesDev tb, CandDev cd, PlansDev out, unsigned char *ws, size_t w
     // ending at any j >= 0 can be read at fixed offsets without clamping
     int64_t *Qb = reinterpret_cast<int64_t *>(lds_raw) + kPad;                        // [2][row_len]
     Pair *rows = reinterpret_cast<Pair *>(lds_raw + size_t(row_len) * 16) + kPad;     // [2][row_len]
-    uint16_t *arg = reinterpret_cast<uint16_t *>(ws + size_t(blockIdx.x) * ws_per_group);
+    StageConst *sc = reinterpret_cast<StageConst *>(lds_raw + size_t(row_len) * 32);  // [S_max]
+    uint32_t *band = reinterpret_cast<uint32_t *>(sc + S_max);                         // [S_max + 1]
+    uint16_t *slot_g = reinterpret_cast<uint16_t *>(band + S_max + 1);                 // [S_max]
+    uint8_t *slot_k = reinterpret_cast<uint8_t *>(slot_g + S_max);                     // [S_max]
+    uint16_t *arg = reinterpret_cast<uint16_t *>(arg_base + size_t(blockIdx.x) * arg_per_group);
     const int64_t *PP = tb.PP(), *PS = tb.PS();
+    const int n_live = *live_count;
+    const int64_t m_cap = tb.M;
 
-    for (int c = blockIdx.x; c < cd.C; c += gridDim.x) {
+    for (int n = blockIdx.x; n < n_live; n += gridDim.x) {
+        const int c = live_list[n];
         __syncthreads();   // the previous candidate's tail has finished with LDS
         const int S = cd.cand_S[c];
-        int status = load_and_check_slots(tb, S, S_max, cd.cand_group + int64_t(c) * S_max,
-                                          cd.cand_tp + int64_t(c) * S_max, slots);
-        if (status == HARP_CAND_OK && S > L) status = HARP_CAND_INFEASIBLE;
-        if (status != HARP_CAND_OK) {
-            write_failed(out, c, S_max, status);
-            continue;
+        {
+            const int32_t *grp = cd.cand_group + int64_t(c) * S_max;
+            const int32_t *tpv = cd.cand_tp + int64_t(c) * S_max;
+            const uint32_t *bw = bands + int64_t(c) * (S_max + 1);
+            for (int s = tid; s < S; s += nthreads) {
+                const int g = grp[s], k = tp_index(tb, tpv[s]);
+                const int g_next = s + 1 < S ? grp[s + 1] : g;
+                slot_g[s] = (uint16_t)g;
+                slot_k[s] = (uint8_t)k;
+                sc[s].cap = int64_t(tb.tp[k]) * tb.type_mem[tb.group_type[g]];
+                sc[s].p32 = tb.P32 + (int64_t(g) * tb.n_tp + k) * tb.pitch32;
+                sc[s].cm = tb.CM + (int64_t(g) * tb.G + g_next) * tb.pitch32;
+                sc[s].shift = tb.tp_shift[k];
+            }
+            for (int s = tid; s <= S; s += nthreads) band[s] = bw[s];
         }
+        __syncthreads();
         int32_t *sp = out.splits + int64_t(c) * (S_max + 1);
         bool dead = false;
         if (S >= 2) {
-            const int R = L - S + 1;          // cells per stage; stage s touches rows s .. s+R
-            for (int s = tid; s < S; s += nthreads) {
-                const int g = slots.g[s], k = slots.k[s];
-                sc[s].cap = int64_t(tb.tp[k]) * tb.type_mem[tb.group_type[g]];
-                sc[s].p32 = tb.P32 + (int64_t(g) * tb.n_tp + k) * tb.pitch32;
-                sc[s].cm = tb.CM + (int64_t(g) * tb.G + (s + 1 < S ? slots.g[s + 1] : g)) * tb.pitch32;
-                sc[s].shift = tb.tp_shift[k];
-            }
-            __syncthreads();
-            const bool live = tid < R;        // this thread owns a cell in every stage but the last
-            const bool stages = tid <= R;     // this thread stages one entry of every row
-            const int64_t m_cap = tb.M;
-
-            // prologue: rows of stage 0 and the thread's own cut time of stage 0
+            // prologue: rows of stage 0 over [0, F[1]] and the thread's own cut time of stage 0
             uint32_t cut_i = 0;
             {
                 const uint32_t *p32 = uniform_ptr(sc[0].p32);
                 const uint32_t *cm = uniform_ptr(sc[0].cm);
                 const int64_t n0 = S < m_cap ? S : m_cap;
-                if (stages) {
-                    rows[tid].p = p32[tid];
-                    Qb[tid] = PP[tid] + n0 * PS[tid];
+                const uint32_t b1 = (uint32_t)uniform((int)band[1]);
+                for (int j = tid; j <= band_hi(b1); j += nthreads) {
+                    rows[j].p = p32[j];
+                    Qb[j] = PP[j] + n0 * PS[j];
                 }
-                if (live) cut_i = cm[tid + 1];
+                if (band_lo(b1) + tid <= band_hi(b1)) cut_i = cm[band_lo(b1) + tid];
                 if (tid < 3) rows[-1 - tid].d = kInf32;   // below cut 0: never a predecessor
-                if (tid == 0) { rows[0].d = 0; fmax_s[0] = 0; fmax_s[1] = -1; }
+                if (tid == 0) rows[0].d = 0;
             }
             lds_barrier();
 
             int cur = 0;
-            int fmax_prev = 0;                // reach of the previous row, carried in a register
-            int f_next = 1, f_reset = 2;      // rotating slots of fmax_s: target now, target next
             for (int s = 0; s < S - 1; ++s) {
                 const int shift = uniform(sc[s].shift);
                 const uint32_t tp = 1u << shift;
                 const int64_t cap = uniform64(sc[s].cap);
-                int *fmax_next = &fmax_s[f_next];
+                const uint32_t b0 = (uint32_t)uniform((int)band[s]);
+                const uint32_t b1 = (uint32_t)uniform((int)band[s + 1]);
+                const uint32_t b2 = (uint32_t)uniform((int)band[s + 2]);
+                const int jl = band_lo(b0), jh = band_hi(b0);     // predecessors: row s
+                const int il = band_lo(b1), ih = band_hi(b1);     // cells: row s + 1
+                const int top_n = band_hi(b2);                    // stage s+1 reads its rows up to here
                 const Pair *prev = rows + cur * row_len;
                 Pair *next = rows + (cur ^ 1) * row_len;
                 const int64_t *Q = Qb + cur * row_len;
                 int64_t *Qn = Qb + (cur ^ 1) * row_len;
-                if (tid == 0) fmax_s[f_reset] = -1;
+                const uint32_t *p32_n = uniform_ptr(sc[s + 1].p32);
+                const uint32_t *cm_n = uniform_ptr(sc[s + 1].cm);
+                const bool next_has_cut = s + 2 < S;
 
                 // requests for stage s+1: entry jn of its rows, and this thread's own cut time
-                const int jn = s + 1 + tid;
-                const bool next_has_cut = s + 2 < S;
+                const int jn = il + tid;
                 uint32_t p_n = 0, cut_n = 0;
                 int64_t pp_n = 0, ps_n = 0;
-                {
-                    const uint32_t *p32 = uniform_ptr(sc[s + 1].p32);
-                    const uint32_t *cm = uniform_ptr(sc[s + 1].cm);
-                    if (stages) { p_n = p32[jn]; pp_n = PP[jn]; ps_n = PS[jn]; }
-                    if (live && next_has_cut) cut_n = cm[jn + 1];
-                }
+                if (jn <= top_n) { p_n = p32_n[jn]; pp_n = PP[jn]; ps_n = PS[jn]; }
+                if (next_has_cut && band_lo(b2) + tid <= top_n) cut_n = cm_n[band_lo(b2) + tid];
 
-                const int i = s + 1 + tid;
-                uint32_t best = kInf32;
-                int best_j = 0;
-                if (live) {
+                int first_j = 0;
+                for (int i = il + tid, trip = 0; i <= ih; i += nthreads, ++trip) {
+                    // a band wider than the workgroup takes more trips; their cut times come
+                    // straight from the table
+                    const uint32_t cut = trip == 0 ? cut_i : uniform_ptr(sc[s].cm)[i];
                     // fitting cuts are j >= lo with Q[lo] >= Q[i] - cap (memory need is monotone
                     // in j), so the downward scan also stops at the first misfit
                     const int64_t th = Q[i] - cap;
                     const uint32_t xi = prev[i].p + tp - 1;
+                    uint32_t best = kInf32;
+                    int best_j = 0;
                     // Four previous cuts per trip, read at fixed offsets below j.  An entry counts
                     // while it fits in memory (monotone in j, so a plain predicate); entries below
-                    // cut s hold D = infinity and never win.  Entries below a stop cannot update
+                    // the band hold D = infinity and never win.  Entries below a stop cannot update
                     // (their time exceeds the best value), so only the last entry of a trip
                     // decides whether the lane goes on.
-                    int j = (i - 1) < fmax_prev ? (i - 1) : fmax_prev;
-                    bool more = true;
+                    int j = (i - 1) < jh ? (i - 1) : jh;
+                    bool more = j >= jl;
                     while (more) {
                         const Pair *pe = prev + (j - 3);
                         const int64_t *pq = Q + (j - 3);
@@ -196,7 +319,7 @@ void k2_fast(TablesDev tb, CandDev cd, PlansDev out, unsigned char *ws, size_t w
 #define HARP_STEP(E, QV, JJ)                                                   \
     {                                                                          \
         tj = (xi - (E).p) >> shift;                                            \
-        const uint32_t v = umax3((E).d, tj, cut_i);                            \
+        const uint32_t v = umax3((E).d, tj, cut);                              \
         const bool upd = ((QV) >= th) & (v <= best);                           \
         best = upd ? v : best;                                                 \
         best_j = upd ? (JJ) : best_j;                                          \
@@ -206,44 +329,46 @@ void k2_fast(TablesDev tb, CandDev cd, PlansDev out, unsigned char *ws, size_t w
                         HARP_STEP(e2, q2, j - 2)
                         HARP_STEP(e3, q3, j - 3)
 #undef HARP_STEP
-                        more = ((j - 3) > s) & (q3 >= th) & (tj <= best);
+                        more = ((j - 3) > jl) & (q3 >= th) & (tj <= best);
                         j -= 4;
                     }
                     next[i].d = best;
+                    if (trip == 0) first_j = best_j;
+                    else arg[s * row_len + i] = (uint16_t)best_j;
                 }
-                if (tid < 3) next[s - tid].d = kInf32;     // cuts below s+1 for the next stage
-                const unsigned long long finite = __ballot(best != kInf32);
-                if (lane == 0 && finite) atomicMax(fmax_next, s + 1 + wave * 64 + 63 - __clzll(finite));
+                if (tid < 3) next[il - 1 - tid].d = kInf32;     // below the band of row s + 1
 
                 // commit the staged entries of stage s+1, then let the back-pointer go
-                if (stages) {
-                    const int64_t n1 = (S - s - 1) < m_cap ? (S - s - 1) : m_cap;
+                const int64_t n1 = (S - s - 1) < m_cap ? (S - s - 1) : m_cap;
+                if (jn <= top_n) {
                     next[jn].p = p_n;
                     Qn[jn] = pp_n + n1 * ps_n;
                 }
+                for (int j = jn + nthreads; j <= top_n; j += nthreads) {
+                    next[j].p = p32_n[j];
+                    Qn[j] = PP[j] + n1 * PS[j];
+                }
                 cut_i = cut_n;
-                if (live) arg[s * row_len + i] = (uint16_t)best_j;
+                if (il + tid <= ih) arg[s * row_len + il + tid] = (uint16_t)first_j;
                 lds_barrier();
                 cur ^= 1;
-                fmax_prev = uniform(*fmax_next);
-                { const int t = 3 - f_next - f_reset; f_next = f_reset; f_reset = t; }
-                if (fmax_prev < 0) { dead = true; break; }   // no cell of this row is reachable
             }
-            if (!dead) {
-                // the last stage has the single cell i = L: lanes over j, lexicographic reduction
+            // the last stage has the single cell i = L: lanes over j, lexicographic reduction
+            {
                 const int s = S - 1;
                 if (wave == 0) {
                     const int shift = uniform(sc[s].shift);
                     const uint32_t tp = 1u << shift;
                     const int64_t cap = uniform64(sc[s].cap);
+                    const uint32_t b0 = (uint32_t)uniform((int)band[s]);
                     const Pair *prev = rows + cur * row_len;
                     const int64_t *Q = Qb + cur * row_len;
                     const int64_t th = Q[L] - cap;
                     const uint32_t xi = prev[L].p + tp - 1;
-                    const int hi = (L - 1) < fmax_prev ? (L - 1) : fmax_prev;
+                    const int hi = (L - 1) < band_hi(b0) ? (L - 1) : band_hi(b0);
                     uint32_t best = kInf32;
                     int best_j = INT32_MAX;
-                    for (int j = s + lane; j <= hi; j += 64) {
+                    for (int j = band_lo(b0) + lane; j <= hi; j += 64) {
                         if (Q[j] < th) continue;
                         const Pair e = prev[j];
                         const uint32_t tj = (xi - e.p) >> shift;
@@ -256,13 +381,10 @@ void k2_fast(TablesDev tb, CandDev cd, PlansDev out, unsigned char *ws, size_t w
                         const int oj = __shfl_xor(best_j, d, 64);
                         if (ov < best || (ov == best && oj < best_j)) { best = ov; best_j = oj; }
                     }
-                    if (lane == 0) {
-                        arg[s * row_len + L] = (uint16_t)(best == kInf32 ? 0 : best_j);
-                        fmax_s[f_next] = best == kInf32 ? -1 : L;
-                    }
+                    if (lane == 0) arg[s * row_len + L] = (uint16_t)(best == kInf32 ? 0xFFFFu : best_j);
                 }
                 __syncthreads();          // back-pointers of every wave are visible to thread 0
-                if (fmax_s[f_next] < 0) dead = true;
+                if (arg[s * row_len + L] == 0xFFFFu) dead = true;   // L <= 1024, so no cut has this value
             }
             if (!dead && tid == 0) {
                 int b = L;
@@ -270,7 +392,7 @@ void k2_fast(TablesDev tb, CandDev cd, PlansDev out, unsigned char *ws, size_t w
                 for (int s = S - 1; s >= 0; --s) { b = arg[s * row_len + b]; sp[s] = b; }
             }
         } else if (tid == 0) {
-            sp[0] = 0;    // one stage holds every operator; the score below checks that it fits
+            sp[0] = 0;    // one stage holds every operator; the pre-pass has checked that it fits
             sp[1] = L;
         }
         if (dead) {
@@ -278,60 +400,78 @@ void k2_fast(TablesDev tb, CandDev cd, PlansDev out, unsigned char *ws, size_t w
             continue;
         }
         for (int s = S + 1 + tid; s <= S_max; s += nthreads) sp[s] = -1;
-        int32_t *df = out.dev_first + int64_t(c) * S_max;
-        for (int s = tid; s < S_max; s += nthreads) df[s] = s < S ? slots.dev_first[s] : -1;
         __syncthreads();              // the cuts written by thread 0 are read by the first wave
-        int st = HARP_CAND_OK;
         if (wave == 0) {
             int64_t bott, iter;
-            st = wave_score_partition(tb, S, slots, sp, lane, bott, iter);
+            const int st = wave_score_partition(tb, S, slot_g, slot_k, sp, lane, bott, iter);
             if (lane == 0) {
                 out.bottleneck[c] = bott;
                 out.iter_time[c] = iter;
                 out.status[c] = st;
             }
         }
-        if (S == 1) {                 // a single stage that does not fit: no plan to report
-            if (__syncthreads_or(wave == 0 && st != HARP_CAND_OK)) {
-                for (int s = tid; s <= S_max; s += nthreads) sp[s] = -1;
-                for (int s = tid; s < S_max; s += nthreads) df[s] = -1;
-            }
-        }
     }
-}
-
-int fast_threads(int L) {
-    int t = (L + 63) / 64 * 64;
-    return t > kMaxThreads ? kMaxThreads : t;
 }
 
 int fast_row_len(int L) { return (L + 1 + kPad + 7) / 8 * 8; }
 
-size_t fast_lds_bytes(int L) { return size_t(fast_row_len(L)) * (16 + 2 * sizeof(Pair)); }
+size_t fast_lds_bytes(int L, int S_max) {
+    size_t b = size_t(fast_row_len(L)) * 32 + size_t(S_max) * sizeof(StageConst) +
+               size_t(S_max + 1) * 4 + size_t(S_max) * 3;
+    return (b + 15) & ~size_t(15);
+}
 
-}  // namespace
-
-size_t plan_fast_ws_per_group(int L, int S_max) {
+size_t fast_arg_per_group(int L, int S_max) {
     size_t b = size_t(S_max) * fast_row_len(L) * sizeof(uint16_t);
     return (b + 255) & ~size_t(255);
 }
 
+// Workspace: live counter | live list [C] | bands [C][S_max+1] | back-pointer slices.
+struct FastWorkspace {
+    int *live_count;
+    int32_t *live_list;
+    uint32_t *bands;
+    unsigned char *arg;
+    size_t total;
+};
+
+FastWorkspace carve(void *ws, int L, int S_max, int C, int n_groups) {
+    auto up = [](size_t x) { return (x + 255) & ~size_t(255); };
+    unsigned char *base = static_cast<unsigned char *>(ws);
+    FastWorkspace w;
+    size_t off = 0;
+    w.live_count = reinterpret_cast<int *>(base + off); off += 256;
+    w.live_list = reinterpret_cast<int32_t *>(base + off); off += up(size_t(C) * 4);
+    w.bands = reinterpret_cast<uint32_t *>(base + off); off += up(size_t(C) * (S_max + 1) * 4);
+    w.arg = base + off; off += size_t(n_groups) * fast_arg_per_group(L, S_max);
+    w.total = off;
+    return w;
+}
+
+}  // namespace
+
+size_t plan_fast_ws_bytes(int L, int S_max, int C, int n_groups) {
+    return carve(nullptr, L, S_max, C, n_groups).total;
+}
+
 // Workgroups that can be resident at once: bounded by threads (2048 per CU) and LDS (160 KiB).
-int plan_fast_groups(int L, int n_cu) {
-    const int by_threads = 2048 / fast_threads(L);
-    const size_t lds = fast_lds_bytes(L) + sizeof(SlotInfo) + 64;
-    int by_lds = int((size_t(160) << 10) / lds);
+int plan_fast_groups(int L, int S_max, int n_cu) {
+    const int by_threads = 2048 / kFastThreads;
+    int by_lds = int((size_t(160) << 10) / (fast_lds_bytes(L, S_max) + 64));
     int per_cu = by_threads < by_lds ? by_threads : by_lds;
-    if (per_cu > 16) per_cu = 16;
     if (per_cu < 1) per_cu = 1;
     return per_cu * n_cu;
 }
 
 void launch_plan_fast(const TablesDev &tb, const CandDev &cd, const PlansDev &out, void *ws,
                       int n_groups, hipStream_t st) {
-    hipLaunchKernelGGL(k2_fast, dim3(n_groups), dim3(fast_threads(tb.L)), fast_lds_bytes(tb.L), st, tb, cd,
-                       out, static_cast<unsigned char *>(ws), plan_fast_ws_per_group(tb.L, cd.S_max),
-                       fast_row_len(tb.L));
+    const FastWorkspace w = carve(ws, tb.L, cd.S_max, cd.C, n_groups);
+    hipLaunchKernelGGL(k2_clear_count, dim3(1), dim3(64), 0, st, w.live_count);
+    hipLaunchKernelGGL(k2_band, dim3((cd.C + 255) / 256), dim3(256), 0, st, tb, cd, out, w.live_count,
+                       w.live_list, w.bands);
+    hipLaunchKernelGGL(k2_fast, dim3(n_groups), dim3(kFastThreads), fast_lds_bytes(tb.L, cd.S_max), st, tb,
+                       cd, out, w.live_count, w.live_list, w.bands, w.arg,
+                       fast_arg_per_group(tb.L, cd.S_max), fast_row_len(tb.L));
 }
 
 }  // namespace harp

@@ -102,7 +102,7 @@ __global__ __launch_bounds__(kThreads) void k2_generic(TablesDev tb, CandDev cd,
         __syncthreads();              // the cuts written by thread 0 are read by the first wave
         if (wave == 0) {
             int64_t bott, iter;
-            const int st = wave_score_partition(tb, S, slots, sp, lane, bott, iter);
+            const int st = wave_score_partition(tb, S, slots.g, slots.k, sp, lane, bott, iter);
             if (lane == 0) {
                 out.bottleneck[c] = bott;
                 out.iter_time[c] = iter;

@@ -23,7 +23,7 @@ __global__ __launch_bounds__(64) void k3_score(TablesDev tb, CandDev cd, const i
                                       cd.cand_tp + int64_t(c) * S_max, slots);
         int64_t bott = kInf, iter = kInf;
         if (st == HARP_CAND_OK)
-            st = wave_score_partition(tb, S, slots, splits + int64_t(c) * (S_max + 1),
+            st = wave_score_partition(tb, S, slots.g, slots.k, splits + int64_t(c) * (S_max + 1),
                                       threadIdx.x, bott, iter);
         if (threadIdx.x == 0) {
             bottleneck[c] = bott;

@@ -64,8 +64,8 @@ __device__ __forceinline__ void write_failed(const PlansDev &out, int c, int S_m
 // for the partition sp[0..S]:  sum_s (t_s + 2 c_s) + (M - 1) max_s max(t_s, c_s), after checking
 // that the cuts rise strictly from 0 to L and that every stage fits in memory (eq. mem_cons).
 // Every lane receives the same status, bottleneck and iteration time.
-__device__ __forceinline__ int wave_score_partition(const TablesDev &tb, int S, const SlotInfo &sl,
-                                                    const int32_t *sp, int lane,
+__device__ __forceinline__ int wave_score_partition(const TablesDev &tb, int S, const uint16_t *slot_g,
+                                                    const uint8_t *slot_k, const int32_t *sp, int lane,
                                                     int64_t &bottleneck, int64_t &iter_time) {
     const int L = tb.L;
     int invalid = 0;
@@ -79,7 +79,7 @@ __device__ __forceinline__ int wave_score_partition(const TablesDev &tb, int S, 
     int64_t worst = 0, single = 0;
     int unfit = 0;
     for (int s = lane; s < S; s += 64) {
-        const int g = sl.g[s], k = sl.k[s];
+        const int g = slot_g[s], k = slot_k[s];
         const int64_t tp = tb.tp[k];
         const int t = tb.group_type[g];
         const int j = sp[s], i = sp[s + 1];
@@ -90,7 +90,7 @@ __device__ __forceinline__ int wave_score_partition(const TablesDev &tb, int S, 
         const int64_t time = (pf[i] - pf[j] + tp - 1) / tp + (pr[i] - pr[j]);
         int64_t cut = 0;
         if (s < S - 1) {
-            const int64_t link = tb.bw[int64_t(g) * tb.G + sl.g[s + 1]];
+            const int64_t link = tb.bw[int64_t(g) * tb.G + slot_g[s + 1]];
             cut = (tb.act_bytes[i - 1] + link - 1) / link;
         }
         const int64_t m = time > cut ? time : cut;

@@ -200,6 +200,27 @@ def test_plan_medium_random_problems(harp, ctx):
         _plan_all_paths(harp, ctx, p, cands, want, "medium %d (L=%d)" % (case, L))
 
 
+def test_plan_wide_bands(harp, ctx):
+    """Loose memory: every DP row is reachable over its whole width, wider than a workgroup, so
+    cells and staged rows take several trips; and memory so tight that bands are a few cells."""
+    rng = np.random.default_rng(31)
+    for L, G, S_max, scale in ((600, 3, 9, 1000.0), (1024, 2, 5, 1000.0), (700, 4, 24, 1.02), (333, 2, 40, 1.3)):
+        T = 2
+        fwd = rng.integers(1, 3000, size=(T, L))
+        params = rng.integers(1, 10**6, size=L)
+        stash = rng.integers(0, 10**4, size=L)
+        bw = rng.integers(20, 4000, size=(G, G))
+        bw = np.minimum(bw, bw.T)
+        mem = np.full(T, int(scale * (params.sum() + S_max * stash.sum()) / S_max))
+        p = simple_problem(np.zeros(L), M=12, T=T, G=G, ndev=[16] * G, tp=(1, 2), fwd=fwd, bwd=fwd,
+                           params=params, stash=stash, act=rng.integers(0, 10**6, size=L),
+                           gtype=rng.integers(0, T, size=G), mem=mem, bw=bw)
+        cands = W.make_candidates(p, L, 81, G, S_max, 0, 40)
+        want = oracle_plan_threaded(oracle.build_tables(p), cands)
+        _, ran = _plan_all_paths(harp, ctx, p, cands, want, "wide bands L=%d" % L)
+        assert harp.PATH_FAST32 in ran
+
+
 def test_plan_adversarial_rows(harp, ctx):
     """Inputs built to break shortcuts: huge transfers on some cuts (non-monotone DP rows), zero
     cost operators (long runs of ties), memory that only fits one-operator stages."""
