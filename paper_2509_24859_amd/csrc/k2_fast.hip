@@ -114,12 +114,32 @@ __device__ void thread_write_failed(const PlansDev &out, int c, int S_max, int s
 // Pre-pass, one thread per candidate: checks the slot list, writes the device assignment, and
 // computes the reachability band [B[s], F[s]] of every DP row from the memory constraint alone
 // (two chains of binary searches over the running sums).  Candidates that are malformed or proven
-// infeasible get their final outputs here; the others are appended to the live list.
-__global__ __launch_bounds__(256) void k2_band(TablesDev tb, CandDev cd, PlansDev out, int *live_count,
-                                               int32_t *live_list, uint32_t *bands) {
-    const int c = blockIdx.x * blockDim.x + threadIdx.x;
-    if (c >= cd.C) return;
+// infeasible get their final outputs here; the others are appended to the live list.  The running
+// sums PP, PS and the per-(group, degree) memory caps are staged in LDS once per workgroup, since
+// every probe of the searches is a dependent load.
+constexpr int kBandThreads = 256;
+constexpr int kBandCapTable = 2048;     // caps kept in LDS when G * n_tp is at most this
+
+__global__ __launch_bounds__(kBandThreads) void k2_band(TablesDev tb, CandDev cd, PlansDev out,
+                                                        int *live_count, int32_t *live_list,
+                                                        uint32_t *bands, int caps_in_lds) {
+    extern __shared__ __align__(16) unsigned char lds_raw[];
     const int L = tb.L, S_max = cd.S_max;
+    int64_t *PP = reinterpret_cast<int64_t *>(lds_raw);      // [L + 1]
+    int64_t *PS = PP + (L + 1);                              // [L + 1]
+    int64_t *caps = PS + (L + 1);                            // [G * n_tp] when caps_in_lds
+    {
+        const int64_t *gp = tb.PP(), *gs = tb.PS();
+        for (int i = threadIdx.x; i <= L; i += kBandThreads) { PP[i] = gp[i]; PS[i] = gs[i]; }
+        if (caps_in_lds)
+            for (int q = threadIdx.x; q < tb.G * tb.n_tp; q += kBandThreads) {
+                const int g = q / tb.n_tp, k = q - g * tb.n_tp;
+                caps[q] = int64_t(tb.tp[k]) * tb.type_mem[tb.group_type[g]];
+            }
+    }
+    __syncthreads();
+    const int c = blockIdx.x * kBandThreads + threadIdx.x;
+    if (c >= cd.C) return;
     const int S = cd.cand_S[c];
     const int32_t *grp = cd.cand_group + int64_t(c) * S_max;
     const int32_t *tpv = cd.cand_tp + int64_t(c) * S_max;
@@ -128,13 +148,19 @@ __global__ __launch_bounds__(256) void k2_band(TablesDev tb, CandDev cd, PlansDe
     int status = HARP_CAND_OK;
     if (S < 1 || S > S_max) status = HARP_CAND_INVALID;
     int64_t used = 0;
+    unsigned long long seen = 0;                      // groups already left, when G <= 64
     for (int s = 0; status == HARP_CAND_OK && s < S; ++s) {
         const int g = grp[s];
         const int k = tp_index(tb, tpv[s]);
         if (g < 0 || g >= tb.G || k < 0) { status = HARP_CAND_INVALID; break; }
         if (s == 0 || grp[s - 1] != g) {              // first slot of a run of group g
-            for (int q = 0; q + 1 < s; ++q)
-                if (grp[q] == g) status = HARP_CAND_INVALID;   // the group was left and entered again
+            if (tb.G <= 64) {
+                if ((seen >> g) & 1ull) status = HARP_CAND_INVALID;   // the group was left and entered again
+                seen |= 1ull << g;
+            } else {
+                for (int q = 0; q + 1 < s; ++q)
+                    if (grp[q] == g) status = HARP_CAND_INVALID;
+            }
             used = 0;
         }
         df[s] = tb.group_base[g] + (int32_t)used;
@@ -148,7 +174,11 @@ __global__ __launch_bounds__(256) void k2_band(TablesDev tb, CandDev cd, PlansDe
     }
     for (int s = S; s < S_max; ++s) df[s] = -1;
 
-    const int64_t *PP = tb.PP(), *PS = tb.PS();
+    auto cap_of = [&](int s) -> int64_t {
+        const int g = grp[s];
+        const int k = tp_index(tb, tpv[s]);
+        return caps_in_lds ? caps[g * tb.n_tp + k] : int64_t(tb.tp[k]) * tb.type_mem[tb.group_type[g]];
+    };
     uint32_t *band = bands + int64_t(c) * (S_max + 1);
     const int R = L - S + 1;
     bool feasible = true;
@@ -156,10 +186,8 @@ __global__ __launch_bounds__(256) void k2_band(TablesDev tb, CandDev cd, PlansDe
     int F = 0;
     band[0] = 0;
     for (int s = 0; s < S; ++s) {
-        const int g = grp[s];
-        const int64_t tp = tpv[s];
         const int64_t n = (S - s) < tb.M ? (S - s) : tb.M;
-        const int64_t cap = tp * tb.type_mem[tb.group_type[g]];
+        const int64_t cap = cap_of(s);
         const int64_t q0 = PP[F] + n * PS[F];
         const int top = (s == S - 1) ? L : s + R;
         int a = F, b = top;                                   // need(F, a) <= cap always holds
@@ -177,10 +205,8 @@ __global__ __launch_bounds__(256) void k2_band(TablesDev tb, CandDev cd, PlansDe
         int B = L;
         band[S] |= uint32_t(L);
         for (int s = S - 1; s >= 0; --s) {
-            const int g = grp[s];
-            const int64_t tp = tpv[s];
             const int64_t n = (S - s) < tb.M ? (S - s) : tb.M;
-            const int64_t cap = tp * tb.type_mem[tb.group_type[g]];
+            const int64_t cap = cap_of(s);
             const int64_t qb = PP[B] + n * PS[B];
             int a = s, b = B;                                 // need(b, B) <= cap holds at b = B
             if (qb - (PP[a] + n * PS[a]) <= cap) b = a;
@@ -198,7 +224,14 @@ __global__ __launch_bounds__(256) void k2_band(TablesDev tb, CandDev cd, PlansDe
         thread_write_failed(out, c, S_max, HARP_CAND_INFEASIBLE);
         return;
     }
-    live_list[atomicAdd(live_count, 1)] = c;
+    // append to the live list with one atomic per wave: the lanes still here rank themselves
+    const int lane = threadIdx.x & 63;
+    const unsigned long long here = __ballot(1);
+    const int leader = __ffsll((long long)here) - 1;
+    int base = 0;
+    if (lane == leader) base = atomicAdd(live_count, __popcll(here));
+    base = __shfl(base, leader, 64);
+    live_list[base + __popcll(here & ((1ull << lane) - 1ull))] = c;
 }
 
 __global__ void k2_clear_count(int *live_count) {
@@ -267,16 +300,23 @@ void k2_fast(TablesDev tb, CandDev cd, PlansDev out, const int *live_count, cons
             lds_barrier();
 
             int cur = 0;
+            const int wave_first = wave * 64;
             for (int s = 0; s < S - 1; ++s) {
+                const uint32_t b1 = (uint32_t)uniform((int)band[s + 1]);
+                const uint32_t b2 = (uint32_t)uniform((int)band[s + 2]);
+                const int il = band_lo(b1), ih = band_hi(b1);     // cells: row s + 1
+                const int top_n = band_hi(b2);                    // stage s+1 reads its rows up to here
+                // a wave whose lanes own neither a cell nor a staged entry only keeps the barrier
+                if (il + wave_first > top_n && wave != 0) {
+                    lds_barrier();
+                    cur ^= 1;
+                    continue;
+                }
                 const int shift = uniform(sc[s].shift);
                 const uint32_t tp = 1u << shift;
                 const int64_t cap = uniform64(sc[s].cap);
                 const uint32_t b0 = (uint32_t)uniform((int)band[s]);
-                const uint32_t b1 = (uint32_t)uniform((int)band[s + 1]);
-                const uint32_t b2 = (uint32_t)uniform((int)band[s + 2]);
                 const int jl = band_lo(b0), jh = band_hi(b0);     // predecessors: row s
-                const int il = band_lo(b1), ih = band_hi(b1);     // cells: row s + 1
-                const int top_n = band_hi(b2);                    // stage s+1 reads its rows up to here
                 const Pair *prev = rows + cur * row_len;
                 Pair *next = rows + (cur ^ 1) * row_len;
                 const int64_t *Q = Qb + cur * row_len;
@@ -467,8 +507,10 @@ void launch_plan_fast(const TablesDev &tb, const CandDev &cd, const PlansDev &ou
                       int n_groups, hipStream_t st) {
     const FastWorkspace w = carve(ws, tb.L, cd.S_max, cd.C, n_groups);
     hipLaunchKernelGGL(k2_clear_count, dim3(1), dim3(64), 0, st, w.live_count);
-    hipLaunchKernelGGL(k2_band, dim3((cd.C + 255) / 256), dim3(256), 0, st, tb, cd, out, w.live_count,
-                       w.live_list, w.bands);
+    const int caps_in_lds = tb.G * tb.n_tp <= kBandCapTable ? 1 : 0;
+    const size_t band_lds = size_t(tb.L + 1) * 16 + (caps_in_lds ? size_t(tb.G) * tb.n_tp * 8 : 0);
+    hipLaunchKernelGGL(k2_band, dim3((cd.C + kBandThreads - 1) / kBandThreads), dim3(kBandThreads), band_lds, st,
+                       tb, cd, out, w.live_count, w.live_list, w.bands, caps_in_lds);
     hipLaunchKernelGGL(k2_fast, dim3(n_groups), dim3(kFastThreads), fast_lds_bytes(tb.L, cd.S_max), st, tb,
                        cd, out, w.live_count, w.live_list, w.bands, w.arg,
                        fast_arg_per_group(tb.L, cd.S_max), fast_row_len(tb.L));
