@@ -49,6 +49,7 @@ namespace {
 constexpr uint32_t kInf32 = 0xFFFFFFFFu;
 constexpr int kPad = 4;
 constexpr int kFastThreads = 256;
+constexpr uint32_t kRowMask = (1u << 27) - 1u;
 
 struct alignas(8) Pair {
     uint32_t d;   // previous DP row
@@ -83,13 +84,15 @@ __device__ __forceinline__ const T *uniform_ptr(const T *p) {
 
 // Per-slot constants of the candidate in flight, computed once per candidate so that the stage
 // loop starts from LDS and never waits on a chain of dependent global loads.
+// Rows are named by element offsets from the table bases, not by pointers: a pointer read back
+// from LDS has no known address space and would turn every table access into a flat load.
 struct alignas(16) StageConst {
     int64_t cap;            // tp * device memory of the slot's GPU type
-    const uint32_t *p32;    // the slot's fused time row
-    const uint32_t *cm;     // cut-time row of the link to the next slot
-    int32_t shift;          // log2 tp
-    int32_t pad;
+    uint32_t p_row;         // element offset of the slot's fused time row in P32
+    uint32_t cm_row_shift;  // element offset of the link's cut-time row in CM (low 27 bits) | log2 tp << 27
 };
+static_assert(sizeof(StageConst) == 16, "one 16-byte LDS read per stage");
+static_assert(kFastCutTableLimit / 4 <= (size_t(1) << 27), "cut-table offsets must fit 27 bits");
 
 __device__ __forceinline__ int band_lo(uint32_t w) { return int(w & 0xFFFFu); }
 __device__ __forceinline__ int band_hi(uint32_t w) { return int(w >> 16); }
@@ -244,7 +247,8 @@ void k2_fast(TablesDev tb, CandDev cd, PlansDev out, const int *live_count, cons
     extern __shared__ __align__(16) unsigned char lds_raw[];
 
     const int L = tb.L, S_max = cd.S_max;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nthreads = blockDim.x;
+    const int tid = threadIdx.x, lane = tid & 63, nthreads = blockDim.x;
+    const int wave = uniform(tid >> 6);
     // every LDS row has kPad spare entries in front, so that the group of four previous cuts
     // ending at any j >= 0 can be read at fixed offsets without clamping
     int64_t *Qb = reinterpret_cast<int64_t *>(lds_raw) + kPad;                        // [2][row_len]
@@ -272,9 +276,9 @@ void k2_fast(TablesDev tb, CandDev cd, PlansDev out, const int *live_count, cons
                 slot_g[s] = (uint16_t)g;
                 slot_k[s] = (uint8_t)k;
                 sc[s].cap = int64_t(tb.tp[k]) * tb.type_mem[tb.group_type[g]];
-                sc[s].p32 = tb.P32 + (int64_t(g) * tb.n_tp + k) * tb.pitch32;
-                sc[s].cm = tb.CM + (int64_t(g) * tb.G + g_next) * tb.pitch32;
-                sc[s].shift = tb.tp_shift[k];
+                sc[s].p_row = uint32_t((int64_t(g) * tb.n_tp + k) * tb.pitch32);
+                sc[s].cm_row_shift = uint32_t((int64_t(g) * tb.G + g_next) * tb.pitch32) |
+                                     (uint32_t(tb.tp_shift[k]) << 27);
             }
             for (int s = tid; s <= S; s += nthreads) band[s] = bw[s];
         }
@@ -285,8 +289,8 @@ void k2_fast(TablesDev tb, CandDev cd, PlansDev out, const int *live_count, cons
             // prologue: rows of stage 0 over [0, F[1]] and the thread's own cut time of stage 0
             uint32_t cut_i = 0;
             {
-                const uint32_t *p32 = uniform_ptr(sc[0].p32);
-                const uint32_t *cm = uniform_ptr(sc[0].cm);
+                const uint32_t *p32 = tb.P32 + (uint32_t)uniform((int)sc[0].p_row);
+                const uint32_t *cm = tb.CM + ((uint32_t)uniform((int)sc[0].cm_row_shift) & kRowMask);
                 const int64_t n0 = S < m_cap ? S : m_cap;
                 const uint32_t b1 = (uint32_t)uniform((int)band[1]);
                 for (int j = tid; j <= band_hi(b1); j += nthreads) {
@@ -312,17 +316,19 @@ void k2_fast(TablesDev tb, CandDev cd, PlansDev out, const int *live_count, cons
                     cur ^= 1;
                     continue;
                 }
-                const int shift = uniform(sc[s].shift);
+                const uint32_t rs = (uint32_t)uniform((int)sc[s].cm_row_shift);
+                const int shift = int(rs >> 27);
                 const uint32_t tp = 1u << shift;
                 const int64_t cap = uniform64(sc[s].cap);
                 const uint32_t b0 = (uint32_t)uniform((int)band[s]);
                 const int jl = band_lo(b0), jh = band_hi(b0);     // predecessors: row s
+                const uint32_t *cm_s = tb.CM + (rs & kRowMask);
                 const Pair *prev = rows + cur * row_len;
                 Pair *next = rows + (cur ^ 1) * row_len;
                 const int64_t *Q = Qb + cur * row_len;
                 int64_t *Qn = Qb + (cur ^ 1) * row_len;
-                const uint32_t *p32_n = uniform_ptr(sc[s + 1].p32);
-                const uint32_t *cm_n = uniform_ptr(sc[s + 1].cm);
+                const uint32_t *p32_n = tb.P32 + (uint32_t)uniform((int)sc[s + 1].p_row);
+                const uint32_t *cm_n = tb.CM + ((uint32_t)uniform((int)sc[s + 1].cm_row_shift) & kRowMask);
                 const bool next_has_cut = s + 2 < S;
 
                 // requests for stage s+1: entry jn of its rows, and this thread's own cut time
@@ -332,22 +338,17 @@ void k2_fast(TablesDev tb, CandDev cd, PlansDev out, const int *live_count, cons
                 if (jn <= top_n) { p_n = p32_n[jn]; pp_n = PP[jn]; ps_n = PS[jn]; }
                 if (next_has_cut && band_lo(b2) + tid <= top_n) cut_n = cm_n[band_lo(b2) + tid];
 
-                int first_j = 0;
-                for (int i = il + tid, trip = 0; i <= ih; i += nthreads, ++trip) {
-                    // a band wider than the workgroup takes more trips; their cut times come
-                    // straight from the table
-                    const uint32_t cut = trip == 0 ? cut_i : uniform_ptr(sc[s].cm)[i];
-                    // fitting cuts are j >= lo with Q[lo] >= Q[i] - cap (memory need is monotone
-                    // in j), so the downward scan also stops at the first misfit
+                // One DP cell: scan the fitting previous cuts of the band downwards, four per trip.
+                // Fitting cuts are j >= lo with Q[lo] >= Q[i] - cap (memory need is monotone in
+                // j), so an entry counts while its Q passes the threshold, a plain predicate;
+                // entries below the band hold D = infinity and never win.  Entries below a stop
+                // cannot update (their time exceeds the best value), so only the last entry of a
+                // trip decides whether the lane goes on.  Returns the back-pointer.
+                auto cell = [&](int i, uint32_t cut) -> int {
                     const int64_t th = Q[i] - cap;
                     const uint32_t xi = prev[i].p + tp - 1;
                     uint32_t best = kInf32;
                     int best_j = 0;
-                    // Four previous cuts per trip, read at fixed offsets below j.  An entry counts
-                    // while it fits in memory (monotone in j, so a plain predicate); entries below
-                    // the band hold D = infinity and never win.  Entries below a stop cannot update
-                    // (their time exceeds the best value), so only the last entry of a trip
-                    // decides whether the lane goes on.
                     int j = (i - 1) < jh ? (i - 1) : jh;
                     bool more = j >= jl;
                     while (more) {
@@ -373,9 +374,15 @@ void k2_fast(TablesDev tb, CandDev cd, PlansDev out, const int *live_count, cons
                         j -= 4;
                     }
                     next[i].d = best;
-                    if (trip == 0) first_j = best_j;
-                    else arg[s * row_len + i] = (uint16_t)best_j;
-                }
+                    return best_j;
+                };
+                const int i0 = il + tid;
+                int first_j = 0;
+                if (i0 <= ih) first_j = cell(i0, cut_i);
+                // a band wider than the workgroup takes more trips; their cut times come straight
+                // from the table
+                for (int i = i0 + nthreads; i <= ih; i += nthreads)
+                    arg[s * row_len + i] = (uint16_t)cell(i, cm_s[i]);
                 if (tid < 3) next[il - 1 - tid].d = kInf32;     // below the band of row s + 1
 
                 // commit the staged entries of stage s+1, then let the back-pointer go
@@ -389,7 +396,7 @@ void k2_fast(TablesDev tb, CandDev cd, PlansDev out, const int *live_count, cons
                     Qn[j] = PP[j] + n1 * PS[j];
                 }
                 cut_i = cut_n;
-                if (il + tid <= ih) arg[s * row_len + il + tid] = (uint16_t)first_j;
+                if (i0 <= ih) arg[s * row_len + i0] = (uint16_t)first_j;
                 lds_barrier();
                 cur ^= 1;
             }
@@ -397,7 +404,7 @@ void k2_fast(TablesDev tb, CandDev cd, PlansDev out, const int *live_count, cons
             {
                 const int s = S - 1;
                 if (wave == 0) {
-                    const int shift = uniform(sc[s].shift);
+                    const int shift = int((uint32_t)uniform((int)sc[s].cm_row_shift) >> 27);
                     const uint32_t tp = 1u << shift;
                     const int64_t cap = uniform64(sc[s].cap);
                     const uint32_t b0 = (uint32_t)uniform((int)band[s]);
