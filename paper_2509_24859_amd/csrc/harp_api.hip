@@ -117,6 +117,7 @@ int check_batch(harp_ctx *ctx, harp_tables *t, const harp_candidates *cd) {
     if (!t || !cd) return fail(ctx, HARP_ERR_INVALID_ARG, "null tables or candidates");
     if (t->device != ctx->device) return fail(ctx, HARP_ERR_INVALID_ARG, "tables belong to another device");
     if (cd->C < 0) return fail(ctx, HARP_ERR_INVALID_ARG, "C must be >= 0");
+    if (cd->C >= (1 << 30)) return fail(ctx, HARP_ERR_SHAPE, "at most 2^30 - 1 candidates per batch");
     if (cd->S_max < 1 || cd->S_max > kMaxStages)
         return fail(ctx, HARP_ERR_SHAPE, "S_max must be in 1..%d", kMaxStages);
     if (cd->C > 0 && (!cd->cand_S || !cd->cand_group || !cd->cand_tp))

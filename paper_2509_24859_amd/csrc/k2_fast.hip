@@ -104,112 +104,110 @@ __device__ __forceinline__ int tp_index(const TablesDev &tb, int tp) {
     return k;
 }
 
-__device__ void thread_write_failed(const PlansDev &out, int c, int S_max, int status) {
-    int32_t *sp = out.splits + int64_t(c) * (S_max + 1);
-    int32_t *df = out.dev_first + int64_t(c) * S_max;
-    for (int s = 0; s <= S_max; ++s) sp[s] = -1;
-    for (int s = 0; s < S_max; ++s) df[s] = -1;
-    out.bottleneck[c] = kInf;
-    out.iter_time[c] = kInf;
-    out.status[c] = status;
-}
+// Pre-pass, one thread per candidate: checks the slot list and computes the reachability band
+// [B[s], F[s]] of every DP row from the memory constraint alone (two chains of binary searches
+// over the running sums).  Candidates that pass go to the live list; malformed ones and those
+// proven infeasible go to the dead list with their status.
+//
+// Every probe of the searches is a dependent load and every candidate walks its slot list twice,
+// so everything the loops touch is staged in LDS first: the running sums PP and PS, the memory
+// cap of every (group, degree), and the workgroup's slot lists, read from global memory once,
+// coalesced, and stored slot-major so that the per-thread walks are conflict-free.  Bands are
+// written slot-major as well ([s][c]), which keeps the writes of a wave contiguous.
+constexpr int kBandCapTable = 1024;     // caps kept in LDS when G * n_tp is at most this
+constexpr uint16_t kBadSlot = 0xFFFFu;
+constexpr uint32_t kDeadStatusShift = 30;
 
-// Pre-pass, one thread per candidate: checks the slot list, writes the device assignment, and
-// computes the reachability band [B[s], F[s]] of every DP row from the memory constraint alone
-// (two chains of binary searches over the running sums).  Candidates that are malformed or proven
-// infeasible get their final outputs here; the others are appended to the live list.  The running
-// sums PP, PS and the per-(group, degree) memory caps are staged in LDS once per workgroup, since
-// every probe of the searches is a dependent load.
-constexpr int kBandThreads = 256;
-constexpr int kBandCapTable = 2048;     // caps kept in LDS when G * n_tp is at most this
+int band_threads(int S_max) { return S_max <= 64 ? 256 : (S_max <= 128 ? 128 : 64); }
 
-__global__ __launch_bounds__(kBandThreads) void k2_band(TablesDev tb, CandDev cd, PlansDev out,
-                                                        int *live_count, int32_t *live_list,
-                                                        uint32_t *bands, int caps_in_lds) {
+__global__ __launch_bounds__(256) void k2_band(TablesDev tb, CandDev cd, int *counts, int32_t *live_list,
+                                               uint32_t *dead_list, uint32_t *bands, int caps_in_lds) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
-    const int L = tb.L, S_max = cd.S_max;
+    const int L = tb.L, S_max = cd.S_max, C = cd.C;
+    const int nthreads = blockDim.x, pitch = nthreads + 2;
     int64_t *PP = reinterpret_cast<int64_t *>(lds_raw);      // [L + 1]
     int64_t *PS = PP + (L + 1);                              // [L + 1]
     int64_t *caps = PS + (L + 1);                            // [G * n_tp] when caps_in_lds
+    uint16_t *slots = reinterpret_cast<uint16_t *>(caps + (caps_in_lds ? tb.G * tb.n_tp : 0));  // [S_max][pitch]
+    const int c0 = blockIdx.x * nthreads;
     {
         const int64_t *gp = tb.PP(), *gs = tb.PS();
-        for (int i = threadIdx.x; i <= L; i += kBandThreads) { PP[i] = gp[i]; PS[i] = gs[i]; }
+        for (int i = threadIdx.x; i <= L; i += nthreads) { PP[i] = gp[i]; PS[i] = gs[i]; }
         if (caps_in_lds)
-            for (int q = threadIdx.x; q < tb.G * tb.n_tp; q += kBandThreads) {
+            for (int q = threadIdx.x; q < tb.G * tb.n_tp; q += nthreads) {
                 const int g = q / tb.n_tp, k = q - g * tb.n_tp;
                 caps[q] = int64_t(tb.tp[k]) * tb.type_mem[tb.group_type[g]];
             }
+        // slot lists of this workgroup's candidates: (group << 3) | degree index, or kBadSlot
+        const int n_here = (C - c0) < nthreads ? (C - c0) : nthreads;
+        const int32_t *grp = cd.cand_group + int64_t(c0) * S_max;
+        const int32_t *tpv = cd.cand_tp + int64_t(c0) * S_max;
+        for (int idx = threadIdx.x; idx < n_here * S_max; idx += nthreads) {
+            const int cl = idx / S_max, s = idx - cl * S_max;
+            const int g = grp[idx];
+            const int k = tp_index(tb, tpv[idx]);
+            slots[s * pitch + cl] = (g < 0 || g >= tb.G || k < 0) ? kBadSlot : (uint16_t)((g << 3) | k);
+        }
     }
     __syncthreads();
-    const int c = blockIdx.x * kBandThreads + threadIdx.x;
-    if (c >= cd.C) return;
+    const int cl = threadIdx.x, c = c0 + cl;
+    if (c >= C) return;
     const int S = cd.cand_S[c];
-    const int32_t *grp = cd.cand_group + int64_t(c) * S_max;
-    const int32_t *tpv = cd.cand_tp + int64_t(c) * S_max;
-    int32_t *df = out.dev_first + int64_t(c) * S_max;
+    const int R = L - S + 1;
+    auto cap_of = [&](int g, int k) -> int64_t {
+        return caps_in_lds ? caps[g * tb.n_tp + k] : int64_t(tb.tp[k]) * tb.type_mem[tb.group_type[g]];
+    };
 
     int status = HARP_CAND_OK;
+    bool feasible = S <= L;
     if (S < 1 || S > S_max) status = HARP_CAND_INVALID;
+    // one walk over the slots: well-formedness, and the forward chain
+    // F[s+1] = largest cut that stage s can reach from F[s]
     int64_t used = 0;
-    unsigned long long seen = 0;                      // groups already left, when G <= 64
+    unsigned long long seen = 0;                      // groups already entered, when G <= 64
+    int prev_g = -1, F = 0;
+    if (status == HARP_CAND_OK) bands[c] = 0;
     for (int s = 0; status == HARP_CAND_OK && s < S; ++s) {
-        const int g = grp[s];
-        const int k = tp_index(tb, tpv[s]);
-        if (g < 0 || g >= tb.G || k < 0) { status = HARP_CAND_INVALID; break; }
-        if (s == 0 || grp[s - 1] != g) {              // first slot of a run of group g
+        const uint16_t code = slots[s * pitch + cl];
+        if (code == kBadSlot) { status = HARP_CAND_INVALID; break; }
+        const int g = code >> 3, k = code & 7;
+        if (g != prev_g) {                            // first slot of a run of group g
             if (tb.G <= 64) {
                 if ((seen >> g) & 1ull) status = HARP_CAND_INVALID;   // the group was left and entered again
                 seen |= 1ull << g;
             } else {
                 for (int q = 0; q + 1 < s; ++q)
-                    if (grp[q] == g) status = HARP_CAND_INVALID;
+                    if ((slots[q * pitch + cl] >> 3) == g) status = HARP_CAND_INVALID;
             }
             used = 0;
+            prev_g = g;
         }
-        df[s] = tb.group_base[g] + (int32_t)used;
         used += tb.tp[k];
         if (used > tb.group_ndev[g]) status = HARP_CAND_INVALID;
-    }
-    if (status == HARP_CAND_OK && S > L) status = HARP_CAND_INFEASIBLE;
-    if (status != HARP_CAND_OK) {
-        thread_write_failed(out, c, S_max, status);
-        return;
-    }
-    for (int s = S; s < S_max; ++s) df[s] = -1;
-
-    auto cap_of = [&](int s) -> int64_t {
-        const int g = grp[s];
-        const int k = tp_index(tb, tpv[s]);
-        return caps_in_lds ? caps[g * tb.n_tp + k] : int64_t(tb.tp[k]) * tb.type_mem[tb.group_type[g]];
-    };
-    uint32_t *band = bands + int64_t(c) * (S_max + 1);
-    const int R = L - S + 1;
-    bool feasible = true;
-    // forward chain: F[s+1] = largest cut that stage s can reach from F[s]
-    int F = 0;
-    band[0] = 0;
-    for (int s = 0; s < S; ++s) {
-        const int64_t n = (S - s) < tb.M ? (S - s) : tb.M;
-        const int64_t cap = cap_of(s);
-        const int64_t q0 = PP[F] + n * PS[F];
-        const int top = (s == S - 1) ? L : s + R;
-        int a = F, b = top;                                   // need(F, a) <= cap always holds
-        if ((PP[b] + n * PS[b]) - q0 <= cap) a = b;
-        while (b - a > 1) {
-            const int m = (a + b) >> 1;
-            if ((PP[m] + n * PS[m]) - q0 <= cap) a = m; else b = m;
+        if (feasible) {
+            const int64_t n = (S - s) < tb.M ? (S - s) : tb.M;
+            const int64_t cap = cap_of(g, k);
+            const int64_t q0 = PP[F] + n * PS[F];
+            const int top = (s == S - 1) ? L : s + R;
+            int a = F, b = top;                               // need(F, a) <= cap always holds
+            if ((PP[b] + n * PS[b]) - q0 <= cap) a = b;
+            while (b - a > 1) {
+                const int m = (a + b) >> 1;
+                if ((PP[m] + n * PS[m]) - q0 <= cap) a = m; else b = m;
+            }
+            F = a;
+            if (F < s + 1 || (s == S - 1 && F != L)) feasible = false;
+            else bands[int64_t(s + 1) * C + c] = uint32_t(F) << 16;
         }
-        F = a;
-        if (F < s + 1 || (s == S - 1 && F != L)) { feasible = false; break; }
-        band[s + 1] = uint32_t(F) << 16;
     }
     // backward chain: B[s] = smallest cut from which stage s can reach B[s+1]
-    if (feasible) {
+    if (status == HARP_CAND_OK && feasible) {
         int B = L;
-        band[S] |= uint32_t(L);
+        bands[int64_t(S) * C + c] |= uint32_t(L);
         for (int s = S - 1; s >= 0; --s) {
+            const uint16_t code = slots[s * pitch + cl];
             const int64_t n = (S - s) < tb.M ? (S - s) : tb.M;
-            const int64_t cap = cap_of(s);
+            const int64_t cap = cap_of(code >> 3, code & 7);
             const int64_t qb = PP[B] + n * PS[B];
             int a = s, b = B;                                 // need(b, B) <= cap holds at b = B
             if (qb - (PP[a] + n * PS[a]) <= cap) b = a;
@@ -218,32 +216,39 @@ __global__ __launch_bounds__(kBandThreads) void k2_band(TablesDev tb, CandDev cd
                 if (qb - (PP[m] + n * PS[m]) <= cap) b = m; else a = m;
             }
             B = b;
-            const int hi = band_hi(band[s]);
+            uint32_t *w = bands + int64_t(s) * C + c;
+            const int hi = band_hi(*w);
             if (hi < B || (s == 0 && B != 0)) { feasible = false; break; }
-            band[s] = uint32_t(B) | (uint32_t(hi) << 16);
+            *w = uint32_t(B) | (uint32_t(hi) << 16);
         }
     }
-    if (!feasible) {
-        thread_write_failed(out, c, S_max, HARP_CAND_INFEASIBLE);
-        return;
-    }
-    // append to the live list with one atomic per wave: the lanes still here rank themselves
+    if (status == HARP_CAND_OK && !feasible) status = HARP_CAND_INFEASIBLE;
+
+    // append to the live or the dead list with one atomic per wave and list: lanes rank themselves
     const int lane = threadIdx.x & 63;
-    const unsigned long long here = __ballot(1);
+    const bool alive = status == HARP_CAND_OK;
+    const unsigned long long here = __ballot(1), live_m = __ballot(alive), dead_m = here & ~live_m;
     const int leader = __ffsll((long long)here) - 1;
-    int base = 0;
-    if (lane == leader) base = atomicAdd(live_count, __popcll(here));
-    base = __shfl(base, leader, 64);
-    live_list[base + __popcll(here & ((1ull << lane) - 1ull))] = c;
+    int base_live = 0, base_dead = 0;
+    if (lane == leader) {
+        if (live_m) base_live = atomicAdd(&counts[0], __popcll(live_m));
+        if (dead_m) base_dead = atomicAdd(&counts[1], __popcll(dead_m));
+    }
+    base_live = __shfl(base_live, leader, 64);
+    base_dead = __shfl(base_dead, leader, 64);
+    const unsigned long long below = (1ull << lane) - 1ull;
+    if (alive) live_list[base_live + __popcll(live_m & below)] = c;
+    else dead_list[base_dead + __popcll(dead_m & below)] = uint32_t(c) | (uint32_t(status) << kDeadStatusShift);
 }
 
-__global__ void k2_clear_count(int *live_count) {
-    if (threadIdx.x == 0) *live_count = 0;
+__global__ void k2_clear_count(int *counts) {
+    if (threadIdx.x < 2) counts[threadIdx.x] = 0;
 }
 
 __global__ __launch_bounds__(kFastThreads) __attribute__((amdgpu_waves_per_eu(8, 8)))
-void k2_fast(TablesDev tb, CandDev cd, PlansDev out, const int *live_count, const int32_t *live_list,
-             const uint32_t *bands, unsigned char *arg_base, size_t arg_per_group, int row_len) {
+void k2_fast(TablesDev tb, CandDev cd, PlansDev out, const int *counts, const int32_t *live_list,
+             const uint32_t *dead_list, const uint32_t *bands, unsigned char *arg_base, size_t arg_per_group,
+             int row_len) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
 
     const int L = tb.L, S_max = cd.S_max;
@@ -259,7 +264,7 @@ void k2_fast(TablesDev tb, CandDev cd, PlansDev out, const int *live_count, cons
     uint8_t *slot_k = reinterpret_cast<uint8_t *>(slot_g + S_max);                     // [S_max]
     uint16_t *arg = reinterpret_cast<uint16_t *>(arg_base + size_t(blockIdx.x) * arg_per_group);
     const int64_t *PP = tb.PP(), *PS = tb.PS();
-    const int n_live = *live_count;
+    const int n_live = counts[0], n_dead = counts[1];
     const int64_t m_cap = tb.M;
 
     for (int n = blockIdx.x; n < n_live; n += gridDim.x) {
@@ -269,7 +274,7 @@ void k2_fast(TablesDev tb, CandDev cd, PlansDev out, const int *live_count, cons
         {
             const int32_t *grp = cd.cand_group + int64_t(c) * S_max;
             const int32_t *tpv = cd.cand_tp + int64_t(c) * S_max;
-            const uint32_t *bw = bands + int64_t(c) * (S_max + 1);
+            int32_t *df = out.dev_first + int64_t(c) * S_max;
             for (int s = tid; s < S; s += nthreads) {
                 const int g = grp[s], k = tp_index(tb, tpv[s]);
                 const int g_next = s + 1 < S ? grp[s + 1] : g;
@@ -279,8 +284,14 @@ void k2_fast(TablesDev tb, CandDev cd, PlansDev out, const int *live_count, cons
                 sc[s].p_row = uint32_t((int64_t(g) * tb.n_tp + k) * tb.pitch32);
                 sc[s].cm_row_shift = uint32_t((int64_t(g) * tb.G + g_next) * tb.pitch32) |
                                      (uint32_t(tb.tp_shift[k]) << 27);
+                // first device of the slot: its group's base plus the degrees of the group's
+                // earlier slots (they are adjacent; the pre-pass has checked that)
+                int32_t first = tb.group_base[g];
+                for (int q = s - 1; q >= 0 && grp[q] == g; --q) first += tpv[q];
+                df[s] = first;
             }
-            for (int s = tid; s <= S; s += nthreads) band[s] = bw[s];
+            for (int s = S + tid; s < S_max; s += nthreads) df[s] = -1;
+            for (int s = tid; s <= S; s += nthreads) band[s] = bands[int64_t(s) * cd.C + c];
         }
         __syncthreads();
         int32_t *sp = out.splits + int64_t(c) * (S_max + 1);
@@ -395,6 +406,10 @@ void k2_fast(TablesDev tb, CandDev cd, PlansDev out, const int *live_count, cons
                     next[j].p = p32_n[j];
                     Qn[j] = PP[j] + n1 * PS[j];
                 }
+                // the cut time requested above must have landed before the next stage issues its own
+                // requests: vector memory returns in order, so a wait placed at its first use inside
+                // the next scan would also wait for those
+                asm volatile("" : "+v"(cut_n));
                 cut_i = cut_n;
                 if (i0 <= ih) arg[s * row_len + i0] = (uint16_t)first_j;
                 lds_barrier();
@@ -458,6 +473,11 @@ void k2_fast(TablesDev tb, CandDev cd, PlansDev out, const int *live_count, cons
             }
         }
     }
+    // candidates the pre-pass rejected: no plan to report
+    for (int n = blockIdx.x; n < n_dead; n += gridDim.x) {
+        const uint32_t e = dead_list[n];
+        write_failed(out, int(e & ((1u << kDeadStatusShift) - 1u)), S_max, int(e >> kDeadStatusShift));
+    }
 }
 
 int fast_row_len(int L) { return (L + 1 + kPad + 7) / 8 * 8; }
@@ -473,10 +493,11 @@ size_t fast_arg_per_group(int L, int S_max) {
     return (b + 255) & ~size_t(255);
 }
 
-// Workspace: live counter | live list [C] | bands [C][S_max+1] | back-pointer slices.
+// Workspace: counters | live list [C] | dead list [C] | bands [S_max+1][C] | back-pointer slices.
 struct FastWorkspace {
-    int *live_count;
+    int *counts;
     int32_t *live_list;
+    uint32_t *dead_list;
     uint32_t *bands;
     unsigned char *arg;
     size_t total;
@@ -487,8 +508,9 @@ FastWorkspace carve(void *ws, int L, int S_max, int C, int n_groups) {
     unsigned char *base = static_cast<unsigned char *>(ws);
     FastWorkspace w;
     size_t off = 0;
-    w.live_count = reinterpret_cast<int *>(base + off); off += 256;
+    w.counts = reinterpret_cast<int *>(base + off); off += 256;
     w.live_list = reinterpret_cast<int32_t *>(base + off); off += up(size_t(C) * 4);
+    w.dead_list = reinterpret_cast<uint32_t *>(base + off); off += up(size_t(C) * 4);
     w.bands = reinterpret_cast<uint32_t *>(base + off); off += up(size_t(C) * (S_max + 1) * 4);
     w.arg = base + off; off += size_t(n_groups) * fast_arg_per_group(L, S_max);
     w.total = off;
@@ -513,13 +535,15 @@ int plan_fast_groups(int L, int S_max, int n_cu) {
 void launch_plan_fast(const TablesDev &tb, const CandDev &cd, const PlansDev &out, void *ws,
                       int n_groups, hipStream_t st) {
     const FastWorkspace w = carve(ws, tb.L, cd.S_max, cd.C, n_groups);
-    hipLaunchKernelGGL(k2_clear_count, dim3(1), dim3(64), 0, st, w.live_count);
+    hipLaunchKernelGGL(k2_clear_count, dim3(1), dim3(64), 0, st, w.counts);
     const int caps_in_lds = tb.G * tb.n_tp <= kBandCapTable ? 1 : 0;
-    const size_t band_lds = size_t(tb.L + 1) * 16 + (caps_in_lds ? size_t(tb.G) * tb.n_tp * 8 : 0);
-    hipLaunchKernelGGL(k2_band, dim3((cd.C + kBandThreads - 1) / kBandThreads), dim3(kBandThreads), band_lds, st,
-                       tb, cd, out, w.live_count, w.live_list, w.bands, caps_in_lds);
+    const int bt = band_threads(cd.S_max);
+    const size_t band_lds = size_t(tb.L + 1) * 16 + (caps_in_lds ? size_t(tb.G) * tb.n_tp * 8 : 0) +
+                            size_t(cd.S_max) * (bt + 2) * 2;
+    hipLaunchKernelGGL(k2_band, dim3((cd.C + bt - 1) / bt), dim3(bt), band_lds, st, tb, cd, w.counts,
+                       w.live_list, w.dead_list, w.bands, caps_in_lds);
     hipLaunchKernelGGL(k2_fast, dim3(n_groups), dim3(kFastThreads), fast_lds_bytes(tb.L, cd.S_max), st, tb,
-                       cd, out, w.live_count, w.live_list, w.bands, w.arg,
+                       cd, out, w.counts, w.live_list, w.dead_list, w.bands, w.arg,
                        fast_arg_per_group(tb.L, cd.S_max), fast_row_len(tb.L));
 }
 

@@ -42,10 +42,26 @@ __global__ __launch_bounds__(kArgminThreads) void k4_argmin(int32_t C, const int
     __shared__ int32_t idx_s[kArgminThreads / 64];
     int64_t best = kInf;
     int32_t bi = INT32_MAX;
-    for (int c = threadIdx.x; c < C; c += kArgminThreads) {
+    // eight independent loads per trip: one workgroup has to cover the whole batch, so the loop
+    // is bound by memory latency, not by arithmetic
+    constexpr int kUnroll = 8;
+    int c = threadIdx.x;
+    for (; c + (kUnroll - 1) * kArgminThreads < C; c += kUnroll * kArgminThreads) {
+        int32_t st[kUnroll];
+        int64_t v[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            st[u] = status[c + u * kArgminThreads];
+            v[u] = iter_time[c + u * kArgminThreads];
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u)     // c rises within a thread: first minimum kept
+            if (st[u] == HARP_CAND_OK && v[u] < best) { best = v[u]; bi = c + u * kArgminThreads; }
+    }
+    for (; c < C; c += kArgminThreads) {
         if (status[c] != HARP_CAND_OK) continue;
         const int64_t v = iter_time[c];
-        if (v < best) { best = v; bi = c; }     // c rises within a thread: first minimum kept
+        if (v < best) { best = v; bi = c; }
     }
     auto fold = [&](int64_t ov, int32_t oi) {
         if (ov < best || (ov == best && oi < bi)) { best = ov; bi = oi; }
