@@ -25,8 +25,9 @@ ALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
 # each counted as two 32-bit lane-operations
 LANE_OPS_PER_TRANSITION = 26
 # HBM bytes per launch of the planner kernel on the stress workload, from rocprofv3 counters
-# (profiles/k2_fast_stress_pmc.txt: FETCH_SIZE + WRITE_SIZE, each scaled by a plain copy's reading)
-MEASURED_TRAFFIC_BYTES = {"stress": 9.56e9 + 9.96e9}
+# (profiles/plan_batch_stress_pmc.txt: FETCH_SIZE + WRITE_SIZE of k2_band and k2_fast, each scaled by
+# a plain copy's reading)
+MEASURED_TRAFFIC_BYTES = {"stress": 4.005e9 + 1.790e9 + 0.249e9 + 0.344e9}
 
 
 def cpu_baseline(w, cands, gpu_plans, budget_candidates):
@@ -126,7 +127,8 @@ def main():
     best_i = torch.empty(1, dtype=torch.int32, device=ctx.device)
     path = {"auto": binding.PATH_AUTO, "generic": binding.PATH_GENERIC, "fast32": binding.PATH_FAST32}[args.path]
     ctx.set_plan_path(path)
-    kernel = "k2_fast" if (tables.fast32 and path != binding.PATH_GENERIC) else "k2_generic"
+    fast = tables.fast32 and path != binding.PATH_GENERIC
+    kernel = "k2_band + k2_fast (one harp_plan_batch call)" if fast else "k2_generic"
 
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
           for _ in range(args.steps)]
@@ -159,7 +161,7 @@ def main():
     kernel_ms = sum(a.elapsed_time(b) for a, b in ev) / args.steps
     got = out.to_host()
     achieved = n_trans * LANE_OPS_PER_TRANSITION / (kernel_ms * 1e-3)
-    traffic = MEASURED_TRAFFIC_BYTES.get(args.workload) if C == w.C and kernel == "k2_fast" else None
+    traffic = MEASURED_TRAFFIC_BYTES.get(args.workload) if C == w.C and fast else None
     result = {
         "metric": "candidate plans/sec (and DP cells/sec) on 1 MI355X",
         "value": C * args.steps / elapsed,
@@ -171,7 +173,7 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "int64" if kernel == "k2_generic" else "u32 times / int64 bytes",
+        "dtype": "u32 times / int64 bytes" if fast else "int64",
         "data": "synthetic",
         "config": {"workload": "%s: L=%d operators, %d candidates, S<=%d, M=%d, %d groups, %d GPU types"
                                % (w.name, w.problem.L, C, w.S_max, w.problem.M, w.problem.G, w.problem.T),
@@ -186,8 +188,9 @@ def main():
             "achieved": achieved / 1e12, "peak": ALU_PEAK_LANE_OPS / 1e12, "unit": "T int32 lane-op/s",
             "frac": achieved / ALU_PEAK_LANE_OPS, "traffic": traffic,
             "note": "achieved = dense-recurrence transitions per launch x 26 lane-ops / mean kernel time "
-                    "(HIP events on the launch stream); the kernel evaluates fewer transitions than the "
-                    "dense count (bounded scans), so this is work delivered, not instructions issued",
+                    "(HIP events on the launch stream around harp_plan_batch); the kernels evaluate far fewer "
+                    "transitions than the dense count (reachability bands, bounded scans), so this is work "
+                    "delivered, not instructions issued: VALU issue utilisation is 61% (profiles/)",
         },
     }
     if args.tables_L:
