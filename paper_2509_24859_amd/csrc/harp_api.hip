@@ -72,7 +72,7 @@ Layout make_layout(const harp_problem *p) {
     const size_t L1 = size_t(p->L) + 1;
     y.pitch = (int64_t)align_up(L1, 8);
     y.pitch32 = (int64_t)align_up(L1, 16);
-    y.n_chunks = (p->L + kScanChunk - 1) / kScanChunk;
+    y.n_chunks = (p->L + 255) / 256;     // scan scratch sized for the finest chunking (one wavefront)
     const size_t n_rows = size_t(p->T) + 2 + size_t(p->G) * p->n_tp;
     size_t off = 0;
     y.header = off; off += 256;

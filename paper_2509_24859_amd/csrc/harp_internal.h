@@ -75,6 +75,7 @@ struct BuildLimits {
 constexpr int kScanThreads = 256;
 constexpr int kScanItems = 4;
 constexpr int kScanChunk = kScanThreads * kScanItems;
+constexpr int kLongL = 1 << 18;        // from here on the table build runs chunk-major, 256 operators per wavefront
 
 void launch_build(const TablesDev &tb, const BuildLimits &lim, hipStream_t st);
 void launch_plan_generic(const TablesDev &tb, const CandDev &cd, const PlansDev &out, void *ws,

@@ -198,6 +198,232 @@ __global__ __launch_bounds__(kScanThreads) void k1_scan_rows(TablesDev tb, Build
     report(tb.header, bad, ovf, wave_act, src.track_act && lane == 0);
 }
 
+// ---------------------------------------------------------------------------------------------
+// Long sequences (L >= kLongL): the same three launches, but chunk-major.  One wavefront owns a
+// run of 256 operators and walks all table rows over it, so the act_bytes of the run are read,
+// checked and converted once for the G * n_tp all-reduce rows instead of once per row, no LDS and
+// no barrier is needed (chunk = wavefront), and the per-element all-reduce time is a handful of
+// double operations: for act < 2^32, multiplier < 2^20 and divisor < 2^52 the product is exact in
+// a double, floor(product * (1 / divisor)) is within 1 of the quotient, and one exact fused
+// multiply-add gives the remainder that corrects it.  What is left is the 8-byte store per table
+// entry, i.e. the HBM write stream.
+
+constexpr int kWaveItems = 4;
+constexpr int kWaveChunk = 64 * kWaveItems;
+
+struct ActRun {                 // one thread's operators of the run
+    int64_t x[kWaveItems];      // act_bytes, 0 beyond L or when rejected
+    double xd[kWaveItems];      // the same as doubles when all are below 2^32
+    bool narrow;                // every x below 2^32
+};
+
+__device__ __forceinline__ ActRun load_act_run(const TablesDev &tb, const BuildLimits &lim, int64_t base,
+                                               unsigned int &bad, unsigned int &ovf,
+                                               unsigned long long &act_seen) {
+    ActRun a;
+    a.narrow = true;
+#pragma unroll
+    for (int q = 0; q < kWaveItems; ++q) {
+        int64_t x = (base + q < tb.L) ? tb.act_bytes[base + q] : 0;
+        if (x < 0) { bad = 1; x = 0; }
+        if ((unsigned long long)x > act_seen) act_seen = (unsigned long long)x;
+        if (x > lim.act_max || x > lim.elem_max) { ovf = 1; x = 0; }
+        a.x[q] = x;
+        a.narrow = a.narrow && x < (int64_t(1) << 32);
+        a.xd[q] = (double)(uint32_t)x;
+    }
+    return a;
+}
+
+struct ArRow {                  // constants of one all-reduce row
+    int64_t mul, den;
+    double mul_d, den_d, inv;
+    bool fast;                  // multiplier < 2^20 and divisor < 2^52
+};
+
+__device__ __forceinline__ ArRow ar_row(const RowSource &s) {
+    ArRow r;
+    r.mul = s.num_mul; r.den = s.den; r.inv = s.inv_den;
+    r.mul_d = (double)s.num_mul; r.den_d = (double)s.den;
+    r.fast = s.num_mul < (int64_t(1) << 20) && s.den < kFastDivLimit;
+    return r;
+}
+
+__device__ __forceinline__ int64_t ar_value(const ArRow &r, const ActRun &a, int q, const BuildLimits &lim,
+                                            unsigned int &ovf) {
+    if (r.mul == 0) return 0;
+    int64_t v;
+    if (r.fast && a.narrow) {
+        const double prod = a.xd[q] * r.mul_d;            // exact: below 2^52
+        double quo = floor(prod * r.inv);
+        double rem = fma(-quo, r.den_d, prod);            // exact: |rem| < 2 den
+        if (rem < 0.0) { quo -= 1.0; rem += r.den_d; }
+        else if (rem >= r.den_d) { quo += 1.0; rem -= r.den_d; }
+        v = (int64_t)(quo + (rem > 0.0 ? 1.0 : 0.0));
+    } else {
+        v = ceil_div_inv(r.mul * a.x[q], r.den, r.inv);
+    }
+    if (v > lim.elem_max) { ovf = 1; v = 0; }
+    return v;
+}
+
+// The common case of an all-reduce row, all four values at once: narrow operands (see ar_row), a
+// divisor not below the multiplier (so the quotient stays below 2^32) and an element bound of at
+// least 2^32 (so no value can trip it).  ceil(p / d) = floor((p + d - 1) / d); the sum p + d - 1 is
+// exact in a double, the product with 1 / d is within 1 of the quotient, and the exact remainder
+// from one fused multiply-add corrects it.
+__device__ __forceinline__ bool ar_tight(const ArRow &r, bool all_narrow, const BuildLimits &lim) {
+    return r.fast && all_narrow && r.den >= r.mul && lim.elem_max >= (int64_t(1) << 32);
+}
+
+__device__ __forceinline__ void ar_values_tight(const ArRow &r, const ActRun &a, uint32_t v[kWaveItems]) {
+    const double bias = r.den_d - 1.0;
+#pragma unroll
+    for (int q = 0; q < kWaveItems; ++q) {
+        const double num = fma(a.xd[q], r.mul_d, bias);   // exact: below 2^53
+        double quo = floor(num * r.inv);
+        const double rem = fma(-quo, r.den_d, num);       // exact
+        quo += rem < 0.0 ? -1.0 : (rem >= r.den_d ? 1.0 : 0.0);
+        v[q] = r.mul == 0 ? 0u : (uint32_t)quo;
+    }
+}
+
+// value q of row r for this thread: all-reduce rows from the staged run, the others from memory
+__device__ __forceinline__ int64_t long_value(const TablesDev &tb, const RowSource &src, const ArRow &arr,
+                                              const ActRun &a, int q, int64_t base, const BuildLimits &lim,
+                                              unsigned int &bad, unsigned int &ovf) {
+    if (base + q >= tb.L) return 0;
+    if (src.is_ar) return ar_value(arr, a, q, lim, ovf);
+    unsigned long long unused = 0;
+    return row_value(src, base + q, lim, bad, ovf, unused);
+}
+
+// Row constants of every table row, worked out once per workgroup (each needs a link bandwidth
+// from memory and a reciprocal) and kept in LDS for the walk over the rows.
+struct LongRow {
+    RowSource src;
+    ArRow arr;
+};
+constexpr int kLongRowsInLds = 512;
+
+__device__ __forceinline__ void stage_long_rows(const TablesDev &tb, LongRow *rows_lds, int n_rows) {
+    if (n_rows <= kLongRowsInLds) {
+        for (int r = threadIdx.x; r < n_rows; r += blockDim.x) {
+            rows_lds[r].src = row_source(tb, r);
+            rows_lds[r].arr = ar_row(rows_lds[r].src);
+        }
+    }
+    __syncthreads();
+}
+
+__device__ __forceinline__ LongRow long_row(const TablesDev &tb, const LongRow *rows_lds, int n_rows, int r) {
+    if (n_rows <= kLongRowsInLds) return rows_lds[r];
+    LongRow lr;
+    lr.src = row_source(tb, r);
+    lr.arr = ar_row(lr.src);
+    return lr;
+}
+
+// Launch 1 for long sequences: sum of every (row, run of 256 operators).
+__global__ __launch_bounds__(kScanThreads) void k1_long_sums(TablesDev tb, BuildLimits lim, int n_runs) {
+    __shared__ LongRow rows_lds[kLongRowsInLds];
+    const int n_rows = tb.n_rows();
+    stage_long_rows(tb, rows_lds, n_rows);
+    const int lane = threadIdx.x & 63;
+    const int run = blockIdx.x * (kScanThreads / 64) + (threadIdx.x >> 6);
+    if (run >= n_runs) return;
+    const int64_t base = int64_t(run) * kWaveChunk + int64_t(lane) * kWaveItems;
+    unsigned int bad = 0, ovf = 0;
+    unsigned long long act_seen = 0;
+    const ActRun a = load_act_run(tb, lim, base, bad, ovf, act_seen);
+    const bool all_narrow = __all(a.narrow);
+    // the rows are split over gridDim.y workgroups so that enough wavefronts are in flight
+    const int r_begin = int(int64_t(n_rows) * blockIdx.y / gridDim.y);
+    const int r_end = int(int64_t(n_rows) * (blockIdx.y + 1) / gridDim.y);
+    for (int r = r_begin; r < r_end; ++r) {
+        const LongRow lr = long_row(tb, rows_lds, n_rows, r);
+        const RowSource &src = lr.src;
+        const ArRow &arr = lr.arr;
+        int64_t sum = 0;
+        if (src.is_ar && ar_tight(arr, all_narrow, lim)) {
+            uint32_t v[kWaveItems];
+            ar_values_tight(arr, a, v);
+#pragma unroll
+            for (int q = 0; q < kWaveItems; ++q) sum += v[q];
+        } else {
+#pragma unroll
+            for (int q = 0; q < kWaveItems; ++q) sum += long_value(tb, src, arr, a, q, base, lim, bad, ovf);
+        }
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) sum += __shfl_xor(sum, d, 64);
+        if (lane == 0) tb.chunk_sums[int64_t(r) * n_runs + run] = sum;
+    }
+    // values are checked again by the scan launch; nothing to report here
+}
+
+// Launch 3 for long sequences: scan every (row, run), add the run's offset, write the table rows.
+__global__ __launch_bounds__(kScanThreads) void k1_long_scan(TablesDev tb, BuildLimits lim, int n_runs) {
+    __shared__ LongRow rows_lds[kLongRowsInLds];
+    const int n_rows = tb.n_rows();
+    stage_long_rows(tb, rows_lds, n_rows);
+    __shared__ int64_t tiles[kScanThreads / 64][kWaveChunk];
+    const int lane = threadIdx.x & 63;
+    const int run = blockIdx.x * (kScanThreads / 64) + (threadIdx.x >> 6);
+    if (run >= n_runs) return;
+    int64_t *tile = tiles[threadIdx.x >> 6];
+    const int64_t base = int64_t(run) * kWaveChunk + int64_t(lane) * kWaveItems;
+    unsigned int bad = 0, ovf = 0;
+    unsigned long long act_seen = 0;
+    const ActRun a = load_act_run(tb, lim, base, bad, ovf, act_seen);
+    const bool all_narrow = __all(a.narrow);
+    // the rows are split over gridDim.y workgroups so that enough wavefronts are in flight
+    const int r_begin = int(int64_t(n_rows) * blockIdx.y / gridDim.y);
+    const int r_end = int(int64_t(n_rows) * (blockIdx.y + 1) / gridDim.y);
+    for (int r = r_begin; r < r_end; ++r) {
+        const LongRow lr = long_row(tb, rows_lds, n_rows, r);
+        const RowSource &src = lr.src;
+        const ArRow &arr = lr.arr;
+        int64_t v[kWaveItems];
+        int64_t sum = 0;
+        if (src.is_ar && ar_tight(arr, all_narrow, lim)) {
+            uint32_t v32[kWaveItems];
+            ar_values_tight(arr, a, v32);
+#pragma unroll
+            for (int q = 0; q < kWaveItems; ++q) { v[q] = v32[q]; sum += v32[q]; }
+        } else {
+#pragma unroll
+            for (int q = 0; q < kWaveItems; ++q) {
+                v[q] = long_value(tb, src, arr, a, q, base, lim, bad, ovf);
+                sum += v[q];
+            }
+        }
+        const int64_t inc = wave_inclusive_scan(sum, lane);
+        int64_t acc = tb.chunk_sums[int64_t(r) * n_runs + run] + inc - sum;
+        int64_t *out = tb.rows + int64_t(r) * tb.pitch;
+        if (run == 0 && lane == 0) out[0] = 0;
+        // a lane holds four consecutive entries; passing them through the wavefront's LDS tile
+        // turns four 8-byte stores at a 32-byte stride into four fully contiguous 512-byte stores
+#pragma unroll
+        for (int q = 0; q < kWaveItems; ++q) {
+            acc += v[q];
+            tile[lane * kWaveItems + q] = acc;
+        }
+        const int64_t first = int64_t(run) * kWaveChunk;
+#pragma unroll
+        for (int q = 0; q < kWaveItems; ++q) {
+            const int e = q * 64 + lane;
+            const int64_t val = tile[e];
+            if (first + e < tb.L) out[first + e + 1] = val;
+        }
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        const unsigned long long o = __shfl_xor(act_seen, d, 64);
+        act_seen = o > act_seen ? o : act_seen;
+    }
+    report(tb.header, bad, ovf, act_seen, lane == 0 && blockIdx.y == 0);
+}
+
 // Launch 4 (one workgroup): checks of the small arrays, device numbering of the groups, the
 // magnitude verdict, and whether the 32-bit fast path may be used.
 __global__ __launch_bounds__(256) void k1_finalize(TablesDev tb, BuildLimits lim) {
@@ -309,6 +535,16 @@ void launch_build(const TablesDev &tb, const BuildLimits &lim, hipStream_t st) {
     const int n_chunks = (tb.L + kScanChunk - 1) / kScanChunk;
     const int n_rows = tb.n_rows();
     hipLaunchKernelGGL(k1_clear_header, dim3(1), dim3(64), 0, st, tb.header);
+    if (tb.L >= kLongL) {
+        const int n_runs = (tb.L + kWaveChunk - 1) / kWaveChunk;
+        const int groups = (n_runs + kScanThreads / 64 - 1) / (kScanThreads / 64);
+        const int row_parts = n_rows >= 32 ? 4 : 1;
+        hipLaunchKernelGGL(k1_long_sums, dim3(groups, row_parts), dim3(kScanThreads), 0, st, tb, lim, n_runs);
+        hipLaunchKernelGGL(k1_scan_chunk_sums, dim3(n_rows), dim3(kScanThreads), 0, st, tb, n_runs);
+        hipLaunchKernelGGL(k1_long_scan, dim3(groups, row_parts), dim3(kScanThreads), 0, st, tb, lim, n_runs);
+        hipLaunchKernelGGL(k1_finalize, dim3(1), dim3(256), 0, st, tb, lim);
+        return;                   // sequences this long are beyond the 32-bit planner path
+    }
     if (n_chunks > 1) {
         hipLaunchKernelGGL(k1_chunk_sums, dim3(n_rows, n_chunks), dim3(kScanThreads), 0, st, tb, lim, n_chunks);
         hipLaunchKernelGGL(k1_scan_chunk_sums, dim3(n_rows), dim3(kScanThreads), 0, st, tb, n_chunks);

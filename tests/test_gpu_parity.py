@@ -79,8 +79,14 @@ def test_tables_match_oracle_long_rows(harp, ctx):
 
 def test_tables_match_oracle_operator_level(harp, ctx):
     """The long-sequence problem of the streaming measurement at a length the oracle finishes in
-    seconds: 200,001 operators = 195 full scan chunks and a ragged tail, 138 rows."""
-    p = W.long_sequence(200001)
+    seconds: 300,001 operators = 1,171 full wavefront runs and a ragged tail, 138 rows, built by
+    the chunk-major kernels; and 100,003 operators, built by the row-parallel ones."""
+    for L in (300001, 100003):
+        _check_operator_level(harp, ctx, L)
+
+
+def _check_operator_level(harp, ctx, L):
+    p = W.long_sequence(L)
     want = oracle.build_tables(p)
     tables = harp.Tables(ctx, p)
     PF, PP, PS, PR = tables.host_copies()
