@@ -49,7 +49,7 @@ def _load():
     if _lib is None:
         _lib = C.CDLL(build())
         for name in ("oracle_build_tables", "oracle_plan_batch", "oracle_score_1f1b",
-                     "oracle_argmin_batch"):
+                     "oracle_argmin_batch", "oracle_plan_exact_batch"):
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -119,6 +119,25 @@ def plan_batch(tables: Tables, cands, c_begin: int = 0, c_end: int | None = None
         _ptr(out.bottleneck), _ptr(out.iter_time), _ptr(out.status))
     if rc != 0:
         raise ValueError("oracle_plan_batch failed with code %d" % rc)
+    return out
+
+
+def plan_exact_batch(tables: Tables, cands, c_begin: int = 0, c_end: int | None = None,
+                     out: Plans | None = None) -> Plans:
+    """Exact optimum of the iteration-time model per candidate (cap sweep); `out.n_caps` counts the
+    caps swept."""
+    c_end = cands.C if c_end is None else c_end
+    out = Plans(cands.C, cands.S_max) if out is None else out
+    if not hasattr(out, "n_caps"):
+        out.n_caps = np.zeros(cands.C, dtype=np.int32)
+    cs, cg, ct = _c32(cands.cand_S), _c32(cands.cand_group), _c32(cands.cand_tp)
+    rc = _load().oracle_plan_exact_batch(
+        C.byref(tables.c), _ptr(tables.PF), _ptr(tables.PP), _ptr(tables.PS), _ptr(tables.PR),
+        C.c_int32(cands.C), C.c_int32(cands.S_max), _ptr(cs), _ptr(cg), _ptr(ct),
+        C.c_int32(c_begin), C.c_int32(c_end), _ptr(out.splits), _ptr(out.dev_first),
+        _ptr(out.bottleneck), _ptr(out.iter_time), _ptr(out.status), _ptr(out.n_caps))
+    if rc != 0:
+        raise ValueError("oracle_plan_exact_batch failed with code %d" % rc)
     return out
 
 

@@ -141,3 +141,72 @@ def best_iteration_time(p, S: int, S_max: int, grp, tp):
             continue
         best = min(best, score(p, S, grp, tp, b)[1])
     return best
+
+
+def _stage_terms(p, S, grp, tp, s, j, i):
+    """(fits, stage time, transfer time) of stage s over [j, i)."""
+    n = min(S - s, int(p.M))
+    fits = memory_fits(p, int(grp[s]), int(tp[s]), n, j, i)
+    t = stage_time(p, int(grp[s]), int(tp[s]), j, i)
+    c = 0 if s == S - 1 else cut_time(p, int(grp[s]), int(grp[s + 1]), i)
+    return fits, t, c
+
+
+def opt_sum(p, S, grp, tp, s, i, cap):
+    """Smallest sum of (t + 2c) over the first i operators on slots 0..s-1 with every stage
+    fitting and every stage and transfer time at most cap, by enumeration."""
+    if s == 0:
+        return 0 if i == 0 else INF
+    if i < s:
+        return INF
+    best = INF
+    for b in partitions(i, s):
+        total = 0
+        for q in range(s):
+            fits, t, c = _stage_terms(p, S, grp, tp, q, b[q], b[q + 1])
+            if not fits or t > cap or c > cap:
+                total = INF
+                break
+            total += t + 2 * c
+        best = min(best, total)
+    return best
+
+
+def plan_exact(p, S: int, S_max: int, grp, tp):
+    """Status, cuts, winning cap, optimum of the iteration-time model (section 5.2.2-5.2.4).
+
+    The optimum is taken over every feasible partition; among the partitions attaining it the
+    reported one has the smallest bottleneck b*, and under the cap b* the cuts are fixed from the
+    back: b_s is the smallest j for which the best capped sum of the first j operators on s slots
+    plus stage s over [j, b_{s+1}) attains the best capped sum of the first b_{s+1} operators."""
+    L = int(p.L)
+    if not valid(p, S, S_max, grp, tp):
+        return 2, None, INF, INF
+    best_T, best_b = INF, INF
+    if S <= L:
+        for b in partitions(L, S):
+            if any(stage_cost(p, S, grp, tp, s, b[s], b[s + 1]) == INF for s in range(S)):
+                continue
+            bott, T = score(p, S, grp, tp, b)
+            if T < best_T or (T == best_T and bott < best_b):
+                best_T, best_b = T, bott
+    if best_T == INF:
+        return 1, None, INF, INF
+    cap = best_b
+    cuts = [0] * (S + 1)
+    cuts[S] = L
+    for s in range(S - 1, -1, -1):
+        target = opt_sum(p, S, grp, tp, s + 1, cuts[s + 1], cap)
+        for j in range(s, cuts[s + 1]):
+            left = opt_sum(p, S, grp, tp, s, j, cap)
+            fits, t, c = _stage_terms(p, S, grp, tp, s, j, cuts[s + 1])
+            if left == INF or not fits or t > cap or c > cap:
+                continue
+            if left + t + 2 * c == target:
+                cuts[s] = j
+                break
+        else:
+            raise AssertionError("no predecessor attains the capped optimum")
+    bott, T = score(p, S, grp, tp, cuts)
+    assert T == best_T and bott == cap
+    return 0, cuts, cap, best_T

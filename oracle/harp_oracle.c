@@ -347,3 +347,136 @@ int oracle_argmin_batch(int32_t C, const int64_t *iter_time, const int32_t *stat
         if (status[c] == CAND_OK && iter_time[c] < *best_time) { *best_time = iter_time[c]; *best_index = c; }
     return ORACLE_OK;
 }
+
+/* ------------------------------------------------------------------------------------------
+ * Exact optimum of the cost model for one candidate: the search of section 5.2.3 / 5.2.4 (2).
+ *
+ * For a fixed cap t_max the DP of eq. dp_general minimises the first term of eq.
+ * gpipe_cost_model, sum_s (t_s + 2 c_s), over partitions whose every stage obeys (i) t_s <= t_max,
+ * (ii) c_s <= t_max and (iii) eq. mem_cons; the latency under that cap is
+ *   T(t_max) = F(S, L; t_max) + (B - 1) t_max,
+ * and the answer is the minimum of T over the candidate caps.  Candidate caps are the distinct
+ * stage costs max(t, c) of fitting stages; those below the smallest feasible cap t_S (the min-max
+ * bottleneck) admit no plan, and those above t_E = ceil(T(t_S) / B) cannot win (section 5.2.4 (2)),
+ * so the sweep runs over the caps in [t_S, t_E] in increasing order.  The first cap that attains
+ * the minimum is kept (strict comparison), and inside a DP the lowest previous cut wins ties.
+ */
+
+static int cmp_i64(const void *a, const void *b)
+{
+    int64_t x = *(const int64_t *)a, y = *(const int64_t *)b;
+    return x < y ? -1 : (x > y ? 1 : 0);
+}
+
+/* capped DP; returns F(S, L) or INF and fills splits with the plan's cuts */
+static int64_t capped_min_sum(const tables_view *v, int S, const int32_t *grp, const int32_t *tp,
+                              int64_t cap, int64_t *F_prev, int64_t *F_next, int32_t *arg, int32_t *splits)
+{
+    const oracle_problem *p = v->p;
+    const int L = p->L;
+    for (int i = 0; i <= L; ++i) F_prev[i] = ORACLE_INF;
+    F_prev[0] = 0;
+    for (int s = 0; s < S; ++s) {
+        const int64_t n = (S - s) < p->M ? (S - s) : p->M;
+        int32_t *arg_row = arg + (size_t)(s + 1) * (L + 1);
+        for (int i = 0; i <= L; ++i) { F_next[i] = ORACLE_INF; arg_row[i] = -1; }
+        for (int i = s + 1; i <= L - (S - 1 - s); ++i) {
+            if (s == S - 1 && i != L) continue;
+            const int64_t c = (s == S - 1) ? 0 : cut_time(p, grp[s], grp[s + 1], i);
+            if (c > cap) continue;                                    /* constraint (ii) */
+            int64_t best = ORACLE_INF;
+            int32_t best_j = -1;
+            for (int j = s; j < i; ++j) {
+                if (F_prev[j] == ORACLE_INF) continue;
+                if (!memory_fits(v, grp[s], tp[s], n, j, i)) continue; /* constraint (iii) */
+                const int64_t t = stage_time(v, grp[s], tp[s], j, i);
+                if (t > cap) continue;                                /* constraint (i) */
+                const int64_t val = F_prev[j] + t + 2 * c;
+                if (val < best) { best = val; best_j = j; }
+            }
+            F_next[i] = best;
+            arg_row[i] = best_j;
+        }
+        int64_t *tmp = F_prev; F_prev = F_next; F_next = tmp;
+    }
+    if (F_prev[L] == ORACLE_INF) return ORACLE_INF;
+    splits[S] = L;
+    for (int s = S - 1; s >= 0; --s)
+        splits[s] = arg[(size_t)(s + 1) * (L + 1) + splits[s + 1]];
+    return F_prev[L];
+}
+
+/* Exact search for candidates c_begin..c_end-1.  Outputs as oracle_plan_batch, with bottleneck =
+ * the winning cap (which is the plan's own largest stage cost) and iter_time = the optimum of eq.
+ * gpipe_cost_model; n_caps[c] = number of caps swept. */
+int oracle_plan_exact_batch(const oracle_problem *p, const int64_t *PF, const int64_t *PP, const int64_t *PS,
+                            const int64_t *PR, int32_t C, int32_t S_max, const int32_t *cand_S,
+                            const int32_t *cand_group, const int32_t *cand_tp, int32_t c_begin, int32_t c_end,
+                            int32_t *splits, int32_t *dev_first, int64_t *bottleneck, int64_t *iter_time,
+                            int32_t *status, int32_t *n_caps)
+{
+    if (C < 0 || S_max < 1 || c_begin < 0 || c_end > C || c_begin > c_end) return ORACLE_BAD_ARG;
+    if (p->L > 65535) return ORACLE_BAD_ARG;
+    const int L = p->L;
+    tables_view v = { p, PF, PP, PS, PR };
+    int64_t *D0 = (int64_t *)malloc(sizeof(int64_t) * (size_t)(L + 1));
+    int64_t *D1 = (int64_t *)malloc(sizeof(int64_t) * (size_t)(L + 1));
+    int32_t *arg = (int32_t *)malloc(sizeof(int32_t) * (size_t)(S_max + 1) * (size_t)(L + 1));
+    int32_t *trial = (int32_t *)malloc(sizeof(int32_t) * (size_t)(S_max + 1));
+    size_t caps_room = 1024;
+    int64_t *caps = (int64_t *)malloc(sizeof(int64_t) * caps_room);
+    if (!D0 || !D1 || !arg || !trial || !caps) return ORACLE_BAD_ARG;
+    for (int32_t c = c_begin; c < c_end; ++c) {
+        const int S = cand_S[c];
+        const int32_t *grp = cand_group + (size_t)c * S_max, *tp = cand_tp + (size_t)c * S_max;
+        int32_t *sp = splits + (size_t)c * (S_max + 1);
+        n_caps[c] = 0;
+        /* smallest feasible cap t_S and the latency of its plan: the min-max search above */
+        status[c] = plan_one(&v, S, S_max, grp, tp, D0, D1, arg, sp, dev_first + (size_t)c * S_max,
+                             bottleneck + c, iter_time + c);
+        if (status[c] != CAND_OK) continue;
+        const int64_t t_S = bottleneck[c];
+        const int64_t t_E = ceil_div(iter_time[c], p->M);
+        /* candidate caps: distinct costs of fitting stages inside [t_S, t_E] */
+        size_t n = 0;
+        for (int s = 0; s < S; ++s) {
+            const int64_t nin = (S - s) < p->M ? (S - s) : p->M;
+            for (int i = s + 1; i <= L - (S - 1 - s); ++i) {
+                if (s == S - 1 && i != L) continue;
+                const int64_t cc = (s == S - 1) ? 0 : cut_time(p, grp[s], grp[s + 1], i);
+                for (int j = s; j < i; ++j) {
+                    if (!memory_fits(&v, grp[s], tp[s], nin, j, i)) continue;
+                    const int64_t w = max64(stage_time(&v, grp[s], tp[s], j, i), cc);
+                    if (w < t_S || w > t_E) continue;
+                    if (n == caps_room) {
+                        caps_room *= 2;
+                        caps = (int64_t *)realloc(caps, sizeof(int64_t) * caps_room);
+                        if (!caps) return ORACLE_BAD_ARG;
+                    }
+                    caps[n++] = w;
+                }
+            }
+        }
+        qsort(caps, n, sizeof(int64_t), cmp_i64);
+        int64_t best_T = ORACLE_INF, best_cap = ORACLE_INF;
+        for (size_t q = 0; q < n; ++q) {
+            if (q > 0 && caps[q] == caps[q - 1]) continue;
+            n_caps[c] += 1;
+            const int64_t F = capped_min_sum(&v, S, grp, tp, caps[q], D0, D1, arg, trial);
+            if (F == ORACLE_INF) continue;
+            const int64_t T = F + (int64_t)(p->M - 1) * caps[q];
+            if (T < best_T) {
+                best_T = T;
+                best_cap = caps[q];
+                for (int s = 0; s <= S; ++s) sp[s] = trial[s];
+            }
+        }
+        if (best_T == ORACLE_INF) abort();          /* t_S itself is a cap and is feasible */
+        int64_t b, t;
+        if (score_partition(&v, S, grp, tp, sp, &b, &t) != CAND_OK || b != best_cap || t != best_T) abort();
+        bottleneck[c] = best_cap;
+        iter_time[c] = best_T;
+    }
+    free(D0); free(D1); free(arg); free(trial); free(caps);
+    return ORACLE_OK;
+}

@@ -414,6 +414,89 @@ def test_magnitude_guard():
     assert oracle.Tables(p).rc == oracle.ERR_BAD_ARG
 
 
+# ---------------------------------------------------------------- exact optimum (cap sweep)
+
+def plan_exact(problem, cands):
+    return oracle.plan_exact_batch(oracle.build_tables(problem), cands)
+
+
+def test_exact_hand_examples():
+    for row in read_golden(os.path.join(GOLD, "hand_examples_exact.txt")):
+        M, splits, cap, T = [f.strip() for f in row.split("|")]
+        p = simple_problem([6, 2, 2, 6], M=int(M), G=2, ndev=(1, 1), act=[0, 5, 0, 0],
+                           bw=[[1000, 1], [1, 1000]])
+        cands = cands_from_lists([[(0, 1), (1, 1)]])
+        out = plan_exact(p, cands)
+        assert list(out.splits[0]) == [int(x) for x in splits.split()]
+        assert out.bottleneck[0] == int(cap) and out.iter_time[0] == int(T)
+        assert list(plan(p, cands).splits[0]) == [0, 2, 4]      # the min-max plan
+
+
+def test_exact_matches_exhaustive_enumeration():
+    n = 0
+    for seed in range(700):
+        w = W.random_small(seed, L_max=9, S_cap=4)
+        cands = w.candidates()
+        out = plan_exact(w.problem, cands)
+        for c in range(cands.C):
+            S = int(cands.cand_S[c])
+            st, cuts, cap, T = brute.plan_exact(w.problem, S, cands.S_max, cands.cand_group[c],
+                                                cands.cand_tp[c])
+            assert st == out.status[c], (seed, c)
+            if st == oracle.OK:
+                n += 1
+                assert list(out.splits[c, :S + 1]) == cuts, (seed, c)
+                assert out.bottleneck[c] == cap and out.iter_time[c] == T, (seed, c)
+                assert T == brute.best_iteration_time(w.problem, S, cands.S_max, cands.cand_group[c],
+                                                      cands.cand_tp[c])
+            else:
+                assert (out.splits[c] == -1).all() and out.iter_time[c] == oracle.INF
+    assert n > 3000
+    w = W.make("tiny")
+    cands = w.candidates()
+    out = plan_exact(w.problem, cands)
+    for c in range(cands.C):
+        S = int(cands.cand_S[c])
+        st, cuts, cap, T = brute.plan_exact(w.problem, S, cands.S_max, cands.cand_group[c], cands.cand_tp[c])
+        assert (st, list(out.splits[c, :S + 1]), out.bottleneck[c], out.iter_time[c]) == (0, cuts, cap, T)
+
+
+def test_exact_uniform_closed_form_and_relation_to_min_max():
+    # uniform operators, no transfers: every plan has the same sum, so the optimum is the min-max one
+    for L, S, a, M in ((12, 4, 5, 8), (10, 4, 3, 2), (7, 3, 11, 1)):
+        p = simple_problem([a] * L, M=M, ndev=(S,))
+        cands = cands_from_lists([same_slot(S)])
+        out = plan_exact(p, cands)
+        big = math.ceil(L / S) * a
+        assert out.bottleneck[0] == big and out.iter_time[0] == L * a + (M - 1) * big
+    for name, n in (("llama7b", 128), ("llama70b", 48)):
+        w = W.make(name)
+        cands = w.candidates(0, n)
+        tables = oracle.build_tables(w.problem)
+        a, e = oracle.plan_batch(tables, cands), oracle.plan_exact_batch(tables, cands)
+        ok = a.status == oracle.OK
+        assert (e.status == a.status).all() and ok.any()
+        assert (e.iter_time[ok] <= a.iter_time[ok]).all() and (e.bottleneck[ok] >= a.bottleneck[ok]).all()
+        assert (e.n_caps[ok] >= 1).all()
+        b, t, st = oracle.score_1f1b(tables, cands, e.splits)
+        assert (b[ok] == e.bottleneck[ok]).all() and (t[ok] == e.iter_time[ok]).all()
+
+
+def test_exact_iteration_time_monotone_as_memory_shrinks():
+    for seed in range(60):
+        w = W.random_small(seed, L_max=9, S_cap=4)
+        p = w.problem
+        cands = w.candidates()
+        start = p.type_mem_bytes.copy()
+        prev = None
+        for step in range(5):
+            p.type_mem_bytes[:] = start * (5 - step) // 5
+            out = plan_exact(p, cands)
+            if prev is not None:
+                assert (out.iter_time >= prev.iter_time).all()
+            prev = out
+
+
 # ---------------------------------------------------------------- the workloads themselves
 
 def test_workload_shapes_and_determinism():
