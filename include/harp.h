@@ -183,6 +183,22 @@ int harp_plan_batch(harp_ctx *ctx, harp_tables *tables, const harp_candidates *c
                     const harp_plans *out, void *workspace, size_t workspace_bytes,
                     void *hip_stream);
 
+/* The exact optimum of eq. gpipe_cost_model per candidate: the sweep over the stage-time cap t_max
+ * of section 5.2.4 (2), between t_S (the smallest feasible cap, found by the min-max search of
+ * harp_plan_batch, which this call runs first) and t_E = ceil(T(t_S) / B), with the capped
+ * least-sum recurrence of section 5.2.3 at each cap.  Outputs as for harp_plan_batch, except that
+ * splits is the partition of least iteration time (ties: the smaller bottleneck, then the lowest
+ * previous cut at every stage of the capped recurrence), bottleneck its largest stage or transfer
+ * time and iter_time its iteration time; statuses are those of harp_plan_batch.
+ * n_passes: DEVICE [C] or NULL; receives the number of capped recurrences run for the candidate
+ * (0 when it has no plan or a single stage).
+ * Needs tables that allow the 32-bit path (harp_tables_fast32), else HARP_ERR_UNIMPLEMENTED;
+ * workspace as for harp_plan_batch.  Asynchronous on `hip_stream`, except that the first use of a view
+ * finalizes it. */
+int harp_plan_exact_batch(harp_ctx *ctx, harp_tables *tables, const harp_candidates *cands,
+                          const harp_plans *out, int32_t *n_passes, void *workspace,
+                          size_t workspace_bytes, void *hip_stream);
+
 /* Scores caller-chosen partitions with eq. gpipe_cost_model (section 5.2.2):
  * splits DEVICE [C][S_max+1].  Status HARP_CAND_INVALID when the candidate is malformed or its
  * cuts are not strictly increasing from 0 to L; HARP_CAND_INFEASIBLE when a stage does not fit

@@ -24,8 +24,8 @@ EXPORTS = (
     "harp_create", "harp_destroy", "harp_last_error", "harp_tables_bytes",
     "harp_build_segment_costs", "harp_tables_finalize", "harp_tables_fast32", "harp_tables_pf",
     "harp_tables_pp", "harp_tables_ps", "harp_tables_pr", "harp_tables_release",
-    "harp_set_plan_path", "harp_plan_workspace_bytes", "harp_plan_batch", "harp_score_1f1b",
-    "harp_argmin_batch",
+    "harp_set_plan_path", "harp_plan_workspace_bytes", "harp_plan_batch", "harp_plan_exact_batch",
+    "harp_score_1f1b", "harp_argmin_batch",
 )
 
 
@@ -89,6 +89,7 @@ def load_library() -> C.CDLL:
     lib.harp_plan_workspace_bytes.argtypes = [vp, vp, C.POINTER(harp_candidates)]
     lib.harp_plan_workspace_bytes.restype = sz
     lib.harp_plan_batch.argtypes = [vp, vp, C.POINTER(harp_candidates), C.POINTER(harp_plans), vp, sz, vp]
+    lib.harp_plan_exact_batch.argtypes = [vp, vp, C.POINTER(harp_candidates), C.POINTER(harp_plans), vp, vp, sz, vp]
     lib.harp_score_1f1b.argtypes = [vp, vp, C.POINTER(harp_candidates), vp, vp, vp, vp, vp]
     lib.harp_argmin_batch.argtypes = [vp, i32, vp, vp, vp, vp, vp]
     _lib = lib
@@ -294,6 +295,13 @@ def harp_plan_batch(ctx: Context, tables: Tables, dc: DeviceCandidates, out: Dev
                                       workspace.data_ptr(), workspace.numel(), _stream_handle(stream)))
 
 
+def harp_plan_exact_batch(ctx: Context, tables: Tables, dc: DeviceCandidates, out: DevicePlans,
+                          workspace, n_passes=None, stream=None):
+    ctx.check(ctx.lib.harp_plan_exact_batch(ctx.handle, tables.handle, C.byref(dc.c), C.byref(out.c),
+                                            n_passes.data_ptr() if n_passes is not None else None,
+                                            workspace.data_ptr(), workspace.numel(), _stream_handle(stream)))
+
+
 def harp_score_1f1b(ctx: Context, tables: Tables, dc: DeviceCandidates, splits, bottleneck,
                     iter_time, status, stream=None):
     ctx.check(ctx.lib.harp_score_1f1b(ctx.handle, tables.handle, C.byref(dc.c), splits.data_ptr(),
@@ -326,3 +334,18 @@ def plan(ctx: Context, problem, cands, path: int = PATH_AUTO):
     finally:
         ctx.set_plan_path(PATH_AUTO)
     return out.to_host(), tables
+
+
+def plan_exact(ctx: Context, problem, cands):
+    """Convenience for tests: tables, exact search over a batch; host copies of the plans and of
+    the number of capped passes per candidate."""
+    torch = _torch()
+    tables = Tables(ctx, problem)
+    dc = DeviceCandidates(ctx, cands)
+    out = DevicePlans(ctx, dc.C, dc.S_max)
+    out.poison()
+    ws = plan_workspace(ctx, tables, dc)
+    n_passes = torch.full((max(dc.C, 1),), -7, dtype=torch.int32, device=ctx.device)
+    harp_plan_exact_batch(ctx, tables, dc, out, ws, n_passes)
+    torch.cuda.synchronize()
+    return out.to_host(), n_passes[:dc.C].cpu().numpy(), tables

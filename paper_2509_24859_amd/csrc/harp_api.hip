@@ -311,6 +311,32 @@ int harp_plan_batch(harp_ctx *ctx, harp_tables *t, const harp_candidates *cd, co
     return HARP_OK;
 }
 
+int harp_plan_exact_batch(harp_ctx *ctx, harp_tables *t, const harp_candidates *cd, const harp_plans *out,
+                          int32_t *n_passes, void *workspace, size_t workspace_bytes, void *hip_stream) {
+    int rc = check_batch(ctx, t, cd);
+    if (rc != HARP_OK) return rc;
+    if (!out || (cd->C > 0 && (!out->splits || !out->dev_first || !out->bottleneck || !out->iter_time || !out->status)))
+        return fail(ctx, HARP_ERR_INVALID_ARG, "null output array");
+    if (!t->fast32)
+        return fail(ctx, HARP_ERR_UNIMPLEMENTED, "the exact search needs tables that allow the 32-bit path");
+    if (cd->C == 0) return HARP_OK;
+    const size_t need = harp_plan_workspace_bytes(ctx, t, cd);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0)
+        return fail(ctx, HARP_ERR_WORKSPACE, "workspace must be a 256-byte aligned device pointer");
+    if (workspace_bytes < need)
+        return fail(ctx, HARP_ERR_WORKSPACE, "workspace holds %zu bytes, %zu needed", workspace_bytes, need);
+    hipError_t e = hipSetDevice(ctx->device);
+    if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
+    const CandDev c = { cd->C, cd->S_max, cd->cand_S, cd->cand_group, cd->cand_tp };
+    const PlansDev o = { out->splits, out->dev_first, out->bottleneck, out->iter_time, out->status };
+    const int groups = n_plan_groups(ctx, cd->C, true, t->dev.L, cd->S_max);
+    launch_plan_fast(t->dev, c, o, workspace, groups, static_cast<hipStream_t>(hip_stream));
+    launch_plan_exact(t->dev, c, o, n_passes, workspace, groups, static_cast<hipStream_t>(hip_stream));
+    e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(ctx, e, "launching the exact-search kernels");
+    return HARP_OK;
+}
+
 int harp_score_1f1b(harp_ctx *ctx, harp_tables *t, const harp_candidates *cd, const int32_t *splits,
                     int64_t *bottleneck, int64_t *iter_time, int32_t *status, void *hip_stream) {
     int rc = check_batch(ctx, t, cd);

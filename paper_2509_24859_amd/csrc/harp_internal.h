@@ -85,6 +85,8 @@ void launch_plan_fast(const TablesDev &tb, const CandDev &cd, const PlansDev &ou
                       int n_groups, hipStream_t st);
 size_t plan_fast_ws_bytes(int L, int S_max, int C, int n_groups);
 int plan_fast_groups(int L, int S_max, int n_cu);
+void launch_plan_exact(const TablesDev &tb, const CandDev &cd, const PlansDev &out, int32_t *n_passes,
+                       void *ws, int n_groups, hipStream_t st);
 void launch_score(const TablesDev &tb, const CandDev &cd, const int32_t *splits,
                   int64_t *bottleneck, int64_t *iter_time, int32_t *status, hipStream_t st);
 void launch_argmin(int32_t C, const int64_t *iter_time, const int32_t *status, int64_t *best_time,

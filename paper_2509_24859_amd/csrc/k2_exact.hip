@@ -1,0 +1,378 @@
+// Exact optimum of the iteration-time model for every candidate: the t_max sweep of the paper's
+// section 5.2.4 (2) on top of the capped recurrence of section 5.2.3.
+//
+// For a cap t_max on every stage and transfer time (constraints (i), (ii)) and the memory limit
+// (constraint (iii), eq. mem_cons), the capped recurrence finds the partition with the least
+//   sum_s (t_s + 2 c_s);
+// the iteration time of eq. gpipe_cost_model is that sum plus (B - 1) t_max, and the optimum over
+// all partitions is the least such total over the caps between t_S, the smallest feasible cap (what
+// the min-max planner found), and t_E = ceil(T(t_S) / B), beyond which no cap can win.
+//
+// Only caps that are the bottleneck of their own least-sum plan can attain the optimum (a plan
+// whose bottleneck is below the cap is found again, with a smaller total, at that bottleneck), so
+// the sweep is walked from the top: run the capped recurrence at the cap, read the bottleneck b of
+// the plan it returns, score it, and continue at cap b - 1.  Every cap in between returns the same
+// plan and a larger total.  The walk ends when b reaches t_S, or as soon as the current least sum
+// plus (B - 1) t_S exceeds the best total so far (sums only grow as the cap shrinks).  Totals are
+// compared with "not larger", so among equal totals the lowest cap is kept, the same choice an
+// increasing sweep makes with "smaller".  The result is bit for bit what the increasing sweep over
+// every distinct stage cost returns; it takes a handful of passes instead of hundreds.
+//
+// One pass is the band-limited, LDS-resident stage loop of the min-max kernel with three changes:
+// a cell's value is the least sum (previous row + stage time, plus twice the cell's transfer time),
+// previous cuts whose stage time exceeds the cap are excluded (the stage time never decreases as
+// the previous cut moves down, so the downward scan stops there), and a cell whose own transfer
+// time exceeds the cap is unreachable.
+//
+// Sums are 32-bit whenever the candidate allows it.  The min-max plan is admissible at every cap of
+// the walk, so no least-sum plan costs more than that plan's own sum U, and a cell whose value
+// exceeds U lies on none of them: such values are replaced by infinity, which changes no result
+// and keeps every finite value at or below U.  With U < 2^31 and infinity = 2^31, a value plus a
+// stage time (below 2^31 on these tables) never wraps and infinity plus any time never passes for
+// a sum.  Candidates with U >= 2^31 (iterations of more than half an hour) are queued and redone
+// by the same kernel instantiated with 64-bit sums.
+#include "fast_common.h"
+#include "harp_internal.h"
+#include "plan_common.h"
+
+namespace harp {
+
+using namespace fastdp;
+
+namespace {
+
+template <typename SumT> struct SumTraits;
+template <> struct SumTraits<uint32_t> {
+    static constexpr uint32_t inf = 0x80000000u;
+    struct alignas(8) Entry { uint32_t d, p; };
+};
+template <> struct SumTraits<uint64_t> {
+    static constexpr uint64_t inf = uint64_t(1) << 62;
+    struct alignas(16) Entry { uint64_t d; uint32_t p; uint32_t unused; };
+};
+
+constexpr int64_t kNarrowLimit = int64_t(1) << 31;   // sums below this run in 32 bits
+
+// counts: [0] live candidates, [1] dead candidates, [2] candidates queued for 64-bit sums.
+// The queue sits in the unused tail of the dead list (live + dead = C entries in all).
+template <typename SumT>
+__device__ __forceinline__ void exact_body(const TablesDev &tb, const CandDev &cd, const PlansDev &out,
+                                           int32_t *n_passes, int *counts, const int32_t *live_list,
+                                           uint32_t *dead_list, const uint32_t *bands,
+                                           unsigned char *arg_base, size_t arg_per_group, int row_len) {
+    using Pair = typename SumTraits<SumT>::Entry;
+    constexpr SumT kInfSum = SumTraits<SumT>::inf;
+    constexpr bool kWide = sizeof(SumT) == 8;
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+
+    const int L = tb.L, S_max = cd.S_max;
+    const int tid = threadIdx.x, lane = tid & 63, nthreads = blockDim.x;
+    const int wave = uniform(tid >> 6);
+    int64_t *Qb = reinterpret_cast<int64_t *>(lds_raw) + kPad;                        // [2][row_len]
+    Pair *rows = reinterpret_cast<Pair *>(lds_raw + size_t(row_len) * 16) + kPad;     // [2][row_len]
+    StageConst *sc = reinterpret_cast<StageConst *>(lds_raw + size_t(row_len) * (16 + 2 * sizeof(Pair)));  // [S_max]
+    uint64_t *scal = reinterpret_cast<uint64_t *>(sc + S_max);                         // [2]
+    uint32_t *band = reinterpret_cast<uint32_t *>(scal + 2);                           // [S_max + 1]
+    int32_t *trial = reinterpret_cast<int32_t *>(band + S_max + 1);                    // [S_max + 1]
+    int32_t *kept = trial + S_max + 1;                                                 // [S_max + 1]
+    uint16_t *slot_g = reinterpret_cast<uint16_t *>(kept + S_max + 1);                 // [S_max]
+    uint8_t *slot_k = reinterpret_cast<uint8_t *>(slot_g + S_max);                     // [S_max]
+    uint16_t *arg = reinterpret_cast<uint16_t *>(arg_base + size_t(blockIdx.x) * arg_per_group);
+    const int64_t *PP = tb.PP(), *PS = tb.PS();
+    const int n_dead = counts[1];
+    const int n_items = kWide ? counts[2] : counts[0];
+    const int64_t m_cap = tb.M;
+
+    for (int n = blockIdx.x; n < n_items; n += gridDim.x) {
+        const int c = kWide ? int(dead_list[n_dead + n]) : live_list[n];
+        __syncthreads();   // the previous candidate's tail has finished with LDS
+        const int S = cd.cand_S[c];
+        // the min-max planner has run on this batch: candidates it found no plan for stay as they are,
+        // and a single stage has only one partition
+        if (out.status[c] != HARP_CAND_OK || S < 2) {
+            if (tid == 0 && n_passes) n_passes[c] = 0;
+            continue;
+        }
+        const int64_t t_S = out.bottleneck[c];
+        const int64_t T_S = out.iter_time[c];
+        const int64_t limit = T_S - (m_cap - 1) * t_S;      // the min-max plan's own sum
+        if (!kWide && limit >= kNarrowLimit) {
+            if (tid == 0) dead_list[n_dead + atomicAdd(&counts[2], 1)] = uint32_t(c);
+            continue;
+        }
+        {
+            const int32_t *grp = cd.cand_group + int64_t(c) * S_max;
+            const int32_t *tpv = cd.cand_tp + int64_t(c) * S_max;
+            for (int s = tid; s < S; s += nthreads) {
+                const int g = grp[s], k = tp_index(tb, tpv[s]);
+                const int g_next = s + 1 < S ? grp[s + 1] : g;
+                slot_g[s] = (uint16_t)g;
+                slot_k[s] = (uint8_t)k;
+                sc[s].cap = int64_t(tb.tp[k]) * tb.type_mem[tb.group_type[g]];
+                sc[s].p_row = uint32_t((int64_t(g) * tb.n_tp + k) * tb.pitch32);
+                sc[s].cm_row_shift = uint32_t((int64_t(g) * tb.G + g_next) * tb.pitch32) |
+                                     (uint32_t(tb.tp_shift[k]) << 27);
+            }
+            for (int s = tid; s <= S; s += nthreads) band[s] = bands[int64_t(s) * cd.C + c];
+        }
+        __syncthreads();
+
+        int64_t t_cap64 = (T_S + m_cap - 1) / m_cap;             // t_E
+        if (t_cap64 > 0x7FFFFFFFll) t_cap64 = 0x7FFFFFFFll;      // no time on these tables is larger
+        int64_t best_T = kInf;
+        int passes = 0;
+        for (;;) {
+            const uint32_t tcap = (uint32_t)uniform((int)(uint32_t)t_cap64);
+            // ---- one capped pass
+            uint32_t cut_i = 0;
+            {
+                const uint32_t *p32 = tb.P32 + (uint32_t)uniform((int)sc[0].p_row);
+                const uint32_t *cm = tb.CM + ((uint32_t)uniform((int)sc[0].cm_row_shift) & kRowMask);
+                const int64_t n0 = S < m_cap ? S : m_cap;
+                const uint32_t b1 = (uint32_t)uniform((int)band[1]);
+                for (int j = tid; j <= band_hi(b1); j += nthreads) {
+                    rows[j].p = p32[j];
+                    Qb[j] = PP[j] + n0 * PS[j];
+                }
+                if (band_lo(b1) + tid <= band_hi(b1)) cut_i = cm[band_lo(b1) + tid];
+                // below cut 0: never a predecessor; the time read there must stay small
+                if (tid < 3) { rows[-1 - tid].d = kInfSum; rows[-1 - tid].p = 0xFFFFFFFFu; }
+                if (tid == 0) rows[0].d = 0;
+            }
+            lds_barrier();
+
+            int cur = 0;
+            const int wave_first = wave * 64;
+            for (int s = 0; s < S - 1; ++s) {
+                const uint32_t b1 = (uint32_t)uniform((int)band[s + 1]);
+                const uint32_t b2 = (uint32_t)uniform((int)band[s + 2]);
+                const int il = band_lo(b1), ih = band_hi(b1);     // cells: row s + 1
+                const int top_n = band_hi(b2);                    // stage s+1 reads its rows up to here
+                if (il + wave_first > top_n && wave != 0) {
+                    lds_barrier();
+                    cur ^= 1;
+                    continue;
+                }
+                const uint32_t rs = (uint32_t)uniform((int)sc[s].cm_row_shift);
+                const int shift = int(rs >> 27);
+                const uint32_t tp = 1u << shift;
+                const int64_t cap = uniform64(sc[s].cap);
+                const uint32_t b0 = (uint32_t)uniform((int)band[s]);
+                const int jl = band_lo(b0), jh = band_hi(b0);     // predecessors: row s
+                const uint32_t *cm_s = tb.CM + (rs & kRowMask);
+                const Pair *prev = rows + cur * row_len;
+                Pair *next = rows + (cur ^ 1) * row_len;
+                const int64_t *Q = Qb + cur * row_len;
+                int64_t *Qn = Qb + (cur ^ 1) * row_len;
+                const uint32_t *p32_n = tb.P32 + (uint32_t)uniform((int)sc[s + 1].p_row);
+                const uint32_t *cm_n = tb.CM + ((uint32_t)uniform((int)sc[s + 1].cm_row_shift) & kRowMask);
+                const bool next_has_cut = s + 2 < S;
+
+                const int jn = il + tid;
+                uint32_t p_n = 0, cut_n = 0;
+                int64_t pp_n = 0, ps_n = 0;
+                if (jn <= top_n) { p_n = p32_n[jn]; pp_n = PP[jn]; ps_n = PS[jn]; }
+                if (next_has_cut && band_lo(b2) + tid <= top_n) cut_n = cm_n[band_lo(b2) + tid];
+
+                // One cell: least sum over the previous cuts that fit in memory and under the cap,
+                // scanned downwards four per trip.  Both limits are monotone in j, so the last
+                // entry of a trip decides whether the lane goes on.  Equal sums keep the lowest j.
+                auto cell = [&](int i, uint32_t cut) -> int {
+                    const int64_t th = Q[i] - cap;
+                    const uint32_t xi = prev[i].p + tp - 1;
+                    SumT best = kInfSum;
+                    int best_j = 0;
+                    int j = (i - 1) < jh ? (i - 1) : jh;
+                    bool more = (j >= jl) & (cut <= tcap);
+                    while (more) {
+                        const Pair *pe = prev + (j - 3);
+                        const int64_t *pq = Q + (j - 3);
+                        const Pair e3 = pe[0], e2 = pe[1], e1 = pe[2], e0 = pe[3];
+                        const int64_t q3 = pq[0], q2 = pq[1], q1 = pq[2], q0 = pq[3];
+                        uint32_t tj;
+#define HARP_STEP(E, QV, JJ)                                                   \
+    {                                                                          \
+        tj = (xi - (E).p) >> shift;                                            \
+        const SumT v = (E).d + tj;                                             \
+        const bool upd = ((QV) >= th) & (tj <= tcap) & (v <= best);            \
+        best = upd ? v : best;                                                 \
+        best_j = upd ? (JJ) : best_j;                                          \
+    }
+                        HARP_STEP(e0, q0, j)
+                        HARP_STEP(e1, q1, j - 1)
+                        HARP_STEP(e2, q2, j - 2)
+                        HARP_STEP(e3, q3, j - 3)
+#undef HARP_STEP
+                        more = ((j - 3) > jl) & (q3 >= th) & (tj <= tcap);
+                        j -= 4;
+                    }
+                    const uint64_t total = uint64_t(best) + 2ull * cut;
+                    next[i].d = (best >= kInfSum || total > uint64_t(limit)) ? kInfSum : SumT(total);
+                    return best_j;
+                };
+                const int i0 = il + tid;
+                int first_j = 0;
+                if (i0 <= ih) first_j = cell(i0, cut_i);
+                for (int i = i0 + nthreads; i <= ih; i += nthreads)
+                    arg[s * row_len + i] = (uint16_t)cell(i, cm_s[i]);
+                if (tid < 3) {                                  // below the band of row s + 1
+                    next[il - 1 - tid].d = kInfSum;
+                    next[il - 1 - tid].p = 0xFFFFFFFFu;
+                }
+
+                const int64_t n1 = (S - s - 1) < m_cap ? (S - s - 1) : m_cap;
+                if (jn <= top_n) {
+                    next[jn].p = p_n;
+                    Qn[jn] = pp_n + n1 * ps_n;
+                }
+                for (int j = jn + nthreads; j <= top_n; j += nthreads) {
+                    next[j].p = p32_n[j];
+                    Qn[j] = PP[j] + n1 * PS[j];
+                }
+                asm volatile("" : "+v"(cut_n));
+                cut_i = cut_n;
+                if (i0 <= ih) arg[s * row_len + i0] = (uint16_t)first_j;
+                lds_barrier();
+                cur ^= 1;
+            }
+            // the last stage has the single cell i = L: lanes over j, lexicographic reduction
+            if (wave == 0) {
+                const int s = S - 1;
+                const int shift = int((uint32_t)uniform((int)sc[s].cm_row_shift) >> 27);
+                const uint32_t tp = 1u << shift;
+                const int64_t cap = uniform64(sc[s].cap);
+                const uint32_t b0 = (uint32_t)uniform((int)band[s]);
+                const Pair *prev = rows + cur * row_len;
+                const int64_t *Q = Qb + cur * row_len;
+                const int64_t th = Q[L] - cap;
+                const uint32_t xi = prev[L].p + tp - 1;
+                const int hi = (L - 1) < band_hi(b0) ? (L - 1) : band_hi(b0);
+                unsigned long long best = kInfSum;
+                int best_j = INT32_MAX;
+                for (int j = band_lo(b0) + lane; j <= hi; j += 64) {
+                    if (Q[j] < th) continue;
+                    const uint32_t tj = (xi - prev[j].p) >> shift;
+                    const unsigned long long v = (unsigned long long)prev[j].d + tj;
+                    if (tj <= tcap && v < best) { best = v; best_j = j; }   // j rises within a lane
+                }
+#pragma unroll
+                for (int d = 32; d >= 1; d >>= 1) {
+                    const unsigned long long ov = __shfl_xor(best, d, 64);
+                    const int oj = __shfl_xor(best_j, d, 64);
+                    if (ov < best || (ov == best && oj < best_j)) { best = ov; best_j = oj; }
+                }
+                if (lane == 0) {
+                    arg[(S - 1) * row_len + L] = (uint16_t)best_j;
+                    scal[0] = best;
+                }
+            }
+            __syncthreads();          // back-pointers of every wave are visible to thread 0
+            const int64_t sum = uniform64((int64_t)scal[0]);
+            if (sum >= int64_t(kInfSum)) break;   // no plan under this cap (cannot happen at or above t_S)
+            if (tid == 0) {
+                int b = L;
+                trial[S] = L;
+                for (int s = S - 1; s >= 0; --s) {
+                    b = arg[s * row_len + b];
+                    b = b < L ? b : L;      // a finite sum only chains through cuts inside the row
+                    trial[s] = b;
+                }
+            }
+            __syncthreads();
+            // the plan's bottleneck, one lane per stage
+            if (wave == 0) {
+                uint32_t w = 0;
+                for (int s = lane; s < S; s += 64) {
+                    const int j = trial[s], i = trial[s + 1];
+                    const uint32_t rs = sc[s].cm_row_shift;
+                    const int shift = int(rs >> 27);
+                    const uint32_t *p = tb.P32 + sc[s].p_row;
+                    const uint32_t t = (p[i] + (1u << shift) - 1u - p[j]) >> shift;
+                    const uint32_t cu = s < S - 1 ? tb.CM[(rs & kRowMask) + uint32_t(i)] : 0u;
+                    const uint32_t m = t > cu ? t : cu;
+                    w = w > m ? w : m;
+                }
+#pragma unroll
+                for (int d = 32; d >= 1; d >>= 1) {
+                    const uint32_t ow = __shfl_xor(w, d, 64);
+                    w = w > ow ? w : ow;
+                }
+                if (lane == 0) scal[1] = w;
+            }
+            __syncthreads();
+            const int64_t b = uniform64((int64_t)scal[1]);
+            const int64_t T = sum + (m_cap - 1) * b;
+            ++passes;
+            if (T <= best_T) {
+                best_T = T;
+                for (int s = tid; s <= S; s += nthreads) kept[s] = trial[s];
+            }
+            if (b <= t_S) break;
+            if (sum + (m_cap - 1) * t_S > best_T) break;
+            if (b > t_cap64 || passes >= (1 << 20)) break;   // the cap must fall with every pass
+            t_cap64 = b - 1;
+        }
+        __syncthreads();
+        if (tid == 0 && n_passes) n_passes[c] = passes;
+        if (best_T == kInf) {
+            write_failed(out, c, S_max, HARP_CAND_INFEASIBLE);
+            continue;
+        }
+        int32_t *sp = out.splits + int64_t(c) * (S_max + 1);
+        for (int s = tid; s <= S; s += nthreads) sp[s] = kept[s];
+        __syncthreads();
+        if (wave == 0) {
+            int64_t bott, iter;
+            const int st = wave_score_partition(tb, S, slot_g, slot_k, sp, lane, bott, iter);
+            if (lane == 0) {
+                out.bottleneck[c] = bott;
+                out.iter_time[c] = iter;
+                out.status[c] = st;
+            }
+        }
+    }
+    // candidates the pre-pass rejected keep the outputs the min-max kernel wrote
+    if (!kWide && n_passes) {
+        for (int n = blockIdx.x * nthreads + tid; n < n_dead; n += gridDim.x * nthreads)
+            n_passes[dead_list[n] & ((1u << kDeadStatusShift) - 1u)] = 0;
+    }
+}
+
+__global__ __launch_bounds__(kFastThreads) __attribute__((amdgpu_waves_per_eu(8, 8)))
+void k2_exact(TablesDev tb, CandDev cd, PlansDev out, int32_t *n_passes, int *counts, const int32_t *live_list,
+              uint32_t *dead_list, const uint32_t *bands, unsigned char *arg_base, size_t arg_per_group,
+              int row_len) {
+    exact_body<uint32_t>(tb, cd, out, n_passes, counts, live_list, dead_list, bands, arg_base, arg_per_group,
+                         row_len);
+}
+
+__global__ __launch_bounds__(kFastThreads)
+void k2_exact_wide(TablesDev tb, CandDev cd, PlansDev out, int32_t *n_passes, int *counts,
+                   const int32_t *live_list, uint32_t *dead_list, const uint32_t *bands,
+                   unsigned char *arg_base, size_t arg_per_group, int row_len) {
+    exact_body<uint64_t>(tb, cd, out, n_passes, counts, live_list, dead_list, bands, arg_base, arg_per_group,
+                         row_len);
+}
+
+size_t exact_lds_bytes(int L, int S_max, size_t entry) {
+    size_t b = size_t(fast_row_len(L)) * (16 + 2 * entry) + size_t(S_max) * sizeof(StageConst) + 16 +
+               size_t(S_max + 1) * 12 + size_t(S_max) * 3;
+    return (b + 15) & ~size_t(15);
+}
+
+}  // namespace
+
+// Runs after launch_plan_fast on the same stream, workspace and group count: the live list, the
+// bands and the min-max results in `out` are its inputs.
+void launch_plan_exact(const TablesDev &tb, const CandDev &cd, const PlansDev &out, int32_t *n_passes,
+                       void *ws, int n_groups, hipStream_t st) {
+    const FastWorkspace w = carve(ws, tb.L, cd.S_max, cd.C, n_groups);
+    hipLaunchKernelGGL(k2_exact, dim3(n_groups), dim3(kFastThreads), exact_lds_bytes(tb.L, cd.S_max, 8), st, tb,
+                       cd, out, n_passes, w.counts, w.live_list, w.dead_list, w.bands, w.arg,
+                       fast_arg_per_group(tb.L, cd.S_max), fast_row_len(tb.L));
+    hipLaunchKernelGGL(k2_exact_wide, dim3(n_groups), dim3(kFastThreads), exact_lds_bytes(tb.L, cd.S_max, 16),
+                       st, tb, cd, out, n_passes, w.counts, w.live_list, w.dead_list, w.bands, w.arg,
+                       fast_arg_per_group(tb.L, cd.S_max), fast_row_len(tb.L));
+}
+
+}  // namespace harp

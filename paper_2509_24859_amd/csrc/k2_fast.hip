@@ -40,69 +40,15 @@
 // cell of the last stage is reduced across a wavefront with a lexicographic (value, j) minimum.
 // Back-pointers go to a per-workgroup slice of the caller's workspace as uint16.
 #include "harp_internal.h"
+#include "fast_common.h"
 #include "plan_common.h"
 
 namespace harp {
 
+using namespace fastdp;
+
 namespace {
 
-constexpr uint32_t kInf32 = 0xFFFFFFFFu;
-constexpr int kPad = 4;
-constexpr int kFastThreads = 256;
-constexpr uint32_t kRowMask = (1u << 27) - 1u;
-
-struct alignas(8) Pair {
-    uint32_t d;   // previous DP row
-    uint32_t p;   // fused time row of the stage's slot
-};
-
-// Workgroup barrier that orders LDS traffic only.  Global loads and stores stay in flight across
-// it (the stage loop never communicates through global memory), which keeps the round trips of the
-// back-pointer stores and of the next stage's table rows off the per-stage critical path.
-__device__ __forceinline__ void lds_barrier() {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-}
-
-__device__ __forceinline__ uint32_t umax3(uint32_t a, uint32_t b, uint32_t c) {
-    uint32_t m = a > b ? a : b;
-    return m > c ? m : c;
-}
-
-// A value every lane of the wave holds, moved to a scalar register.
-__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
-__device__ __forceinline__ int64_t uniform64(int64_t v) {
-    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
-    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)((uint64_t)v >> 32));
-    return (int64_t)(((uint64_t)hi << 32) | lo);
-}
-template <typename T>
-__device__ __forceinline__ const T *uniform_ptr(const T *p) {
-    return reinterpret_cast<const T *>(uniform64(reinterpret_cast<int64_t>(p)));
-}
-
-// Per-slot constants of the candidate in flight, computed once per candidate so that the stage
-// loop starts from LDS and never waits on a chain of dependent global loads.
-// Rows are named by element offsets from the table bases, not by pointers: a pointer read back
-// from LDS has no known address space and would turn every table access into a flat load.
-struct alignas(16) StageConst {
-    int64_t cap;            // tp * device memory of the slot's GPU type
-    uint32_t p_row;         // element offset of the slot's fused time row in P32
-    uint32_t cm_row_shift;  // element offset of the link's cut-time row in CM (low 27 bits) | log2 tp << 27
-};
-static_assert(sizeof(StageConst) == 16, "one 16-byte LDS read per stage");
-static_assert(kFastCutTableLimit / 4 <= (size_t(1) << 27), "cut-table offsets must fit 27 bits");
-
-__device__ __forceinline__ int band_lo(uint32_t w) { return int(w & 0xFFFFu); }
-__device__ __forceinline__ int band_hi(uint32_t w) { return int(w >> 16); }
-
-__device__ __forceinline__ int tp_index(const TablesDev &tb, int tp) {
-    int k = -1;
-    for (int q = 0; q < tb.n_tp; ++q)
-        if (tb.tp[q] == tp) k = q;
-    return k;
-}
 
 // Pre-pass, one thread per candidate: checks the slot list and computes the reachability band
 // [B[s], F[s]] of every DP row from the memory constraint alone (two chains of binary searches
@@ -116,7 +62,6 @@ __device__ __forceinline__ int tp_index(const TablesDev &tb, int tp) {
 // written slot-major as well ([s][c]), which keeps the writes of a wave contiguous.
 constexpr int kBandCapTable = 1024;     // caps kept in LDS when G * n_tp is at most this
 constexpr uint16_t kBadSlot = 0xFFFFu;
-constexpr uint32_t kDeadStatusShift = 30;
 
 int band_threads(int S_max) { return S_max <= 64 ? 256 : (S_max <= 128 ? 128 : 64); }
 
@@ -242,7 +187,7 @@ __global__ __launch_bounds__(256) void k2_band(TablesDev tb, CandDev cd, int *co
 }
 
 __global__ void k2_clear_count(int *counts) {
-    if (threadIdx.x < 2) counts[threadIdx.x] = 0;
+    if (threadIdx.x < 4) counts[threadIdx.x] = 0;
 }
 
 __global__ __launch_bounds__(kFastThreads) __attribute__((amdgpu_waves_per_eu(8, 8)))
@@ -480,42 +425,6 @@ void k2_fast(TablesDev tb, CandDev cd, PlansDev out, const int *counts, const in
     }
 }
 
-int fast_row_len(int L) { return (L + 1 + kPad + 7) / 8 * 8; }
-
-size_t fast_lds_bytes(int L, int S_max) {
-    size_t b = size_t(fast_row_len(L)) * 32 + size_t(S_max) * sizeof(StageConst) +
-               size_t(S_max + 1) * 4 + size_t(S_max) * 3;
-    return (b + 15) & ~size_t(15);
-}
-
-size_t fast_arg_per_group(int L, int S_max) {
-    size_t b = size_t(S_max) * fast_row_len(L) * sizeof(uint16_t);
-    return (b + 255) & ~size_t(255);
-}
-
-// Workspace: counters | live list [C] | dead list [C] | bands [S_max+1][C] | back-pointer slices.
-struct FastWorkspace {
-    int *counts;
-    int32_t *live_list;
-    uint32_t *dead_list;
-    uint32_t *bands;
-    unsigned char *arg;
-    size_t total;
-};
-
-FastWorkspace carve(void *ws, int L, int S_max, int C, int n_groups) {
-    auto up = [](size_t x) { return (x + 255) & ~size_t(255); };
-    unsigned char *base = static_cast<unsigned char *>(ws);
-    FastWorkspace w;
-    size_t off = 0;
-    w.counts = reinterpret_cast<int *>(base + off); off += 256;
-    w.live_list = reinterpret_cast<int32_t *>(base + off); off += up(size_t(C) * 4);
-    w.dead_list = reinterpret_cast<uint32_t *>(base + off); off += up(size_t(C) * 4);
-    w.bands = reinterpret_cast<uint32_t *>(base + off); off += up(size_t(C) * (S_max + 1) * 4);
-    w.arg = base + off; off += size_t(n_groups) * fast_arg_per_group(L, S_max);
-    w.total = off;
-    return w;
-}
 
 }  // namespace
 

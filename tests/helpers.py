@@ -70,6 +70,20 @@ def oracle_plan_threaded(tables, cands, threads=None, step=16):
     return out
 
 
+def oracle_plan_exact_threaded(tables, cands, threads=None):
+    """Oracle exact-optimum plans for a whole batch, one candidate per task over host threads."""
+    import os
+    from concurrent.futures import ThreadPoolExecutor
+
+    import oracle
+    threads = threads or min(16, len(os.sched_getaffinity(0)))
+    out = oracle.Plans(cands.C, cands.S_max)
+    out.n_caps = np.zeros(cands.C, dtype=np.int32)
+    with ThreadPoolExecutor(threads) as ex:
+        list(ex.map(lambda c: oracle.plan_exact_batch(tables, cands, c, c + 1, out), range(cands.C)))
+    return out
+
+
 def assert_plans_equal(got, want, label=""):
     """Bit-exact comparison of every output array of a batch."""
     for name in ("status", "splits", "dev_first", "bottleneck", "iter_time"):
