@@ -85,6 +85,58 @@ def tables_streaming(ctx, binding, workloads, torch, L, reps=10):
             "achieved": rate / 1e9, "peak": 8000.0, "unit": "GB/s", "frac": rate / 8e12}
 
 
+def exact_search(ctx, binding, torch, w, tables, dc, cands, minmax, reps, cpu_candidates):
+    """The exact search (cap sweep on top of the min-max plans) over the same batch: time per call,
+    capped passes per candidate, what it gains over the min-max plans, and the oracle's sweep timed
+    on a few candidates (which also checks the GPU's answers for them bit for bit)."""
+    import numpy as np
+
+    out = binding.DevicePlans(ctx, dc.C, dc.S_max)
+    ws = binding.plan_workspace(ctx, tables, dc)
+    n_passes = torch.zeros(dc.C, dtype=torch.int32, device=ctx.device)
+    binding.harp_plan_exact_batch(ctx, tables, dc, out, ws, n_passes)
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(reps):
+        binding.harp_plan_exact_batch(ctx, tables, dc, out, ws, n_passes)
+    b.record()
+    torch.cuda.synchronize()
+    ms = a.elapsed_time(b) / reps
+    got = out.to_host()
+    passes = n_passes.cpu().numpy()
+    ok = got.status == 0
+    gain = 1.0 - got.iter_time[ok] / np.maximum(1, minmax.iter_time[ok])
+    res = {"kernel": "k2_band + k2_fast + k2_exact (one harp_plan_exact_batch call)", "ms_per_call": ms,
+           "plans_per_s": dc.C / (ms * 1e-3), "capped_passes_total": int(passes.sum()),
+           "capped_passes_mean_feasible": float(passes[ok].mean()) if ok.any() else 0.0,
+           "capped_passes_max": int(passes.max()) if passes.size else 0,
+           "improved_fraction": float((got.iter_time[ok] < minmax.iter_time[ok]).mean()) if ok.any() else 0.0,
+           "mean_iter_time_gain": float(gain.mean()) if ok.any() else 0.0,
+           "best_iter_time_us": int(got.iter_time[ok].min()) if ok.any() else None}
+    if cpu_candidates:
+        import oracle
+        from concurrent.futures import ThreadPoolExecutor
+        cores = min(16, len(os.sched_getaffinity(0)))
+        idx = np.nonzero(ok)[0][:cpu_candidates]
+        sub = cands.take(idx)
+        ot = oracle.build_tables(w.problem)
+        want = oracle.Plans(sub.C, sub.S_max)
+        want.n_caps = np.zeros(sub.C, dtype=np.int32)
+        t0 = time.perf_counter()
+        with ThreadPoolExecutor(cores) as ex:
+            list(ex.map(lambda c: oracle.plan_exact_batch(ot, sub, c, c + 1, want), range(sub.C)))
+        dt = time.perf_counter() - t0
+        for name in ("status", "splits", "bottleneck", "iter_time"):
+            if not (getattr(want, name) == getattr(got, name)[idx]).all():
+                raise SystemExit("GPU exact plans differ from the oracle in %s on the baseline sample" % name)
+        res["cpu_baseline"] = {"value": sub.C / dt, "unit": "plans/s", "cores": cores, "kind": "oracle",
+                               "sample": "first %d feasible candidates of the batch, one per task over %d threads, "
+                                         "%.1f s wall, %d caps swept per candidate on average; GPU answers for "
+                                         "the sample verified bit-exact" % (sub.C, cores, dt, want.n_caps.mean())}
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -97,6 +149,9 @@ def main():
     ap.add_argument("--cpu-candidates", type=int, default=0)
     ap.add_argument("--tables-L", type=int, default=1 << 20,
                     help="operators of the table-build streaming measurement (0 = skip)")
+    ap.add_argument("--exact-reps", type=int, default=3,
+                    help="timed calls of the exact search over the same batch (0 = skip)")
+    ap.add_argument("--exact-cpu-candidates", type=int, default=16)
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="also run one plain device copy of this many MiB (reference for HBM counters)")
     args = ap.parse_args()
@@ -195,6 +250,9 @@ def main():
     }
     if args.tables_L:
         result["tables_streaming"] = tables_streaming(ctx, binding, workloads, torch, args.tables_L)
+    if args.exact_reps and fast:
+        result["exact_search"] = exact_search(ctx, binding, torch, w, tables, dc, cands, got, args.exact_reps,
+                                              0 if args.no_cpu_baseline else args.exact_cpu_candidates)
     if not args.no_cpu_baseline:
         # about 20 core-seconds of oracle work at 1-5 ns per dense transition
         budget = args.cpu_candidates or max(64, int(1.6e10 / max(1.0, n_trans / C)))

@@ -70,7 +70,7 @@ inline int fast_row_len(int L) { return (L + 1 + kPad + 7) / 8 * 8; }
 
 inline size_t fast_lds_bytes(int L, int S_max) {
     size_t b = size_t(fast_row_len(L)) * 32 + size_t(S_max) * sizeof(StageConst) +
-               size_t(S_max + 1) * 4 + size_t(S_max) * 3;
+               size_t(S_max + 2) * 4 + size_t(S_max) * 3;
     return (b + 15) & ~size_t(15);
 }
 

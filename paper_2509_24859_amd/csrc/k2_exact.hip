@@ -53,7 +53,8 @@ template <> struct SumTraits<uint64_t> {
 
 constexpr int64_t kNarrowLimit = int64_t(1) << 31;   // sums below this run in 32 bits
 
-// counts: [0] live candidates, [1] dead candidates, [2] candidates queued for 64-bit sums.
+// counts: [0] live candidates, [1] dead candidates, [2] candidates queued for 64-bit sums,
+// [3], [4] next item of the two kernels' work lists.
 // The queue sits in the unused tail of the dead list (live + dead = C entries in all).
 template <typename SumT>
 __device__ __forceinline__ void exact_body(const TablesDev &tb, const CandDev &cd, const PlansDev &out,
@@ -83,9 +84,15 @@ __device__ __forceinline__ void exact_body(const TablesDev &tb, const CandDev &c
     const int n_items = kWide ? counts[2] : counts[0];
     const int64_t m_cap = tb.M;
 
-    for (int n = blockIdx.x; n < n_items; n += gridDim.x) {
-        const int c = kWide ? int(dead_list[n_dead + n]) : live_list[n];
+    // candidates differ widely in passes, so workgroups draw them from a shared counter
+    int *next_item = counts + (kWide ? 4 : 3);
+    for (;;) {
         __syncthreads();   // the previous candidate's tail has finished with LDS
+        if (tid == 0) scal[0] = (uint64_t)atomicAdd(next_item, 1);
+        __syncthreads();
+        const int n = uniform((int)scal[0]);
+        if (n >= n_items) break;
+        const int c = kWide ? int(dead_list[n_dead + n]) : live_list[n];
         const int S = cd.cand_S[c];
         // the min-max planner has run on this batch: candidates it found no plan for stay as they are,
         // and a single stage has only one partition

@@ -28,8 +28,8 @@
 // because ceil(a / tp) + b = ceil((a + tp b) / tp) for integers.  Transfer times come from the
 // per-link cut table built beside the rows.
 //
-// Mapping of k2_fast: one workgroup per live candidate at a time (persistent workgroups stride
-// over the list k2_band compacted), one lane per DP cell of the current stage's band (more trips
+// Mapping of k2_fast: one workgroup per live candidate at a time (persistent workgroups draw
+// from the list k2_band compacted through a shared counter), one lane per DP cell of the current stage's band (more trips
 // when the band is wider than the workgroup), lanes of a wave on consecutive cells so that LDS
 // reads of (D[j], P[j]) pairs are stride-1 or broadcast.  The previous DP row and the slot's P row
 // sit interleaved in LDS so that one 8-byte read feeds a transition.  What stage s+1 needs from
@@ -187,11 +187,11 @@ __global__ __launch_bounds__(256) void k2_band(TablesDev tb, CandDev cd, int *co
 }
 
 __global__ void k2_clear_count(int *counts) {
-    if (threadIdx.x < 4) counts[threadIdx.x] = 0;
+    if (threadIdx.x < 8) counts[threadIdx.x] = 0;
 }
 
 __global__ __launch_bounds__(kFastThreads) __attribute__((amdgpu_waves_per_eu(8, 8)))
-void k2_fast(TablesDev tb, CandDev cd, PlansDev out, const int *counts, const int32_t *live_list,
+void k2_fast(TablesDev tb, CandDev cd, PlansDev out, int *counts, const int32_t *live_list,
              const uint32_t *dead_list, const uint32_t *bands, unsigned char *arg_base, size_t arg_per_group,
              int row_len) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
@@ -204,17 +204,24 @@ void k2_fast(TablesDev tb, CandDev cd, PlansDev out, const int *counts, const in
     int64_t *Qb = reinterpret_cast<int64_t *>(lds_raw) + kPad;                        // [2][row_len]
     Pair *rows = reinterpret_cast<Pair *>(lds_raw + size_t(row_len) * 16) + kPad;     // [2][row_len]
     StageConst *sc = reinterpret_cast<StageConst *>(lds_raw + size_t(row_len) * 32);  // [S_max]
-    uint32_t *band = reinterpret_cast<uint32_t *>(sc + S_max);                         // [S_max + 1]
+    uint32_t *ticket = reinterpret_cast<uint32_t *>(sc + S_max);                       // [1]
+    uint32_t *band = ticket + 1;                                                       // [S_max + 1]
     uint16_t *slot_g = reinterpret_cast<uint16_t *>(band + S_max + 1);                 // [S_max]
     uint8_t *slot_k = reinterpret_cast<uint8_t *>(slot_g + S_max);                     // [S_max]
     uint16_t *arg = reinterpret_cast<uint16_t *>(arg_base + size_t(blockIdx.x) * arg_per_group);
     const int64_t *PP = tb.PP(), *PS = tb.PS();
     const int n_live = counts[0], n_dead = counts[1];
+    int *next_item = counts + 5;
     const int64_t m_cap = tb.M;
 
-    for (int n = blockIdx.x; n < n_live; n += gridDim.x) {
-        const int c = live_list[n];
+    // candidates differ in stages and band widths, so workgroups draw them from a shared counter
+    for (;;) {
         __syncthreads();   // the previous candidate's tail has finished with LDS
+        if (tid == 0) *ticket = (uint32_t)atomicAdd(next_item, 1);
+        __syncthreads();
+        const int n = uniform((int)*ticket);
+        if (n >= n_live) break;
+        const int c = live_list[n];
         const int S = cd.cand_S[c];
         {
             const int32_t *grp = cd.cand_group + int64_t(c) * S_max;
