@@ -10,13 +10,16 @@
 //
 // Only caps that are the bottleneck of their own least-sum plan can attain the optimum (a plan
 // whose bottleneck is below the cap is found again, with a smaller total, at that bottleneck), so
-// the sweep is walked from the top: run the capped recurrence at the cap, read the bottleneck b of
-// the plan it returns, score it, and continue at cap b - 1.  Every cap in between returns the same
-// plan and a larger total.  The walk ends when b reaches t_S, or as soon as the current least sum
-// plus (B - 1) t_S exceeds the best total so far (sums only grow as the cap shrinks).  Totals are
-// compared with "not larger", so among equal totals the lowest cap is kept, the same choice an
-// increasing sweep makes with "smaller".  The result is bit for bit what the increasing sweep over
-// every distinct stage cost returns; it takes a handful of passes instead of hundreds.
+// the sweep is walked instead of enumerated.  The first pass runs at t_S and gives a total T that
+// is usually close to the optimum.  The walk then starts at ceil(T / B) and moves down: run the
+// capped recurrence at the cap, read the bottleneck b of the plan it returns, score it, continue
+// at b - 1; every cap in between returns the same plan and a larger total.  Sums only grow as the
+// cap shrinks, so once a pass has returned the sum s, a lower cap can match the best total T only
+// with a bottleneck of at most (T - s) / (B - 1): the walk jumps to that cap when it is below
+// b - 1, and ends when the next cap would be t_S or less.  Among equal totals the lower cap is
+// kept, the choice an increasing sweep makes by accepting only strictly smaller totals.  The
+// result is bit for bit what the increasing sweep over every distinct stage cost returns; it
+// takes a handful of passes instead of hundreds.
 //
 // One pass is the band-limited, LDS-resident stage loop of the min-max kernel with three changes:
 // a cell's value is the least sum (previous row + stage time, plus twice the cell's transfer time),
@@ -124,9 +127,8 @@ __device__ __forceinline__ void exact_body(const TablesDev &tb, const CandDev &c
         }
         __syncthreads();
 
-        int64_t t_cap64 = (T_S + m_cap - 1) / m_cap;             // t_E
-        if (t_cap64 > 0x7FFFFFFFll) t_cap64 = 0x7FFFFFFFll;      // no time on these tables is larger
-        int64_t best_T = kInf;
+        int64_t t_cap64 = t_S;                  // the first pass: least sum at the smallest feasible cap
+        int64_t best_T = kInf, best_b = kInf;
         int passes = 0;
         for (;;) {
             const uint32_t tcap = (uint32_t)uniform((int)(uint32_t)t_cap64);
@@ -310,14 +312,30 @@ __device__ __forceinline__ void exact_body(const TablesDev &tb, const CandDev &c
             const int64_t b = uniform64((int64_t)scal[1]);
             const int64_t T = sum + (m_cap - 1) * b;
             ++passes;
-            if (T <= best_T) {
+            if (T < best_T || (T == best_T && b < best_b)) {     // equal totals: the lower cap
                 best_T = T;
+                best_b = b;
                 for (int s = tid; s <= S; s += nthreads) kept[s] = trial[s];
             }
-            if (b <= t_S) break;
-            if (sum + (m_cap - 1) * t_S > best_T) break;
-            if (b > t_cap64 || passes >= (1 << 20)) break;   // the cap must fall with every pass
-            t_cap64 = b - 1;
+            if (passes >= (1 << 20) || b > t_cap64) break;       // cannot happen: the cap falls with every pass
+            int64_t next_cap;
+            if (passes == 1) {
+                // every plan costs at least B times its bottleneck (the bottleneck is one of the
+                // terms of the sum), so nothing above t_E = ceil(T / B) can beat the total T in hand
+                next_cap = (best_T + m_cap - 1) / m_cap;
+                if (next_cap > 0x7FFFFFFFll) next_cap = 0x7FFFFFFFll;   // no time on these tables is larger
+            } else {
+                next_cap = b - 1;
+            }
+            // Sums only grow as the cap shrinks, so a plan found at or below a cap that returned
+            // the sum `sum` costs at least sum + (B - 1) b' with its own bottleneck b': it can match
+            // the best total only if b' <= (best_T - sum) / (B - 1).  Caps above that are skipped.
+            if (passes > 1 && m_cap > 1) {
+                const int64_t bound = (best_T - sum) / (m_cap - 1);
+                next_cap = next_cap < bound ? next_cap : bound;
+            }
+            if (next_cap <= t_S) break;         // the plan at t_S is already in hand
+            t_cap64 = next_cap;
         }
         __syncthreads();
         if (tid == 0 && n_passes) n_passes[c] = passes;
