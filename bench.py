@@ -27,7 +27,7 @@ LANE_OPS_PER_TRANSITION = 26
 # HBM bytes per launch of the planner kernel on the stress workload, from rocprofv3 counters
 # (profiles/plan_batch_stress_pmc.txt: FETCH_SIZE + WRITE_SIZE of k2_band and k2_fast, each scaled by
 # a plain copy's reading)
-MEASURED_TRAFFIC_BYTES = {"stress": 4.005e9 + 1.790e9 + 0.249e9 + 0.344e9}
+MEASURED_TRAFFIC_BYTES = {"stress": 3.394e9 + 1.795e9 + 0.254e9 + 0.344e9}
 
 
 def cpu_baseline(w, cands, gpu_plans, budget_candidates):
@@ -245,7 +245,7 @@ def main():
             "note": "achieved = dense-recurrence transitions per launch x 26 lane-ops / mean kernel time "
                     "(HIP events on the launch stream around harp_plan_batch); the kernels evaluate far fewer "
                     "transitions than the dense count (reachability bands, bounded scans), so this is work "
-                    "delivered, not instructions issued: VALU issue utilisation is 61% (profiles/)",
+                    "delivered, not instructions issued: VALU issue utilisation is 69% (profiles/)",
         },
     }
     if args.tables_L:
