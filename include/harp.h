@@ -192,7 +192,7 @@ int harp_plan_batch(harp_ctx *ctx, harp_tables *tables, const harp_candidates *c
  * time and iter_time its iteration time; statuses are those of harp_plan_batch.
  * n_passes: DEVICE [C] or NULL; receives the number of capped recurrences run for the candidate
  * (0 when it has no plan or a single stage).
- * Needs tables that allow the 32-bit path (harp_tables_fast32), else HARP_ERR_UNIMPLEMENTED;
+ * Kernel selection as for harp_plan_batch (harp_set_plan_path; identical results on every path);
  * workspace as for harp_plan_batch.  Asynchronous on `hip_stream`, except that the first use of a view
  * finalizes it. */
 int harp_plan_exact_batch(harp_ctx *ctx, harp_tables *tables, const harp_candidates *cands,

@@ -336,7 +336,7 @@ def plan(ctx: Context, problem, cands, path: int = PATH_AUTO):
     return out.to_host(), tables
 
 
-def plan_exact(ctx: Context, problem, cands):
+def plan_exact(ctx: Context, problem, cands, path: int = PATH_AUTO):
     """Convenience for tests: tables, exact search over a batch; host copies of the plans and of
     the number of capped passes per candidate."""
     torch = _torch()
@@ -346,6 +346,10 @@ def plan_exact(ctx: Context, problem, cands):
     out.poison()
     ws = plan_workspace(ctx, tables, dc)
     n_passes = torch.full((max(dc.C, 1),), -7, dtype=torch.int32, device=ctx.device)
-    harp_plan_exact_batch(ctx, tables, dc, out, ws, n_passes)
-    torch.cuda.synchronize()
+    ctx.set_plan_path(path)
+    try:
+        harp_plan_exact_batch(ctx, tables, dc, out, ws, n_passes)
+        torch.cuda.synchronize()
+    finally:
+        ctx.set_plan_path(PATH_AUTO)
     return out.to_host(), n_passes[:dc.C].cpu().numpy(), tables

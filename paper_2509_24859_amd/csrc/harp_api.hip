@@ -317,8 +317,8 @@ int harp_plan_exact_batch(harp_ctx *ctx, harp_tables *t, const harp_candidates *
     if (rc != HARP_OK) return rc;
     if (!out || (cd->C > 0 && (!out->splits || !out->dev_first || !out->bottleneck || !out->iter_time || !out->status)))
         return fail(ctx, HARP_ERR_INVALID_ARG, "null output array");
-    if (!t->fast32)
-        return fail(ctx, HARP_ERR_UNIMPLEMENTED, "the exact search needs tables that allow the 32-bit path");
+    if (ctx->plan_path == HARP_PATH_FAST32 && !t->fast32)
+        return fail(ctx, HARP_ERR_UNIMPLEMENTED, "the 32-bit path was requested but these tables do not allow it");
     if (cd->C == 0) return HARP_OK;
     const size_t need = harp_plan_workspace_bytes(ctx, t, cd);
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0)
@@ -329,9 +329,14 @@ int harp_plan_exact_batch(harp_ctx *ctx, harp_tables *t, const harp_candidates *
     if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
     const CandDev c = { cd->C, cd->S_max, cd->cand_S, cd->cand_group, cd->cand_tp };
     const PlansDev o = { out->splits, out->dev_first, out->bottleneck, out->iter_time, out->status };
-    const int groups = n_plan_groups(ctx, cd->C, true, t->dev.L, cd->S_max);
-    launch_plan_fast(t->dev, c, o, workspace, groups, static_cast<hipStream_t>(hip_stream));
-    launch_plan_exact(t->dev, c, o, n_passes, workspace, groups, static_cast<hipStream_t>(hip_stream));
+    const bool fast = use_fast(ctx, t);
+    const int groups = n_plan_groups(ctx, cd->C, fast, t->dev.L, cd->S_max);
+    if (fast) {
+        launch_plan_fast(t->dev, c, o, workspace, groups, static_cast<hipStream_t>(hip_stream));
+        launch_plan_exact(t->dev, c, o, n_passes, workspace, groups, static_cast<hipStream_t>(hip_stream));
+    } else {
+        launch_plan_generic_exact(t->dev, c, o, n_passes, workspace, groups, static_cast<hipStream_t>(hip_stream));
+    }
     e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(ctx, e, "launching the exact-search kernels");
     return HARP_OK;

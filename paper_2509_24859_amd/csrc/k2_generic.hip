@@ -18,16 +18,106 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
 
+// Per-workgroup slice of the workspace: two DP rows and the back-pointers.
+struct GenericSlice {
+    int64_t *D0, *D1;
+    uint16_t *arg;      // [S_max][L+1], row s = stage s
+};
+
+__device__ __forceinline__ GenericSlice generic_slice(unsigned char *ws, size_t ws_per_group, int L) {
+    unsigned char *mine = ws + size_t(blockIdx.x) * ws_per_group;
+    GenericSlice g;
+    g.D0 = reinterpret_cast<int64_t *>(mine);
+    g.D1 = g.D0 + (L + 1);
+    g.arg = reinterpret_cast<uint16_t *>(g.D1 + (L + 1));
+    return g;
+}
+
+// One pass of the recurrence over all stages of the candidate in `slots`, every thread of the
+// workgroup taking part.  kCapped = false: the min-max form, D[s+1][i] = min_j max(D[s][j], time,
+// comm).  kCapped = true: the least-sum form under a cap on every stage and transfer time
+// (section 5.2.3 with constraints (i), (ii)), D[s+1][i] = min_j D[s][j] + time + 2 comm over
+// time <= cap, cells with comm > cap unreachable.  Both keep the lowest j among equal values.
+// Returns the row that holds D[S][.].
+template <bool kCapped>
+__device__ __forceinline__ const int64_t *generic_pass(const TablesDev &tb, const SlotInfo &slots, int S,
+                                                       const GenericSlice &w, int64_t time_cap) {
+    const int L = tb.L;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t *PP = tb.PP(), *PS = tb.PS();
+    for (int i = threadIdx.x; i <= L; i += kThreads) w.D0[i] = (i == 0) ? 0 : kInf;
+    __syncthreads();
+    int64_t *Dp = w.D0, *Dn = w.D1;
+    for (int s = 0; s < S; ++s) {
+        const int g = slots.g[s], k = slots.k[s];
+        const int64_t tp = tb.tp[k];
+        const int shift = tb.tp_shift[k];
+        const int t = tb.group_type[g];
+        const int64_t *pf = tb.PF(t), *pr = tb.PR(g, k);
+        const int64_t n_inflight = (S - s) < tb.M ? (S - s) : tb.M;
+        const int64_t cap = tp * tb.type_mem[t];
+        const bool last = (s == S - 1);
+        const int64_t link = last ? 1 : tb.bw[int64_t(g) * tb.G + slots.g[s + 1]];
+        const int i_lo = last ? L : s + 1, i_hi = L - (S - 1 - s);
+        uint16_t *arg_row = w.arg + size_t(s) * (L + 1);
+        for (int i = i_lo + wave; i <= i_hi; i += kWaves) {
+            const int64_t cut = last ? 0 : (tb.act_bytes[i - 1] + link - 1) / link;
+            const int64_t pfi = pf[i], pri = pr[i], ppi = PP[i], psi = PS[i];
+            int64_t best = kInf;
+            int best_j = INT32_MAX;
+            if (!kCapped || cut <= time_cap) {
+                for (int j = s + lane; j < i; j += 64) {
+                    const int64_t dj = Dp[j];
+                    if (dj == kInf) continue;
+                    const int64_t need = (ppi - PP[j]) + n_inflight * (psi - PS[j]);
+                    if (need > cap) continue;
+                    const int64_t work = pfi - pf[j];
+                    const int64_t comp = shift >= 0 ? (work + tp - 1) >> shift : (work + tp - 1) / tp;
+                    const int64_t time = comp + (pri - pr[j]);
+                    int64_t val;
+                    if (kCapped) {
+                        if (time > time_cap) continue;
+                        val = dj + time;
+                    } else {
+                        val = time > dj ? time : dj;
+                        val = val > cut ? val : cut;
+                    }
+                    if (val < best) { best = val; best_j = j; }
+                }
+            }
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) {
+                const int64_t ov = __shfl_xor(best, d, 64);
+                const int oj = __shfl_xor(best_j, d, 64);
+                if (ov < best || (ov == best && oj < best_j)) { best = ov; best_j = oj; }
+            }
+            if (lane == 0) {
+                Dn[i] = (kCapped && best != kInf) ? best + 2 * cut : best;
+                arg_row[i] = (uint16_t)(best == kInf ? 0 : best_j);
+            }
+        }
+        __syncthreads();
+        int64_t *tmp = Dp; Dp = Dn; Dn = tmp;
+    }
+    return Dp;
+}
+
+// Thread 0: follows the back-pointers from (S, L) into cuts[0..S].
+__device__ __forceinline__ void generic_backtrack(const GenericSlice &w, int S, int L, int32_t *cuts) {
+    int b = L;
+    cuts[S] = L;
+    for (int s = S - 1; s >= 0; --s) {
+        b = w.arg[size_t(s) * (L + 1) + b];
+        cuts[s] = b;
+    }
+}
+
 __global__ __launch_bounds__(kThreads) void k2_generic(TablesDev tb, CandDev cd, PlansDev out,
                                                         unsigned char *ws, size_t ws_per_group) {
     __shared__ SlotInfo slots;
     const int L = tb.L, S_max = cd.S_max;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    unsigned char *mine = ws + size_t(blockIdx.x) * ws_per_group;
-    int64_t *D0 = reinterpret_cast<int64_t *>(mine);
-    int64_t *D1 = D0 + (L + 1);
-    uint16_t *arg = reinterpret_cast<uint16_t *>(D1 + (L + 1));   // [S_max][L+1], row s = stage s
-    const int64_t *PP = tb.PP(), *PS = tb.PS();
+    const GenericSlice w = generic_slice(ws, ws_per_group, L);
 
     for (int c = blockIdx.x; c < cd.C; c += gridDim.x) {
         __syncthreads();   // previous candidate's tail is done with the shared state
@@ -40,62 +130,13 @@ __global__ __launch_bounds__(kThreads) void k2_generic(TablesDev tb, CandDev cd,
             write_failed(out, c, S_max, status);
             continue;
         }
-        for (int i = threadIdx.x; i <= L; i += kThreads) D0[i] = (i == 0) ? 0 : kInf;
-        __syncthreads();
-        int64_t *Dp = D0, *Dn = D1;
-        for (int s = 0; s < S; ++s) {
-            const int g = slots.g[s], k = slots.k[s];
-            const int64_t tp = tb.tp[k];
-            const int shift = tb.tp_shift[k];
-            const int t = tb.group_type[g];
-            const int64_t *pf = tb.PF(t), *pr = tb.PR(g, k);
-            const int64_t n_inflight = (S - s) < tb.M ? (S - s) : tb.M;
-            const int64_t cap = tp * tb.type_mem[t];
-            const bool last = (s == S - 1);
-            const int64_t link = last ? 1 : tb.bw[int64_t(g) * tb.G + slots.g[s + 1]];
-            const int i_lo = last ? L : s + 1, i_hi = L - (S - 1 - s);
-            uint16_t *arg_row = arg + size_t(s) * (L + 1);
-            for (int i = i_lo + wave; i <= i_hi; i += kWaves) {
-                const int64_t cut = last ? 0 : (tb.act_bytes[i - 1] + link - 1) / link;
-                const int64_t pfi = pf[i], pri = pr[i], ppi = PP[i], psi = PS[i];
-                int64_t best = kInf;
-                int best_j = INT32_MAX;
-                for (int j = s + lane; j < i; j += 64) {
-                    const int64_t dj = Dp[j];
-                    if (dj == kInf) continue;
-                    const int64_t need = (ppi - PP[j]) + n_inflight * (psi - PS[j]);
-                    if (need > cap) continue;
-                    const int64_t work = pfi - pf[j];
-                    const int64_t comp = shift >= 0 ? (work + tp - 1) >> shift : (work + tp - 1) / tp;
-                    int64_t val = comp + (pri - pr[j]);
-                    val = val > dj ? val : dj;
-                    val = val > cut ? val : cut;
-                    if (val < best) { best = val; best_j = j; }
-                }
-#pragma unroll
-                for (int d = 32; d >= 1; d >>= 1) {
-                    const int64_t ov = __shfl_xor(best, d, 64);
-                    const int oj = __shfl_xor(best_j, d, 64);
-                    if (ov < best || (ov == best && oj < best_j)) { best = ov; best_j = oj; }
-                }
-                if (lane == 0) {
-                    Dn[i] = best;
-                    arg_row[i] = (uint16_t)(best == kInf ? 0 : best_j);
-                }
-            }
-            __syncthreads();
-            int64_t *tmp = Dp; Dp = Dn; Dn = tmp;
-        }
+        const int64_t *Dp = generic_pass<false>(tb, slots, S, w, 0);
         if (Dp[L] == kInf) {          // uniform: every thread reads the same cell
             write_failed(out, c, S_max, HARP_CAND_INFEASIBLE);
             continue;
         }
         int32_t *sp = out.splits + int64_t(c) * (S_max + 1);
-        if (threadIdx.x == 0) {
-            int b = L;
-            sp[S] = L;
-            for (int s = S - 1; s >= 0; --s) { b = arg[size_t(s) * (L + 1) + b]; sp[s] = b; }
-        }
+        if (threadIdx.x == 0) generic_backtrack(w, S, L, sp);
         for (int s = S + 1 + threadIdx.x; s <= S_max; s += kThreads) sp[s] = -1;
         int32_t *df = out.dev_first + int64_t(c) * S_max;
         for (int s = threadIdx.x; s < S_max; s += kThreads) df[s] = s < S ? slots.dev_first[s] : -1;
@@ -112,6 +153,95 @@ __global__ __launch_bounds__(kThreads) void k2_generic(TablesDev tb, CandDev cd,
     }
 }
 
+// The exact search (sweep over the cap of section 5.2.4 (2)) in int64, for tables without the
+// 32-bit rows: the min-max pass gives t_S, then capped least-sum passes walk the caps exactly as
+// the 32-bit kernel does (first at t_S, then down from ceil(T / B), skipping caps that the sums
+// rule out; equal totals keep the lower cap).
+__global__ __launch_bounds__(kThreads) void k2_generic_exact(TablesDev tb, CandDev cd, PlansDev out,
+                                                              int32_t *n_passes, unsigned char *ws,
+                                                              size_t ws_per_group) {
+    __shared__ SlotInfo slots;
+    __shared__ int32_t trial[kMaxStages + 1], kept[kMaxStages + 1];
+    __shared__ int64_t scored[2];
+    const int L = tb.L, S_max = cd.S_max;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const GenericSlice w = generic_slice(ws, ws_per_group, L);
+    const int64_t m_cap = tb.M;
+
+    // all threads: bottleneck and total of the cuts in trial[], by the cost model itself
+    auto score_trial = [&](int S, int64_t &bott, int64_t &total) {
+        __syncthreads();              // the cuts written by thread 0 are read by the first wave
+        if (wave == 0) {
+            int64_t b, t;
+            wave_score_partition(tb, S, slots.g, slots.k, trial, lane, b, t);
+            if (lane == 0) { scored[0] = b; scored[1] = t; }
+        }
+        __syncthreads();
+        bott = scored[0];
+        total = scored[1];
+    };
+
+    for (int c = blockIdx.x; c < cd.C; c += gridDim.x) {
+        __syncthreads();
+        const int S = cd.cand_S[c];
+        const int32_t *grp = cd.cand_group + int64_t(c) * S_max;
+        const int32_t *tpv = cd.cand_tp + int64_t(c) * S_max;
+        int status = load_and_check_slots(tb, S, S_max, grp, tpv, slots);
+        if (status == HARP_CAND_OK && S > L) status = HARP_CAND_INFEASIBLE;
+        if (status == HARP_CAND_OK && generic_pass<false>(tb, slots, S, w, 0)[L] == kInf)
+            status = HARP_CAND_INFEASIBLE;
+        if (status != HARP_CAND_OK) {
+            write_failed(out, c, S_max, status);
+            if (threadIdx.x == 0 && n_passes) n_passes[c] = 0;
+            continue;
+        }
+        if (threadIdx.x == 0) generic_backtrack(w, S, L, trial);
+        int64_t t_S, best_T, best_b;
+        score_trial(S, t_S, best_T);
+        best_b = t_S;
+        for (int s = threadIdx.x; s <= S; s += kThreads) kept[s] = trial[s];
+        int passes = 0;
+        int64_t cap = t_S;
+        while (S >= 2) {
+            const int64_t sum = generic_pass<true>(tb, slots, S, w, cap)[L];
+            if (sum == kInf) break;   // cannot happen at or above t_S
+            if (threadIdx.x == 0) generic_backtrack(w, S, L, trial);
+            int64_t b, T;
+            score_trial(S, b, T);
+            ++passes;
+            if (T < best_T || (T == best_T && b <= best_b)) {   // equal totals: the lower cap; equal caps: the capped plan
+                best_T = T;
+                best_b = b;
+                for (int s = threadIdx.x; s <= S; s += kThreads) kept[s] = trial[s];
+            }
+            if (passes >= (1 << 20) || b > cap) break;           // cannot happen: the cap falls with every pass
+            int64_t next_cap;
+            if (passes == 1) {
+                next_cap = (best_T + m_cap - 1) / m_cap;
+            } else {
+                next_cap = b - 1;
+                if (m_cap > 1) {
+                    const int64_t bound = (best_T - sum) / (m_cap - 1);
+                    next_cap = next_cap < bound ? next_cap : bound;
+                }
+            }
+            if (next_cap <= t_S) break;
+            cap = next_cap;
+        }
+        __syncthreads();
+        int32_t *sp = out.splits + int64_t(c) * (S_max + 1);
+        for (int s = threadIdx.x; s <= S_max; s += kThreads) sp[s] = s <= S ? kept[s] : -1;
+        int32_t *df = out.dev_first + int64_t(c) * S_max;
+        for (int s = threadIdx.x; s < S_max; s += kThreads) df[s] = s < S ? slots.dev_first[s] : -1;
+        if (threadIdx.x == 0) {
+            out.bottleneck[c] = best_b;
+            out.iter_time[c] = best_T;
+            out.status[c] = HARP_CAND_OK;
+            if (n_passes) n_passes[c] = passes;
+        }
+    }
+}
+
 }  // namespace
 
 size_t plan_generic_ws_per_group(int L, int S_max) {
@@ -122,6 +252,12 @@ size_t plan_generic_ws_per_group(int L, int S_max) {
 void launch_plan_generic(const TablesDev &tb, const CandDev &cd, const PlansDev &out, void *ws,
                          int n_groups, hipStream_t st) {
     hipLaunchKernelGGL(k2_generic, dim3(n_groups), dim3(kThreads), 0, st, tb, cd, out,
+                       static_cast<unsigned char *>(ws), plan_generic_ws_per_group(tb.L, cd.S_max));
+}
+
+void launch_plan_generic_exact(const TablesDev &tb, const CandDev &cd, const PlansDev &out, int32_t *n_passes,
+                               void *ws, int n_groups, hipStream_t st) {
+    hipLaunchKernelGGL(k2_generic_exact, dim3(n_groups), dim3(kThreads), 0, st, tb, cd, out, n_passes,
                        static_cast<unsigned char *>(ws), plan_generic_ws_per_group(tb.L, cd.S_max));
 }
 

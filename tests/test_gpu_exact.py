@@ -22,16 +22,20 @@ def ctx(harp):
     c.close()
 
 
-def _check(harp, ctx, problem, cands, label):
+def _check(harp, ctx, problem, cands, label, need_fast=True):
+    """Both kernel paths (int64 always, 32-bit when the tables allow it) against the oracle's sweep."""
     tables = oracle.build_tables(problem)
     want = oracle_plan_exact_threaded(tables, cands)
-    got, n_passes, dev_tables = harp.plan_exact(ctx, problem, cands)
-    assert dev_tables.fast32, label
-    assert_plans_equal(got, want, label)
     ok = (want.status == oracle.OK) & (cands.cand_S >= 2)
-    assert (n_passes[ok] >= 1).all() and (n_passes[~ok] == 0).all(), label
-    # never more capped recurrences than the increasing sweep would run, the opening pass at t_S aside
-    assert (n_passes[ok] <= want.n_caps[ok] + 1).all(), label
+    fast32 = harp.Tables(ctx, problem).fast32
+    assert fast32 or not need_fast, label
+    for path in [harp.PATH_GENERIC] + ([harp.PATH_FAST32] if fast32 else []):
+        tag = "%s (path %d)" % (label, path)
+        got, n_passes, _ = harp.plan_exact(ctx, problem, cands, path)
+        assert_plans_equal(got, want, tag)
+        assert (n_passes[ok] >= 1).all() and (n_passes[~ok] == 0).all(), tag
+        # never more capped recurrences than the increasing sweep would run, the opening pass at t_S aside
+        assert (n_passes[ok] <= want.n_caps[ok] + 1).all(), tag
     return got, want, n_passes
 
 
@@ -52,16 +56,12 @@ def test_exact_tiny(harp, ctx):
 
 
 def test_exact_random_small(harp, ctx):
-    ran = 0
+    fast_runs = 0
     for seed in range(400):
         w = W.random_small(seed)
-        cands = w.candidates()
-        dev_tables = harp.Tables(ctx, w.problem)
-        if not dev_tables.fast32:
-            continue
-        ran += 1
-        _check(harp, ctx, w.problem, cands, "seed %d" % seed)
-    assert ran > 200
+        fast_runs += harp.Tables(ctx, w.problem).fast32
+        _check(harp, ctx, w.problem, w.candidates(), "seed %d" % seed, need_fast=False)
+    assert fast_runs > 200
 
 
 @pytest.mark.parametrize("name,n,stride", [("llama7b", 1024, 1), ("llama70b", 384, 171), ("finegrained", 32, 1021),
@@ -162,27 +162,33 @@ def test_exact_sums_beyond_32_bits(harp, ctx):
     assert (sums >= 1 << 31).any() and (sums < 1 << 31).any()
 
 
-def test_exact_argument_errors(harp, ctx):
-    import torch
+def test_exact_odd_degrees_and_wide_times_use_int64_path(harp, ctx):
     rng = np.random.default_rng(9)
-    # degrees that are not powers of two: no 32-bit rows, so no exact search
-    L = 40
+    L = 50
     p = simple_problem(np.zeros(L), M=6, G=2, ndev=(6, 6), tp=(1, 2, 3, 6),
-                       fwd=rng.integers(1, 1000, size=(1, L)), bwd=rng.integers(1, 1000, size=(1, L)))
-    for problem in (p,):
-        cands = W.make_candidates(problem, 0, 79, 2, 6, 0, 8)
-        tables = harp.Tables(ctx, problem)
-        dc = harp.DeviceCandidates(ctx, cands)
-        out = harp.DevicePlans(ctx, dc.C, dc.S_max)
-        ws = harp.plan_workspace(ctx, tables, dc)
-        with pytest.raises(harp.HarpError) as e:
-            harp.harp_plan_exact_batch(ctx, tables, dc, out, ws)
-        assert e.value.code == harp.ERR_UNIMPLEMENTED
-    torch.cuda.synchronize()
-    # an empty batch is fine
+                       fwd=rng.integers(1, 1000, size=(1, L)), bwd=rng.integers(1, 1000, size=(1, L)),
+                       act=rng.integers(0, 10**5, size=L), bw=[[900, 10], [10, 700]])
+    cands = W.make_candidates(p, 0, 79, 2, 6, 0, 32)
+    _check(harp, ctx, p, cands, "odd degrees", need_fast=False)
+    assert not harp.Tables(ctx, p).fast32
+    # asking for the 32-bit path on such tables is an error, not a silent switch
+    with pytest.raises(harp.HarpError) as e:
+        harp.plan_exact(ctx, p, cands, harp.PATH_FAST32)
+    assert e.value.code == harp.ERR_UNIMPLEMENTED
+
+    L = 40
+    fwd = rng.integers(1, 1 << 36, size=(2, L))
+    p = simple_problem(np.zeros(L), M=50, T=2, G=2, ndev=(4, 4), tp=(1, 2, 4), fwd=fwd, bwd=fwd // 3,
+                       act=rng.integers(0, 1 << 40, size=L), gtype=[0, 1], bw=[[1 << 20, 5], [5, 1 << 18]])
+    cands = W.make_candidates(p, 0, 80, 2, 8, 0, 32)
+    got, want, _ = _check(harp, ctx, p, cands, "times beyond 32 bits", need_fast=False)
+    assert not harp.Tables(ctx, p).fast32 and want.iter_time.max() > (1 << 40)
+
+
+def test_exact_empty_batch(harp, ctx):
     w = W.make("tiny")
     got, n_passes, _ = harp.plan_exact(ctx, w.problem, w.candidates(0, 0))
-    assert got.status.shape == (0,)
+    assert got.status.shape == (0,) and n_passes.shape == (0,)
 
 
 def test_exact_full_stress_batch_properties(harp, ctx):
