@@ -85,6 +85,48 @@ def tables_streaming(ctx, binding, workloads, torch, L, reps=10):
             "achieved": rate / 1e9, "peak": 8000.0, "unit": "GB/s", "frac": rate / 8e12}
 
 
+def measured_peaks(ctx, binding, torch):
+    """What this GPU sustains, measured in the same run: 32-bit integer vector operations (a kernel
+    of nothing but independent add/max chains, 8 waves per SIMD) and a plain device-to-device copy."""
+    sink = torch.zeros(1, dtype=torch.int32, device=ctx.device)
+    blocks, iters = 256 * 8 * 4, 4096
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    binding.harp_measure_valu_int32(ctx, blocks, 64, sink)
+    torch.cuda.synchronize()
+    a.record()
+    binding.harp_measure_valu_int32(ctx, blocks, iters, sink)
+    b.record()
+    torch.cuda.synchronize()
+    valu = blocks * 256 * iters * 16 / (a.elapsed_time(b) * 1e-3)
+    src = torch.ones(1 << 30, dtype=torch.uint8, device=ctx.device)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    a.record()
+    for _ in range(4):
+        dst.copy_(src)
+    b.record()
+    torch.cuda.synchronize()
+    copy = 4 * 2 * src.numel() / (a.elapsed_time(b) * 1e-3)
+    del src, dst
+    return {"valu_int32_lane_ops_per_s": valu, "valu_frac_of_nominal": valu / ALU_PEAK_LANE_OPS,
+            "hbm_copy_bytes_per_s": copy, "hbm_copy_frac_of_nominal": copy / 8e12,
+            "note": "add/max chains, 8192 workgroups x 256 threads x 65536 ops per lane; "
+                    "1 GiB device-to-device copy, read + written bytes"}
+
+
+def timed_ms(torch, fn, reps):
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    fn()
+    torch.cuda.synchronize()
+    a.record()
+    for _ in range(reps):
+        fn()
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) / reps
+
+
 def exact_search(ctx, binding, torch, w, tables, dc, cands, minmax, reps, cpu_candidates):
     """The exact search (cap sweep on top of the min-max plans) over the same batch: time per call,
     capped passes per candidate, what it gains over the min-max plans, and the oracle's sweep timed
@@ -146,6 +188,7 @@ def main():
     ap.add_argument("--path", default="auto", choices=("auto", "generic", "fast32"))
     ap.add_argument("--candidates", type=int, default=0, help="use only the first N candidates")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-peaks", action="store_true", help="skip the VALU and copy micro-benchmarks")
     ap.add_argument("--cpu-candidates", type=int, default=0)
     ap.add_argument("--tables-L", type=int, default=1 << 20,
                     help="operators of the table-build streaming measurement (0 = skip)")
@@ -213,8 +256,19 @@ def main():
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
 
-    kernel_ms = sum(a.elapsed_time(b) for a, b in ev) / args.steps
+    per_step = sorted(a.elapsed_time(b) for a, b in ev)
+    kernel_ms = sum(per_step) / args.steps
     got = out.to_host()
+    # the other kernels of a step, each on its own (enqueue to enqueue, HIP events)
+    parts = {"tables_build_ms": timed_ms(torch, tables.rebuild, 20),
+             "argmin_ms": timed_ms(torch, lambda: binding.harp_argmin_batch(ctx, dc.C, out.iter_time, out.status,
+                                                                            best_t, best_i), 20)}
+    tables.finalize()
+    b2 = torch.empty(dc.C, dtype=torch.int64, device=ctx.device)
+    t2 = torch.empty_like(b2)
+    s2 = torch.empty(dc.C, dtype=torch.int32, device=ctx.device)
+    parts["score_ms"] = timed_ms(torch, lambda: binding.harp_score_1f1b(ctx, tables, dc, out.splits, b2, t2, s2), 10)
+    del b2, t2, s2
     achieved = n_trans * LANE_OPS_PER_TRANSITION / (kernel_ms * 1e-3)
     traffic = MEASURED_TRAFFIC_BYTES.get(args.workload) if C == w.C and fast else None
     result = {
@@ -236,6 +290,9 @@ def main():
         "cells_per_s": n_cells * args.steps / elapsed,
         "dense_transitions_per_s": n_trans * args.steps / elapsed,
         "plan_kernel_ms": kernel_ms,
+        "plan_kernel_ms_median": per_step[len(per_step) // 2],
+        "plan_kernel_ms_min": per_step[0],
+        "other_kernels": parts,
         "feasible_fraction": float((got.status == 0).mean()),
         "best_plan": {"index": int(best_i.item()), "iter_time_us": int(best_t.item())},
         "roofline": {
@@ -248,6 +305,10 @@ def main():
                     "delivered, not instructions issued: VALU issue utilisation is 69% (profiles/)",
         },
     }
+    if not args.no_peaks:
+        peaks = measured_peaks(ctx, binding, torch)
+        result["measured_peaks"] = peaks
+        result["roofline"]["frac_of_measured_peak"] = achieved / peaks["valu_int32_lane_ops_per_s"]
     if args.tables_L:
         result["tables_streaming"] = tables_streaming(ctx, binding, workloads, torch, args.tables_L)
     if args.exact_reps and fast:

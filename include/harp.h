@@ -213,6 +213,15 @@ int harp_score_1f1b(harp_ctx *ctx, harp_tables *tables, const harp_candidates *c
 int harp_argmin_batch(harp_ctx *ctx, int32_t C, const int64_t *iter_time, const int32_t *status,
                       int64_t *best_time, int32_t *best_index, void *hip_stream);
 
+/* Measurement support for the roofline of the planner kernels (which are bound by integer vector
+ * arithmetic, not by a contraction or by memory): launches `blocks` workgroups of 256 threads in
+ * which every lane issues iters * 16 32-bit integer vector operations (8 independent chains of one
+ * add and one max).  The caller times the launch; lane-operations = blocks * 256 * iters * 16.
+ * sink: DEVICE [1], written only in a case that practically never occurs (it keeps the arithmetic
+ * alive).  Asynchronous on `hip_stream`. */
+int harp_measure_valu_int32(harp_ctx *ctx, int32_t blocks, int32_t iters, uint32_t *sink,
+                            void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

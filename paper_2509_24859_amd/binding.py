@@ -25,7 +25,7 @@ EXPORTS = (
     "harp_build_segment_costs", "harp_tables_finalize", "harp_tables_fast32", "harp_tables_pf",
     "harp_tables_pp", "harp_tables_ps", "harp_tables_pr", "harp_tables_release",
     "harp_set_plan_path", "harp_plan_workspace_bytes", "harp_plan_batch", "harp_plan_exact_batch",
-    "harp_score_1f1b", "harp_argmin_batch",
+    "harp_score_1f1b", "harp_argmin_batch", "harp_measure_valu_int32",
 )
 
 
@@ -92,6 +92,7 @@ def load_library() -> C.CDLL:
     lib.harp_plan_exact_batch.argtypes = [vp, vp, C.POINTER(harp_candidates), C.POINTER(harp_plans), vp, vp, sz, vp]
     lib.harp_score_1f1b.argtypes = [vp, vp, C.POINTER(harp_candidates), vp, vp, vp, vp, vp]
     lib.harp_argmin_batch.argtypes = [vp, i32, vp, vp, vp, vp, vp]
+    lib.harp_measure_valu_int32.argtypes = [vp, i32, i32, vp, vp]
     _lib = lib
     return lib
 
@@ -313,6 +314,10 @@ def harp_argmin_batch(ctx: Context, C_: int, iter_time, status, best_time, best_
     ctx.check(ctx.lib.harp_argmin_batch(ctx.handle, C_, iter_time.data_ptr(), status.data_ptr(),
                                         best_time.data_ptr(), best_index.data_ptr(),
                                         _stream_handle(stream)))
+
+
+def harp_measure_valu_int32(ctx: Context, blocks: int, iters: int, sink, stream=None):
+    ctx.check(ctx.lib.harp_measure_valu_int32(ctx.handle, blocks, iters, sink.data_ptr(), _stream_handle(stream)))
 
 
 def harp_build_segment_costs(ctx: Context, problem, stream=None, finalize: bool = True) -> Tables:

@@ -371,4 +371,16 @@ int harp_argmin_batch(harp_ctx *ctx, int32_t C, const int64_t *iter_time, const 
     return HARP_OK;
 }
 
+int harp_measure_valu_int32(harp_ctx *ctx, int32_t blocks, int32_t iters, uint32_t *sink, void *hip_stream) {
+    if (!ctx) return HARP_ERR_INVALID_ARG;
+    if (blocks < 1 || blocks > (1 << 20) || iters < 1 || !sink)
+        return fail(ctx, HARP_ERR_INVALID_ARG, "blocks must be in 1..2^20, iters >= 1, sink non-null");
+    hipError_t e = hipSetDevice(ctx->device);
+    if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
+    launch_valu_int32(blocks, iters, sink, static_cast<hipStream_t>(hip_stream));
+    e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(ctx, e, "launching the VALU measurement kernel");
+    return HARP_OK;
+}
+
 }  // extern "C"

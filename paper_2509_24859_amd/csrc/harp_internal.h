@@ -91,6 +91,7 @@ void launch_plan_exact(const TablesDev &tb, const CandDev &cd, const PlansDev &o
                        void *ws, int n_groups, hipStream_t st);
 void launch_score(const TablesDev &tb, const CandDev &cd, const int32_t *splits,
                   int64_t *bottleneck, int64_t *iter_time, int32_t *status, hipStream_t st);
+void launch_valu_int32(int blocks, int iters, uint32_t *sink, hipStream_t st);
 void launch_argmin(int32_t C, const int64_t *iter_time, const int32_t *status, int64_t *best_time,
                    int32_t *best_index, hipStream_t st);
 
