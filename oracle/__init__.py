@@ -49,7 +49,8 @@ def _load():
     if _lib is None:
         _lib = C.CDLL(build())
         for name in ("oracle_build_tables", "oracle_plan_batch", "oracle_score_1f1b",
-                     "oracle_argmin_batch", "oracle_plan_exact_batch"):
+                     "oracle_argmin_batch", "oracle_plan_exact_batch", "oracle_plan_h1f1b_batch",
+                     "oracle_score_h1f1b"):
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -139,6 +140,46 @@ def plan_exact_batch(tables: Tables, cands, c_begin: int = 0, c_end: int | None 
     if rc != 0:
         raise ValueError("oracle_plan_exact_batch failed with code %d" % rc)
     return out
+
+
+def plan_h1f1b_batch(tables: Tables, cands, t_max, c_begin: int = 0, c_end: int | None = None,
+                     out: Plans | None = None) -> Plans:
+    """Capped suffix recurrence with H-1F1B warm-up counts, candidate c under the cap t_max[c];
+    `out.warmup[c][s]` = forward microbatches stage s launches during warm-up."""
+    c_end = cands.C if c_end is None else c_end
+    out = Plans(cands.C, cands.S_max) if out is None else out
+    if not hasattr(out, "warmup"):
+        out.warmup = np.full((cands.C, cands.S_max), -1, dtype=np.int32)
+    caps = np.ascontiguousarray(t_max, dtype=np.int64)
+    assert caps.shape == (cands.C,)
+    cs, cg, ct = _c32(cands.cand_S), _c32(cands.cand_group), _c32(cands.cand_tp)
+    rc = _load().oracle_plan_h1f1b_batch(
+        C.byref(tables.c), _ptr(tables.PF), _ptr(tables.PP), _ptr(tables.PS), _ptr(tables.PR),
+        C.c_int32(cands.C), C.c_int32(cands.S_max), _ptr(cs), _ptr(cg), _ptr(ct), _ptr(caps),
+        C.c_int32(c_begin), C.c_int32(c_end), _ptr(out.splits), _ptr(out.dev_first), _ptr(out.warmup),
+        _ptr(out.bottleneck), _ptr(out.iter_time), _ptr(out.status))
+    if rc != 0:
+        raise ValueError("oracle_plan_h1f1b_batch failed with code %d" % rc)
+    return out
+
+
+def score_h1f1b(tables: Tables, cands, splits, t_max):
+    """Warm-up counts, bottleneck, iteration time and status of given partitions under H-1F1B."""
+    sp = _c32(splits)
+    assert sp.shape == (cands.C, cands.S_max + 1)
+    caps = np.ascontiguousarray(t_max, dtype=np.int64)
+    cs, cg, ct = _c32(cands.cand_S), _c32(cands.cand_group), _c32(cands.cand_tp)
+    warmup = np.full((cands.C, cands.S_max), -1, dtype=np.int32)
+    bott = np.full(cands.C, INF, dtype=np.int64)
+    it = np.full(cands.C, INF, dtype=np.int64)
+    st = np.full(cands.C, -1, dtype=np.int32)
+    rc = _load().oracle_score_h1f1b(
+        C.byref(tables.c), _ptr(tables.PF), _ptr(tables.PP), _ptr(tables.PS), _ptr(tables.PR),
+        C.c_int32(cands.C), C.c_int32(cands.S_max), _ptr(cs), _ptr(cg), _ptr(ct), _ptr(sp), _ptr(caps),
+        _ptr(warmup), _ptr(bott), _ptr(it), _ptr(st))
+    if rc != 0:
+        raise ValueError("oracle_score_h1f1b failed with code %d" % rc)
+    return warmup, bott, it, st
 
 
 def score_1f1b(tables: Tables, cands, splits):

@@ -210,3 +210,94 @@ def plan_exact(p, S: int, S_max: int, grp, tp):
     bott, T = score(p, S, grp, tp, cuts)
     assert T == best_T and bott == cap
     return 0, cuts, cap, best_T
+
+
+# ---------------------------------------------------------------- H-1F1B warm-up counts
+
+def h1f1b_delta(c: int, t_max: int) -> int:
+    """Extra forward microbatches a stage launches over the next one (sections 4.1, 5.2.3):
+    ceil(2c / t_max - 1/64) + 1 in integers, the 1/64 of t_max rounded down."""
+    slack = t_max // 64
+    if 2 * c <= slack:
+        return 1
+    return 1 + _cdiv(2 * c - slack, t_max)
+
+
+def h1f1b_evaluate(p, S: int, grp, tp, b, t_max: int):
+    """Warm-up counts of the partition b under the cap t_max by eq. Ni (1 + the deltas of all later
+    cuts, never more than M), and the sum of (t + 2c); None when a stage or transfer time exceeds
+    the cap or a stage does not fit with its count."""
+    M = int(p.M)
+    deltas = [h1f1b_delta(cut_time(p, int(grp[s]), int(grp[s + 1]), b[s + 1]), t_max) for s in range(S - 1)]
+    total, counts = 0, []
+    for s in range(S):
+        n = min(M, 1 + sum(deltas[s:]))
+        t = stage_time(p, int(grp[s]), int(tp[s]), b[s], b[s + 1])
+        c = 0 if s == S - 1 else cut_time(p, int(grp[s]), int(grp[s + 1]), b[s + 1])
+        if t > t_max or c > t_max or not memory_fits(p, int(grp[s]), int(tp[s]), n, b[s], b[s + 1]):
+            return None
+        counts.append(n)
+        total += t + 2 * c
+    return counts, total
+
+
+def h1f1b_best_sum(p, S: int, grp, tp, t_max: int) -> int:
+    """Least sum of (t + 2c) over ALL partitions that are feasible under H-1F1B with the cap t_max,
+    by enumeration: a lower bound for the recurrence, which keeps only the least-sum continuation
+    of every state and may therefore miss a plan whose tail is costlier but needs fewer warm-up
+    launches."""
+    best = INF
+    if S <= int(p.L):
+        for b in partitions(int(p.L), S):
+            r = h1f1b_evaluate(p, S, grp, tp, b, t_max)
+            if r is not None:
+                best = min(best, r[1])
+    return best
+
+
+def plan_h1f1b(p, S: int, S_max: int, grp, tp, t_max: int):
+    """The capped suffix recurrence with the warm-up count carried by the least-sum continuation
+    (eq. dp_general, eq. dp_ni), written as a memoised recursion over (first operator, first slot):
+    returns (status, cuts, counts, least sum)."""
+    L, M = int(p.L), int(p.M)
+    if not valid(p, S, S_max, grp, tp):
+        return 2, None, None, INF
+    if S > L or t_max < 0:
+        return 1, None, None, INF
+    memo = {}
+
+    def state(i: int, slot: int):
+        """(least sum, count of the first stage, its end cut) for operators i.. on slots slot.."""
+        if slot == S:
+            return (0, 0, -1) if i == L else (INF, 0, -1)
+        key = (i, slot)
+        if key in memo:
+            return memo[key]
+        g, d = int(grp[slot]), int(tp[slot])
+        best = (INF, 0, -1)
+        for j in range(i + 1, L - (S - slot - 1) + 1):
+            rest, n_next, _ = state(j, slot + 1)
+            if rest == INF:
+                continue
+            c = 0 if slot == S - 1 else cut_time(p, g, int(grp[slot + 1]), j)
+            t = stage_time(p, g, d, i, j)
+            if c > t_max or t > t_max:
+                continue
+            n = min(M, h1f1b_delta(c, t_max) + n_next)
+            if not memory_fits(p, g, d, n, i, j):
+                continue
+            if rest + t + 2 * c < best[0]:
+                best = (rest + t + 2 * c, n, j)
+        memo[key] = best
+        return best
+
+    total = state(0, 0)[0]
+    if total == INF:
+        return 1, None, None, INF
+    cuts, counts, i = [0], [], 0
+    for slot in range(S):
+        _, n, j = state(i, slot)
+        counts.append(n)
+        cuts.append(j)
+        i = j
+    return 0, cuts, counts, total

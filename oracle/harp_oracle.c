@@ -480,3 +480,165 @@ int oracle_plan_exact_batch(const oracle_problem *p, const int64_t *PF, const in
     free(D0); free(D1); free(arg); free(trial); free(caps);
     return ORACLE_OK;
 }
+
+/* ---------------------------------------------------------------------------------------------
+ * H-1F1B warm-up counts inside the capped recurrence (paper sections 4.1 and 5.2.3).
+ *
+ * Under H-1F1B the last stage launches one forward microbatch during warm-up and every earlier
+ * stage launches delta more than the stage after it (eq. Ni), delta growing with the transfer
+ * time of the cut between them relative to the cap t_max.  The recurrence is the paper's own
+ * suffix form (eq. dp_general): a state is "the last s stages start at operator i"; its value is
+ * the least sum of (t + 2c) under the cap, and it carries the warm-up count N of its first stage
+ * as determined by the continuation that attained that least sum (eq. dp_ni), which the memory
+ * constraint of the stage placed in front of it then uses (eq. mem_cons).  No search over N: a
+ * continuation with a larger sum and a smaller N is not kept, as in the paper.
+ *
+ * Integer form of eq. dp_ni's increment, ceil(2c / t_max - eps) + 1 with eps = 1/64:
+ *   delta(c; t_max) = 1                                    if 2c <= floor(t_max / 64)
+ *                   = 1 + ceil((2c - floor(t_max/64)) / t_max)  otherwise   (2 or 3 when c <= t_max)
+ * and counts never exceed the number of microbatches M.
+ * ------------------------------------------------------------------------------------------- */
+static int64_t h1f1b_delta(int64_t c, int64_t t_max)
+{
+    const int64_t x = 2 * c - t_max / 64;
+    if (x <= 0) return 1;
+    return 1 + ceil_div(x, t_max);                 /* x > 0 and c <= t_max imply t_max >= 1 */
+}
+
+/* One candidate under the cap t_max.  G and N are (S+1) x (L+1) tables: G[s][i] = least sum for
+ * operators i..L-1 on the last s slots, N[s][i] = warm-up count of the first of those stages.
+ * Ties keep the lowest end cut j of the first stage.  Returns the status; fills the outputs. */
+static int plan_h1f1b_one(const tables_view *v, int S, int S_max, const int32_t *grp, const int32_t *tp,
+                          int64_t t_max, int64_t *G, int64_t *N, int32_t *arg, int32_t *splits,
+                          int32_t *dev_first, int32_t *warmup, int64_t *bott, int64_t *iter)
+{
+    const oracle_problem *p = v->p;
+    const int L = p->L;
+    fill_failed(S_max, splits, dev_first, bott, iter);
+    for (int s = 0; s < S_max; ++s) warmup[s] = -1;
+    if (!candidate_valid(p, S, S_max, grp, tp)) return CAND_INVALID;
+    if (S > L || t_max < 0) return CAND_INFEASIBLE;
+    const size_t W = (size_t)(L + 1);
+    for (size_t x = 0; x < (size_t)(S + 1) * W; ++x) { G[x] = ORACLE_INF; N[x] = 0; arg[x] = -1; }
+    G[(size_t)0 * W + L] = 0;                       /* no stages left, no operators left */
+    for (int s = 1; s <= S; ++s) {
+        const int slot = S - s;                     /* the stage this step places */
+        for (int i = slot; i <= L - s; ++i) {
+            int64_t best = ORACLE_INF, best_n = 0;
+            int32_t best_j = -1;
+            for (int j = i + 1; j <= L - (s - 1); ++j) {
+                const int64_t rest = G[(size_t)(s - 1) * W + j];
+                if (rest == ORACLE_INF) continue;
+                const int64_t c = (s == 1) ? 0 : cut_time(p, grp[slot], grp[slot + 1], j);
+                if (c > t_max) continue;                                   /* constraint (ii) */
+                const int64_t t = stage_time(v, grp[slot], tp[slot], i, j);
+                if (t > t_max) continue;                                   /* constraint (i) */
+                int64_t n = h1f1b_delta(c, t_max) + N[(size_t)(s - 1) * W + j];   /* eq. dp_ni */
+                if (n > p->M) n = p->M;
+                if (!memory_fits(v, grp[slot], tp[slot], n, i, j)) continue;      /* constraint (iii) */
+                const int64_t val = rest + t + 2 * c;
+                if (val < best) { best = val; best_j = j; best_n = n; }
+            }
+            G[(size_t)s * W + i] = best;
+            N[(size_t)s * W + i] = best_n;
+            arg[(size_t)s * W + i] = best_j;
+        }
+    }
+    if (G[(size_t)S * W + 0] == ORACLE_INF) return CAND_INFEASIBLE;
+    int64_t worst = 0;
+    int cutpos = 0;
+    for (int slot = 0; slot < S; ++slot) {
+        const int s = S - slot;
+        const int next = arg[(size_t)s * W + cutpos];
+        splits[slot] = cutpos;
+        warmup[slot] = (int32_t)N[(size_t)s * W + cutpos];
+        const int64_t c = (slot == S - 1) ? 0 : cut_time(p, grp[slot], grp[slot + 1], next);
+        worst = max64(worst, max64(stage_time(v, grp[slot], tp[slot], cutpos, next), c));
+        cutpos = next;
+    }
+    splits[S] = L;
+    if (cutpos != L) abort();
+    slot_devices(p, S, S_max, grp, tp, dev_first);
+    *bott = worst;
+    *iter = G[(size_t)S * W + 0] + (int64_t)(p->M - 1) * t_max;     /* T(t_max) of section 5.2.3 */
+    return CAND_OK;
+}
+
+/* Capped H-1F1B recurrence for candidates c_begin..c_end-1, candidate c under the cap t_max[c].
+ * splits, dev_first, status as oracle_plan_batch; warmup[c][s] = forward microbatches stage s
+ * launches during warm-up (-1 beyond S or without a plan); bottleneck = the plan's own largest
+ * stage or transfer time (<= the cap); iter_time = least sum + (M - 1) t_max[c]. */
+int oracle_plan_h1f1b_batch(const oracle_problem *p, const int64_t *PF, const int64_t *PP, const int64_t *PS,
+                            const int64_t *PR, int32_t C, int32_t S_max, const int32_t *cand_S,
+                            const int32_t *cand_group, const int32_t *cand_tp, const int64_t *t_max,
+                            int32_t c_begin, int32_t c_end, int32_t *splits, int32_t *dev_first,
+                            int32_t *warmup, int64_t *bottleneck, int64_t *iter_time, int32_t *status)
+{
+    if (C < 0 || S_max < 1 || c_begin < 0 || c_end > C || c_begin > c_end) return ORACLE_BAD_ARG;
+    if (p->L > 65535) return ORACLE_BAD_ARG;
+    const size_t cells = (size_t)(S_max + 1) * (size_t)(p->L + 1);
+    int64_t *G = (int64_t *)malloc(sizeof(int64_t) * cells);
+    int64_t *N = (int64_t *)malloc(sizeof(int64_t) * cells);
+    int32_t *arg = (int32_t *)malloc(sizeof(int32_t) * cells);
+    if (!G || !N || !arg) return ORACLE_BAD_ARG;
+    for (int32_t c = c_begin; c < c_end; ++c)
+        status[c] = plan_h1f1b_one(&(tables_view){ p, PF, PP, PS, PR }, cand_S[c], S_max,
+                                   cand_group + (size_t)c * S_max, cand_tp + (size_t)c * S_max, t_max[c],
+                                   G, N, arg, splits + (size_t)c * (S_max + 1),
+                                   dev_first + (size_t)c * S_max, warmup + (size_t)c * S_max,
+                                   bottleneck + c, iter_time + c);
+    free(G); free(N); free(arg);
+    return ORACLE_OK;
+}
+
+/* Warm-up counts and iteration time of given partitions under H-1F1B with the cap t_max[c]
+ * (section 4.1: eq. Ni, eq. delta_i in the integer form above): INVALID for a malformed candidate
+ * or cuts; INFEASIBLE when a stage or transfer time exceeds the cap or a stage does not fit in
+ * memory with its warm-up count; otherwise warmup, bottleneck (own) and sum + (M - 1) t_max. */
+int oracle_score_h1f1b(const oracle_problem *p, const int64_t *PF, const int64_t *PP, const int64_t *PS,
+                       const int64_t *PR, int32_t C, int32_t S_max, const int32_t *cand_S,
+                       const int32_t *cand_group, const int32_t *cand_tp, const int32_t *splits,
+                       const int64_t *t_max, int32_t *warmup, int64_t *bottleneck, int64_t *iter_time,
+                       int32_t *status)
+{
+    if (C < 0 || S_max < 1) return ORACLE_BAD_ARG;
+    const int L = p->L;
+    tables_view v = { p, PF, PP, PS, PR };
+    for (int32_t c = 0; c < C; ++c) {
+        const int S = cand_S[c];
+        const int32_t *grp = cand_group + (size_t)c * S_max, *tp = cand_tp + (size_t)c * S_max;
+        const int32_t *sp = splits + (size_t)c * (S_max + 1);
+        int32_t *wu = warmup + (size_t)c * S_max;
+        for (int s = 0; s < S_max; ++s) wu[s] = -1;
+        bottleneck[c] = ORACLE_INF;
+        iter_time[c] = ORACLE_INF;
+        status[c] = CAND_INVALID;
+        if (!candidate_valid(p, S, S_max, grp, tp)) continue;
+        int ok = sp[0] == 0 && sp[S] == L;
+        for (int s = 0; s < S && ok; ++s) ok = sp[s + 1] > sp[s];
+        if (!ok) continue;
+        status[c] = CAND_INFEASIBLE;
+        if (t_max[c] < 0) continue;
+        int64_t n = 0, sum = 0, worst = 0;
+        int fits = 1;
+        for (int s = S - 1; s >= 0; --s) {          /* counts accumulate from the last stage */
+            const int64_t cc = (s == S - 1) ? 0 : cut_time(p, grp[s], grp[s + 1], sp[s + 1]);
+            const int64_t t = stage_time(&v, grp[s], tp[s], sp[s], sp[s + 1]);
+            if (cc > t_max[c] || t > t_max[c]) { fits = 0; break; }
+            n += h1f1b_delta(cc, t_max[c]);
+            if (n > p->M) n = p->M;
+            if (!memory_fits(&v, grp[s], tp[s], n, sp[s], sp[s + 1])) { fits = 0; break; }
+            wu[s] = (int32_t)n;
+            sum += t + 2 * cc;
+            worst = max64(worst, max64(t, cc));
+        }
+        if (!fits) {
+            for (int s = 0; s < S_max; ++s) wu[s] = -1;
+            continue;
+        }
+        status[c] = CAND_OK;
+        bottleneck[c] = worst;
+        iter_time[c] = sum + (int64_t)(p->M - 1) * t_max[c];
+    }
+    return ORACLE_OK;
+}

@@ -497,6 +497,115 @@ def test_exact_iteration_time_monotone_as_memory_shrinks():
             prev = out
 
 
+# ---------------------------------------------------------------- H-1F1B warm-up counts
+
+def _chain_problem(cuts_us, t_max, M=16, mem=BIG, stash=0, params=0):
+    """S = len(cuts) + 1 stages of one operator each, one group of one device per stage, link s
+    carrying exactly cuts_us[s] microseconds (1 byte/us), every operator t_max long."""
+    S = len(cuts_us) + 1
+    bw = np.ones((S, S), dtype=np.int64)
+    return simple_problem([t_max] * S, M=M, G=S, ndev=(1,) * S, act=list(cuts_us) + [0], bw=bw,
+                          stash=[stash] * S, params=[params] * S, mem=[mem])
+
+
+def test_h1f1b_counts_of_the_papers_examples_and_band_edges():
+    for row in read_golden(os.path.join(GOLD, "h1f1b_warmup_examples.txt")):
+        t_max, cuts, counts = [f.strip() for f in row.split("|")]
+        cuts = [int(x) for x in cuts.split()]
+        want = [int(x) for x in counts.split()]
+        p = _chain_problem(cuts, int(t_max))
+        S = len(cuts) + 1
+        cands = cands_from_lists([[(g, 1) for g in range(S)]])
+        tables = oracle.build_tables(p)
+        out = oracle.plan_h1f1b_batch(tables, cands, [int(t_max)])
+        assert out.status[0] == oracle.OK and list(out.splits[0]) == list(range(S + 1))
+        assert list(out.warmup[0]) == want, row
+        assert out.iter_time[0] == S * int(t_max) + 2 * sum(cuts) + (p.M - 1) * int(t_max)
+        wu, b, t, st = oracle.score_h1f1b(tables, cands, out.splits, [int(t_max)])
+        assert list(wu[0]) == want and st[0] == oracle.OK and t[0] == out.iter_time[0]
+        # with two compute-balanced stages the count gap is ceil(1 + 2c/(f+b)) (the K-block lemma of
+        # section 4.2) wherever the 1/64 slack does not move the band
+        slack = int(t_max) // 64
+        for c, d in zip(cuts, np.diff(want[::-1])[::-1]):
+            if c == 0 or slack < 2 * c <= int(t_max) or int(t_max) + slack < 2 * c:
+                assert d == math.ceil(1 + 2 * c / int(t_max)) or c == 0 and d == 1
+
+
+def test_h1f1b_counts_enter_the_memory_constraint():
+    # three one-operator stages, stash 10 per operator, cuts slow then fast: counts 5, 2, 1.
+    # Stage 0 needs 5 x 10 = 50 bytes: 49 is infeasible, 50 fits; the classic schedule needs 30.
+    for mem, ok in ((50, True), (49, False)):
+        p = _chain_problem([750, 0], 1000, mem=mem, stash=10)
+        cands = cands_from_lists([[(0, 1), (1, 1), (2, 1)]])
+        tables = oracle.build_tables(p)
+        out = oracle.plan_h1f1b_batch(tables, cands, [1000])
+        assert (out.status[0] == oracle.OK) == ok
+        assert plan(p, cands).status[0] == oracle.OK
+    # counts never exceed the number of microbatches
+    p = _chain_problem([750, 750, 750], 1000, M=4)
+    out = oracle.plan_h1f1b_batch(oracle.build_tables(p), cands_from_lists([[(g, 1) for g in range(4)]]), [1000])
+    assert list(out.warmup[0]) == [4, 4, 4, 1]
+    # a cap below a transfer or stage time leaves no plan
+    p = _chain_problem([750, 0], 1000)
+    cands = cands_from_lists([[(0, 1), (1, 1), (2, 1)]])
+    for cap, st in ((999, oracle.INFEASIBLE), (1000, oracle.OK)):
+        assert oracle.plan_h1f1b_batch(oracle.build_tables(p), cands, [cap]).status[0] == st
+
+
+def test_h1f1b_recurrence_against_its_twin_and_exhaustive_enumeration():
+    n = below = 0
+    for seed in range(400):
+        w = W.random_small(seed, L_max=9, S_cap=4)
+        p, cands = w.problem, w.candidates()
+        tables = oracle.build_tables(p)
+        mm = plan(p, cands)
+        for num, den in ((1, 1), (5, 4), (3, 1)):
+            caps = np.where(mm.status == oracle.OK, mm.bottleneck // den * num, 7).astype(np.int64)
+            out = oracle.plan_h1f1b_batch(tables, cands, caps)
+            wu, sb, stt, sst = oracle.score_h1f1b(tables, cands, out.splits, caps)
+            for c in range(cands.C):
+                S, grp, tp, cap = int(cands.cand_S[c]), cands.cand_group[c], cands.cand_tp[c], int(caps[c])
+                st, cuts, counts, total = brute.plan_h1f1b(p, S, cands.S_max, grp, tp, cap)
+                assert st == out.status[c], (seed, c)
+                if st != oracle.OK:
+                    assert (out.warmup[c] == -1).all() and out.iter_time[c] == oracle.INF
+                    continue
+                n += 1
+                assert list(out.splits[c, :S + 1]) == cuts and list(out.warmup[c, :S]) == counts, (seed, c)
+                assert out.iter_time[c] == total + (p.M - 1) * cap
+                # the counts and the sum are eq. Ni and the cost model of the reported cuts
+                assert brute.h1f1b_evaluate(p, S, grp, tp, cuts, cap) == (counts, total)
+                assert (wu[c] == out.warmup[c]).all() and sst[c] == oracle.OK
+                assert sb[c] == out.bottleneck[c] <= cap and stt[c] == out.iter_time[c]
+                # never better than the true optimum over all partitions feasible under H-1F1B
+                lower = brute.h1f1b_best_sum(p, S, grp, tp, cap)
+                assert lower <= total
+                below += lower < total
+                # H-1F1B holds at least the classic number of microbatches in flight
+                assert all(counts[s] >= min(S - s, p.M) for s in range(S))
+    assert n > 4000
+    print("recurrence above the exhaustive optimum in %d of %d cases" % (below, n))
+
+
+def test_h1f1b_without_memory_pressure_equals_the_capped_least_sum():
+    for seed in range(150):
+        w = W.random_small(seed, L_max=9, S_cap=4)
+        p, cands = w.problem, w.candidates()
+        p.type_mem_bytes[:] = BIG
+        tables = oracle.build_tables(p)
+        ex = oracle.plan_exact_batch(tables, cands)
+        ok = ex.status == oracle.OK
+        caps = np.where(ok, ex.bottleneck, 0)
+        out = oracle.plan_h1f1b_batch(tables, cands, caps)
+        # at the winning cap of the exact search, without memory limits, both minimise the same sum
+        assert (out.status == ex.status).all()
+        assert (out.iter_time[ok] == ex.iter_time[ok]).all()
+        for c in np.nonzero(ok)[0]:
+            S = int(cands.cand_S[c])
+            assert out.iter_time[c] - (p.M - 1) * caps[c] == brute.opt_sum(
+                p, S, cands.cand_group[c], cands.cand_tp[c], S, p.L, int(caps[c]))
+
+
 # ---------------------------------------------------------------- the workloads themselves
 
 def test_workload_shapes_and_determinism():
