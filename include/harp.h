@@ -199,6 +199,32 @@ int harp_plan_exact_batch(harp_ctx *ctx, harp_tables *tables, const harp_candida
                           const harp_plans *out, int32_t *n_passes, void *workspace,
                           size_t workspace_bytes, void *hip_stream);
 
+/* The capped recurrence under the H-1F1B scheduler (sections 4.1 and 5.2.3): for candidate c and
+ * the cap t_max[c] on every stage and transfer time (constraints (i), (ii)), the suffix recurrence
+ * of eq. dp_general with the warm-up launch count carried in the state (eq. dp_ni) and used by the
+ * memory constraint (eq. mem_cons):
+ *   delta(c_cut; t_max) = 1 if 2 c_cut <= floor(t_max / 64), else 1 + ceil((2 c_cut - floor(t_max / 64)) / t_max)
+ *   N(last stage) = 1,  N(stage s) = min(M, delta(cut behind s) + N(stage s + 1))        (eq. Ni)
+ *   a state keeps the continuation of least sum (lowest end cut among equal sums) and its N.
+ * t_max: DEVICE [C] (negative: no plan).  warmup: DEVICE [C][S_max], receives N per stage, -1 beyond
+ * S and for candidates without a plan.  out as for harp_plan_batch, with bottleneck = the plan's own
+ * largest stage or transfer time (<= t_max[c]) and iter_time = least sum + (M - 1) t_max[c], the
+ * T(t_max) of section 5.2.3; HARP_CAND_INFEASIBLE when no partition satisfies (i)-(iii) under the
+ * cap.  Kernel selection, workspace and asynchrony as for harp_plan_batch. */
+int harp_plan_h1f1b_batch(harp_ctx *ctx, harp_tables *tables, const harp_candidates *cands,
+                          const int64_t *t_max, const harp_plans *out, int32_t *warmup,
+                          void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Warm-up counts and iteration time of caller-chosen partitions under H-1F1B with the cap
+ * t_max[c] (section 4.1, eq. Ni; delta as above): splits DEVICE [C][S_max+1], t_max DEVICE [C];
+ * outputs DEVICE: warmup [C][S_max], bottleneck (the partition's own), iter_time = sum of
+ * (t + 2c) + (M - 1) t_max[c], status.  HARP_CAND_INVALID for a malformed candidate or cuts,
+ * HARP_CAND_INFEASIBLE when a stage or transfer time exceeds the cap or a stage does not fit in
+ * memory with its count (then warmup is -1 and the times HARP_INF). */
+int harp_score_h1f1b(harp_ctx *ctx, harp_tables *tables, const harp_candidates *cands,
+                     const int32_t *splits, const int64_t *t_max, int32_t *warmup,
+                     int64_t *bottleneck, int64_t *iter_time, int32_t *status, void *hip_stream);
+
 /* Scores caller-chosen partitions with eq. gpipe_cost_model (section 5.2.2):
  * splits DEVICE [C][S_max+1].  Status HARP_CAND_INVALID when the candidate is malformed or its
  * cuts are not strictly increasing from 0 to L; HARP_CAND_INFEASIBLE when a stage does not fit

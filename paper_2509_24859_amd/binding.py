@@ -25,6 +25,7 @@ EXPORTS = (
     "harp_build_segment_costs", "harp_tables_finalize", "harp_tables_fast32", "harp_tables_pf",
     "harp_tables_pp", "harp_tables_ps", "harp_tables_pr", "harp_tables_release",
     "harp_set_plan_path", "harp_plan_workspace_bytes", "harp_plan_batch", "harp_plan_exact_batch",
+    "harp_plan_h1f1b_batch", "harp_score_h1f1b",
     "harp_score_1f1b", "harp_argmin_batch", "harp_measure_valu_int32",
 )
 
@@ -90,6 +91,8 @@ def load_library() -> C.CDLL:
     lib.harp_plan_workspace_bytes.restype = sz
     lib.harp_plan_batch.argtypes = [vp, vp, C.POINTER(harp_candidates), C.POINTER(harp_plans), vp, sz, vp]
     lib.harp_plan_exact_batch.argtypes = [vp, vp, C.POINTER(harp_candidates), C.POINTER(harp_plans), vp, vp, sz, vp]
+    lib.harp_plan_h1f1b_batch.argtypes = [vp, vp, C.POINTER(harp_candidates), vp, C.POINTER(harp_plans), vp, vp, sz, vp]
+    lib.harp_score_h1f1b.argtypes = [vp, vp, C.POINTER(harp_candidates), vp, vp, vp, vp, vp, vp, vp]
     lib.harp_score_1f1b.argtypes = [vp, vp, C.POINTER(harp_candidates), vp, vp, vp, vp, vp]
     lib.harp_argmin_batch.argtypes = [vp, i32, vp, vp, vp, vp, vp]
     lib.harp_measure_valu_int32.argtypes = [vp, i32, i32, vp, vp]
@@ -303,6 +306,20 @@ def harp_plan_exact_batch(ctx: Context, tables: Tables, dc: DeviceCandidates, ou
                                             workspace.data_ptr(), workspace.numel(), _stream_handle(stream)))
 
 
+def harp_plan_h1f1b_batch(ctx: Context, tables: Tables, dc: DeviceCandidates, t_max, out: DevicePlans,
+                          warmup, workspace, stream=None):
+    ctx.check(ctx.lib.harp_plan_h1f1b_batch(ctx.handle, tables.handle, C.byref(dc.c), t_max.data_ptr(),
+                                            C.byref(out.c), warmup.data_ptr(), workspace.data_ptr(),
+                                            workspace.numel(), _stream_handle(stream)))
+
+
+def harp_score_h1f1b(ctx: Context, tables: Tables, dc: DeviceCandidates, splits, t_max, warmup, bottleneck,
+                     iter_time, status, stream=None):
+    ctx.check(ctx.lib.harp_score_h1f1b(ctx.handle, tables.handle, C.byref(dc.c), splits.data_ptr(),
+                                       t_max.data_ptr(), warmup.data_ptr(), bottleneck.data_ptr(),
+                                       iter_time.data_ptr(), status.data_ptr(), _stream_handle(stream)))
+
+
 def harp_score_1f1b(ctx: Context, tables: Tables, dc: DeviceCandidates, splits, bottleneck,
                     iter_time, status, stream=None):
     ctx.check(ctx.lib.harp_score_1f1b(ctx.handle, tables.handle, C.byref(dc.c), splits.data_ptr(),
@@ -339,6 +356,28 @@ def plan(ctx: Context, problem, cands, path: int = PATH_AUTO):
     finally:
         ctx.set_plan_path(PATH_AUTO)
     return out.to_host(), tables
+
+
+def plan_h1f1b(ctx: Context, problem, cands, t_max, path: int = PATH_AUTO):
+    """Convenience for tests: tables, capped H-1F1B recurrence over a batch; host copies of the
+    plans (with `.warmup`) and the tables."""
+    torch = _torch()
+    tables = Tables(ctx, problem)
+    dc = DeviceCandidates(ctx, cands)
+    out = DevicePlans(ctx, dc.C, dc.S_max)
+    out.poison()
+    ws = plan_workspace(ctx, tables, dc)
+    caps = _dev(np.asarray(t_max, dtype=np.int64).reshape(-1), np.int64, ctx.device)
+    warmup = torch.full((max(dc.C, 1), dc.S_max), -7, dtype=torch.int32, device=ctx.device)
+    ctx.set_plan_path(path)
+    try:
+        harp_plan_h1f1b_batch(ctx, tables, dc, caps, out, warmup, ws)
+        torch.cuda.synchronize()
+    finally:
+        ctx.set_plan_path(PATH_AUTO)
+    got = out.to_host()
+    got.warmup = warmup[:dc.C].cpu().numpy()
+    return got, tables
 
 
 def plan_exact(ctx: Context, problem, cands, path: int = PATH_AUTO):

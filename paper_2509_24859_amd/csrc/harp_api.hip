@@ -276,8 +276,11 @@ size_t harp_plan_workspace_bytes(harp_ctx *ctx, const harp_tables *t, const harp
     if (t->dev.L > HARP_MAX_L_PLAN) return 0;
     // sized for whichever path may run, so that the answer does not depend on the build verdict
     const int C = cd->C;
-    size_t gen = size_t(n_plan_groups(ctx, C, false, t->dev.L, cd->S_max)) *
-                 plan_generic_ws_per_group(t->dev.L, cd->S_max);
+    const size_t per_group = plan_generic_ws_per_group(t->dev.L, cd->S_max) >
+                                     plan_generic_h1f1b_ws_per_group(t->dev.L, cd->S_max)
+                                 ? plan_generic_ws_per_group(t->dev.L, cd->S_max)
+                                 : plan_generic_h1f1b_ws_per_group(t->dev.L, cd->S_max);
+    size_t gen = size_t(n_plan_groups(ctx, C, false, t->dev.L, cd->S_max)) * per_group;
     size_t fast = 0;
     if (t->lim.want_fast)
         fast = plan_fast_ws_bytes(t->dev.L, cd->S_max, C, n_plan_groups(ctx, C, true, t->dev.L, cd->S_max));
@@ -339,6 +342,53 @@ int harp_plan_exact_batch(harp_ctx *ctx, harp_tables *t, const harp_candidates *
     }
     e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(ctx, e, "launching the exact-search kernels");
+    return HARP_OK;
+}
+
+int harp_plan_h1f1b_batch(harp_ctx *ctx, harp_tables *t, const harp_candidates *cd, const int64_t *t_max,
+                          const harp_plans *out, int32_t *warmup, void *workspace, size_t workspace_bytes,
+                          void *hip_stream) {
+    int rc = check_batch(ctx, t, cd);
+    if (rc != HARP_OK) return rc;
+    if (!out || (cd->C > 0 && (!out->splits || !out->dev_first || !out->bottleneck || !out->iter_time ||
+                               !out->status || !warmup || !t_max)))
+        return fail(ctx, HARP_ERR_INVALID_ARG, "null array");
+    if (ctx->plan_path == HARP_PATH_FAST32 && !t->fast32)
+        return fail(ctx, HARP_ERR_UNIMPLEMENTED, "the 32-bit path was requested but these tables do not allow it");
+    if (cd->C == 0) return HARP_OK;
+    const size_t need = harp_plan_workspace_bytes(ctx, t, cd);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0)
+        return fail(ctx, HARP_ERR_WORKSPACE, "workspace must be a 256-byte aligned device pointer");
+    if (workspace_bytes < need)
+        return fail(ctx, HARP_ERR_WORKSPACE, "workspace holds %zu bytes, %zu needed", workspace_bytes, need);
+    hipError_t e = hipSetDevice(ctx->device);
+    if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
+    const CandDev c = { cd->C, cd->S_max, cd->cand_S, cd->cand_group, cd->cand_tp };
+    const PlansDev o = { out->splits, out->dev_first, out->bottleneck, out->iter_time, out->status };
+    const bool fast = use_fast(ctx, t);
+    const int groups = n_plan_groups(ctx, cd->C, fast, t->dev.L, cd->S_max);
+    if (fast) launch_plan_h1f1b(t->dev, c, t_max, o, warmup, workspace, groups, static_cast<hipStream_t>(hip_stream));
+    else launch_plan_generic_h1f1b(t->dev, c, t_max, o, warmup, workspace, groups, static_cast<hipStream_t>(hip_stream));
+    e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(ctx, e, "launching the H-1F1B planner kernels");
+    return HARP_OK;
+}
+
+int harp_score_h1f1b(harp_ctx *ctx, harp_tables *t, const harp_candidates *cd, const int32_t *splits,
+                     const int64_t *t_max, int32_t *warmup, int64_t *bottleneck, int64_t *iter_time,
+                     int32_t *status, void *hip_stream) {
+    int rc = check_batch(ctx, t, cd);
+    if (rc != HARP_OK) return rc;
+    if (cd->C == 0) return HARP_OK;
+    if (!splits || !t_max || !warmup || !bottleneck || !iter_time || !status)
+        return fail(ctx, HARP_ERR_INVALID_ARG, "null array");
+    hipError_t e = hipSetDevice(ctx->device);
+    if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
+    const CandDev c = { cd->C, cd->S_max, cd->cand_S, cd->cand_group, cd->cand_tp };
+    launch_score_h1f1b(t->dev, c, splits, t_max, warmup, bottleneck, iter_time, status,
+                       static_cast<hipStream_t>(hip_stream));
+    e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(ctx, e, "launching the H-1F1B scorer kernel");
     return HARP_OK;
 }
 

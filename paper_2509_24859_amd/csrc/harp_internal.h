@@ -85,6 +85,15 @@ void launch_plan_generic_exact(const TablesDev &tb, const CandDev &cd, const Pla
 size_t plan_generic_ws_per_group(int L, int S_max);
 void launch_plan_fast(const TablesDev &tb, const CandDev &cd, const PlansDev &out, void *ws,
                       int n_groups, hipStream_t st);
+void launch_plan_prepass(const TablesDev &tb, const CandDev &cd, void *ws, int n_groups, hipStream_t st);
+void launch_plan_h1f1b(const TablesDev &tb, const CandDev &cd, const int64_t *t_max, const PlansDev &out,
+                       int32_t *warmup, void *ws, int n_groups, hipStream_t st);
+void launch_plan_generic_h1f1b(const TablesDev &tb, const CandDev &cd, const int64_t *t_max, const PlansDev &out,
+                               int32_t *warmup, void *ws, int n_groups, hipStream_t st);
+size_t plan_generic_h1f1b_ws_per_group(int L, int S_max);
+void launch_score_h1f1b(const TablesDev &tb, const CandDev &cd, const int32_t *splits, const int64_t *t_max,
+                        int32_t *warmup, int64_t *bottleneck, int64_t *iter_time, int32_t *status,
+                        hipStream_t st);
 size_t plan_fast_ws_bytes(int L, int S_max, int C, int n_groups);
 int plan_fast_groups(int L, int S_max, int n_cu);
 void launch_plan_exact(const TablesDev &tb, const CandDev &cd, const PlansDev &out, int32_t *n_passes,

@@ -448,8 +448,9 @@ int plan_fast_groups(int L, int S_max, int n_cu) {
     return per_cu * n_cu;
 }
 
-void launch_plan_fast(const TablesDev &tb, const CandDev &cd, const PlansDev &out, void *ws,
-                      int n_groups, hipStream_t st) {
+// Pre-pass shared by every 32-bit planner entry point: clears the counters, checks the slot lists,
+// computes the reachability bands and compacts the live and dead lists.
+void launch_plan_prepass(const TablesDev &tb, const CandDev &cd, void *ws, int n_groups, hipStream_t st) {
     const FastWorkspace w = carve(ws, tb.L, cd.S_max, cd.C, n_groups);
     hipLaunchKernelGGL(k2_clear_count, dim3(1), dim3(64), 0, st, w.counts);
     const int caps_in_lds = tb.G * tb.n_tp <= kBandCapTable ? 1 : 0;
@@ -458,6 +459,12 @@ void launch_plan_fast(const TablesDev &tb, const CandDev &cd, const PlansDev &ou
                             size_t(cd.S_max) * (bt + 2) * 2;
     hipLaunchKernelGGL(k2_band, dim3((cd.C + bt - 1) / bt), dim3(bt), band_lds, st, tb, cd, w.counts,
                        w.live_list, w.dead_list, w.bands, caps_in_lds);
+}
+
+void launch_plan_fast(const TablesDev &tb, const CandDev &cd, const PlansDev &out, void *ws,
+                      int n_groups, hipStream_t st) {
+    const FastWorkspace w = carve(ws, tb.L, cd.S_max, cd.C, n_groups);
+    launch_plan_prepass(tb, cd, ws, n_groups, st);
     hipLaunchKernelGGL(k2_fast, dim3(n_groups), dim3(kFastThreads), fast_lds_bytes(tb.L, cd.S_max), st, tb,
                        cd, out, w.counts, w.live_list, w.dead_list, w.bands, w.arg,
                        fast_arg_per_group(tb.L, cd.S_max), fast_row_len(tb.L));

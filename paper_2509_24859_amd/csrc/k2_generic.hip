@@ -242,7 +242,175 @@ __global__ __launch_bounds__(kThreads) void k2_generic_exact(TablesDev tb, CandD
     }
 }
 
+// The capped suffix recurrence with H-1F1B warm-up counts (paper sections 4.1, 5.2.3: eq.
+// dp_general, eq. dp_ni, eq. mem_cons) in int64, for tables without the 32-bit rows.  Slice of the
+// workspace: two rows of suffix sums, two of counts, the row handed to the slot in front (sum plus
+// twice the cut's transfer time; count the stage in front would have), back-pointers.
+struct H1Slice {
+    int64_t *G0, *G1, *H;
+    int32_t *N0, *N1, *NN;
+    uint16_t *arg;      // [S_max][L+1], row = slot
+};
+
+__device__ __forceinline__ H1Slice h1_slice(unsigned char *ws, size_t ws_per_group, int L) {
+    unsigned char *mine = ws + size_t(blockIdx.x) * ws_per_group;
+    H1Slice g;
+    g.G0 = reinterpret_cast<int64_t *>(mine);
+    g.G1 = g.G0 + (L + 1);
+    g.H = g.G1 + (L + 1);
+    g.N0 = reinterpret_cast<int32_t *>(g.H + (L + 1));
+    g.N1 = g.N0 + (L + 1);
+    g.NN = g.N1 + (L + 1);
+    g.arg = reinterpret_cast<uint16_t *>(g.NN + (L + 1));
+    return g;
+}
+
+__global__ __launch_bounds__(kThreads) void k2_generic_h1f1b(TablesDev tb, CandDev cd, const int64_t *t_max,
+                                                              PlansDev out, int32_t *warmup,
+                                                              unsigned char *ws, size_t ws_per_group) {
+    __shared__ SlotInfo slots;
+    __shared__ int32_t trial[kMaxStages + 1], count[kMaxStages];
+    const int L = tb.L, S_max = cd.S_max;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const H1Slice w = h1_slice(ws, ws_per_group, L);
+    const int64_t *PP = tb.PP(), *PS = tb.PS();
+    const int64_t m_cap = tb.M;
+
+    for (int c = blockIdx.x; c < cd.C; c += gridDim.x) {
+        __syncthreads();
+        const int S = cd.cand_S[c];
+        const int64_t cap_t = t_max[c];
+        const int32_t *grp = cd.cand_group + int64_t(c) * S_max;
+        const int32_t *tpv = cd.cand_tp + int64_t(c) * S_max;
+        int32_t *wu = warmup + int64_t(c) * S_max;
+        int status = load_and_check_slots(tb, S, S_max, grp, tpv, slots);
+        if (status == HARP_CAND_OK && (S > L || cap_t < 0)) status = HARP_CAND_INFEASIBLE;
+        const int64_t *Gp = w.G0;
+        if (status == HARP_CAND_OK) {
+            for (int i = threadIdx.x; i <= L; i += kThreads) { w.G0[i] = (i == L) ? 0 : kInf; w.N0[i] = 0; }
+            int64_t *Gn = w.G1;
+            int32_t *Np = w.N0, *Nn = w.N1;
+            int64_t *Gcur = w.G0;
+            for (int slot = S - 1; slot >= 0; --slot) {
+                const int s = S - slot;                     // stages from this slot to the end
+                const int g = slots.g[slot], k = slots.k[slot];
+                const int64_t tp = tb.tp[k];
+                const int shift = tb.tp_shift[k];
+                const int t = tb.group_type[g];
+                const int64_t *pf = tb.PF(t), *pr = tb.PR(g, k);
+                const int64_t capm = tp * tb.type_mem[t];
+                const bool last = (slot == S - 1);
+                const int64_t link = last ? 1 : tb.bw[int64_t(g) * tb.G + slots.g[slot + 1]];
+                const int j_lo = slot + 1, j_hi = L - (s - 1);
+                __syncthreads();                            // the previous slot's rows are complete
+                // the row handed over by the slots behind, made ready for this slot's transitions
+                for (int j = j_lo + threadIdx.x; j <= j_hi; j += kThreads) {
+                    const int64_t cut = last ? 0 : (tb.act_bytes[j - 1] + link - 1) / link;
+                    const int64_t rest = Gcur[j];
+                    w.H[j] = (rest == kInf || cut > cap_t) ? kInf : rest + 2 * cut;
+                    const int64_t x = 2 * cut - (cap_t >> 6);
+                    const int64_t n = 1 + (x > 0 ? 1 : 0) + (x > cap_t ? 1 : 0) + Np[j];
+                    w.NN[j] = int32_t(n < m_cap ? n : m_cap);
+                }
+                __syncthreads();
+                const int i_lo = slot, i_hi = slot == 0 ? 0 : L - s;
+                uint16_t *arg_row = w.arg + size_t(slot) * (L + 1);
+                for (int i = i_lo + wave; i <= i_hi; i += kWaves) {
+                    const int64_t pfi = pf[i], pri = pr[i], ppi = PP[i], psi = PS[i];
+                    int64_t best = kInf;
+                    int best_j = INT32_MAX, best_n = 0;
+                    for (int j = (i + 1 > j_lo ? i + 1 : j_lo) + lane; j <= j_hi; j += 64) {
+                        const int64_t h = w.H[j];
+                        if (h == kInf) continue;
+                        const int64_t work = pf[j] - pfi;
+                        const int64_t comp = shift >= 0 ? (work + tp - 1) >> shift : (work + tp - 1) / tp;
+                        const int64_t time = comp + (pr[j] - pri);
+                        if (time > cap_t) continue;
+                        const int n = w.NN[j];
+                        if ((PP[j] - ppi) + int64_t(n) * (PS[j] - psi) > capm) continue;
+                        const int64_t val = h + time;
+                        if (val < best) { best = val; best_j = j; best_n = n; }   // j rises within a lane
+                    }
+#pragma unroll
+                    for (int d = 32; d >= 1; d >>= 1) {
+                        const int64_t ov = __shfl_xor(best, d, 64);
+                        const int oj = __shfl_xor(best_j, d, 64);
+                        const int on = __shfl_xor(best_n, d, 64);
+                        if (ov < best || (ov == best && oj < best_j)) { best = ov; best_j = oj; best_n = on; }
+                    }
+                    if (lane == 0) {
+                        Gn[i] = best;
+                        Nn[i] = best_n;
+                        arg_row[i] = (uint16_t)(best == kInf ? 0 : best_j);
+                    }
+                }
+                // cells of the next slot read Gn over [slot, ...]: everything it may touch is written
+                // above, except starts this slot cannot use
+                for (int i = i_hi + 1 + threadIdx.x; i <= L; i += kThreads) { Gn[i] = kInf; Nn[i] = 0; }
+                int64_t *tg = Gcur; Gcur = Gn; Gn = tg;
+                int32_t *tn = Np; Np = Nn; Nn = tn;
+            }
+            __syncthreads();
+            Gp = Gcur;
+            if (Gp[0] == kInf) status = HARP_CAND_INFEASIBLE;
+        }
+        if (status != HARP_CAND_OK) {
+            write_failed(out, c, S_max, status);
+            for (int s = threadIdx.x; s < S_max; s += kThreads) wu[s] = -1;
+            continue;
+        }
+        const int64_t sum = Gp[0];
+        if (threadIdx.x == 0) {
+            int b = 0;
+            for (int slot = 0; slot < S; ++slot) { trial[slot] = b; b = w.arg[size_t(slot) * (L + 1) + b]; }
+            trial[S] = b;
+            // counts by eq. Ni along the plan, from the last stage backwards
+            int64_t n = 0;
+            for (int slot = S - 1; slot >= 0; --slot) {
+                int64_t cut = 0;
+                if (slot < S - 1) {
+                    const int64_t link = tb.bw[int64_t(slots.g[slot]) * tb.G + slots.g[slot + 1]];
+                    cut = (tb.act_bytes[trial[slot + 1] - 1] + link - 1) / link;
+                }
+                const int64_t x = 2 * cut - (cap_t >> 6);
+                n += 1 + (x > 0 ? 1 : 0) + (x > cap_t ? 1 : 0);
+                n = n < m_cap ? n : m_cap;
+                count[slot] = int32_t(n);
+            }
+        }
+        __syncthreads();
+        int32_t *sp = out.splits + int64_t(c) * (S_max + 1);
+        for (int s = threadIdx.x; s <= S_max; s += kThreads) sp[s] = s <= S ? trial[s] : -1;
+        int32_t *df = out.dev_first + int64_t(c) * S_max;
+        for (int s = threadIdx.x; s < S_max; s += kThreads) {
+            df[s] = s < S ? slots.dev_first[s] : -1;
+            wu[s] = s < S ? count[s] : -1;
+        }
+        if (wave == 0) {
+            int64_t bott, iter;
+            wave_score_partition(tb, S, slots.g, slots.k, trial, lane, bott, iter);   // the plan's own bottleneck
+            if (lane == 0) {
+                out.bottleneck[c] = bott;
+                out.iter_time[c] = sum + (m_cap - 1) * cap_t;
+                out.status[c] = HARP_CAND_OK;
+            }
+        }
+    }
+}
+
 }  // namespace
+
+size_t plan_generic_h1f1b_ws_per_group(int L, int S_max) {
+    size_t b = size_t(3) * (L + 1) * sizeof(int64_t) + size_t(3) * (L + 1) * sizeof(int32_t) +
+               size_t(S_max) * (L + 1) * sizeof(uint16_t);
+    return (b + 255) & ~size_t(255);
+}
+
+void launch_plan_generic_h1f1b(const TablesDev &tb, const CandDev &cd, const int64_t *t_max, const PlansDev &out,
+                               int32_t *warmup, void *ws, int n_groups, hipStream_t st) {
+    hipLaunchKernelGGL(k2_generic_h1f1b, dim3(n_groups), dim3(kThreads), 0, st, tb, cd, t_max, out, warmup,
+                       static_cast<unsigned char *>(ws), plan_generic_h1f1b_ws_per_group(tb.L, cd.S_max));
+}
 
 size_t plan_generic_ws_per_group(int L, int S_max) {
     size_t b = size_t(2) * (L + 1) * sizeof(int64_t) + size_t(S_max) * (L + 1) * sizeof(uint16_t);

@@ -1,0 +1,311 @@
+// The capped recurrence with H-1F1B warm-up counts (paper sections 4.1 and 5.2.3), 32-bit path.
+//
+// Under H-1F1B the last stage launches one forward microbatch during warm-up and every earlier
+// stage launches delta more than the stage after it (eq. Ni), with delta in {1, 2, 3} growing with
+// the transfer time of the cut between them relative to the cap t_max (eq. dp_ni; integer form:
+// slack = t_max / 64 rounded down, delta = 1 if 2c <= slack, 2 if 2c - slack <= t_max, else 3).
+// A stage's memory need depends on its count (eq. mem_cons), and the count depends on everything
+// behind the stage, so the recurrence runs in the paper's own suffix direction (eq. dp_general):
+// the state "the last stages, from slot sigma on, start at operator i" holds the least sum of
+// (t + 2c) under the cap and carries the warm-up count of its first stage as determined by the
+// continuation that attained the least sum.  Counts never exceed the number of microbatches.
+//
+// Mapping: as in the min-max kernel, one workgroup per live candidate at a time, one lane per cell
+// of the current slot's reachability band (the bands of the pre-pass were computed with the classic
+// 1F1B counts, which are never larger than H-1F1B's, so they remain outer bounds), rows in LDS.
+// The row handed from slot sigma+1 to slot sigma is stored ready for use: entry j holds the
+// suffix sum plus twice the transfer time of the cut at j (infinity when that transfer exceeds the
+// cap) and the count the stage in front of j would have, so a transition is one stage time, one
+// memory test and one add.  Scans run upwards in j (the stage time grows with j and stops the scan
+// at the cap; so does the stage's memory need at the smallest possible count), with a strict
+// comparison, which keeps the lowest j among equal sums.
+//
+// Sums are 32-bit while they stay below 2^31 - 1 - cap, so that a stored sum plus any admissible
+// stage time cannot reach infinity (2^31); a candidate for which some cell would exceed that is
+// queued and redone by the instantiation with 64-bit sums.
+#include "fast_common.h"
+#include "harp_internal.h"
+#include "plan_common.h"
+
+namespace harp {
+
+using namespace fastdp;
+
+namespace {
+
+constexpr int kTail = 4;     // spare entries behind a row: a group of four may overrun the band
+
+template <typename SumT> struct H1Traits;
+template <> struct H1Traits<uint32_t> {
+    static constexpr uint32_t inf = 0x80000000u;
+    struct alignas(8) Entry { uint32_t h, nn; };
+};
+template <> struct H1Traits<uint64_t> {
+    static constexpr uint64_t inf = uint64_t(1) << 62;
+    struct alignas(16) Entry { uint64_t h; uint32_t nn; uint32_t unused; };
+};
+
+struct alignas(16) MemPair { int64_t pp, ps; };
+
+// c <= cap, so the quotient of eq. dp_ni is 0, 1 or 2 and needs no division.
+__device__ __forceinline__ uint32_t h1f1b_delta(uint32_t c, int64_t cap) {
+    const int64_t x = 2 * int64_t(c) - (cap >> 6);
+    return 1u + (x > 0 ? 1u : 0u) + (x > cap ? 1u : 0u);
+}
+
+// counts: [0] live, [1] dead, [2] queued for 64-bit sums, [6] and [7] tickets of the two kernels.
+template <typename SumT>
+__device__ __forceinline__ void h1f1b_body(const TablesDev &tb, const CandDev &cd, const int64_t *t_max,
+                                           const PlansDev &out, int32_t *warmup, int *counts,
+                                           const int32_t *live_list, uint32_t *dead_list,
+                                           const uint32_t *bands, unsigned char *arg_base,
+                                           size_t arg_per_group, int row_len, int arg_pitch) {
+    using Entry = typename H1Traits<SumT>::Entry;
+    constexpr SumT kInfSum = H1Traits<SumT>::inf;
+    constexpr bool kWide = sizeof(SumT) == 8;
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+
+    const int L = tb.L, S_max = cd.S_max;
+    const int tid = threadIdx.x, lane = tid & 63, nthreads = blockDim.x;
+    const int wave = uniform(tid >> 6);
+    MemPair *mem = reinterpret_cast<MemPair *>(lds_raw);                               // [row_len]
+    Entry *rows = reinterpret_cast<Entry *>(mem + row_len);                            // [2][row_len]
+    uint32_t *prow = reinterpret_cast<uint32_t *>(rows + 2 * row_len);                 // [row_len]
+    StageConst *sc = reinterpret_cast<StageConst *>(prow + row_len);                   // [S_max]
+    uint64_t *scal = reinterpret_cast<uint64_t *>(sc + S_max);                         // [2]
+    uint32_t *band = reinterpret_cast<uint32_t *>(scal + 2);                           // [S_max + 1]
+    int32_t *trial = reinterpret_cast<int32_t *>(band + S_max + 1);                    // [S_max + 1]
+    uint32_t *flags = reinterpret_cast<uint32_t *>(trial + S_max + 1);                 // [2]: ticket, overflow
+    uint16_t *slot_g = reinterpret_cast<uint16_t *>(flags + 2);                        // [S_max]
+    uint8_t *slot_k = reinterpret_cast<uint8_t *>(slot_g + S_max);                     // [S_max]
+    uint16_t *arg = reinterpret_cast<uint16_t *>(arg_base + size_t(blockIdx.x) * arg_per_group);
+    const int n_dead = counts[1];
+    const int n_items = kWide ? counts[2] : counts[0];
+    int *next_item = counts + (kWide ? 7 : 6);
+    const int64_t m_cap = tb.M;
+
+    // the running sums of parameter and stash bytes are the same for every candidate
+    {
+        const int64_t *PP = tb.PP(), *PS = tb.PS();
+        for (int j = tid; j <= L; j += nthreads) mem[j] = MemPair{PP[j], PS[j]};
+    }
+
+    for (;;) {
+        __syncthreads();   // the previous candidate's tail has finished with LDS
+        if (tid == 0) { flags[0] = (uint32_t)atomicAdd(next_item, 1); flags[1] = 0; }
+        __syncthreads();
+        const int n = uniform((int)flags[0]);
+        if (n >= n_items) break;
+        const int c = kWide ? int(dead_list[n_dead + n]) : live_list[n];
+        const int S = cd.cand_S[c];
+        const int64_t cap64 = t_max[c];
+        int32_t *sp = out.splits + int64_t(c) * (S_max + 1);
+        int32_t *df = out.dev_first + int64_t(c) * S_max;
+        int32_t *wu = warmup + int64_t(c) * S_max;
+        if (cap64 < 0) {              // no time fits under a negative cap
+            write_failed(out, c, S_max, HARP_CAND_INFEASIBLE);
+            for (int s = tid; s < S_max; s += nthreads) wu[s] = -1;
+            continue;
+        }
+        const uint32_t tcap = (uint32_t)(cap64 > 0x7FFFFFFFll ? 0x7FFFFFFFll : cap64);   // no time here is larger
+        {
+            const int32_t *grp = cd.cand_group + int64_t(c) * S_max;
+            const int32_t *tpv = cd.cand_tp + int64_t(c) * S_max;
+            for (int s = tid; s < S; s += nthreads) {
+                const int g = grp[s], k = tp_index(tb, tpv[s]);
+                const int g_next = s + 1 < S ? grp[s + 1] : g;
+                slot_g[s] = (uint16_t)g;
+                slot_k[s] = (uint8_t)k;
+                sc[s].cap = int64_t(tb.tp[k]) * tb.type_mem[tb.group_type[g]];
+                sc[s].p_row = uint32_t((int64_t(g) * tb.n_tp + k) * tb.pitch32);
+                sc[s].cm_row_shift = uint32_t((int64_t(g) * tb.G + g_next) * tb.pitch32) |
+                                     (uint32_t(tb.tp_shift[k]) << 27);
+                int32_t first = tb.group_base[g];
+                for (int q = s - 1; q >= 0 && grp[q] == g; --q) first += tpv[q];
+                df[s] = first;
+            }
+            for (int s = S + tid; s < S_max; s += nthreads) df[s] = -1;
+            for (int s = tid; s <= S; s += nthreads) band[s] = bands[int64_t(s) * cd.C + c];
+            // behind the last stage: no operators left, nothing launched yet; the last stage itself
+            // adds delta(0) = 1
+            if (tid == 0) { rows[L].h = 0; rows[L].nn = 1; }
+            if (tid >= 1 && tid <= kTail) rows[L + tid].h = kInfSum;
+        }
+        // stored sums stay this small, so that adding an admissible stage time cannot reach infinity
+        const uint64_t limit = kWide ? uint64_t(kInfSum) - 1 : uint64_t(kInfSum) - 1 - tcap;
+        int cur = 0;
+        for (int slot = S - 1; slot >= 0; --slot) {
+            __syncthreads();      // slot constants are in LDS; the previous slot is done with prow
+            const uint32_t b0 = (uint32_t)uniform((int)band[slot]);
+            const uint32_t b1 = (uint32_t)uniform((int)band[slot + 1]);
+            const int il = slot == 0 ? 0 : band_lo(b0), ih = slot == 0 ? 0 : band_hi(b0);   // cells
+            const int jl = band_lo(b1), jh = band_hi(b1);                                     // continuations
+            const uint32_t rsv = (uint32_t)uniform((int)sc[slot].cm_row_shift);
+            const int shift = int(rsv >> 27);
+            const uint32_t tp = 1u << shift;
+            const int64_t capm = uniform64(sc[slot].cap);
+            {
+                const uint32_t *p32 = tb.P32 + (uint32_t)uniform((int)sc[slot].p_row);
+                for (int x = il + tid; x <= jh; x += nthreads) prow[x] = p32[x];
+            }
+            __syncthreads();
+            const Entry *prev = rows + cur * row_len;
+            Entry *next = rows + (cur ^ 1) * row_len;
+            // the cut in front of this slot's stage (between slot - 1 and slot)
+            const uint32_t *cm_front = slot > 0 ? tb.CM + ((uint32_t)uniform((int)sc[slot - 1].cm_row_shift) & kRowMask)
+                                                : nullptr;
+            for (int i = il + tid; i <= ih; i += nthreads) {
+                const MemPair mi = mem[i];
+                const uint32_t xi = prow[i];
+                SumT best = kInfSum;
+                uint32_t best_n = 0;
+                int best_j = 0;
+                int j = (i + 1) > jl ? (i + 1) : jl;
+                bool more = j <= jh;
+                while (more) {
+                    uint32_t tj = 0;
+                    int64_t least = 0;
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const Entry e = prev[j + u];
+                        const MemPair mj = mem[(j + u) <= L ? (j + u) : L];
+                        tj = (prow[(j + u) <= L ? (j + u) : L] + tp - 1 - xi) >> shift;
+                        const int64_t dpp = mj.pp - mi.pp, dps = mj.ps - mi.ps;
+                        least = dpp + dps;                                   // need at the smallest count
+                        const bool fits = dpp + int64_t(e.nn) * dps <= capm;
+                        const SumT v = e.h + tj;
+                        const bool upd = fits & (tj <= tcap) & (v < best) & ((j + u) <= jh);
+                        best = upd ? v : best;
+                        best_n = upd ? e.nn : best_n;
+                        best_j = upd ? (j + u) : best_j;
+                    }
+                    more = ((j + 4) <= jh) & (tj <= tcap) & (least <= capm);
+                    j += 4;
+                }
+                arg[slot * arg_pitch + i] = (uint16_t)best_j;
+                if (slot > 0) {
+                    const uint32_t cf = cm_front[i];
+                    const uint64_t total = uint64_t(best) + 2ull * cf;
+                    const bool reach = (best < kInfSum) & (cf <= tcap);
+                    if (reach & (total > limit)) flags[1] = 1;        // needs 64-bit sums
+                    next[i].h = (reach & (total <= limit)) ? SumT(total) : kInfSum;
+                    const uint32_t nn = h1f1b_delta(cf, cap64) + best_n;
+                    next[i].nn = nn < uint32_t(m_cap) ? nn : uint32_t(m_cap);
+                } else {
+                    scal[0] = uint64_t(best);
+                }
+            }
+            if (slot > 0 && tid < kTail) next[ih + 1 + tid].h = kInfSum;     // behind the band
+            cur ^= 1;
+        }
+        __syncthreads();
+        if (!kWide && uniform((int)flags[1]) != 0) {
+            if (tid == 0) dead_list[n_dead + atomicAdd(&counts[2], 1)] = uint32_t(c);
+            continue;
+        }
+        const uint64_t sum = (uint64_t)uniform64((int64_t)scal[0]);
+        if (sum >= uint64_t(kInfSum)) {
+            write_failed(out, c, S_max, HARP_CAND_INFEASIBLE);
+            for (int s = tid; s < S_max; s += nthreads) wu[s] = -1;
+            continue;
+        }
+        if (tid == 0) {
+            int b = 0;
+            for (int slot = 0; slot < S; ++slot) {
+                trial[slot] = b;
+                b = arg[slot * arg_pitch + b];
+                b = b <= L ? b : L;      // a finite sum only chains through cuts inside the row
+            }
+            trial[S] = b;
+        }
+        __syncthreads();
+        // one lane per stage: the plan's own bottleneck, and the counts by eq. Ni along the plan
+        if (wave == 0) {
+            uint32_t w = 0;
+            for (int s = lane; s < S; s += 64) {
+                const int j = trial[s], i = trial[s + 1];
+                const uint32_t rsl = sc[s].cm_row_shift;
+                const int shift = int(rsl >> 27);
+                const uint32_t *p = tb.P32 + sc[s].p_row;
+                const uint32_t t = (p[i] + (1u << shift) - 1u - p[j]) >> shift;
+                const uint32_t cu = s < S - 1 ? tb.CM[(rsl & kRowMask) + uint32_t(i)] : 0u;
+                const uint32_t m = t > cu ? t : cu;
+                w = w > m ? w : m;
+                prow[s] = s < S - 1 ? h1f1b_delta(cu, cap64) : 1u;     // prow is free now: the deltas
+            }
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) {
+                const uint32_t ow = __shfl_xor(w, d, 64);
+                w = w > ow ? w : ow;
+            }
+            if (lane == 0) {
+                out.bottleneck[c] = int64_t(w);
+                out.iter_time[c] = int64_t(sum) + (m_cap - 1) * cap64;
+                out.status[c] = HARP_CAND_OK;
+            }
+        }
+        __syncthreads();
+        if (tid == 0) {
+            uint32_t nrun = 0;
+            for (int s = S - 1; s >= 0; --s) {
+                nrun += prow[s];
+                nrun = nrun < uint32_t(m_cap) ? nrun : uint32_t(m_cap);
+                wu[s] = int32_t(nrun);
+            }
+        }
+        for (int s = tid; s <= S_max; s += nthreads) sp[s] = s <= S ? trial[s] : -1;
+        for (int s = S + tid; s < S_max; s += nthreads) wu[s] = -1;
+    }
+    // candidates the pre-pass rejected: no plan to report
+    if (!kWide) {
+        for (int n = blockIdx.x; n < n_dead; n += gridDim.x) {
+            const uint32_t e = dead_list[n];
+            const int c = int(e & ((1u << kDeadStatusShift) - 1u));
+            write_failed(out, c, S_max, int(e >> kDeadStatusShift));
+            for (int s = tid; s < S_max; s += nthreads) warmup[int64_t(c) * S_max + s] = -1;
+        }
+    }
+}
+
+__global__ __launch_bounds__(kFastThreads) __attribute__((amdgpu_waves_per_eu(8, 8)))
+void k2_h1f1b(TablesDev tb, CandDev cd, const int64_t *t_max, PlansDev out, int32_t *warmup, int *counts,
+              const int32_t *live_list, uint32_t *dead_list, const uint32_t *bands, unsigned char *arg_base,
+              size_t arg_per_group, int row_len, int arg_pitch) {
+    h1f1b_body<uint32_t>(tb, cd, t_max, out, warmup, counts, live_list, dead_list, bands, arg_base,
+                         arg_per_group, row_len, arg_pitch);
+}
+
+__global__ __launch_bounds__(kFastThreads)
+void k2_h1f1b_wide(TablesDev tb, CandDev cd, const int64_t *t_max, PlansDev out, int32_t *warmup, int *counts,
+                   const int32_t *live_list, uint32_t *dead_list, const uint32_t *bands,
+                   unsigned char *arg_base, size_t arg_per_group, int row_len, int arg_pitch) {
+    h1f1b_body<uint64_t>(tb, cd, t_max, out, warmup, counts, live_list, dead_list, bands, arg_base,
+                         arg_per_group, row_len, arg_pitch);
+}
+
+int h1f1b_row_len(int L) { return (L + 1 + kTail + 7) / 8 * 8; }
+
+size_t h1f1b_lds_bytes(int L, int S_max, size_t entry) {
+    size_t b = size_t(h1f1b_row_len(L)) * (sizeof(MemPair) + 2 * entry + 4) + size_t(S_max) * sizeof(StageConst) +
+               16 + size_t(S_max + 1) * 8 + 8 + size_t(S_max) * 3;
+    return (b + 15) & ~size_t(15);
+}
+
+}  // namespace
+
+// Runs the pre-pass itself (launch_plan_fast's first two kernels are shared through
+// launch_plan_prepass) and then the two instantiations.
+void launch_plan_h1f1b(const TablesDev &tb, const CandDev &cd, const int64_t *t_max, const PlansDev &out,
+                       int32_t *warmup, void *ws, int n_groups, hipStream_t st) {
+    const FastWorkspace w = carve(ws, tb.L, cd.S_max, cd.C, n_groups);
+    launch_plan_prepass(tb, cd, ws, n_groups, st);
+    const int row_len = h1f1b_row_len(tb.L);
+    hipLaunchKernelGGL(k2_h1f1b, dim3(n_groups), dim3(kFastThreads), h1f1b_lds_bytes(tb.L, cd.S_max, 8), st, tb,
+                       cd, t_max, out, warmup, w.counts, w.live_list, w.dead_list, w.bands, w.arg,
+                       fast_arg_per_group(tb.L, cd.S_max), row_len, fast_row_len(tb.L));
+    hipLaunchKernelGGL(k2_h1f1b_wide, dim3(n_groups), dim3(kFastThreads), h1f1b_lds_bytes(tb.L, cd.S_max, 16),
+                       st, tb, cd, t_max, out, warmup, w.counts, w.live_list, w.dead_list, w.bands, w.arg,
+                       fast_arg_per_group(tb.L, cd.S_max), row_len, fast_row_len(tb.L));
+}
+
+}  // namespace harp

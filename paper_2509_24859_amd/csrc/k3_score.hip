@@ -33,6 +33,88 @@ __global__ __launch_bounds__(64) void k3_score(TablesDev tb, CandDev cd, const i
     }
 }
 
+// H-1F1B counterpart of k3_score (paper section 4.1: eq. Ni with the integer form of eq. dp_ni's
+// increment): warm-up counts of caller-chosen partitions under the cap t_max[c], the memory
+// constraint with those counts, and sum + (M - 1) t_max.  One wavefront per candidate: lanes
+// compute the per-stage terms, lane 0 accumulates the counts from the last stage backwards.
+__global__ __launch_bounds__(64) void k3_score_h1f1b(TablesDev tb, CandDev cd, const int32_t *splits,
+                                                     const int64_t *t_max, int32_t *warmup,
+                                                     int64_t *bottleneck, int64_t *iter_time, int32_t *status) {
+    __shared__ SlotInfo slots;
+    __shared__ int32_t count[kMaxStages];
+    const int S_max = cd.S_max, L = tb.L, lane = threadIdx.x;
+    const int64_t *PP = tb.PP(), *PS = tb.PS();
+    for (int c = blockIdx.x; c < cd.C; c += gridDim.x) {
+        __syncthreads();
+        const int S = cd.cand_S[c];
+        const int32_t *sp = splits + int64_t(c) * (S_max + 1);
+        int32_t *wu = warmup + int64_t(c) * S_max;
+        const int64_t cap = t_max[c];
+        int st = load_and_check_slots(tb, S, S_max, cd.cand_group + int64_t(c) * S_max,
+                                      cd.cand_tp + int64_t(c) * S_max, slots);
+        if (st == HARP_CAND_OK) {
+            int invalid = (lane == 0 && (sp[0] != 0 || sp[S] != L)) ? 1 : 0;
+            for (int s = lane; s < S; s += 64)
+                if (sp[s + 1] <= sp[s]) invalid = 1;
+            if (__any(invalid)) st = HARP_CAND_INVALID;
+        }
+        int64_t worst = 0, sum = 0;
+        if (st == HARP_CAND_OK) {
+            int over = cap < 0 ? 1 : 0;
+            for (int s = lane; s < S; s += 64) {
+                const int g = slots.g[s], k = slots.k[s];
+                const int64_t tp = tb.tp[k];
+                const int j = sp[s], i = sp[s + 1];
+                const int64_t *pf = tb.PF(tb.group_type[g]), *pr = tb.PR(g, k);
+                const int64_t time = (pf[i] - pf[j] + tp - 1) / tp + (pr[i] - pr[j]);
+                int64_t cut = 0;
+                if (s < S - 1) {
+                    const int64_t link = tb.bw[int64_t(g) * tb.G + slots.g[s + 1]];
+                    cut = (tb.act_bytes[i - 1] + link - 1) / link;
+                }
+                if (time > cap || cut > cap) over = 1;
+                const int64_t x = 2 * cut - (cap >> 6);
+                count[s] = 1 + (x > 0 ? 1 : 0) + (x > cap ? 1 : 0);     // delta; cut <= cap bounds the quotient by 2
+                const int64_t m = time > cut ? time : cut;
+                worst = worst > m ? worst : m;
+                sum += time + 2 * cut;
+            }
+            if (__any(over)) st = HARP_CAND_INFEASIBLE;
+        }
+        __syncthreads();
+        if (st == HARP_CAND_OK) {
+            if (lane == 0) {
+                int64_t n = 0;
+                for (int s = S - 1; s >= 0; --s) {
+                    n += count[s];
+                    n = n < tb.M ? n : tb.M;
+                    count[s] = int32_t(n);
+                }
+            }
+            __syncthreads();
+            int unfit = 0;
+            for (int s = lane; s < S; s += 64) {
+                const int j = sp[s], i = sp[s + 1];
+                const int64_t need = (PP[i] - PP[j]) + int64_t(count[s]) * (PS[i] - PS[j]);
+                if (need > int64_t(tb.tp[slots.k[s]]) * tb.type_mem[tb.group_type[slots.g[s]]]) unfit = 1;
+            }
+            if (__any(unfit)) st = HARP_CAND_INFEASIBLE;
+        }
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) {
+            const int64_t ow = __shfl_xor(worst, d, 64);
+            sum += __shfl_xor(sum, d, 64);
+            worst = worst > ow ? worst : ow;
+        }
+        for (int s = lane; s < S_max; s += 64) wu[s] = (st == HARP_CAND_OK && s < S) ? count[s] : -1;
+        if (lane == 0) {
+            bottleneck[c] = st == HARP_CAND_OK ? worst : kInf;
+            iter_time[c] = st == HARP_CAND_OK ? sum + int64_t(tb.M - 1) * cap : kInf;
+            status[c] = st;
+        }
+    }
+}
+
 constexpr int kArgminThreads = 1024;
 
 __global__ __launch_bounds__(kArgminThreads) void k4_argmin(int32_t C, const int64_t *iter_time,
@@ -85,6 +167,15 @@ void launch_score(const TablesDev &tb, const CandDev &cd, const int32_t *splits,
     const int groups = cd.C < (1 << 20) ? cd.C : (1 << 20);
     hipLaunchKernelGGL(k3_score, dim3(groups), dim3(64), 0, st, tb, cd, splits, bottleneck,
                        iter_time, status);
+}
+
+void launch_score_h1f1b(const TablesDev &tb, const CandDev &cd, const int32_t *splits, const int64_t *t_max,
+                        int32_t *warmup, int64_t *bottleneck, int64_t *iter_time, int32_t *status,
+                        hipStream_t st) {
+    if (cd.C == 0) return;
+    const int groups = cd.C < (1 << 20) ? cd.C : (1 << 20);
+    hipLaunchKernelGGL(k3_score_h1f1b, dim3(groups), dim3(64), 0, st, tb, cd, splits, t_max, warmup,
+                       bottleneck, iter_time, status);
 }
 
 void launch_argmin(int32_t C, const int64_t *iter_time, const int32_t *status, int64_t *best_time,

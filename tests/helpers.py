@@ -84,6 +84,22 @@ def oracle_plan_exact_threaded(tables, cands, threads=None):
     return out
 
 
+def oracle_plan_h1f1b_threaded(tables, cands, t_max, threads=None, step=8):
+    """Oracle H-1F1B plans for a whole batch, candidates spread over host threads."""
+    import os
+    from concurrent.futures import ThreadPoolExecutor
+
+    import oracle
+    threads = threads or min(16, len(os.sched_getaffinity(0)))
+    out = oracle.Plans(cands.C, cands.S_max)
+    out.warmup = np.full((cands.C, cands.S_max), -1, dtype=np.int32)
+    caps = np.ascontiguousarray(t_max, dtype=np.int64)
+    with ThreadPoolExecutor(threads) as ex:
+        list(ex.map(lambda lo: oracle.plan_h1f1b_batch(tables, cands, caps, lo, min(lo + step, cands.C), out),
+                    range(0, cands.C, step)))
+    return out
+
+
 def assert_plans_equal(got, want, label=""):
     """Bit-exact comparison of every output array of a batch."""
     for name in ("status", "splits", "dev_first", "bottleneck", "iter_time"):
