@@ -155,7 +155,8 @@ def exact_search(ctx, binding, torch, w, tables, dc, cands, minmax, reps, cpu_ca
            "capped_passes_max": int(passes.max()) if passes.size else 0,
            "improved_fraction": float((got.iter_time[ok] < minmax.iter_time[ok]).mean()) if ok.any() else 0.0,
            "mean_iter_time_gain": float(gain.mean()) if ok.any() else 0.0,
-           "best_iter_time_us": int(got.iter_time[ok].min()) if ok.any() else None}
+           "best_iter_time_us": int(got.iter_time[ok].min()) if ok.any() else None,
+           "_caps": np.where(ok, got.bottleneck, 0).astype(np.int64)}
     if cpu_candidates:
         import oracle
         from concurrent.futures import ThreadPoolExecutor
@@ -179,6 +180,48 @@ def exact_search(ctx, binding, torch, w, tables, dc, cands, minmax, reps, cpu_ca
     return res
 
 
+def h1f1b_search(ctx, binding, torch, w, tables, dc, cands, caps_host, reps, cpu_candidates):
+    """The capped recurrence with H-1F1B warm-up counts over the same batch, every candidate under
+    the cap the exact search chose for it: time per call, feasible fraction, and the oracle timed on
+    the first candidates (which also checks the GPU's answers for them bit for bit)."""
+    import numpy as np
+
+    out = binding.DevicePlans(ctx, dc.C, dc.S_max)
+    ws = binding.plan_workspace(ctx, tables, dc)
+    caps = torch.from_numpy(np.ascontiguousarray(caps_host, dtype=np.int64)).to(ctx.device)
+    warmup = torch.empty((dc.C, dc.S_max), dtype=torch.int32, device=ctx.device)
+    ms = timed_ms(torch, lambda: binding.harp_plan_h1f1b_batch(ctx, tables, dc, caps, out, warmup, ws), reps)
+    got = out.to_host()
+    got.warmup = warmup.cpu().numpy()
+    ok = got.status == 0
+    res = {"kernel": "k2_band + k2_h1f1b (one harp_plan_h1f1b_batch call)", "ms_per_call": ms,
+           "plans_per_s": dc.C / (ms * 1e-3), "feasible_fraction": float(ok.mean()),
+           "mean_first_stage_warmup": float(got.warmup[ok, 0].mean()) if ok.any() else None,
+           "caps": "bottleneck of the exact search's plan per candidate"}
+    if cpu_candidates:
+        import oracle
+        from concurrent.futures import ThreadPoolExecutor
+        cores = min(16, len(os.sched_getaffinity(0)))
+        n = min(cands.C, cpu_candidates)
+        sub = cands.slice(0, n)
+        ot = oracle.build_tables(w.problem)
+        want = oracle.Plans(n, sub.S_max)
+        want.warmup = np.full((n, sub.S_max), -1, dtype=np.int32)
+        sub_caps = np.ascontiguousarray(caps_host[:n], dtype=np.int64)
+        t0 = time.perf_counter()
+        with ThreadPoolExecutor(cores) as ex:
+            list(ex.map(lambda lo: oracle.plan_h1f1b_batch(ot, sub, sub_caps, lo, min(lo + 8, n), want),
+                        range(0, n, 8)))
+        dt = time.perf_counter() - t0
+        for name in ("status", "splits", "dev_first", "warmup", "bottleneck", "iter_time"):
+            if not (getattr(want, name) == getattr(got, name)[:n]).all():
+                raise SystemExit("GPU H-1F1B plans differ from the oracle in %s on the baseline sample" % name)
+        res["cpu_baseline"] = {"value": n / dt, "unit": "plans/s", "cores": cores, "kind": "oracle",
+                               "sample": "first %d candidates of the batch over %d threads, %.1f s wall; GPU "
+                                         "answers for the sample verified bit-exact" % (n, cores, dt)}
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -195,6 +238,9 @@ def main():
     ap.add_argument("--exact-reps", type=int, default=3,
                     help="timed calls of the exact search over the same batch (0 = skip)")
     ap.add_argument("--exact-cpu-candidates", type=int, default=16)
+    ap.add_argument("--h1f1b-reps", type=int, default=3,
+                    help="timed calls of the H-1F1B recurrence at the exact search's caps (0 = skip)")
+    ap.add_argument("--h1f1b-cpu-candidates", type=int, default=1024)
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="also run one plain device copy of this many MiB (reference for HBM counters)")
     args = ap.parse_args()
@@ -314,6 +360,11 @@ def main():
     if args.exact_reps and fast:
         result["exact_search"] = exact_search(ctx, binding, torch, w, tables, dc, cands, got, args.exact_reps,
                                               0 if args.no_cpu_baseline else args.exact_cpu_candidates)
+        result["_exact_caps"] = result["exact_search"].pop("_caps")
+    if args.h1f1b_reps and fast and "exact_search" in result:
+        result["h1f1b"] = h1f1b_search(ctx, binding, torch, w, tables, dc, cands, result.pop("_exact_caps"),
+                                       args.h1f1b_reps, 0 if args.no_cpu_baseline else args.h1f1b_cpu_candidates)
+    result.pop("_exact_caps", None)
     if not args.no_cpu_baseline:
         # about 20 core-seconds of oracle work at 1-5 ns per dense transition
         budget = args.cpu_candidates or max(64, int(1.6e10 / max(1.0, n_trans / C)))
