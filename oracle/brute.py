@@ -301,3 +301,122 @@ def plan_h1f1b(p, S: int, S_max: int, grp, tp, t_max: int):
         cuts.append(j)
         i = j
     return 0, cuts, counts, total
+
+
+# ---------------------------------------------------------------- submesh choice inside the recurrence
+
+def slicings(p, groups, S: int):
+    """Every way to cut the devices of the ordered groups into S stages: each group's devices are
+    split into an ordered sequence of allowed degrees that uses all of them.  Yields slot lists
+    [(group, degree), ...] of length S."""
+    degrees = [int(x) for x in p.tp_degrees]
+
+    def compositions(n):
+        if n == 0:
+            yield ()
+            return
+        for d in degrees:
+            if d <= n:
+                for rest in compositions(n - d):
+                    yield (d,) + rest
+
+    def rec(k, left):
+        if k == len(groups):
+            if left == 0:
+                yield []
+            return
+        g = int(groups[k])
+        for comp in compositions(int(p.group_ndev[g])):
+            if len(comp) <= left - (len(groups) - k - 1):
+                for tail in rec(k + 1, left - len(comp)):
+                    yield [(g, d) for d in comp] + tail
+
+    yield from rec(0, S)
+
+
+def mesh_valid(p, S: int, S_max: int, groups) -> bool:
+    groups = [int(g) for g in groups]
+    return 1 <= S <= S_max and len(groups) >= 1 and len(set(groups)) == len(groups) and \
+        all(0 <= g < int(p.G) for g in groups)
+
+
+def mesh_best_bottleneck(p, S: int, groups) -> int:
+    """Smallest bottleneck over EVERY slicing of the ordered groups into S stages and every
+    partition of the operators, by enumeration (INF when none is feasible)."""
+    L = int(p.L)
+    best = INF
+    if S <= L:
+        for slots in slicings(p, groups, S):
+            grp = [g for g, _ in slots]
+            tp = [d for _, d in slots]
+            for b in partitions(L, S):
+                w = 0
+                for s in range(S):
+                    w = max(w, stage_cost(p, S, grp, tp, s, b[s], b[s + 1]))
+                    if w >= best:
+                        break
+                best = min(best, w)
+    return best
+
+
+def plan_mesh(p, S: int, S_max: int, groups):
+    """The recurrence over (stages, operators, devices used) as a memoised recursion: returns
+    (status, bottleneck, cuts, slot list).  state(s, i, d) = best value with the first s stages on the
+    first i operators and the first d devices; ties: lowest previous cut, then smallest degree."""
+    L, M = int(p.L), int(p.M)
+    if not mesh_valid(p, S, S_max, groups):
+        return 2, INF, None, None
+    groups = [int(g) for g in groups]
+    bounds = [0]
+    for g in groups:
+        bounds.append(bounds[-1] + int(p.group_ndev[g]))
+    total = bounds[-1]
+    degrees = [int(x) for x in p.tp_degrees]
+    if S > L or S < len(groups) or S > total:
+        return 1, INF, None, None
+    memo = {}
+
+    def group_at(d):
+        return max(k for k in range(len(groups)) if bounds[k] <= d)
+
+    def state(s, i, d):
+        if s == 0:
+            return (0, -1, -1) if (i == 0 and d == 0) else (INF, -1, -1)
+        key = (s, i, d)
+        if key in memo:
+            return memo[key]
+        best = (INF, -1, -1)
+        last = s == S
+        n = min(S - (s - 1), M)
+        for q, deg in enumerate(degrees):
+            d0 = d - deg
+            if d0 < 0:
+                continue
+            k = group_at(d0)
+            if d > bounds[k + 1] or (d == total) != last:
+                continue
+            g = groups[k]
+            g_next = g if (last or d < bounds[k + 1]) else groups[k + 1]
+            c = 0 if last else cut_time(p, g, g_next, i)
+            for j in range(s - 1, i):
+                prev = state(s - 1, j, d0)[0]
+                if prev == INF or not memory_fits(p, g, deg, n, j, i):
+                    continue
+                val = max(prev, stage_time(p, g, deg, j, i), c)
+                if (val, j, q) < best:
+                    best = (val, j, q)
+        memo[key] = best
+        return best
+
+    value = state(S, L, total)[0]
+    if value == INF:
+        return 1, INF, None, None
+    cuts, slots = [L], []
+    i, d = L, total
+    for s in range(S, 0, -1):
+        _, j, q = state(s, i, d)
+        d -= degrees[q]
+        slots.append((groups[group_at(d)], degrees[q]))
+        cuts.append(j)
+        i = j
+    return 0, value, cuts[::-1], slots[::-1]

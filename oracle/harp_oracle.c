@@ -642,3 +642,122 @@ int oracle_score_h1f1b(const oracle_problem *p, const int64_t *PF, const int64_t
     }
     return ORACLE_OK;
 }
+
+/* ---------------------------------------------------------------------------------------------
+ * Submesh choice inside the recurrence (paper section 5.2.3, eq. dp_general's third index).
+ *
+ * A candidate is an ORDER of device groups and a stage count S; how each group's devices are cut
+ * into stages is decided by the recurrence itself.  With O_0 = 0, O_k = devices of the first k
+ * groups of the order, the state (s, i, d) means: the first s stages hold the first i operators and
+ * use exactly the first d devices of the ordered groups.  A stage placed at device offset d runs on
+ * the group k with O_k <= d < O_{k+1} and takes tp of its devices, tp an allowed degree with
+ * d + tp <= O_{k+1}; when that exhausts the group the next stage is on the next group and the cut
+ * between them crosses the inter-group link, otherwise the intra-group link (the paper's rule for
+ * C(j)).  Every device of every listed group is used: the answer is read at (S, L, O_K).
+ * Min-max form, classic 1F1B counts, as on the hot path:
+ *   D[s+1][i][d + tp] = min over (j, tp) of max(D[s][j][d], time, comm)
+ * with ties resolved by the lowest previous cut j, then the smallest degree.
+ * ------------------------------------------------------------------------------------------- */
+int oracle_plan_mesh_batch(const oracle_problem *p, const int64_t *PF, const int64_t *PP, const int64_t *PS,
+                           const int64_t *PR, int32_t C, int32_t G_max, int32_t S_max, const int32_t *ord_S,
+                           const int32_t *ord_G, const int32_t *ord_group, int32_t c_begin, int32_t c_end,
+                           int32_t *splits, int32_t *stage_group, int32_t *stage_tp, int32_t *dev_first,
+                           int64_t *bottleneck, int64_t *iter_time, int32_t *status)
+{
+    if (C < 0 || S_max < 1 || G_max < 1 || c_begin < 0 || c_end > C || c_begin > c_end) return ORACLE_BAD_ARG;
+    if (p->L > 65535) return ORACLE_BAD_ARG;
+    const int L = p->L;
+    tables_view v = { p, PF, PP, PS, PR };
+    int64_t total_dev = 0;
+    for (int g = 0; g < p->G; ++g) total_dev += p->group_ndev[g];
+    const size_t W = (size_t)(L + 1), Dn = (size_t)total_dev + 1;
+    int64_t *D = (int64_t *)malloc(sizeof(int64_t) * (size_t)(S_max + 1) * W * Dn);
+    int32_t *arg_j = (int32_t *)malloc(sizeof(int32_t) * (size_t)(S_max + 1) * W * Dn);
+    int32_t *arg_k = (int32_t *)malloc(sizeof(int32_t) * (size_t)(S_max + 1) * W * Dn);
+    int64_t *O = (int64_t *)malloc(sizeof(int64_t) * (size_t)(G_max + 1));
+    char *seen = (char *)malloc((size_t)p->G);
+    if (!D || !arg_j || !arg_k || !O || !seen) return ORACLE_BAD_ARG;
+#define AT(s, i, d) (((size_t)(s) * W + (size_t)(i)) * Dn + (size_t)(d))
+    for (int32_t c = c_begin; c < c_end; ++c) {
+        const int S = ord_S[c], K = ord_G[c];
+        const int32_t *og = ord_group + (size_t)c * G_max;
+        int32_t *sp = splits + (size_t)c * (S_max + 1), *sg = stage_group + (size_t)c * S_max;
+        int32_t *st = stage_tp + (size_t)c * S_max, *df = dev_first + (size_t)c * S_max;
+        fill_failed(S_max, sp, df, bottleneck + c, iter_time + c);
+        for (int s = 0; s < S_max; ++s) { sg[s] = -1; st[s] = -1; }
+        status[c] = CAND_INVALID;
+        if (S < 1 || S > S_max || K < 1 || K > G_max) continue;
+        int ok = 1;
+        memset(seen, 0, (size_t)p->G);
+        O[0] = 0;
+        for (int k = 0; k < K && ok; ++k) {
+            if (og[k] < 0 || og[k] >= p->G || seen[og[k]]) { ok = 0; break; }
+            seen[og[k]] = 1;
+            O[k + 1] = O[k] + p->group_ndev[og[k]];
+        }
+        if (!ok) continue;
+        status[c] = CAND_INFEASIBLE;
+        const int64_t Dtot = O[K];
+        if (S > L || S < K || S > Dtot) continue;
+        for (size_t x = 0; x < (size_t)(S + 1) * W * Dn; ++x) { D[x] = ORACLE_INF; arg_j[x] = -1; arg_k[x] = -1; }
+        D[AT(0, 0, 0)] = 0;
+        for (int s = 0; s < S; ++s) {
+            const int last = (s == S - 1);
+            const int64_t n = (S - s) < p->M ? (S - s) : p->M;
+            int k = 0;
+            for (int64_t d = 0; d < Dtot; ++d) {
+                while (O[k + 1] <= d) ++k;                      /* the group this stage runs on */
+                const int g = og[k];
+                for (int q = 0; q < p->n_tp; ++q) {
+                    const int tp = p->tp_degrees[q];
+                    const int64_t d2 = d + tp;
+                    if (d2 > O[k + 1]) continue;                 /* a stage stays inside one group */
+                    if (last != (d2 == Dtot)) continue;          /* the last stage, and only it, uses up the devices */
+                    const int g_next = last ? g : (d2 == O[k + 1] ? og[k + 1] : g);
+                    for (int i = s + 1; i <= L - (S - 1 - s); ++i) {
+                        if (last && i != L) continue;
+                        const int64_t cc = last ? 0 : cut_time(p, g, g_next, i);
+                        int64_t best = D[AT(s + 1, i, d2)];
+                        int32_t bj = arg_j[AT(s + 1, i, d2)], bq = arg_k[AT(s + 1, i, d2)];
+                        for (int j = s; j < i; ++j) {
+                            const int64_t prev = D[AT(s, j, d)];
+                            if (prev == ORACLE_INF) continue;
+                            if (!memory_fits(&v, g, tp, n, j, i)) continue;
+                            const int64_t val = max64(prev, max64(stage_time(&v, g, tp, j, i), cc));
+                            if (val < best || (val == best && (j < bj || (j == bj && q < bq)))) {
+                                best = val; bj = j; bq = q;
+                            }
+                        }
+                        D[AT(s + 1, i, d2)] = best;
+                        arg_j[AT(s + 1, i, d2)] = bj;
+                        arg_k[AT(s + 1, i, d2)] = bq;
+                    }
+                }
+            }
+        }
+        if (D[AT(S, L, Dtot)] == ORACLE_INF) continue;
+        int i = L;
+        int64_t d = Dtot;
+        sp[S] = L;
+        for (int s = S; s >= 1; --s) {
+            const int j = arg_j[AT(s, i, d)], q = arg_k[AT(s, i, d)];
+            const int tp = p->tp_degrees[q];
+            d -= tp;
+            int k = 0;
+            while (O[k + 1] <= d) ++k;
+            sp[s - 1] = j;
+            sg[s - 1] = og[k];
+            st[s - 1] = tp;
+            i = j;
+        }
+        if (i != 0 || d != 0) abort();
+        if (!candidate_valid(p, S, S_max, sg, st)) abort();      /* the slicing found is a well-formed candidate */
+        slot_devices(p, S, S_max, sg, st, df);
+        if (score_partition(&v, S, sg, st, sp, bottleneck + c, iter_time + c) != CAND_OK ||
+            bottleneck[c] != D[AT(S, L, Dtot)]) abort();
+        status[c] = CAND_OK;
+    }
+#undef AT
+    free(D); free(arg_j); free(arg_k); free(O); free(seen);
+    return ORACLE_OK;
+}

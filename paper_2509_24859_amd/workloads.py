@@ -345,6 +345,59 @@ def make(name: str, seed: int = 0) -> Workload:
     return WORKLOADS[name](seed)
 
 
+@dataclass
+class Orderings:
+    """A batch of group orderings: candidate c runs its S stages on the groups ord_group[c, :ord_G[c]]
+    in that order; how each group's devices are cut into stages is left to the planner."""
+    C: int
+    G_max: int
+    S_max: int
+    ord_S: np.ndarray        # [C] int32
+    ord_G: np.ndarray        # [C] int32
+    ord_group: np.ndarray    # [C][G_max] int32, -1 beyond ord_G
+
+    def slice(self, lo: int, hi: int) -> "Orderings":
+        return Orderings(hi - lo, self.G_max, self.S_max, self.ord_S[lo:hi].copy(), self.ord_G[lo:hi].copy(),
+                         self.ord_group[lo:hi].copy())
+
+
+def orderings_from_lists(lists, S_max=None, G_max=None) -> Orderings:
+    """lists: per candidate (S, [group ids in order])."""
+    G_max = max(len(g) for _, g in lists) if G_max is None else G_max
+    S_max = max(S for S, _ in lists) if S_max is None else S_max
+    C = len(lists)
+    og = np.full((C, G_max), -1, dtype=np.int32)
+    for c, (_, groups) in enumerate(lists):
+        og[c, :len(groups)] = groups[:G_max]
+    return Orderings(C, G_max, max(S_max, 1), np.array([S for S, _ in lists], dtype=np.int32),
+                     np.array([len(g) for _, g in lists], dtype=np.int32), og)
+
+
+def make_orderings(p: Problem, seed: int, config_id: int, S_min: int, S_max: int, lo: int, hi: int) -> Orderings:
+    """Orderings lo..hi-1 of a batch; ordering c depends only on (seed, config_id, c): a uniformly
+    random order of all G groups (Fisher-Yates) and a stage count drawn from [max(S_min, G),
+    min(S_max, devices)]."""
+    n = hi - lo
+    G = p.G
+    cs = np.arange(lo, hi, dtype=np.uint64)
+    with np.errstate(over="ignore"):
+        st = _mix(_stream_state(seed, config_id, 2000) + cs * np.uint64(0xA0761D6478BD642F))
+    rng = Streams(st)
+    order = np.tile(np.arange(G, dtype=np.int64), (n, 1))
+    rows = np.arange(n)
+    for k in range(G - 1, 0, -1):
+        r = rng.below(k + 1)
+        a = order[rows, k].copy()
+        order[rows, k] = order[rows, r]
+        order[rows, r] = a
+    top = min(S_max, int(p.group_ndev.sum()))
+    low = max(S_min, G)
+    if top < low:
+        raise ValueError("no stage count between the number of groups and the number of devices")
+    S = low + rng.below(top - low + 1)
+    return Orderings(n, G, S_max, S.astype(np.int32), np.full(n, G, dtype=np.int32), order.astype(np.int32))
+
+
 def memory_to_compute_order(p: Problem) -> np.ndarray:
     """Group ids in the order the paper's heuristic would run them (section 5.2.1): groups whose
     devices have the most memory per unit of compute throughput first, because earlier stages of a

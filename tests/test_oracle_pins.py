@@ -606,6 +606,85 @@ def test_h1f1b_without_memory_pressure_equals_the_capped_least_sum():
                 p, S, cands.cand_group[c], cands.cand_tp[c], S, p.L, int(caps[c]))
 
 
+# ---------------------------------------------------------------- submesh choice inside the recurrence
+
+def test_mesh_hand_examples_and_statuses():
+    # one group of two devices, degrees 1 and 2, operators 3 1 1 3 (no all-reduce cost: act = 0)
+    p = simple_problem([3, 1, 1, 3], M=4, G=1, ndev=(2,), tp=(1, 2))
+    orders = W.orderings_from_lists([(1, [0]), (2, [0]), (3, [0])], S_max=3)
+    out = oracle.plan_mesh_batch(oracle.build_tables(p), orders)
+    # S = 1: both devices in one stage of degree 2: ceil(8 / 2) = 4
+    assert out.status[0] == oracle.OK and list(out.stage_tp[0]) == [2, -1, -1] and out.bottleneck[0] == 4
+    assert out.iter_time[0] == 4 * 4
+    # S = 2: two stages of one device: the hot path's hand example, cuts 0 2 4
+    assert list(out.stage_tp[1]) == [1, 1, -1] and list(out.splits[1]) == [0, 2, 4, -1] and out.bottleneck[1] == 4
+    assert list(out.dev_first[1]) == [0, 1, -1]
+    # S = 3: three stages cannot use exactly two devices
+    assert out.status[2] == oracle.INFEASIBLE and (out.splits[2] == -1).all()
+
+    p = simple_problem([1] * 6, G=3, ndev=(2, 1, 1), tp=(1, 2), bw=np.ones((3, 3)))
+    lists = [(3, [0, 1, 2]), (4, [2, 0, 1]), (2, [0, 1, 2]), (5, [0, 1, 2]), (3, [0, 0, 1]), (3, [0, 3]),
+             (0, [0]), (3, [1, 2])]
+    orders = W.orderings_from_lists(lists, S_max=6)
+    out = oracle.plan_mesh_batch(oracle.build_tables(p), orders)
+    assert list(out.status) == [0, 0, 1, 1, 2, 2, 2, 1]
+    assert list(out.stage_group[1, :4]) == [2, 0, 0, 1] and list(out.stage_tp[1, :4]) == [1, 1, 1, 1]
+    assert list(out.stage_tp[0, :3]) == [2, 1, 1]
+
+
+def test_mesh_against_its_twin_exhaustive_enumeration_and_the_hot_path():
+    n = 0
+    for seed in range(260):
+        w = W.random_small(seed, L_max=8, S_cap=4)
+        p = w.problem
+        if int(p.group_ndev.sum()) > 8:
+            continue
+        tables = oracle.build_tables(p)
+        orders = W.make_orderings(p, seed, 5, 1, 5, 0, 6)
+        out = oracle.plan_mesh_batch(tables, orders)
+        for c in range(orders.C):
+            S, groups = int(orders.ord_S[c]), orders.ord_group[c, :orders.ord_G[c]]
+            st, val, cuts, slots = brute.plan_mesh(p, S, orders.S_max, groups)
+            assert st == out.status[c], (seed, c)
+            exhaustive = brute.mesh_best_bottleneck(p, S, groups) if S <= p.L else brute.INF
+            if st != oracle.OK:
+                assert exhaustive == brute.INF and out.bottleneck[c] == oracle.INF
+                continue
+            n += 1
+            got_slots = [(int(g), int(t)) for g, t in zip(out.stage_group[c, :S], out.stage_tp[c, :S])]
+            assert out.bottleneck[c] == val == exhaustive, (seed, c)
+            assert list(out.splits[c, :S + 1]) == cuts and got_slots == slots, (seed, c)
+            # the slicing found is one of the enumerated ones, and the hot-path oracle, given every
+            # slicing as an ordinary candidate, finds the same optimum and the same plan for this one
+            every = list(brute.slicings(p, groups, S))
+            assert got_slots in every
+            cands = cands_from_lists(every, S_max=orders.S_max)
+            hot = oracle.plan_batch(tables, cands)
+            assert hot.bottleneck.min() == val
+            k = every.index(got_slots)
+            assert hot.bottleneck[k] == val and list(hot.splits[k, :S + 1]) == cuts
+            assert hot.iter_time[k] == out.iter_time[c] and (hot.dev_first[k] == out.dev_first[c]).all()
+    assert n > 300
+
+
+def test_mesh_with_forced_slicing_is_the_hot_path():
+    # single-device groups leave the recurrence no choice: same plans as the candidates (g, 1)
+    for seed in range(40):
+        rng = np.random.default_rng(seed)
+        G, L = int(rng.integers(2, 5)), int(rng.integers(6, 14))
+        bw = rng.integers(1, 50, size=(G, G))
+        p = simple_problem(rng.integers(1, 100, size=L), M=int(rng.integers(1, 9)), G=G, ndev=(1,) * G,
+                           act=rng.integers(0, 400, size=L), bw=np.minimum(bw, bw.T),
+                           params=rng.integers(0, 50, size=L), stash=rng.integers(0, 20, size=L),
+                           mem=[int(rng.integers(150, 600))])
+        order = [int(x) for x in rng.permutation(G)]
+        tables = oracle.build_tables(p)
+        mesh = oracle.plan_mesh_batch(tables, W.orderings_from_lists([(G, order)]))
+        hot = oracle.plan_batch(tables, cands_from_lists([[(g, 1) for g in order]]))
+        for name in ("status", "splits", "dev_first", "bottleneck", "iter_time"):
+            assert (getattr(mesh, name) == getattr(hot, name)).all(), (seed, name)
+
+
 # ---------------------------------------------------------------- the workloads themselves
 
 def test_workload_shapes_and_determinism():
