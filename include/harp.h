@@ -199,6 +199,39 @@ int harp_plan_exact_batch(harp_ctx *ctx, harp_tables *tables, const harp_candida
                           const harp_plans *out, int32_t *n_passes, void *workspace,
                           size_t workspace_bytes, void *hip_stream);
 
+/* A batch of group orderings for harp_plan_mesh_batch: candidate c runs S = ord_S[c] stages on the
+ * groups ord_group[c][0 .. ord_G[c]-1], in that order; the planner decides how each group's
+ * devices are cut into stages. */
+typedef struct {
+    int32_t C;      /* orderings, >= 0 */
+    int32_t G_max;  /* row length of ord_group, 1..1024 */
+    int32_t S_max;  /* row length of the per-stage outputs, >= every ord_S */
+    const int32_t *ord_S;     /* DEVICE [C] */
+    const int32_t *ord_G;     /* DEVICE [C] groups listed, 1..G_max */
+    const int32_t *ord_group; /* DEVICE [C][G_max] distinct group ids (entries beyond ord_G ignored) */
+} harp_orderings;
+
+/* Bytes of DEVICE workspace harp_plan_mesh_batch needs (0 on malformed arguments; finalizes the
+ * view, because the size depends on the number of devices in the problem). */
+size_t harp_plan_mesh_workspace_bytes(harp_ctx *ctx, harp_tables *tables, const harp_orderings *orders);
+
+/* The search with the submesh of every stage chosen inside the recurrence (section 5.2.3, the third
+ * index of eq. dp_general): state = (stages placed, operators placed, devices used across the
+ * ordered groups).  A stage takes tp devices of the group its device offset falls in, tp an
+ * allowed degree that does not reach beyond that group; the cut behind a stage that exhausts its
+ * group crosses to the next group's link.  Every device of every listed group is used.  Min-max
+ * form with the classic 1F1B counts, exactly the definitions of harp_plan_batch; ties: lowest
+ * previous cut, then smallest degree.  The result for an ordering equals the best harp_plan_batch
+ * result over all slicings of its groups into S stages.
+ * out as for harp_plan_batch (rows of length S_max + 1 / S_max); stage_group, stage_tp: DEVICE
+ * [C][S_max], the slicing found (-1 beyond S or without a plan).  HARP_CAND_INVALID: S outside
+ * 1..S_max, ord_G outside 1..G_max, a group id out of range or listed twice; HARP_CAND_INFEASIBLE:
+ * S > L, S < ord_G, S > devices, or no plan fits in memory.  At most 65535 devices.
+ * Asynchronous on `hip_stream`, except that the first use of a view finalizes it. */
+int harp_plan_mesh_batch(harp_ctx *ctx, harp_tables *tables, const harp_orderings *orders,
+                         const harp_plans *out, int32_t *stage_group, int32_t *stage_tp,
+                         void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* The capped recurrence under the H-1F1B scheduler (sections 4.1 and 5.2.3): for candidate c and
  * the cap t_max[c] on every stage and transfer time (constraints (i), (ii)), the suffix recurrence
  * of eq. dp_general with the warm-up launch count carried in the state (eq. dp_ni) and used by the

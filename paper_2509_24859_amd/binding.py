@@ -26,6 +26,7 @@ EXPORTS = (
     "harp_tables_pp", "harp_tables_ps", "harp_tables_pr", "harp_tables_release",
     "harp_set_plan_path", "harp_plan_workspace_bytes", "harp_plan_batch", "harp_plan_exact_batch",
     "harp_plan_h1f1b_batch", "harp_score_h1f1b",
+    "harp_plan_mesh_workspace_bytes", "harp_plan_mesh_batch",
     "harp_score_1f1b", "harp_argmin_batch", "harp_measure_valu_int32",
 )
 
@@ -43,6 +44,11 @@ class harp_problem(C.Structure):
                 ("param_bytes", C.c_void_p), ("stash_bytes", C.c_void_p), ("act_bytes", C.c_void_p),
                 ("group_type", C.c_void_p), ("group_ndev", C.c_void_p),
                 ("type_mem_bytes", C.c_void_p), ("bw_bytes_per_us", C.c_void_p)]
+
+
+class harp_orderings(C.Structure):
+    _fields_ = [("C", C.c_int32), ("G_max", C.c_int32), ("S_max", C.c_int32), ("ord_S", C.c_void_p),
+                ("ord_G", C.c_void_p), ("ord_group", C.c_void_p)]
 
 
 class harp_candidates(C.Structure):
@@ -93,6 +99,9 @@ def load_library() -> C.CDLL:
     lib.harp_plan_exact_batch.argtypes = [vp, vp, C.POINTER(harp_candidates), C.POINTER(harp_plans), vp, vp, sz, vp]
     lib.harp_plan_h1f1b_batch.argtypes = [vp, vp, C.POINTER(harp_candidates), vp, C.POINTER(harp_plans), vp, vp, sz, vp]
     lib.harp_score_h1f1b.argtypes = [vp, vp, C.POINTER(harp_candidates), vp, vp, vp, vp, vp, vp, vp]
+    lib.harp_plan_mesh_workspace_bytes.argtypes = [vp, vp, C.POINTER(harp_orderings)]
+    lib.harp_plan_mesh_workspace_bytes.restype = sz
+    lib.harp_plan_mesh_batch.argtypes = [vp, vp, C.POINTER(harp_orderings), C.POINTER(harp_plans), vp, vp, vp, sz, vp]
     lib.harp_score_1f1b.argtypes = [vp, vp, C.POINTER(harp_candidates), vp, vp, vp, vp, vp]
     lib.harp_argmin_batch.argtypes = [vp, i32, vp, vp, vp, vp, vp]
     lib.harp_measure_valu_int32.argtypes = [vp, i32, i32, vp, vp]
@@ -356,6 +365,50 @@ def plan(ctx: Context, problem, cands, path: int = PATH_AUTO):
     finally:
         ctx.set_plan_path(PATH_AUTO)
     return out.to_host(), tables
+
+
+class DeviceOrderings:
+    def __init__(self, ctx: Context, orders):
+        self.C, self.G_max, self.S_max = int(orders.C), int(orders.G_max), int(orders.S_max)
+        self.ord_S = _dev(orders.ord_S, np.int32, ctx.device)
+        self.ord_G = _dev(orders.ord_G, np.int32, ctx.device)
+        self.ord_group = _dev(orders.ord_group, np.int32, ctx.device)
+        self.c = harp_orderings(self.C, self.G_max, self.S_max, self.ord_S.data_ptr(), self.ord_G.data_ptr(),
+                                self.ord_group.data_ptr())
+
+
+def harp_plan_mesh_batch(ctx: Context, tables: Tables, do: DeviceOrderings, out: DevicePlans, stage_group,
+                         stage_tp, workspace, stream=None):
+    ctx.check(ctx.lib.harp_plan_mesh_batch(ctx.handle, tables.handle, C.byref(do.c), C.byref(out.c),
+                                           stage_group.data_ptr(), stage_tp.data_ptr(), workspace.data_ptr(),
+                                           workspace.numel(), _stream_handle(stream)))
+
+
+def mesh_workspace(ctx: Context, tables: Tables, do: DeviceOrderings):
+    torch = _torch()
+    n = ctx.lib.harp_plan_mesh_workspace_bytes(ctx.handle, tables.handle, C.byref(do.c))
+    if n == 0:
+        raise HarpError(ERR_INVALID_ARG, ctx.lib.harp_last_error(ctx.handle).decode() or "malformed orderings")
+    return torch.empty(n, dtype=torch.uint8, device=ctx.device)
+
+
+def plan_mesh(ctx: Context, problem, orders):
+    """Convenience for tests: tables, submesh planner over a batch of orderings; host copies of the
+    plans with `.stage_group` and `.stage_tp`."""
+    torch = _torch()
+    tables = Tables(ctx, problem)
+    do = DeviceOrderings(ctx, orders)
+    out = DevicePlans(ctx, do.C, do.S_max)
+    out.poison()
+    sg = torch.full((max(do.C, 1), do.S_max), -7, dtype=torch.int32, device=ctx.device)
+    st = torch.full((max(do.C, 1), do.S_max), -7, dtype=torch.int32, device=ctx.device)
+    ws = mesh_workspace(ctx, tables, do)
+    harp_plan_mesh_batch(ctx, tables, do, out, sg, st, ws)
+    torch.cuda.synchronize()
+    got = out.to_host()
+    got.stage_group = sg[:do.C].cpu().numpy()
+    got.stage_tp = st[:do.C].cpu().numpy()
+    return got, tables
 
 
 def plan_h1f1b(ctx: Context, problem, cands, t_max, path: int = PATH_AUTO):

@@ -27,6 +27,7 @@ struct harp_tables {
     bool finalized;
     int verdict;
     bool fast32;
+    long long total_devices;
     size_t bytes;
 };
 
@@ -101,6 +102,7 @@ int finalize_tables(harp_ctx *ctx, harp_tables *t) {
     if (e != hipSuccess) return hip_fail(ctx, e, "waiting for the table build");
     t->finalized = true;
     t->fast32 = ctx->pinned->fast32 != 0;
+    t->total_devices = ctx->pinned->total_devices;
     if (ctx->pinned->bad_arg)
         t->verdict = fail(ctx, HARP_ERR_INVALID_ARG,
                           "problem arrays hold a negative value, a bandwidth below 1, a group type out of range or an empty group");
@@ -130,6 +132,29 @@ int n_plan_groups(const harp_ctx *ctx, int C, bool fast, int L, int S_max) {
     int resident = fast ? plan_fast_groups(L, S_max, ctx->n_cu) : ctx->n_cu * 8;
     if (resident < 1) resident = 1;
     return C < resident ? (C < 1 ? 1 : C) : resident;
+}
+
+// Workgroups of the submesh planner: resident ones, fewer when their slices would pass 16 GiB.
+int n_mesh_groups(const harp_ctx *ctx, int C, size_t per_group) {
+    long long n = (long long)ctx->n_cu * 4;
+    const long long fit = (long long)((size_t(16) << 30) / (per_group ? per_group : 1));
+    if (n > fit) n = fit;
+    if (n > C) n = C;
+    return n < 1 ? 1 : int(n);
+}
+
+int check_orderings(harp_ctx *ctx, harp_tables *t, const harp_orderings *od) {
+    if (!ctx) return HARP_ERR_INVALID_ARG;
+    if (!t || !od) return fail(ctx, HARP_ERR_INVALID_ARG, "null tables or orderings");
+    if (t->device != ctx->device) return fail(ctx, HARP_ERR_INVALID_ARG, "tables belong to another device");
+    if (od->C < 0) return fail(ctx, HARP_ERR_INVALID_ARG, "C must be >= 0");
+    if (od->S_max < 1 || od->S_max > kMaxStages) return fail(ctx, HARP_ERR_SHAPE, "S_max must be in 1..%d", kMaxStages);
+    if (od->G_max < 1 || od->G_max > kMaxOrderGroups)
+        return fail(ctx, HARP_ERR_SHAPE, "G_max must be in 1..%d", kMaxOrderGroups);
+    if (od->C > 0 && (!od->ord_S || !od->ord_G || !od->ord_group))
+        return fail(ctx, HARP_ERR_INVALID_ARG, "null ordering array");
+    if (t->dev.L > HARP_MAX_L_PLAN) return fail(ctx, HARP_ERR_SHAPE, "planning needs L <= %d", HARP_MAX_L_PLAN);
+    return finalize_tables(ctx, t);
 }
 
 bool use_fast(const harp_ctx *ctx, const harp_tables *t) {
@@ -231,6 +256,7 @@ int harp_build_segment_costs(harp_ctx *ctx, const harp_problem *p, void *table_b
     t->finalized = false;
     t->verdict = HARP_OK;
     t->fast32 = false;
+    t->total_devices = 0;
     t->bytes = y.total;
 
     launch_build(d, t->lim, t->build_stream);
@@ -371,6 +397,40 @@ int harp_plan_h1f1b_batch(harp_ctx *ctx, harp_tables *t, const harp_candidates *
     else launch_plan_generic_h1f1b(t->dev, c, t_max, o, warmup, workspace, groups, static_cast<hipStream_t>(hip_stream));
     e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(ctx, e, "launching the H-1F1B planner kernels");
+    return HARP_OK;
+}
+
+size_t harp_plan_mesh_workspace_bytes(harp_ctx *ctx, harp_tables *t, const harp_orderings *od) {
+    if (check_orderings(ctx, t, od) != HARP_OK) return 0;
+    const size_t per_group = plan_mesh_ws_per_group(t->dev.L, od->S_max, t->total_devices);
+    return 256 + size_t(n_mesh_groups(ctx, od->C, per_group)) * per_group;
+}
+
+int harp_plan_mesh_batch(harp_ctx *ctx, harp_tables *t, const harp_orderings *od, const harp_plans *out,
+                         int32_t *stage_group, int32_t *stage_tp, void *workspace, size_t workspace_bytes,
+                         void *hip_stream) {
+    int rc = check_orderings(ctx, t, od);
+    if (rc != HARP_OK) return rc;
+    if (!out || (od->C > 0 && (!out->splits || !out->dev_first || !out->bottleneck || !out->iter_time ||
+                               !out->status || !stage_group || !stage_tp)))
+        return fail(ctx, HARP_ERR_INVALID_ARG, "null output array");
+    if (od->C == 0) return HARP_OK;
+    if (t->total_devices > 65535) return fail(ctx, HARP_ERR_SHAPE, "the submesh planner handles at most 65535 devices");
+    const size_t per_group = plan_mesh_ws_per_group(t->dev.L, od->S_max, t->total_devices);
+    const int groups = n_mesh_groups(ctx, od->C, per_group);
+    const size_t need = 256 + size_t(groups) * per_group;
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0)
+        return fail(ctx, HARP_ERR_WORKSPACE, "workspace must be a 256-byte aligned device pointer");
+    if (workspace_bytes < need)
+        return fail(ctx, HARP_ERR_WORKSPACE, "workspace holds %zu bytes, %zu needed", workspace_bytes, need);
+    hipError_t e = hipSetDevice(ctx->device);
+    if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
+    const OrdDev o = { od->C, od->G_max, od->S_max, od->ord_S, od->ord_G, od->ord_group };
+    const PlansDev pl = { out->splits, out->dev_first, out->bottleneck, out->iter_time, out->status };
+    launch_plan_mesh(t->dev, o, pl, stage_group, stage_tp, workspace, groups, t->total_devices,
+                     static_cast<hipStream_t>(hip_stream));
+    e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(ctx, e, "launching the submesh planner kernel");
     return HARP_OK;
 }
 

@@ -23,7 +23,8 @@ struct BuildHeader {
     unsigned int pad;
     unsigned long long max_act;  // largest act_bytes entry
     long long worst_time;        // largest stage or transfer time any plan can see
-    long long reserved[4];
+    long long total_devices;     // sum of group_ndev
+    long long reserved[3];
 };
 
 // Everything a kernel needs to read the tables; passed by value.
@@ -94,6 +95,14 @@ size_t plan_generic_h1f1b_ws_per_group(int L, int S_max);
 void launch_score_h1f1b(const TablesDev &tb, const CandDev &cd, const int32_t *splits, const int64_t *t_max,
                         int32_t *warmup, int64_t *bottleneck, int64_t *iter_time, int32_t *status,
                         hipStream_t st);
+struct OrdDev {
+    int32_t C, G_max, S_max;
+    const int32_t *ord_S, *ord_G, *ord_group;
+};
+constexpr int kMaxOrderGroups = 1024;   // groups one ordering may list (their offsets sit in LDS)
+void launch_plan_mesh(const TablesDev &tb, const OrdDev &od, const PlansDev &out, int32_t *stage_group,
+                      int32_t *stage_tp, void *ws, int n_groups, int64_t total_devices, hipStream_t st);
+size_t plan_mesh_ws_per_group(int L, int S_max, int64_t total_devices);
 size_t plan_fast_ws_bytes(int L, int S_max, int C, int n_groups);
 int plan_fast_groups(int L, int S_max, int n_cu);
 void launch_plan_exact(const TablesDev &tb, const CandDev &cd, const PlansDev &out, int32_t *n_passes,

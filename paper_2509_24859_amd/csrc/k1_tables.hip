@@ -460,6 +460,7 @@ __global__ __launch_bounds__(256) void k1_finalize(TablesDev tb, BuildLimits lim
             base += n > 0 ? n : 0;
             if (base > INT32_MAX) { atomicOr(&ovf_s, 1u); base = 0; }
         }
+        tb.header->total_devices = base;
     }
     if (groups_ok) {
         for (int q = threadIdx.x; q < tb.G * tb.n_tp; q += blockDim.x) {
@@ -524,8 +525,8 @@ __global__ __launch_bounds__(256) void k1_fast_rows(TablesDev tb) {
 __global__ void k1_clear_header(BuildHeader *h) {
     if (threadIdx.x == 0) {
         h->bad_arg = 0; h->overflow = 0; h->fast32 = 0; h->pad = 0;
-        h->max_act = 0; h->worst_time = 0;
-        for (int q = 0; q < 4; ++q) h->reserved[q] = 0;
+        h->max_act = 0; h->worst_time = 0; h->total_devices = 0;
+        for (int q = 0; q < 3; ++q) h->reserved[q] = 0;
     }
 }
 

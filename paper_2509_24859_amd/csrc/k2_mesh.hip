@@ -1,0 +1,219 @@
+// Submesh choice inside the recurrence (paper section 5.2.3, eq. dp_general's third index).
+//
+// A candidate is an order of device groups and a stage count S.  With O_k = devices of the first k
+// groups of the order, the state (s, i, d) means: the first s stages hold the first i operators and
+// use exactly the first d devices.  A stage placed at device offset d runs on the group k with
+// O_k <= d < O_{k+1} and takes tp of its devices (an allowed degree, d + tp <= O_{k+1}); when that
+// exhausts the group, the next stage is on the next group and the cut crosses the inter-group
+// link, otherwise the intra-group link.  All devices of all listed groups are used: the answer is
+// the state (S, L, O_K).  Min-max form with the classic 1F1B counts, as on the hot path:
+//   D[s+1][i][d + tp] = min over (j, tp) of max(D[s][j][d], time, comm),
+// ties resolved by the lowest previous cut j, then the smallest degree.
+//
+// Mapping: one workgroup per ordering at a time (drawn from a shared counter); within a stage one
+// lane per target cell (i, d'), the cells of a wave on consecutive i of one d' so that reads of the
+// previous row and of the table rows are contiguous.  For every degree the lane scans the previous
+// cuts downwards and stops once the stage time alone exceeds the best value found (the stage time
+// never decreases as j moves down) or the stage no longer fits in memory (monotone as well); the
+// stop is strict and the update accepts equal values at a lower j, which keeps the lowest j.  The
+// three-index table does not fit in LDS (L x devices entries per stage): the two live rows and the
+// back-pointers sit in a per-workgroup slice of the caller's workspace, L2-resident at the sizes
+// of interest.  Arithmetic in int64 from the int64 tables, so any degrees and time widths work.
+#include "harp_internal.h"
+#include "plan_common.h"
+
+namespace harp {
+
+namespace {
+
+constexpr int kMeshThreads = 256;
+
+struct MeshSlice {
+    int64_t *D0, *D1;    // [devices + 1][L + 1]
+    uint32_t *arg;       // [S_max][devices + 1][L + 1]: j | degree index << 16
+};
+
+__device__ __forceinline__ MeshSlice mesh_slice(unsigned char *ws, size_t per_group, int L, int64_t n_dev) {
+    unsigned char *mine = ws + size_t(blockIdx.x) * per_group;
+    const size_t row = size_t(n_dev + 1) * size_t(L + 1);
+    MeshSlice m;
+    m.D0 = reinterpret_cast<int64_t *>(mine);
+    m.D1 = m.D0 + row;
+    m.arg = reinterpret_cast<uint32_t *>(m.D1 + row);
+    return m;
+}
+
+__global__ __launch_bounds__(kMeshThreads) void k2_mesh(TablesDev tb, OrdDev od, PlansDev out,
+                                                        int32_t *stage_group, int32_t *stage_tp,
+                                                        unsigned char *ws, size_t per_group, int64_t n_dev,
+                                                        int *ticket) {
+    __shared__ int32_t offs[kMaxOrderGroups + 1];     // O_0 .. O_K
+    __shared__ int32_t order[kMaxOrderGroups];
+    __shared__ int32_t cuts[kMaxStages + 1];
+    __shared__ uint16_t slot_g[kMaxStages];
+    __shared__ uint8_t slot_k[kMaxStages];
+    __shared__ int32_t slot_first[kMaxStages];
+    __shared__ int shared_int[2];
+    const int L = tb.L, S_max = od.S_max;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int W = L + 1;
+    const MeshSlice m = mesh_slice(ws, per_group, L, n_dev);
+    const int64_t *PP = tb.PP(), *PS = tb.PS();
+
+    for (;;) {
+        __syncthreads();
+        if (tid == 0) shared_int[0] = atomicAdd(ticket, 1);
+        __syncthreads();
+        const int c = shared_int[0];
+        if (c >= od.C) break;
+        const int S = od.ord_S[c], K = od.ord_G[c];
+        const int32_t *og = od.ord_group + int64_t(c) * od.G_max;
+        int32_t *sg = stage_group + int64_t(c) * S_max, *stp = stage_tp + int64_t(c) * S_max;
+        auto fail = [&](int status) {
+            write_failed(out, c, S_max, status);
+            for (int s = tid; s < S_max; s += kMeshThreads) { sg[s] = -1; stp[s] = -1; }
+        };
+        // the ordering itself: counts in range, group ids in range and distinct
+        int bad = (S < 1 || S > S_max || K < 1 || K > od.G_max) ? 1 : 0;
+        if (!bad)
+            for (int k = tid; k < K; k += kMeshThreads) {
+                const int g = og[k];
+                if (g < 0 || g >= tb.G) { bad = 1; continue; }
+                for (int q = 0; q < k; ++q)
+                    if (og[q] == g) bad = 1;
+                order[k] = g;
+            }
+        if (__syncthreads_or(bad)) { fail(HARP_CAND_INVALID); continue; }
+        if (tid == 0) {
+            int64_t o = 0;
+            offs[0] = 0;
+            for (int k = 0; k < K; ++k) { o += tb.group_ndev[order[k]]; offs[k + 1] = int32_t(o); }
+        }
+        __syncthreads();
+        const int Dtot = offs[K];
+        if (S > L || S < K || S > Dtot) { fail(HARP_CAND_INFEASIBLE); continue; }
+
+        int64_t *Dp = m.D0, *Dn = m.D1;
+        for (int x = tid; x < (Dtot + 1) * W; x += kMeshThreads) Dp[x] = kInf;
+        __syncthreads();
+        if (tid == 0) Dp[0] = 0;                     // no stage, no operator, no device
+        for (int s = 0; s < S; ++s) {
+            __syncthreads();                         // row s is complete
+            const bool last = (s == S - 1);
+            const int64_t n_inflight = (S - s) < tb.M ? (S - s) : tb.M;
+            // targets: i in [i_lo, i_hi], d' in [d_lo, d_hi]; every later stage needs an operator and a device
+            const int i_lo = last ? L : s + 1, i_hi = L - (S - 1 - s);
+            const int d_lo = last ? Dtot : s + 1, d_hi = last ? Dtot : Dtot - (S - 1 - s);
+            const int n_i = i_hi - i_lo + 1, n_d = d_hi - d_lo + 1;
+            uint32_t *arg_s = m.arg + size_t(s) * size_t(n_dev + 1) * W;
+            for (int x = tid; x < n_i * n_d; x += kMeshThreads) {
+                const int i = i_lo + x % n_i, d2 = d_lo + x / n_i;
+                int64_t best = kInf;
+                int best_j = 0x7FFF, best_q = 0;
+                // the group whose devices end at or after d2: the stage [d2 - tp, d2) must lie inside one group
+                int k = 0;
+                while (offs[k + 1] < d2) ++k;        // offs[k] < d2 <= offs[k + 1]
+                const int g = order[k];
+                const int t = tb.group_type[g];
+                const int64_t *pf = tb.PF(t);
+                const int64_t mem_dev = tb.type_mem[t];
+                const int g_next = last ? g : (d2 == offs[k + 1] ? order[k + 1 < K ? k + 1 : k] : g);
+                int64_t cut = 0;
+                if (!last) {
+                    const int64_t link = tb.bw[int64_t(g) * tb.G + g_next];
+                    cut = (tb.act_bytes[i - 1] + link - 1) / link;
+                }
+                const int64_t pfi = pf[i], ppi = PP[i], psi = PS[i];
+                for (int q = 0; q < tb.n_tp; ++q) {
+                    const int64_t tp = tb.tp[q];
+                    const int d = d2 - int(tp);
+                    // the stage must stay inside group k, and s stages have used at least s devices
+                    // (row s holds nothing else: entries outside the ranges written for it are stale)
+                    if (d < offs[k] || d < s) continue;
+                    const int shift = tb.tp_shift[q];
+                    const int64_t *pr = tb.PR(g, q);
+                    const int64_t pri = pr[i];
+                    const int64_t capm = tp * mem_dev;
+                    const int64_t *row = Dp + size_t(d) * W;
+                    for (int j = i - 1; j >= s; --j) {
+                        const int64_t work = pfi - pf[j];
+                        const int64_t time = (shift >= 0 ? (work + tp - 1) >> shift : (work + tp - 1) / tp) + (pri - pr[j]);
+                        if (time > best) break;                     // no lower j can match the best value
+                        if ((ppi - PP[j]) + n_inflight * (psi - PS[j]) > capm) break;   // nor fit in memory
+                        const int64_t prev = row[j];
+                        if (prev == kInf) continue;
+                        int64_t val = prev > time ? prev : time;
+                        val = val > cut ? val : cut;
+                        if (val < best || (val == best && j < best_j)) { best = val; best_j = j; best_q = q; }
+                    }
+                }
+                Dn[size_t(d2) * W + i] = best;
+                arg_s[size_t(d2) * W + i] = uint32_t(best_j) | (uint32_t(best_q) << 16);
+            }
+            __syncthreads();
+            int64_t *tmp = Dp; Dp = Dn; Dn = tmp;
+        }
+        __syncthreads();
+        const int64_t value = Dp[size_t(Dtot) * W + L];
+        if (value == kInf) { fail(HARP_CAND_INFEASIBLE); continue; }
+        if (tid == 0) {
+            int i = L, d = Dtot;
+            cuts[S] = L;
+            for (int s = S; s >= 1; --s) {
+                const uint32_t a = m.arg[(size_t(s - 1) * size_t(n_dev + 1) + size_t(d)) * W + i];
+                const int j = int(a & 0xFFFFu), q = int(a >> 16);
+                d -= tb.tp[q];
+                int k = 0;
+                while (offs[k + 1] <= d) ++k;
+                cuts[s - 1] = j;
+                slot_g[s - 1] = uint16_t(order[k]);
+                slot_k[s - 1] = uint8_t(q);
+                slot_first[s - 1] = tb.group_base[order[k]] + (d - offs[k]);
+                i = j;
+            }
+        }
+        __syncthreads();
+        int32_t *sp = out.splits + int64_t(c) * (S_max + 1);
+        int32_t *df = out.dev_first + int64_t(c) * S_max;
+        for (int s = tid; s <= S_max; s += kMeshThreads) sp[s] = s <= S ? cuts[s] : -1;
+        for (int s = tid; s < S_max; s += kMeshThreads) {
+            sg[s] = s < S ? int32_t(slot_g[s]) : -1;
+            stp[s] = s < S ? tb.tp[slot_k[s]] : -1;
+            df[s] = s < S ? slot_first[s] : -1;
+        }
+        if (wave == 0) {
+            int64_t bott, iter;
+            const int st = wave_score_partition(tb, S, slot_g, slot_k, cuts, lane, bott, iter);
+            if (lane == 0) {
+                out.bottleneck[c] = bott;
+                out.iter_time[c] = iter;
+                out.status[c] = st;
+            }
+        }
+    }
+}
+
+__global__ void k2_mesh_clear(int *ticket) {
+    if (threadIdx.x == 0) *ticket = 0;
+}
+
+}  // namespace
+
+// Per-workgroup slice: two rows of the table, the back-pointers, and (first slice only) the ticket.
+size_t plan_mesh_ws_per_group(int L, int S_max, int64_t total_devices) {
+    const size_t row = size_t(total_devices + 1) * size_t(L + 1);
+    size_t b = 2 * row * sizeof(int64_t) + size_t(S_max) * row * sizeof(uint32_t);
+    return (b + 255) & ~size_t(255);
+}
+
+void launch_plan_mesh(const TablesDev &tb, const OrdDev &od, const PlansDev &out, int32_t *stage_group,
+                      int32_t *stage_tp, void *ws, int n_groups, int64_t total_devices, hipStream_t st) {
+    // layout: 256 bytes for the ticket, then the slices
+    int *ticket = static_cast<int *>(ws);
+    unsigned char *slices = static_cast<unsigned char *>(ws) + 256;
+    hipLaunchKernelGGL(k2_mesh_clear, dim3(1), dim3(64), 0, st, ticket);
+    hipLaunchKernelGGL(k2_mesh, dim3(n_groups), dim3(kMeshThreads), 0, st, tb, od, out, stage_group, stage_tp,
+                       slices, plan_mesh_ws_per_group(tb.L, od.S_max, total_devices), total_devices, ticket);
+}
+
+}  // namespace harp

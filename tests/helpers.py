@@ -100,6 +100,21 @@ def oracle_plan_h1f1b_threaded(tables, cands, t_max, threads=None, step=8):
     return out
 
 
+def oracle_plan_mesh_threaded(tables, orders, threads=None):
+    """Oracle submesh plans for a whole batch of orderings, one ordering per task over host threads."""
+    import os
+    from concurrent.futures import ThreadPoolExecutor
+
+    import oracle
+    threads = threads or min(16, len(os.sched_getaffinity(0)))
+    out = oracle.Plans(orders.C, orders.S_max)
+    out.stage_group = np.full((orders.C, orders.S_max), -1, dtype=np.int32)
+    out.stage_tp = np.full((orders.C, orders.S_max), -1, dtype=np.int32)
+    with ThreadPoolExecutor(threads) as ex:
+        list(ex.map(lambda c: oracle.plan_mesh_batch(tables, orders, c, c + 1, out), range(orders.C)))
+    return out
+
+
 def assert_plans_equal(got, want, label=""):
     """Bit-exact comparison of every output array of a batch."""
     for name in ("status", "splits", "dev_first", "bottleneck", "iter_time"):

@@ -1,0 +1,149 @@
+"""GPU parity of the planner that chooses the submesh of every stage inside the recurrence (section
+5.2.3, third index of eq. dp_general): harp_plan_mesh_batch against the oracle, bit for bit."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2509_24859_amd import workloads as W
+
+from helpers import assert_plans_equal, cands_from_lists, oracle_plan_mesh_threaded, simple_problem
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx(harp):
+    c = harp.Context(0)
+    yield c
+    c.close()
+
+
+def _check(harp, ctx, problem, orders, label):
+    want = oracle_plan_mesh_threaded(oracle.build_tables(problem), orders)
+    got, tables = harp.plan_mesh(ctx, problem, orders)
+    assert_plans_equal(got, want, label)
+    for name in ("stage_group", "stage_tp"):
+        a, b = getattr(got, name), getattr(want, name)
+        if not (a == b).all():
+            bad = np.nonzero((a != b).any(axis=1))[0]
+            raise AssertionError("%s: %s differs at %d orderings, first %d: got %s want %s"
+                                 % (label, name, bad.size, bad[0], a[bad[0]], b[bad[0]]))
+    return got, want, tables
+
+
+def test_mesh_hand_examples_and_statuses(harp, ctx):
+    p = simple_problem([3, 1, 1, 3], M=4, G=1, ndev=(2,), tp=(1, 2))
+    got, want, _ = _check(harp, ctx, p, W.orderings_from_lists([(1, [0]), (2, [0]), (3, [0])], S_max=3), "two devices")
+    assert list(got.stage_tp[0]) == [2, -1, -1] and got.bottleneck[0] == 4
+    assert list(got.splits[1]) == [0, 2, 4, -1] and list(got.status) == [0, 0, 1]
+    p = simple_problem([1] * 6, G=3, ndev=(2, 1, 1), tp=(1, 2), bw=np.ones((3, 3)))
+    lists = [(3, [0, 1, 2]), (4, [2, 0, 1]), (2, [0, 1, 2]), (5, [0, 1, 2]), (3, [0, 0, 1]), (3, [0, 3]),
+             (0, [0]), (3, [1, 2])]
+    got, want, _ = _check(harp, ctx, p, W.orderings_from_lists(lists, S_max=6), "statuses")
+    assert list(want.status) == [0, 0, 1, 1, 2, 2, 2, 1]
+    # an empty batch
+    got, _ = harp.plan_mesh(ctx, p, W.orderings_from_lists(lists, S_max=6).slice(0, 0))
+    assert got.status.shape == (0,)
+
+
+def test_mesh_random_small(harp, ctx):
+    feasible = 0
+    for seed in range(300):
+        w = W.random_small(seed)
+        p = w.problem
+        top = min(8, int(p.group_ndev.sum()))
+        orders = W.make_orderings(p, seed, 5, 1, max(top, p.G), 0, 12)
+        _, want, _ = _check(harp, ctx, p, orders, "seed %d" % seed)
+        feasible += int((want.status == oracle.OK).sum())
+    assert feasible > 1000
+
+
+@pytest.mark.parametrize("name,n", [("tiny", 16), ("llama7b", 256), ("llama70b", 96)])
+def test_mesh_workloads(harp, ctx, name, n):
+    w = W.make(name)
+    p = w.problem
+    orders = W.make_orderings(p, w.seed, w.config_id, p.G, w.S_max, 0, n)
+    got, want, tables = _check(harp, ctx, p, orders, name)
+    ok = want.status == oracle.OK
+    assert ok.any()
+    # the slicing found, handed to the hot path as an ordinary candidate, gives the same plan
+    cands = W.Candidates(orders.C, orders.S_max, orders.ord_S.copy(), np.where(got.stage_group < 0, 0, got.stage_group),
+                         np.where(got.stage_tp < 0, 1, got.stage_tp))
+    sub = cands.take(np.nonzero(ok)[0])
+    hot, _ = harp.plan(ctx, p, sub)
+    for field in ("splits", "dev_first", "bottleneck", "iter_time"):
+        assert (getattr(hot, field) == getattr(got, field)[ok]).all(), field
+    # and no random slicing of the same order does better
+    rng = np.random.default_rng(3)
+    lists = []
+    for c in np.nonzero(ok)[0]:
+        S, order = int(orders.ord_S[c]), orders.ord_group[c, :orders.ord_G[c]]
+        slots = None
+        for _ in range(200):                                     # rejection: total stages must come out as S
+            trial = []
+            for g in order:
+                left = int(p.group_ndev[g])
+                while left:
+                    d = int(rng.choice([x for x in p.tp_degrees if x <= left]))
+                    trial.append((int(g), d))
+                    left -= d
+            if len(trial) == S:
+                slots = trial
+                break
+        lists.append(slots if slots is not None else
+                     [(int(g), int(t)) for g, t in zip(got.stage_group[c, :S], got.stage_tp[c, :S])])
+    rand, _ = harp.plan(ctx, p, cands_from_lists(lists, S_max=orders.S_max))
+    assert (rand.bottleneck >= got.bottleneck[ok]).all()
+
+
+def test_mesh_forced_slicing_and_odd_degrees(harp, ctx):
+    for seed in range(20):
+        rng = np.random.default_rng(seed)
+        G, L = int(rng.integers(2, 5)), int(rng.integers(6, 40))
+        bw = rng.integers(1, 50, size=(G, G))
+        p = simple_problem(rng.integers(1, 100, size=L), M=int(rng.integers(1, 9)), G=G, ndev=(1,) * G,
+                           act=rng.integers(0, 400, size=L), bw=np.minimum(bw, bw.T),
+                           params=rng.integers(0, 50, size=L), stash=rng.integers(0, 20, size=L),
+                           mem=[int(rng.integers(600, 3000))])
+        order = [int(x) for x in rng.permutation(G)]
+        mesh, want, _ = _check(harp, ctx, p, W.orderings_from_lists([(G, order)]), "forced %d" % seed)
+        hot, _ = harp.plan(ctx, p, cands_from_lists([[(g, 1) for g in order]]))
+        for name in ("status", "splits", "dev_first", "bottleneck", "iter_time"):
+            assert (getattr(mesh, name) == getattr(hot, name)).all(), (seed, name)
+    rng = np.random.default_rng(8)
+    L = 70
+    p = simple_problem(np.zeros(L), M=6, G=2, ndev=(6, 6), tp=(1, 2, 3, 6),
+                       fwd=rng.integers(1, 1000, size=(1, L)), bwd=rng.integers(1, 1000, size=(1, L)),
+                       act=rng.integers(0, 10**5, size=L), params=rng.integers(0, 100, size=L),
+                       stash=rng.integers(0, 30, size=L), mem=[900], bw=[[900, 10], [10, 700]])
+    lists = [(S, order) for S in range(2, 13) for order in ([0, 1], [1, 0], [0], [1])]
+    _check(harp, ctx, p, W.orderings_from_lists(lists, S_max=12), "degrees 1 2 3 6")
+
+
+def test_mesh_medium_problem_properties(harp, ctx):
+    """A size the oracle cannot sweep in seconds (fine-grained workload: 160 operators, 256 devices):
+    what must hold whatever the size."""
+    import torch
+    w = W.make("finegrained")
+    p = w.problem
+    orders = W.make_orderings(p, w.seed, w.config_id, p.G, w.S_max, 0, 24)
+    got, tables = harp.plan_mesh(ctx, p, orders)
+    ok = got.status == oracle.OK
+    assert ok.any()
+    for c in np.nonzero(ok)[0]:
+        S = int(orders.ord_S[c])
+        g, t = got.stage_group[c, :S], got.stage_tp[c, :S]
+        # every device of every group used, groups in the given order, stages of a group adjacent
+        firsts = [int(g[s]) for s in range(S) if s == 0 or g[s] != g[s - 1]]
+        assert firsts == [int(x) for x in orders.ord_group[c, :orders.ord_G[c]]]
+        for grp in firsts:
+            assert int(t[g == grp].sum()) == int(p.group_ndev[grp])
+    # the reported times are the cost model's for the reported plan (scorer kernel, oracle on a sample)
+    cands = W.Candidates(orders.C, orders.S_max, orders.ord_S.copy(), np.where(got.stage_group < 0, 0, got.stage_group),
+                         np.where(got.stage_tp < 0, 1, got.stage_tp))
+    sub = cands.take(np.nonzero(ok)[0])
+    ob, ot, ost = oracle.score_1f1b(oracle.build_tables(p), sub, got.splits[ok])
+    assert (ost == 0).all() and (ob == got.bottleneck[ok]).all() and (ot == got.iter_time[ok]).all()
+    # and the hot path, given the slicing found, cannot do better nor worse
+    hot, _ = harp.plan(ctx, p, sub)
+    assert (hot.bottleneck == got.bottleneck[ok]).all()
