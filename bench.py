@@ -222,6 +222,55 @@ def h1f1b_search(ctx, binding, torch, w, tables, dc, cands, caps_host, reps, cpu
     return res
 
 
+def mesh_search(ctx, binding, torch, workloads, name, n_orders, reps, cpu_orders):
+    """The planner that chooses the slicing inside the recurrence, over a batch of random group
+    orderings of one of the smaller workloads (the state space has a device dimension, so the work
+    per ordering is devices x degrees times that of a hot-path candidate)."""
+    import numpy as np
+
+    w = workloads.make(name)
+    p = w.problem
+    orders = workloads.make_orderings(p, w.seed, w.config_id, p.G, w.S_max, 0, n_orders)
+    tables = binding.Tables(ctx, p)
+    do = binding.DeviceOrderings(ctx, orders)
+    out = binding.DevicePlans(ctx, do.C, do.S_max)
+    sg = torch.empty((do.C, do.S_max), dtype=torch.int32, device=ctx.device)
+    st = torch.empty_like(sg)
+    ws = binding.mesh_workspace(ctx, tables, do)
+    ms = timed_ms(torch, lambda: binding.harp_plan_mesh_batch(ctx, tables, do, out, sg, st, ws), reps)
+    got = out.to_host()
+    ok = got.status == 0
+    S = orders.ord_S.astype(np.float64)
+    dense = float((S * p.L * p.L / 2 * int(p.group_ndev.sum()) * len(p.tp_degrees)).sum())
+    res = {"kernel": "k2_mesh (one harp_plan_mesh_batch call)", "workload": "%s: L=%d, %d devices in %d groups, %d orderings, S<=%d"
+           % (name, p.L, int(p.group_ndev.sum()), p.G, do.C, do.S_max), "ms_per_call": ms,
+           "orderings_per_s": do.C / (ms * 1e-3), "dense_transitions_per_s": dense / (ms * 1e-3),
+           "feasible_fraction": float(ok.mean()), "workspace_bytes": int(ws.numel())}
+    if cpu_orders:
+        import oracle
+        from concurrent.futures import ThreadPoolExecutor
+        cores = min(16, len(os.sched_getaffinity(0)))
+        n = min(do.C, cpu_orders)
+        sub = orders.slice(0, n)
+        ot = oracle.build_tables(p)
+        want = oracle.Plans(n, sub.S_max)
+        want.stage_group = np.full((n, sub.S_max), -1, dtype=np.int32)
+        want.stage_tp = np.full((n, sub.S_max), -1, dtype=np.int32)
+        t0 = time.perf_counter()
+        with ThreadPoolExecutor(cores) as ex:
+            list(ex.map(lambda c: oracle.plan_mesh_batch(ot, sub, c, c + 1, want), range(n)))
+        dt = time.perf_counter() - t0
+        for field in ("status", "splits", "dev_first", "bottleneck", "iter_time"):
+            if not (getattr(want, field) == getattr(got, field)[:n]).all():
+                raise SystemExit("GPU submesh plans differ from the oracle in %s on the baseline sample" % field)
+        if not (want.stage_tp == st[:n].cpu().numpy()).all() or not (want.stage_group == sg[:n].cpu().numpy()).all():
+            raise SystemExit("GPU submesh slicings differ from the oracle on the baseline sample")
+        res["cpu_baseline"] = {"value": n / dt, "unit": "orderings/s", "cores": cores, "kind": "oracle",
+                               "sample": "first %d orderings over %d threads, %.1f s wall; GPU answers for the "
+                                         "sample verified bit-exact" % (n, cores, dt)}
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -241,6 +290,10 @@ def main():
     ap.add_argument("--h1f1b-reps", type=int, default=3,
                     help="timed calls of the H-1F1B recurrence at the exact search's caps (0 = skip)")
     ap.add_argument("--h1f1b-cpu-candidates", type=int, default=1024)
+    ap.add_argument("--mesh-workload", default="llama70b")
+    ap.add_argument("--mesh-orderings", type=int, default=4096,
+                    help="group orderings for the submesh-in-recurrence planner (0 = skip)")
+    ap.add_argument("--mesh-cpu-orderings", type=int, default=128)
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="also run one plain device copy of this many MiB (reference for HBM counters)")
     args = ap.parse_args()
@@ -365,6 +418,9 @@ def main():
         result["h1f1b"] = h1f1b_search(ctx, binding, torch, w, tables, dc, cands, result.pop("_exact_caps"),
                                        args.h1f1b_reps, 0 if args.no_cpu_baseline else args.h1f1b_cpu_candidates)
     result.pop("_exact_caps", None)
+    if args.mesh_orderings:
+        result["mesh"] = mesh_search(ctx, binding, torch, workloads, args.mesh_workload, args.mesh_orderings, 2,
+                                     0 if args.no_cpu_baseline else args.mesh_cpu_orderings)
     if not args.no_cpu_baseline:
         # about 20 core-seconds of oracle work at 1-5 ns per dense transition
         budget = args.cpu_candidates or max(64, int(1.6e10 / max(1.0, n_trans / C)))
