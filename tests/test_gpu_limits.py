@@ -1,0 +1,94 @@
+"""GPU parity at the stated limits of the entry points: the largest stage count, the longest
+sequence the 32-bit path takes, sequences beyond it (int64 path), and S = L."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2509_24859_amd import workloads as W
+
+from helpers import (assert_plans_equal, cands_from_lists, oracle_plan_exact_threaded, oracle_plan_h1f1b_threaded,
+                     oracle_plan_threaded, same_slot, simple_problem)
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx(harp):
+    c = harp.Context(0)
+    yield c
+    c.close()
+
+
+def _all_entry_points(harp, ctx, p, cands, label, exact=True):
+    tables = oracle.build_tables(p)
+    want = oracle_plan_threaded(tables, cands)
+    fast32 = harp.Tables(ctx, p).fast32
+    paths = [harp.PATH_GENERIC] + ([harp.PATH_FAST32] if fast32 else [])
+    for path in paths:
+        got, _ = harp.plan(ctx, p, cands, path)
+        assert_plans_equal(got, want, "%s min-max path %d" % (label, path))
+    caps = np.where(want.status == oracle.OK, want.bottleneck // 8 * 9, 3).astype(np.int64)
+    want_h = oracle_plan_h1f1b_threaded(tables, cands, caps)
+    for path in paths:
+        got, _ = harp.plan_h1f1b(ctx, p, cands, caps, path)
+        assert_plans_equal(got, want_h, "%s H-1F1B path %d" % (label, path))
+        assert (got.warmup == want_h.warmup).all()
+    if exact:
+        want_e = oracle_plan_exact_threaded(tables, cands)
+        for path in paths:
+            got, _, _ = harp.plan_exact(ctx, p, cands, path)
+            assert_plans_equal(got, want_e, "%s exact path %d" % (label, path))
+    return want, fast32
+
+
+def test_largest_stage_count(harp, ctx):
+    """S = S_max = 256 stages on one group of 256 devices."""
+    rng = np.random.default_rng(41)
+    L = 300
+    p = simple_problem(np.zeros(L), M=300, G=1, ndev=(256,), tp=(1, 2),
+                       fwd=rng.integers(1, 500, size=(1, L)), bwd=rng.integers(1, 900, size=(1, L)),
+                       act=rng.integers(0, 10**4, size=L), params=rng.integers(0, 1000, size=L),
+                       stash=rng.integers(0, 50, size=L), mem=[40000], bw=[[50]])
+    cands = cands_from_lists([same_slot(256), same_slot(255), same_slot(200), [(0, 2)] * 128, [(0, 2)] * 129],
+                             S_max=256)
+    want, fast32 = _all_entry_points(harp, ctx, p, cands, "256 stages", exact=False)
+    assert fast32 and list(want.status[:4]) == [0, 0, 0, 0] and want.status[4] == oracle.INVALID
+    # one beyond the limit is an argument error, not a silent truncation
+    import torch
+    tables = harp.Tables(ctx, p)
+    over = cands_from_lists([same_slot(256)], S_max=257)
+    with pytest.raises(harp.HarpError) as e:
+        dc = harp.DeviceCandidates(ctx, over)
+        out = harp.DevicePlans(ctx, 1, 257)
+        harp.harp_plan_batch(ctx, tables, dc, out, torch.empty(1 << 20, dtype=torch.uint8, device=ctx.device))
+    assert e.value.code == harp.ERR_SHAPE
+
+
+def test_every_operator_its_own_stage(harp, ctx):
+    """S = L: the only partition has one operator per stage; S = L + 1 has none."""
+    rng = np.random.default_rng(42)
+    L = 64
+    p = simple_problem(rng.integers(1, 100, size=L), M=7, G=2, ndev=(40, 40), tp=(1, 2),
+                       act=rng.integers(0, 2000, size=L), bw=[[100, 7], [7, 90]])
+    slots = [(0, 1)] * 30 + [(1, 1)] * 34
+    cands = cands_from_lists([slots, slots + [(1, 1)], slots[:-1]], S_max=65)
+    want, _ = _all_entry_points(harp, ctx, p, cands, "S = L")
+    assert list(want.status) == [oracle.OK, oracle.INFEASIBLE, oracle.OK]
+    assert list(want.splits[0, :L + 1]) == list(range(L + 1))
+
+
+def test_longest_sequence_of_the_32_bit_path_and_beyond(harp, ctx):
+    rng = np.random.default_rng(43)
+    for L, expect_fast in ((1024, True), (1025, False), (3000, False)):
+        G = 3
+        bw = rng.integers(20, 4000, size=(G, G))
+        # many microbatches keep [t_S, t_E] narrow, so that the oracle's sweep stays in seconds
+        p = simple_problem(np.zeros(L), M=5000, T=2, G=G, ndev=(8, 8, 8), tp=(1, 2, 4),
+                           fwd=rng.integers(1, 2000, size=(2, L)), bwd=rng.integers(1, 3000, size=(2, L)),
+                           act=rng.integers(0, 10**6, size=L), params=rng.integers(1, 10**5, size=L),
+                           stash=rng.integers(0, 10**3, size=L), gtype=[0, 1, 0],
+                           mem=[int(4e7), int(3e7)], bw=np.minimum(bw, bw.T))
+        cands = W.make_candidates(p, L, 91, G, 6, 0, 6 if L > 2000 else 16)
+        print("L = %d" % L, flush=True)
+        want, fast32 = _all_entry_points(harp, ctx, p, cands, "L = %d" % L, exact=(L <= 1025))
+        assert fast32 == expect_fast and (want.status == oracle.OK).any()
