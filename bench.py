@@ -28,6 +28,10 @@ LANE_OPS_PER_TRANSITION = 26
 # (profiles/plan_batch_stress_pmc.txt: FETCH_SIZE + WRITE_SIZE of k2_band and k2_fast, each scaled by
 # a plain copy's reading)
 MEASURED_TRAFFIC_BYTES = {"stress": 3.394e9 + 1.795e9 + 0.254e9 + 0.344e9}
+# issued-instruction view of k2_fast on the same workload, from the same counter runs
+MEASURED_ISSUE = {"stress": {"valu_issue_utilisation": 0.686, "lanes_active_per_valu_instruction": 0.57,
+                             "lds_bank_conflict_fraction": 0.12,
+                             "source": "profiles/plan_batch_stress_pmc.txt (rocprofv3 --pmc, k2_fast)"}}
 
 
 def cpu_baseline(w, cands, gpu_plans, budget_candidates):
@@ -398,6 +402,7 @@ def main():
             "bound": "alu", "kernel": kernel,
             "achieved": achieved / 1e12, "peak": ALU_PEAK_LANE_OPS / 1e12, "unit": "T int32 lane-op/s",
             "frac": achieved / ALU_PEAK_LANE_OPS, "traffic": traffic,
+            "issued": MEASURED_ISSUE.get(args.workload) if C == w.C and fast else None,
             "note": "achieved = dense-recurrence transitions per launch x 26 lane-ops / mean kernel time "
                     "(HIP events on the launch stream around harp_plan_batch); the kernels evaluate far fewer "
                     "transitions than the dense count (reachability bands, bounded scans), so this is work "
