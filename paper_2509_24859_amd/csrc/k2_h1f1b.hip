@@ -70,8 +70,8 @@ __device__ __forceinline__ void h1f1b_body(const TablesDev &tb, const CandDev &c
     const int wave = uniform(tid >> 6);
     MemPair *mem = reinterpret_cast<MemPair *>(lds_raw);                               // [row_len]
     Entry *rows = reinterpret_cast<Entry *>(mem + row_len);                            // [2][row_len]
-    uint32_t *prow = reinterpret_cast<uint32_t *>(rows + 2 * row_len);                 // [row_len]
-    StageConst *sc = reinterpret_cast<StageConst *>(prow + row_len);                   // [S_max]
+    uint32_t *prow = reinterpret_cast<uint32_t *>(rows + 2 * row_len);                 // [2][row_len]
+    StageConst *sc = reinterpret_cast<StageConst *>(prow + 2 * row_len);               // [S_max]
     uint64_t *scal = reinterpret_cast<uint64_t *>(sc + S_max);                         // [2]
     uint32_t *band = reinterpret_cast<uint32_t *>(scal + 2);                           // [S_max + 1]
     int32_t *trial = reinterpret_cast<int32_t *>(band + S_max + 1);                    // [S_max + 1]
@@ -88,6 +88,8 @@ __device__ __forceinline__ void h1f1b_body(const TablesDev &tb, const CandDev &c
     {
         const int64_t *PP = tb.PP(), *PS = tb.PS();
         for (int j = tid; j <= L; j += nthreads) mem[j] = MemPair{PP[j], PS[j]};
+        for (int j = L + 1 + tid; j < row_len; j += nthreads) mem[j] = MemPair{0, 0};
+        for (int j = L + 1 + tid; j < row_len; j += nthreads) { prow[j] = 0; prow[row_len + j] = 0; }
     }
 
     for (;;) {
@@ -133,30 +135,53 @@ __device__ __forceinline__ void h1f1b_body(const TablesDev &tb, const CandDev &c
         }
         // stored sums stay this small, so that adding an admissible stage time cannot reach infinity
         const uint64_t limit = kWide ? uint64_t(kInfSum) - 1 : uint64_t(kInfSum) - 1 - tcap;
-        int cur = 0;
+        __syncthreads();          // slot constants and bands are in LDS
+        // prologue: the fused time row of the last slot over its cells and its single continuation
+        {
+            const int il0 = (S == 1) ? 0 : band_lo((uint32_t)uniform((int)band[S - 1]));
+            const uint32_t *p32 = tb.P32 + (uint32_t)uniform((int)sc[S - 1].p_row);
+            for (int x = il0 + tid; x <= L; x += nthreads) prow[x] = p32[x];
+        }
+        lds_barrier();
+        int cur = 0, pcur = 0;
+        const int wave_first = wave * 64;
         for (int slot = S - 1; slot >= 0; --slot) {
-            __syncthreads();      // slot constants are in LDS; the previous slot is done with prow
             const uint32_t b0 = (uint32_t)uniform((int)band[slot]);
             const uint32_t b1 = (uint32_t)uniform((int)band[slot + 1]);
             const int il = slot == 0 ? 0 : band_lo(b0), ih = slot == 0 ? 0 : band_hi(b0);   // cells
             const int jl = band_lo(b1), jh = band_hi(b1);                                     // continuations
+            // what the slot in front will read of its own time row: its cells and this slot's cells
+            const int nl = slot >= 2 ? band_lo((uint32_t)uniform((int)band[slot - 1])) : 0;
+            const bool stage_next = slot >= 1;
+            // a wave whose lanes own neither a cell nor a staged entry only keeps the barrier
+            if (il + wave_first > ih && (!stage_next || nl + wave_first > ih)) {
+                lds_barrier();
+                cur ^= 1;
+                pcur ^= 1;
+                continue;
+            }
             const uint32_t rsv = (uint32_t)uniform((int)sc[slot].cm_row_shift);
             const int shift = int(rsv >> 27);
             const uint32_t tp = 1u << shift;
             const int64_t capm = uniform64(sc[slot].cap);
-            {
-                const uint32_t *p32 = tb.P32 + (uint32_t)uniform((int)sc[slot].p_row);
-                for (int x = il + tid; x <= jh; x += nthreads) prow[x] = p32[x];
-            }
-            __syncthreads();
+            const uint32_t *pr_cur = prow + pcur * row_len;
+            uint32_t *pr_next = prow + (pcur ^ 1) * row_len;
             const Entry *prev = rows + cur * row_len;
             Entry *next = rows + (cur ^ 1) * row_len;
             // the cut in front of this slot's stage (between slot - 1 and slot)
-            const uint32_t *cm_front = slot > 0 ? tb.CM + ((uint32_t)uniform((int)sc[slot - 1].cm_row_shift) & kRowMask)
-                                                : nullptr;
+            const uint32_t *cm_front = stage_next ? tb.CM + ((uint32_t)uniform((int)sc[slot - 1].cm_row_shift) & kRowMask)
+                                                  : nullptr;
+            const uint32_t *p32_n = stage_next ? tb.P32 + (uint32_t)uniform((int)sc[slot - 1].p_row) : nullptr;
+            // requests for the slot in front: entry xn of its time row, and this lane's own cut time
+            const int xn = nl + tid;
+            uint32_t p_n = 0, cf_first = 0;
+            if (stage_next && xn <= ih) p_n = p32_n[xn];
+            if (stage_next && il + tid <= ih) cf_first = cm_front[il + tid];
+
+            bool first_trip = true;
             for (int i = il + tid; i <= ih; i += nthreads) {
                 const MemPair mi = mem[i];
-                const uint32_t xi = prow[i];
+                const uint32_t xi = pr_cur[i];
                 SumT best = kInfSum;
                 uint32_t best_n = 0;
                 int best_j = 0;
@@ -167,9 +192,11 @@ __device__ __forceinline__ void h1f1b_body(const TablesDev &tb, const CandDev &c
                     int64_t least = 0;
 #pragma unroll
                     for (int u = 0; u < 4; ++u) {
+                        // entries behind the band (up to kTail behind L) hold an infinite sum; what
+                        // the other rows hold there is never used
                         const Entry e = prev[j + u];
-                        const MemPair mj = mem[(j + u) <= L ? (j + u) : L];
-                        tj = (prow[(j + u) <= L ? (j + u) : L] + tp - 1 - xi) >> shift;
+                        const MemPair mj = mem[j + u];
+                        tj = (pr_cur[j + u] + tp - 1 - xi) >> shift;
                         const int64_t dpp = mj.pp - mi.pp, dps = mj.ps - mi.ps;
                         least = dpp + dps;                                   // need at the smallest count
                         const bool fits = dpp + int64_t(e.nn) * dps <= capm;
@@ -183,8 +210,8 @@ __device__ __forceinline__ void h1f1b_body(const TablesDev &tb, const CandDev &c
                     j += 4;
                 }
                 arg[slot * arg_pitch + i] = (uint16_t)best_j;
-                if (slot > 0) {
-                    const uint32_t cf = cm_front[i];
+                if (stage_next) {
+                    const uint32_t cf = first_trip ? cf_first : cm_front[i];
                     const uint64_t total = uint64_t(best) + 2ull * cf;
                     const bool reach = (best < kInfSum) & (cf <= tcap);
                     if (reach & (total > limit)) flags[1] = 1;        // needs 64-bit sums
@@ -194,9 +221,16 @@ __device__ __forceinline__ void h1f1b_body(const TablesDev &tb, const CandDev &c
                 } else {
                     scal[0] = uint64_t(best);
                 }
+                first_trip = false;
             }
-            if (slot > 0 && tid < kTail) next[ih + 1 + tid].h = kInfSum;     // behind the band
+            if (stage_next) {
+                if (tid < kTail) next[ih + 1 + tid].h = kInfSum;     // behind the band
+                if (xn <= ih) pr_next[xn] = p_n;
+                for (int x = xn + nthreads; x <= ih; x += nthreads) pr_next[x] = p32_n[x];
+            }
+            lds_barrier();
             cur ^= 1;
+            pcur ^= 1;
         }
         __syncthreads();
         if (!kWide && uniform((int)flags[1]) != 0) {
@@ -286,7 +320,7 @@ void k2_h1f1b_wide(TablesDev tb, CandDev cd, const int64_t *t_max, PlansDev out,
 int h1f1b_row_len(int L) { return (L + 1 + kTail + 7) / 8 * 8; }
 
 size_t h1f1b_lds_bytes(int L, int S_max, size_t entry) {
-    size_t b = size_t(h1f1b_row_len(L)) * (sizeof(MemPair) + 2 * entry + 4) + size_t(S_max) * sizeof(StageConst) +
+    size_t b = size_t(h1f1b_row_len(L)) * (sizeof(MemPair) + 2 * entry + 8) + size_t(S_max) * sizeof(StageConst) +
                16 + size_t(S_max + 1) * 8 + 8 + size_t(S_max) * 3;
     return (b + 15) & ~size_t(15);
 }
