@@ -50,7 +50,8 @@ def _load():
         _lib = C.CDLL(build())
         for name in ("oracle_build_tables", "oracle_plan_batch", "oracle_score_1f1b",
                      "oracle_argmin_batch", "oracle_plan_exact_batch", "oracle_plan_h1f1b_batch",
-                     "oracle_score_h1f1b", "oracle_plan_mesh_batch"):
+                     "oracle_score_h1f1b", "oracle_plan_mesh_batch",
+                     "oracle_plan_mesh_exact_batch"):
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -183,22 +184,29 @@ def score_h1f1b(tables: Tables, cands, splits, t_max):
 
 
 def plan_mesh_batch(tables: Tables, orders, c_begin: int = 0, c_end: int | None = None,
-                    out: Plans | None = None) -> Plans:
-    """Min-max recurrence with the submesh of every stage chosen inside it; `orders` is a batch of
-    group orderings.  `out.stage_group`, `out.stage_tp` give the slicing found."""
+                    out: Plans | None = None, exact: bool = False) -> Plans:
+    """Recurrence with the submesh of every stage chosen inside it; `orders` is a batch of group
+    orderings.  exact=False: the min-max plan; exact=True: the optimum of the iteration-time model by
+    the sweep over the cap (`out.n_caps` counts the caps).  `out.stage_group`, `out.stage_tp` give
+    the slicing found."""
     c_end = orders.C if c_end is None else c_end
     out = Plans(orders.C, orders.S_max) if out is None else out
     if not hasattr(out, "stage_group"):
         out.stage_group = np.full((orders.C, orders.S_max), -1, dtype=np.int32)
         out.stage_tp = np.full((orders.C, orders.S_max), -1, dtype=np.int32)
+    if exact and not hasattr(out, "n_caps"):
+        out.n_caps = np.zeros(orders.C, dtype=np.int32)
     os_, og_, ogr = _c32(orders.ord_S), _c32(orders.ord_G), _c32(orders.ord_group)
-    rc = _load().oracle_plan_mesh_batch(
-        C.byref(tables.c), _ptr(tables.PF), _ptr(tables.PP), _ptr(tables.PS), _ptr(tables.PR),
-        C.c_int32(orders.C), C.c_int32(orders.G_max), C.c_int32(orders.S_max), _ptr(os_), _ptr(og_), _ptr(ogr),
-        C.c_int32(c_begin), C.c_int32(c_end), _ptr(out.splits), _ptr(out.stage_group), _ptr(out.stage_tp),
-        _ptr(out.dev_first), _ptr(out.bottleneck), _ptr(out.iter_time), _ptr(out.status))
+    args = [C.byref(tables.c), _ptr(tables.PF), _ptr(tables.PP), _ptr(tables.PS), _ptr(tables.PR),
+            C.c_int32(orders.C), C.c_int32(orders.G_max), C.c_int32(orders.S_max), _ptr(os_), _ptr(og_), _ptr(ogr),
+            C.c_int32(c_begin), C.c_int32(c_end), _ptr(out.splits), _ptr(out.stage_group), _ptr(out.stage_tp),
+            _ptr(out.dev_first), _ptr(out.bottleneck), _ptr(out.iter_time), _ptr(out.status)]
+    if exact:
+        rc = _load().oracle_plan_mesh_exact_batch(*args, _ptr(out.n_caps))
+    else:
+        rc = _load().oracle_plan_mesh_batch(*args)
     if rc != 0:
-        raise ValueError("oracle_plan_mesh_batch failed with code %d" % rc)
+        raise ValueError("oracle mesh planner failed with code %d" % rc)
     return out
 
 

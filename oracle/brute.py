@@ -420,3 +420,83 @@ def plan_mesh(p, S: int, S_max: int, groups):
         cuts.append(j)
         i = j
     return 0, value, cuts[::-1], slots[::-1]
+
+
+def mesh_best_iteration_time(p, S: int, groups):
+    """(T*, bottleneck) of the best plan over EVERY slicing of the ordered groups into S stages and
+    every partition, by enumeration; among equal iteration times the smaller bottleneck."""
+    L = int(p.L)
+    best = (INF, INF)
+    if S <= L:
+        for slots in slicings(p, groups, S):
+            grp = [g for g, _ in slots]
+            tp = [d for _, d in slots]
+            for b in partitions(L, S):
+                if any(stage_cost(p, S, grp, tp, s, b[s], b[s + 1]) == INF for s in range(S)):
+                    continue
+                bott, T = score(p, S, grp, tp, b)
+                best = min(best, (T, bott))
+    return best
+
+
+def plan_mesh_capped(p, S: int, groups, cap: int):
+    """Least sum of (t + 2c) with every stage and transfer time at most cap, over slicings and
+    partitions, as a memoised recursion over (stages, operators, devices); ties: lowest previous
+    cut, then smallest degree.  Returns (sum, cuts, slot list) or (INF, None, None)."""
+    L, M = int(p.L), int(p.M)
+    groups = [int(g) for g in groups]
+    bounds = [0]
+    for g in groups:
+        bounds.append(bounds[-1] + int(p.group_ndev[g]))
+    total = bounds[-1]
+    degrees = [int(x) for x in p.tp_degrees]
+    memo = {}
+
+    def group_at(d):
+        return max(k for k in range(len(groups)) if bounds[k] <= d)
+
+    def state(s, i, d):
+        if s == 0:
+            return (0, -1, -1) if (i == 0 and d == 0) else (INF, -1, -1)
+        key = (s, i, d)
+        if key in memo:
+            return memo[key]
+        best = (INF, -1, -1)
+        last = s == S
+        n = min(S - (s - 1), M)
+        for q, deg in enumerate(degrees):
+            d0 = d - deg
+            if d0 < 0:
+                continue
+            k = group_at(d0)
+            if d > bounds[k + 1] or (d == total) != last:
+                continue
+            g = groups[k]
+            g_next = g if (last or d < bounds[k + 1]) else groups[k + 1]
+            c = 0 if last else cut_time(p, g, g_next, i)
+            if c > cap:
+                continue
+            for j in range(s - 1, i):
+                prev = state(s - 1, j, d0)[0]
+                t = stage_time(p, g, deg, j, i)
+                if prev == INF or t > cap or not memory_fits(p, g, deg, n, j, i):
+                    continue
+                if (prev + t + 2 * c, j, q) < best:
+                    best = (prev + t + 2 * c, j, q)
+        memo[key] = best
+        return best
+
+    if S > L or S < len(groups) or S > total:
+        return INF, None, None
+    value = state(S, L, total)[0]
+    if value == INF:
+        return INF, None, None
+    cuts, slots = [L], []
+    i, d = L, total
+    for s in range(S, 0, -1):
+        _, j, q = state(s, i, d)
+        d -= degrees[q]
+        slots.append((groups[group_at(d)], degrees[q]))
+        cuts.append(j)
+        i = j
+    return value, cuts[::-1], slots[::-1]

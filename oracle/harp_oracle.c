@@ -658,11 +658,115 @@ int oracle_score_h1f1b(const oracle_problem *p, const int64_t *PF, const int64_t
  *   D[s+1][i][d + tp] = min over (j, tp) of max(D[s][j][d], time, comm)
  * with ties resolved by the lowest previous cut j, then the smallest degree.
  * ------------------------------------------------------------------------------------------- */
-int oracle_plan_mesh_batch(const oracle_problem *p, const int64_t *PF, const int64_t *PP, const int64_t *PS,
-                           const int64_t *PR, int32_t C, int32_t G_max, int32_t S_max, const int32_t *ord_S,
-                           const int32_t *ord_G, const int32_t *ord_group, int32_t c_begin, int32_t c_end,
-                           int32_t *splits, int32_t *stage_group, int32_t *stage_tp, int32_t *dev_first,
-                           int64_t *bottleneck, int64_t *iter_time, int32_t *status)
+/* Scratch of the three-index table for one call. */
+typedef struct {
+    int64_t *D;          /* (S_max + 1) x (L + 1) x (devices + 1) */
+    int32_t *arg_j, *arg_k;
+    int64_t *O;          /* offsets of the ordered groups */
+    size_t W, Dn;
+} mesh_tables;
+
+#define MESH_AT(m, s, i, d) (((size_t)(s) * (m)->W + (size_t)(i)) * (m)->Dn + (size_t)(d))
+
+/* Fills the table for one ordering (K groups og[], offsets m->O) and S stages.
+ * capped = 0: min-max form.  capped = 1: least sum of (t + 2c) over transitions whose stage and
+ * transfer times are at most cap (constraints (i), (ii)).  Ties: lowest previous cut, then
+ * smallest degree.  If caps is not NULL, every fitting transition's max(time, comm) inside
+ * [cap_lo, cap_hi] is appended to it (the candidate caps of section 5.2.4 (2)). */
+static int mesh_fill(const tables_view *v, mesh_tables *m, int K, const int32_t *og, int S, int capped,
+                     int64_t cap, int64_t **caps, size_t *n_caps, size_t *caps_room, int64_t cap_lo,
+                     int64_t cap_hi)
+{
+    const oracle_problem *p = v->p;
+    const int L = p->L;
+    const int64_t Dtot = m->O[K];
+    for (size_t x = 0; x < (size_t)(S + 1) * m->W * m->Dn; ++x) { m->D[x] = ORACLE_INF; m->arg_j[x] = -1; m->arg_k[x] = -1; }
+    m->D[MESH_AT(m, 0, 0, 0)] = 0;
+    for (int s = 0; s < S; ++s) {
+        const int last = (s == S - 1);
+        const int64_t n = (S - s) < p->M ? (S - s) : p->M;
+        int k = 0;
+        for (int64_t d = 0; d < Dtot; ++d) {
+            while (m->O[k + 1] <= d) ++k;                      /* the group this stage runs on */
+            const int g = og[k];
+            for (int q = 0; q < p->n_tp; ++q) {
+                const int tp = p->tp_degrees[q];
+                const int64_t d2 = d + tp;
+                if (d2 > m->O[k + 1]) continue;                /* a stage stays inside one group */
+                if (last != (d2 == Dtot)) continue;            /* the last stage, and only it, uses up the devices */
+                const int g_next = last ? g : (d2 == m->O[k + 1] ? og[k + 1] : g);
+                for (int i = s + 1; i <= L - (S - 1 - s); ++i) {
+                    if (last && i != L) continue;
+                    const int64_t cc = last ? 0 : cut_time(p, g, g_next, i);
+                    int64_t best = m->D[MESH_AT(m, s + 1, i, d2)];
+                    int32_t bj = m->arg_j[MESH_AT(m, s + 1, i, d2)], bq = m->arg_k[MESH_AT(m, s + 1, i, d2)];
+                    for (int j = s; j < i; ++j) {
+                        if (!memory_fits(v, g, tp, n, j, i)) continue;
+                        const int64_t t = stage_time(v, g, tp, j, i);
+                        if (caps) {
+                            const int64_t w = max64(t, cc);
+                            if (w >= cap_lo && w <= cap_hi) {
+                                if (*n_caps == *caps_room) {
+                                    *caps_room *= 2;
+                                    *caps = (int64_t *)realloc(*caps, sizeof(int64_t) * *caps_room);
+                                    if (!*caps) return ORACLE_BAD_ARG;
+                                }
+                                (*caps)[(*n_caps)++] = w;
+                            }
+                        }
+                        const int64_t prev = m->D[MESH_AT(m, s, j, d)];
+                        if (prev == ORACLE_INF) continue;
+                        int64_t val;
+                        if (capped) {
+                            if (t > cap || cc > cap) continue;
+                            val = prev + t + 2 * cc;
+                        } else {
+                            val = max64(prev, max64(t, cc));
+                        }
+                        if (val < best || (val == best && (j < bj || (j == bj && q < bq)))) {
+                            best = val; bj = j; bq = q;
+                        }
+                    }
+                    m->D[MESH_AT(m, s + 1, i, d2)] = best;
+                    m->arg_j[MESH_AT(m, s + 1, i, d2)] = bj;
+                    m->arg_k[MESH_AT(m, s + 1, i, d2)] = bq;
+                }
+            }
+        }
+    }
+    return ORACLE_OK;
+}
+
+/* Follows the back-pointers from (S, L, all devices): cuts, group and degree of every stage. */
+static void mesh_backtrack(const tables_view *v, const mesh_tables *m, int K, const int32_t *og, int S,
+                           int32_t *sp, int32_t *sg, int32_t *st)
+{
+    const oracle_problem *p = v->p;
+    int i = p->L;
+    int64_t d = m->O[K];
+    sp[S] = p->L;
+    for (int s = S; s >= 1; --s) {
+        const int j = m->arg_j[MESH_AT(m, s, i, d)], q = m->arg_k[MESH_AT(m, s, i, d)];
+        const int tp = p->tp_degrees[q];
+        d -= tp;
+        int k = 0;
+        while (m->O[k + 1] <= d) ++k;
+        sp[s - 1] = j;
+        sg[s - 1] = og[k];
+        st[s - 1] = tp;
+        i = j;
+    }
+    if (i != 0 || d != 0) abort();
+}
+
+/* exact = 0: the min-max plan of every ordering.  exact = 1: the optimum of eq. gpipe_cost_model
+ * over every slicing and partition, by the increasing sweep over the cap (section 5.2.4 (2)) with
+ * the capped least-sum table at every cap; n_caps (may be NULL) receives the caps swept. */
+static int mesh_batch(const oracle_problem *p, const int64_t *PF, const int64_t *PP, const int64_t *PS,
+                      const int64_t *PR, int32_t C, int32_t G_max, int32_t S_max, const int32_t *ord_S,
+                      const int32_t *ord_G, const int32_t *ord_group, int32_t c_begin, int32_t c_end,
+                      int32_t *splits, int32_t *stage_group, int32_t *stage_tp, int32_t *dev_first,
+                      int64_t *bottleneck, int64_t *iter_time, int32_t *status, int exact, int32_t *n_caps)
 {
     if (C < 0 || S_max < 1 || G_max < 1 || c_begin < 0 || c_end > C || c_begin > c_end) return ORACLE_BAD_ARG;
     if (p->L > 65535) return ORACLE_BAD_ARG;
@@ -670,14 +774,19 @@ int oracle_plan_mesh_batch(const oracle_problem *p, const int64_t *PF, const int
     tables_view v = { p, PF, PP, PS, PR };
     int64_t total_dev = 0;
     for (int g = 0; g < p->G; ++g) total_dev += p->group_ndev[g];
-    const size_t W = (size_t)(L + 1), Dn = (size_t)total_dev + 1;
-    int64_t *D = (int64_t *)malloc(sizeof(int64_t) * (size_t)(S_max + 1) * W * Dn);
-    int32_t *arg_j = (int32_t *)malloc(sizeof(int32_t) * (size_t)(S_max + 1) * W * Dn);
-    int32_t *arg_k = (int32_t *)malloc(sizeof(int32_t) * (size_t)(S_max + 1) * W * Dn);
-    int64_t *O = (int64_t *)malloc(sizeof(int64_t) * (size_t)(G_max + 1));
+    mesh_tables m;
+    m.W = (size_t)(L + 1);
+    m.Dn = (size_t)total_dev + 1;
+    const size_t cells = (size_t)(S_max + 1) * m.W * m.Dn;
+    m.D = (int64_t *)malloc(sizeof(int64_t) * cells);
+    m.arg_j = (int32_t *)malloc(sizeof(int32_t) * cells);
+    m.arg_k = (int32_t *)malloc(sizeof(int32_t) * cells);
+    m.O = (int64_t *)malloc(sizeof(int64_t) * (size_t)(G_max + 1));
     char *seen = (char *)malloc((size_t)p->G);
-    if (!D || !arg_j || !arg_k || !O || !seen) return ORACLE_BAD_ARG;
-#define AT(s, i, d) (((size_t)(s) * W + (size_t)(i)) * Dn + (size_t)(d))
+    int32_t *trial = (int32_t *)malloc(sizeof(int32_t) * 3 * (size_t)(S_max + 1));
+    size_t caps_room = 1024;
+    int64_t *caps = (int64_t *)malloc(sizeof(int64_t) * caps_room);
+    if (!m.D || !m.arg_j || !m.arg_k || !m.O || !seen || !trial || !caps) return ORACLE_BAD_ARG;
     for (int32_t c = c_begin; c < c_end; ++c) {
         const int S = ord_S[c], K = ord_G[c];
         const int32_t *og = ord_group + (size_t)c * G_max;
@@ -685,79 +794,84 @@ int oracle_plan_mesh_batch(const oracle_problem *p, const int64_t *PF, const int
         int32_t *st = stage_tp + (size_t)c * S_max, *df = dev_first + (size_t)c * S_max;
         fill_failed(S_max, sp, df, bottleneck + c, iter_time + c);
         for (int s = 0; s < S_max; ++s) { sg[s] = -1; st[s] = -1; }
+        if (n_caps) n_caps[c] = 0;
         status[c] = CAND_INVALID;
         if (S < 1 || S > S_max || K < 1 || K > G_max) continue;
         int ok = 1;
         memset(seen, 0, (size_t)p->G);
-        O[0] = 0;
+        m.O[0] = 0;
         for (int k = 0; k < K && ok; ++k) {
             if (og[k] < 0 || og[k] >= p->G || seen[og[k]]) { ok = 0; break; }
             seen[og[k]] = 1;
-            O[k + 1] = O[k] + p->group_ndev[og[k]];
+            m.O[k + 1] = m.O[k] + p->group_ndev[og[k]];
         }
         if (!ok) continue;
         status[c] = CAND_INFEASIBLE;
-        const int64_t Dtot = O[K];
+        const int64_t Dtot = m.O[K];
         if (S > L || S < K || S > Dtot) continue;
-        for (size_t x = 0; x < (size_t)(S + 1) * W * Dn; ++x) { D[x] = ORACLE_INF; arg_j[x] = -1; arg_k[x] = -1; }
-        D[AT(0, 0, 0)] = 0;
-        for (int s = 0; s < S; ++s) {
-            const int last = (s == S - 1);
-            const int64_t n = (S - s) < p->M ? (S - s) : p->M;
-            int k = 0;
-            for (int64_t d = 0; d < Dtot; ++d) {
-                while (O[k + 1] <= d) ++k;                      /* the group this stage runs on */
-                const int g = og[k];
-                for (int q = 0; q < p->n_tp; ++q) {
-                    const int tp = p->tp_degrees[q];
-                    const int64_t d2 = d + tp;
-                    if (d2 > O[k + 1]) continue;                 /* a stage stays inside one group */
-                    if (last != (d2 == Dtot)) continue;          /* the last stage, and only it, uses up the devices */
-                    const int g_next = last ? g : (d2 == O[k + 1] ? og[k + 1] : g);
-                    for (int i = s + 1; i <= L - (S - 1 - s); ++i) {
-                        if (last && i != L) continue;
-                        const int64_t cc = last ? 0 : cut_time(p, g, g_next, i);
-                        int64_t best = D[AT(s + 1, i, d2)];
-                        int32_t bj = arg_j[AT(s + 1, i, d2)], bq = arg_k[AT(s + 1, i, d2)];
-                        for (int j = s; j < i; ++j) {
-                            const int64_t prev = D[AT(s, j, d)];
-                            if (prev == ORACLE_INF) continue;
-                            if (!memory_fits(&v, g, tp, n, j, i)) continue;
-                            const int64_t val = max64(prev, max64(stage_time(&v, g, tp, j, i), cc));
-                            if (val < best || (val == best && (j < bj || (j == bj && q < bq)))) {
-                                best = val; bj = j; bq = q;
-                            }
-                        }
-                        D[AT(s + 1, i, d2)] = best;
-                        arg_j[AT(s + 1, i, d2)] = bj;
-                        arg_k[AT(s + 1, i, d2)] = bq;
-                    }
+        if (mesh_fill(&v, &m, K, og, S, 0, 0, NULL, NULL, NULL, 0, 0) != ORACLE_OK) return ORACLE_BAD_ARG;
+        const int64_t t_S = m.D[MESH_AT(&m, S, L, Dtot)];
+        if (t_S == ORACLE_INF) continue;
+        mesh_backtrack(&v, &m, K, og, S, sp, sg, st);
+        if (!candidate_valid(p, S, S_max, sg, st)) abort();      /* the slicing found is a well-formed candidate */
+        if (score_partition(&v, S, sg, st, sp, bottleneck + c, iter_time + c) != CAND_OK || bottleneck[c] != t_S)
+            abort();
+        status[c] = CAND_OK;
+        if (exact) {
+            const int64_t t_E = ceil_div(iter_time[c], p->M);
+            size_t n = 0;
+            /* one more pass of the min-max table only to collect the candidate caps in [t_S, t_E] */
+            if (mesh_fill(&v, &m, K, og, S, 0, 0, &caps, &n, &caps_room, t_S, t_E) != ORACLE_OK) return ORACLE_BAD_ARG;
+            qsort(caps, n, sizeof(int64_t), cmp_i64);
+            int64_t best_T = ORACLE_INF, best_cap = ORACLE_INF;
+            int32_t *tsp = trial, *tsg = trial + (S_max + 1), *tst = trial + 2 * (S_max + 1);
+            for (size_t q = 0; q < n; ++q) {
+                if (q > 0 && caps[q] == caps[q - 1]) continue;
+                if (n_caps) n_caps[c] += 1;
+                if (mesh_fill(&v, &m, K, og, S, 1, caps[q], NULL, NULL, NULL, 0, 0) != ORACLE_OK) return ORACLE_BAD_ARG;
+                const int64_t F = m.D[MESH_AT(&m, S, L, Dtot)];
+                if (F == ORACLE_INF) continue;
+                const int64_t T = F + (int64_t)(p->M - 1) * caps[q];
+                if (T < best_T) {
+                    best_T = T;
+                    best_cap = caps[q];
+                    mesh_backtrack(&v, &m, K, og, S, tsp, tsg, tst);
+                    for (int s = 0; s <= S; ++s) sp[s] = tsp[s];
+                    for (int s = 0; s < S; ++s) { sg[s] = tsg[s]; st[s] = tst[s]; }
                 }
             }
+            if (best_T == ORACLE_INF) abort();                   /* t_S itself is a cap and is feasible */
+            int64_t b, t;
+            if (score_partition(&v, S, sg, st, sp, &b, &t) != CAND_OK || b != best_cap || t != best_T) abort();
+            bottleneck[c] = best_cap;
+            iter_time[c] = best_T;
         }
-        if (D[AT(S, L, Dtot)] == ORACLE_INF) continue;
-        int i = L;
-        int64_t d = Dtot;
-        sp[S] = L;
-        for (int s = S; s >= 1; --s) {
-            const int j = arg_j[AT(s, i, d)], q = arg_k[AT(s, i, d)];
-            const int tp = p->tp_degrees[q];
-            d -= tp;
-            int k = 0;
-            while (O[k + 1] <= d) ++k;
-            sp[s - 1] = j;
-            sg[s - 1] = og[k];
-            st[s - 1] = tp;
-            i = j;
-        }
-        if (i != 0 || d != 0) abort();
-        if (!candidate_valid(p, S, S_max, sg, st)) abort();      /* the slicing found is a well-formed candidate */
         slot_devices(p, S, S_max, sg, st, df);
-        if (score_partition(&v, S, sg, st, sp, bottleneck + c, iter_time + c) != CAND_OK ||
-            bottleneck[c] != D[AT(S, L, Dtot)]) abort();
-        status[c] = CAND_OK;
     }
-#undef AT
-    free(D); free(arg_j); free(arg_k); free(O); free(seen);
+    free(m.D); free(m.arg_j); free(m.arg_k); free(m.O); free(seen); free(trial); free(caps);
     return ORACLE_OK;
+}
+
+int oracle_plan_mesh_batch(const oracle_problem *p, const int64_t *PF, const int64_t *PP, const int64_t *PS,
+                           const int64_t *PR, int32_t C, int32_t G_max, int32_t S_max, const int32_t *ord_S,
+                           const int32_t *ord_G, const int32_t *ord_group, int32_t c_begin, int32_t c_end,
+                           int32_t *splits, int32_t *stage_group, int32_t *stage_tp, int32_t *dev_first,
+                           int64_t *bottleneck, int64_t *iter_time, int32_t *status)
+{
+    return mesh_batch(p, PF, PP, PS, PR, C, G_max, S_max, ord_S, ord_G, ord_group, c_begin, c_end, splits,
+                      stage_group, stage_tp, dev_first, bottleneck, iter_time, status, 0, NULL);
+}
+
+/* The paper's full search for one ordering: eq. dp_general with its device index, swept over the
+ * cap.  Outputs as oracle_plan_mesh_batch, with bottleneck = the winning cap (the plan's own largest
+ * time) and iter_time = the optimum; n_caps[c] = caps swept. */
+int oracle_plan_mesh_exact_batch(const oracle_problem *p, const int64_t *PF, const int64_t *PP,
+                                 const int64_t *PS, const int64_t *PR, int32_t C, int32_t G_max, int32_t S_max,
+                                 const int32_t *ord_S, const int32_t *ord_G, const int32_t *ord_group,
+                                 int32_t c_begin, int32_t c_end, int32_t *splits, int32_t *stage_group,
+                                 int32_t *stage_tp, int32_t *dev_first, int64_t *bottleneck, int64_t *iter_time,
+                                 int32_t *status, int32_t *n_caps)
+{
+    return mesh_batch(p, PF, PP, PS, PR, C, G_max, S_max, ord_S, ord_G, ord_group, c_begin, c_end, splits,
+                      stage_group, stage_tp, dev_first, bottleneck, iter_time, status, 1, n_caps);
 }

@@ -667,6 +667,37 @@ def test_mesh_against_its_twin_exhaustive_enumeration_and_the_hot_path():
     assert n > 300
 
 
+def test_mesh_exact_against_exhaustive_enumeration_and_its_twin():
+    n = better = 0
+    for seed in range(260):
+        w = W.random_small(seed, L_max=8, S_cap=4)
+        p = w.problem
+        if int(p.group_ndev.sum()) > 8:
+            continue
+        tables = oracle.build_tables(p)
+        orders = W.make_orderings(p, seed, 5, 1, 5, 0, 6)
+        mm = oracle.plan_mesh_batch(tables, orders)
+        out = oracle.plan_mesh_batch(tables, orders, exact=True)
+        assert (out.status == mm.status).all()
+        for c in np.nonzero(out.status == oracle.OK)[0]:
+            S, groups = int(orders.ord_S[c]), orders.ord_group[c, :orders.ord_G[c]]
+            n += 1
+            # the optimum over every slicing and every partition, ties to the smaller bottleneck
+            T, b = brute.mesh_best_iteration_time(p, S, groups)
+            assert (T, b) == (out.iter_time[c], out.bottleneck[c]), (seed, c)
+            # the plan: the capped least-sum recurrence at that cap, with its tie rule
+            val, cuts, slots = brute.plan_mesh_capped(p, S, groups, int(b))
+            assert val + (p.M - 1) * b == T
+            assert list(out.splits[c, :S + 1]) == cuts
+            assert [(int(g), int(t)) for g, t in zip(out.stage_group[c, :S], out.stage_tp[c, :S])] == slots
+            # and the hot-path exact search, given that slicing as an ordinary candidate, agrees
+            ex = oracle.plan_exact_batch(tables, cands_from_lists([slots], S_max=orders.S_max))
+            assert ex.iter_time[0] == T and ex.bottleneck[0] == b and list(ex.splits[0, :S + 1]) == cuts
+            assert out.iter_time[c] <= mm.iter_time[c] and out.bottleneck[c] >= mm.bottleneck[c]
+            better += out.iter_time[c] < mm.iter_time[c]
+    assert n > 500 and better > 50
+
+
 def test_mesh_with_forced_slicing_is_the_hot_path():
     # single-device groups leave the recurrence no choice: same plans as the candidates (g, 1)
     for seed in range(40):
