@@ -232,6 +232,18 @@ int harp_plan_mesh_batch(harp_ctx *ctx, harp_tables *tables, const harp_ordering
                          const harp_plans *out, int32_t *stage_group, int32_t *stage_tp,
                          void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* The paper's full search for every ordering (sections 5.2.3 and 5.2.4 (2)): the capped least-sum
+ * table of eq. dp_general with its device index, swept over the cap t_max between t_S (what
+ * harp_plan_mesh_batch finds) and t_E = ceil(T(t_S) / B).  Outputs as harp_plan_mesh_batch, except
+ * that the plan is the one of least iteration time over every slicing and partition (ties: smaller
+ * bottleneck, then lowest previous cut and smallest degree at every stage of the capped table),
+ * bottleneck its largest stage or transfer time and iter_time its iteration time.  n_passes: DEVICE
+ * [C] or NULL, capped tables filled per ordering.  Workspace as for harp_plan_mesh_batch. */
+int harp_plan_mesh_exact_batch(harp_ctx *ctx, harp_tables *tables, const harp_orderings *orders,
+                               const harp_plans *out, int32_t *stage_group, int32_t *stage_tp,
+                               int32_t *n_passes, void *workspace, size_t workspace_bytes,
+                               void *hip_stream);
+
 /* The capped recurrence under the H-1F1B scheduler (sections 4.1 and 5.2.3): for candidate c and
  * the cap t_max[c] on every stage and transfer time (constraints (i), (ii)), the suffix recurrence
  * of eq. dp_general with the warm-up launch count carried in the state (eq. dp_ni) and used by the

@@ -26,7 +26,7 @@ EXPORTS = (
     "harp_tables_pp", "harp_tables_ps", "harp_tables_pr", "harp_tables_release",
     "harp_set_plan_path", "harp_plan_workspace_bytes", "harp_plan_batch", "harp_plan_exact_batch",
     "harp_plan_h1f1b_batch", "harp_score_h1f1b",
-    "harp_plan_mesh_workspace_bytes", "harp_plan_mesh_batch",
+    "harp_plan_mesh_workspace_bytes", "harp_plan_mesh_batch", "harp_plan_mesh_exact_batch",
     "harp_score_1f1b", "harp_argmin_batch", "harp_measure_valu_int32",
 )
 
@@ -102,6 +102,8 @@ def load_library() -> C.CDLL:
     lib.harp_plan_mesh_workspace_bytes.argtypes = [vp, vp, C.POINTER(harp_orderings)]
     lib.harp_plan_mesh_workspace_bytes.restype = sz
     lib.harp_plan_mesh_batch.argtypes = [vp, vp, C.POINTER(harp_orderings), C.POINTER(harp_plans), vp, vp, vp, sz, vp]
+    lib.harp_plan_mesh_exact_batch.argtypes = [vp, vp, C.POINTER(harp_orderings), C.POINTER(harp_plans), vp, vp, vp,
+                                               vp, sz, vp]
     lib.harp_score_1f1b.argtypes = [vp, vp, C.POINTER(harp_candidates), vp, vp, vp, vp, vp]
     lib.harp_argmin_batch.argtypes = [vp, i32, vp, vp, vp, vp, vp]
     lib.harp_measure_valu_int32.argtypes = [vp, i32, i32, vp, vp]
@@ -384,6 +386,14 @@ def harp_plan_mesh_batch(ctx: Context, tables: Tables, do: DeviceOrderings, out:
                                            workspace.numel(), _stream_handle(stream)))
 
 
+def harp_plan_mesh_exact_batch(ctx: Context, tables: Tables, do: DeviceOrderings, out: DevicePlans, stage_group,
+                               stage_tp, workspace, n_passes=None, stream=None):
+    ctx.check(ctx.lib.harp_plan_mesh_exact_batch(ctx.handle, tables.handle, C.byref(do.c), C.byref(out.c),
+                                                 stage_group.data_ptr(), stage_tp.data_ptr(),
+                                                 n_passes.data_ptr() if n_passes is not None else None,
+                                                 workspace.data_ptr(), workspace.numel(), _stream_handle(stream)))
+
+
 def mesh_workspace(ctx: Context, tables: Tables, do: DeviceOrderings):
     torch = _torch()
     n = ctx.lib.harp_plan_mesh_workspace_bytes(ctx.handle, tables.handle, C.byref(do.c))
@@ -392,9 +402,9 @@ def mesh_workspace(ctx: Context, tables: Tables, do: DeviceOrderings):
     return torch.empty(n, dtype=torch.uint8, device=ctx.device)
 
 
-def plan_mesh(ctx: Context, problem, orders):
-    """Convenience for tests: tables, submesh planner over a batch of orderings; host copies of the
-    plans with `.stage_group` and `.stage_tp`."""
+def plan_mesh(ctx: Context, problem, orders, exact: bool = False):
+    """Convenience for tests: tables, submesh planner over a batch of orderings (min-max, or the
+    exact search); host copies of the plans with `.stage_group`, `.stage_tp` (and `.n_passes`)."""
     torch = _torch()
     tables = Tables(ctx, problem)
     do = DeviceOrderings(ctx, orders)
@@ -402,12 +412,17 @@ def plan_mesh(ctx: Context, problem, orders):
     out.poison()
     sg = torch.full((max(do.C, 1), do.S_max), -7, dtype=torch.int32, device=ctx.device)
     st = torch.full((max(do.C, 1), do.S_max), -7, dtype=torch.int32, device=ctx.device)
+    n_passes = torch.full((max(do.C, 1),), -7, dtype=torch.int32, device=ctx.device)
     ws = mesh_workspace(ctx, tables, do)
-    harp_plan_mesh_batch(ctx, tables, do, out, sg, st, ws)
+    if exact:
+        harp_plan_mesh_exact_batch(ctx, tables, do, out, sg, st, ws, n_passes)
+    else:
+        harp_plan_mesh_batch(ctx, tables, do, out, sg, st, ws)
     torch.cuda.synchronize()
     got = out.to_host()
     got.stage_group = sg[:do.C].cpu().numpy()
     got.stage_tp = st[:do.C].cpu().numpy()
+    got.n_passes = n_passes[:do.C].cpu().numpy()
     return got, tables
 
 

@@ -406,9 +406,13 @@ size_t harp_plan_mesh_workspace_bytes(harp_ctx *ctx, harp_tables *t, const harp_
     return 256 + size_t(n_mesh_groups(ctx, od->C, per_group)) * per_group;
 }
 
-int harp_plan_mesh_batch(harp_ctx *ctx, harp_tables *t, const harp_orderings *od, const harp_plans *out,
-                         int32_t *stage_group, int32_t *stage_tp, void *workspace, size_t workspace_bytes,
-                         void *hip_stream) {
+}  // extern "C"
+
+namespace {
+
+int plan_mesh_common(harp_ctx *ctx, harp_tables *t, const harp_orderings *od, const harp_plans *out,
+                     int32_t *stage_group, int32_t *stage_tp, int32_t *n_passes, bool exact, void *workspace,
+                     size_t workspace_bytes, void *hip_stream) {
     int rc = check_orderings(ctx, t, od);
     if (rc != HARP_OK) return rc;
     if (!out || (od->C > 0 && (!out->splits || !out->dev_first || !out->bottleneck || !out->iter_time ||
@@ -427,11 +431,29 @@ int harp_plan_mesh_batch(harp_ctx *ctx, harp_tables *t, const harp_orderings *od
     if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
     const OrdDev o = { od->C, od->G_max, od->S_max, od->ord_S, od->ord_G, od->ord_group };
     const PlansDev pl = { out->splits, out->dev_first, out->bottleneck, out->iter_time, out->status };
-    launch_plan_mesh(t->dev, o, pl, stage_group, stage_tp, workspace, groups, t->total_devices,
+    launch_plan_mesh(t->dev, o, pl, stage_group, stage_tp, n_passes, exact, workspace, groups, t->total_devices,
                      static_cast<hipStream_t>(hip_stream));
     e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(ctx, e, "launching the submesh planner kernel");
     return HARP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int harp_plan_mesh_batch(harp_ctx *ctx, harp_tables *t, const harp_orderings *od, const harp_plans *out,
+                         int32_t *stage_group, int32_t *stage_tp, void *workspace, size_t workspace_bytes,
+                         void *hip_stream) {
+    return plan_mesh_common(ctx, t, od, out, stage_group, stage_tp, nullptr, false, workspace, workspace_bytes,
+                            hip_stream);
+}
+
+int harp_plan_mesh_exact_batch(harp_ctx *ctx, harp_tables *t, const harp_orderings *od, const harp_plans *out,
+                               int32_t *stage_group, int32_t *stage_tp, int32_t *n_passes, void *workspace,
+                               size_t workspace_bytes, void *hip_stream) {
+    return plan_mesh_common(ctx, t, od, out, stage_group, stage_tp, n_passes, true, workspace, workspace_bytes,
+                            hip_stream);
 }
 
 int harp_score_h1f1b(harp_ctx *ctx, harp_tables *t, const harp_candidates *cd, const int32_t *splits,

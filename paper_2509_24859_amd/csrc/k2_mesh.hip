@@ -43,22 +43,154 @@ __device__ __forceinline__ MeshSlice mesh_slice(unsigned char *ws, size_t per_gr
     return m;
 }
 
-__global__ __launch_bounds__(kMeshThreads) void k2_mesh(TablesDev tb, OrdDev od, PlansDev out,
-                                                        int32_t *stage_group, int32_t *stage_tp,
-                                                        unsigned char *ws, size_t per_group, int64_t n_dev,
-                                                        int *ticket) {
+// One pass over all stages for the ordering in (offs, order), every thread of the workgroup taking
+// part.  kCapped = false: min-max form.  kCapped = true: least sum of (t + 2c) over transitions
+// whose stage and transfer times are at most cap.  Returns the value of the state (S, L, all
+// devices); back-pointers are left in the slice.
+template <bool kCapped>
+__device__ __forceinline__ int64_t mesh_pass(const TablesDev &tb, const MeshSlice &m, const int32_t *offs,
+                                             const int32_t *order, int K, int S, int64_t n_dev, int64_t cap) {
+    const int L = tb.L, W = L + 1, tid = threadIdx.x;
+    const int Dtot = offs[K];
+    const int64_t *PP = tb.PP(), *PS = tb.PS();
+    int64_t *Dp = m.D0, *Dn = m.D1;
+    __syncthreads();                                 // the previous pass is done with the rows
+    for (int x = tid; x < (Dtot + 1) * W; x += kMeshThreads) Dp[x] = kInf;
+    __syncthreads();
+    if (tid == 0) Dp[0] = 0;                         // no stage, no operator, no device
+    for (int s = 0; s < S; ++s) {
+        __syncthreads();                             // row s is complete
+        const bool last = (s == S - 1);
+        const int64_t n_inflight = (S - s) < tb.M ? (S - s) : tb.M;
+        // targets: i in [i_lo, i_hi], d' in [d_lo, d_hi]; every later stage needs an operator and a device
+        const int i_lo = last ? L : s + 1, i_hi = L - (S - 1 - s);
+        const int d_lo = last ? Dtot : s + 1, d_hi = last ? Dtot : Dtot - (S - 1 - s);
+        const int n_i = i_hi - i_lo + 1, n_d = d_hi - d_lo + 1;
+        uint32_t *arg_s = m.arg + size_t(s) * size_t(n_dev + 1) * W;
+        for (int x = tid; x < n_i * n_d; x += kMeshThreads) {
+            const int i = i_lo + x % n_i, d2 = d_lo + x / n_i;
+            int64_t best = kInf;
+            int best_j = 0x7FFF, best_q = 0;
+            // the group whose devices end at or after d2: the stage [d2 - tp, d2) must lie inside one group
+            int k = 0;
+            while (offs[k + 1] < d2) ++k;            // offs[k] < d2 <= offs[k + 1]
+            const int g = order[k];
+            const int t = tb.group_type[g];
+            const int64_t *pf = tb.PF(t);
+            const int64_t mem_dev = tb.type_mem[t];
+            const int g_next = last ? g : (d2 == offs[k + 1] ? order[k + 1 < K ? k + 1 : k] : g);
+            int64_t cut = 0;
+            if (!last) {
+                const int64_t link = tb.bw[int64_t(g) * tb.G + g_next];
+                cut = (tb.act_bytes[i - 1] + link - 1) / link;
+            }
+            const int64_t pfi = pf[i], ppi = PP[i], psi = PS[i];
+            if (!kCapped || cut <= cap) {
+                for (int q = 0; q < tb.n_tp; ++q) {
+                    const int64_t tp = tb.tp[q];
+                    const int d = d2 - int(tp);
+                    // the stage must stay inside group k, and s stages have used at least s devices
+                    // (row s holds nothing else: entries outside the ranges written for it are stale)
+                    if (d < offs[k] || d < s) continue;
+                    const int shift = tb.tp_shift[q];
+                    const int64_t *pr = tb.PR(g, q);
+                    const int64_t pri = pr[i];
+                    const int64_t capm = tp * mem_dev;
+                    const int64_t *row = Dp + size_t(d) * W;
+                    for (int j = i - 1; j >= s; --j) {
+                        const int64_t work = pfi - pf[j];
+                        const int64_t time = (shift >= 0 ? (work + tp - 1) >> shift : (work + tp - 1) / tp) + (pri - pr[j]);
+                        // the stage time never decreases as j moves down: beyond the cap, or beyond the
+                        // best value of the min-max form, no lower j can be taken or can match
+                        if (time > (kCapped ? cap : best)) break;
+                        if ((ppi - PP[j]) + n_inflight * (psi - PS[j]) > capm) break;   // nor fit in memory
+                        const int64_t prev = row[j];
+                        if (prev == kInf) continue;
+                        int64_t val;
+                        if (kCapped) {
+                            val = prev + time + 2 * cut;
+                        } else {
+                            val = prev > time ? prev : time;
+                            val = val > cut ? val : cut;
+                        }
+                        if (val < best || (val == best && j < best_j)) { best = val; best_j = j; best_q = q; }
+                    }
+                }
+            }
+            Dn[size_t(d2) * W + i] = best;
+            arg_s[size_t(d2) * W + i] = uint32_t(best_j) | (uint32_t(best_q) << 16);
+        }
+        int64_t *tmp = Dp; Dp = Dn; Dn = tmp;
+    }
+    __syncthreads();
+    return Dp[size_t(Dtot) * W + L];
+}
+
+// Thread 0: follows the back-pointers from (S, L, all devices).
+__device__ __forceinline__ void mesh_backtrack(const TablesDev &tb, const MeshSlice &m, const int32_t *offs,
+                                               const int32_t *order, int K, int S, int64_t n_dev, int32_t *cuts,
+                                               uint16_t *slot_g, uint8_t *slot_k, int32_t *slot_first) {
+    const int L = tb.L, W = L + 1;
+    int i = L, d = offs[K];
+    cuts[S] = L;
+    for (int s = S; s >= 1; --s) {
+        const uint32_t a = m.arg[(size_t(s - 1) * size_t(n_dev + 1) + size_t(d)) * W + i];
+        int j = int(a & 0xFFFFu);
+        const int q = int(a >> 16) & 7;
+        j = j < L ? j : L - 1;                      // a finite value only chains through cuts inside the row
+        d -= tb.tp[q];
+        d = d > 0 ? d : 0;
+        int k = 0;
+        while (k + 1 < K && offs[k + 1] <= d) ++k;
+        cuts[s - 1] = j;
+        slot_g[s - 1] = uint16_t(order[k]);
+        slot_k[s - 1] = uint8_t(q);
+        slot_first[s - 1] = tb.group_base[order[k]] + (d - offs[k]);
+        i = j;
+    }
+}
+
+// kExact = false: the min-max plan of every ordering.  kExact = true: the optimum of the
+// iteration-time model (section 5.2.2) over every slicing and partition: the capped least-sum
+// table is walked over the caps exactly as the exact search of the hot path walks them (first at
+// t_S, then down from ceil(T / B), skipping caps that the sums rule out; equal totals keep the lower
+// cap), which returns what the increasing sweep over every distinct stage cost returns.
+template <bool kExact>
+__device__ __forceinline__ void mesh_body(const TablesDev &tb, const OrdDev &od, const PlansDev &out,
+                                          int32_t *stage_group, int32_t *stage_tp, int32_t *n_passes,
+                                          unsigned char *ws, size_t per_group, int64_t n_dev, int *ticket) {
     __shared__ int32_t offs[kMaxOrderGroups + 1];     // O_0 .. O_K
     __shared__ int32_t order[kMaxOrderGroups];
-    __shared__ int32_t cuts[kMaxStages + 1];
-    __shared__ uint16_t slot_g[kMaxStages];
-    __shared__ uint8_t slot_k[kMaxStages];
-    __shared__ int32_t slot_first[kMaxStages];
+    __shared__ int32_t cuts[kMaxStages + 1], kept_cuts[kMaxStages + 1];
+    __shared__ uint16_t slot_g[kMaxStages], kept_g[kMaxStages];
+    __shared__ uint8_t slot_k[kMaxStages], kept_k[kMaxStages];
+    __shared__ int32_t slot_first[kMaxStages], kept_first[kMaxStages];
+    __shared__ int64_t scored[2];
     __shared__ int shared_int[2];
     const int L = tb.L, S_max = od.S_max;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int W = L + 1;
     const MeshSlice m = mesh_slice(ws, per_group, L, n_dev);
-    const int64_t *PP = tb.PP(), *PS = tb.PS();
+    const int64_t m_cap = tb.M;
+
+    // all threads: thread 0 backtracks into cuts/slot_*, the first wave scores them
+    auto backtrack_and_score = [&](int K, int S, int64_t &bott, int64_t &total) {
+        if (tid == 0) mesh_backtrack(tb, m, offs, order, K, S, n_dev, cuts, slot_g, slot_k, slot_first);
+        __syncthreads();
+        if (wave == 0) {
+            int64_t b, t;
+            wave_score_partition(tb, S, slot_g, slot_k, cuts, lane, b, t);
+            if (lane == 0) { scored[0] = b; scored[1] = t; }
+        }
+        __syncthreads();
+        bott = scored[0];
+        total = scored[1];
+    };
+    auto keep = [&](int S) {
+        for (int s = tid; s <= S; s += kMeshThreads) kept_cuts[s] = cuts[s];
+        for (int s = tid; s < S; s += kMeshThreads) {
+            kept_g[s] = slot_g[s]; kept_k[s] = slot_k[s]; kept_first[s] = slot_first[s];
+        }
+    };
 
     for (;;) {
         __syncthreads();
@@ -72,6 +204,7 @@ __global__ __launch_bounds__(kMeshThreads) void k2_mesh(TablesDev tb, OrdDev od,
         auto fail = [&](int status) {
             write_failed(out, c, S_max, status);
             for (int s = tid; s < S_max; s += kMeshThreads) { sg[s] = -1; stp[s] = -1; }
+            if (tid == 0 && n_passes) n_passes[c] = 0;
         };
         // the ordering itself: counts in range, group ids in range and distinct
         int bad = (S < 1 || S > S_max || K < 1 || K > od.G_max) ? 1 : 0;
@@ -93,104 +226,70 @@ __global__ __launch_bounds__(kMeshThreads) void k2_mesh(TablesDev tb, OrdDev od,
         const int Dtot = offs[K];
         if (S > L || S < K || S > Dtot) { fail(HARP_CAND_INFEASIBLE); continue; }
 
-        int64_t *Dp = m.D0, *Dn = m.D1;
-        for (int x = tid; x < (Dtot + 1) * W; x += kMeshThreads) Dp[x] = kInf;
-        __syncthreads();
-        if (tid == 0) Dp[0] = 0;                     // no stage, no operator, no device
-        for (int s = 0; s < S; ++s) {
-            __syncthreads();                         // row s is complete
-            const bool last = (s == S - 1);
-            const int64_t n_inflight = (S - s) < tb.M ? (S - s) : tb.M;
-            // targets: i in [i_lo, i_hi], d' in [d_lo, d_hi]; every later stage needs an operator and a device
-            const int i_lo = last ? L : s + 1, i_hi = L - (S - 1 - s);
-            const int d_lo = last ? Dtot : s + 1, d_hi = last ? Dtot : Dtot - (S - 1 - s);
-            const int n_i = i_hi - i_lo + 1, n_d = d_hi - d_lo + 1;
-            uint32_t *arg_s = m.arg + size_t(s) * size_t(n_dev + 1) * W;
-            for (int x = tid; x < n_i * n_d; x += kMeshThreads) {
-                const int i = i_lo + x % n_i, d2 = d_lo + x / n_i;
-                int64_t best = kInf;
-                int best_j = 0x7FFF, best_q = 0;
-                // the group whose devices end at or after d2: the stage [d2 - tp, d2) must lie inside one group
-                int k = 0;
-                while (offs[k + 1] < d2) ++k;        // offs[k] < d2 <= offs[k + 1]
-                const int g = order[k];
-                const int t = tb.group_type[g];
-                const int64_t *pf = tb.PF(t);
-                const int64_t mem_dev = tb.type_mem[t];
-                const int g_next = last ? g : (d2 == offs[k + 1] ? order[k + 1 < K ? k + 1 : k] : g);
-                int64_t cut = 0;
-                if (!last) {
-                    const int64_t link = tb.bw[int64_t(g) * tb.G + g_next];
-                    cut = (tb.act_bytes[i - 1] + link - 1) / link;
+        if (mesh_pass<false>(tb, m, offs, order, K, S, n_dev, 0) == kInf) { fail(HARP_CAND_INFEASIBLE); continue; }
+        int64_t t_S, best_T;
+        backtrack_and_score(K, S, t_S, best_T);
+        int64_t best_b = t_S;
+        keep(S);
+        int passes = 0;
+        if (kExact) {
+            int64_t cap = t_S;
+            while (S >= 2) {
+                const int64_t sum = mesh_pass<true>(tb, m, offs, order, K, S, n_dev, cap);
+                if (sum == kInf) break;              // cannot happen at or above t_S
+                int64_t b, T;
+                backtrack_and_score(K, S, b, T);
+                ++passes;
+                if (T < best_T || (T == best_T && b <= best_b)) {   // equal totals: the lower cap; equal caps: the capped plan
+                    best_T = T;
+                    best_b = b;
+                    keep(S);
                 }
-                const int64_t pfi = pf[i], ppi = PP[i], psi = PS[i];
-                for (int q = 0; q < tb.n_tp; ++q) {
-                    const int64_t tp = tb.tp[q];
-                    const int d = d2 - int(tp);
-                    // the stage must stay inside group k, and s stages have used at least s devices
-                    // (row s holds nothing else: entries outside the ranges written for it are stale)
-                    if (d < offs[k] || d < s) continue;
-                    const int shift = tb.tp_shift[q];
-                    const int64_t *pr = tb.PR(g, q);
-                    const int64_t pri = pr[i];
-                    const int64_t capm = tp * mem_dev;
-                    const int64_t *row = Dp + size_t(d) * W;
-                    for (int j = i - 1; j >= s; --j) {
-                        const int64_t work = pfi - pf[j];
-                        const int64_t time = (shift >= 0 ? (work + tp - 1) >> shift : (work + tp - 1) / tp) + (pri - pr[j]);
-                        if (time > best) break;                     // no lower j can match the best value
-                        if ((ppi - PP[j]) + n_inflight * (psi - PS[j]) > capm) break;   // nor fit in memory
-                        const int64_t prev = row[j];
-                        if (prev == kInf) continue;
-                        int64_t val = prev > time ? prev : time;
-                        val = val > cut ? val : cut;
-                        if (val < best || (val == best && j < best_j)) { best = val; best_j = j; best_q = q; }
+                if (passes >= (1 << 20) || b > cap) break;           // cannot happen: the cap falls with every pass
+                int64_t next_cap;
+                if (passes == 1) {
+                    next_cap = (best_T + m_cap - 1) / m_cap;
+                } else {
+                    next_cap = b - 1;
+                    if (m_cap > 1) {
+                        const int64_t bound = (best_T - sum) / (m_cap - 1);
+                        next_cap = next_cap < bound ? next_cap : bound;
                     }
                 }
-                Dn[size_t(d2) * W + i] = best;
-                arg_s[size_t(d2) * W + i] = uint32_t(best_j) | (uint32_t(best_q) << 16);
-            }
-            __syncthreads();
-            int64_t *tmp = Dp; Dp = Dn; Dn = tmp;
-        }
-        __syncthreads();
-        const int64_t value = Dp[size_t(Dtot) * W + L];
-        if (value == kInf) { fail(HARP_CAND_INFEASIBLE); continue; }
-        if (tid == 0) {
-            int i = L, d = Dtot;
-            cuts[S] = L;
-            for (int s = S; s >= 1; --s) {
-                const uint32_t a = m.arg[(size_t(s - 1) * size_t(n_dev + 1) + size_t(d)) * W + i];
-                const int j = int(a & 0xFFFFu), q = int(a >> 16);
-                d -= tb.tp[q];
-                int k = 0;
-                while (offs[k + 1] <= d) ++k;
-                cuts[s - 1] = j;
-                slot_g[s - 1] = uint16_t(order[k]);
-                slot_k[s - 1] = uint8_t(q);
-                slot_first[s - 1] = tb.group_base[order[k]] + (d - offs[k]);
-                i = j;
+                if (next_cap <= t_S) break;
+                cap = next_cap;
             }
         }
         __syncthreads();
         int32_t *sp = out.splits + int64_t(c) * (S_max + 1);
         int32_t *df = out.dev_first + int64_t(c) * S_max;
-        for (int s = tid; s <= S_max; s += kMeshThreads) sp[s] = s <= S ? cuts[s] : -1;
+        for (int s = tid; s <= S_max; s += kMeshThreads) sp[s] = s <= S ? kept_cuts[s] : -1;
         for (int s = tid; s < S_max; s += kMeshThreads) {
-            sg[s] = s < S ? int32_t(slot_g[s]) : -1;
-            stp[s] = s < S ? tb.tp[slot_k[s]] : -1;
-            df[s] = s < S ? slot_first[s] : -1;
+            sg[s] = s < S ? int32_t(kept_g[s]) : -1;
+            stp[s] = s < S ? tb.tp[kept_k[s]] : -1;
+            df[s] = s < S ? kept_first[s] : -1;
         }
-        if (wave == 0) {
-            int64_t bott, iter;
-            const int st = wave_score_partition(tb, S, slot_g, slot_k, cuts, lane, bott, iter);
-            if (lane == 0) {
-                out.bottleneck[c] = bott;
-                out.iter_time[c] = iter;
-                out.status[c] = st;
-            }
+        if (tid == 0) {
+            out.bottleneck[c] = best_b;
+            out.iter_time[c] = best_T;
+            out.status[c] = HARP_CAND_OK;
+            if (n_passes) n_passes[c] = passes;
         }
     }
+}
+
+__global__ __launch_bounds__(kMeshThreads) void k2_mesh(TablesDev tb, OrdDev od, PlansDev out,
+                                                        int32_t *stage_group, int32_t *stage_tp,
+                                                        unsigned char *ws, size_t per_group, int64_t n_dev,
+                                                        int *ticket) {
+    mesh_body<false>(tb, od, out, stage_group, stage_tp, nullptr, ws, per_group, n_dev, ticket);
+}
+
+__global__ __launch_bounds__(kMeshThreads) void k2_mesh_exact(TablesDev tb, OrdDev od, PlansDev out,
+                                                              int32_t *stage_group, int32_t *stage_tp,
+                                                              int32_t *n_passes, unsigned char *ws,
+                                                              size_t per_group, int64_t n_dev, int *ticket) {
+    mesh_body<true>(tb, od, out, stage_group, stage_tp, n_passes, ws, per_group, n_dev, ticket);
 }
 
 __global__ void k2_mesh_clear(int *ticket) {
@@ -207,13 +306,19 @@ size_t plan_mesh_ws_per_group(int L, int S_max, int64_t total_devices) {
 }
 
 void launch_plan_mesh(const TablesDev &tb, const OrdDev &od, const PlansDev &out, int32_t *stage_group,
-                      int32_t *stage_tp, void *ws, int n_groups, int64_t total_devices, hipStream_t st) {
+                      int32_t *stage_tp, int32_t *n_passes, bool exact, void *ws, int n_groups,
+                      int64_t total_devices, hipStream_t st) {
     // layout: 256 bytes for the ticket, then the slices
     int *ticket = static_cast<int *>(ws);
     unsigned char *slices = static_cast<unsigned char *>(ws) + 256;
+    const size_t per_group = plan_mesh_ws_per_group(tb.L, od.S_max, total_devices);
     hipLaunchKernelGGL(k2_mesh_clear, dim3(1), dim3(64), 0, st, ticket);
-    hipLaunchKernelGGL(k2_mesh, dim3(n_groups), dim3(kMeshThreads), 0, st, tb, od, out, stage_group, stage_tp,
-                       slices, plan_mesh_ws_per_group(tb.L, od.S_max, total_devices), total_devices, ticket);
+    if (exact)
+        hipLaunchKernelGGL(k2_mesh_exact, dim3(n_groups), dim3(kMeshThreads), 0, st, tb, od, out, stage_group,
+                           stage_tp, n_passes, slices, per_group, total_devices, ticket);
+    else
+        hipLaunchKernelGGL(k2_mesh, dim3(n_groups), dim3(kMeshThreads), 0, st, tb, od, out, stage_group, stage_tp,
+                           slices, per_group, total_devices, ticket);
 }
 
 }  // namespace harp

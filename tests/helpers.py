@@ -100,7 +100,7 @@ def oracle_plan_h1f1b_threaded(tables, cands, t_max, threads=None, step=8):
     return out
 
 
-def oracle_plan_mesh_threaded(tables, orders, threads=None):
+def oracle_plan_mesh_threaded(tables, orders, threads=None, exact=False):
     """Oracle submesh plans for a whole batch of orderings, one ordering per task over host threads."""
     import os
     from concurrent.futures import ThreadPoolExecutor
@@ -110,8 +110,9 @@ def oracle_plan_mesh_threaded(tables, orders, threads=None):
     out = oracle.Plans(orders.C, orders.S_max)
     out.stage_group = np.full((orders.C, orders.S_max), -1, dtype=np.int32)
     out.stage_tp = np.full((orders.C, orders.S_max), -1, dtype=np.int32)
+    out.n_caps = np.zeros(orders.C, dtype=np.int32)
     with ThreadPoolExecutor(threads) as ex:
-        list(ex.map(lambda c: oracle.plan_mesh_batch(tables, orders, c, c + 1, out), range(orders.C)))
+        list(ex.map(lambda c: oracle.plan_mesh_batch(tables, orders, c, c + 1, out, exact), range(orders.C)))
     return out
 
 

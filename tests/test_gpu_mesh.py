@@ -18,9 +18,13 @@ def ctx(harp):
     c.close()
 
 
-def _check(harp, ctx, problem, orders, label):
-    want = oracle_plan_mesh_threaded(oracle.build_tables(problem), orders)
-    got, tables = harp.plan_mesh(ctx, problem, orders)
+def _check(harp, ctx, problem, orders, label, exact=False):
+    want = oracle_plan_mesh_threaded(oracle.build_tables(problem), orders, exact=exact)
+    got, tables = harp.plan_mesh(ctx, problem, orders, exact)
+    if exact:
+        ok = (want.status == oracle.OK) & (orders.ord_S >= 2)
+        assert (got.n_passes[ok] >= 1).all() and (got.n_passes[~ok] == 0).all(), label
+        assert (got.n_passes[ok] <= want.n_caps[ok] + 1).all(), label
     assert_plans_equal(got, want, label)
     for name in ("stage_group", "stage_tp"):
         a, b = getattr(got, name), getattr(want, name)
@@ -147,3 +151,30 @@ def test_mesh_medium_problem_properties(harp, ctx):
     # and the hot path, given the slicing found, cannot do better nor worse
     hot, _ = harp.plan(ctx, p, sub)
     assert (hot.bottleneck == got.bottleneck[ok]).all()
+
+
+def test_mesh_exact_small_and_workloads(harp, ctx):
+    """The full search over an ordering (capped least-sum table with the device index, walked over
+    the caps) against the oracle's increasing sweep."""
+    p = simple_problem([6, 2, 2, 6], M=2, G=2, ndev=(1, 1), act=[0, 5, 0, 0], bw=[[1000, 1], [1, 1000]])
+    got, want, _ = _check(harp, ctx, p, W.orderings_from_lists([(2, [0, 1])]), "hand example", exact=True)
+    assert list(got.splits[0]) == [0, 1, 4] and got.iter_time[0] == 26       # not the min-max plan
+    feasible = better = 0
+    for seed in range(200):
+        w = W.random_small(seed)
+        p = w.problem
+        top = min(8, int(p.group_ndev.sum()))
+        orders = W.make_orderings(p, seed, 5, 1, max(top, p.G), 0, 8)
+        got, want, _ = _check(harp, ctx, p, orders, "seed %d" % seed, exact=True)
+        feasible += int((want.status == oracle.OK).sum())
+    assert feasible > 500
+    for name, n in (("tiny", 16), ("llama7b", 96), ("llama70b", 8)):
+        w = W.make(name)
+        orders = W.make_orderings(w.problem, w.seed, w.config_id, w.problem.G, w.S_max, 0, n)
+        got, want, _ = _check(harp, ctx, w.problem, orders, name, exact=True)
+        mm, _ = harp.plan_mesh(ctx, w.problem, orders)
+        ok = want.status == oracle.OK
+        assert ok.any() and (got.iter_time[ok] <= mm.iter_time[ok]).all()
+        better += int((got.iter_time[ok] < mm.iter_time[ok]).sum())
+        print("%s: %.1f capped tables per ordering, the sweep has %.0f caps" % (name, got.n_passes[ok].mean(), want.n_caps[ok].mean()))
+    assert better > 0
