@@ -92,3 +92,64 @@ def test_longest_sequence_of_the_32_bit_path_and_beyond(harp, ctx):
         print("L = %d" % L, flush=True)
         want, fast32 = _all_entry_points(harp, ctx, p, cands, "L = %d" % L, exact=(L <= 1025))
         assert fast32 == expect_fast and (want.status == oracle.OK).any()
+
+
+def test_argument_errors_of_the_newer_entry_points(harp, ctx):
+    """Every planner entry point refuses a short or misaligned workspace, null arrays and shapes
+    beyond its limits with an error code, and launches nothing."""
+    import torch
+    w = W.make("tiny")
+    tables = harp.Tables(ctx, w.problem)
+    dc = harp.DeviceCandidates(ctx, w.candidates())
+    out = harp.DevicePlans(ctx, dc.C, dc.S_max)
+    out.poison()
+    ws = harp.plan_workspace(ctx, tables, dc)
+    small = torch.empty(256, dtype=torch.uint8, device=ctx.device)
+    caps = torch.zeros(dc.C, dtype=torch.int64, device=ctx.device)
+    warm = torch.zeros((dc.C, dc.S_max), dtype=torch.int32, device=ctx.device)
+
+    class Null:
+        @staticmethod
+        def data_ptr():
+            return None
+
+    calls = {
+        "exact": lambda work: harp.harp_plan_exact_batch(ctx, tables, dc, out, work),
+        "h1f1b": lambda work: harp.harp_plan_h1f1b_batch(ctx, tables, dc, caps, out, warm, work),
+    }
+    for name, call in calls.items():
+        for work, code in ((small, harp.ERR_WORKSPACE), (ws[1:], harp.ERR_WORKSPACE)):
+            with pytest.raises(harp.HarpError) as e:
+                call(work)
+            assert e.value.code == code, name
+    with pytest.raises(harp.HarpError) as e:
+        harp.harp_plan_h1f1b_batch(ctx, tables, dc, Null, out, warm, ws)
+    assert e.value.code == harp.ERR_INVALID_ARG
+    with pytest.raises(harp.HarpError) as e:
+        harp.harp_score_h1f1b(ctx, tables, dc, out.splits, caps, Null, out.bottleneck, out.iter_time, out.status)
+    assert e.value.code == harp.ERR_INVALID_ARG
+
+    orders = W.make_orderings(w.problem, 0, 1, 2, 4, 0, 8)
+    do = harp.DeviceOrderings(ctx, orders)
+    mout = harp.DevicePlans(ctx, do.C, do.S_max)
+    sg = torch.zeros((do.C, do.S_max), dtype=torch.int32, device=ctx.device)
+    mws = harp.mesh_workspace(ctx, tables, do)
+    for work in (small, mws[1:]):
+        with pytest.raises(harp.HarpError) as e:
+            harp.harp_plan_mesh_batch(ctx, tables, do, mout, sg, sg.clone(), work)
+        assert e.value.code == harp.ERR_WORKSPACE
+        with pytest.raises(harp.HarpError) as e:
+            harp.harp_plan_mesh_exact_batch(ctx, tables, do, mout, sg, sg.clone(), work)
+        assert e.value.code == harp.ERR_WORKSPACE
+    with pytest.raises(harp.HarpError) as e:
+        harp.harp_plan_mesh_batch(ctx, tables, do, mout, Null, sg, mws)
+    assert e.value.code == harp.ERR_INVALID_ARG
+    do.c.G_max = 5000
+    with pytest.raises(harp.HarpError) as e:
+        harp.harp_plan_mesh_batch(ctx, tables, do, mout, sg, sg.clone(), mws)
+    assert e.value.code == harp.ERR_SHAPE
+    with pytest.raises(harp.HarpError) as e:
+        harp.harp_measure_valu_int32(ctx, 0, 10, small)
+    assert e.value.code == harp.ERR_INVALID_ARG
+    torch.cuda.synchronize()
+    assert (out.to_host().status == -7).all()          # nothing ran
