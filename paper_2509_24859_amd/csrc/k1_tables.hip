@@ -324,6 +324,18 @@ __device__ __forceinline__ LongRow long_row(const TablesDev &tb, const LongRow *
     return lr;
 }
 
+// Order in which the long kernels walk the table rows: the fixed rows first, then the all-reduce
+// rows degree-major, so that groups whose own link has the same speed (the usual case: subclusters
+// of one GPU type) come one after the other with identical constants, and a row that equals the
+// one before it is stored again without being recomputed.
+__device__ __forceinline__ int long_row_order(const TablesDev &tb, int x) {
+    const int n_fixed = tb.T + 2;
+    if (x < n_fixed) return x;
+    const int e = x - n_fixed;
+    const int k = e / tb.G, g = e - k * tb.G;
+    return n_fixed + g * tb.n_tp + k;
+}
+
 // Launch 1 for long sequences: sum of every (row, run of 256 operators).
 __global__ __launch_bounds__(kScanThreads) void k1_long_sums(TablesDev tb, BuildLimits lim, int n_runs) {
     __shared__ LongRow rows_lds[kLongRowsInLds];
@@ -338,24 +350,33 @@ __global__ __launch_bounds__(kScanThreads) void k1_long_sums(TablesDev tb, Build
     const ActRun a = load_act_run(tb, lim, base, bad, ovf, act_seen);
     const bool all_narrow = __all(a.narrow);
     // the rows are split over gridDim.y workgroups so that enough wavefronts are in flight
-    const int r_begin = int(int64_t(n_rows) * blockIdx.y / gridDim.y);
-    const int r_end = int(int64_t(n_rows) * (blockIdx.y + 1) / gridDim.y);
-    for (int r = r_begin; r < r_end; ++r) {
+    const int x_begin = int(int64_t(n_rows) * blockIdx.y / gridDim.y);
+    const int x_end = int(int64_t(n_rows) * (blockIdx.y + 1) / gridDim.y);
+    int64_t same_mul = -1, same_den = -1, same_sum = 0;     // the all-reduce row computed last
+    for (int x = x_begin; x < x_end; ++x) {
+        const int r = long_row_order(tb, x);
         const LongRow lr = long_row(tb, rows_lds, n_rows, r);
         const RowSource &src = lr.src;
         const ArRow &arr = lr.arr;
         int64_t sum = 0;
         if (src.is_ar && ar_tight(arr, all_narrow, lim)) {
-            uint32_t v[kWaveItems];
-            ar_values_tight(arr, a, v);
+            if (arr.mul == same_mul && arr.den == same_den) {
+                sum = same_sum;                             // same link speed and degree: the same row
+            } else {
+                uint32_t v[kWaveItems];
+                ar_values_tight(arr, a, v);
 #pragma unroll
-            for (int q = 0; q < kWaveItems; ++q) sum += v[q];
+                for (int q = 0; q < kWaveItems; ++q) sum += v[q];
+#pragma unroll
+                for (int d = 32; d >= 1; d >>= 1) sum += __shfl_xor(sum, d, 64);
+                same_mul = arr.mul; same_den = arr.den; same_sum = sum;
+            }
         } else {
 #pragma unroll
             for (int q = 0; q < kWaveItems; ++q) sum += long_value(tb, src, arr, a, q, base, lim, bad, ovf);
-        }
 #pragma unroll
-        for (int d = 32; d >= 1; d >>= 1) sum += __shfl_xor(sum, d, 64);
+            for (int d = 32; d >= 1; d >>= 1) sum += __shfl_xor(sum, d, 64);
+        }
         if (lane == 0) tb.chunk_sums[int64_t(r) * n_runs + run] = sum;
     }
     // values are checked again by the scan launch; nothing to report here
@@ -377,36 +398,46 @@ __global__ __launch_bounds__(kScanThreads) void k1_long_scan(TablesDev tb, Build
     const ActRun a = load_act_run(tb, lim, base, bad, ovf, act_seen);
     const bool all_narrow = __all(a.narrow);
     // the rows are split over gridDim.y workgroups so that enough wavefronts are in flight
-    const int r_begin = int(int64_t(n_rows) * blockIdx.y / gridDim.y);
-    const int r_end = int(int64_t(n_rows) * (blockIdx.y + 1) / gridDim.y);
-    for (int r = r_begin; r < r_end; ++r) {
+    const int x_begin = int(int64_t(n_rows) * blockIdx.y / gridDim.y);
+    const int x_end = int(int64_t(n_rows) * (blockIdx.y + 1) / gridDim.y);
+    int64_t same_mul = -1, same_den = -1, same_start = -1;  // what the LDS tile currently holds
+    for (int x = x_begin; x < x_end; ++x) {
+        const int r = long_row_order(tb, x);
         const LongRow lr = long_row(tb, rows_lds, n_rows, r);
         const RowSource &src = lr.src;
         const ArRow &arr = lr.arr;
-        int64_t v[kWaveItems];
-        int64_t sum = 0;
-        if (src.is_ar && ar_tight(arr, all_narrow, lim)) {
-            uint32_t v32[kWaveItems];
-            ar_values_tight(arr, a, v32);
-#pragma unroll
-            for (int q = 0; q < kWaveItems; ++q) { v[q] = v32[q]; sum += v32[q]; }
-        } else {
-#pragma unroll
-            for (int q = 0; q < kWaveItems; ++q) {
-                v[q] = long_value(tb, src, arr, a, q, base, lim, bad, ovf);
-                sum += v[q];
-            }
-        }
-        const int64_t inc = wave_inclusive_scan(sum, lane);
-        int64_t acc = tb.chunk_sums[int64_t(r) * n_runs + run] + inc - sum;
         int64_t *out = tb.rows + int64_t(r) * tb.pitch;
         if (run == 0 && lane == 0) out[0] = 0;
-        // a lane holds four consecutive entries; passing them through the wavefront's LDS tile
-        // turns four 8-byte stores at a 32-byte stride into four fully contiguous 512-byte stores
+        const int64_t start = tb.chunk_sums[int64_t(r) * n_runs + run];   // sum of the row before this run
+        const bool tight = src.is_ar && ar_tight(arr, all_narrow, lim);
+        // rows of groups with the same link speed and degree are identical: the tile already holds them
+        const bool reuse = tight && arr.mul == same_mul && arr.den == same_den && start == same_start;
+        if (!reuse) {
+            int64_t v[kWaveItems];
+            int64_t sum = 0;
+            if (tight) {
+                uint32_t v32[kWaveItems];
+                ar_values_tight(arr, a, v32);
 #pragma unroll
-        for (int q = 0; q < kWaveItems; ++q) {
-            acc += v[q];
-            tile[lane * kWaveItems + q] = acc;
+                for (int q = 0; q < kWaveItems; ++q) { v[q] = v32[q]; sum += v32[q]; }
+                same_mul = arr.mul; same_den = arr.den; same_start = start;
+            } else {
+#pragma unroll
+                for (int q = 0; q < kWaveItems; ++q) {
+                    v[q] = long_value(tb, src, arr, a, q, base, lim, bad, ovf);
+                    sum += v[q];
+                }
+                same_mul = -1;
+            }
+            const int64_t inc = wave_inclusive_scan(sum, lane);
+            int64_t acc = start + inc - sum;
+            // a lane holds four consecutive entries; passing them through the wavefront's LDS tile
+            // turns four 8-byte stores at a 32-byte stride into four fully contiguous 512-byte stores
+#pragma unroll
+            for (int q = 0; q < kWaveItems; ++q) {
+                acc += v[q];
+                tile[lane * kWaveItems + q] = acc;
+            }
         }
         const int64_t first = int64_t(run) * kWaveChunk;
 #pragma unroll

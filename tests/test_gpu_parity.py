@@ -83,10 +83,16 @@ def test_tables_match_oracle_operator_level(harp, ctx):
     the chunk-major kernels; and 100,003 operators, built by the row-parallel ones."""
     for L in (300001, 100003):
         _check_operator_level(harp, ctx, L)
+    # groups whose own links differ (every third one alike): the chunk-major kernels reuse a row only
+    # when the one walked just before it has the same link speed and degree
+    _check_operator_level(harp, ctx, 270001, own_links=lambda g: 400_000 - 1000 * (g % 3) - (17 * g if g > 20 else 0))
 
 
-def _check_operator_level(harp, ctx, L):
+def _check_operator_level(harp, ctx, L, own_links=None):
     p = W.long_sequence(L)
+    if own_links is not None:
+        for g in range(p.G):
+            p.bw[g, g] = own_links(g)
     want = oracle.build_tables(p)
     tables = harp.Tables(ctx, p)
     PF, PP, PS, PR = tables.host_copies()
