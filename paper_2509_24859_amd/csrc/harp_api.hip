@@ -135,8 +135,8 @@ int n_plan_groups(const harp_ctx *ctx, int C, bool fast, int L, int S_max) {
 }
 
 // Workgroups of the submesh planner: resident ones, fewer when their slices would pass 16 GiB.
-int n_mesh_groups(const harp_ctx *ctx, int C, size_t per_group) {
-    long long n = (long long)ctx->n_cu * 4;
+int n_mesh_groups(const harp_ctx *ctx, int C, size_t per_group, int threads) {
+    long long n = (long long)ctx->n_cu * (2048 / threads);         // as many wavefronts as a CU holds
     const long long fit = (long long)((size_t(16) << 30) / (per_group ? per_group : 1));
     if (n > fit) n = fit;
     if (n > C) n = C;
@@ -403,7 +403,7 @@ int harp_plan_h1f1b_batch(harp_ctx *ctx, harp_tables *t, const harp_candidates *
 size_t harp_plan_mesh_workspace_bytes(harp_ctx *ctx, harp_tables *t, const harp_orderings *od) {
     if (check_orderings(ctx, t, od) != HARP_OK) return 0;
     const size_t per_group = plan_mesh_ws_per_group(t->dev.L, od->S_max, t->total_devices);
-    return 256 + size_t(n_mesh_groups(ctx, od->C, per_group)) * per_group;
+    return 256 + size_t(n_mesh_groups(ctx, od->C, per_group, plan_mesh_threads(t->dev.L, t->total_devices))) * per_group;
 }
 
 }  // extern "C"
@@ -421,7 +421,7 @@ int plan_mesh_common(harp_ctx *ctx, harp_tables *t, const harp_orderings *od, co
     if (od->C == 0) return HARP_OK;
     if (t->total_devices > 65535) return fail(ctx, HARP_ERR_SHAPE, "the submesh planner handles at most 65535 devices");
     const size_t per_group = plan_mesh_ws_per_group(t->dev.L, od->S_max, t->total_devices);
-    const int groups = n_mesh_groups(ctx, od->C, per_group);
+    const int groups = n_mesh_groups(ctx, od->C, per_group, plan_mesh_threads(t->dev.L, t->total_devices));
     const size_t need = 256 + size_t(groups) * per_group;
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0)
         return fail(ctx, HARP_ERR_WORKSPACE, "workspace must be a 256-byte aligned device pointer");

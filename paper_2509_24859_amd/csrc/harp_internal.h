@@ -104,6 +104,7 @@ void launch_plan_mesh(const TablesDev &tb, const OrdDev &od, const PlansDev &out
                       int32_t *stage_tp, int32_t *n_passes, bool exact, void *ws, int n_groups,
                       int64_t total_devices, hipStream_t st);
 size_t plan_mesh_ws_per_group(int L, int S_max, int64_t total_devices);
+int plan_mesh_threads(int L, int64_t total_devices);
 size_t plan_fast_ws_bytes(int L, int S_max, int C, int n_groups);
 int plan_fast_groups(int L, int S_max, int n_cu);
 void launch_plan_exact(const TablesDev &tb, const CandDev &cd, const PlansDev &out, int32_t *n_passes,

@@ -26,7 +26,7 @@ namespace harp {
 
 namespace {
 
-constexpr int kMeshThreads = 256;
+constexpr int kMeshMaxThreads = 1024;   // workgroup size is chosen per launch: 256 or 1024
 
 struct MeshSlice {
     int64_t *D0, *D1;    // [devices + 1][L + 1]
@@ -50,12 +50,12 @@ __device__ __forceinline__ MeshSlice mesh_slice(unsigned char *ws, size_t per_gr
 template <bool kCapped>
 __device__ __forceinline__ int64_t mesh_pass(const TablesDev &tb, const MeshSlice &m, const int32_t *offs,
                                              const int32_t *order, int K, int S, int64_t n_dev, int64_t cap) {
-    const int L = tb.L, W = L + 1, tid = threadIdx.x;
+    const int L = tb.L, W = L + 1, tid = threadIdx.x, nthreads = blockDim.x;
     const int Dtot = offs[K];
     const int64_t *PP = tb.PP(), *PS = tb.PS();
     int64_t *Dp = m.D0, *Dn = m.D1;
     __syncthreads();                                 // the previous pass is done with the rows
-    for (int x = tid; x < (Dtot + 1) * W; x += kMeshThreads) Dp[x] = kInf;
+    for (int x = tid; x < (Dtot + 1) * W; x += nthreads) Dp[x] = kInf;
     __syncthreads();
     if (tid == 0) Dp[0] = 0;                         // no stage, no operator, no device
     for (int s = 0; s < S; ++s) {
@@ -67,7 +67,7 @@ __device__ __forceinline__ int64_t mesh_pass(const TablesDev &tb, const MeshSlic
         const int d_lo = last ? Dtot : s + 1, d_hi = last ? Dtot : Dtot - (S - 1 - s);
         const int n_i = i_hi - i_lo + 1, n_d = d_hi - d_lo + 1;
         uint32_t *arg_s = m.arg + size_t(s) * size_t(n_dev + 1) * W;
-        for (int x = tid; x < n_i * n_d; x += kMeshThreads) {
+        for (int x = tid; x < n_i * n_d; x += nthreads) {
             const int i = i_lo + x % n_i, d2 = d_lo + x / n_i;
             int64_t best = kInf;
             int best_j = 0x7FFF, best_q = 0;
@@ -168,7 +168,7 @@ __device__ __forceinline__ void mesh_body(const TablesDev &tb, const OrdDev &od,
     __shared__ int64_t scored[2];
     __shared__ int shared_int[2];
     const int L = tb.L, S_max = od.S_max;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nthreads = blockDim.x;
     const MeshSlice m = mesh_slice(ws, per_group, L, n_dev);
     const int64_t m_cap = tb.M;
 
@@ -186,8 +186,8 @@ __device__ __forceinline__ void mesh_body(const TablesDev &tb, const OrdDev &od,
         total = scored[1];
     };
     auto keep = [&](int S) {
-        for (int s = tid; s <= S; s += kMeshThreads) kept_cuts[s] = cuts[s];
-        for (int s = tid; s < S; s += kMeshThreads) {
+        for (int s = tid; s <= S; s += nthreads) kept_cuts[s] = cuts[s];
+        for (int s = tid; s < S; s += nthreads) {
             kept_g[s] = slot_g[s]; kept_k[s] = slot_k[s]; kept_first[s] = slot_first[s];
         }
     };
@@ -203,13 +203,13 @@ __device__ __forceinline__ void mesh_body(const TablesDev &tb, const OrdDev &od,
         int32_t *sg = stage_group + int64_t(c) * S_max, *stp = stage_tp + int64_t(c) * S_max;
         auto fail = [&](int status) {
             write_failed(out, c, S_max, status);
-            for (int s = tid; s < S_max; s += kMeshThreads) { sg[s] = -1; stp[s] = -1; }
+            for (int s = tid; s < S_max; s += nthreads) { sg[s] = -1; stp[s] = -1; }
             if (tid == 0 && n_passes) n_passes[c] = 0;
         };
         // the ordering itself: counts in range, group ids in range and distinct
         int bad = (S < 1 || S > S_max || K < 1 || K > od.G_max) ? 1 : 0;
         if (!bad)
-            for (int k = tid; k < K; k += kMeshThreads) {
+            for (int k = tid; k < K; k += nthreads) {
                 const int g = og[k];
                 if (g < 0 || g >= tb.G) { bad = 1; continue; }
                 for (int q = 0; q < k; ++q)
@@ -263,8 +263,8 @@ __device__ __forceinline__ void mesh_body(const TablesDev &tb, const OrdDev &od,
         __syncthreads();
         int32_t *sp = out.splits + int64_t(c) * (S_max + 1);
         int32_t *df = out.dev_first + int64_t(c) * S_max;
-        for (int s = tid; s <= S_max; s += kMeshThreads) sp[s] = s <= S ? kept_cuts[s] : -1;
-        for (int s = tid; s < S_max; s += kMeshThreads) {
+        for (int s = tid; s <= S_max; s += nthreads) sp[s] = s <= S ? kept_cuts[s] : -1;
+        for (int s = tid; s < S_max; s += nthreads) {
             sg[s] = s < S ? int32_t(kept_g[s]) : -1;
             stp[s] = s < S ? tb.tp[kept_k[s]] : -1;
             df[s] = s < S ? kept_first[s] : -1;
@@ -278,14 +278,14 @@ __device__ __forceinline__ void mesh_body(const TablesDev &tb, const OrdDev &od,
     }
 }
 
-__global__ __launch_bounds__(kMeshThreads) void k2_mesh(TablesDev tb, OrdDev od, PlansDev out,
+__global__ __launch_bounds__(kMeshMaxThreads) void k2_mesh(TablesDev tb, OrdDev od, PlansDev out,
                                                         int32_t *stage_group, int32_t *stage_tp,
                                                         unsigned char *ws, size_t per_group, int64_t n_dev,
                                                         int *ticket) {
     mesh_body<false>(tb, od, out, stage_group, stage_tp, nullptr, ws, per_group, n_dev, ticket);
 }
 
-__global__ __launch_bounds__(kMeshThreads) void k2_mesh_exact(TablesDev tb, OrdDev od, PlansDev out,
+__global__ __launch_bounds__(kMeshMaxThreads) void k2_mesh_exact(TablesDev tb, OrdDev od, PlansDev out,
                                                               int32_t *stage_group, int32_t *stage_tp,
                                                               int32_t *n_passes, unsigned char *ws,
                                                               size_t per_group, int64_t n_dev, int *ticket) {
@@ -297,6 +297,12 @@ __global__ void k2_mesh_clear(int *ticket) {
 }
 
 }  // namespace
+
+// A stage has up to L x devices target cells: small tables get many small workgroups (more
+// orderings in flight), large ones few large workgroups (more lanes per ordering).
+int plan_mesh_threads(int L, int64_t total_devices) {
+    return int64_t(L + 1) * (total_devices + 1) >= 16384 ? kMeshMaxThreads : 256;
+}
 
 // Per-workgroup slice: two rows of the table, the back-pointers, and (first slice only) the ticket.
 size_t plan_mesh_ws_per_group(int L, int S_max, int64_t total_devices) {
@@ -312,12 +318,13 @@ void launch_plan_mesh(const TablesDev &tb, const OrdDev &od, const PlansDev &out
     int *ticket = static_cast<int *>(ws);
     unsigned char *slices = static_cast<unsigned char *>(ws) + 256;
     const size_t per_group = plan_mesh_ws_per_group(tb.L, od.S_max, total_devices);
+    const int threads = plan_mesh_threads(tb.L, total_devices);
     hipLaunchKernelGGL(k2_mesh_clear, dim3(1), dim3(64), 0, st, ticket);
     if (exact)
-        hipLaunchKernelGGL(k2_mesh_exact, dim3(n_groups), dim3(kMeshThreads), 0, st, tb, od, out, stage_group,
+        hipLaunchKernelGGL(k2_mesh_exact, dim3(n_groups), dim3(threads), 0, st, tb, od, out, stage_group,
                            stage_tp, n_passes, slices, per_group, total_devices, ticket);
     else
-        hipLaunchKernelGGL(k2_mesh, dim3(n_groups), dim3(kMeshThreads), 0, st, tb, od, out, stage_group, stage_tp,
+        hipLaunchKernelGGL(k2_mesh, dim3(n_groups), dim3(threads), 0, st, tb, od, out, stage_group, stage_tp,
                            slices, per_group, total_devices, ticket);
 }
 
