@@ -402,7 +402,7 @@ def mesh_workspace(ctx: Context, tables: Tables, do: DeviceOrderings):
     return torch.empty(n, dtype=torch.uint8, device=ctx.device)
 
 
-def plan_mesh(ctx: Context, problem, orders, exact: bool = False):
+def plan_mesh(ctx: Context, problem, orders, exact: bool = False, path: int = PATH_AUTO):
     """Convenience for tests: tables, submesh planner over a batch of orderings (min-max, or the
     exact search); host copies of the plans with `.stage_group`, `.stage_tp` (and `.n_passes`)."""
     torch = _torch()
@@ -414,11 +414,15 @@ def plan_mesh(ctx: Context, problem, orders, exact: bool = False):
     st = torch.full((max(do.C, 1), do.S_max), -7, dtype=torch.int32, device=ctx.device)
     n_passes = torch.full((max(do.C, 1),), -7, dtype=torch.int32, device=ctx.device)
     ws = mesh_workspace(ctx, tables, do)
-    if exact:
-        harp_plan_mesh_exact_batch(ctx, tables, do, out, sg, st, ws, n_passes)
-    else:
-        harp_plan_mesh_batch(ctx, tables, do, out, sg, st, ws)
-    torch.cuda.synchronize()
+    ctx.set_plan_path(path)
+    try:
+        if exact:
+            harp_plan_mesh_exact_batch(ctx, tables, do, out, sg, st, ws, n_passes)
+        else:
+            harp_plan_mesh_batch(ctx, tables, do, out, sg, st, ws)
+        torch.cuda.synchronize()
+    finally:
+        ctx.set_plan_path(PATH_AUTO)
     got = out.to_host()
     got.stage_group = sg[:do.C].cpu().numpy()
     got.stage_tp = st[:do.C].cpu().numpy()

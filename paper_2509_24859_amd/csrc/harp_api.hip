@@ -418,6 +418,8 @@ int plan_mesh_common(harp_ctx *ctx, harp_tables *t, const harp_orderings *od, co
     if (!out || (od->C > 0 && (!out->splits || !out->dev_first || !out->bottleneck || !out->iter_time ||
                                !out->status || !stage_group || !stage_tp)))
         return fail(ctx, HARP_ERR_INVALID_ARG, "null output array");
+    if (ctx->plan_path == HARP_PATH_FAST32 && !t->fast32)
+        return fail(ctx, HARP_ERR_UNIMPLEMENTED, "the 32-bit path was requested but these tables do not allow it");
     if (od->C == 0) return HARP_OK;
     if (t->total_devices > 65535) return fail(ctx, HARP_ERR_SHAPE, "the submesh planner handles at most 65535 devices");
     const size_t per_group = plan_mesh_ws_per_group(t->dev.L, od->S_max, t->total_devices);
@@ -431,7 +433,8 @@ int plan_mesh_common(harp_ctx *ctx, harp_tables *t, const harp_orderings *od, co
     if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
     const OrdDev o = { od->C, od->G_max, od->S_max, od->ord_S, od->ord_G, od->ord_group };
     const PlansDev pl = { out->splits, out->dev_first, out->bottleneck, out->iter_time, out->status };
-    launch_plan_mesh(t->dev, o, pl, stage_group, stage_tp, n_passes, exact, workspace, groups, t->total_devices,
+    launch_plan_mesh(t->dev, o, pl, stage_group, stage_tp, n_passes, exact, use_fast(ctx, t), workspace, groups,
+                     t->total_devices,
                      static_cast<hipStream_t>(hip_stream));
     e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(ctx, e, "launching the submesh planner kernel");

@@ -101,7 +101,7 @@ struct OrdDev {
 };
 constexpr int kMaxOrderGroups = 1024;   // groups one ordering may list (their offsets sit in LDS)
 void launch_plan_mesh(const TablesDev &tb, const OrdDev &od, const PlansDev &out, int32_t *stage_group,
-                      int32_t *stage_tp, int32_t *n_passes, bool exact, void *ws, int n_groups,
+                      int32_t *stage_tp, int32_t *n_passes, bool exact, bool fast32, void *ws, int n_groups,
                       int64_t total_devices, hipStream_t st);
 size_t plan_mesh_ws_per_group(int L, int S_max, int64_t total_devices);
 int plan_mesh_threads(int L, int64_t total_devices);

@@ -18,7 +18,8 @@
 // stop is strict and the update accepts equal values at a lower j, which keeps the lowest j.  The
 // three-index table does not fit in LDS (L x devices entries per stage): the two live rows and the
 // back-pointers sit in a per-workgroup slice of the caller's workspace, L2-resident at the sizes
-// of interest.  Arithmetic in int64 from the int64 tables, so any degrees and time widths work.
+// of interest.  Values are int64; stage and transfer times come from the 32-bit rows and the cut
+// table when the tables have them, else from the int64 rows (any degrees, any time width).
 #include "harp_internal.h"
 #include "plan_common.h"
 
@@ -47,9 +48,14 @@ __device__ __forceinline__ MeshSlice mesh_slice(unsigned char *ws, size_t per_gr
 // part.  kCapped = false: min-max form.  kCapped = true: least sum of (t + 2c) over transitions
 // whose stage and transfer times are at most cap.  Returns the value of the state (S, L, all
 // devices); back-pointers are left in the slice.
-template <bool kCapped>
+constexpr int kMeshGroupTable = 4096;   // device offsets whose group index is kept in LDS
+
+// kFast: stage times from the fused 32-bit rows and transfer times from the cut table (tables that
+// allow the 32-bit path); otherwise from the int64 rows, with a division per transfer time.
+template <bool kCapped, bool kFast>
 __device__ __forceinline__ int64_t mesh_pass(const TablesDev &tb, const MeshSlice &m, const int32_t *offs,
-                                             const int32_t *order, int K, int S, int64_t n_dev, int64_t cap) {
+                                             const int32_t *order, const uint16_t *group_at, int K, int S,
+                                             int64_t n_dev, int64_t cap) {
     const int L = tb.L, W = L + 1, tid = threadIdx.x, nthreads = blockDim.x;
     const int Dtot = offs[K];
     const int64_t *PP = tb.PP(), *PS = tb.PS();
@@ -73,7 +79,8 @@ __device__ __forceinline__ int64_t mesh_pass(const TablesDev &tb, const MeshSlic
             int best_j = 0x7FFF, best_q = 0;
             // the group whose devices end at or after d2: the stage [d2 - tp, d2) must lie inside one group
             int k = 0;
-            while (offs[k + 1] < d2) ++k;            // offs[k] < d2 <= offs[k + 1]
+            if (Dtot <= kMeshGroupTable) k = group_at[d2 - 1];     // the group of the stage's last device
+            else while (offs[k + 1] < d2) ++k;                     // offs[k] < d2 <= offs[k + 1]
             const int g = order[k];
             const int t = tb.group_type[g];
             const int64_t *pf = tb.PF(t);
@@ -81,10 +88,14 @@ __device__ __forceinline__ int64_t mesh_pass(const TablesDev &tb, const MeshSlic
             const int g_next = last ? g : (d2 == offs[k + 1] ? order[k + 1 < K ? k + 1 : k] : g);
             int64_t cut = 0;
             if (!last) {
-                const int64_t link = tb.bw[int64_t(g) * tb.G + g_next];
-                cut = (tb.act_bytes[i - 1] + link - 1) / link;
+                if (kFast) {
+                    cut = tb.CM[(int64_t(g) * tb.G + g_next) * tb.pitch32 + i];
+                } else {
+                    const int64_t link = tb.bw[int64_t(g) * tb.G + g_next];
+                    cut = (tb.act_bytes[i - 1] + link - 1) / link;
+                }
             }
-            const int64_t pfi = pf[i], ppi = PP[i], psi = PS[i];
+            const int64_t pfi = kFast ? 0 : pf[i], ppi = PP[i], psi = PS[i];
             if (!kCapped || cut <= cap) {
                 for (int q = 0; q < tb.n_tp; ++q) {
                     const int64_t tp = tb.tp[q];
@@ -94,12 +105,19 @@ __device__ __forceinline__ int64_t mesh_pass(const TablesDev &tb, const MeshSlic
                     if (d < offs[k] || d < s) continue;
                     const int shift = tb.tp_shift[q];
                     const int64_t *pr = tb.PR(g, q);
-                    const int64_t pri = pr[i];
+                    const uint32_t *p32 = kFast ? tb.P32 + (int64_t(g) * tb.n_tp + q) * tb.pitch32 : nullptr;
+                    const int64_t pri = kFast ? 0 : pr[i];
+                    const uint32_t xi = kFast ? p32[i] + uint32_t(tp) - 1u : 0u;
                     const int64_t capm = tp * mem_dev;
                     const int64_t *row = Dp + size_t(d) * W;
                     for (int j = i - 1; j >= s; --j) {
-                        const int64_t work = pfi - pf[j];
-                        const int64_t time = (shift >= 0 ? (work + tp - 1) >> shift : (work + tp - 1) / tp) + (pri - pr[j]);
+                        int64_t time;
+                        if (kFast) {
+                            time = int64_t((xi - p32[j]) >> shift);
+                        } else {
+                            const int64_t work = pfi - pf[j];
+                            time = (shift >= 0 ? (work + tp - 1) >> shift : (work + tp - 1) / tp) + (pri - pr[j]);
+                        }
                         // the stage time never decreases as j moves down: beyond the cap, or beyond the
                         // best value of the min-max form, no lower j can be taken or can match
                         if (time > (kCapped ? cap : best)) break;
@@ -155,12 +173,13 @@ __device__ __forceinline__ void mesh_backtrack(const TablesDev &tb, const MeshSl
 // table is walked over the caps exactly as the exact search of the hot path walks them (first at
 // t_S, then down from ceil(T / B), skipping caps that the sums rule out; equal totals keep the lower
 // cap), which returns what the increasing sweep over every distinct stage cost returns.
-template <bool kExact>
+template <bool kExact, bool kFast>
 __device__ __forceinline__ void mesh_body(const TablesDev &tb, const OrdDev &od, const PlansDev &out,
                                           int32_t *stage_group, int32_t *stage_tp, int32_t *n_passes,
                                           unsigned char *ws, size_t per_group, int64_t n_dev, int *ticket) {
     __shared__ int32_t offs[kMaxOrderGroups + 1];     // O_0 .. O_K
     __shared__ int32_t order[kMaxOrderGroups];
+    __shared__ uint16_t group_at[kMeshGroupTable];    // group index (in the order) of every device offset
     __shared__ int32_t cuts[kMaxStages + 1], kept_cuts[kMaxStages + 1];
     __shared__ uint16_t slot_g[kMaxStages], kept_g[kMaxStages];
     __shared__ uint8_t slot_k[kMaxStages], kept_k[kMaxStages];
@@ -225,8 +244,12 @@ __device__ __forceinline__ void mesh_body(const TablesDev &tb, const OrdDev &od,
         __syncthreads();
         const int Dtot = offs[K];
         if (S > L || S < K || S > Dtot) { fail(HARP_CAND_INFEASIBLE); continue; }
+        if (Dtot <= kMeshGroupTable) {
+            for (int k = 0; k < K; ++k)
+                for (int d = offs[k] + tid; d < offs[k + 1]; d += nthreads) group_at[d] = uint16_t(k);
+        }
 
-        if (mesh_pass<false>(tb, m, offs, order, K, S, n_dev, 0) == kInf) { fail(HARP_CAND_INFEASIBLE); continue; }
+        if (mesh_pass<false, kFast>(tb, m, offs, order, group_at, K, S, n_dev, 0) == kInf) { fail(HARP_CAND_INFEASIBLE); continue; }
         int64_t t_S, best_T;
         backtrack_and_score(K, S, t_S, best_T);
         int64_t best_b = t_S;
@@ -235,7 +258,7 @@ __device__ __forceinline__ void mesh_body(const TablesDev &tb, const OrdDev &od,
         if (kExact) {
             int64_t cap = t_S;
             while (S >= 2) {
-                const int64_t sum = mesh_pass<true>(tb, m, offs, order, K, S, n_dev, cap);
+                const int64_t sum = mesh_pass<true, kFast>(tb, m, offs, order, group_at, K, S, n_dev, cap);
                 if (sum == kInf) break;              // cannot happen at or above t_S
                 int64_t b, T;
                 backtrack_and_score(K, S, b, T);
@@ -278,18 +301,12 @@ __device__ __forceinline__ void mesh_body(const TablesDev &tb, const OrdDev &od,
     }
 }
 
+template <bool kExact, bool kFast>
 __global__ __launch_bounds__(kMeshMaxThreads) void k2_mesh(TablesDev tb, OrdDev od, PlansDev out,
-                                                        int32_t *stage_group, int32_t *stage_tp,
-                                                        unsigned char *ws, size_t per_group, int64_t n_dev,
-                                                        int *ticket) {
-    mesh_body<false>(tb, od, out, stage_group, stage_tp, nullptr, ws, per_group, n_dev, ticket);
-}
-
-__global__ __launch_bounds__(kMeshMaxThreads) void k2_mesh_exact(TablesDev tb, OrdDev od, PlansDev out,
-                                                              int32_t *stage_group, int32_t *stage_tp,
-                                                              int32_t *n_passes, unsigned char *ws,
-                                                              size_t per_group, int64_t n_dev, int *ticket) {
-    mesh_body<true>(tb, od, out, stage_group, stage_tp, n_passes, ws, per_group, n_dev, ticket);
+                                                           int32_t *stage_group, int32_t *stage_tp,
+                                                           int32_t *n_passes, unsigned char *ws,
+                                                           size_t per_group, int64_t n_dev, int *ticket) {
+    mesh_body<kExact, kFast>(tb, od, out, stage_group, stage_tp, n_passes, ws, per_group, n_dev, ticket);
 }
 
 __global__ void k2_mesh_clear(int *ticket) {
@@ -312,20 +329,22 @@ size_t plan_mesh_ws_per_group(int L, int S_max, int64_t total_devices) {
 }
 
 void launch_plan_mesh(const TablesDev &tb, const OrdDev &od, const PlansDev &out, int32_t *stage_group,
-                      int32_t *stage_tp, int32_t *n_passes, bool exact, void *ws, int n_groups,
+                      int32_t *stage_tp, int32_t *n_passes, bool exact, bool fast32, void *ws, int n_groups,
                       int64_t total_devices, hipStream_t st) {
     // layout: 256 bytes for the ticket, then the slices
     int *ticket = static_cast<int *>(ws);
     unsigned char *slices = static_cast<unsigned char *>(ws) + 256;
     const size_t per_group = plan_mesh_ws_per_group(tb.L, od.S_max, total_devices);
-    const int threads = plan_mesh_threads(tb.L, total_devices);
+    const dim3 grid(n_groups), block(plan_mesh_threads(tb.L, total_devices));
     hipLaunchKernelGGL(k2_mesh_clear, dim3(1), dim3(64), 0, st, ticket);
-    if (exact)
-        hipLaunchKernelGGL(k2_mesh_exact, dim3(n_groups), dim3(threads), 0, st, tb, od, out, stage_group,
-                           stage_tp, n_passes, slices, per_group, total_devices, ticket);
-    else
-        hipLaunchKernelGGL(k2_mesh, dim3(n_groups), dim3(threads), 0, st, tb, od, out, stage_group, stage_tp,
-                           slices, per_group, total_devices, ticket);
+#define HARP_MESH_LAUNCH(E, F)                                                                            \
+    hipLaunchKernelGGL(HIP_KERNEL_NAME(k2_mesh<E, F>), grid, block, 0, st, tb, od, out, stage_group, stage_tp, \
+                       n_passes, slices, per_group, total_devices, ticket)
+    if (exact && fast32) HARP_MESH_LAUNCH(true, true);
+    else if (exact) HARP_MESH_LAUNCH(true, false);
+    else if (fast32) HARP_MESH_LAUNCH(false, true);
+    else HARP_MESH_LAUNCH(false, false);
+#undef HARP_MESH_LAUNCH
 }
 
 }  // namespace harp

@@ -19,19 +19,23 @@ def ctx(harp):
 
 
 def _check(harp, ctx, problem, orders, label, exact=False):
+    """Both arithmetic paths (int64 rows always, 32-bit rows when the tables have them)."""
     want = oracle_plan_mesh_threaded(oracle.build_tables(problem), orders, exact=exact)
-    got, tables = harp.plan_mesh(ctx, problem, orders, exact)
-    if exact:
-        ok = (want.status == oracle.OK) & (orders.ord_S >= 2)
-        assert (got.n_passes[ok] >= 1).all() and (got.n_passes[~ok] == 0).all(), label
-        assert (got.n_passes[ok] <= want.n_caps[ok] + 1).all(), label
-    assert_plans_equal(got, want, label)
-    for name in ("stage_group", "stage_tp"):
-        a, b = getattr(got, name), getattr(want, name)
-        if not (a == b).all():
-            bad = np.nonzero((a != b).any(axis=1))[0]
-            raise AssertionError("%s: %s differs at %d orderings, first %d: got %s want %s"
-                                 % (label, name, bad.size, bad[0], a[bad[0]], b[bad[0]]))
+    fast32 = harp.Tables(ctx, problem).fast32
+    for path in [harp.PATH_GENERIC] + ([harp.PATH_FAST32] if fast32 else []):
+        tag = "%s (path %d)" % (label, path)
+        got, tables = harp.plan_mesh(ctx, problem, orders, exact, path)
+        if exact:
+            ok = (want.status == oracle.OK) & (orders.ord_S >= 2)
+            assert (got.n_passes[ok] >= 1).all() and (got.n_passes[~ok] == 0).all(), tag
+            assert (got.n_passes[ok] <= want.n_caps[ok] + 1).all(), tag
+        assert_plans_equal(got, want, tag)
+        for name in ("stage_group", "stage_tp"):
+            a, b = getattr(got, name), getattr(want, name)
+            if not (a == b).all():
+                bad = np.nonzero((a != b).any(axis=1))[0]
+                raise AssertionError("%s: %s differs at %d orderings, first %d: got %s want %s"
+                                     % (tag, name, bad.size, bad[0], a[bad[0]], b[bad[0]]))
     return got, want, tables
 
 
