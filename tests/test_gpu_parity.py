@@ -164,8 +164,8 @@ def test_plan_tiny_all_paths(harp, ctx):
     assert harp.PATH_FAST32 in ran
 
 
-@pytest.mark.parametrize("name,n", [("llama7b", 1024), ("llama70b", 16384), ("finegrained", 4096),
-                                    ("stress", 384)])
+@pytest.mark.parametrize("name,n", [("llama7b", 1024), ("llama70b", 16384), ("finegrained", 65536),
+                                    ("stress", 16384)])
 def test_plan_workloads_all_paths(harp, ctx, name, n):
     w = W.make(name)
     cands = w.candidates(0, n)
