@@ -298,32 +298,6 @@ __device__ __forceinline__ int64_t long_value(const TablesDev &tb, const RowSour
     return row_value(src, base + q, lim, bad, ovf, unused);
 }
 
-// Row constants of every table row, worked out once per workgroup (each needs a link bandwidth
-// from memory and a reciprocal) and kept in LDS for the walk over the rows.
-struct LongRow {
-    RowSource src;
-    ArRow arr;
-};
-constexpr int kLongRowsInLds = 512;
-
-__device__ __forceinline__ void stage_long_rows(const TablesDev &tb, LongRow *rows_lds, int n_rows) {
-    if (n_rows <= kLongRowsInLds) {
-        for (int r = threadIdx.x; r < n_rows; r += blockDim.x) {
-            rows_lds[r].src = row_source(tb, r);
-            rows_lds[r].arr = ar_row(rows_lds[r].src);
-        }
-    }
-    __syncthreads();
-}
-
-__device__ __forceinline__ LongRow long_row(const TablesDev &tb, const LongRow *rows_lds, int n_rows, int r) {
-    if (n_rows <= kLongRowsInLds) return rows_lds[r];
-    LongRow lr;
-    lr.src = row_source(tb, r);
-    lr.arr = ar_row(lr.src);
-    return lr;
-}
-
 // Order in which the long kernels walk the table rows: the fixed rows first, then the all-reduce
 // rows degree-major, so that groups whose own link has the same speed (the usual case: subclusters
 // of one GPU type) come one after the other with identical constants, and a row that equals the
@@ -336,11 +310,45 @@ __device__ __forceinline__ int long_row_order(const TablesDev &tb, int x) {
     return n_fixed + g * tb.n_tp + k;
 }
 
+// Row constants of the table rows a workgroup walks (positions x_begin .. x_end - 1 of the order
+// above), worked out once per workgroup (each needs a link bandwidth from memory and a reciprocal)
+// and kept in LDS.  The array is dynamic LDS sized for the workgroup's share of this problem's rows:
+// a fixed array for the largest case would leave room for two workgroups per CU only.
+struct LongRow {
+    RowSource src;
+    ArRow arr;
+};
+constexpr int kLongRowsInLds = 512;     // rows per workgroup beyond which the constants are recomputed per use
+
+__device__ __forceinline__ void stage_long_rows(const TablesDev &tb, LongRow *rows_lds, int x_begin, int x_end) {
+    if (x_end - x_begin <= kLongRowsInLds) {
+        for (int x = x_begin + threadIdx.x; x < x_end; x += blockDim.x) {
+            const int r = long_row_order(tb, x);
+            rows_lds[x - x_begin].src = row_source(tb, r);
+            rows_lds[x - x_begin].arr = ar_row(rows_lds[x - x_begin].src);
+        }
+    }
+    __syncthreads();
+}
+
+__device__ __forceinline__ LongRow long_row(const TablesDev &tb, const LongRow *rows_lds, int x_begin, int x_end,
+                                            int x) {
+    if (x_end - x_begin <= kLongRowsInLds) return rows_lds[x - x_begin];
+    LongRow lr;
+    lr.src = row_source(tb, long_row_order(tb, x));
+    lr.arr = ar_row(lr.src);
+    return lr;
+}
+
 // Launch 1 for long sequences: sum of every (row, run of 256 operators).
 __global__ __launch_bounds__(kScanThreads) void k1_long_sums(TablesDev tb, BuildLimits lim, int n_runs) {
-    __shared__ LongRow rows_lds[kLongRowsInLds];
+    extern __shared__ __align__(16) unsigned char long_lds[];
+    LongRow *rows_lds = reinterpret_cast<LongRow *>(long_lds);
     const int n_rows = tb.n_rows();
-    stage_long_rows(tb, rows_lds, n_rows);
+    // the rows are split over gridDim.y workgroups so that enough wavefronts are in flight
+    const int x_begin = int(int64_t(n_rows) * blockIdx.y / gridDim.y);
+    const int x_end = int(int64_t(n_rows) * (blockIdx.y + 1) / gridDim.y);
+    stage_long_rows(tb, rows_lds, x_begin, x_end);
     const int lane = threadIdx.x & 63;
     const int run = blockIdx.x * (kScanThreads / 64) + (threadIdx.x >> 6);
     if (run >= n_runs) return;
@@ -349,13 +357,10 @@ __global__ __launch_bounds__(kScanThreads) void k1_long_sums(TablesDev tb, Build
     unsigned long long act_seen = 0;
     const ActRun a = load_act_run(tb, lim, base, bad, ovf, act_seen);
     const bool all_narrow = __all(a.narrow);
-    // the rows are split over gridDim.y workgroups so that enough wavefronts are in flight
-    const int x_begin = int(int64_t(n_rows) * blockIdx.y / gridDim.y);
-    const int x_end = int(int64_t(n_rows) * (blockIdx.y + 1) / gridDim.y);
     int64_t same_mul = -1, same_den = -1, same_sum = 0;     // the all-reduce row computed last
     for (int x = x_begin; x < x_end; ++x) {
         const int r = long_row_order(tb, x);
-        const LongRow lr = long_row(tb, rows_lds, n_rows, r);
+        const LongRow lr = long_row(tb, rows_lds, x_begin, x_end, x);
         const RowSource &src = lr.src;
         const ArRow &arr = lr.arr;
         int64_t sum = 0;
@@ -384,9 +389,13 @@ __global__ __launch_bounds__(kScanThreads) void k1_long_sums(TablesDev tb, Build
 
 // Launch 3 for long sequences: scan every (row, run), add the run's offset, write the table rows.
 __global__ __launch_bounds__(kScanThreads) void k1_long_scan(TablesDev tb, BuildLimits lim, int n_runs) {
-    __shared__ LongRow rows_lds[kLongRowsInLds];
+    extern __shared__ __align__(16) unsigned char long_lds[];
+    LongRow *rows_lds = reinterpret_cast<LongRow *>(long_lds);
     const int n_rows = tb.n_rows();
-    stage_long_rows(tb, rows_lds, n_rows);
+    // the rows are split over gridDim.y workgroups so that enough wavefronts are in flight
+    const int x_begin = int(int64_t(n_rows) * blockIdx.y / gridDim.y);
+    const int x_end = int(int64_t(n_rows) * (blockIdx.y + 1) / gridDim.y);
+    stage_long_rows(tb, rows_lds, x_begin, x_end);
     __shared__ int64_t tiles[kScanThreads / 64][kWaveChunk];
     const int lane = threadIdx.x & 63;
     const int run = blockIdx.x * (kScanThreads / 64) + (threadIdx.x >> 6);
@@ -397,13 +406,10 @@ __global__ __launch_bounds__(kScanThreads) void k1_long_scan(TablesDev tb, Build
     unsigned long long act_seen = 0;
     const ActRun a = load_act_run(tb, lim, base, bad, ovf, act_seen);
     const bool all_narrow = __all(a.narrow);
-    // the rows are split over gridDim.y workgroups so that enough wavefronts are in flight
-    const int x_begin = int(int64_t(n_rows) * blockIdx.y / gridDim.y);
-    const int x_end = int(int64_t(n_rows) * (blockIdx.y + 1) / gridDim.y);
     int64_t same_mul = -1, same_den = -1, same_start = -1;  // what the LDS tile currently holds
     for (int x = x_begin; x < x_end; ++x) {
         const int r = long_row_order(tb, x);
-        const LongRow lr = long_row(tb, rows_lds, n_rows, r);
+        const LongRow lr = long_row(tb, rows_lds, x_begin, x_end, x);
         const RowSource &src = lr.src;
         const ArRow &arr = lr.arr;
         int64_t *out = tb.rows + int64_t(r) * tb.pitch;
@@ -571,9 +577,11 @@ void launch_build(const TablesDev &tb, const BuildLimits &lim, hipStream_t st) {
         const int n_runs = (tb.L + kWaveChunk - 1) / kWaveChunk;
         const int groups = (n_runs + kScanThreads / 64 - 1) / (kScanThreads / 64);
         const int row_parts = n_rows >= 32 ? 4 : 1;
-        hipLaunchKernelGGL(k1_long_sums, dim3(groups, row_parts), dim3(kScanThreads), 0, st, tb, lim, n_runs);
+        const int rows_per_part = (n_rows + row_parts - 1) / row_parts + 1;
+        const size_t row_lds = rows_per_part <= kLongRowsInLds ? size_t(rows_per_part) * sizeof(LongRow) : 16;
+        hipLaunchKernelGGL(k1_long_sums, dim3(groups, row_parts), dim3(kScanThreads), row_lds, st, tb, lim, n_runs);
         hipLaunchKernelGGL(k1_scan_chunk_sums, dim3(n_rows), dim3(kScanThreads), 0, st, tb, n_runs);
-        hipLaunchKernelGGL(k1_long_scan, dim3(groups, row_parts), dim3(kScanThreads), 0, st, tb, lim, n_runs);
+        hipLaunchKernelGGL(k1_long_scan, dim3(groups, row_parts), dim3(kScanThreads), row_lds, st, tb, lim, n_runs);
         hipLaunchKernelGGL(k1_finalize, dim3(1), dim3(256), 0, st, tb, lim);
         return;                   // sequences this long are beyond the 32-bit planner path
     }
