@@ -48,13 +48,13 @@ __device__ __forceinline__ MeshSlice mesh_slice(unsigned char *ws, size_t per_gr
 // part.  kCapped = false: min-max form.  kCapped = true: least sum of (t + 2c) over transitions
 // whose stage and transfer times are at most cap.  Returns the value of the state (S, L, all
 // devices); back-pointers are left in the slice.
-constexpr int kMeshGroupTable = 4096;   // device offsets whose group index is kept in LDS
+constexpr int kMeshGroupTable = 2048;   // device offsets whose group index is kept in LDS
 
 // kFast: stage times from the fused 32-bit rows and transfer times from the cut table (tables that
 // allow the 32-bit path); otherwise from the int64 rows, with a division per transfer time.
 template <bool kCapped, bool kFast>
 __device__ __forceinline__ int64_t mesh_pass(const TablesDev &tb, const MeshSlice &m, const int32_t *offs,
-                                             const int32_t *order, const uint16_t *group_at, int K, int S,
+                                             const uint16_t *order, const uint16_t *group_at, int K, int S,
                                              int64_t n_dev, int64_t cap) {
     const int L = tb.L, W = L + 1, tid = threadIdx.x, nthreads = blockDim.x;
     const int Dtot = offs[K];
@@ -146,7 +146,7 @@ __device__ __forceinline__ int64_t mesh_pass(const TablesDev &tb, const MeshSlic
 
 // Thread 0: follows the back-pointers from (S, L, all devices).
 __device__ __forceinline__ void mesh_backtrack(const TablesDev &tb, const MeshSlice &m, const int32_t *offs,
-                                               const int32_t *order, int K, int S, int64_t n_dev, int32_t *cuts,
+                                               const uint16_t *order, int K, int S, int64_t n_dev, int32_t *cuts,
                                                uint16_t *slot_g, uint8_t *slot_k, int32_t *slot_first) {
     const int L = tb.L, W = L + 1;
     int i = L, d = offs[K];
@@ -178,7 +178,7 @@ __device__ __forceinline__ void mesh_body(const TablesDev &tb, const OrdDev &od,
                                           int32_t *stage_group, int32_t *stage_tp, int32_t *n_passes,
                                           unsigned char *ws, size_t per_group, int64_t n_dev, int *ticket) {
     __shared__ int32_t offs[kMaxOrderGroups + 1];     // O_0 .. O_K
-    __shared__ int32_t order[kMaxOrderGroups];
+    __shared__ uint16_t order[kMaxOrderGroups];      // group ids are below 4096
     __shared__ uint16_t group_at[kMeshGroupTable];    // group index (in the order) of every device offset
     __shared__ int32_t cuts[kMaxStages + 1], kept_cuts[kMaxStages + 1];
     __shared__ uint16_t slot_g[kMaxStages], kept_g[kMaxStages];
@@ -233,7 +233,7 @@ __device__ __forceinline__ void mesh_body(const TablesDev &tb, const OrdDev &od,
                 if (g < 0 || g >= tb.G) { bad = 1; continue; }
                 for (int q = 0; q < k; ++q)
                     if (og[q] == g) bad = 1;
-                order[k] = g;
+                order[k] = uint16_t(g);
             }
         if (__syncthreads_or(bad)) { fail(HARP_CAND_INVALID); continue; }
         if (tid == 0) {
