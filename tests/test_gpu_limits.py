@@ -153,3 +153,35 @@ def test_argument_errors_of_the_newer_entry_points(harp, ctx):
     assert e.value.code == harp.ERR_INVALID_ARG
     torch.cuda.synchronize()
     assert (out.to_host().status == -7).all()          # nothing ran
+
+
+def test_calls_on_a_caller_stream_and_back_to_back(harp, ctx):
+    """Every entry point enqueues on the stream it is given; calls queued back to back on one stream
+    with one workspace (each after the other, no host synchronisation in between) give the same
+    results as calls made one at a time."""
+    import torch
+    w = W.make("llama70b")
+    cands = w.candidates(0, 2048)
+    ref, _ = harp.plan(ctx, w.problem, cands)
+    ref_exact, _, _ = harp.plan_exact(ctx, w.problem, cands)
+    side = torch.cuda.Stream()                      # default priority
+    with torch.cuda.stream(side):
+        tables = harp.Tables(ctx, w.problem, side)
+        dc = harp.DeviceCandidates(ctx, cands)
+        out1 = harp.DevicePlans(ctx, dc.C, dc.S_max)
+        out2 = harp.DevicePlans(ctx, dc.C, dc.S_max)
+        out3 = harp.DevicePlans(ctx, dc.C, dc.S_max)
+        ws = harp.plan_workspace(ctx, tables, dc)
+        best_t = torch.empty(1, dtype=torch.int64, device=ctx.device)
+        best_i = torch.empty(1, dtype=torch.int32, device=ctx.device)
+        harp.harp_plan_batch(ctx, tables, dc, out1, ws, side)
+        harp.harp_plan_exact_batch(ctx, tables, dc, out2, ws, None, side)
+        harp.harp_plan_batch(ctx, tables, dc, out3, ws, side)
+        harp.harp_argmin_batch(ctx, dc.C, out2.iter_time, out2.status, best_t, best_i, side)
+    side.synchronize()
+    a, b, c = out1.to_host(), out2.to_host(), out3.to_host()
+    for name in ("status", "splits", "dev_first", "bottleneck", "iter_time"):
+        assert (getattr(a, name) == getattr(ref, name)).all(), name
+        assert (getattr(c, name) == getattr(ref, name)).all(), name
+        assert (getattr(b, name) == getattr(ref_exact, name)).all(), name
+    assert (int(best_t.item()), int(best_i.item())) == oracle.argmin_batch(ref_exact.iter_time, ref_exact.status)
