@@ -131,6 +131,28 @@ def timed_ms(torch, fn, reps):
     return a.elapsed_time(b) / reps
 
 
+def graph_replay(ctx, binding, torch, tables, dc, out, ws, best_t, best_i, reps):
+    """plan + argmin of one step captured once in a HIP graph and replayed: what a caller that plans
+    many small batches saves in launch overhead (the table build stays outside: its verdict is read
+    back on the host)."""
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+
+    def body(stream):
+        binding.harp_plan_batch(ctx, tables, dc, out, ws, stream)
+        binding.harp_argmin_batch(ctx, dc.C, out.iter_time, out.status, best_t, best_i, stream)
+
+    with torch.cuda.stream(side):
+        body(side)
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        body(torch.cuda.current_stream())
+    eager = timed_ms(torch, lambda: body(None), reps)
+    replay = timed_ms(torch, graph.replay, reps)
+    return {"eager_ms": eager, "replay_ms": replay, "launches_captured": 4}
+
+
 def exact_search(ctx, binding, torch, w, tables, dc, cands, minmax, reps, cpu_candidates):
     """The exact search (cap sweep on top of the min-max plans) over the same batch: time per call,
     capped passes per candidate, what it gains over the min-max plans, and the oracle's sweep timed
@@ -288,6 +310,8 @@ def main():
     ap.add_argument("--cpu-candidates", type=int, default=0)
     ap.add_argument("--tables-L", type=int, default=1 << 20,
                     help="operators of the table-build streaming measurement (0 = skip)")
+    ap.add_argument("--graph-reps", type=int, default=20,
+                    help="replays of plan + argmin captured in a HIP graph (0 = skip)")
     ap.add_argument("--exact-reps", type=int, default=3,
                     help="timed calls of the exact search over the same batch (0 = skip)")
     ap.add_argument("--exact-cpu-candidates", type=int, default=16)
@@ -415,6 +439,8 @@ def main():
         result["roofline"]["frac_of_measured_peak"] = achieved / peaks["valu_int32_lane_ops_per_s"]
     if args.tables_L:
         result["tables_streaming"] = tables_streaming(ctx, binding, workloads, torch, args.tables_L)
+    if args.graph_reps and fast:
+        result["graph_replay"] = graph_replay(ctx, binding, torch, tables, dc, out, ws, best_t, best_i, args.graph_reps)
     if args.exact_reps and fast:
         result["exact_search"] = exact_search(ctx, binding, torch, w, tables, dc, cands, got, args.exact_reps,
                                               0 if args.no_cpu_baseline else args.exact_cpu_candidates)

@@ -185,3 +185,49 @@ def test_calls_on_a_caller_stream_and_back_to_back(harp, ctx):
         assert (getattr(c, name) == getattr(ref, name)).all(), name
         assert (getattr(b, name) == getattr(ref_exact, name)).all(), name
     assert (int(best_t.item()), int(best_i.item())) == oracle.argmin_batch(ref_exact.iter_time, ref_exact.status)
+
+
+def test_planner_calls_inside_a_hip_graph(harp, ctx):
+    """The planner launches are plain kernel launches on the caller's stream (counters are cleared by
+    a kernel, never by a memset), so a caller may capture them: a graph of plan + exact + argmin is
+    replayed several times, with the candidates changed in place and eager work in between, and
+    every replay is compared with eager calls on the same inputs."""
+    import torch
+    w = W.make("llama7b")
+    all_cands = w.candidates()
+    tables = harp.Tables(ctx, w.problem)                 # built and finalized outside the graph
+    first = all_cands.slice(0, 256)
+    dc = harp.DeviceCandidates(ctx, first)
+    out = harp.DevicePlans(ctx, dc.C, dc.S_max)
+    out_e = harp.DevicePlans(ctx, dc.C, dc.S_max)
+    ws = harp.plan_workspace(ctx, tables, dc)
+    best_t = torch.empty(1, dtype=torch.int64, device=ctx.device)
+    best_i = torch.empty(1, dtype=torch.int32, device=ctx.device)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                        # warm-up on the capture stream
+        harp.harp_plan_batch(ctx, tables, dc, out, ws, side)
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        s = torch.cuda.current_stream()
+        harp.harp_plan_batch(ctx, tables, dc, out, ws, s)
+        harp.harp_plan_exact_batch(ctx, tables, dc, out_e, ws, None, s)
+        harp.harp_argmin_batch(ctx, dc.C, out_e.iter_time, out_e.status, best_t, best_i, s)
+    for k in range(4):
+        batch = all_cands.slice(256 * k, 256 * (k + 1))
+        dc.cs.copy_(torch.from_numpy(batch.cand_S))
+        dc.cg.copy_(torch.from_numpy(batch.cand_group))
+        dc.ct.copy_(torch.from_numpy(batch.cand_tp))
+        out.poison()
+        out_e.poison()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got, got_e = out.to_host(), out_e.to_host()
+        want, _ = harp.plan(ctx, w.problem, batch)       # eager work between the replays
+        want_e, _, _ = harp.plan_exact(ctx, w.problem, batch)
+        for name in ("status", "splits", "dev_first", "bottleneck", "iter_time"):
+            assert (getattr(got, name) == getattr(want, name)).all(), (k, name)
+            assert (getattr(got_e, name) == getattr(want_e, name)).all(), (k, name)
+        assert (int(best_t.item()), int(best_i.item())) == oracle.argmin_batch(want_e.iter_time, want_e.status)
