@@ -500,3 +500,68 @@ def plan_mesh_capped(p, S: int, groups, cap: int):
         cuts.append(j)
         i = j
     return value, cuts[::-1], slots[::-1]
+
+
+def plan_mesh_h1f1b(p, S: int, S_max: int, groups, t_max: int):
+    """The full recurrence of section 5.2.3 for one cap (device index and H-1F1B count in the
+    state, suffix direction) as a memoised recursion: (status, cuts, slot list, counts, least sum).
+    state(i, slot, d) = the stages from `slot` on start at operator i and at device offset d."""
+    L, M = int(p.L), int(p.M)
+    if not mesh_valid(p, S, S_max, groups):
+        return 2, None, None, None, INF
+    groups = [int(g) for g in groups]
+    bounds = [0]
+    for g in groups:
+        bounds.append(bounds[-1] + int(p.group_ndev[g]))
+    total = bounds[-1]
+    degrees = [int(x) for x in p.tp_degrees]
+    if S > L or S < len(groups) or S > total or t_max < 0:
+        return 1, None, None, None, INF
+    memo = {}
+
+    def group_at(d):
+        return max(k for k in range(len(groups)) if bounds[k] <= d)
+
+    def state(i, slot, d):
+        if slot == S:
+            return (0, 0, -1, -1) if (i == L and d == total) else (INF, 0, -1, -1)
+        key = (i, slot, d)
+        if key in memo:
+            return memo[key]
+        best = (INF, 0, -1, -1)
+        if d < total:
+            k = group_at(d)
+            g = groups[k]
+            last = slot == S - 1
+            for j in range(i + 1, L - (S - slot - 1) + 1):
+                for q, deg in enumerate(degrees):
+                    d2 = d + deg
+                    if d2 > bounds[k + 1] or (d2 == total) != last:
+                        continue
+                    rest, n_next, _, _ = state(j, slot + 1, d2)
+                    if rest == INF:
+                        continue
+                    g_next = g if (last or d2 < bounds[k + 1]) else groups[k + 1]
+                    c = 0 if last else cut_time(p, g, g_next, j)
+                    t = stage_time(p, g, deg, i, j)
+                    if c > t_max or t > t_max:
+                        continue
+                    n = min(M, h1f1b_delta(c, t_max) + n_next)
+                    if not memory_fits(p, g, deg, n, i, j):
+                        continue
+                    if (rest + t + 2 * c, j, q) < (best[0], best[2] if best[2] >= 0 else INF, best[3]):
+                        best = (rest + t + 2 * c, n, j, q)
+        memo[key] = best
+        return best
+
+    total_sum = state(0, 0, 0)[0]
+    if total_sum == INF:
+        return 1, None, None, None, INF
+    cuts, slots, counts, i, d = [0], [], [], 0, 0
+    for slot in range(S):
+        _, n, j, q = state(i, slot, d)
+        slots.append((groups[group_at(d)], degrees[q]))
+        counts.append(n)
+        cuts.append(j)
+        i, d = j, d + degrees[q]
+    return 0, cuts, slots, counts, total_sum

@@ -875,3 +875,138 @@ int oracle_plan_mesh_exact_batch(const oracle_problem *p, const int64_t *PF, con
     return mesh_batch(p, PF, PP, PS, PR, C, G_max, S_max, ord_S, ord_G, ord_group, c_begin, c_end, splits,
                       stage_group, stage_tp, dev_first, bottleneck, iter_time, status, 1, n_caps);
 }
+
+/* ---------------------------------------------------------------------------------------------
+ * The paper's recurrence in full for one cap (section 5.2.3): eq. dp_general with its device index
+ * AND the H-1F1B warm-up count of eq. dp_ni in the state, in the suffix direction.
+ *
+ * State (s, i, e): the last s stages hold the operators i..L-1 and use exactly the last e devices
+ * of the ordered groups; it keeps the least sum of (t + 2c) under the cap and the warm-up count N of
+ * its first stage, as determined by the continuation that attained the least sum.  The first of
+ * those stages starts at device offset D - e, runs on the group that offset falls in and takes tp
+ * of its devices (not reaching beyond the group); the cut behind it crosses to the next group's
+ * link when the stage exhausts its group.  Ties: lowest end cut j, then smallest degree.
+ * ------------------------------------------------------------------------------------------- */
+int oracle_plan_mesh_h1f1b_batch(const oracle_problem *p, const int64_t *PF, const int64_t *PP,
+                                 const int64_t *PS, const int64_t *PR, int32_t C, int32_t G_max, int32_t S_max,
+                                 const int32_t *ord_S, const int32_t *ord_G, const int32_t *ord_group,
+                                 const int64_t *t_max, int32_t c_begin, int32_t c_end, int32_t *splits,
+                                 int32_t *stage_group, int32_t *stage_tp, int32_t *dev_first, int32_t *warmup,
+                                 int64_t *bottleneck, int64_t *iter_time, int32_t *status)
+{
+    if (C < 0 || S_max < 1 || G_max < 1 || c_begin < 0 || c_end > C || c_begin > c_end) return ORACLE_BAD_ARG;
+    if (p->L > 65535) return ORACLE_BAD_ARG;
+    const int L = p->L;
+    tables_view v = { p, PF, PP, PS, PR };
+    int64_t total_dev = 0;
+    for (int g = 0; g < p->G; ++g) total_dev += p->group_ndev[g];
+    mesh_tables m;
+    m.W = (size_t)(L + 1);
+    m.Dn = (size_t)total_dev + 1;
+    const size_t cells = (size_t)(S_max + 1) * m.W * m.Dn;
+    m.D = (int64_t *)malloc(sizeof(int64_t) * cells);
+    m.arg_j = (int32_t *)malloc(sizeof(int32_t) * cells);
+    m.arg_k = (int32_t *)malloc(sizeof(int32_t) * cells);
+    int32_t *N = (int32_t *)malloc(sizeof(int32_t) * cells);
+    m.O = (int64_t *)malloc(sizeof(int64_t) * (size_t)(G_max + 1));
+    char *seen = (char *)malloc((size_t)p->G);
+    if (!m.D || !m.arg_j || !m.arg_k || !N || !m.O || !seen) return ORACLE_BAD_ARG;
+    for (int32_t c = c_begin; c < c_end; ++c) {
+        const int S = ord_S[c], K = ord_G[c];
+        const int64_t cap = t_max[c];
+        const int32_t *og = ord_group + (size_t)c * G_max;
+        int32_t *sp = splits + (size_t)c * (S_max + 1), *sg = stage_group + (size_t)c * S_max;
+        int32_t *st = stage_tp + (size_t)c * S_max, *df = dev_first + (size_t)c * S_max;
+        int32_t *wu = warmup + (size_t)c * S_max;
+        fill_failed(S_max, sp, df, bottleneck + c, iter_time + c);
+        for (int s = 0; s < S_max; ++s) { sg[s] = -1; st[s] = -1; wu[s] = -1; }
+        status[c] = CAND_INVALID;
+        if (S < 1 || S > S_max || K < 1 || K > G_max) continue;
+        int ok = 1;
+        memset(seen, 0, (size_t)p->G);
+        m.O[0] = 0;
+        for (int k = 0; k < K && ok; ++k) {
+            if (og[k] < 0 || og[k] >= p->G || seen[og[k]]) { ok = 0; break; }
+            seen[og[k]] = 1;
+            m.O[k + 1] = m.O[k] + p->group_ndev[og[k]];
+        }
+        if (!ok) continue;
+        status[c] = CAND_INFEASIBLE;
+        const int64_t Dtot = m.O[K];
+        if (S > L || S < K || S > Dtot || cap < 0) continue;
+        for (size_t x = 0; x < (size_t)(S + 1) * m.W * m.Dn; ++x) { m.D[x] = ORACLE_INF; N[x] = 0; m.arg_j[x] = -1; m.arg_k[x] = -1; }
+        m.D[MESH_AT(&m, 0, L, 0)] = 0;                    /* no stages left, no operators, no devices */
+        for (int s = 1; s <= S; ++s) {
+            for (int64_t e = s; e <= Dtot - (S - s); ++e) {
+                if ((s == S) != (e == Dtot)) continue;    /* the whole pipeline, and only it, uses every device */
+                const int64_t d0 = Dtot - e;              /* first device of the stage this step places */
+                int k = 0;
+                while (m.O[k + 1] <= d0) ++k;
+                const int g = og[k];
+                for (int q = 0; q < p->n_tp; ++q) {
+                    const int tp = p->tp_degrees[q];
+                    if (d0 + tp > m.O[k + 1]) continue;   /* a stage stays inside one group */
+                    const int64_t e0 = e - tp;            /* devices of the stages behind it */
+                    if ((s == 1) != (e0 == 0)) continue;
+                    const int g_next = (s == 1) ? g : (d0 + tp == m.O[k + 1] ? og[k + 1] : g);
+                    for (int i = S - s; i <= L - s; ++i) {
+                        if (s == S && i != 0) continue;
+                        int64_t best = m.D[MESH_AT(&m, s, i, e)];
+                        int32_t bj = m.arg_j[MESH_AT(&m, s, i, e)], bq = m.arg_k[MESH_AT(&m, s, i, e)];
+                        int32_t bn = N[MESH_AT(&m, s, i, e)];
+                        for (int j = i + 1; j <= L - (s - 1); ++j) {
+                            const int64_t rest = m.D[MESH_AT(&m, s - 1, j, e0)];
+                            if (rest == ORACLE_INF) continue;
+                            const int64_t cc = (s == 1) ? 0 : cut_time(p, g, g_next, j);
+                            if (cc > cap) continue;                                     /* constraint (ii) */
+                            const int64_t t = stage_time(&v, g, tp, i, j);
+                            if (t > cap) continue;                                      /* constraint (i) */
+                            int64_t n = h1f1b_delta(cc, cap) + N[MESH_AT(&m, s - 1, j, e0)];   /* eq. dp_ni */
+                            if (n > p->M) n = p->M;
+                            if (!memory_fits(&v, g, tp, n, i, j)) continue;             /* constraint (iii) */
+                            const int64_t val = rest + t + 2 * cc;
+                            if (val < best || (val == best && (bj < 0 || j < bj || (j == bj && q < bq)))) {
+                                best = val; bj = j; bq = q; bn = (int32_t)n;
+                            }
+                        }
+                        m.D[MESH_AT(&m, s, i, e)] = best;
+                        m.arg_j[MESH_AT(&m, s, i, e)] = bj;
+                        m.arg_k[MESH_AT(&m, s, i, e)] = bq;
+                        N[MESH_AT(&m, s, i, e)] = bn;
+                    }
+                }
+            }
+        }
+        const int64_t sum = m.D[MESH_AT(&m, S, 0, Dtot)];
+        if (sum == ORACLE_INF) continue;
+        int i = 0;
+        int64_t e = Dtot, worst = 0;
+        for (int slot = 0; slot < S; ++slot) {
+            const int s = S - slot;
+            const int j = m.arg_j[MESH_AT(&m, s, i, e)], q = m.arg_k[MESH_AT(&m, s, i, e)];
+            const int tp = p->tp_degrees[q];
+            const int64_t d0 = Dtot - e;
+            int k = 0;
+            while (m.O[k + 1] <= d0) ++k;
+            sp[slot] = i;
+            sg[slot] = og[k];
+            st[slot] = tp;
+            wu[slot] = N[MESH_AT(&m, s, i, e)];
+            i = j;
+            e -= tp;
+        }
+        sp[S] = L;
+        if (i != L || e != 0) abort();
+        if (!candidate_valid(p, S, S_max, sg, st)) abort();
+        for (int slot = 0; slot < S; ++slot) {
+            const int64_t cc = (slot == S - 1) ? 0 : cut_time(p, sg[slot], sg[slot + 1], sp[slot + 1]);
+            worst = max64(worst, max64(stage_time(&v, sg[slot], st[slot], sp[slot], sp[slot + 1]), cc));
+        }
+        slot_devices(p, S, S_max, sg, st, df);
+        bottleneck[c] = worst;
+        iter_time[c] = sum + (int64_t)(p->M - 1) * cap;
+        status[c] = CAND_OK;
+    }
+    free(m.D); free(m.arg_j); free(m.arg_k); free(N); free(m.O); free(seen);
+    return ORACLE_OK;
+}

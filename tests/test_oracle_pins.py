@@ -698,6 +698,76 @@ def test_mesh_exact_against_exhaustive_enumeration_and_its_twin():
     assert n > 500 and better > 50
 
 
+def test_mesh_h1f1b_against_its_twin_enumeration_and_special_cases():
+    n = below = 0
+    for seed in range(260):
+        w = W.random_small(seed, L_max=8, S_cap=4)
+        p = w.problem
+        if int(p.group_ndev.sum()) > 8:
+            continue
+        tables = oracle.build_tables(p)
+        orders = W.make_orderings(p, seed, 5, 1, 5, 0, 6)
+        mm = oracle.plan_mesh_batch(tables, orders)
+        for num, den in ((1, 1), (5, 4), (3, 1)):
+            caps = np.where(mm.status == oracle.OK, mm.bottleneck // den * num, 7).astype(np.int64)
+            out = oracle.plan_mesh_h1f1b_batch(tables, orders, caps)
+            for c in range(orders.C):
+                S, groups, cap = int(orders.ord_S[c]), orders.ord_group[c, :orders.ord_G[c]], int(caps[c])
+                st, cuts, slots, counts, total = brute.plan_mesh_h1f1b(p, S, orders.S_max, groups, cap)
+                assert st == out.status[c], (seed, c)
+                if st != oracle.OK:
+                    assert (out.warmup[c] == -1).all() and out.iter_time[c] == oracle.INF
+                    continue
+                n += 1
+                got_slots = [(int(g), int(t)) for g, t in zip(out.stage_group[c, :S], out.stage_tp[c, :S])]
+                assert list(out.splits[c, :S + 1]) == cuts and got_slots == slots, (seed, c)
+                assert list(out.warmup[c, :S]) == counts and out.iter_time[c] == total + (p.M - 1) * cap
+                # the counts and the sum are eq. Ni and the cost model of the reported plan
+                grp, tp = [g for g, _ in slots], [d for _, d in slots]
+                assert brute.h1f1b_evaluate(p, S, grp, tp, cuts, cap) == (counts, total)
+                assert got_slots in list(brute.slicings(p, groups, S))
+                # never better than the best of ALL slicings and partitions feasible under H-1F1B
+                lower = min(brute.h1f1b_best_sum(p, S, [g for g, _ in sl], [d for _, d in sl], cap)
+                            for sl in brute.slicings(p, groups, S))
+                assert lower <= total
+                below += lower < total
+    assert n > 1500
+    print("full recurrence above the exhaustive optimum in %d of %d cases" % (below, n))
+    # single-device groups leave no choice of slicing: the same recurrence as the candidate form
+    for seed in range(30):
+        rng = np.random.default_rng(seed)
+        G, L = int(rng.integers(2, 5)), int(rng.integers(6, 14))
+        bw = rng.integers(1, 50, size=(G, G))
+        p = simple_problem(rng.integers(1, 100, size=L), M=int(rng.integers(1, 9)), G=G, ndev=(1,) * G,
+                           act=rng.integers(0, 400, size=L), bw=np.minimum(bw, bw.T),
+                           params=rng.integers(0, 50, size=L), stash=rng.integers(0, 20, size=L),
+                           mem=[int(rng.integers(150, 600))])
+        order = [int(x) for x in rng.permutation(G)]
+        tables = oracle.build_tables(p)
+        cap = int(plan(p, cands_from_lists([[(g, 1) for g in order]])).bottleneck[0])
+        if cap == oracle.INF:
+            continue
+        for k in (cap, cap * 2):
+            mesh = oracle.plan_mesh_h1f1b_batch(tables, W.orderings_from_lists([(G, order)]), [k])
+            hot = oracle.plan_h1f1b_batch(tables, cands_from_lists([[(g, 1) for g in order]]), [k])
+            for name in ("status", "splits", "dev_first", "warmup", "bottleneck", "iter_time"):
+                assert (getattr(mesh, name) == getattr(hot, name)).all(), (seed, name)
+    # without memory pressure the count plays no part: the capped least sum over slicings
+    for seed in range(80):
+        w = W.random_small(seed, L_max=8, S_cap=4)
+        p = w.problem
+        if int(p.group_ndev.sum()) > 8:
+            continue
+        p.type_mem_bytes[:] = BIG
+        tables = oracle.build_tables(p)
+        orders = W.make_orderings(p, seed, 5, 1, 5, 0, 6)
+        ex = oracle.plan_mesh_batch(tables, orders, exact=True)
+        caps = np.where(ex.status == oracle.OK, ex.bottleneck, 0)
+        out = oracle.plan_mesh_h1f1b_batch(tables, orders, caps)
+        ok = ex.status == oracle.OK
+        assert (out.status == ex.status).all() and (out.iter_time[ok] == ex.iter_time[ok]).all()
+
+
 def test_mesh_with_forced_slicing_is_the_hot_path():
     # single-device groups leave the recurrence no choice: same plans as the candidates (g, 1)
     for seed in range(40):
