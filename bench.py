@@ -272,6 +272,15 @@ def mesh_search(ctx, binding, torch, workloads, name, n_orders, reps, cpu_orders
            % (name, p.L, int(p.group_ndev.sum()), p.G, do.C, do.S_max), "ms_per_call": ms,
            "orderings_per_s": do.C / (ms * 1e-3), "dense_transitions_per_s": dense / (ms * 1e-3),
            "feasible_fraction": float(ok.mean()), "workspace_bytes": int(ws.numel())}
+    # the full recurrence (device index and H-1F1B count) under caps one eighth above the min-max bottleneck
+    caps_host = np.where(ok, got.bottleneck // 8 * 9, -1).astype(np.int64)
+    caps = torch.from_numpy(caps_host).to(ctx.device)
+    out_h = binding.DevicePlans(ctx, do.C, do.S_max)
+    wu = torch.empty_like(sg)
+    ms_h = timed_ms(torch, lambda: binding.harp_plan_mesh_h1f1b_batch(ctx, tables, do, caps, out_h, sg, st, wu, ws), reps)
+    res["h1f1b_ms_per_call"] = ms_h
+    res["h1f1b_feasible_fraction"] = float((out_h.to_host().status == 0).mean())
+    timed_ms(torch, lambda: binding.harp_plan_mesh_batch(ctx, tables, do, out, sg, st, ws), 1)   # restore sg, st
     if cpu_orders:
         import oracle
         from concurrent.futures import ThreadPoolExecutor

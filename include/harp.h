@@ -244,6 +244,19 @@ int harp_plan_mesh_exact_batch(harp_ctx *ctx, harp_tables *tables, const harp_or
                                int32_t *n_passes, void *workspace, size_t workspace_bytes,
                                void *hip_stream);
 
+/* The paper's recurrence in full for one cap per ordering (section 5.2.3): eq. dp_general with its
+ * device index and the H-1F1B warm-up count of eq. dp_ni in the state, suffix direction, the memory
+ * constraint eq. mem_cons with that count; delta, the cap on counts and the tie rule as for
+ * harp_plan_h1f1b_batch (ties: lowest end cut, then smallest degree); device model as for
+ * harp_plan_mesh_batch.  t_max: DEVICE [C].  Outputs: out as for harp_plan_mesh_batch with
+ * bottleneck = the plan's own largest time and iter_time = least sum + (M - 1) t_max[c];
+ * stage_group, stage_tp, warmup: DEVICE [C][S_max].  With single-device groups this is
+ * harp_plan_h1f1b_batch on the one slicing there is.  Workspace as for harp_plan_mesh_batch. */
+int harp_plan_mesh_h1f1b_batch(harp_ctx *ctx, harp_tables *tables, const harp_orderings *orders,
+                               const int64_t *t_max, const harp_plans *out, int32_t *stage_group,
+                               int32_t *stage_tp, int32_t *warmup, void *workspace,
+                               size_t workspace_bytes, void *hip_stream);
+
 /* The capped recurrence under the H-1F1B scheduler (sections 4.1 and 5.2.3): for candidate c and
  * the cap t_max[c] on every stage and transfer time (constraints (i), (ii)), the suffix recurrence
  * of eq. dp_general with the warm-up launch count carried in the state (eq. dp_ni) and used by the

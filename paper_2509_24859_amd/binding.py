@@ -26,7 +26,7 @@ EXPORTS = (
     "harp_tables_pp", "harp_tables_ps", "harp_tables_pr", "harp_tables_release",
     "harp_set_plan_path", "harp_plan_workspace_bytes", "harp_plan_batch", "harp_plan_exact_batch",
     "harp_plan_h1f1b_batch", "harp_score_h1f1b",
-    "harp_plan_mesh_workspace_bytes", "harp_plan_mesh_batch", "harp_plan_mesh_exact_batch",
+    "harp_plan_mesh_workspace_bytes", "harp_plan_mesh_batch", "harp_plan_mesh_exact_batch", "harp_plan_mesh_h1f1b_batch",
     "harp_score_1f1b", "harp_argmin_batch", "harp_measure_valu_int32",
 )
 
@@ -104,6 +104,8 @@ def load_library() -> C.CDLL:
     lib.harp_plan_mesh_batch.argtypes = [vp, vp, C.POINTER(harp_orderings), C.POINTER(harp_plans), vp, vp, vp, sz, vp]
     lib.harp_plan_mesh_exact_batch.argtypes = [vp, vp, C.POINTER(harp_orderings), C.POINTER(harp_plans), vp, vp, vp,
                                                vp, sz, vp]
+    lib.harp_plan_mesh_h1f1b_batch.argtypes = [vp, vp, C.POINTER(harp_orderings), vp, C.POINTER(harp_plans), vp, vp,
+                                               vp, vp, sz, vp]
     lib.harp_score_1f1b.argtypes = [vp, vp, C.POINTER(harp_candidates), vp, vp, vp, vp, vp]
     lib.harp_argmin_batch.argtypes = [vp, i32, vp, vp, vp, vp, vp]
     lib.harp_measure_valu_int32.argtypes = [vp, i32, i32, vp, vp]
@@ -392,6 +394,40 @@ def harp_plan_mesh_exact_batch(ctx: Context, tables: Tables, do: DeviceOrderings
                                                  stage_group.data_ptr(), stage_tp.data_ptr(),
                                                  n_passes.data_ptr() if n_passes is not None else None,
                                                  workspace.data_ptr(), workspace.numel(), _stream_handle(stream)))
+
+
+def harp_plan_mesh_h1f1b_batch(ctx: Context, tables: Tables, do: DeviceOrderings, t_max, out: DevicePlans,
+                               stage_group, stage_tp, warmup, workspace, stream=None):
+    ctx.check(ctx.lib.harp_plan_mesh_h1f1b_batch(ctx.handle, tables.handle, C.byref(do.c), t_max.data_ptr(),
+                                                 C.byref(out.c), stage_group.data_ptr(), stage_tp.data_ptr(),
+                                                 warmup.data_ptr(), workspace.data_ptr(), workspace.numel(),
+                                                 _stream_handle(stream)))
+
+
+def plan_mesh_h1f1b(ctx: Context, problem, orders, t_max, path: int = PATH_AUTO):
+    """Convenience for tests: the full recurrence for one cap per ordering; host copies of the plans
+    with `.stage_group`, `.stage_tp`, `.warmup`."""
+    torch = _torch()
+    tables = Tables(ctx, problem)
+    do = DeviceOrderings(ctx, orders)
+    out = DevicePlans(ctx, do.C, do.S_max)
+    out.poison()
+    sg = torch.full((max(do.C, 1), do.S_max), -7, dtype=torch.int32, device=ctx.device)
+    st = torch.full((max(do.C, 1), do.S_max), -7, dtype=torch.int32, device=ctx.device)
+    wu = torch.full((max(do.C, 1), do.S_max), -7, dtype=torch.int32, device=ctx.device)
+    caps = _dev(np.asarray(t_max, dtype=np.int64).reshape(-1), np.int64, ctx.device)
+    ws = mesh_workspace(ctx, tables, do)
+    ctx.set_plan_path(path)
+    try:
+        harp_plan_mesh_h1f1b_batch(ctx, tables, do, caps, out, sg, st, wu, ws)
+        torch.cuda.synchronize()
+    finally:
+        ctx.set_plan_path(PATH_AUTO)
+    got = out.to_host()
+    got.stage_group = sg[:do.C].cpu().numpy()
+    got.stage_tp = st[:do.C].cpu().numpy()
+    got.warmup = wu[:do.C].cpu().numpy()
+    return got, tables
 
 
 def mesh_workspace(ctx: Context, tables: Tables, do: DeviceOrderings):

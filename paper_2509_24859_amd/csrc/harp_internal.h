@@ -103,6 +103,9 @@ constexpr int kMaxOrderGroups = 1024;   // groups one ordering may list (their o
 void launch_plan_mesh(const TablesDev &tb, const OrdDev &od, const PlansDev &out, int32_t *stage_group,
                       int32_t *stage_tp, int32_t *n_passes, bool exact, bool fast32, void *ws, int n_groups,
                       int64_t total_devices, hipStream_t st);
+void launch_plan_mesh_h1f1b(const TablesDev &tb, const OrdDev &od, const int64_t *t_max, const PlansDev &out,
+                            int32_t *stage_group, int32_t *stage_tp, int32_t *warmup, bool fast32, void *ws,
+                            int n_groups, int64_t total_devices, hipStream_t st);
 size_t plan_mesh_ws_per_group(int L, int S_max, int64_t total_devices);
 int plan_mesh_threads(int L, int64_t total_devices);
 size_t plan_fast_ws_bytes(int L, int S_max, int C, int n_groups);

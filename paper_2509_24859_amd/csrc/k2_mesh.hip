@@ -31,6 +31,7 @@ constexpr int kMeshMaxThreads = 1024;   // workgroup size is chosen per launch: 
 
 struct MeshSlice {
     int64_t *D0, *D1;    // [devices + 1][L + 1]
+    int32_t *N0, *N1;    // [devices + 1][L + 1]: warm-up counts (H-1F1B form only)
     uint32_t *arg;       // [S_max][devices + 1][L + 1]: j | degree index << 16
 };
 
@@ -40,7 +41,9 @@ __device__ __forceinline__ MeshSlice mesh_slice(unsigned char *ws, size_t per_gr
     MeshSlice m;
     m.D0 = reinterpret_cast<int64_t *>(mine);
     m.D1 = m.D0 + row;
-    m.arg = reinterpret_cast<uint32_t *>(m.D1 + row);
+    m.N0 = reinterpret_cast<int32_t *>(m.D1 + row);
+    m.N1 = m.N0 + row;
+    m.arg = reinterpret_cast<uint32_t *>(m.N1 + row);
     return m;
 }
 
@@ -309,6 +312,225 @@ __global__ __launch_bounds__(kMeshMaxThreads) void k2_mesh(TablesDev tb, OrdDev 
     mesh_body<kExact, kFast>(tb, od, out, stage_group, stage_tp, n_passes, ws, per_group, n_dev, ticket);
 }
 
+// c <= cap, so the quotient of eq. dp_ni is 0, 1 or 2 and needs no division.
+__device__ __forceinline__ int mesh_delta(int64_t c, int64_t cap) {
+    const int64_t x = 2 * c - (cap >> 6);
+    return 1 + (x > 0 ? 1 : 0) + (x > cap ? 1 : 0);
+}
+
+// The paper's recurrence in full for one cap (section 5.2.3: eq. dp_general with its device index and
+// the H-1F1B warm-up count of eq. dp_ni in the state), suffix direction.  State (s, i, e): the last s
+// stages hold the operators from i on and use the last e devices; it keeps the least sum of (t + 2c)
+// under the cap and the count of its first stage as determined by the continuation that attained
+// it.  One lane per target cell (i, e); per degree an upward scan of the end cuts j, which stops at
+// the cap (the stage time grows with j) or when the stage no longer fits even with a count of one.
+// Ties: lowest end cut, then smallest degree.  Returns the value of (S, 0, all devices).
+template <bool kFast>
+__device__ __forceinline__ int64_t mesh_h1_pass(const TablesDev &tb, const MeshSlice &m, const int32_t *offs,
+                                                const uint16_t *order, const uint16_t *group_at, int K, int S,
+                                                int64_t n_dev, int64_t cap) {
+    const int L = tb.L, W = L + 1, tid = threadIdx.x, nthreads = blockDim.x;
+    const int Dtot = offs[K];
+    const int64_t *PP = tb.PP(), *PS = tb.PS();
+    int64_t *Gp = m.D0, *Gn = m.D1;
+    int32_t *Np = m.N0, *Nn = m.N1;
+    __syncthreads();
+    for (int x = tid; x < (Dtot + 1) * W; x += nthreads) { Gp[x] = kInf; Np[x] = 0; }
+    __syncthreads();
+    if (tid == 0) Gp[L] = 0;                         // no stages left: no operators, no devices (e = 0, i = L)
+    for (int s = 1; s <= S; ++s) {
+        __syncthreads();                             // row s - 1 is complete
+        const bool whole = (s == S);
+        const int i_lo = whole ? 0 : S - s, i_hi = whole ? 0 : L - s;
+        const int e_lo = whole ? Dtot : s, e_hi = whole ? Dtot : Dtot - (S - s);
+        const int j_hi = L - (s - 1);
+        const int n_i = i_hi - i_lo + 1, n_e = e_hi - e_lo + 1;
+        uint32_t *arg_s = m.arg + size_t(s - 1) * size_t(n_dev + 1) * W;
+        for (int x = tid; x < n_i * n_e; x += nthreads) {
+            const int i = i_lo + x % n_i, e = e_lo + x / n_i;
+            const int d0 = Dtot - e;                 // first device of the stage this step places
+            int k = 0;
+            if (Dtot <= kMeshGroupTable) k = group_at[d0];
+            else while (offs[k + 1] <= d0) ++k;
+            const int g = order[k];
+            const int t = tb.group_type[g];
+            const int64_t *pf = tb.PF(t);
+            const int64_t mem_dev = tb.type_mem[t];
+            const int64_t pfi = kFast ? 0 : pf[i], ppi = PP[i], psi = PS[i];
+            int64_t best = kInf;
+            int best_j = 0x7FFFFFFF, best_q = 0, best_n = 0;
+            for (int q = 0; q < tb.n_tp; ++q) {
+                const int64_t tp = tb.tp[q];
+                const int e0 = e - int(tp);
+                // the stage stays inside group k; the stages behind it have used at least one device
+                // each (row s - 1 holds nothing else), and none at all exactly when there are none
+                if (d0 + int(tp) > offs[k + 1] || e0 < s - 1 || (s == 1) != (e0 == 0)) continue;
+                const int g_next = (s == 1) ? g : (d0 + int(tp) == offs[k + 1] ? order[k + 1 < K ? k + 1 : k] : g);
+                const int shift = tb.tp_shift[q];
+                const int64_t *pr = tb.PR(g, q);
+                const uint32_t *p32 = kFast ? tb.P32 + (int64_t(g) * tb.n_tp + q) * tb.pitch32 : nullptr;
+                const uint32_t *cm = kFast ? tb.CM + (int64_t(g) * tb.G + g_next) * tb.pitch32 : nullptr;
+                const int64_t link = tb.bw[int64_t(g) * tb.G + g_next];
+                const int64_t pri = kFast ? 0 : pr[i];
+                const uint32_t base32 = kFast ? p32[i] : 0u;
+                const int64_t capm = tp * mem_dev;
+                const int64_t *rowG = Gp + size_t(e0) * W;
+                const int32_t *rowN = Np + size_t(e0) * W;
+                for (int j = i + 1; j <= j_hi; ++j) {
+                    int64_t time;
+                    if (kFast) {
+                        time = int64_t((p32[j] + uint32_t(tp) - 1u - base32) >> shift);
+                    } else {
+                        const int64_t work = pf[j] - pfi;
+                        time = (shift >= 0 ? (work + tp - 1) >> shift : (work + tp - 1) / tp) + (pr[j] - pri);
+                    }
+                    if (time > cap) break;                                   // constraint (i); grows with j
+                    const int64_t dpp = PP[j] - ppi, dps = PS[j] - psi;
+                    if (dpp + dps > capm) break;                             // no count fits from here on
+                    const int64_t rest = rowG[j];
+                    if (rest == kInf) continue;
+                    int64_t cut = 0;
+                    if (s > 1) cut = kFast ? int64_t(cm[j]) : (tb.act_bytes[j - 1] + link - 1) / link;
+                    if (cut > cap) continue;                                 // constraint (ii)
+                    int64_t n = mesh_delta(cut, cap) + rowN[j];              // eq. dp_ni
+                    n = n < tb.M ? n : tb.M;
+                    if (dpp + n * dps > capm) continue;                      // constraint (iii), eq. mem_cons
+                    const int64_t val = rest + time + 2 * cut;
+                    if (val < best || (val == best && j < best_j)) { best = val; best_j = j; best_q = q; best_n = int(n); }
+                }
+            }
+            Gn[size_t(e) * W + i] = best;
+            Nn[size_t(e) * W + i] = best_n;
+            arg_s[size_t(e) * W + i] = uint32_t(best_j & 0xFFFF) | (uint32_t(best_q) << 16);
+        }
+        int64_t *tg = Gp; Gp = Gn; Gn = tg;
+        int32_t *tn = Np; Np = Nn; Nn = tn;
+    }
+    __syncthreads();
+    return Gp[size_t(Dtot) * W];
+}
+
+template <bool kFast>
+__device__ __forceinline__ void mesh_h1_body(const TablesDev &tb, const OrdDev &od, const int64_t *t_max,
+                                             const PlansDev &out, int32_t *stage_group, int32_t *stage_tp,
+                                             int32_t *warmup, unsigned char *ws, size_t per_group, int64_t n_dev,
+                                             int *ticket) {
+    __shared__ int32_t offs[kMaxOrderGroups + 1];
+    __shared__ uint16_t order[kMaxOrderGroups];
+    __shared__ uint16_t group_at[kMeshGroupTable];
+    __shared__ int32_t cuts[kMaxStages + 1], count[kMaxStages];
+    __shared__ uint16_t slot_g[kMaxStages];
+    __shared__ uint8_t slot_k[kMaxStages];
+    __shared__ int32_t slot_first[kMaxStages];
+    __shared__ int shared_int[2];
+    const int L = tb.L, S_max = od.S_max, W = L + 1;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nthreads = blockDim.x;
+    const MeshSlice m = mesh_slice(ws, per_group, L, n_dev);
+    const int64_t m_cap = tb.M;
+
+    for (;;) {
+        __syncthreads();
+        if (tid == 0) shared_int[0] = atomicAdd(ticket, 1);
+        __syncthreads();
+        const int c = shared_int[0];
+        if (c >= od.C) break;
+        const int S = od.ord_S[c], K = od.ord_G[c];
+        const int64_t cap = t_max[c];
+        const int32_t *og = od.ord_group + int64_t(c) * od.G_max;
+        int32_t *sg = stage_group + int64_t(c) * S_max, *stp = stage_tp + int64_t(c) * S_max;
+        int32_t *wu = warmup + int64_t(c) * S_max;
+        auto fail = [&](int status) {
+            write_failed(out, c, S_max, status);
+            for (int s = tid; s < S_max; s += nthreads) { sg[s] = -1; stp[s] = -1; wu[s] = -1; }
+        };
+        int bad = (S < 1 || S > S_max || K < 1 || K > od.G_max) ? 1 : 0;
+        if (!bad)
+            for (int k = tid; k < K; k += nthreads) {
+                const int g = og[k];
+                if (g < 0 || g >= tb.G) { bad = 1; continue; }
+                for (int q = 0; q < k; ++q)
+                    if (og[q] == g) bad = 1;
+                order[k] = uint16_t(g);
+            }
+        if (__syncthreads_or(bad)) { fail(HARP_CAND_INVALID); continue; }
+        if (tid == 0) {
+            int64_t o = 0;
+            offs[0] = 0;
+            for (int k = 0; k < K; ++k) { o += tb.group_ndev[order[k]]; offs[k + 1] = int32_t(o); }
+        }
+        __syncthreads();
+        const int Dtot = offs[K];
+        if (S > L || S < K || S > Dtot || cap < 0) { fail(HARP_CAND_INFEASIBLE); continue; }
+        if (Dtot <= kMeshGroupTable) {
+            for (int k = 0; k < K; ++k)
+                for (int d = offs[k] + tid; d < offs[k + 1]; d += nthreads) group_at[d] = uint16_t(k);
+        }
+        const int64_t sum = mesh_h1_pass<kFast>(tb, m, offs, order, group_at, K, S, n_dev, cap);
+        if (sum == kInf) { fail(HARP_CAND_INFEASIBLE); continue; }
+        if (tid == 0) {
+            int i = 0, e = Dtot;
+            for (int slot = 0; slot < S; ++slot) {
+                const int s = S - slot;
+                const uint32_t a = m.arg[(size_t(s - 1) * size_t(n_dev + 1) + size_t(e)) * W + i];
+                int j = int(a & 0xFFFFu);
+                const int q = int(a >> 16) & 7;
+                j = j <= L ? j : L;                     // a finite sum only chains through cuts inside the row
+                const int d0 = Dtot - e;
+                int k = 0;
+                while (k + 1 < K && offs[k + 1] <= d0) ++k;
+                cuts[slot] = i;
+                slot_g[slot] = order[k];
+                slot_k[slot] = uint8_t(q);
+                slot_first[slot] = tb.group_base[order[k]] + (d0 - offs[k]);
+                i = j;
+                e -= tb.tp[q];
+                e = e > 0 ? e : 0;
+            }
+            cuts[S] = L;
+            // counts by eq. Ni along the plan, from the last stage backwards
+            int64_t n = 0;
+            for (int slot = S - 1; slot >= 0; --slot) {
+                int64_t cut = 0;
+                if (slot < S - 1) {
+                    const int64_t link = tb.bw[int64_t(slot_g[slot]) * tb.G + slot_g[slot + 1]];
+                    cut = (tb.act_bytes[cuts[slot + 1] - 1] + link - 1) / link;
+                }
+                n += mesh_delta(cut, cap);
+                n = n < m_cap ? n : m_cap;
+                count[slot] = int32_t(n);
+            }
+        }
+        __syncthreads();
+        int32_t *sp = out.splits + int64_t(c) * (S_max + 1);
+        int32_t *df = out.dev_first + int64_t(c) * S_max;
+        for (int s = tid; s <= S_max; s += nthreads) sp[s] = s <= S ? cuts[s] : -1;
+        for (int s = tid; s < S_max; s += nthreads) {
+            sg[s] = s < S ? int32_t(slot_g[s]) : -1;
+            stp[s] = s < S ? tb.tp[slot_k[s]] : -1;
+            df[s] = s < S ? slot_first[s] : -1;
+            wu[s] = s < S ? count[s] : -1;
+        }
+        if (wave == 0) {
+            int64_t bott, iter;
+            wave_score_partition(tb, S, slot_g, slot_k, cuts, lane, bott, iter);   // the plan's own bottleneck
+            if (lane == 0) {
+                out.bottleneck[c] = bott;
+                out.iter_time[c] = sum + (m_cap - 1) * cap;
+                out.status[c] = HARP_CAND_OK;
+            }
+        }
+    }
+}
+
+template <bool kFast>
+__global__ __launch_bounds__(kMeshMaxThreads) void k2_mesh_h1f1b(TablesDev tb, OrdDev od, const int64_t *t_max,
+                                                                 PlansDev out, int32_t *stage_group,
+                                                                 int32_t *stage_tp, int32_t *warmup,
+                                                                 unsigned char *ws, size_t per_group,
+                                                                 int64_t n_dev, int *ticket) {
+    mesh_h1_body<kFast>(tb, od, t_max, out, stage_group, stage_tp, warmup, ws, per_group, n_dev, ticket);
+}
+
 __global__ void k2_mesh_clear(int *ticket) {
     if (threadIdx.x == 0) *ticket = 0;
 }
@@ -324,7 +546,7 @@ int plan_mesh_threads(int L, int64_t total_devices) {
 // Per-workgroup slice: two rows of the table, the back-pointers, and (first slice only) the ticket.
 size_t plan_mesh_ws_per_group(int L, int S_max, int64_t total_devices) {
     const size_t row = size_t(total_devices + 1) * size_t(L + 1);
-    size_t b = 2 * row * sizeof(int64_t) + size_t(S_max) * row * sizeof(uint32_t);
+    size_t b = 2 * row * sizeof(int64_t) + 2 * row * sizeof(int32_t) + size_t(S_max) * row * sizeof(uint32_t);
     return (b + 255) & ~size_t(255);
 }
 
@@ -345,6 +567,22 @@ void launch_plan_mesh(const TablesDev &tb, const OrdDev &od, const PlansDev &out
     else if (fast32) HARP_MESH_LAUNCH(false, true);
     else HARP_MESH_LAUNCH(false, false);
 #undef HARP_MESH_LAUNCH
+}
+
+void launch_plan_mesh_h1f1b(const TablesDev &tb, const OrdDev &od, const int64_t *t_max, const PlansDev &out,
+                            int32_t *stage_group, int32_t *stage_tp, int32_t *warmup, bool fast32, void *ws,
+                            int n_groups, int64_t total_devices, hipStream_t st) {
+    int *ticket = static_cast<int *>(ws);
+    unsigned char *slices = static_cast<unsigned char *>(ws) + 256;
+    const size_t per_group = plan_mesh_ws_per_group(tb.L, od.S_max, total_devices);
+    const dim3 grid(n_groups), block(plan_mesh_threads(tb.L, total_devices));
+    hipLaunchKernelGGL(k2_mesh_clear, dim3(1), dim3(64), 0, st, ticket);
+    if (fast32)
+        hipLaunchKernelGGL(HIP_KERNEL_NAME(k2_mesh_h1f1b<true>), grid, block, 0, st, tb, od, t_max, out, stage_group,
+                           stage_tp, warmup, slices, per_group, total_devices, ticket);
+    else
+        hipLaunchKernelGGL(HIP_KERNEL_NAME(k2_mesh_h1f1b<false>), grid, block, 0, st, tb, od, t_max, out,
+                           stage_group, stage_tp, warmup, slices, per_group, total_devices, ticket);
 }
 
 }  // namespace harp

@@ -116,6 +116,23 @@ def oracle_plan_mesh_threaded(tables, orders, threads=None, exact=False):
     return out
 
 
+def oracle_plan_mesh_h1f1b_threaded(tables, orders, t_max, threads=None):
+    """Oracle plans of the full recurrence (device index and H-1F1B count) for a batch of orderings."""
+    import os
+    from concurrent.futures import ThreadPoolExecutor
+
+    import oracle
+    threads = threads or min(16, len(os.sched_getaffinity(0)))
+    out = oracle.Plans(orders.C, orders.S_max)
+    out.stage_group = np.full((orders.C, orders.S_max), -1, dtype=np.int32)
+    out.stage_tp = np.full((orders.C, orders.S_max), -1, dtype=np.int32)
+    out.warmup = np.full((orders.C, orders.S_max), -1, dtype=np.int32)
+    caps = np.ascontiguousarray(t_max, dtype=np.int64)
+    with ThreadPoolExecutor(threads) as ex:
+        list(ex.map(lambda c: oracle.plan_mesh_h1f1b_batch(tables, orders, caps, c, c + 1, out), range(orders.C)))
+    return out
+
+
 def assert_plans_equal(got, want, label=""):
     """Bit-exact comparison of every output array of a batch."""
     for name in ("status", "splits", "dev_first", "bottleneck", "iter_time"):

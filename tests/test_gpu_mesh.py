@@ -6,7 +6,8 @@ import pytest
 import oracle
 from paper_2509_24859_amd import workloads as W
 
-from helpers import assert_plans_equal, cands_from_lists, oracle_plan_mesh_threaded, simple_problem
+from helpers import (assert_plans_equal, cands_from_lists, oracle_plan_mesh_h1f1b_threaded,
+                     oracle_plan_mesh_threaded, simple_problem)
 
 pytestmark = pytest.mark.gpu
 
@@ -182,3 +183,68 @@ def test_mesh_exact_small_and_workloads(harp, ctx):
         better += int((got.iter_time[ok] < mm.iter_time[ok]).sum())
         print("%s: %.1f capped tables per ordering, the sweep has %.0f caps" % (name, got.n_passes[ok].mean(), want.n_caps[ok].mean()))
     assert better > 0
+
+
+def _check_h1(harp, ctx, problem, orders, caps, label):
+    caps = np.ascontiguousarray(caps, dtype=np.int64)
+    want = oracle_plan_mesh_h1f1b_threaded(oracle.build_tables(problem), orders, caps)
+    fast32 = harp.Tables(ctx, problem).fast32
+    for path in [harp.PATH_GENERIC] + ([harp.PATH_FAST32] if fast32 else []):
+        tag = "%s (path %d)" % (label, path)
+        got, _ = harp.plan_mesh_h1f1b(ctx, problem, orders, caps, path)
+        assert_plans_equal(got, want, tag)
+        for name in ("stage_group", "stage_tp", "warmup"):
+            a, b = getattr(got, name), getattr(want, name)
+            if not (a == b).all():
+                bad = np.nonzero((a != b).any(axis=1))[0]
+                raise AssertionError("%s: %s differs at %d orderings, first %d: got %s want %s"
+                                     % (tag, name, bad.size, bad[0], a[bad[0]], b[bad[0]]))
+    return got, want
+
+
+def test_mesh_h1f1b_full_recurrence(harp, ctx):
+    """Device index and H-1F1B warm-up count in the state (the paper's recurrence in full, one cap
+    per ordering) against the oracle."""
+    feasible = 0
+    for seed in range(200):
+        w = W.random_small(seed)
+        p = w.problem
+        top = min(8, int(p.group_ndev.sum()))
+        orders = W.make_orderings(p, seed, 5, 1, max(top, p.G), 0, 8)
+        mm = oracle.plan_mesh_batch(oracle.build_tables(p), orders)
+        for num, den in ((1, 1), (5, 4), (4, 1)):
+            caps = np.where(mm.status == oracle.OK, mm.bottleneck // den * num, 7)
+            _, want = _check_h1(harp, ctx, p, orders, caps, "seed %d x%d/%d" % (seed, num, den))
+            feasible += int((want.status == oracle.OK).sum())
+    assert feasible > 1000
+    for name, n in (("tiny", 16), ("llama7b", 128), ("llama70b", 48)):
+        w = W.make(name)
+        orders = W.make_orderings(w.problem, w.seed, w.config_id, w.problem.G, w.S_max, 0, n)
+        mm, _ = harp.plan_mesh(ctx, w.problem, orders)
+        ok_any = False
+        for num, den in ((1, 1), (9, 8), (2, 1)):
+            caps = np.where(mm.status == oracle.OK, mm.bottleneck // den * num, -1)
+            got, want = _check_h1(harp, ctx, w.problem, orders, caps, "%s x%d/%d" % (name, num, den))
+            ok = want.status == oracle.OK
+            ok_any |= bool(ok.any())
+            assert (got.bottleneck[ok] <= caps[ok]).all()
+        assert ok_any
+    # single-device groups: the candidate form of the same recurrence
+    for seed in range(12):
+        rng = np.random.default_rng(seed)
+        G, L = int(rng.integers(2, 5)), int(rng.integers(6, 40))
+        bw = rng.integers(1, 50, size=(G, G))
+        p = simple_problem(rng.integers(1, 100, size=L), M=int(rng.integers(1, 9)), G=G, ndev=(1,) * G,
+                           act=rng.integers(0, 400, size=L), bw=np.minimum(bw, bw.T),
+                           params=rng.integers(0, 50, size=L), stash=rng.integers(0, 20, size=L),
+                           mem=[int(rng.integers(600, 3000))])
+        order = [int(x) for x in rng.permutation(G)]
+        cands = cands_from_lists([[(g, 1) for g in order]])
+        cap = int(oracle.plan_batch(oracle.build_tables(p), cands).bottleneck[0])
+        if cap == oracle.INF:
+            continue
+        for k in (cap, 2 * cap):
+            mesh, _ = _check_h1(harp, ctx, p, W.orderings_from_lists([(G, order)]), [k], "forced %d" % seed)
+            hot, _ = harp.plan_h1f1b(ctx, p, cands, [k])
+            for name in ("status", "splits", "dev_first", "warmup", "bottleneck", "iter_time"):
+                assert (getattr(mesh, name) == getattr(hot, name)).all(), (seed, name)
