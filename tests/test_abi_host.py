@@ -75,3 +75,20 @@ def test_product_package_does_not_import_the_oracle():
                 text = open(os.path.join(dirpath, f)).read()
                 assert "import oracle" not in text and "from oracle" not in text, f
                 assert "harp_oracle" not in text, f
+
+
+def test_header_is_plain_c99(tmp_path):
+    """The boundary is a C interface: the header must compile as strict C99 with no warnings, and a
+    C translation unit must be able to name every struct in it by value."""
+    import subprocess
+    src = tmp_path / "uses_header.c"
+    src.write_text('#include "harp.h"\n'
+                   "int main(void) {\n"
+                   "    harp_problem p; harp_candidates c; harp_plans o; harp_orderings g;\n"
+                   "    (void)p; (void)c; (void)o; (void)g;\n"
+                   "    return (int)(sizeof(p) + sizeof(c) + sizeof(o) + sizeof(g)) == 0;\n"
+                   "}\n")
+    r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic",
+                        "-I", os.path.join(ROOT, "include"), "-fsyntax-only", str(src)],
+                       capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
