@@ -65,6 +65,28 @@ def cpu_baseline(w, cands, gpu_plans, budget_candidates):
             "transitions_per_s": float(trans.sum()) / dt, "cells_per_s": float(cells.sum()) / dt}
 
 
+def device_state():
+    """Clock and power state of the first GPU as the amdgpu driver publishes it in sysfs, read
+    before the run (plain file reads: no child process is started)."""
+    import glob
+    state = {}
+    for card in sorted(glob.glob("/sys/class/drm/card[0-9]*/device")):
+        if not os.path.exists(os.path.join(card, "pp_dpm_sclk")):
+            continue
+        for name in ("pp_dpm_sclk", "pp_dpm_mclk", "power_dpm_force_performance_level"):
+            try:
+                with open(os.path.join(card, name)) as f:
+                    lines = [x.strip() for x in f.read().strip().splitlines()]
+            except OSError as e:
+                state[name] = "unreadable: %s" % e.strerror
+                continue
+            current = [x for x in lines if x.endswith("*")]
+            state[name] = {"levels": lines, "current": current[0] if current else None} if len(lines) > 1 else lines[0]
+        state["card"] = card
+        break
+    return state or {"error": "no amdgpu clock files under /sys/class/drm"}
+
+
 def tables_streaming(ctx, binding, workloads, torch, L, reps=10):
     """Table build alone on an operator-level sequence: the launch that is HBM-bound by nature but
     moves under 3 MB at the planner's own sizes.  Algorithmic bytes: every input read once, every
@@ -338,6 +360,7 @@ def main():
         raise SystemExit("bench.py measures one GPU: this build has no multi-GPU path "
                          "(candidates would shard across GPUs with one 16-byte reduction); run with --gpus 1")
 
+    state_before = device_state()
     import numpy as np
     import torch
 
@@ -346,6 +369,7 @@ def main():
     if not torch.cuda.is_available():
         raise SystemExit("bench.py needs the GPU: there is no CPU path")
     ctx = binding.Context(0)
+    props = torch.cuda.get_device_properties(0)
     w = workloads.make(args.workload)
     C = args.candidates or w.C
     cands = w.candidates(0, C)
@@ -431,6 +455,10 @@ def main():
         "other_kernels": parts,
         "feasible_fraction": float((got.status == 0).mean()),
         "best_plan": {"index": int(best_i.item()), "iter_time_us": int(best_t.item())},
+        "device": {"name": props.name, "compute_units": props.multi_processor_count,
+                   "max_clock_mhz": (getattr(props, "clock_rate", 0) or 0) / 1e3 or None,
+                   "hbm_bytes": props.total_memory,
+                   "sysfs_before_run": state_before},
         "roofline": {
             "bound": "alu", "kernel": kernel,
             "achieved": achieved / 1e12, "peak": ALU_PEAK_LANE_OPS / 1e12, "unit": "T int32 lane-op/s",
@@ -446,6 +474,9 @@ def main():
         peaks = measured_peaks(ctx, binding, torch)
         result["measured_peaks"] = peaks
         result["roofline"]["frac_of_measured_peak"] = achieved / peaks["valu_int32_lane_ops_per_s"]
+        # clock under load, read off the add/max chain: one lane-op per lane per cycle
+        result["device"]["valu_clock_under_load_ghz"] = (peaks["valu_int32_lane_ops_per_s"]
+                                                         / (props.multi_processor_count * 64) / 1e9)
     if args.tables_L:
         result["tables_streaming"] = tables_streaming(ctx, binding, workloads, torch, args.tables_L)
     if args.graph_reps and fast:

@@ -20,7 +20,10 @@
 // back-pointers sit in a per-workgroup slice of the caller's workspace, L2-resident at the sizes
 // of interest.  Values are int64; stage and transfer times come from the 32-bit rows and the cut
 // table when the tables have them, else from the int64 rows (any degrees, any time width).
+#include <type_traits>
+
 #include "harp_internal.h"
+#include "fast_common.h"
 #include "plan_common.h"
 
 namespace harp {
@@ -53,9 +56,9 @@ __device__ __forceinline__ MeshSlice mesh_slice(unsigned char *ws, size_t per_gr
 // devices); back-pointers are left in the slice.
 constexpr int kMeshGroupTable = 2048;   // device offsets whose group index is kept in LDS
 
-// kFast: stage times from the fused 32-bit rows and transfer times from the cut table (tables that
-// allow the 32-bit path); otherwise from the int64 rows, with a division per transfer time.
-template <bool kCapped, bool kFast>
+// This form works from the int64 rows (any degrees, any time width), with a division per transfer
+// time; mesh_pass_fast below is the form for tables that have the 32-bit rows.
+template <bool kCapped>
 __device__ __forceinline__ int64_t mesh_pass(const TablesDev &tb, const MeshSlice &m, const int32_t *offs,
                                              const uint16_t *order, const uint16_t *group_at, int K, int S,
                                              int64_t n_dev, int64_t cap) {
@@ -91,14 +94,10 @@ __device__ __forceinline__ int64_t mesh_pass(const TablesDev &tb, const MeshSlic
             const int g_next = last ? g : (d2 == offs[k + 1] ? order[k + 1 < K ? k + 1 : k] : g);
             int64_t cut = 0;
             if (!last) {
-                if (kFast) {
-                    cut = tb.CM[(int64_t(g) * tb.G + g_next) * tb.pitch32 + i];
-                } else {
-                    const int64_t link = tb.bw[int64_t(g) * tb.G + g_next];
-                    cut = (tb.act_bytes[i - 1] + link - 1) / link;
-                }
+                const int64_t link = tb.bw[int64_t(g) * tb.G + g_next];
+                cut = (tb.act_bytes[i - 1] + link - 1) / link;
             }
-            const int64_t pfi = kFast ? 0 : pf[i], ppi = PP[i], psi = PS[i];
+            const int64_t pfi = pf[i], ppi = PP[i], psi = PS[i];
             if (!kCapped || cut <= cap) {
                 for (int q = 0; q < tb.n_tp; ++q) {
                     const int64_t tp = tb.tp[q];
@@ -108,19 +107,12 @@ __device__ __forceinline__ int64_t mesh_pass(const TablesDev &tb, const MeshSlic
                     if (d < offs[k] || d < s) continue;
                     const int shift = tb.tp_shift[q];
                     const int64_t *pr = tb.PR(g, q);
-                    const uint32_t *p32 = kFast ? tb.P32 + (int64_t(g) * tb.n_tp + q) * tb.pitch32 : nullptr;
-                    const int64_t pri = kFast ? 0 : pr[i];
-                    const uint32_t xi = kFast ? p32[i] + uint32_t(tp) - 1u : 0u;
+                    const int64_t pri = pr[i];
                     const int64_t capm = tp * mem_dev;
                     const int64_t *row = Dp + size_t(d) * W;
                     for (int j = i - 1; j >= s; --j) {
-                        int64_t time;
-                        if (kFast) {
-                            time = int64_t((xi - p32[j]) >> shift);
-                        } else {
-                            const int64_t work = pfi - pf[j];
-                            time = (shift >= 0 ? (work + tp - 1) >> shift : (work + tp - 1) / tp) + (pri - pr[j]);
-                        }
+                        const int64_t work = pfi - pf[j];
+                        const int64_t time = (shift >= 0 ? (work + tp - 1) >> shift : (work + tp - 1) / tp) + (pri - pr[j]);
                         // the stage time never decreases as j moves down: beyond the cap, or beyond the
                         // best value of the min-max form, no lower j can be taken or can match
                         if (time > (kCapped ? cap : best)) break;
@@ -145,6 +137,123 @@ __device__ __forceinline__ int64_t mesh_pass(const TablesDev &tb, const MeshSlic
     }
     __syncthreads();
     return Dp[size_t(Dtot) * W + L];
+}
+
+// The same pass on the 32-bit rows, for tables that allow them (every degree a power of two, every
+// time below 2^31 us) and L <= kMeshFastMaxL.  What changes is the cost of a transition, not the result:
+//  * the memory test of eq. mem_cons becomes one comparison: with Q[j] = PP[j] + N_s PS[j], kept in
+//    LDS for the stage, the stage [j, i) fits iff Q[j] >= Q[i] - tp * mem;
+//  * the min-max values are times, so the live rows are uint32 (the least sums of the capped form
+//    stay int64);
+//  * the best (value, previous cut, degree index) is one 64-bit key and the tie rule (lowest cut,
+//    then smallest degree) is an unsigned minimum: min-max key = value << 32 | j << 3 | q, capped
+//    key = sum << 19 | j << 3 | q (a sum of at most 256 stage and transfer times stays below 2^42);
+//  * four previous cuts per trip, all evaluated under predicates; entries below a stop cannot
+//    update (their time exceeds the best value or the cap, or they do not fit), so only the last
+//    entry of a trip decides whether the lane goes on.
+constexpr int kMeshFastMaxL = 4096;
+
+template <bool kCapped>
+__device__ __forceinline__ int64_t mesh_pass_fast(const TablesDev &tb, const MeshSlice &m, const int32_t *offs,
+                                                  const uint16_t *order, const uint16_t *group_at, int64_t *Q,
+                                                  int K, int S, int64_t n_dev, int64_t cap) {
+    using ValT = typename std::conditional<kCapped, int64_t, uint32_t>::type;
+    constexpr uint64_t kNoKey = ~0ull;
+    const int L = tb.L, W = L + 1, tid = threadIdx.x, nthreads = blockDim.x;
+    const int Dtot = offs[K];
+    const int64_t *PP = tb.PP(), *PS = tb.PS();
+    ValT *Dp = reinterpret_cast<ValT *>(m.D0), *Dn = reinterpret_cast<ValT *>(m.D1);
+    const ValT none = kCapped ? ValT(kInf) : ValT(fastdp::kInf32);
+    if (kCapped && cap < 0) return kInf;             // no transition has a negative time (uniform exit)
+    const uint32_t cap32 = cap > 0xFFFFFFFEll ? 0xFFFFFFFEu : uint32_t(cap);
+    __syncthreads();                                 // the previous pass is done with the rows
+    for (int x = tid; x < (Dtot + 1) * W; x += nthreads) Dp[x] = none;
+    __syncthreads();
+    if (tid == 0) Dp[0] = 0;                         // no stage, no operator, no device
+    for (int s = 0; s < S; ++s) {
+        __syncthreads();                             // row s is complete, the previous stage is done with Q
+        const bool last = (s == S - 1);
+        const int64_t n_inflight = (S - s) < tb.M ? (S - s) : tb.M;
+        for (int j = tid; j <= L; j += nthreads) Q[j] = PP[j] + n_inflight * PS[j];
+        __syncthreads();
+        const int i_lo = last ? L : s + 1, i_hi = L - (S - 1 - s);
+        const int d_lo = last ? Dtot : s + 1, d_hi = last ? Dtot : Dtot - (S - 1 - s);
+        const int n_i = i_hi - i_lo + 1, n_d = d_hi - d_lo + 1;
+        uint32_t *arg_s = m.arg + size_t(s) * size_t(n_dev + 1) * W;
+        for (int x = tid; x < n_i * n_d; x += nthreads) {
+            const int i = i_lo + x % n_i, d2 = d_lo + x / n_i;
+            int k = 0;
+            if (Dtot <= kMeshGroupTable) k = group_at[d2 - 1];     // the group of the stage's last device
+            else while (offs[k + 1] < d2) ++k;                     // offs[k] < d2 <= offs[k + 1]
+            const int g = order[k];
+            const int64_t mem_dev = tb.type_mem[tb.group_type[g]];
+            const int g_next = last ? g : (d2 == offs[k + 1] ? order[k + 1 < K ? k + 1 : k] : g);
+            const uint32_t cut = last ? 0u : tb.CM[(int64_t(g) * tb.G + g_next) * tb.pitch32 + i];
+            const int64_t qi = Q[i];
+            uint64_t best = kNoKey;
+            if (!kCapped || cut <= cap32) {
+                for (int q = 0; q < tb.n_tp; ++q) {
+                    const int tp = tb.tp[q];
+                    const int d = d2 - tp;
+                    // the stage must stay inside group k, and s stages have used at least s devices
+                    // (row s holds nothing else: entries outside the ranges written for it are stale)
+                    if (d < offs[k] || d < s) continue;
+                    const int shift = tb.tp_shift[q];
+                    const uint32_t *p32 = tb.P32 + (int64_t(g) * tb.n_tp + q) * tb.pitch32;
+                    const uint32_t xi = p32[i] + uint32_t(tp) - 1u;
+                    const int64_t th = qi - int64_t(tp) * mem_dev;
+                    const ValT *row = Dp + size_t(d) * W;
+                    int j = i - 1;
+                    bool more = true;                 // i > s always
+                    while (more) {
+                        const int j1 = (j - 1) > s ? (j - 1) : s, j2 = (j - 2) > s ? (j - 2) : s,
+                                  j3 = (j - 3) > s ? (j - 3) : s;
+                        const uint32_t p0 = p32[j], p1 = p32[j1], p2 = p32[j2], p3 = p32[j3];
+                        const ValT r0 = row[j], r1 = row[j1], r2 = row[j2], r3 = row[j3];
+                        const int64_t q0 = Q[j], q1 = Q[j1], q2 = Q[j2], q3 = Q[j3];
+                        uint32_t tj;
+#define HARP_MESH_STEP(P, R, QV, JJ)                                                              \
+    {                                                                                             \
+        tj = (xi - (P)) >> shift;                                                                 \
+        uint64_t key;                                                                             \
+        bool ok = (QV) >= th;                                                                     \
+        if (kCapped) {                                                                            \
+            ok = ok & ((R) != none) & (tj <= cap32);                                              \
+            key = ((uint64_t(R) + uint64_t(tj) + 2ull * cut) << 19) |                             \
+                  uint64_t((uint32_t(JJ) << 3) | uint32_t(q));                                    \
+        } else {                                                                                  \
+            key = (uint64_t(fastdp::umax3(uint32_t(R), tj, cut)) << 32) |                         \
+                  uint64_t((uint32_t(JJ) << 3) | uint32_t(q));                                    \
+        }                                                                                         \
+        best = (ok & (key < best)) ? key : best;                                                  \
+    }
+                        HARP_MESH_STEP(p0, r0, q0, j)
+                        HARP_MESH_STEP(p1, r1, q1, j1)
+                        HARP_MESH_STEP(p2, r2, q2, j2)
+                        HARP_MESH_STEP(p3, r3, q3, j3)
+#undef HARP_MESH_STEP
+                        more = ((j - 3) > s) & (q3 >= th) & (tj <= (kCapped ? cap32 : uint32_t(best >> 32)));
+                        j -= 4;
+                    }
+                }
+            }
+            ValT value;
+            uint32_t jq;
+            if (kCapped) {
+                value = best == kNoKey ? none : ValT(best >> 19);
+                jq = uint32_t(best) & 0x7FFFFu;
+            } else {
+                value = ValT(best >> 32);             // an unreached cell keeps all ones
+                jq = uint32_t(best) & 0x7FFFFu;
+            }
+            Dn[size_t(d2) * W + i] = value;
+            arg_s[size_t(d2) * W + i] = (jq >> 3) | ((jq & 7u) << 16);
+        }
+        ValT *tmp = Dp; Dp = Dn; Dn = tmp;
+    }
+    __syncthreads();
+    const ValT v = Dp[size_t(Dtot) * W + L];
+    return v == none ? kInf : int64_t(v);
 }
 
 // Thread 0: follows the back-pointers from (S, L, all devices).
@@ -207,6 +316,14 @@ __device__ __forceinline__ void mesh_body(const TablesDev &tb, const OrdDev &od,
         bott = scored[0];
         total = scored[1];
     };
+    // one pass over the stages, in the form the launch chose (the fast form keeps a row of memory sums in LDS)
+    extern __shared__ __align__(16) unsigned char mesh_lds[];
+    int64_t *Q = reinterpret_cast<int64_t *>(mesh_lds);
+    auto run_pass = [&](auto capped, int K, int S, int64_t cap) -> int64_t {
+        constexpr bool kCapped = decltype(capped)::value;
+        if constexpr (kFast) return mesh_pass_fast<kCapped>(tb, m, offs, order, group_at, Q, K, S, n_dev, cap);
+        else return mesh_pass<kCapped>(tb, m, offs, order, group_at, K, S, n_dev, cap);
+    };
     auto keep = [&](int S) {
         for (int s = tid; s <= S; s += nthreads) kept_cuts[s] = cuts[s];
         for (int s = tid; s < S; s += nthreads) {
@@ -252,7 +369,7 @@ __device__ __forceinline__ void mesh_body(const TablesDev &tb, const OrdDev &od,
                 for (int d = offs[k] + tid; d < offs[k + 1]; d += nthreads) group_at[d] = uint16_t(k);
         }
 
-        if (mesh_pass<false, kFast>(tb, m, offs, order, group_at, K, S, n_dev, 0) == kInf) { fail(HARP_CAND_INFEASIBLE); continue; }
+        if (run_pass(std::false_type(), K, S, 0) == kInf) { fail(HARP_CAND_INFEASIBLE); continue; }
         int64_t t_S, best_T;
         backtrack_and_score(K, S, t_S, best_T);
         int64_t best_b = t_S;
@@ -261,7 +378,7 @@ __device__ __forceinline__ void mesh_body(const TablesDev &tb, const OrdDev &od,
         if (kExact) {
             int64_t cap = t_S;
             while (S >= 2) {
-                const int64_t sum = mesh_pass<true, kFast>(tb, m, offs, order, group_at, K, S, n_dev, cap);
+                const int64_t sum = run_pass(std::true_type(), K, S, cap);
                 if (sum == kInf) break;              // cannot happen at or above t_S
                 int64_t b, T;
                 backtrack_and_score(K, S, b, T);
@@ -558,9 +675,11 @@ void launch_plan_mesh(const TablesDev &tb, const OrdDev &od, const PlansDev &out
     unsigned char *slices = static_cast<unsigned char *>(ws) + 256;
     const size_t per_group = plan_mesh_ws_per_group(tb.L, od.S_max, total_devices);
     const dim3 grid(n_groups), block(plan_mesh_threads(tb.L, total_devices));
+    fast32 = fast32 && tb.L <= kMeshFastMaxL;      // the fast form keeps L + 1 memory sums in LDS
+    const size_t lds = fast32 ? size_t(tb.L + 1) * sizeof(int64_t) : 0;
     hipLaunchKernelGGL(k2_mesh_clear, dim3(1), dim3(64), 0, st, ticket);
 #define HARP_MESH_LAUNCH(E, F)                                                                            \
-    hipLaunchKernelGGL(HIP_KERNEL_NAME(k2_mesh<E, F>), grid, block, 0, st, tb, od, out, stage_group, stage_tp, \
+    hipLaunchKernelGGL(HIP_KERNEL_NAME(k2_mesh<E, F>), grid, block, lds, st, tb, od, out, stage_group, stage_tp, \
                        n_passes, slices, per_group, total_devices, ticket)
     if (exact && fast32) HARP_MESH_LAUNCH(true, true);
     else if (exact) HARP_MESH_LAUNCH(true, false);
