@@ -302,6 +302,15 @@ def mesh_search(ctx, binding, torch, workloads, name, n_orders, reps, cpu_orders
     ms_h = timed_ms(torch, lambda: binding.harp_plan_mesh_h1f1b_batch(ctx, tables, do, caps, out_h, sg, st, wu, ws), reps)
     res["h1f1b_ms_per_call"] = ms_h
     res["h1f1b_feasible_fraction"] = float((out_h.to_host().status == 0).mean())
+    # the exact form: the capped least-sum pass walked over the caps
+    npass = torch.empty(do.C, dtype=torch.int32, device=ctx.device)
+    out_e = binding.DevicePlans(ctx, do.C, do.S_max)
+    ms_e = timed_ms(torch, lambda: binding.harp_plan_mesh_exact_batch(ctx, tables, do, out_e, sg, st, ws, npass), reps)
+    got_e = out_e.to_host()
+    res["exact_ms_per_call"] = ms_e
+    res["exact_mean_capped_passes"] = float(npass.cpu().numpy()[ok].mean()) if ok.any() else None
+    res["exact_mean_gain_over_min_max"] = (float((1.0 - got_e.iter_time[ok] / got.iter_time[ok]).mean())
+                                           if ok.any() else None)
     timed_ms(torch, lambda: binding.harp_plan_mesh_batch(ctx, tables, do, out, sg, st, ws), 1)   # restore sg, st
     if cpu_orders:
         import oracle

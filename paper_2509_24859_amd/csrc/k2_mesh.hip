@@ -18,8 +18,9 @@
 // stop is strict and the update accepts equal values at a lower j, which keeps the lowest j.  The
 // three-index table does not fit in LDS (L x devices entries per stage): the two live rows and the
 // back-pointers sit in a per-workgroup slice of the caller's workspace, L2-resident at the sizes
-// of interest.  Values are int64; stage and transfer times come from the 32-bit rows and the cut
-// table when the tables have them, else from the int64 rows (any degrees, any time width).
+// of interest.  Two forms of every pass: one on the int64 rows (any degrees, any time width, values
+// int64), and one on the fused 32-bit rows and the cut table for tables that have them
+// (mesh_pass_fast, mesh_h1_pass_fast), chosen per launch.
 #include <type_traits>
 
 #include "harp_internal.h"
@@ -442,7 +443,6 @@ __device__ __forceinline__ int mesh_delta(int64_t c, int64_t cap) {
 // it.  One lane per target cell (i, e); per degree an upward scan of the end cuts j, which stops at
 // the cap (the stage time grows with j) or when the stage no longer fits even with a count of one.
 // Ties: lowest end cut, then smallest degree.  Returns the value of (S, 0, all devices).
-template <bool kFast>
 __device__ __forceinline__ int64_t mesh_h1_pass(const TablesDev &tb, const MeshSlice &m, const int32_t *offs,
                                                 const uint16_t *order, const uint16_t *group_at, int K, int S,
                                                 int64_t n_dev, int64_t cap) {
@@ -473,7 +473,7 @@ __device__ __forceinline__ int64_t mesh_h1_pass(const TablesDev &tb, const MeshS
             const int t = tb.group_type[g];
             const int64_t *pf = tb.PF(t);
             const int64_t mem_dev = tb.type_mem[t];
-            const int64_t pfi = kFast ? 0 : pf[i], ppi = PP[i], psi = PS[i];
+            const int64_t pfi = pf[i], ppi = PP[i], psi = PS[i];
             int64_t best = kInf;
             int best_j = 0x7FFFFFFF, best_q = 0, best_n = 0;
             for (int q = 0; q < tb.n_tp; ++q) {
@@ -485,29 +485,21 @@ __device__ __forceinline__ int64_t mesh_h1_pass(const TablesDev &tb, const MeshS
                 const int g_next = (s == 1) ? g : (d0 + int(tp) == offs[k + 1] ? order[k + 1 < K ? k + 1 : k] : g);
                 const int shift = tb.tp_shift[q];
                 const int64_t *pr = tb.PR(g, q);
-                const uint32_t *p32 = kFast ? tb.P32 + (int64_t(g) * tb.n_tp + q) * tb.pitch32 : nullptr;
-                const uint32_t *cm = kFast ? tb.CM + (int64_t(g) * tb.G + g_next) * tb.pitch32 : nullptr;
                 const int64_t link = tb.bw[int64_t(g) * tb.G + g_next];
-                const int64_t pri = kFast ? 0 : pr[i];
-                const uint32_t base32 = kFast ? p32[i] : 0u;
+                const int64_t pri = pr[i];
                 const int64_t capm = tp * mem_dev;
                 const int64_t *rowG = Gp + size_t(e0) * W;
                 const int32_t *rowN = Np + size_t(e0) * W;
                 for (int j = i + 1; j <= j_hi; ++j) {
-                    int64_t time;
-                    if (kFast) {
-                        time = int64_t((p32[j] + uint32_t(tp) - 1u - base32) >> shift);
-                    } else {
-                        const int64_t work = pf[j] - pfi;
-                        time = (shift >= 0 ? (work + tp - 1) >> shift : (work + tp - 1) / tp) + (pr[j] - pri);
-                    }
+                    const int64_t work = pf[j] - pfi;
+                    const int64_t time = (shift >= 0 ? (work + tp - 1) >> shift : (work + tp - 1) / tp) + (pr[j] - pri);
                     if (time > cap) break;                                   // constraint (i); grows with j
                     const int64_t dpp = PP[j] - ppi, dps = PS[j] - psi;
                     if (dpp + dps > capm) break;                             // no count fits from here on
                     const int64_t rest = rowG[j];
                     if (rest == kInf) continue;
                     int64_t cut = 0;
-                    if (s > 1) cut = kFast ? int64_t(cm[j]) : (tb.act_bytes[j - 1] + link - 1) / link;
+                    if (s > 1) cut = (tb.act_bytes[j - 1] + link - 1) / link;
                     if (cut > cap) continue;                                 // constraint (ii)
                     int64_t n = mesh_delta(cut, cap) + rowN[j];              // eq. dp_ni
                     n = n < tb.M ? n : tb.M;
@@ -527,6 +519,114 @@ __device__ __forceinline__ int64_t mesh_h1_pass(const TablesDev &tb, const MeshS
     return Gp[size_t(Dtot) * W];
 }
 
+// The same pass on the 32-bit rows (tables that have them, L <= kMeshFastMaxL).  The running sums PP and
+// PS sit in LDS for the whole pass.  A state's least sum and its count share one 64-bit word,
+// sum << 10 | count: a count grows by at most 3 per stage (eq. delta_i under constraint (ii)) and
+// there are at most 256 stages, so it stays below 1024, and a sum stays below 2^42.  The quotient
+// of eq. dp_ni is read off two thresholds on the transfer time: 2c - e > 0 iff c > e >> 1, and
+// 2c - e > cap iff c > (cap + e) >> 1, with e = cap >> 6.  The best (sum, end cut, degree index) is
+// one key, sum << 19 | j << 3 | q; four end cuts per trip under predicates, the last one deciding
+// whether the lane goes on (the stage time and the memory need with a count of one both grow with j).
+__device__ __forceinline__ int64_t mesh_h1_pass_fast(const TablesDev &tb, const MeshSlice &m, const int32_t *offs,
+                                                     const uint16_t *order, const uint16_t *group_at,
+                                                     int64_t *PPl, int K, int S, int64_t n_dev, int64_t cap) {
+    constexpr uint64_t kNone = ~0ull;
+    const int L = tb.L, W = L + 1, tid = threadIdx.x, nthreads = blockDim.x;
+    const int Dtot = offs[K];
+    int64_t *PSl = PPl + W;
+    uint64_t *Gp = reinterpret_cast<uint64_t *>(m.D0), *Gn = reinterpret_cast<uint64_t *>(m.D1);
+    const uint32_t cap32 = cap > 0xFFFFFFFEll ? 0xFFFFFFFEu : uint32_t(cap);
+    const uint64_t e6 = uint64_t(cap) >> 6;
+    const uint64_t th1_64 = e6 >> 1, th2_64 = (uint64_t(cap) + e6) >> 1;
+    const uint32_t th1 = th1_64 > 0xFFFFFFFFull ? 0xFFFFFFFFu : uint32_t(th1_64);
+    const uint32_t th2 = th2_64 > 0xFFFFFFFFull ? 0xFFFFFFFFu : uint32_t(th2_64);
+    const uint32_t m_cap = uint32_t(tb.M);
+    __syncthreads();
+    {
+        const int64_t *PP = tb.PP(), *PS = tb.PS();
+        for (int j = tid; j <= L; j += nthreads) { PPl[j] = PP[j]; PSl[j] = PS[j]; }
+    }
+    for (int x = tid; x < (Dtot + 1) * W; x += nthreads) Gp[x] = kNone;
+    __syncthreads();
+    if (tid == 0) Gp[L] = 0;                         // no stages left: no operators, no devices, count 0
+    for (int s = 1; s <= S; ++s) {
+        __syncthreads();                             // row s - 1 is complete
+        const bool whole = (s == S);
+        const int i_lo = whole ? 0 : S - s, i_hi = whole ? 0 : L - s;
+        const int e_lo = whole ? Dtot : s, e_hi = whole ? Dtot : Dtot - (S - s);
+        const int j_hi = L - (s - 1);
+        const int n_i = i_hi - i_lo + 1, n_e = e_hi - e_lo + 1;
+        uint32_t *arg_s = m.arg + size_t(s - 1) * size_t(n_dev + 1) * W;
+        for (int x = tid; x < n_i * n_e; x += nthreads) {
+            const int i = i_lo + x % n_i, e = e_lo + x / n_i;
+            const int d0 = Dtot - e;                 // first device of the stage this step places
+            int k = 0;
+            if (Dtot <= kMeshGroupTable) k = group_at[d0];
+            else while (offs[k + 1] <= d0) ++k;
+            const int g = order[k];
+            const int64_t mem_dev = tb.type_mem[tb.group_type[g]];
+            const int64_t ppi = PPl[i], psi = PSl[i];
+            uint64_t best = kNone;
+            uint32_t best_n = 0;
+            for (int q = 0; q < tb.n_tp; ++q) {
+                const int tp = tb.tp[q];
+                const int e0 = e - tp;
+                // the stage stays inside group k; the stages behind it have used at least one device
+                // each (row s - 1 holds nothing else), and none at all exactly when there are none
+                if (d0 + tp > offs[k + 1] || e0 < s - 1 || (s == 1) != (e0 == 0)) continue;
+                const int g_next = (s == 1) ? g : (d0 + tp == offs[k + 1] ? order[k + 1 < K ? k + 1 : k] : g);
+                const int shift = tb.tp_shift[q];
+                const uint32_t *p32 = tb.P32 + (int64_t(g) * tb.n_tp + q) * tb.pitch32;
+                const uint32_t *cm = tb.CM + (int64_t(g) * tb.G + g_next) * tb.pitch32;
+                const uint32_t xi = p32[i] - uint32_t(tp) + 1u;       // time = (P[j] + tp - 1 - P[i]) >> shift
+                const int64_t capm = int64_t(tp) * mem_dev;
+                const uint64_t *row = Gp + size_t(e0) * W;
+                int j = i + 1;
+                bool more = true;                     // i < j_hi always
+                while (more) {
+                    const int j1 = (j + 1) < j_hi ? (j + 1) : j_hi, j2 = (j + 2) < j_hi ? (j + 2) : j_hi,
+                              j3 = (j + 3) < j_hi ? (j + 3) : j_hi;
+                    const uint32_t p0 = p32[j], p1 = p32[j1], p2 = p32[j2], p3 = p32[j3];
+                    uint32_t c0 = 0, c1 = 0, c2 = 0, c3 = 0;
+                    if (s > 1) { c0 = cm[j]; c1 = cm[j1]; c2 = cm[j2]; c3 = cm[j3]; }
+                    const uint64_t r0 = row[j], r1 = row[j1], r2 = row[j2], r3 = row[j3];
+                    const int64_t a0 = PPl[j], a1 = PPl[j1], a2 = PPl[j2], a3 = PPl[j3];
+                    const int64_t b0 = PSl[j], b1 = PSl[j1], b2 = PSl[j2], b3 = PSl[j3];
+                    bool live;
+#define HARP_MESH_H1_STEP(P, CUT, R, A, B, JJ)                                                    \
+    {                                                                                             \
+        const uint32_t tj = ((P) - xi) >> shift;                                                  \
+        const int64_t dpp = (A) - ppi, dps = (B) - psi;                                           \
+        live = (tj <= cap32) & (dpp + dps <= capm);          /* constraint (i); a count of one */ \
+        uint32_t n = 1u + ((CUT) > th1 ? 1u : 0u) + ((CUT) > th2 ? 1u : 0u) + (uint32_t(R) & 1023u); \
+        n = n < m_cap ? n : m_cap;                                                     /* eq. dp_ni */ \
+        const bool ok = live & ((R) != kNone) & ((CUT) <= cap32) & (dpp + int64_t(n) * dps <= capm); \
+        const uint64_t key = ((((R) >> 10) + uint64_t(tj) + 2ull * (CUT)) << 19) |                \
+                             uint64_t((uint32_t(JJ) << 3) | uint32_t(q));                         \
+        const bool upd = ok & (key < best);                                                       \
+        best = upd ? key : best;                                                                  \
+        best_n = upd ? n : best_n;                                                                \
+    }
+                    HARP_MESH_H1_STEP(p0, c0, r0, a0, b0, j)
+                    HARP_MESH_H1_STEP(p1, c1, r1, a1, b1, j1)
+                    HARP_MESH_H1_STEP(p2, c2, r2, a2, b2, j2)
+                    HARP_MESH_H1_STEP(p3, c3, r3, a3, b3, j3)
+#undef HARP_MESH_H1_STEP
+                    more = ((j + 3) < j_hi) & live;
+                    j += 4;
+                }
+            }
+            Gn[size_t(e) * W + i] = best == kNone ? kNone : (((best >> 19) << 10) | uint64_t(best_n));
+            const uint32_t jq = uint32_t(best) & 0x7FFFFu;
+            arg_s[size_t(e) * W + i] = (jq >> 3) | ((jq & 7u) << 16);
+        }
+        uint64_t *tg = Gp; Gp = Gn; Gn = tg;
+    }
+    __syncthreads();
+    const uint64_t v = Gp[size_t(Dtot) * W];
+    return v == kNone ? kInf : int64_t(v >> 10);
+}
+
 template <bool kFast>
 __device__ __forceinline__ void mesh_h1_body(const TablesDev &tb, const OrdDev &od, const int64_t *t_max,
                                              const PlansDev &out, int32_t *stage_group, int32_t *stage_tp,
@@ -535,6 +635,8 @@ __device__ __forceinline__ void mesh_h1_body(const TablesDev &tb, const OrdDev &
     __shared__ int32_t offs[kMaxOrderGroups + 1];
     __shared__ uint16_t order[kMaxOrderGroups];
     __shared__ uint16_t group_at[kMeshGroupTable];
+    extern __shared__ __align__(16) unsigned char mesh_lds[];      // fast form: PP and PS, L + 1 entries each
+    int64_t *sums_lds = reinterpret_cast<int64_t *>(mesh_lds);
     __shared__ int32_t cuts[kMaxStages + 1], count[kMaxStages];
     __shared__ uint16_t slot_g[kMaxStages];
     __shared__ uint8_t slot_k[kMaxStages];
@@ -582,7 +684,9 @@ __device__ __forceinline__ void mesh_h1_body(const TablesDev &tb, const OrdDev &
             for (int k = 0; k < K; ++k)
                 for (int d = offs[k] + tid; d < offs[k + 1]; d += nthreads) group_at[d] = uint16_t(k);
         }
-        const int64_t sum = mesh_h1_pass<kFast>(tb, m, offs, order, group_at, K, S, n_dev, cap);
+        int64_t sum;
+        if constexpr (kFast) sum = mesh_h1_pass_fast(tb, m, offs, order, group_at, sums_lds, K, S, n_dev, cap);
+        else sum = mesh_h1_pass(tb, m, offs, order, group_at, K, S, n_dev, cap);
         if (sum == kInf) { fail(HARP_CAND_INFEASIBLE); continue; }
         if (tid == 0) {
             int i = 0, e = Dtot;
@@ -695,9 +799,11 @@ void launch_plan_mesh_h1f1b(const TablesDev &tb, const OrdDev &od, const int64_t
     unsigned char *slices = static_cast<unsigned char *>(ws) + 256;
     const size_t per_group = plan_mesh_ws_per_group(tb.L, od.S_max, total_devices);
     const dim3 grid(n_groups), block(plan_mesh_threads(tb.L, total_devices));
+    fast32 = fast32 && tb.L <= kMeshFastMaxL;      // the fast form keeps 2 (L + 1) running sums in LDS
+    const size_t lds = fast32 ? 2 * size_t(tb.L + 1) * sizeof(int64_t) : 0;
     hipLaunchKernelGGL(k2_mesh_clear, dim3(1), dim3(64), 0, st, ticket);
     if (fast32)
-        hipLaunchKernelGGL(HIP_KERNEL_NAME(k2_mesh_h1f1b<true>), grid, block, 0, st, tb, od, t_max, out, stage_group,
+        hipLaunchKernelGGL(HIP_KERNEL_NAME(k2_mesh_h1f1b<true>), grid, block, lds, st, tb, od, t_max, out, stage_group,
                            stage_tp, warmup, slices, per_group, total_devices, ticket);
     else
         hipLaunchKernelGGL(HIP_KERNEL_NAME(k2_mesh_h1f1b<false>), grid, block, 0, st, tb, od, t_max, out,

@@ -86,6 +86,13 @@ def test_h1f1b_tiny_and_random_small(harp, ctx):
             caps, _ = _caps_from_min_max(w.problem, cands, num, den)
             _check(harp, ctx, w.problem, cands, caps, "seed %d x%d/%d" % (seed, num, den), need_fast=False)
     assert fast_runs > 150
+    # caps at the edges of the 32-bit arithmetic: zero, one, around 2^31 and 2^32, far above every time
+    edge = np.array([0, 1, 2 ** 31 - 1, 2 ** 31, 2 ** 32 + 5, 2 ** 40], dtype=np.int64)
+    for seed in range(40):
+        w = W.random_small(seed)
+        cands = w.candidates()
+        _check(harp, ctx, w.problem, cands, edge[np.arange(cands.C) % edge.size], "edge caps, seed %d" % seed,
+               need_fast=False)
 
 
 @pytest.mark.parametrize("name,n,stride", [("llama7b", 1024, 1), ("llama70b", 2048, 8), ("finegrained", 512, 127),

@@ -217,6 +217,14 @@ def test_mesh_h1f1b_full_recurrence(harp, ctx):
             _, want = _check_h1(harp, ctx, p, orders, caps, "seed %d x%d/%d" % (seed, num, den))
             feasible += int((want.status == oracle.OK).sum())
     assert feasible > 1000
+    # caps at the edges of the 32-bit arithmetic: zero, one, around 2^31 and 2^32, far above every time
+    for seed in range(40):
+        w = W.random_small(seed)
+        p = w.problem
+        top = min(8, int(p.group_ndev.sum()))
+        orders = W.make_orderings(p, seed, 5, 1, max(top, p.G), 0, 6)
+        caps = np.array([0, 1, 2 ** 31 - 1, 2 ** 31, 2 ** 32 + 5, 2 ** 40], dtype=np.int64)[:orders.C]
+        _check_h1(harp, ctx, p, orders, caps, "edge caps, seed %d" % seed)
     for name, n in (("tiny", 16), ("llama7b", 128), ("llama70b", 48)):
         w = W.make(name)
         orders = W.make_orderings(w.problem, w.seed, w.config_id, w.problem.G, w.S_max, 0, n)
