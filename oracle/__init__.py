@@ -51,7 +51,8 @@ def _load():
         for name in ("oracle_build_tables", "oracle_plan_batch", "oracle_score_1f1b",
                      "oracle_argmin_batch", "oracle_plan_exact_batch", "oracle_plan_h1f1b_batch",
                      "oracle_score_h1f1b", "oracle_plan_mesh_batch",
-                     "oracle_plan_mesh_exact_batch", "oracle_plan_mesh_h1f1b_batch"):
+                     "oracle_plan_mesh_exact_batch", "oracle_plan_mesh_h1f1b_batch",
+                     "oracle_plan_mesh_h1f1b_sweep_batch"):
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -232,6 +233,33 @@ def plan_mesh_h1f1b_batch(tables: Tables, orders, t_max, c_begin: int = 0, c_end
         _ptr(out.status))
     if rc != 0:
         raise ValueError("oracle_plan_mesh_h1f1b_batch failed with code %d" % rc)
+    return out
+
+
+def plan_mesh_h1f1b_sweep_batch(tables: Tables, orders, max_caps: int = 1 << 20, c_begin: int = 0,
+                                c_end: int | None = None, out: Plans | None = None) -> Plans:
+    """The search in full: the cap swept over the candidate values from the smallest feasible one
+    to ceil(T / B), the full recurrence at every cap.  `out.t_max` is the cap of the answer,
+    `out.n_caps` the caps tried."""
+    c_end = orders.C if c_end is None else c_end
+    out = Plans(orders.C, orders.S_max) if out is None else out
+    if not hasattr(out, "stage_group"):
+        out.stage_group = np.full((orders.C, orders.S_max), -1, dtype=np.int32)
+        out.stage_tp = np.full((orders.C, orders.S_max), -1, dtype=np.int32)
+    if not hasattr(out, "warmup"):
+        out.warmup = np.full((orders.C, orders.S_max), -1, dtype=np.int32)
+    if not hasattr(out, "t_max"):
+        out.t_max = np.full(orders.C, INF, dtype=np.int64)
+        out.n_caps = np.zeros(orders.C, dtype=np.int32)
+    os_, og_, ogr = _c32(orders.ord_S), _c32(orders.ord_G), _c32(orders.ord_group)
+    rc = _load().oracle_plan_mesh_h1f1b_sweep_batch(
+        C.byref(tables.c), _ptr(tables.PF), _ptr(tables.PP), _ptr(tables.PS), _ptr(tables.PR),
+        C.c_int32(orders.C), C.c_int32(orders.G_max), C.c_int32(orders.S_max), _ptr(os_), _ptr(og_), _ptr(ogr),
+        C.c_int32(max_caps), C.c_int32(c_begin), C.c_int32(c_end), _ptr(out.splits), _ptr(out.stage_group),
+        _ptr(out.stage_tp), _ptr(out.dev_first), _ptr(out.warmup), _ptr(out.bottleneck), _ptr(out.iter_time),
+        _ptr(out.status), _ptr(out.t_max), _ptr(out.n_caps))
+    if rc != 0:
+        raise ValueError("oracle_plan_mesh_h1f1b_sweep_batch failed with code %d" % rc)
     return out
 
 

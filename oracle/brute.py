@@ -565,3 +565,47 @@ def plan_mesh_h1f1b(p, S: int, S_max: int, groups, t_max: int):
         cuts.append(j)
         i, d = j, d + degrees[q]
     return 0, cuts, slots, counts, total_sum
+
+
+def mesh_cap_values(p, groups):
+    """Candidate caps of an ordering (section 5.2.4 (2)): every stage time of every listed group,
+    usable degree and operator range, and every transfer time of an inner cut on the links the
+    ordering can use (inside a group, and to the group after it).  Sorted, distinct."""
+    L = int(p.L)
+    groups = [int(g) for g in groups]
+    values = set()
+    for k, g in enumerate(groups):
+        for deg in (int(x) for x in p.tp_degrees):
+            if deg <= int(p.group_ndev[g]):
+                values.update(stage_time(p, g, deg, j, i) for j in range(L) for i in range(j + 1, L + 1))
+        links = [g] + ([groups[k + 1]] if k + 1 < len(groups) else [])
+        values.update(cut_time(p, g, h, i) for h in links for i in range(1, L))
+    return sorted(values)
+
+
+def sweep_mesh_h1f1b(p, S: int, S_max: int, groups, max_caps: int = 1 << 20):
+    """The search around the full recurrence, twin of the oracle's: caps in increasing order from
+    the classic min-max bottleneck; the first cap with a plan fixes t_E = ceil(T / M); smallest
+    T = least sum + (M - 1) cap wins, the lower cap on ties.
+    Returns (status, cap, cuts, slot list, counts, T, caps tried)."""
+    status, t_S, _, _ = plan_mesh(p, S, S_max, groups)
+    if status != 0:
+        return status, INF, None, None, None, INF, 0
+    M = int(p.M)
+    best = (1, INF, None, None, None, INF)
+    t_E, tried = INF, 0
+    for cap in mesh_cap_values(p, groups):
+        if cap < t_S:
+            continue
+        if cap > t_E or tried >= max_caps:
+            break
+        tried += 1
+        st, cuts, slots, counts, total = plan_mesh_h1f1b(p, S, S_max, groups, cap)
+        if st != 0:
+            continue
+        T = total + (M - 1) * cap
+        if t_E == INF:
+            t_E = _cdiv(T, M)
+        if T < best[5]:
+            best = (0, cap, cuts, slots, counts, T)
+    return best + (tried,)

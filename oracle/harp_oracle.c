@@ -1010,3 +1010,123 @@ int oracle_plan_mesh_h1f1b_batch(const oracle_problem *p, const int64_t *PF, con
     free(m.D); free(m.arg_j); free(m.arg_k); free(N); free(m.O); free(seen);
     return ORACLE_OK;
 }
+
+/* ---------------------------------------------------------------------------------------------
+ * The search of section 5.2.4 (2) around the full recurrence: the cap t_max swept over the sorted,
+ * deduplicated candidate values, from the smallest feasible one up to t_E = ceil(T(t_S) / B).
+ *
+ * Candidate values of an ordering (what a profiler would hand over, independent of where in the
+ * pipeline a stage sits): every stage time time(g, tp; j, i) for a group g of the ordering, an
+ * allowed degree tp <= devices of g, and 0 <= j < i <= L; and every transfer time of a cut
+ * 1 <= i <= L - 1 on the links the ordering can use (inside each listed group, and from each
+ * listed group to the one after it).  These are the values at which the set of transitions that
+ * constraints (i) and (ii) admit can change.
+ *
+ * Sweep, per ordering: the lower end is the classic min-max bottleneck (no cap below it admits a
+ * plan, and H-1F1B's counts are never below the classic ones).  Caps are taken in increasing order
+ * from there; each one is given to the full recurrence (oracle_plan_mesh_h1f1b_batch, one
+ * ordering).  The first cap with a plan fixes t_E = ceil(T / B) from that plan's T; the sweep ends
+ * past t_E, at the end of the list, or after max_caps caps.  The answer is the plan with the
+ * smallest T = least sum + (B - 1) cap, the lower cap on equal T.  t_max_out receives the cap of
+ * the answer (INF if none), n_caps the caps tried.
+ * ------------------------------------------------------------------------------------------- */
+int oracle_plan_mesh_h1f1b_sweep_batch(const oracle_problem *p, const int64_t *PF, const int64_t *PP,
+                                       const int64_t *PS, const int64_t *PR, int32_t C, int32_t G_max,
+                                       int32_t S_max, const int32_t *ord_S, const int32_t *ord_G,
+                                       const int32_t *ord_group, int32_t max_caps, int32_t c_begin,
+                                       int32_t c_end, int32_t *splits, int32_t *stage_group, int32_t *stage_tp,
+                                       int32_t *dev_first, int32_t *warmup, int64_t *bottleneck,
+                                       int64_t *iter_time, int32_t *status, int64_t *t_max_out, int32_t *n_caps)
+{
+    if (C < 0 || S_max < 1 || G_max < 1 || c_begin < 0 || c_end > C || c_begin > c_end || max_caps < 1)
+        return ORACLE_BAD_ARG;
+    const int L = p->L;
+    tables_view v = { p, PF, PP, PS, PR };
+    /* one ordering's worth of outputs for the trial calls */
+    int32_t *tsp = (int32_t *)malloc(sizeof(int32_t) * (size_t)(S_max + 1));
+    int32_t *tsg = (int32_t *)malloc(sizeof(int32_t) * (size_t)S_max);
+    int32_t *tst = (int32_t *)malloc(sizeof(int32_t) * (size_t)S_max);
+    int32_t *tdf = (int32_t *)malloc(sizeof(int32_t) * (size_t)S_max);
+    int32_t *twu = (int32_t *)malloc(sizeof(int32_t) * (size_t)S_max);
+    size_t room = 1024, n = 0;
+    int64_t *grid = (int64_t *)malloc(sizeof(int64_t) * room);
+    if (!tsp || !tsg || !tst || !tdf || !twu || !grid) return ORACLE_BAD_ARG;
+    for (int32_t c = c_begin; c < c_end; ++c) {
+        const int32_t *og = ord_group + (size_t)c * G_max;
+        int32_t *sp = splits + (size_t)c * (S_max + 1), *sg = stage_group + (size_t)c * S_max;
+        int32_t *st = stage_tp + (size_t)c * S_max, *df = dev_first + (size_t)c * S_max;
+        int32_t *wu = warmup + (size_t)c * S_max;
+        for (int s = 0; s < S_max; ++s) wu[s] = -1;
+        t_max_out[c] = ORACLE_INF;
+        if (n_caps) n_caps[c] = 0;
+        /* the classic min-max plan of this ordering: validity, and the lower end of the sweep */
+        int64_t t_S, unused;
+        int32_t st0;
+        int rc = oracle_plan_mesh_batch(p, PF, PP, PS, PR, 1, G_max, S_max, ord_S + c, ord_G + c, og, 0, 1,
+                                        sp, sg, st, df, &t_S, &unused, &st0);
+        if (rc != ORACLE_OK) return rc;
+        /* whatever happens next, the outputs start out as "no plan" */
+        fill_failed(S_max, sp, df, bottleneck + c, iter_time + c);
+        for (int s = 0; s < S_max; ++s) { sg[s] = -1; st[s] = -1; }
+        status[c] = st0;
+        if (st0 != CAND_OK) continue;
+        status[c] = CAND_INFEASIBLE;
+        const int K = ord_G[c];
+        /* the candidate values at or above t_S */
+        n = 0;
+#define GRID_PUSH(x)                                                                          \
+    do {                                                                                      \
+        const int64_t val_ = (x);                                                             \
+        if (val_ >= t_S) {                                                                    \
+            if (n == room) {                                                                  \
+                room *= 2;                                                                    \
+                grid = (int64_t *)realloc(grid, sizeof(int64_t) * room);                      \
+                if (!grid) return ORACLE_BAD_ARG;                                             \
+            }                                                                                 \
+            grid[n++] = val_;                                                                 \
+        }                                                                                     \
+    } while (0)
+        for (int k = 0; k < K; ++k) {
+            const int g = og[k];
+            for (int q = 0; q < p->n_tp; ++q) {
+                const int tp = p->tp_degrees[q];
+                if (tp > p->group_ndev[g]) continue;
+                for (int j = 0; j < L; ++j)
+                    for (int i = j + 1; i <= L; ++i) GRID_PUSH(stage_time(&v, g, tp, j, i));
+            }
+            for (int i = 1; i <= L - 1; ++i) {
+                GRID_PUSH(cut_time(p, g, g, i));
+                if (k + 1 < K) GRID_PUSH(cut_time(p, g, og[k + 1], i));
+            }
+        }
+#undef GRID_PUSH
+        qsort(grid, n, sizeof(int64_t), cmp_i64);
+        int64_t best_T = ORACLE_INF, t_E = ORACLE_INF;
+        int tried = 0;
+        for (size_t x = 0; x < n && tried < max_caps; ++x) {
+            if (x > 0 && grid[x] == grid[x - 1]) continue;
+            const int64_t cap = grid[x];
+            if (cap > t_E) break;
+            ++tried;
+            int64_t b1, T1;
+            int32_t s1;
+            rc = oracle_plan_mesh_h1f1b_batch(p, PF, PP, PS, PR, 1, G_max, S_max, ord_S + c, ord_G + c, og, &cap,
+                                              0, 1, tsp, tsg, tst, tdf, twu, &b1, &T1, &s1);
+            if (rc != ORACLE_OK) return rc;
+            if (s1 != CAND_OK) continue;
+            if (t_E == ORACLE_INF) t_E = ceil_div(T1, p->M);
+            if (T1 < best_T) {
+                best_T = T1;
+                for (int s = 0; s <= S_max; ++s) sp[s] = tsp[s];
+                for (int s = 0; s < S_max; ++s) { sg[s] = tsg[s]; st[s] = tst[s]; df[s] = tdf[s]; wu[s] = twu[s]; }
+                bottleneck[c] = b1;
+                iter_time[c] = T1;
+                t_max_out[c] = cap;
+                status[c] = CAND_OK;
+            }
+        }
+        if (n_caps) n_caps[c] = tried;
+    }
+    free(tsp); free(tsg); free(tst); free(tdf); free(twu); free(grid);
+    return ORACLE_OK;
+}

@@ -360,6 +360,11 @@ class Orderings:
         return Orderings(hi - lo, self.G_max, self.S_max, self.ord_S[lo:hi].copy(), self.ord_G[lo:hi].copy(),
                          self.ord_group[lo:hi].copy())
 
+    def take(self, idx) -> "Orderings":
+        idx = np.asarray(idx, dtype=np.int64)
+        return Orderings(int(idx.size), self.G_max, self.S_max, self.ord_S[idx].copy(), self.ord_G[idx].copy(),
+                         self.ord_group[idx].copy())
+
 
 def orderings_from_lists(lists, S_max=None, G_max=None) -> Orderings:
     """lists: per candidate (S, [group ids in order])."""

@@ -4,6 +4,7 @@ The oracle (oracle/harp_oracle.c) is checked against: hand-worked fixtures, brut
 enumeration of every partition from the raw inputs, an independent algorithm for the textbook
 linear-partition special case, closed forms for uniform operators, and invariants of the model.
 """
+import dataclasses
 import math
 import os
 
@@ -820,3 +821,59 @@ def test_stress_workload_is_memory_tight():
     out = plan(w.problem, cands)
     frac = float((out.status == oracle.INFEASIBLE).mean())
     assert 0.15 < frac < 0.45        # about 30% over the first 4096 candidates
+
+
+def test_mesh_h1f1b_sweep_against_its_twin_and_what_bounds_it():
+    """The search around the full recurrence (section 5.2.4 (2)): the oracle against the recursion
+    twin's sweep; the answer is the smallest T over the caps tried; it equals the exact search of the
+    classic counts when memory is unlimited (then the counts decide nothing); a cap limit of one
+    gives the plan at the first candidate value at or above the min-max bottleneck."""
+    n = differs = 0
+    for seed in range(160):
+        w = W.random_small(seed, L_max=8, S_cap=4)
+        p = w.problem
+        if int(p.group_ndev.sum()) > 8:
+            continue
+        tables = oracle.build_tables(p)
+        orders = W.make_orderings(p, seed, 5, 1, 5, 0, 5)
+        out = oracle.plan_mesh_h1f1b_sweep_batch(tables, orders)
+        one = oracle.plan_mesh_h1f1b_sweep_batch(tables, orders, max_caps=1)
+        mm = oracle.plan_mesh_batch(tables, orders)
+        for c in range(orders.C):
+            S, groups = int(orders.ord_S[c]), orders.ord_group[c, :orders.ord_G[c]]
+            st, cap, cuts, slots, counts, T, tried = brute.sweep_mesh_h1f1b(p, S, orders.S_max, groups)
+            assert st == out.status[c] and tried == out.n_caps[c], (seed, c)
+            if mm.status[c] == oracle.OK:
+                assert one.n_caps[c] == 1
+                first = oracle.plan_mesh_h1f1b_batch(tables, orders.slice(c, c + 1), [int(mm.bottleneck[c])])
+                assert one.status[c] == first.status[0] and one.iter_time[c] == first.iter_time[0]
+            if st != oracle.OK:
+                assert out.t_max[c] == oracle.INF and (out.warmup[c] == -1).all() and (out.splits[c] == -1).all()
+                continue
+            n += 1
+            got_slots = [(int(g), int(t)) for g, t in zip(out.stage_group[c, :S], out.stage_tp[c, :S])]
+            assert out.t_max[c] == cap and out.iter_time[c] == T, (seed, c)
+            assert list(out.splits[c, :S + 1]) == cuts and got_slots == slots and list(out.warmup[c, :S]) == counts
+            # the answer is what the recurrence gives at its cap, and no tried cap does better
+            values = [v for v in brute.mesh_cap_values(p, groups) if v >= mm.bottleneck[c]][:tried]
+            assert cap in values
+            at_caps = oracle.plan_mesh_h1f1b_batch(tables, orders.take([c] * len(values)), values)
+            ok = at_caps.status == oracle.OK
+            assert at_caps.iter_time[ok].min() == T
+            assert values[int(np.nonzero(ok & (at_caps.iter_time == T))[0][0])] == cap      # the lower cap on ties
+            differs += cap != mm.bottleneck[c]
+    assert n > 250 and differs > 10
+    # unlimited memory: H-1F1B's counts constrain nothing, so the sweep finds the optimum of the cost model
+    for seed in range(60):
+        w = W.random_small(seed, L_max=8, S_cap=4)
+        p = w.problem
+        if int(p.group_ndev.sum()) > 8:
+            continue
+        p = dataclasses.replace(p, type_mem_bytes=np.full_like(p.type_mem_bytes, 1 << 50))
+        tables = oracle.build_tables(p)
+        orders = W.make_orderings(p, seed, 5, 1, 5, 0, 5)
+        sweep = oracle.plan_mesh_h1f1b_sweep_batch(tables, orders)
+        exact = oracle.plan_mesh_batch(tables, orders, exact=True)
+        assert (sweep.status == exact.status).all()
+        ok = exact.status == oracle.OK
+        assert (sweep.iter_time[ok] == exact.iter_time[ok]).all()
