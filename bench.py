@@ -141,9 +141,10 @@ def measured_peaks(ctx, binding, torch):
                     "1 GiB device-to-device copy, read + written bytes"}
 
 
-def timed_ms(torch, fn, reps):
+def timed_ms(torch, fn, reps, warmup=1):
     a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    fn()
+    for _ in range(warmup):
+        fn()
     torch.cuda.synchronize()
     a.record()
     for _ in range(reps):
@@ -270,7 +271,7 @@ def h1f1b_search(ctx, binding, torch, w, tables, dc, cands, caps_host, reps, cpu
     return res
 
 
-def mesh_search(ctx, binding, torch, workloads, name, n_orders, reps, cpu_orders):
+def mesh_search(ctx, binding, torch, workloads, name, n_orders, reps, cpu_orders, sweep_orders):
     """The planner that chooses the slicing inside the recurrence, over a batch of random group
     orderings of one of the smaller workloads (the state space has a device dimension, so the work
     per ordering is devices x degrees times that of a hot-path candidate)."""
@@ -311,6 +312,50 @@ def mesh_search(ctx, binding, torch, workloads, name, n_orders, reps, cpu_orders
     res["exact_mean_capped_passes"] = float(npass.cpu().numpy()[ok].mean()) if ok.any() else None
     res["exact_mean_gain_over_min_max"] = (float((1.0 - got_e.iter_time[ok] / got.iter_time[ok]).mean())
                                            if ok.any() else None)
+    # the search around the full recurrence: every candidate cap from t_S to ceil(T / B), one pass each
+    n_sweep = min(do.C, sweep_orders)
+    if n_sweep:
+        sub = orders.slice(0, n_sweep)
+        ds = binding.DeviceOrderings(ctx, sub)
+        out_s = binding.DevicePlans(ctx, ds.C, ds.S_max)
+        tm = torch.empty(ds.C, dtype=torch.int64, device=ctx.device)
+        nc = torch.empty(ds.C, dtype=torch.int32, device=ctx.device)
+        ws_s = binding.mesh_workspace(ctx, tables, ds)
+        sg_s, st_s, wu_s = (torch.empty((ds.C, ds.S_max), dtype=torch.int32, device=ctx.device) for _ in range(3))
+        run = lambda cap_limit: binding.harp_plan_mesh_h1f1b_sweep_batch(ctx, tables, ds, cap_limit, out_s, sg_s, st_s,
+                                                                         wu_s, tm, ws_s, nc)
+        ms_s = timed_ms(torch, lambda: run(1 << 20), 1, warmup=0)
+        got_s = out_s.to_host()
+        oks = got_s.status == 0
+        tried = nc.cpu().numpy()
+        res["sweep"] = {"kernel": "k2_mesh_h1f1b_sweep (one harp_plan_mesh_h1f1b_sweep_batch call)",
+                        "orderings": int(ds.C), "ms_per_call": ms_s, "mean_caps_tried": float(tried.mean()),
+                        "max_caps_tried": int(tried.max()), "passes_per_s": float(tried.sum()) / (ms_s * 1e-3),
+                        "feasible_fraction": float(oks.mean())}
+        if cpu_orders:
+            import oracle
+            from concurrent.futures import ThreadPoolExecutor
+            # the oracle under a limit of 24 caps on the first orderings, the GPU under the same limit
+            n_chk, limit = min(ds.C, 16), 24
+            run(limit)
+            torch.cuda.synchronize()
+            lim = out_s.to_host()
+            ot = oracle.build_tables(p)
+            want = None
+            t0 = time.perf_counter()
+            with ThreadPoolExecutor(min(16, len(os.sched_getaffinity(0)))) as ex:
+                outs = list(ex.map(lambda c: oracle.plan_mesh_h1f1b_sweep_batch(ot, sub, limit, c, c + 1), range(n_chk)))
+            dt = time.perf_counter() - t0
+            for c, want in enumerate(outs):
+                for name in ("status", "splits", "dev_first", "bottleneck", "iter_time"):
+                    if not (getattr(want, name)[c] == getattr(lim, name)[c]).all():
+                        raise SystemExit("GPU sweep differs from the oracle in %s at ordering %d" % (name, c))
+                if want.t_max[c] != int(tm[c].item()) or want.n_caps[c] != int(nc[c].item()):
+                    raise SystemExit("GPU sweep differs from the oracle in the cap chosen at ordering %d" % c)
+            res["sweep"]["cpu_baseline"] = {"value": n_chk * limit / dt, "unit": "capped passes/s", "cores": min(16, len(os.sched_getaffinity(0))),
+                                            "kind": "oracle", "sample": "first %d orderings under a limit of %d caps, "
+                                            "one ordering per thread, %.1f s wall; GPU answers under the same limit "
+                                            "verified bit-exact" % (n_chk, limit, dt)}
     timed_ms(torch, lambda: binding.harp_plan_mesh_batch(ctx, tables, do, out, sg, st, ws), 1)   # restore sg, st
     if cpu_orders:
         import oracle
@@ -362,6 +407,8 @@ def main():
     ap.add_argument("--mesh-orderings", type=int, default=4096,
                     help="group orderings for the submesh-in-recurrence planner (0 = skip)")
     ap.add_argument("--mesh-cpu-orderings", type=int, default=128)
+    ap.add_argument("--mesh-sweep-orderings", type=int, default=256,
+                    help="orderings given to the search around the full recurrence (0 = skip)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="also run one plain device copy of this many MiB (reference for HBM counters)")
     args = ap.parse_args()
@@ -500,7 +547,7 @@ def main():
     result.pop("_exact_caps", None)
     if args.mesh_orderings:
         result["mesh"] = mesh_search(ctx, binding, torch, workloads, args.mesh_workload, args.mesh_orderings, 2,
-                                     0 if args.no_cpu_baseline else args.mesh_cpu_orderings)
+                                     0 if args.no_cpu_baseline else args.mesh_cpu_orderings, args.mesh_sweep_orderings)
     if not args.no_cpu_baseline:
         # about 20 core-seconds of oracle work at 1-5 ns per dense transition
         budget = args.cpu_candidates or max(64, int(1.6e10 / max(1.0, n_trans / C)))

@@ -257,6 +257,27 @@ int harp_plan_mesh_h1f1b_batch(harp_ctx *ctx, harp_tables *tables, const harp_or
                                int32_t *stage_tp, int32_t *warmup, void *workspace,
                                size_t workspace_bytes, void *hip_stream);
 
+/* The search of section 5.2.4 (2) around that recurrence, per ordering: the cap t_max is swept over
+ * the sorted, distinct candidate values, from the smallest feasible one up to t_E = ceil(T / B), and
+ * harp_plan_mesh_h1f1b_batch's recurrence is evaluated at every one of them.  Candidate values of an
+ * ordering: every stage time of a listed group, an allowed degree not above the group's device
+ * count and an operator range [j, i), 0 <= j < i <= L; and every transfer time of a cut
+ * 1 <= i <= L - 1 on the links the ordering can use (inside each listed group, and from each
+ * listed group to the one after it).  The sweep starts at the bottleneck harp_plan_mesh_batch
+ * finds (no smaller cap admits a plan, and H-1F1B's counts are never below the classic ones), takes
+ * the values in increasing order, fixes t_E from the T of the first cap that has a plan, and ends
+ * past t_E, when the values run out, or after max_caps (>= 1) caps.  The answer is the plan with
+ * the smallest T = least sum + (M - 1) cap, the lower cap on equal T.  Outputs as
+ * harp_plan_mesh_h1f1b_batch at that cap; t_max_out: DEVICE [C], the cap of the answer (INT64_MAX
+ * when there is none); n_caps: DEVICE [C] or NULL, caps tried.  HARP_CAND_INFEASIBLE when no tried
+ * cap has a plan.  The work per ordering is caps tried x one harp_plan_mesh_h1f1b_batch pass.
+ * Workspace as for harp_plan_mesh_batch. */
+int harp_plan_mesh_h1f1b_sweep_batch(harp_ctx *ctx, harp_tables *tables, const harp_orderings *orders,
+                                     int32_t max_caps, const harp_plans *out, int32_t *stage_group,
+                                     int32_t *stage_tp, int32_t *warmup, int64_t *t_max_out,
+                                     int32_t *n_caps, void *workspace, size_t workspace_bytes,
+                                     void *hip_stream);
+
 /* The capped recurrence under the H-1F1B scheduler (sections 4.1 and 5.2.3): for candidate c and
  * the cap t_max[c] on every stage and transfer time (constraints (i), (ii)), the suffix recurrence
  * of eq. dp_general with the warm-up launch count carried in the state (eq. dp_ni) and used by the

@@ -27,6 +27,7 @@ EXPORTS = (
     "harp_set_plan_path", "harp_plan_workspace_bytes", "harp_plan_batch", "harp_plan_exact_batch",
     "harp_plan_h1f1b_batch", "harp_score_h1f1b",
     "harp_plan_mesh_workspace_bytes", "harp_plan_mesh_batch", "harp_plan_mesh_exact_batch", "harp_plan_mesh_h1f1b_batch",
+    "harp_plan_mesh_h1f1b_sweep_batch",
     "harp_score_1f1b", "harp_argmin_batch", "harp_measure_valu_int32",
 )
 
@@ -106,6 +107,8 @@ def load_library() -> C.CDLL:
                                                vp, sz, vp]
     lib.harp_plan_mesh_h1f1b_batch.argtypes = [vp, vp, C.POINTER(harp_orderings), vp, C.POINTER(harp_plans), vp, vp,
                                                vp, vp, sz, vp]
+    lib.harp_plan_mesh_h1f1b_sweep_batch.argtypes = [vp, vp, C.POINTER(harp_orderings), i32, C.POINTER(harp_plans),
+                                                     vp, vp, vp, vp, vp, vp, sz, vp]
     lib.harp_score_1f1b.argtypes = [vp, vp, C.POINTER(harp_candidates), vp, vp, vp, vp, vp]
     lib.harp_argmin_batch.argtypes = [vp, i32, vp, vp, vp, vp, vp]
     lib.harp_measure_valu_int32.argtypes = [vp, i32, i32, vp, vp]
@@ -427,6 +430,45 @@ def plan_mesh_h1f1b(ctx: Context, problem, orders, t_max, path: int = PATH_AUTO)
     got.stage_group = sg[:do.C].cpu().numpy()
     got.stage_tp = st[:do.C].cpu().numpy()
     got.warmup = wu[:do.C].cpu().numpy()
+    return got, tables
+
+
+def harp_plan_mesh_h1f1b_sweep_batch(ctx: Context, tables: Tables, do: DeviceOrderings, max_caps: int,
+                                     out: DevicePlans, stage_group, stage_tp, warmup, t_max_out, workspace,
+                                     n_caps=None, stream=None):
+    ctx.check(ctx.lib.harp_plan_mesh_h1f1b_sweep_batch(
+        ctx.handle, tables.handle, C.byref(do.c), int(max_caps), C.byref(out.c), stage_group.data_ptr(),
+        stage_tp.data_ptr(), warmup.data_ptr(), t_max_out.data_ptr(),
+        n_caps.data_ptr() if n_caps is not None else None, workspace.data_ptr(), workspace.numel(),
+        _stream_handle(stream)))
+
+
+def plan_mesh_h1f1b_sweep(ctx: Context, problem, orders, max_caps: int = 1 << 20, path: int = PATH_AUTO):
+    """Convenience for tests: the search around the full recurrence; host copies of the plans with
+    `.stage_group`, `.stage_tp`, `.warmup`, `.t_max`, `.n_caps`."""
+    torch = _torch()
+    tables = Tables(ctx, problem)
+    do = DeviceOrderings(ctx, orders)
+    out = DevicePlans(ctx, do.C, do.S_max)
+    out.poison()
+    sg = torch.full((max(do.C, 1), do.S_max), -7, dtype=torch.int32, device=ctx.device)
+    st = torch.full((max(do.C, 1), do.S_max), -7, dtype=torch.int32, device=ctx.device)
+    wu = torch.full((max(do.C, 1), do.S_max), -7, dtype=torch.int32, device=ctx.device)
+    tm = torch.full((max(do.C, 1),), -7, dtype=torch.int64, device=ctx.device)
+    nc = torch.full((max(do.C, 1),), -7, dtype=torch.int32, device=ctx.device)
+    ws = mesh_workspace(ctx, tables, do)
+    ctx.set_plan_path(path)
+    try:
+        harp_plan_mesh_h1f1b_sweep_batch(ctx, tables, do, max_caps, out, sg, st, wu, tm, ws, nc)
+        torch.cuda.synchronize()
+    finally:
+        ctx.set_plan_path(PATH_AUTO)
+    got = out.to_host()
+    got.stage_group = sg[:do.C].cpu().numpy()
+    got.stage_tp = st[:do.C].cpu().numpy()
+    got.warmup = wu[:do.C].cpu().numpy()
+    got.t_max = tm[:do.C].cpu().numpy()
+    got.n_caps = nc[:do.C].cpu().numpy()
     return got, tables
 
 

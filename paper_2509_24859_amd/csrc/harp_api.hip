@@ -403,7 +403,8 @@ int harp_plan_h1f1b_batch(harp_ctx *ctx, harp_tables *t, const harp_candidates *
 size_t harp_plan_mesh_workspace_bytes(harp_ctx *ctx, harp_tables *t, const harp_orderings *od) {
     if (check_orderings(ctx, t, od) != HARP_OK) return 0;
     const size_t per_group = plan_mesh_ws_per_group(t->dev.L, od->S_max, t->total_devices);
-    return 256 + size_t(n_mesh_groups(ctx, od->C, per_group, plan_mesh_threads(t->dev.L, t->total_devices))) * per_group;
+    return 256 + size_t(n_mesh_groups(ctx, od->C, per_group,
+                                      plan_mesh_threads(t->dev.L, t->total_devices, od->C, ctx->n_cu))) * per_group;
 }
 
 }  // extern "C"
@@ -423,7 +424,8 @@ int plan_mesh_common(harp_ctx *ctx, harp_tables *t, const harp_orderings *od, co
     if (od->C == 0) return HARP_OK;
     if (t->total_devices > 65535) return fail(ctx, HARP_ERR_SHAPE, "the submesh planner handles at most 65535 devices");
     const size_t per_group = plan_mesh_ws_per_group(t->dev.L, od->S_max, t->total_devices);
-    const int groups = n_mesh_groups(ctx, od->C, per_group, plan_mesh_threads(t->dev.L, t->total_devices));
+    const int threads = plan_mesh_threads(t->dev.L, t->total_devices, od->C, ctx->n_cu);
+    const int groups = n_mesh_groups(ctx, od->C, per_group, threads);
     const size_t need = 256 + size_t(groups) * per_group;
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0)
         return fail(ctx, HARP_ERR_WORKSPACE, "workspace must be a 256-byte aligned device pointer");
@@ -434,7 +436,7 @@ int plan_mesh_common(harp_ctx *ctx, harp_tables *t, const harp_orderings *od, co
     const OrdDev o = { od->C, od->G_max, od->S_max, od->ord_S, od->ord_G, od->ord_group };
     const PlansDev pl = { out->splits, out->dev_first, out->bottleneck, out->iter_time, out->status };
     launch_plan_mesh(t->dev, o, pl, stage_group, stage_tp, n_passes, exact, use_fast(ctx, t), workspace, groups,
-                     t->total_devices,
+                     threads, t->total_devices,
                      static_cast<hipStream_t>(hip_stream));
     e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(ctx, e, "launching the submesh planner kernel");
@@ -465,7 +467,8 @@ int harp_plan_mesh_h1f1b_batch(harp_ctx *ctx, harp_tables *t, const harp_orderin
     if (od->C == 0) return HARP_OK;
     if (t->total_devices > 65535) return fail(ctx, HARP_ERR_SHAPE, "the submesh planner handles at most 65535 devices");
     const size_t per_group = plan_mesh_ws_per_group(t->dev.L, od->S_max, t->total_devices);
-    const int groups = n_mesh_groups(ctx, od->C, per_group, plan_mesh_threads(t->dev.L, t->total_devices));
+    const int threads = plan_mesh_threads(t->dev.L, t->total_devices, od->C, ctx->n_cu);
+    const int groups = n_mesh_groups(ctx, od->C, per_group, threads);
     const size_t need = 256 + size_t(groups) * per_group;
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0)
         return fail(ctx, HARP_ERR_WORKSPACE, "workspace must be a 256-byte aligned device pointer");
@@ -476,9 +479,43 @@ int harp_plan_mesh_h1f1b_batch(harp_ctx *ctx, harp_tables *t, const harp_orderin
     const OrdDev o = { od->C, od->G_max, od->S_max, od->ord_S, od->ord_G, od->ord_group };
     const PlansDev pl = { out->splits, out->dev_first, out->bottleneck, out->iter_time, out->status };
     launch_plan_mesh_h1f1b(t->dev, o, t_max, pl, stage_group, stage_tp, warmup, use_fast(ctx, t), workspace, groups,
-                           t->total_devices, static_cast<hipStream_t>(hip_stream));
+                           threads, t->total_devices, static_cast<hipStream_t>(hip_stream));
     e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(ctx, e, "launching the submesh H-1F1B kernel");
+    return HARP_OK;
+}
+
+int harp_plan_mesh_h1f1b_sweep_batch(harp_ctx *ctx, harp_tables *t, const harp_orderings *od, int32_t max_caps,
+                                     const harp_plans *out, int32_t *stage_group, int32_t *stage_tp,
+                                     int32_t *warmup, int64_t *t_max_out, int32_t *n_caps, void *workspace,
+                                     size_t workspace_bytes, void *hip_stream) {
+    int rc = check_orderings(ctx, t, od);
+    if (rc != HARP_OK) return rc;
+    if (max_caps < 1) return fail(ctx, HARP_ERR_INVALID_ARG, "max_caps must be >= 1");
+    if (!out || (od->C > 0 && (!out->splits || !out->dev_first || !out->bottleneck || !out->iter_time ||
+                               !out->status || !stage_group || !stage_tp || !warmup || !t_max_out)))
+        return fail(ctx, HARP_ERR_INVALID_ARG, "null array");
+    if (ctx->plan_path == HARP_PATH_FAST32 && !t->fast32)
+        return fail(ctx, HARP_ERR_UNIMPLEMENTED, "the 32-bit path was requested but these tables do not allow it");
+    if (od->C == 0) return HARP_OK;
+    if (t->total_devices > 65535) return fail(ctx, HARP_ERR_SHAPE, "the submesh planner handles at most 65535 devices");
+    const size_t per_group = plan_mesh_ws_per_group(t->dev.L, od->S_max, t->total_devices);
+    const int threads = plan_mesh_threads(t->dev.L, t->total_devices, od->C, ctx->n_cu);
+    const int groups = n_mesh_groups(ctx, od->C, per_group, threads);
+    const size_t need = 256 + size_t(groups) * per_group;
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0)
+        return fail(ctx, HARP_ERR_WORKSPACE, "workspace must be a 256-byte aligned device pointer");
+    if (workspace_bytes < need)
+        return fail(ctx, HARP_ERR_WORKSPACE, "workspace holds %zu bytes, %zu needed", workspace_bytes, need);
+    hipError_t e = hipSetDevice(ctx->device);
+    if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
+    const OrdDev o = { od->C, od->G_max, od->S_max, od->ord_S, od->ord_G, od->ord_group };
+    const PlansDev pl = { out->splits, out->dev_first, out->bottleneck, out->iter_time, out->status };
+    launch_plan_mesh_h1f1b_sweep(t->dev, o, max_caps, pl, stage_group, stage_tp, warmup, t_max_out, n_caps,
+                                 use_fast(ctx, t), workspace, groups, threads, t->total_devices,
+                                 static_cast<hipStream_t>(hip_stream));
+    e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(ctx, e, "launching the submesh H-1F1B sweep kernel");
     return HARP_OK;
 }
 

@@ -102,12 +102,16 @@ struct OrdDev {
 constexpr int kMaxOrderGroups = 1024;   // groups one ordering may list (their offsets sit in LDS)
 void launch_plan_mesh(const TablesDev &tb, const OrdDev &od, const PlansDev &out, int32_t *stage_group,
                       int32_t *stage_tp, int32_t *n_passes, bool exact, bool fast32, void *ws, int n_groups,
-                      int64_t total_devices, hipStream_t st);
+                      int threads, int64_t total_devices, hipStream_t st);
 void launch_plan_mesh_h1f1b(const TablesDev &tb, const OrdDev &od, const int64_t *t_max, const PlansDev &out,
                             int32_t *stage_group, int32_t *stage_tp, int32_t *warmup, bool fast32, void *ws,
-                            int n_groups, int64_t total_devices, hipStream_t st);
+                            int n_groups, int threads, int64_t total_devices, hipStream_t st);
+void launch_plan_mesh_h1f1b_sweep(const TablesDev &tb, const OrdDev &od, int max_caps, const PlansDev &out,
+                                  int32_t *stage_group, int32_t *stage_tp, int32_t *warmup, int64_t *t_max_out,
+                                  int32_t *n_caps, bool fast32, void *ws, int n_groups, int threads,
+                                  int64_t total_devices, hipStream_t st);
 size_t plan_mesh_ws_per_group(int L, int S_max, int64_t total_devices);
-int plan_mesh_threads(int L, int64_t total_devices);
+int plan_mesh_threads(int L, int64_t total_devices, int C, int n_cu);
 size_t plan_fast_ws_bytes(int L, int S_max, int C, int n_groups);
 int plan_fast_groups(int L, int S_max, int n_cu);
 void launch_plan_exact(const TablesDev &tb, const CandDev &cd, const PlansDev &out, int32_t *n_passes,

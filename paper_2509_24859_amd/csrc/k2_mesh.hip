@@ -627,6 +627,46 @@ __device__ __forceinline__ int64_t mesh_h1_pass_fast(const TablesDev &tb, const 
     return v == kNone ? kInf : int64_t(v >> 10);
 }
 
+// Thread 0: follows the back-pointers of the H-1F1B form from (S, 0, all devices) and recomputes the
+// counts by eq. Ni along the plan, from the last stage backwards.
+__device__ __forceinline__ void mesh_h1_backtrack(const TablesDev &tb, const MeshSlice &m, const int32_t *offs,
+                                                  const uint16_t *order, int K, int S, int64_t n_dev, int64_t cap,
+                                                  int32_t *cuts, uint16_t *slot_g, uint8_t *slot_k,
+                                                  int32_t *slot_first, int32_t *count) {
+    const int L = tb.L, W = L + 1, Dtot = offs[K];
+    const int64_t m_cap = tb.M;
+    int i = 0, e = Dtot;
+    for (int slot = 0; slot < S; ++slot) {
+        const int s = S - slot;
+        const uint32_t a = m.arg[(size_t(s - 1) * size_t(n_dev + 1) + size_t(e)) * W + i];
+        int j = int(a & 0xFFFFu);
+        const int q = int(a >> 16) & 7;
+        j = j <= L ? j : L;                     // a finite sum only chains through cuts inside the row
+        const int d0 = Dtot - e;
+        int k = 0;
+        while (k + 1 < K && offs[k + 1] <= d0) ++k;
+        cuts[slot] = i;
+        slot_g[slot] = order[k];
+        slot_k[slot] = uint8_t(q);
+        slot_first[slot] = tb.group_base[order[k]] + (d0 - offs[k]);
+        i = j;
+        e -= tb.tp[q];
+        e = e > 0 ? e : 0;
+    }
+    cuts[S] = L;
+    int64_t n = 0;
+    for (int slot = S - 1; slot >= 0; --slot) {
+        int64_t cut = 0;
+        if (slot < S - 1) {
+            const int64_t link = tb.bw[int64_t(slot_g[slot]) * tb.G + slot_g[slot + 1]];
+            cut = (tb.act_bytes[cuts[slot + 1] - 1] + link - 1) / link;
+        }
+        n += mesh_delta(cut, cap);
+        n = n < m_cap ? n : m_cap;
+        count[slot] = int32_t(n);
+    }
+}
+
 template <bool kFast>
 __device__ __forceinline__ void mesh_h1_body(const TablesDev &tb, const OrdDev &od, const int64_t *t_max,
                                              const PlansDev &out, int32_t *stage_group, int32_t *stage_tp,
@@ -642,7 +682,7 @@ __device__ __forceinline__ void mesh_h1_body(const TablesDev &tb, const OrdDev &
     __shared__ uint8_t slot_k[kMaxStages];
     __shared__ int32_t slot_first[kMaxStages];
     __shared__ int shared_int[2];
-    const int L = tb.L, S_max = od.S_max, W = L + 1;
+    const int L = tb.L, S_max = od.S_max;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nthreads = blockDim.x;
     const MeshSlice m = mesh_slice(ws, per_group, L, n_dev);
     const int64_t m_cap = tb.M;
@@ -688,39 +728,7 @@ __device__ __forceinline__ void mesh_h1_body(const TablesDev &tb, const OrdDev &
         if constexpr (kFast) sum = mesh_h1_pass_fast(tb, m, offs, order, group_at, sums_lds, K, S, n_dev, cap);
         else sum = mesh_h1_pass(tb, m, offs, order, group_at, K, S, n_dev, cap);
         if (sum == kInf) { fail(HARP_CAND_INFEASIBLE); continue; }
-        if (tid == 0) {
-            int i = 0, e = Dtot;
-            for (int slot = 0; slot < S; ++slot) {
-                const int s = S - slot;
-                const uint32_t a = m.arg[(size_t(s - 1) * size_t(n_dev + 1) + size_t(e)) * W + i];
-                int j = int(a & 0xFFFFu);
-                const int q = int(a >> 16) & 7;
-                j = j <= L ? j : L;                     // a finite sum only chains through cuts inside the row
-                const int d0 = Dtot - e;
-                int k = 0;
-                while (k + 1 < K && offs[k + 1] <= d0) ++k;
-                cuts[slot] = i;
-                slot_g[slot] = order[k];
-                slot_k[slot] = uint8_t(q);
-                slot_first[slot] = tb.group_base[order[k]] + (d0 - offs[k]);
-                i = j;
-                e -= tb.tp[q];
-                e = e > 0 ? e : 0;
-            }
-            cuts[S] = L;
-            // counts by eq. Ni along the plan, from the last stage backwards
-            int64_t n = 0;
-            for (int slot = S - 1; slot >= 0; --slot) {
-                int64_t cut = 0;
-                if (slot < S - 1) {
-                    const int64_t link = tb.bw[int64_t(slot_g[slot]) * tb.G + slot_g[slot + 1]];
-                    cut = (tb.act_bytes[cuts[slot + 1] - 1] + link - 1) / link;
-                }
-                n += mesh_delta(cut, cap);
-                n = n < m_cap ? n : m_cap;
-                count[slot] = int32_t(n);
-            }
-        }
+        if (tid == 0) mesh_h1_backtrack(tb, m, offs, order, K, S, n_dev, cap, cuts, slot_g, slot_k, slot_first, count);
         __syncthreads();
         int32_t *sp = out.splits + int64_t(c) * (S_max + 1);
         int32_t *df = out.dev_first + int64_t(c) * S_max;
@@ -752,6 +760,206 @@ __global__ __launch_bounds__(kMeshMaxThreads) void k2_mesh_h1f1b(TablesDev tb, O
     mesh_h1_body<kFast>(tb, od, t_max, out, stage_group, stage_tp, warmup, ws, per_group, n_dev, ticket);
 }
 
+// The smallest candidate cap above b (section 5.2.4 (2)): candidate caps of an ordering are the
+// stage times of every listed group, usable degree and operator range, and the transfer times of
+// the inner cuts on the links the ordering can use (inside a group, and to the group after it).
+// A stage time grows with its end cut, so per (group, degree, start) a binary search finds the
+// first one above b; transfer times are looked at one by one.  Every thread takes part; kInf when
+// there is none.
+template <bool kFast>
+__device__ __forceinline__ int64_t mesh_next_cap(const TablesDev &tb, const uint16_t *order, int K, int64_t b,
+                                                 unsigned long long *slot) {
+    const int L = tb.L, tid = threadIdx.x, nthreads = blockDim.x;
+    __syncthreads();
+    if (tid == 0) *slot = ~0ull;
+    __syncthreads();
+    unsigned long long least = ~0ull;
+    const int n_rows = K * tb.n_tp;
+    for (int x = tid; x < n_rows * L; x += nthreads) {
+        const int j = x % L, r = x / L, q = r % tb.n_tp, k = r / tb.n_tp;
+        const int g = order[k];
+        const int64_t tp = tb.tp[q];
+        if (tp > tb.group_ndev[g]) continue;
+        const int shift = tb.tp_shift[q];
+        const uint32_t *p32 = kFast ? tb.P32 + (int64_t(g) * tb.n_tp + q) * tb.pitch32 : nullptr;
+        const int64_t *pf = tb.PF(tb.group_type[g]), *pr = tb.PR(g, q);
+        auto time_to = [&](int i) -> int64_t {
+            if (kFast) return int64_t((p32[i] + uint32_t(tp) - 1u - p32[j]) >> shift);
+            const int64_t work = pf[i] - pf[j];
+            return (shift >= 0 ? (work + tp - 1) >> shift : (work + tp - 1) / tp) + (pr[i] - pr[j]);
+        };
+        if (time_to(L) <= b) continue;
+        int lo = j + 1, hi = L;                       // time_to(hi) > b
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (time_to(mid) > b) hi = mid; else lo = mid + 1;
+        }
+        const unsigned long long v = (unsigned long long)time_to(hi);
+        least = v < least ? v : least;
+    }
+    if (L >= 2) {
+        for (int x = tid; x < K * 2 * (L - 1); x += nthreads) {
+            const int i = 1 + x % (L - 1), r = x / (L - 1), k = r >> 1;
+            if ((r & 1) && k + 1 >= K) continue;
+            const int g = order[k], h = (r & 1) ? order[k + 1] : g;
+            int64_t v;
+            if (kFast) {
+                v = tb.CM[(int64_t(g) * tb.G + h) * tb.pitch32 + i];
+            } else {
+                const int64_t link = tb.bw[int64_t(g) * tb.G + h];
+                v = (tb.act_bytes[i - 1] + link - 1) / link;
+            }
+            if (v > b && (unsigned long long)v < least) least = (unsigned long long)v;
+        }
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        const uint32_t lo = __shfl_xor(uint32_t(least), d, 64), hi = __shfl_xor(uint32_t(least >> 32), d, 64);
+        const unsigned long long o = ((unsigned long long)hi << 32) | lo;
+        least = o < least ? o : least;
+    }
+    if ((tid & 63) == 0 && least != ~0ull) atomicMin(slot, least);
+    __syncthreads();
+    const unsigned long long v = *slot;
+    return v == ~0ull ? kInf : int64_t(v);
+}
+
+// The search around the full recurrence (section 5.2.4 (2)): per ordering the classic min-max pass
+// gives the lower end t_S of the sweep (no cap below it admits a plan, and H-1F1B's counts are never
+// below the classic ones); the caps are then taken in increasing order, each one given to the
+// H-1F1B pass; the first cap with a plan fixes t_E = ceil(T / B); the sweep ends past t_E, when the
+// candidate values run out, or after max_caps caps.  Kept: the plan with the smallest
+// T = least sum + (B - 1) cap, the lower cap on equal T.
+template <bool kFast>
+__device__ __forceinline__ void mesh_sweep_body(const TablesDev &tb, const OrdDev &od, int max_caps,
+                                                const PlansDev &out, int32_t *stage_group, int32_t *stage_tp,
+                                                int32_t *warmup, int64_t *t_max_out, int32_t *n_caps,
+                                                unsigned char *ws, size_t per_group, int64_t n_dev, int *ticket) {
+    extern __shared__ __align__(16) unsigned char mesh_lds[];      // fast form: PP and PS (or Q), L + 1 entries each
+    int64_t *sums_lds = reinterpret_cast<int64_t *>(mesh_lds);
+    __shared__ int32_t offs[kMaxOrderGroups + 1];
+    __shared__ uint16_t order[kMaxOrderGroups];
+    __shared__ uint16_t group_at[kMeshGroupTable];
+    __shared__ int32_t cuts[kMaxStages + 1], count[kMaxStages], kept_cuts[kMaxStages + 1], kept_count[kMaxStages];
+    __shared__ uint16_t slot_g[kMaxStages], kept_g[kMaxStages];
+    __shared__ uint8_t slot_k[kMaxStages], kept_k[kMaxStages];
+    __shared__ int32_t slot_first[kMaxStages], kept_first[kMaxStages];
+    __shared__ int shared_int[2];
+    __shared__ unsigned long long next_slot;
+    const int L = tb.L, S_max = od.S_max;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nthreads = blockDim.x;
+    const MeshSlice m = mesh_slice(ws, per_group, L, n_dev);
+    const int64_t m_cap = tb.M;
+
+    for (;;) {
+        __syncthreads();
+        if (tid == 0) shared_int[0] = atomicAdd(ticket, 1);
+        __syncthreads();
+        const int c = shared_int[0];
+        if (c >= od.C) break;
+        const int S = od.ord_S[c], K = od.ord_G[c];
+        const int32_t *og = od.ord_group + int64_t(c) * od.G_max;
+        int32_t *sg = stage_group + int64_t(c) * S_max, *stp = stage_tp + int64_t(c) * S_max;
+        int32_t *wu = warmup + int64_t(c) * S_max;
+        auto fail = [&](int status, int tried) {
+            write_failed(out, c, S_max, status);
+            for (int s = tid; s < S_max; s += nthreads) { sg[s] = -1; stp[s] = -1; wu[s] = -1; }
+            if (tid == 0) {
+                t_max_out[c] = kInf;
+                if (n_caps) n_caps[c] = tried;
+            }
+        };
+        int bad = (S < 1 || S > S_max || K < 1 || K > od.G_max) ? 1 : 0;
+        if (!bad)
+            for (int k = tid; k < K; k += nthreads) {
+                const int g = og[k];
+                if (g < 0 || g >= tb.G) { bad = 1; continue; }
+                for (int q = 0; q < k; ++q)
+                    if (og[q] == g) bad = 1;
+                order[k] = uint16_t(g);
+            }
+        if (__syncthreads_or(bad)) { fail(HARP_CAND_INVALID, 0); continue; }
+        if (tid == 0) {
+            int64_t o = 0;
+            offs[0] = 0;
+            for (int k = 0; k < K; ++k) { o += tb.group_ndev[order[k]]; offs[k + 1] = int32_t(o); }
+        }
+        __syncthreads();
+        const int Dtot = offs[K];
+        if (S > L || S < K || S > Dtot) { fail(HARP_CAND_INFEASIBLE, 0); continue; }
+        if (Dtot <= kMeshGroupTable) {
+            for (int k = 0; k < K; ++k)
+                for (int d = offs[k] + tid; d < offs[k + 1]; d += nthreads) group_at[d] = uint16_t(k);
+        }
+        int64_t t_S;
+        if constexpr (kFast) t_S = mesh_pass_fast<false>(tb, m, offs, order, group_at, sums_lds, K, S, n_dev, 0);
+        else t_S = mesh_pass<false>(tb, m, offs, order, group_at, K, S, n_dev, 0);
+        if (t_S == kInf) { fail(HARP_CAND_INFEASIBLE, 0); continue; }
+        int64_t cap = t_S, t_E = kInf, best_T = kInf, best_cap = kInf;
+        int tried = 0;
+        for (;;) {
+            int64_t sum;
+            if constexpr (kFast) sum = mesh_h1_pass_fast(tb, m, offs, order, group_at, sums_lds, K, S, n_dev, cap);
+            else sum = mesh_h1_pass(tb, m, offs, order, group_at, K, S, n_dev, cap);
+            ++tried;
+            if (sum != kInf) {
+                const int64_t T = sum + (m_cap - 1) * cap;
+                if (t_E == kInf) t_E = (T + m_cap - 1) / m_cap;
+                if (T < best_T) {
+                    best_T = T;
+                    best_cap = cap;
+                    if (tid == 0)
+                        mesh_h1_backtrack(tb, m, offs, order, K, S, n_dev, cap, cuts, slot_g, slot_k, slot_first, count);
+                    __syncthreads();
+                    for (int s = tid; s <= S; s += nthreads) kept_cuts[s] = cuts[s];
+                    for (int s = tid; s < S; s += nthreads) {
+                        kept_g[s] = slot_g[s]; kept_k[s] = slot_k[s]; kept_first[s] = slot_first[s];
+                        kept_count[s] = count[s];
+                    }
+                }
+            }
+            if (tried >= max_caps) break;
+            const int64_t nb = mesh_next_cap<kFast>(tb, order, K, cap, &next_slot);
+            if (nb == kInf || nb > t_E) break;          // t_E is infinite until a cap has a plan
+            cap = nb;
+        }
+        __syncthreads();
+        if (best_T == kInf) { fail(HARP_CAND_INFEASIBLE, tried); continue; }
+        int32_t *sp = out.splits + int64_t(c) * (S_max + 1);
+        int32_t *df = out.dev_first + int64_t(c) * S_max;
+        for (int s = tid; s <= S_max; s += nthreads) sp[s] = s <= S ? kept_cuts[s] : -1;
+        for (int s = tid; s < S_max; s += nthreads) {
+            sg[s] = s < S ? int32_t(kept_g[s]) : -1;
+            stp[s] = s < S ? tb.tp[kept_k[s]] : -1;
+            df[s] = s < S ? kept_first[s] : -1;
+            wu[s] = s < S ? kept_count[s] : -1;
+        }
+        if (wave == 0) {
+            int64_t bott, iter;
+            wave_score_partition(tb, S, kept_g, kept_k, kept_cuts, lane, bott, iter);   // the plan's own bottleneck
+            if (lane == 0) {
+                out.bottleneck[c] = bott;
+                out.iter_time[c] = best_T;
+                out.status[c] = HARP_CAND_OK;
+                t_max_out[c] = best_cap;
+                if (n_caps) n_caps[c] = tried;
+            }
+        }
+    }
+}
+
+template <bool kFast>
+__global__ __launch_bounds__(kMeshMaxThreads) void k2_mesh_h1f1b_sweep(TablesDev tb, OrdDev od, int max_caps,
+                                                                       PlansDev out, int32_t *stage_group,
+                                                                       int32_t *stage_tp, int32_t *warmup,
+                                                                       int64_t *t_max_out, int32_t *n_caps,
+                                                                       unsigned char *ws, size_t per_group,
+                                                                       int64_t n_dev, int *ticket) {
+    mesh_sweep_body<kFast>(tb, od, max_caps, out, stage_group, stage_tp, warmup, t_max_out, n_caps, ws, per_group,
+                           n_dev, ticket);
+}
+
+
 __global__ void k2_mesh_clear(int *ticket) {
     if (threadIdx.x == 0) *ticket = 0;
 }
@@ -760,8 +968,12 @@ __global__ void k2_mesh_clear(int *ticket) {
 
 // A stage has up to L x devices target cells: small tables get many small workgroups (more
 // orderings in flight), large ones few large workgroups (more lanes per ordering).
-int plan_mesh_threads(int L, int64_t total_devices) {
-    return int64_t(L + 1) * (total_devices + 1) >= 16384 ? kMeshMaxThreads : 256;
+int plan_mesh_threads(int L, int64_t total_devices, int C, int n_cu) {
+    if (int64_t(L + 1) * (total_devices + 1) >= 16384) return kMeshMaxThreads;
+    // a batch too small to fill the chip with 256-thread workgroups gets more lanes per ordering
+    if (C <= 2 * n_cu) return kMeshMaxThreads;
+    if (C <= 4 * n_cu) return 512;
+    return 256;
 }
 
 // Per-workgroup slice: two rows of the table, the back-pointers, and (first slice only) the ticket.
@@ -773,12 +985,12 @@ size_t plan_mesh_ws_per_group(int L, int S_max, int64_t total_devices) {
 
 void launch_plan_mesh(const TablesDev &tb, const OrdDev &od, const PlansDev &out, int32_t *stage_group,
                       int32_t *stage_tp, int32_t *n_passes, bool exact, bool fast32, void *ws, int n_groups,
-                      int64_t total_devices, hipStream_t st) {
+                      int threads, int64_t total_devices, hipStream_t st) {
     // layout: 256 bytes for the ticket, then the slices
     int *ticket = static_cast<int *>(ws);
     unsigned char *slices = static_cast<unsigned char *>(ws) + 256;
     const size_t per_group = plan_mesh_ws_per_group(tb.L, od.S_max, total_devices);
-    const dim3 grid(n_groups), block(plan_mesh_threads(tb.L, total_devices));
+    const dim3 grid(n_groups), block(threads);
     fast32 = fast32 && tb.L <= kMeshFastMaxL;      // the fast form keeps L + 1 memory sums in LDS
     const size_t lds = fast32 ? size_t(tb.L + 1) * sizeof(int64_t) : 0;
     hipLaunchKernelGGL(k2_mesh_clear, dim3(1), dim3(64), 0, st, ticket);
@@ -794,11 +1006,11 @@ void launch_plan_mesh(const TablesDev &tb, const OrdDev &od, const PlansDev &out
 
 void launch_plan_mesh_h1f1b(const TablesDev &tb, const OrdDev &od, const int64_t *t_max, const PlansDev &out,
                             int32_t *stage_group, int32_t *stage_tp, int32_t *warmup, bool fast32, void *ws,
-                            int n_groups, int64_t total_devices, hipStream_t st) {
+                            int n_groups, int threads, int64_t total_devices, hipStream_t st) {
     int *ticket = static_cast<int *>(ws);
     unsigned char *slices = static_cast<unsigned char *>(ws) + 256;
     const size_t per_group = plan_mesh_ws_per_group(tb.L, od.S_max, total_devices);
-    const dim3 grid(n_groups), block(plan_mesh_threads(tb.L, total_devices));
+    const dim3 grid(n_groups), block(threads);
     fast32 = fast32 && tb.L <= kMeshFastMaxL;      // the fast form keeps 2 (L + 1) running sums in LDS
     const size_t lds = fast32 ? 2 * size_t(tb.L + 1) * sizeof(int64_t) : 0;
     hipLaunchKernelGGL(k2_mesh_clear, dim3(1), dim3(64), 0, st, ticket);
@@ -808,6 +1020,25 @@ void launch_plan_mesh_h1f1b(const TablesDev &tb, const OrdDev &od, const int64_t
     else
         hipLaunchKernelGGL(HIP_KERNEL_NAME(k2_mesh_h1f1b<false>), grid, block, 0, st, tb, od, t_max, out,
                            stage_group, stage_tp, warmup, slices, per_group, total_devices, ticket);
+}
+
+void launch_plan_mesh_h1f1b_sweep(const TablesDev &tb, const OrdDev &od, int max_caps, const PlansDev &out,
+                                  int32_t *stage_group, int32_t *stage_tp, int32_t *warmup, int64_t *t_max_out,
+                                  int32_t *n_caps, bool fast32, void *ws, int n_groups, int threads,
+                                  int64_t total_devices, hipStream_t st) {
+    int *ticket = static_cast<int *>(ws);
+    unsigned char *slices = static_cast<unsigned char *>(ws) + 256;
+    const size_t per_group = plan_mesh_ws_per_group(tb.L, od.S_max, total_devices);
+    const dim3 grid(n_groups), block(threads);
+    fast32 = fast32 && tb.L <= kMeshFastMaxL;
+    const size_t lds = fast32 ? 2 * size_t(tb.L + 1) * sizeof(int64_t) : 0;
+    hipLaunchKernelGGL(k2_mesh_clear, dim3(1), dim3(64), 0, st, ticket);
+    if (fast32)
+        hipLaunchKernelGGL(HIP_KERNEL_NAME(k2_mesh_h1f1b_sweep<true>), grid, block, lds, st, tb, od, max_caps, out,
+                           stage_group, stage_tp, warmup, t_max_out, n_caps, slices, per_group, total_devices, ticket);
+    else
+        hipLaunchKernelGGL(HIP_KERNEL_NAME(k2_mesh_h1f1b_sweep<false>), grid, block, lds, st, tb, od, max_caps, out,
+                           stage_group, stage_tp, warmup, t_max_out, n_caps, slices, per_group, total_devices, ticket);
 }
 
 }  // namespace harp

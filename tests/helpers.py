@@ -133,6 +133,25 @@ def oracle_plan_mesh_h1f1b_threaded(tables, orders, t_max, threads=None):
     return out
 
 
+def oracle_plan_mesh_h1f1b_sweep_threaded(tables, orders, max_caps=1 << 20, threads=None):
+    """Oracle answers of the search around the full recurrence for a batch of orderings."""
+    import os
+    from concurrent.futures import ThreadPoolExecutor
+
+    import oracle
+    threads = threads or min(16, len(os.sched_getaffinity(0)))
+    out = oracle.Plans(orders.C, orders.S_max)
+    out.stage_group = np.full((orders.C, orders.S_max), -1, dtype=np.int32)
+    out.stage_tp = np.full((orders.C, orders.S_max), -1, dtype=np.int32)
+    out.warmup = np.full((orders.C, orders.S_max), -1, dtype=np.int32)
+    out.t_max = np.full(orders.C, oracle.INF, dtype=np.int64)
+    out.n_caps = np.zeros(orders.C, dtype=np.int32)
+    with ThreadPoolExecutor(threads) as ex:
+        list(ex.map(lambda c: oracle.plan_mesh_h1f1b_sweep_batch(tables, orders, max_caps, c, c + 1, out),
+                    range(orders.C)))
+    return out
+
+
 def assert_plans_equal(got, want, label=""):
     """Bit-exact comparison of every output array of a batch."""
     for name in ("status", "splits", "dev_first", "bottleneck", "iter_time"):

@@ -6,8 +6,8 @@ import pytest
 import oracle
 from paper_2509_24859_amd import workloads as W
 
-from helpers import (assert_plans_equal, cands_from_lists, oracle_plan_mesh_h1f1b_threaded,
-                     oracle_plan_mesh_threaded, simple_problem)
+from helpers import (assert_plans_equal, cands_from_lists, oracle_plan_mesh_h1f1b_sweep_threaded,
+                     oracle_plan_mesh_h1f1b_threaded, oracle_plan_mesh_threaded, simple_problem)
 
 pytestmark = pytest.mark.gpu
 
@@ -256,3 +256,56 @@ def test_mesh_h1f1b_full_recurrence(harp, ctx):
             hot, _ = harp.plan_h1f1b(ctx, p, cands, [k])
             for name in ("status", "splits", "dev_first", "warmup", "bottleneck", "iter_time"):
                 assert (getattr(mesh, name) == getattr(hot, name)).all(), (seed, name)
+
+
+def _check_sweep(harp, ctx, problem, orders, label, max_caps=1 << 20):
+    want = oracle_plan_mesh_h1f1b_sweep_threaded(oracle.build_tables(problem), orders, max_caps)
+    fast32 = harp.Tables(ctx, problem).fast32
+    for path in [harp.PATH_GENERIC] + ([harp.PATH_FAST32] if fast32 else []):
+        tag = "%s (path %d)" % (label, path)
+        got, _ = harp.plan_mesh_h1f1b_sweep(ctx, problem, orders, max_caps, path)
+        assert_plans_equal(got, want, tag)
+        for name in ("stage_group", "stage_tp", "warmup", "t_max", "n_caps"):
+            a, b = getattr(got, name), getattr(want, name)
+            if not (a == b).all():
+                bad = np.nonzero((a != b).reshape(a.shape[0], -1).any(axis=1))[0]
+                raise AssertionError("%s: %s differs at %d orderings, first %d: got %s want %s"
+                                     % (tag, name, bad.size, bad[0], a[bad[0]], b[bad[0]]))
+    return got, want
+
+
+def test_mesh_h1f1b_sweep(harp, ctx):
+    """The search of section 5.2.4 (2) around the full recurrence (caps swept from the smallest
+    feasible one to ceil(T / B)) against the oracle: plans, counts, chosen cap and caps tried."""
+    feasible = moved = 0
+    for seed in range(120):
+        w = W.random_small(seed)
+        p = w.problem
+        top = min(8, int(p.group_ndev.sum()))
+        orders = W.make_orderings(p, seed, 5, 1, max(top, p.G), 0, 8)
+        got, want = _check_sweep(harp, ctx, p, orders, "seed %d" % seed)
+        ok = want.status == oracle.OK
+        feasible += int(ok.sum())
+        mm, _ = harp.plan_mesh(ctx, p, orders)
+        moved += int((want.t_max[ok] != mm.bottleneck[ok]).sum())
+        if seed % 10 == 0:                                       # a limit on the caps tried
+            _check_sweep(harp, ctx, p, orders, "seed %d, 3 caps" % seed, max_caps=3)
+    assert feasible > 400 and moved > 20
+    # statuses: malformed and infeasible orderings, an empty batch
+    p = simple_problem([1] * 6, G=3, ndev=(2, 1, 1), tp=(1, 2), bw=np.ones((3, 3)))
+    lists = [(3, [0, 1, 2]), (4, [2, 0, 1]), (2, [0, 1, 2]), (5, [0, 1, 2]), (3, [0, 0, 1]), (3, [0, 3]),
+             (0, [0]), (3, [1, 2])]
+    _, want = _check_sweep(harp, ctx, p, W.orderings_from_lists(lists, S_max=6), "statuses")
+    assert list(want.status) == [0, 0, 1, 1, 2, 2, 2, 1]
+    got, _ = harp.plan_mesh_h1f1b_sweep(ctx, p, W.orderings_from_lists(lists, S_max=6).slice(0, 0))
+    assert got.status.shape == (0,)
+    for name, n in (("tiny", 16), ("llama7b", 24)):
+        w = W.make(name)
+        orders = W.make_orderings(w.problem, w.seed, w.config_id, w.problem.G, w.S_max, 0, n)
+        got, want = _check_sweep(harp, ctx, w.problem, orders, name)
+        ok = want.status == oracle.OK
+        assert ok.any()
+        # the answer is the recurrence's plan at the chosen cap
+        at, _ = harp.plan_mesh_h1f1b(ctx, w.problem, orders, np.where(ok, want.t_max, -1))
+        for field in ("splits", "warmup", "iter_time", "stage_tp"):
+            assert (getattr(at, field)[ok] == getattr(got, field)[ok]).all(), (name, field)
