@@ -302,7 +302,9 @@ def mesh_search(ctx, binding, torch, workloads, name, n_orders, reps, cpu_orders
     wu = torch.empty_like(sg)
     ms_h = timed_ms(torch, lambda: binding.harp_plan_mesh_h1f1b_batch(ctx, tables, do, caps, out_h, sg, st, wu, ws), reps)
     res["h1f1b_ms_per_call"] = ms_h
-    res["h1f1b_feasible_fraction"] = float((out_h.to_host().status == 0).mean())
+    got_h = out_h.to_host()
+    got_h.warmup = wu.cpu().numpy()
+    res["h1f1b_feasible_fraction"] = float((got_h.status == 0).mean())
     # the exact form: the capped least-sum pass walked over the caps
     npass = torch.empty(do.C, dtype=torch.int32, device=ctx.device)
     out_e = binding.DevicePlans(ctx, do.C, do.S_max)
@@ -376,9 +378,34 @@ def mesh_search(ctx, binding, torch, workloads, name, n_orders, reps, cpu_orders
                 raise SystemExit("GPU submesh plans differ from the oracle in %s on the baseline sample" % field)
         if not (want.stage_tp == st[:n].cpu().numpy()).all() or not (want.stage_group == sg[:n].cpu().numpy()).all():
             raise SystemExit("GPU submesh slicings differ from the oracle on the baseline sample")
+        # the H-1F1B form and the exact form of the same launches, on shorter prefixes (their oracles are slower)
+        n_h, n_e = min(n, 64), min(n, 16)
+        want_h = oracle.Plans(n_h, sub.S_max)
+        want_h.stage_group = np.full((n_h, sub.S_max), -1, dtype=np.int32)
+        want_h.stage_tp = np.full((n_h, sub.S_max), -1, dtype=np.int32)
+        want_h.warmup = np.full((n_h, sub.S_max), -1, dtype=np.int32)
+        sub_h, sub_e = orders.slice(0, n_h), orders.slice(0, n_e)
+        want_e = oracle.Plans(n_e, sub.S_max)
+        want_e.stage_group = np.full((n_e, sub.S_max), -1, dtype=np.int32)
+        want_e.stage_tp = np.full((n_e, sub.S_max), -1, dtype=np.int32)
+        want_e.n_caps = np.zeros(n_e, dtype=np.int32)
+        t1 = time.perf_counter()
+        with ThreadPoolExecutor(cores) as ex:
+            list(ex.map(lambda c: oracle.plan_mesh_h1f1b_batch(ot, sub_h, caps_host[:n_h], c, c + 1, want_h), range(n_h)))
+            list(ex.map(lambda c: oracle.plan_mesh_batch(ot, sub_e, c, c + 1, want_e, True), range(n_e)))
+        dt1 = time.perf_counter() - t1
+        for field in ("status", "splits", "dev_first", "bottleneck", "iter_time"):
+            if not (getattr(want_h, field) == getattr(got_h, field)[:n_h]).all():
+                raise SystemExit("GPU submesh H-1F1B plans differ from the oracle in %s on the baseline sample" % field)
+            if not (getattr(want_e, field) == getattr(got_e, field)[:n_e]).all():
+                raise SystemExit("GPU submesh exact plans differ from the oracle in %s on the baseline sample" % field)
+        if not (want_h.warmup == got_h.warmup[:n_h]).all():
+            raise SystemExit("GPU submesh H-1F1B counts differ from the oracle on the baseline sample")
         res["cpu_baseline"] = {"value": n / dt, "unit": "orderings/s", "cores": cores, "kind": "oracle",
                                "sample": "first %d orderings over %d threads, %.1f s wall; GPU answers for the "
-                                         "sample verified bit-exact" % (n, cores, dt)}
+                                         "sample verified bit-exact; also the H-1F1B form on the first %d and "
+                                         "the exact form on the first %d (%.1f s wall, %d caps swept per "
+                                         "ordering on average)" % (n, cores, dt, n_h, n_e, dt1, want_e.n_caps.mean())}
     return res
 
 
