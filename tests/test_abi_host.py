@@ -92,3 +92,36 @@ def test_header_is_plain_c99(tmp_path):
                         "-I", os.path.join(ROOT, "include"), "-fsyntax-only", str(src)],
                        capture_output=True, text=True)
     assert r.returncode == 0, r.stderr
+
+
+def test_a_c_program_links_and_calls_the_library(tmp_path):
+    """A plain C translation unit, compiled with gcc, links against the shared library and calls
+    entry points that need no GPU (argument checks and the table-size query)."""
+    import subprocess
+    from paper_2509_24859_amd import binding
+    _library()
+    src = tmp_path / "client.c"
+    src.write_text('#include <stdio.h>\n#include "harp.h"\n'
+                   "int main(void) {\n"
+                   "    int32_t tp[2] = {1, 2};\n"
+                   "    harp_problem p = {0};\n"
+                   "    p.L = 8; p.T = 2; p.G = 2; p.M = 4; p.ar_count = 4; p.n_tp = 2; p.tp_degrees = tp;\n"
+                   '    printf("%zu %d %s\\n", harp_tables_bytes(&p), harp_set_plan_path(NULL, 0), harp_last_error(NULL));\n'
+                   "    p.L = 0;\n"
+                   '    printf("%zu\\n", harp_tables_bytes(&p));\n'
+                   "    return 0;\n"
+                   "}\n")
+    exe = tmp_path / "client"
+    libdir = os.path.dirname(binding.LIB_PATH)
+    libname = os.path.basename(binding.LIB_PATH)
+    r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), str(src),
+                        "-o", str(exe), "-L", libdir, "-l:" + libname, "-Wl,-rpath," + libdir,
+                        "-Wl,-rpath,/opt/rocm/lib", "-Wl,--allow-shlib-undefined"],
+                       capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    r = subprocess.run([str(exe)], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0, r.stderr
+    first, second = r.stdout.strip().splitlines()
+    size, rc, msg = first.split(" ", 2)
+    assert int(size) > 0 and int(rc) == binding.ERR_INVALID_ARG and msg == "null context"
+    assert int(second) == 0
