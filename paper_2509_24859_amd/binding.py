@@ -73,6 +73,9 @@ def load_library() -> C.CDLL:
     if not os.path.exists(LIB_PATH):
         raise RuntimeError("%s is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
                            "(or paper_2509_24859_amd.build.build_library()) first" % LIB_PATH)
+    # torch first: it brings its own HIP runtime, and the library must bind to that same runtime
+    # (device pointers and streams are torch's), not load a second one beside it
+    _torch()
     lib = C.CDLL(LIB_PATH)
     vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
     lib.harp_create.argtypes = [C.POINTER(vp), C.c_int]
