@@ -143,6 +143,30 @@ int n_mesh_groups(const harp_ctx *ctx, int C, size_t per_group, int threads) {
     return n < 1 ? 1 : int(n);
 }
 
+// The search over the cap puts W workgroups on one ordering when the batch alone would leave
+// compute units idle; its workspace holds the slices of the resident workgroups and W + 1 kept
+// plans per ordering.
+struct SweepLayout {
+    int threads, groups, W;
+    size_t per_group, bytes;
+};
+SweepLayout sweep_layout(const harp_ctx *ctx, const harp_tables *t, const harp_orderings *od) {
+    SweepLayout s;
+    s.per_group = plan_mesh_ws_per_group(t->dev.L, od->S_max, t->total_devices);
+    s.threads = plan_mesh_threads(t->dev.L, t->total_devices, od->C, ctx->n_cu);
+    long long resident = (long long)ctx->n_cu * (2048 / s.threads);
+    const long long fit = (long long)((size_t(16) << 30) / (s.per_group ? s.per_group : 1));
+    if (resident > fit) resident = fit;
+    if (resident < 1) resident = 1;
+    const long long C = od->C > 0 ? od->C : 1;
+    long long W = resident / C;
+    W = W < 1 ? 1 : (W > 32 ? 32 : W);
+    s.W = int(W);
+    s.groups = int(resident < C * W ? resident : C * W);
+    s.bytes = 256 + size_t(s.groups) * s.per_group + size_t(C) * size_t(W + 1) * plan_mesh_sweep_slot_bytes(od->S_max);
+    return s;
+}
+
 int check_orderings(harp_ctx *ctx, harp_tables *t, const harp_orderings *od) {
     if (!ctx) return HARP_ERR_INVALID_ARG;
     if (!t || !od) return fail(ctx, HARP_ERR_INVALID_ARG, "null tables or orderings");
@@ -402,9 +426,7 @@ int harp_plan_h1f1b_batch(harp_ctx *ctx, harp_tables *t, const harp_candidates *
 
 size_t harp_plan_mesh_workspace_bytes(harp_ctx *ctx, harp_tables *t, const harp_orderings *od) {
     if (check_orderings(ctx, t, od) != HARP_OK) return 0;
-    const size_t per_group = plan_mesh_ws_per_group(t->dev.L, od->S_max, t->total_devices);
-    return 256 + size_t(n_mesh_groups(ctx, od->C, per_group,
-                                      plan_mesh_threads(t->dev.L, t->total_devices, od->C, ctx->n_cu))) * per_group;
+    return sweep_layout(ctx, t, od).bytes;    // the largest need of the entry points that share it
 }
 
 }  // extern "C"
@@ -499,10 +521,8 @@ int harp_plan_mesh_h1f1b_sweep_batch(harp_ctx *ctx, harp_tables *t, const harp_o
         return fail(ctx, HARP_ERR_UNIMPLEMENTED, "the 32-bit path was requested but these tables do not allow it");
     if (od->C == 0) return HARP_OK;
     if (t->total_devices > 65535) return fail(ctx, HARP_ERR_SHAPE, "the submesh planner handles at most 65535 devices");
-    const size_t per_group = plan_mesh_ws_per_group(t->dev.L, od->S_max, t->total_devices);
-    const int threads = plan_mesh_threads(t->dev.L, t->total_devices, od->C, ctx->n_cu);
-    const int groups = n_mesh_groups(ctx, od->C, per_group, threads);
-    const size_t need = 256 + size_t(groups) * per_group;
+    const SweepLayout lay = sweep_layout(ctx, t, od);
+    const size_t need = lay.bytes;
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0)
         return fail(ctx, HARP_ERR_WORKSPACE, "workspace must be a 256-byte aligned device pointer");
     if (workspace_bytes < need)
@@ -512,7 +532,7 @@ int harp_plan_mesh_h1f1b_sweep_batch(harp_ctx *ctx, harp_tables *t, const harp_o
     const OrdDev o = { od->C, od->G_max, od->S_max, od->ord_S, od->ord_G, od->ord_group };
     const PlansDev pl = { out->splits, out->dev_first, out->bottleneck, out->iter_time, out->status };
     launch_plan_mesh_h1f1b_sweep(t->dev, o, max_caps, pl, stage_group, stage_tp, warmup, t_max_out, n_caps,
-                                 use_fast(ctx, t), workspace, groups, threads, t->total_devices,
+                                 use_fast(ctx, t), workspace, lay.groups, lay.threads, lay.W, t->total_devices,
                                  static_cast<hipStream_t>(hip_stream));
     e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(ctx, e, "launching the submesh H-1F1B sweep kernel");

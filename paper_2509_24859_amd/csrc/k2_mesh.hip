@@ -824,51 +824,96 @@ __device__ __forceinline__ int64_t mesh_next_cap(const TablesDev &tb, const uint
     return v == ~0ull ? kInf : int64_t(v);
 }
 
-// The search around the full recurrence (section 5.2.4 (2)): per ordering the classic min-max pass
-// gives the lower end t_S of the sweep (no cap below it admits a plan, and H-1F1B's counts are never
-// below the classic ones); the caps are then taken in increasing order, each one given to the
-// H-1F1B pass; the first cap with a plan fixes t_E = ceil(T / B); the sweep ends past t_E, when the
-// candidate values run out, or after max_caps caps.  Kept: the plan with the smallest
-// T = least sum + (B - 1) cap, the lower cap on equal T.
-template <bool kFast>
-__device__ __forceinline__ void mesh_sweep_body(const TablesDev &tb, const OrdDev &od, int max_caps,
-                                                const PlansDev &out, int32_t *stage_group, int32_t *stage_tp,
-                                                int32_t *warmup, int64_t *t_max_out, int32_t *n_caps,
-                                                unsigned char *ws, size_t per_group, int64_t n_dev, int *ticket) {
+// The search around the full recurrence (section 5.2.4 (2)) in three launches, so that the caps of
+// one ordering can be tried by several workgroups at once (the batched evaluation of 5.2.4 (3)):
+//  first:  one workgroup per ordering; the classic min-max pass gives the lower end t_S of the
+//          sweep (no cap below it admits a plan, and H-1F1B's counts are never below the classic
+//          ones); the caps are then taken in increasing order until one has a plan, which fixes
+//          t_E = ceil(T / B);
+//  rest:   W workgroups per ordering; each walks ALL later caps up to t_E (finding the next cap
+//          costs a few percent of a pass) and runs the H-1F1B pass on every W-th of them, keeping
+//          its best plan;
+//  pick:   per ordering the smallest T = least sum + (B - 1) cap over the W + 1 kept plans, the
+//          lower cap on equal T; that is what trying the caps one after the other returns.
+// The k-th cap tried has index k whoever tries it, so the limit max_caps cuts the sweep at the
+// same cap for every W.
+struct SweepHead {
+    int64_t T, cap;
+    int32_t tried, state;    // state: kSweepNone, kSweepPlan, or kSweepFailed + a candidate status
+    int32_t pad[2];
+};
+constexpr int kSweepNone = 0, kSweepPlan = 1, kSweepFailed = 16;
+
+// One kept plan: head | cuts [S_max + 1] | first device [S_max] | count [S_max] (int32) | group
+// [S_max] (uint16) | degree index [S_max] (uint8), rounded up to 16 bytes.
+__host__ __device__ inline size_t sweep_slot_bytes(int S_max) {
+    const size_t b = sizeof(SweepHead) + 4 * size_t(3 * S_max + 1) + 2 * size_t(S_max) + size_t(S_max);
+    return (b + 15) & ~size_t(15);
+}
+struct SweepSlot {
+    SweepHead *head;
+    int32_t *cuts, *first, *count;
+    uint16_t *g;
+    uint8_t *k;
+};
+__device__ __forceinline__ SweepSlot sweep_slot(unsigned char *slots, int S_max, int W, int c, int j) {
+    unsigned char *base = slots + (size_t(c) * size_t(W + 1) + size_t(j)) * sweep_slot_bytes(S_max);
+    SweepSlot t;
+    t.head = reinterpret_cast<SweepHead *>(base);
+    t.cuts = reinterpret_cast<int32_t *>(base + sizeof(SweepHead));
+    t.first = t.cuts + (S_max + 1);
+    t.count = t.first + S_max;
+    t.g = reinterpret_cast<uint16_t *>(t.count + S_max);
+    t.k = reinterpret_cast<uint8_t *>(t.g + S_max);
+    return t;
+}
+
+// kRest = false: the first launch (ticket over orderings).  kRest = true: the second (ticket over
+// ordering x W).
+template <bool kFast, bool kRest>
+__device__ __forceinline__ void mesh_sweep_body(const TablesDev &tb, const OrdDev &od, int max_caps, int W,
+                                                unsigned char *slots, unsigned char *ws, size_t per_group,
+                                                int64_t n_dev, int *ticket) {
     extern __shared__ __align__(16) unsigned char mesh_lds[];      // fast form: PP and PS (or Q), L + 1 entries each
     int64_t *sums_lds = reinterpret_cast<int64_t *>(mesh_lds);
     __shared__ int32_t offs[kMaxOrderGroups + 1];
     __shared__ uint16_t order[kMaxOrderGroups];
     __shared__ uint16_t group_at[kMeshGroupTable];
-    __shared__ int32_t cuts[kMaxStages + 1], count[kMaxStages], kept_cuts[kMaxStages + 1], kept_count[kMaxStages];
-    __shared__ uint16_t slot_g[kMaxStages], kept_g[kMaxStages];
-    __shared__ uint8_t slot_k[kMaxStages], kept_k[kMaxStages];
-    __shared__ int32_t slot_first[kMaxStages], kept_first[kMaxStages];
+    __shared__ int32_t cuts[kMaxStages + 1], count[kMaxStages];
+    __shared__ uint16_t slot_g[kMaxStages];
+    __shared__ uint8_t slot_k[kMaxStages];
+    __shared__ int32_t slot_first[kMaxStages];
     __shared__ int shared_int[2];
     __shared__ unsigned long long next_slot;
     const int L = tb.L, S_max = od.S_max;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nthreads = blockDim.x;
+    const int tid = threadIdx.x, nthreads = blockDim.x;
     const MeshSlice m = mesh_slice(ws, per_group, L, n_dev);
     const int64_t m_cap = tb.M;
+    const int n_items = kRest ? od.C * W : od.C;
 
     for (;;) {
         __syncthreads();
         if (tid == 0) shared_int[0] = atomicAdd(ticket, 1);
         __syncthreads();
-        const int c = shared_int[0];
-        if (c >= od.C) break;
+        const int item = shared_int[0];
+        if (item >= n_items) break;
+        const int c = kRest ? item / W : item, j = kRest ? item - c * W : W;
+        const SweepSlot mine = sweep_slot(slots, S_max, W, c, j);
+        const SweepSlot opening = sweep_slot(slots, S_max, W, c, W);
+        auto leave = [&](int state, int tried) {
+            if (tid == 0) { mine.head->T = kInf; mine.head->cap = kInf; mine.head->tried = tried; mine.head->state = state; }
+        };
+        int64_t cap = 0, t_E = kInf;
+        int tried = 0;
+        if (kRest) {
+            // what the first launch found for this ordering (written before this kernel started)
+            if (opening.head->state != kSweepPlan) { leave(kSweepNone, opening.head->tried); continue; }
+            cap = opening.head->cap;
+            tried = opening.head->tried;
+            t_E = (opening.head->T + m_cap - 1) / m_cap;
+        }
         const int S = od.ord_S[c], K = od.ord_G[c];
         const int32_t *og = od.ord_group + int64_t(c) * od.G_max;
-        int32_t *sg = stage_group + int64_t(c) * S_max, *stp = stage_tp + int64_t(c) * S_max;
-        int32_t *wu = warmup + int64_t(c) * S_max;
-        auto fail = [&](int status, int tried) {
-            write_failed(out, c, S_max, status);
-            for (int s = tid; s < S_max; s += nthreads) { sg[s] = -1; stp[s] = -1; wu[s] = -1; }
-            if (tid == 0) {
-                t_max_out[c] = kInf;
-                if (n_caps) n_caps[c] = tried;
-            }
-        };
         int bad = (S < 1 || S > S_max || K < 1 || K > od.G_max) ? 1 : 0;
         if (!bad)
             for (int k = tid; k < K; k += nthreads) {
@@ -878,7 +923,7 @@ __device__ __forceinline__ void mesh_sweep_body(const TablesDev &tb, const OrdDe
                     if (og[q] == g) bad = 1;
                 order[k] = uint16_t(g);
             }
-        if (__syncthreads_or(bad)) { fail(HARP_CAND_INVALID, 0); continue; }
+        if (__syncthreads_or(bad)) { leave(kSweepFailed + HARP_CAND_INVALID, 0); continue; }
         if (tid == 0) {
             int64_t o = 0;
             offs[0] = 0;
@@ -886,82 +931,132 @@ __device__ __forceinline__ void mesh_sweep_body(const TablesDev &tb, const OrdDe
         }
         __syncthreads();
         const int Dtot = offs[K];
-        if (S > L || S < K || S > Dtot) { fail(HARP_CAND_INFEASIBLE, 0); continue; }
+        if (S > L || S < K || S > Dtot) { leave(kSweepFailed + HARP_CAND_INFEASIBLE, 0); continue; }
         if (Dtot <= kMeshGroupTable) {
             for (int k = 0; k < K; ++k)
                 for (int d = offs[k] + tid; d < offs[k + 1]; d += nthreads) group_at[d] = uint16_t(k);
         }
-        int64_t t_S;
-        if constexpr (kFast) t_S = mesh_pass_fast<false>(tb, m, offs, order, group_at, sums_lds, K, S, n_dev, 0);
-        else t_S = mesh_pass<false>(tb, m, offs, order, group_at, K, S, n_dev, 0);
-        if (t_S == kInf) { fail(HARP_CAND_INFEASIBLE, 0); continue; }
-        int64_t cap = t_S, t_E = kInf, best_T = kInf, best_cap = kInf;
-        int tried = 0;
-        for (;;) {
-            int64_t sum;
-            if constexpr (kFast) sum = mesh_h1_pass_fast(tb, m, offs, order, group_at, sums_lds, K, S, n_dev, cap);
-            else sum = mesh_h1_pass(tb, m, offs, order, group_at, K, S, n_dev, cap);
-            ++tried;
-            if (sum != kInf) {
+        auto h1_pass = [&](int64_t at) -> int64_t {
+            if constexpr (kFast) return mesh_h1_pass_fast(tb, m, offs, order, group_at, sums_lds, K, S, n_dev, at);
+            else return mesh_h1_pass(tb, m, offs, order, group_at, K, S, n_dev, at);
+        };
+        // thread 0 backtracks the pass just run; everyone copies the plan to this item's slot
+        auto keep = [&](int64_t at, int64_t T) {
+            if (tid == 0)
+                mesh_h1_backtrack(tb, m, offs, order, K, S, n_dev, at, cuts, slot_g, slot_k, slot_first, count);
+            __syncthreads();
+            for (int s = tid; s <= S; s += nthreads) mine.cuts[s] = cuts[s];
+            for (int s = tid; s < S; s += nthreads) {
+                mine.g[s] = slot_g[s]; mine.k[s] = slot_k[s]; mine.first[s] = slot_first[s]; mine.count[s] = count[s];
+            }
+            if (tid == 0) { mine.head->T = T; mine.head->cap = at; }
+        };
+        if (!kRest) {
+            int64_t t_S;
+            if constexpr (kFast) t_S = mesh_pass_fast<false>(tb, m, offs, order, group_at, sums_lds, K, S, n_dev, 0);
+            else t_S = mesh_pass<false>(tb, m, offs, order, group_at, K, S, n_dev, 0);
+            if (t_S == kInf) { leave(kSweepFailed + HARP_CAND_INFEASIBLE, 0); continue; }
+            cap = t_S;
+            int state = kSweepFailed + HARP_CAND_INFEASIBLE;
+            for (;;) {
+                const int64_t sum = h1_pass(cap);
+                ++tried;
+                if (sum != kInf) {
+                    keep(cap, sum + (m_cap - 1) * cap);
+                    state = kSweepPlan;
+                    break;
+                }
+                if (tried >= max_caps) break;
+                const int64_t nb = mesh_next_cap<kFast>(tb, order, K, cap, &next_slot);
+                if (nb == kInf) break;
+                cap = nb;
+            }
+            if (state != kSweepPlan) { leave(state, tried); continue; }
+            if (tid == 0) { mine.head->tried = tried; mine.head->state = kSweepPlan; }
+        } else {
+            int64_t best_T = kInf;
+            for (int step = 0; tried < max_caps; ++step) {
+                const int64_t nb = mesh_next_cap<kFast>(tb, order, K, cap, &next_slot);
+                if (nb == kInf || nb > t_E) break;
+                cap = nb;
+                ++tried;
+                if (step % W != j) continue;
+                const int64_t sum = h1_pass(cap);
+                if (sum == kInf) continue;
                 const int64_t T = sum + (m_cap - 1) * cap;
-                if (t_E == kInf) t_E = (T + m_cap - 1) / m_cap;
-                if (T < best_T) {
+                if (T < best_T) {                      // caps rise, so the lower cap keeps an equal T
                     best_T = T;
-                    best_cap = cap;
-                    if (tid == 0)
-                        mesh_h1_backtrack(tb, m, offs, order, K, S, n_dev, cap, cuts, slot_g, slot_k, slot_first, count);
-                    __syncthreads();
-                    for (int s = tid; s <= S; s += nthreads) kept_cuts[s] = cuts[s];
-                    for (int s = tid; s < S; s += nthreads) {
-                        kept_g[s] = slot_g[s]; kept_k[s] = slot_k[s]; kept_first[s] = slot_first[s];
-                        kept_count[s] = count[s];
-                    }
+                    keep(cap, T);
                 }
             }
-            if (tried >= max_caps) break;
-            const int64_t nb = mesh_next_cap<kFast>(tb, order, K, cap, &next_slot);
-            if (nb == kInf || nb > t_E) break;          // t_E is infinite until a cap has a plan
-            cap = nb;
-        }
-        __syncthreads();
-        if (best_T == kInf) { fail(HARP_CAND_INFEASIBLE, tried); continue; }
-        int32_t *sp = out.splits + int64_t(c) * (S_max + 1);
-        int32_t *df = out.dev_first + int64_t(c) * S_max;
-        for (int s = tid; s <= S_max; s += nthreads) sp[s] = s <= S ? kept_cuts[s] : -1;
-        for (int s = tid; s < S_max; s += nthreads) {
-            sg[s] = s < S ? int32_t(kept_g[s]) : -1;
-            stp[s] = s < S ? tb.tp[kept_k[s]] : -1;
-            df[s] = s < S ? kept_first[s] : -1;
-            wu[s] = s < S ? kept_count[s] : -1;
-        }
-        if (wave == 0) {
-            int64_t bott, iter;
-            wave_score_partition(tb, S, kept_g, kept_k, kept_cuts, lane, bott, iter);   // the plan's own bottleneck
-            if (lane == 0) {
-                out.bottleneck[c] = bott;
-                out.iter_time[c] = best_T;
-                out.status[c] = HARP_CAND_OK;
-                t_max_out[c] = best_cap;
-                if (n_caps) n_caps[c] = tried;
-            }
+            if (best_T == kInf) { leave(kSweepNone, tried); continue; }
+            if (tid == 0) { mine.head->tried = tried; mine.head->state = kSweepPlan; }
         }
     }
 }
 
-template <bool kFast>
-__global__ __launch_bounds__(kMeshMaxThreads) void k2_mesh_h1f1b_sweep(TablesDev tb, OrdDev od, int max_caps,
-                                                                       PlansDev out, int32_t *stage_group,
-                                                                       int32_t *stage_tp, int32_t *warmup,
-                                                                       int64_t *t_max_out, int32_t *n_caps,
-                                                                       unsigned char *ws, size_t per_group,
-                                                                       int64_t n_dev, int *ticket) {
-    mesh_sweep_body<kFast>(tb, od, max_caps, out, stage_group, stage_tp, warmup, t_max_out, n_caps, ws, per_group,
-                           n_dev, ticket);
+template <bool kFast, bool kRest>
+__global__ __launch_bounds__(kMeshMaxThreads) void k2_mesh_h1f1b_sweep(TablesDev tb, OrdDev od, int max_caps, int W,
+                                                                       unsigned char *slots, unsigned char *ws,
+                                                                       size_t per_group, int64_t n_dev, int *ticket) {
+    mesh_sweep_body<kFast, kRest>(tb, od, max_caps, W, slots, ws, per_group, n_dev, ticket);
+}
+
+// One wavefront per ordering: the best of its W + 1 kept plans goes to the outputs.
+__global__ __launch_bounds__(256) void k2_mesh_sweep_pick(TablesDev tb, OrdDev od, int W, unsigned char *slots,
+                                                          PlansDev out, int32_t *stage_group, int32_t *stage_tp,
+                                                          int32_t *warmup, int64_t *t_max_out, int32_t *n_caps) {
+    const int lane = threadIdx.x & 63;
+    const int c = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    if (c >= od.C) return;
+    const int S_max = od.S_max;
+    int32_t *sp = out.splits + int64_t(c) * (S_max + 1), *df = out.dev_first + int64_t(c) * S_max;
+    int32_t *sg = stage_group + int64_t(c) * S_max, *stp = stage_tp + int64_t(c) * S_max;
+    int32_t *wu = warmup + int64_t(c) * S_max;
+    const SweepSlot opening = sweep_slot(slots, S_max, W, c, W);
+    if (opening.head->state != kSweepPlan) {
+        for (int s = lane; s <= S_max; s += 64) sp[s] = -1;
+        for (int s = lane; s < S_max; s += 64) { df[s] = -1; sg[s] = -1; stp[s] = -1; wu[s] = -1; }
+        if (lane == 0) {
+            out.bottleneck[c] = kInf;
+            out.iter_time[c] = kInf;
+            out.status[c] = opening.head->state - kSweepFailed;
+            t_max_out[c] = kInf;
+            if (n_caps) n_caps[c] = opening.head->tried;
+        }
+        return;
+    }
+    int best = W;
+    int64_t best_T = opening.head->T, best_cap = opening.head->cap;
+    for (int j = 0; j < W; ++j) {
+        const SweepHead *h = sweep_slot(slots, S_max, W, c, j).head;
+        if (h->state == kSweepPlan && (h->T < best_T || (h->T == best_T && h->cap < best_cap))) {
+            best = j; best_T = h->T; best_cap = h->cap;
+        }
+    }
+    const SweepSlot b = sweep_slot(slots, S_max, W, c, best);
+    const int S = od.ord_S[c];
+    for (int s = lane; s <= S_max; s += 64) sp[s] = s <= S ? b.cuts[s] : -1;
+    for (int s = lane; s < S_max; s += 64) {
+        sg[s] = s < S ? int32_t(b.g[s]) : -1;
+        stp[s] = s < S ? tb.tp[b.k[s]] : -1;
+        df[s] = s < S ? b.first[s] : -1;
+        wu[s] = s < S ? b.count[s] : -1;
+    }
+    int64_t bott, iter;
+    wave_score_partition(tb, S, b.g, b.k, b.cuts, lane, bott, iter);      // the plan's own bottleneck
+    if (lane == 0) {
+        out.bottleneck[c] = bott;
+        out.iter_time[c] = best_T;
+        out.status[c] = HARP_CAND_OK;
+        t_max_out[c] = best_cap;
+        if (n_caps) n_caps[c] = sweep_slot(slots, S_max, W, c, 0).head->tried;
+    }
 }
 
 
 __global__ void k2_mesh_clear(int *ticket) {
-    if (threadIdx.x == 0) *ticket = 0;
+    if (threadIdx.x < 4) ticket[threadIdx.x] = 0;
 }
 
 }  // namespace
@@ -1024,21 +1119,29 @@ void launch_plan_mesh_h1f1b(const TablesDev &tb, const OrdDev &od, const int64_t
 
 void launch_plan_mesh_h1f1b_sweep(const TablesDev &tb, const OrdDev &od, int max_caps, const PlansDev &out,
                                   int32_t *stage_group, int32_t *stage_tp, int32_t *warmup, int64_t *t_max_out,
-                                  int32_t *n_caps, bool fast32, void *ws, int n_groups, int threads,
+                                  int32_t *n_caps, bool fast32, void *ws, int n_groups, int threads, int W,
                                   int64_t total_devices, hipStream_t st) {
+    // layout: 256 bytes for the tickets, n_groups slices, then (W + 1) kept plans per ordering
     int *ticket = static_cast<int *>(ws);
     unsigned char *slices = static_cast<unsigned char *>(ws) + 256;
     const size_t per_group = plan_mesh_ws_per_group(tb.L, od.S_max, total_devices);
-    const dim3 grid(n_groups), block(threads);
+    unsigned char *slots = slices + size_t(n_groups) * per_group;
     fast32 = fast32 && tb.L <= kMeshFastMaxL;
     const size_t lds = fast32 ? 2 * size_t(tb.L + 1) * sizeof(int64_t) : 0;
+    const int first_groups = n_groups < od.C ? n_groups : od.C;
+    const dim3 block(threads);
     hipLaunchKernelGGL(k2_mesh_clear, dim3(1), dim3(64), 0, st, ticket);
-    if (fast32)
-        hipLaunchKernelGGL(HIP_KERNEL_NAME(k2_mesh_h1f1b_sweep<true>), grid, block, lds, st, tb, od, max_caps, out,
-                           stage_group, stage_tp, warmup, t_max_out, n_caps, slices, per_group, total_devices, ticket);
-    else
-        hipLaunchKernelGGL(HIP_KERNEL_NAME(k2_mesh_h1f1b_sweep<false>), grid, block, lds, st, tb, od, max_caps, out,
-                           stage_group, stage_tp, warmup, t_max_out, n_caps, slices, per_group, total_devices, ticket);
+#define HARP_SWEEP_LAUNCH(F)                                                                                  \
+    hipLaunchKernelGGL(HIP_KERNEL_NAME(k2_mesh_h1f1b_sweep<F, false>), dim3(first_groups), block, lds, st, tb, od, \
+                       max_caps, W, slots, slices, per_group, total_devices, ticket);                           \
+    hipLaunchKernelGGL(HIP_KERNEL_NAME(k2_mesh_h1f1b_sweep<F, true>), dim3(n_groups), block, lds, st, tb, od,    \
+                       max_caps, W, slots, slices, per_group, total_devices, ticket + 1)
+    if (fast32) { HARP_SWEEP_LAUNCH(true); } else { HARP_SWEEP_LAUNCH(false); }
+#undef HARP_SWEEP_LAUNCH
+    hipLaunchKernelGGL(k2_mesh_sweep_pick, dim3((od.C + 3) / 4), dim3(256), 0, st, tb, od, W, slots, out,
+                       stage_group, stage_tp, warmup, t_max_out, n_caps);
 }
+
+size_t plan_mesh_sweep_slot_bytes(int S_max) { return sweep_slot_bytes(S_max); }
 
 }  // namespace harp
