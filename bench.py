@@ -322,7 +322,7 @@ def mesh_search(ctx, binding, torch, workloads, name, n_orders, reps, cpu_orders
         out_s = binding.DevicePlans(ctx, ds.C, ds.S_max)
         tm = torch.empty(ds.C, dtype=torch.int64, device=ctx.device)
         nc = torch.empty(ds.C, dtype=torch.int32, device=ctx.device)
-        ws_s = binding.mesh_workspace(ctx, tables, ds)
+        ws_s = binding.mesh_sweep_workspace(ctx, tables, ds)
         sg_s, st_s, wu_s = (torch.empty((ds.C, ds.S_max), dtype=torch.int32, device=ctx.device) for _ in range(3))
         run = lambda cap_limit: binding.harp_plan_mesh_h1f1b_sweep_batch(ctx, tables, ds, cap_limit, out_s, sg_s, st_s,
                                                                          wu_s, tm, ws_s, nc)

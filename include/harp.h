@@ -270,8 +270,11 @@ int harp_plan_mesh_h1f1b_batch(harp_ctx *ctx, harp_tables *tables, const harp_or
  * the smallest T = least sum + (M - 1) cap, the lower cap on equal T.  Outputs as
  * harp_plan_mesh_h1f1b_batch at that cap; t_max_out: DEVICE [C], the cap of the answer (INT64_MAX
  * when there is none); n_caps: DEVICE [C] or NULL, caps tried.  HARP_CAND_INFEASIBLE when no tried
- * cap has a plan.  The work per ordering is caps tried x one harp_plan_mesh_h1f1b_batch pass.
- * Workspace as for harp_plan_mesh_batch. */
+ * cap has a plan.  The work per ordering is caps tried x one harp_plan_mesh_h1f1b_batch pass; when
+ * the batch alone would leave compute units idle, several workgroups share the caps of one ordering
+ * (same results).  Workspace: harp_plan_mesh_sweep_workspace_bytes (the slices of the resident
+ * workgroups plus up to 33 kept plans per ordering), 256-byte aligned, contents irrelevant. */
+size_t harp_plan_mesh_sweep_workspace_bytes(harp_ctx *ctx, harp_tables *tables, const harp_orderings *orders);
 int harp_plan_mesh_h1f1b_sweep_batch(harp_ctx *ctx, harp_tables *tables, const harp_orderings *orders,
                                      int32_t max_caps, const harp_plans *out, int32_t *stage_group,
                                      int32_t *stage_tp, int32_t *warmup, int64_t *t_max_out,

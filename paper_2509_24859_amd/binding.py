@@ -27,7 +27,7 @@ EXPORTS = (
     "harp_set_plan_path", "harp_plan_workspace_bytes", "harp_plan_batch", "harp_plan_exact_batch",
     "harp_plan_h1f1b_batch", "harp_score_h1f1b",
     "harp_plan_mesh_workspace_bytes", "harp_plan_mesh_batch", "harp_plan_mesh_exact_batch", "harp_plan_mesh_h1f1b_batch",
-    "harp_plan_mesh_h1f1b_sweep_batch",
+    "harp_plan_mesh_h1f1b_sweep_batch", "harp_plan_mesh_sweep_workspace_bytes",
     "harp_score_1f1b", "harp_argmin_batch", "harp_measure_valu_int32",
 )
 
@@ -105,6 +105,8 @@ def load_library() -> C.CDLL:
     lib.harp_score_h1f1b.argtypes = [vp, vp, C.POINTER(harp_candidates), vp, vp, vp, vp, vp, vp, vp]
     lib.harp_plan_mesh_workspace_bytes.argtypes = [vp, vp, C.POINTER(harp_orderings)]
     lib.harp_plan_mesh_workspace_bytes.restype = sz
+    lib.harp_plan_mesh_sweep_workspace_bytes.argtypes = [vp, vp, C.POINTER(harp_orderings)]
+    lib.harp_plan_mesh_sweep_workspace_bytes.restype = sz
     lib.harp_plan_mesh_batch.argtypes = [vp, vp, C.POINTER(harp_orderings), C.POINTER(harp_plans), vp, vp, vp, sz, vp]
     lib.harp_plan_mesh_exact_batch.argtypes = [vp, vp, C.POINTER(harp_orderings), C.POINTER(harp_plans), vp, vp, vp,
                                                vp, sz, vp]
@@ -459,7 +461,7 @@ def plan_mesh_h1f1b_sweep(ctx: Context, problem, orders, max_caps: int = 1 << 20
     wu = torch.full((max(do.C, 1), do.S_max), -7, dtype=torch.int32, device=ctx.device)
     tm = torch.full((max(do.C, 1),), -7, dtype=torch.int64, device=ctx.device)
     nc = torch.full((max(do.C, 1),), -7, dtype=torch.int32, device=ctx.device)
-    ws = mesh_workspace(ctx, tables, do)
+    ws = mesh_sweep_workspace(ctx, tables, do)
     ctx.set_plan_path(path)
     try:
         harp_plan_mesh_h1f1b_sweep_batch(ctx, tables, do, max_caps, out, sg, st, wu, tm, ws, nc)
@@ -478,6 +480,14 @@ def plan_mesh_h1f1b_sweep(ctx: Context, problem, orders, max_caps: int = 1 << 20
 def mesh_workspace(ctx: Context, tables: Tables, do: DeviceOrderings):
     torch = _torch()
     n = ctx.lib.harp_plan_mesh_workspace_bytes(ctx.handle, tables.handle, C.byref(do.c))
+    if n == 0:
+        raise HarpError(ERR_INVALID_ARG, ctx.lib.harp_last_error(ctx.handle).decode() or "malformed orderings")
+    return torch.empty(n, dtype=torch.uint8, device=ctx.device)
+
+
+def mesh_sweep_workspace(ctx: Context, tables: Tables, do: DeviceOrderings):
+    torch = _torch()
+    n = ctx.lib.harp_plan_mesh_sweep_workspace_bytes(ctx.handle, tables.handle, C.byref(do.c))
     if n == 0:
         raise HarpError(ERR_INVALID_ARG, ctx.lib.harp_last_error(ctx.handle).decode() or "malformed orderings")
     return torch.empty(n, dtype=torch.uint8, device=ctx.device)

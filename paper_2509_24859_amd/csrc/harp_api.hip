@@ -426,7 +426,14 @@ int harp_plan_h1f1b_batch(harp_ctx *ctx, harp_tables *t, const harp_candidates *
 
 size_t harp_plan_mesh_workspace_bytes(harp_ctx *ctx, harp_tables *t, const harp_orderings *od) {
     if (check_orderings(ctx, t, od) != HARP_OK) return 0;
-    return sweep_layout(ctx, t, od).bytes;    // the largest need of the entry points that share it
+    const size_t per_group = plan_mesh_ws_per_group(t->dev.L, od->S_max, t->total_devices);
+    return 256 + size_t(n_mesh_groups(ctx, od->C, per_group,
+                                      plan_mesh_threads(t->dev.L, t->total_devices, od->C, ctx->n_cu))) * per_group;
+}
+
+size_t harp_plan_mesh_sweep_workspace_bytes(harp_ctx *ctx, harp_tables *t, const harp_orderings *od) {
+    if (check_orderings(ctx, t, od) != HARP_OK) return 0;
+    return sweep_layout(ctx, t, od).bytes;
 }
 
 }  // extern "C"

@@ -299,6 +299,21 @@ def test_mesh_h1f1b_sweep(harp, ctx):
     assert list(want.status) == [0, 0, 1, 1, 2, 2, 2, 1]
     got, _ = harp.plan_mesh_h1f1b_sweep(ctx, p, W.orderings_from_lists(lists, S_max=6).slice(0, 0))
     assert got.status.shape == (0,)
+    # argument errors: a cap limit below one, a workspace sized for the other submesh entry points
+    import torch
+    tables = harp.Tables(ctx, p)
+    do = harp.DeviceOrderings(ctx, W.orderings_from_lists(lists, S_max=6))
+    out = harp.DevicePlans(ctx, do.C, do.S_max)
+    a, b, c3 = (torch.empty((do.C, do.S_max), dtype=torch.int32, device=ctx.device) for _ in range(3))
+    tm = torch.empty(do.C, dtype=torch.int64, device=ctx.device)
+    with pytest.raises(harp.HarpError) as e:
+        harp.harp_plan_mesh_h1f1b_sweep_batch(ctx, tables, do, 0, out, a, b, c3, tm, harp.mesh_sweep_workspace(ctx, tables, do))
+    assert e.value.code == harp.ERR_INVALID_ARG
+    small = harp.mesh_workspace(ctx, tables, do)
+    assert small.numel() < harp.mesh_sweep_workspace(ctx, tables, do).numel()
+    with pytest.raises(harp.HarpError) as e:
+        harp.harp_plan_mesh_h1f1b_sweep_batch(ctx, tables, do, 8, out, a, b, c3, tm, small)
+    assert e.value.code == harp.ERR_WORKSPACE
     for name, n in (("tiny", 16), ("llama7b", 24)):
         w = W.make(name)
         orders = W.make_orderings(w.problem, w.seed, w.config_id, w.problem.G, w.S_max, 0, n)
