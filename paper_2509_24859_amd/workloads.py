@@ -403,18 +403,6 @@ def make_orderings(p: Problem, seed: int, config_id: int, S_min: int, S_max: int
     return Orderings(n, G, S_max, S.astype(np.int32), np.full(n, G, dtype=np.int32), order.astype(np.int32))
 
 
-def memory_to_compute_order(p: Problem) -> np.ndarray:
-    """Group ids in the order the paper's heuristic would run them (section 5.2.1): groups whose
-    devices have the most memory per unit of compute throughput first, because earlier stages of a
-    1F1B-style schedule keep more microbatches in flight.  Throughput of a GPU type is taken as the
-    reciprocal of its total forward+backward time over the model; ties go to the lower group id.
-    A pre-filter for candidate orderings: it holds none of the method's arithmetic."""
-    work = (p.fwd_us + p.bwd_us).sum(axis=1).astype(np.float64)          # per type, us for the whole model
-    ratio = p.type_mem_bytes.astype(np.float64) * work                   # memory / (1 / time)
-    per_group = ratio[p.group_type]
-    return np.lexsort((np.arange(p.G), -per_group)).astype(np.int32)
-
-
 def make_candidates(p: Problem, seed: int, config_id: int, S_min: int, S_max: int,
                     lo: int, hi: int) -> Candidates:
     """Candidates lo..hi-1 of the batch; candidate c depends only on (seed, config_id, c).

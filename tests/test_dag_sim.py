@@ -93,13 +93,13 @@ def test_order_and_deadlock():
 
 def test_subcluster_order_heuristic():
     """Section 5.2.1: subclusters with more memory per unit of compute go first."""
-    from paper_2509_24859_amd import workloads as W
+    from paper_2509_24859_amd import ordering, workloads as W
     # three types: (memory, relative time per operator); ratio memory x time: 80, 96, 72
     p = simple_problem(np.zeros(4), T=3, G=5, ndev=(2,) * 5, gtype=[0, 1, 2, 1, 0],
                        fwd=np.array([[10] * 4, [24] * 4, [30] * 4]), bwd=np.zeros((3, 4), dtype=np.int64),
                        mem=[80, 40, 24])
-    assert list(W.memory_to_compute_order(p)) == [1, 3, 0, 4, 2]
+    assert list(ordering.memory_to_compute_order(p)) == [1, 3, 0, 4, 2]
     w = W.make("llama70b")
-    order = W.memory_to_compute_order(w.problem)
+    order = ordering.memory_to_compute_order(w.problem)
     r = w.problem.type_mem_bytes * (w.problem.fwd_us + w.problem.bwd_us).sum(axis=1)
     assert (np.diff(r[w.problem.group_type[order]].astype(np.float64)) <= 0).all()
