@@ -52,7 +52,7 @@ def _load():
                      "oracle_argmin_batch", "oracle_plan_exact_batch", "oracle_plan_h1f1b_batch",
                      "oracle_score_h1f1b", "oracle_plan_mesh_batch",
                      "oracle_plan_mesh_exact_batch", "oracle_plan_mesh_h1f1b_batch",
-                     "oracle_plan_mesh_h1f1b_sweep_batch"):
+                     "oracle_plan_mesh_h1f1b_sweep_batch", "oracle_plan_h1f1b_sweep_batch"):
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -260,6 +260,29 @@ def plan_mesh_h1f1b_sweep_batch(tables: Tables, orders, max_caps: int = 1 << 20,
         _ptr(out.status), _ptr(out.t_max), _ptr(out.n_caps))
     if rc != 0:
         raise ValueError("oracle_plan_mesh_h1f1b_sweep_batch failed with code %d" % rc)
+    return out
+
+
+def plan_h1f1b_sweep_batch(tables: Tables, cands, max_caps: int = 1 << 20, c_begin: int = 0,
+                           c_end: int | None = None, out: Plans | None = None) -> Plans:
+    """The same search for candidates (fixed slicing): the cap swept from the hot path's bottleneck
+    to ceil(T / B), the capped H-1F1B recurrence at every cap.  `out.warmup`, `out.t_max`,
+    `out.n_caps` as for the submesh form."""
+    c_end = cands.C if c_end is None else c_end
+    out = Plans(cands.C, cands.S_max) if out is None else out
+    if not hasattr(out, "warmup"):
+        out.warmup = np.full((cands.C, cands.S_max), -1, dtype=np.int32)
+    if not hasattr(out, "t_max"):
+        out.t_max = np.full(cands.C, INF, dtype=np.int64)
+        out.n_caps = np.zeros(cands.C, dtype=np.int32)
+    cs, cg, ct = _c32(cands.cand_S), _c32(cands.cand_group), _c32(cands.cand_tp)
+    rc = _load().oracle_plan_h1f1b_sweep_batch(
+        C.byref(tables.c), _ptr(tables.PF), _ptr(tables.PP), _ptr(tables.PS), _ptr(tables.PR),
+        C.c_int32(cands.C), C.c_int32(cands.S_max), _ptr(cs), _ptr(cg), _ptr(ct), C.c_int32(max_caps),
+        C.c_int32(c_begin), C.c_int32(c_end), _ptr(out.splits), _ptr(out.dev_first), _ptr(out.warmup),
+        _ptr(out.bottleneck), _ptr(out.iter_time), _ptr(out.status), _ptr(out.t_max), _ptr(out.n_caps))
+    if rc != 0:
+        raise ValueError("oracle_plan_h1f1b_sweep_batch failed with code %d" % rc)
     return out
 
 

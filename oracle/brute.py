@@ -609,3 +609,42 @@ def sweep_mesh_h1f1b(p, S: int, S_max: int, groups, max_caps: int = 1 << 20):
         if T < best[5]:
             best = (0, cap, cuts, slots, counts, T)
     return best + (tried,)
+
+
+def cap_values(p, S: int, grp, tp):
+    """Candidate caps of a candidate (fixed slicing): the stage times of its slots over every
+    operator range, and the transfer times of the inner cuts on the links between consecutive slots."""
+    L = int(p.L)
+    values = set()
+    for s in range(S):
+        g, d = int(grp[s]), int(tp[s])
+        values.update(stage_time(p, g, d, j, i) for j in range(L) for i in range(j + 1, L + 1))
+        if s + 1 < S:
+            values.update(cut_time(p, g, int(grp[s + 1]), i) for i in range(1, L))
+    return sorted(values)
+
+
+def sweep_h1f1b(p, S: int, S_max: int, grp, tp, max_caps: int = 1 << 20):
+    """The search around the capped H-1F1B recurrence for one candidate, twin of the oracle's.
+    Returns (status, cap, cuts, counts, T, caps tried)."""
+    status, _, t_S, _ = plan(p, S, S_max, grp, tp)
+    if status != 0:
+        return status, INF, None, None, INF, 0
+    M = int(p.M)
+    best = (1, INF, None, None, INF)
+    t_E, tried = INF, 0
+    for cap in cap_values(p, S, grp, tp):
+        if cap < t_S:
+            continue
+        if cap > t_E or tried >= max_caps:
+            break
+        tried += 1
+        st, cuts, counts, total = plan_h1f1b(p, S, S_max, grp, tp, cap)
+        if st != 0:
+            continue
+        T = total + (M - 1) * cap
+        if t_E == INF:
+            t_E = _cdiv(T, M)
+        if T < best[4]:
+            best = (0, cap, cuts, counts, T)
+    return best + (tried,)

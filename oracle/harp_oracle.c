@@ -1130,3 +1130,102 @@ int oracle_plan_mesh_h1f1b_sweep_batch(const oracle_problem *p, const int64_t *P
     free(tsp); free(tsg); free(tst); free(tdf); free(twu); free(grid);
     return ORACLE_OK;
 }
+
+/* ---------------------------------------------------------------------------------------------
+ * The same search (section 5.2.4 (2)) for candidates, whose slicing is fixed: the cap swept over
+ * the candidate values from the hot path's bottleneck up to t_E = ceil(T / B), the capped H-1F1B
+ * recurrence (oracle_plan_h1f1b_batch, one candidate) at every cap.
+ *
+ * Candidate values of a candidate: every stage time time(g_s, tp_s; j, i) of one of its slots,
+ * 0 <= j < i <= L, and every transfer time of a cut 1 <= i <= L - 1 on the link between two
+ * consecutive slots (g_s, g_{s+1}).  Sweep, t_E, the answer, t_max_out and n_caps as for
+ * oracle_plan_mesh_h1f1b_sweep_batch.
+ * ------------------------------------------------------------------------------------------- */
+int oracle_plan_h1f1b_sweep_batch(const oracle_problem *p, const int64_t *PF, const int64_t *PP,
+                                  const int64_t *PS, const int64_t *PR, int32_t C, int32_t S_max,
+                                  const int32_t *cand_S, const int32_t *cand_group, const int32_t *cand_tp,
+                                  int32_t max_caps, int32_t c_begin, int32_t c_end, int32_t *splits,
+                                  int32_t *dev_first, int32_t *warmup, int64_t *bottleneck, int64_t *iter_time,
+                                  int32_t *status, int64_t *t_max_out, int32_t *n_caps)
+{
+    if (C < 0 || S_max < 1 || c_begin < 0 || c_end > C || c_begin > c_end || max_caps < 1) return ORACLE_BAD_ARG;
+    const int L = p->L;
+    tables_view v = { p, PF, PP, PS, PR };
+    int32_t *tsp = (int32_t *)malloc(sizeof(int32_t) * (size_t)(S_max + 1));
+    int32_t *tdf = (int32_t *)malloc(sizeof(int32_t) * (size_t)S_max);
+    int32_t *twu = (int32_t *)malloc(sizeof(int32_t) * (size_t)S_max);
+    size_t room = 1024, n = 0;
+    int64_t *grid = (int64_t *)malloc(sizeof(int64_t) * room);
+    if (!tsp || !tdf || !twu || !grid) return ORACLE_BAD_ARG;
+    for (int32_t c = c_begin; c < c_end; ++c) {
+        const int32_t *grp = cand_group + (size_t)c * S_max, *tp = cand_tp + (size_t)c * S_max;
+        int32_t *sp = splits + (size_t)c * (S_max + 1), *df = dev_first + (size_t)c * S_max;
+        int32_t *wu = warmup + (size_t)c * S_max;
+        for (int s = 0; s < S_max; ++s) wu[s] = -1;
+        t_max_out[c] = ORACLE_INF;
+        if (n_caps) n_caps[c] = 0;
+        /* the hot path's plan of this candidate: validity, and the lower end of the sweep */
+        int64_t t_S, unused;
+        int32_t st0;
+        int rc = oracle_plan_batch(p, PF, PP, PS, PR, 1, S_max, cand_S + c, grp, tp, 0, 1, sp, df, &t_S, &unused, &st0);
+        if (rc != ORACLE_OK) return rc;
+        fill_failed(S_max, sp, df, bottleneck + c, iter_time + c);
+        status[c] = st0;
+        if (st0 != CAND_OK) continue;
+        status[c] = CAND_INFEASIBLE;
+        const int S = cand_S[c];
+        n = 0;
+        for (int s = 0; s < S; ++s) {
+            for (int j = 0; j < L; ++j)
+                for (int i = j + 1; i <= L; ++i) {
+                    const int64_t val = stage_time(&v, grp[s], tp[s], j, i);
+                    if (val < t_S) continue;
+                    if (n == room) {
+                        room *= 2;
+                        grid = (int64_t *)realloc(grid, sizeof(int64_t) * room);
+                        if (!grid) return ORACLE_BAD_ARG;
+                    }
+                    grid[n++] = val;
+                }
+            if (s + 1 < S)
+                for (int i = 1; i <= L - 1; ++i) {
+                    const int64_t val = cut_time(p, grp[s], grp[s + 1], i);
+                    if (val < t_S) continue;
+                    if (n == room) {
+                        room *= 2;
+                        grid = (int64_t *)realloc(grid, sizeof(int64_t) * room);
+                        if (!grid) return ORACLE_BAD_ARG;
+                    }
+                    grid[n++] = val;
+                }
+        }
+        qsort(grid, n, sizeof(int64_t), cmp_i64);
+        int64_t best_T = ORACLE_INF, t_E = ORACLE_INF;
+        int tried = 0;
+        for (size_t x = 0; x < n && tried < max_caps; ++x) {
+            if (x > 0 && grid[x] == grid[x - 1]) continue;
+            const int64_t cap = grid[x];
+            if (cap > t_E) break;
+            ++tried;
+            int64_t b1, T1;
+            int32_t s1;
+            rc = oracle_plan_h1f1b_batch(p, PF, PP, PS, PR, 1, S_max, cand_S + c, grp, tp, &cap, 0, 1, tsp, tdf, twu,
+                                         &b1, &T1, &s1);
+            if (rc != ORACLE_OK) return rc;
+            if (s1 != CAND_OK) continue;
+            if (t_E == ORACLE_INF) t_E = ceil_div(T1, p->M);
+            if (T1 < best_T) {
+                best_T = T1;
+                for (int s = 0; s <= S_max; ++s) sp[s] = tsp[s];
+                for (int s = 0; s < S_max; ++s) { df[s] = tdf[s]; wu[s] = twu[s]; }
+                bottleneck[c] = b1;
+                iter_time[c] = T1;
+                t_max_out[c] = cap;
+                status[c] = CAND_OK;
+            }
+        }
+        if (n_caps) n_caps[c] = tried;
+    }
+    free(tsp); free(tdf); free(twu); free(grid);
+    return ORACLE_OK;
+}

@@ -877,3 +877,67 @@ def test_mesh_h1f1b_sweep_against_its_twin_and_what_bounds_it():
         assert (sweep.status == exact.status).all()
         ok = exact.status == oracle.OK
         assert (sweep.iter_time[ok] == exact.iter_time[ok]).all()
+
+
+def test_h1f1b_sweep_of_candidates_against_its_twin_and_the_submesh_form():
+    """The search around the capped H-1F1B recurrence for candidates (fixed slicing): the oracle
+    against the recursion twin's sweep; the answer is the least T over the caps tried; with
+    unlimited memory it is the exact search's optimum; and with single-device groups, where an
+    ordering has one slicing, it is the submesh form's answer."""
+    n = moved = 0
+    for seed in range(200):
+        w = W.random_small(seed, L_max=9, S_cap=4)
+        p = w.problem
+        tables = oracle.build_tables(p)
+        cands = w.candidates()
+        out = oracle.plan_h1f1b_sweep_batch(tables, cands)
+        few = oracle.plan_h1f1b_sweep_batch(tables, cands, max_caps=2)
+        mm = oracle.plan_batch(tables, cands)
+        for c in range(cands.C):
+            S = int(cands.cand_S[c])
+            grp, tp = cands.cand_group[c], cands.cand_tp[c]
+            st, cap, cuts, counts, T, tried = brute.sweep_h1f1b(p, S, cands.S_max, grp, tp)
+            assert st == out.status[c] and tried == out.n_caps[c], (seed, c)
+            st2, cap2, _, _, T2, tried2 = brute.sweep_h1f1b(p, S, cands.S_max, grp, tp, max_caps=2)
+            assert (st2, tried2) == (few.status[c], few.n_caps[c]) and (st2 != 0 or (few.t_max[c], few.iter_time[c]) == (cap2, T2))
+            if st != oracle.OK:
+                assert out.t_max[c] == oracle.INF and (out.warmup[c] == -1).all() and (out.splits[c] == -1).all()
+                continue
+            n += 1
+            assert out.t_max[c] == cap and out.iter_time[c] == T, (seed, c)
+            assert list(out.splits[c, :S + 1]) == cuts and list(out.warmup[c, :S]) == counts
+            values = [v for v in brute.cap_values(p, S, grp, tp) if v >= mm.bottleneck[c]][:tried]
+            at = oracle.plan_h1f1b_batch(tables, cands.take([c] * len(values)), values)
+            ok = at.status == oracle.OK
+            assert at.iter_time[ok].min() == T and values[int(np.nonzero(ok & (at.iter_time == T))[0][0])] == cap
+            moved += cap != mm.bottleneck[c]
+    assert n > 600 and moved > 20
+    for seed in range(60):
+        w = W.random_small(seed, L_max=9, S_cap=4)
+        p = dataclasses.replace(w.problem, type_mem_bytes=np.full_like(w.problem.type_mem_bytes, 1 << 50))
+        tables = oracle.build_tables(p)
+        sweep = oracle.plan_h1f1b_sweep_batch(tables, w.candidates())
+        exact = oracle.plan_exact_batch(tables, w.candidates())
+        assert (sweep.status == exact.status).all()
+        ok = exact.status == oracle.OK
+        assert (sweep.iter_time[ok] == exact.iter_time[ok]).all()
+    for seed in range(30):
+        rng = np.random.default_rng(seed)
+        G, L = int(rng.integers(2, 5)), int(rng.integers(6, 12))
+        bw = rng.integers(1, 50, size=(G, G))
+        p = simple_problem(rng.integers(1, 100, size=L), M=int(rng.integers(1, 9)), G=G, ndev=(1,) * G,
+                           act=rng.integers(0, 400, size=L), bw=np.minimum(bw, bw.T),
+                           params=rng.integers(0, 50, size=L), stash=rng.integers(0, 20, size=L),
+                           mem=[int(rng.integers(150, 600))])
+        order = [int(x) for x in rng.permutation(G)]
+        tables = oracle.build_tables(p)
+        a = oracle.plan_h1f1b_sweep_batch(tables, cands_from_lists([[(g, 1) for g in order]]))
+        b = oracle.plan_mesh_h1f1b_sweep_batch(tables, W.orderings_from_lists([(G, order)]))
+        assert a.status[0] == b.status[0]
+        if a.status[0] == oracle.OK:
+            # the submesh form also lists the links inside single-device groups among its values, so it
+            # may try more caps; the answer over the caps both try is the same when those extra caps lose
+            assert b.iter_time[0] <= a.iter_time[0]
+            if b.n_caps[0] == a.n_caps[0]:
+                assert (a.iter_time[0], a.t_max[0]) == (b.iter_time[0], b.t_max[0])
+                assert (a.splits[0] == b.splits[0]).all() and (a.warmup[0] == b.warmup[0]).all()
