@@ -281,6 +281,23 @@ int harp_plan_mesh_h1f1b_sweep_batch(harp_ctx *ctx, harp_tables *tables, const h
                                      int32_t *n_caps, void *workspace, size_t workspace_bytes,
                                      void *hip_stream);
 
+/* The same search for candidates, whose slicing is fixed: the cap swept over the candidate values
+ * from the bottleneck harp_plan_batch finds up to t_E = ceil(T / B), harp_plan_h1f1b_batch's
+ * recurrence at every one of them.  Candidate values of a candidate: every stage time of one of
+ * its slots (its group, its degree) over an operator range [j, i), 0 <= j < i <= L, and every
+ * transfer time of a cut 1 <= i <= L - 1 on the link between two consecutive slots.  Order of the
+ * sweep, t_E, the answer, max_caps, t_max_out and n_caps as for harp_plan_mesh_h1f1b_sweep_batch;
+ * out and warmup as for harp_plan_h1f1b_batch at the cap of the answer; statuses as for
+ * harp_plan_batch, and HARP_CAND_INFEASIBLE when no tried cap has a plan.  It runs on the submesh
+ * kernels with every stage's group and degree given (one device offset per stage), not on the hot
+ * path's: meant for batches of moderate size.  Workspace: harp_plan_h1f1b_sweep_workspace_bytes,
+ * 256-byte aligned, contents irrelevant. */
+size_t harp_plan_h1f1b_sweep_workspace_bytes(harp_ctx *ctx, harp_tables *tables, const harp_candidates *cands);
+int harp_plan_h1f1b_sweep_batch(harp_ctx *ctx, harp_tables *tables, const harp_candidates *cands,
+                                int32_t max_caps, const harp_plans *out, int32_t *warmup,
+                                int64_t *t_max_out, int32_t *n_caps, void *workspace,
+                                size_t workspace_bytes, void *hip_stream);
+
 /* The capped recurrence under the H-1F1B scheduler (sections 4.1 and 5.2.3): for candidate c and
  * the cap t_max[c] on every stage and transfer time (constraints (i), (ii)), the suffix recurrence
  * of eq. dp_general with the warm-up launch count carried in the state (eq. dp_ni) and used by the

@@ -28,6 +28,7 @@ EXPORTS = (
     "harp_plan_h1f1b_batch", "harp_score_h1f1b",
     "harp_plan_mesh_workspace_bytes", "harp_plan_mesh_batch", "harp_plan_mesh_exact_batch", "harp_plan_mesh_h1f1b_batch",
     "harp_plan_mesh_h1f1b_sweep_batch", "harp_plan_mesh_sweep_workspace_bytes",
+    "harp_plan_h1f1b_sweep_batch", "harp_plan_h1f1b_sweep_workspace_bytes",
     "harp_score_1f1b", "harp_argmin_batch", "harp_measure_valu_int32",
 )
 
@@ -105,6 +106,10 @@ def load_library() -> C.CDLL:
     lib.harp_score_h1f1b.argtypes = [vp, vp, C.POINTER(harp_candidates), vp, vp, vp, vp, vp, vp, vp]
     lib.harp_plan_mesh_workspace_bytes.argtypes = [vp, vp, C.POINTER(harp_orderings)]
     lib.harp_plan_mesh_workspace_bytes.restype = sz
+    lib.harp_plan_h1f1b_sweep_workspace_bytes.argtypes = [vp, vp, C.POINTER(harp_candidates)]
+    lib.harp_plan_h1f1b_sweep_workspace_bytes.restype = sz
+    lib.harp_plan_h1f1b_sweep_batch.argtypes = [vp, vp, C.POINTER(harp_candidates), i32, C.POINTER(harp_plans),
+                                                vp, vp, vp, vp, sz, vp]
     lib.harp_plan_mesh_sweep_workspace_bytes.argtypes = [vp, vp, C.POINTER(harp_orderings)]
     lib.harp_plan_mesh_sweep_workspace_bytes.restype = sz
     lib.harp_plan_mesh_batch.argtypes = [vp, vp, C.POINTER(harp_orderings), C.POINTER(harp_plans), vp, vp, vp, sz, vp]
@@ -483,6 +488,47 @@ def mesh_workspace(ctx: Context, tables: Tables, do: DeviceOrderings):
     if n == 0:
         raise HarpError(ERR_INVALID_ARG, ctx.lib.harp_last_error(ctx.handle).decode() or "malformed orderings")
     return torch.empty(n, dtype=torch.uint8, device=ctx.device)
+
+
+def harp_plan_h1f1b_sweep_batch(ctx: Context, tables: Tables, dc: DeviceCandidates, max_caps: int,
+                                out: DevicePlans, warmup, t_max_out, workspace, n_caps=None, stream=None):
+    ctx.check(ctx.lib.harp_plan_h1f1b_sweep_batch(
+        ctx.handle, tables.handle, C.byref(dc.c), int(max_caps), C.byref(out.c), warmup.data_ptr(),
+        t_max_out.data_ptr(), n_caps.data_ptr() if n_caps is not None else None, workspace.data_ptr(),
+        workspace.numel(), _stream_handle(stream)))
+
+
+def h1f1b_sweep_workspace(ctx: Context, tables: Tables, dc: DeviceCandidates):
+    torch = _torch()
+    n = ctx.lib.harp_plan_h1f1b_sweep_workspace_bytes(ctx.handle, tables.handle, C.byref(dc.c))
+    if n == 0:
+        raise HarpError(ERR_INVALID_ARG, ctx.lib.harp_last_error(ctx.handle).decode() or "malformed candidates")
+    return torch.empty(n, dtype=torch.uint8, device=ctx.device)
+
+
+def plan_h1f1b_sweep(ctx: Context, problem, cands, max_caps: int = 1 << 20, path: int = PATH_AUTO):
+    """Convenience for tests: the search over the cap for candidates; host copies of the plans with
+    `.warmup`, `.t_max`, `.n_caps`."""
+    torch = _torch()
+    tables = Tables(ctx, problem)
+    dc = DeviceCandidates(ctx, cands)
+    out = DevicePlans(ctx, dc.C, dc.S_max)
+    out.poison()
+    wu = torch.full((max(dc.C, 1), dc.S_max), -7, dtype=torch.int32, device=ctx.device)
+    tm = torch.full((max(dc.C, 1),), -7, dtype=torch.int64, device=ctx.device)
+    nc = torch.full((max(dc.C, 1),), -7, dtype=torch.int32, device=ctx.device)
+    ws = h1f1b_sweep_workspace(ctx, tables, dc)
+    ctx.set_plan_path(path)
+    try:
+        harp_plan_h1f1b_sweep_batch(ctx, tables, dc, max_caps, out, wu, tm, ws, nc)
+        torch.cuda.synchronize()
+    finally:
+        ctx.set_plan_path(PATH_AUTO)
+    got = out.to_host()
+    got.warmup = wu[:dc.C].cpu().numpy()
+    got.t_max = tm[:dc.C].cpu().numpy()
+    got.n_caps = nc[:dc.C].cpu().numpy()
+    return got, tables
 
 
 def mesh_sweep_workspace(ctx: Context, tables: Tables, do: DeviceOrderings):

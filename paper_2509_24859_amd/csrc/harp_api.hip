@@ -538,11 +538,48 @@ int harp_plan_mesh_h1f1b_sweep_batch(harp_ctx *ctx, harp_tables *t, const harp_o
     if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
     const OrdDev o = { od->C, od->G_max, od->S_max, od->ord_S, od->ord_G, od->ord_group };
     const PlansDev pl = { out->splits, out->dev_first, out->bottleneck, out->iter_time, out->status };
-    launch_plan_mesh_h1f1b_sweep(t->dev, o, max_caps, pl, stage_group, stage_tp, warmup, t_max_out, n_caps,
+    launch_plan_mesh_h1f1b_sweep(t->dev, o, nullptr, nullptr, max_caps, pl, stage_group, stage_tp, warmup, t_max_out, n_caps,
                                  use_fast(ctx, t), workspace, lay.groups, lay.threads, lay.W, t->total_devices,
                                  static_cast<hipStream_t>(hip_stream));
     e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(ctx, e, "launching the submesh H-1F1B sweep kernel");
+    return HARP_OK;
+}
+
+size_t harp_plan_h1f1b_sweep_workspace_bytes(harp_ctx *ctx, harp_tables *t, const harp_candidates *cd) {
+    if (check_batch(ctx, t, cd) != HARP_OK) return 0;
+    const harp_orderings shape = { cd->C, 1, cd->S_max, nullptr, nullptr, nullptr };
+    return sweep_layout(ctx, t, &shape).bytes;
+}
+
+int harp_plan_h1f1b_sweep_batch(harp_ctx *ctx, harp_tables *t, const harp_candidates *cd, int32_t max_caps,
+                                const harp_plans *out, int32_t *warmup, int64_t *t_max_out, int32_t *n_caps,
+                                void *workspace, size_t workspace_bytes, void *hip_stream) {
+    int rc = check_batch(ctx, t, cd);
+    if (rc != HARP_OK) return rc;
+    if (max_caps < 1) return fail(ctx, HARP_ERR_INVALID_ARG, "max_caps must be >= 1");
+    if (!out || (cd->C > 0 && (!out->splits || !out->dev_first || !out->bottleneck || !out->iter_time ||
+                               !out->status || !warmup || !t_max_out)))
+        return fail(ctx, HARP_ERR_INVALID_ARG, "null array");
+    if (ctx->plan_path == HARP_PATH_FAST32 && !t->fast32)
+        return fail(ctx, HARP_ERR_UNIMPLEMENTED, "the 32-bit path was requested but these tables do not allow it");
+    if (cd->C == 0) return HARP_OK;
+    if (t->total_devices > 65535) return fail(ctx, HARP_ERR_SHAPE, "the search over the cap handles at most 65535 devices");
+    const harp_orderings shape = { cd->C, 1, cd->S_max, nullptr, nullptr, nullptr };
+    const SweepLayout lay = sweep_layout(ctx, t, &shape);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0)
+        return fail(ctx, HARP_ERR_WORKSPACE, "workspace must be a 256-byte aligned device pointer");
+    if (workspace_bytes < lay.bytes)
+        return fail(ctx, HARP_ERR_WORKSPACE, "workspace holds %zu bytes, %zu needed", workspace_bytes, lay.bytes);
+    hipError_t e = hipSetDevice(ctx->device);
+    if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
+    const OrdDev o = { cd->C, 1, cd->S_max, cd->cand_S, nullptr, nullptr };
+    const PlansDev pl = { out->splits, out->dev_first, out->bottleneck, out->iter_time, out->status };
+    launch_plan_mesh_h1f1b_sweep(t->dev, o, cd->cand_group, cd->cand_tp, max_caps, pl, nullptr, nullptr, warmup,
+                                 t_max_out, n_caps, use_fast(ctx, t), workspace, lay.groups, lay.threads, lay.W,
+                                 t->total_devices, static_cast<hipStream_t>(hip_stream));
+    e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(ctx, e, "launching the search over the cap");
     return HARP_OK;
 }
 

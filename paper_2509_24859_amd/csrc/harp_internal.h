@@ -106,7 +106,8 @@ void launch_plan_mesh(const TablesDev &tb, const OrdDev &od, const PlansDev &out
 void launch_plan_mesh_h1f1b(const TablesDev &tb, const OrdDev &od, const int64_t *t_max, const PlansDev &out,
                             int32_t *stage_group, int32_t *stage_tp, int32_t *warmup, bool fast32, void *ws,
                             int n_groups, int threads, int64_t total_devices, hipStream_t st);
-void launch_plan_mesh_h1f1b_sweep(const TablesDev &tb, const OrdDev &od, int max_caps, const PlansDev &out,
+void launch_plan_mesh_h1f1b_sweep(const TablesDev &tb, const OrdDev &od, const int32_t *cand_group,
+                                  const int32_t *cand_tp, int max_caps, const PlansDev &out,
                                   int32_t *stage_group, int32_t *stage_tp, int32_t *warmup, int64_t *t_max_out,
                                   int32_t *n_caps, bool fast32, void *ws, int n_groups, int threads, int W,
                                   int64_t total_devices, hipStream_t st);

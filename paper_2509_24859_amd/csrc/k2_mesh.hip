@@ -62,7 +62,8 @@ constexpr int kMeshGroupTable = 2048;   // device offsets whose group index is k
 template <bool kCapped>
 __device__ __forceinline__ int64_t mesh_pass(const TablesDev &tb, const MeshSlice &m, const int32_t *offs,
                                              const uint16_t *order, const uint16_t *group_at, int K, int S,
-                                             int64_t n_dev, int64_t cap) {
+                                             int64_t n_dev, int64_t cap, const uint8_t *forced = nullptr,
+                                             const int32_t *forced_off = nullptr) {
     const int L = tb.L, W = L + 1, tid = threadIdx.x, nthreads = blockDim.x;
     const int Dtot = offs[K];
     const int64_t *PP = tb.PP(), *PS = tb.PS();
@@ -77,7 +78,9 @@ __device__ __forceinline__ int64_t mesh_pass(const TablesDev &tb, const MeshSlic
         const int64_t n_inflight = (S - s) < tb.M ? (S - s) : tb.M;
         // targets: i in [i_lo, i_hi], d' in [d_lo, d_hi]; every later stage needs an operator and a device
         const int i_lo = last ? L : s + 1, i_hi = L - (S - 1 - s);
-        const int d_lo = last ? Dtot : s + 1, d_hi = last ? Dtot : Dtot - (S - 1 - s);
+        // a fixed slicing (forced) leaves one device offset per stage
+        const int d_lo = forced ? forced_off[s + 1] : (last ? Dtot : s + 1);
+        const int d_hi = forced ? forced_off[s + 1] : (last ? Dtot : Dtot - (S - 1 - s));
         const int n_i = i_hi - i_lo + 1, n_d = d_hi - d_lo + 1;
         uint32_t *arg_s = m.arg + size_t(s) * size_t(n_dev + 1) * W;
         for (int x = tid; x < n_i * n_d; x += nthreads) {
@@ -101,6 +104,7 @@ __device__ __forceinline__ int64_t mesh_pass(const TablesDev &tb, const MeshSlic
             const int64_t pfi = pf[i], ppi = PP[i], psi = PS[i];
             if (!kCapped || cut <= cap) {
                 for (int q = 0; q < tb.n_tp; ++q) {
+                    if (forced && q != forced[s]) continue;
                     const int64_t tp = tb.tp[q];
                     const int d = d2 - int(tp);
                     // the stage must stay inside group k, and s stages have used at least s devices
@@ -157,7 +161,9 @@ constexpr int kMeshFastMaxL = 4096;
 template <bool kCapped>
 __device__ __forceinline__ int64_t mesh_pass_fast(const TablesDev &tb, const MeshSlice &m, const int32_t *offs,
                                                   const uint16_t *order, const uint16_t *group_at, int64_t *Q,
-                                                  int K, int S, int64_t n_dev, int64_t cap) {
+                                                  int K, int S, int64_t n_dev, int64_t cap,
+                                                  const uint8_t *forced = nullptr,
+                                                  const int32_t *forced_off = nullptr) {
     using ValT = typename std::conditional<kCapped, int64_t, uint32_t>::type;
     constexpr uint64_t kNoKey = ~0ull;
     const int L = tb.L, W = L + 1, tid = threadIdx.x, nthreads = blockDim.x;
@@ -178,7 +184,9 @@ __device__ __forceinline__ int64_t mesh_pass_fast(const TablesDev &tb, const Mes
         for (int j = tid; j <= L; j += nthreads) Q[j] = PP[j] + n_inflight * PS[j];
         __syncthreads();
         const int i_lo = last ? L : s + 1, i_hi = L - (S - 1 - s);
-        const int d_lo = last ? Dtot : s + 1, d_hi = last ? Dtot : Dtot - (S - 1 - s);
+        // a fixed slicing (forced) leaves one device offset per stage
+        const int d_lo = forced ? forced_off[s + 1] : (last ? Dtot : s + 1);
+        const int d_hi = forced ? forced_off[s + 1] : (last ? Dtot : Dtot - (S - 1 - s));
         const int n_i = i_hi - i_lo + 1, n_d = d_hi - d_lo + 1;
         uint32_t *arg_s = m.arg + size_t(s) * size_t(n_dev + 1) * W;
         for (int x = tid; x < n_i * n_d; x += nthreads) {
@@ -194,6 +202,7 @@ __device__ __forceinline__ int64_t mesh_pass_fast(const TablesDev &tb, const Mes
             uint64_t best = kNoKey;
             if (!kCapped || cut <= cap32) {
                 for (int q = 0; q < tb.n_tp; ++q) {
+                    if (forced && q != forced[s]) continue;
                     const int tp = tb.tp[q];
                     const int d = d2 - tp;
                     // the stage must stay inside group k, and s stages have used at least s devices
@@ -445,7 +454,8 @@ __device__ __forceinline__ int mesh_delta(int64_t c, int64_t cap) {
 // Ties: lowest end cut, then smallest degree.  Returns the value of (S, 0, all devices).
 __device__ __forceinline__ int64_t mesh_h1_pass(const TablesDev &tb, const MeshSlice &m, const int32_t *offs,
                                                 const uint16_t *order, const uint16_t *group_at, int K, int S,
-                                                int64_t n_dev, int64_t cap) {
+                                                int64_t n_dev, int64_t cap, const uint8_t *forced = nullptr,
+                                                const int32_t *forced_off = nullptr) {
     const int L = tb.L, W = L + 1, tid = threadIdx.x, nthreads = blockDim.x;
     const int Dtot = offs[K];
     const int64_t *PP = tb.PP(), *PS = tb.PS();
@@ -459,7 +469,9 @@ __device__ __forceinline__ int64_t mesh_h1_pass(const TablesDev &tb, const MeshS
         __syncthreads();                             // row s - 1 is complete
         const bool whole = (s == S);
         const int i_lo = whole ? 0 : S - s, i_hi = whole ? 0 : L - s;
-        const int e_lo = whole ? Dtot : s, e_hi = whole ? Dtot : Dtot - (S - s);
+        // a fixed slicing (forced) leaves one device count for the last s stages
+        const int e_lo = forced ? Dtot - forced_off[S - s] : (whole ? Dtot : s);
+        const int e_hi = forced ? Dtot - forced_off[S - s] : (whole ? Dtot : Dtot - (S - s));
         const int j_hi = L - (s - 1);
         const int n_i = i_hi - i_lo + 1, n_e = e_hi - e_lo + 1;
         uint32_t *arg_s = m.arg + size_t(s - 1) * size_t(n_dev + 1) * W;
@@ -477,6 +489,7 @@ __device__ __forceinline__ int64_t mesh_h1_pass(const TablesDev &tb, const MeshS
             int64_t best = kInf;
             int best_j = 0x7FFFFFFF, best_q = 0, best_n = 0;
             for (int q = 0; q < tb.n_tp; ++q) {
+                if (forced && q != forced[S - s]) continue;
                 const int64_t tp = tb.tp[q];
                 const int e0 = e - int(tp);
                 // the stage stays inside group k; the stages behind it have used at least one device
@@ -529,7 +542,9 @@ __device__ __forceinline__ int64_t mesh_h1_pass(const TablesDev &tb, const MeshS
 // whether the lane goes on (the stage time and the memory need with a count of one both grow with j).
 __device__ __forceinline__ int64_t mesh_h1_pass_fast(const TablesDev &tb, const MeshSlice &m, const int32_t *offs,
                                                      const uint16_t *order, const uint16_t *group_at,
-                                                     int64_t *PPl, int K, int S, int64_t n_dev, int64_t cap) {
+                                                     int64_t *PPl, int K, int S, int64_t n_dev, int64_t cap,
+                                                     const uint8_t *forced = nullptr,
+                                                     const int32_t *forced_off = nullptr) {
     constexpr uint64_t kNone = ~0ull;
     const int L = tb.L, W = L + 1, tid = threadIdx.x, nthreads = blockDim.x;
     const int Dtot = offs[K];
@@ -553,7 +568,9 @@ __device__ __forceinline__ int64_t mesh_h1_pass_fast(const TablesDev &tb, const 
         __syncthreads();                             // row s - 1 is complete
         const bool whole = (s == S);
         const int i_lo = whole ? 0 : S - s, i_hi = whole ? 0 : L - s;
-        const int e_lo = whole ? Dtot : s, e_hi = whole ? Dtot : Dtot - (S - s);
+        // a fixed slicing (forced) leaves one device count for the last s stages
+        const int e_lo = forced ? Dtot - forced_off[S - s] : (whole ? Dtot : s);
+        const int e_hi = forced ? Dtot - forced_off[S - s] : (whole ? Dtot : Dtot - (S - s));
         const int j_hi = L - (s - 1);
         const int n_i = i_hi - i_lo + 1, n_e = e_hi - e_lo + 1;
         uint32_t *arg_s = m.arg + size_t(s - 1) * size_t(n_dev + 1) * W;
@@ -569,6 +586,7 @@ __device__ __forceinline__ int64_t mesh_h1_pass_fast(const TablesDev &tb, const 
             uint64_t best = kNone;
             uint32_t best_n = 0;
             for (int q = 0; q < tb.n_tp; ++q) {
+                if (forced && q != forced[S - s]) continue;
                 const int tp = tb.tp[q];
                 const int e0 = e - tp;
                 // the stage stays inside group k; the stages behind it have used at least one device
@@ -824,6 +842,63 @@ __device__ __forceinline__ int64_t mesh_next_cap(const TablesDev &tb, const uint
     return v == ~0ull ? kInf : int64_t(v);
 }
 
+// The same for a fixed slicing: the candidate values are the stage times of the slots (group and
+// degree of every stage given) and the transfer times on the links between consecutive slots.
+template <bool kFast>
+__device__ __forceinline__ int64_t mesh_next_cap_slots(const TablesDev &tb, int S, const uint16_t *stage_g,
+                                                       const uint8_t *stage_q, int64_t b, unsigned long long *slot) {
+    const int L = tb.L, tid = threadIdx.x, nthreads = blockDim.x;
+    __syncthreads();
+    if (tid == 0) *slot = ~0ull;
+    __syncthreads();
+    unsigned long long least = ~0ull;
+    for (int x = tid; x < S * L; x += nthreads) {
+        const int j = x % L, st = x / L, q = stage_q[st];
+        const int g = stage_g[st];
+        const int64_t tp = tb.tp[q];
+        const int shift = tb.tp_shift[q];
+        const uint32_t *p32 = kFast ? tb.P32 + (int64_t(g) * tb.n_tp + q) * tb.pitch32 : nullptr;
+        const int64_t *pf = tb.PF(tb.group_type[g]), *pr = tb.PR(g, q);
+        auto time_to = [&](int i) -> int64_t {
+            if (kFast) return int64_t((p32[i] + uint32_t(tp) - 1u - p32[j]) >> shift);
+            const int64_t work = pf[i] - pf[j];
+            return (shift >= 0 ? (work + tp - 1) >> shift : (work + tp - 1) / tp) + (pr[i] - pr[j]);
+        };
+        if (time_to(L) <= b) continue;
+        int lo = j + 1, hi = L;                       // time_to(hi) > b
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (time_to(mid) > b) hi = mid; else lo = mid + 1;
+        }
+        const unsigned long long v = (unsigned long long)time_to(hi);
+        least = v < least ? v : least;
+    }
+    if (L >= 2) {
+        for (int x = tid; x < (S - 1) * (L - 1); x += nthreads) {
+            const int i = 1 + x % (L - 1), st = x / (L - 1);
+            const int g = stage_g[st], h = stage_g[st + 1];
+            int64_t v;
+            if (kFast) {
+                v = tb.CM[(int64_t(g) * tb.G + h) * tb.pitch32 + i];
+            } else {
+                const int64_t link = tb.bw[int64_t(g) * tb.G + h];
+                v = (tb.act_bytes[i - 1] + link - 1) / link;
+            }
+            if (v > b && (unsigned long long)v < least) least = (unsigned long long)v;
+        }
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        const uint32_t lo = __shfl_xor(uint32_t(least), d, 64), hi = __shfl_xor(uint32_t(least >> 32), d, 64);
+        const unsigned long long o = ((unsigned long long)hi << 32) | lo;
+        least = o < least ? o : least;
+    }
+    if ((tid & 63) == 0 && least != ~0ull) atomicMin(slot, least);
+    __syncthreads();
+    const unsigned long long v = *slot;
+    return v == ~0ull ? kInf : int64_t(v);
+}
+
 // The search around the full recurrence (section 5.2.4 (2)) in three launches, so that the caps of
 // one ordering can be tried by several workgroups at once (the batched evaluation of 5.2.4 (3)):
 //  first:  one workgroup per ordering; the classic min-max pass gives the lower end t_S of the
@@ -870,8 +945,13 @@ __device__ __forceinline__ SweepSlot sweep_slot(unsigned char *slots, int S_max,
 
 // kRest = false: the first launch (ticket over orderings).  kRest = true: the second (ticket over
 // ordering x W).
-template <bool kFast, bool kRest>
-__device__ __forceinline__ void mesh_sweep_body(const TablesDev &tb, const OrdDev &od, int max_caps, int W,
+// kForced: the batch holds candidates with a fixed slicing (od.ord_S = their stage counts, slot
+// lists in cand_group / cand_tp): every stage's group and degree are given, so each stage has one
+// device offset and one degree, and the candidate values are those of the slots and of the links
+// between consecutive slots.
+template <bool kFast, bool kRest, bool kForced>
+__device__ __forceinline__ void mesh_sweep_body(const TablesDev &tb, const OrdDev &od, const int32_t *cand_group,
+                                                const int32_t *cand_tp, int max_caps, int W,
                                                 unsigned char *slots, unsigned char *ws, size_t per_group,
                                                 int64_t n_dev, int *ticket) {
     extern __shared__ __align__(16) unsigned char mesh_lds[];      // fast form: PP and PS (or Q), L + 1 entries each
@@ -885,11 +965,16 @@ __device__ __forceinline__ void mesh_sweep_body(const TablesDev &tb, const OrdDe
     __shared__ int32_t slot_first[kMaxStages];
     __shared__ int shared_int[2];
     __shared__ unsigned long long next_slot;
+    __shared__ uint8_t forced_q[kForced ? kMaxStages : 1];          // degree index of every stage
+    __shared__ uint16_t forced_g[kForced ? kMaxStages : 1];         // group of every stage
+    __shared__ int32_t forced_off[kForced ? kMaxStages + 1 : 1];    // device offset of every stage
     const int L = tb.L, S_max = od.S_max;
     const int tid = threadIdx.x, nthreads = blockDim.x;
     const MeshSlice m = mesh_slice(ws, per_group, L, n_dev);
     const int64_t m_cap = tb.M;
     const int n_items = kRest ? od.C * W : od.C;
+    const uint8_t *fq = kForced ? forced_q : nullptr;
+    const int32_t *fo = kForced ? forced_off : nullptr;
 
     for (;;) {
         __syncthreads();
@@ -912,24 +997,62 @@ __device__ __forceinline__ void mesh_sweep_body(const TablesDev &tb, const OrdDe
             tried = opening.head->tried;
             t_E = (opening.head->T + m_cap - 1) / m_cap;
         }
-        const int S = od.ord_S[c], K = od.ord_G[c];
-        const int32_t *og = od.ord_group + int64_t(c) * od.G_max;
-        int bad = (S < 1 || S > S_max || K < 1 || K > od.G_max) ? 1 : 0;
-        if (!bad)
-            for (int k = tid; k < K; k += nthreads) {
-                const int g = og[k];
-                if (g < 0 || g >= tb.G) { bad = 1; continue; }
-                for (int q = 0; q < k; ++q)
-                    if (og[q] == g) bad = 1;
-                order[k] = uint16_t(g);
+        const int S = od.ord_S[c];
+        int K;
+        if constexpr (kForced) {
+            // the slot list: stages in range, groups and degrees known, slots of a group adjacent and
+            // within the group's devices; the groups in order of appearance are the ordering
+            int bad = (S < 1 || S > S_max) ? 1 : 0;
+            if (tid == 0 && !bad) {
+                const int32_t *grp = cand_group + int64_t(c) * S_max, *tpv = cand_tp + int64_t(c) * S_max;
+                int k = -1, used = 0;
+                forced_off[0] = 0;
+                for (int st = 0; st < S && !bad; ++st) {
+                    const int g = grp[st];
+                    int q = -1;
+                    for (int x = 0; x < tb.n_tp; ++x)
+                        if (tb.tp[x] == tpv[st]) q = x;
+                    if (g < 0 || g >= tb.G || q < 0) { bad = 1; break; }
+                    if (k < 0 || order[k] != g) {                  // first slot of a run of group g
+                        for (int x = 0; x <= k; ++x)
+                            if (order[x] == g) bad = 1;            // the group was left and entered again
+                        if (k >= 0) offs[k + 1] = forced_off[st];
+                        ++k;
+                        order[k] = uint16_t(g);
+                        used = 0;
+                    }
+                    used += tpv[st];
+                    if (used > tb.group_ndev[g]) bad = 1;
+                    forced_q[st] = uint8_t(q);
+                    forced_g[st] = uint16_t(g);
+                    forced_off[st + 1] = forced_off[st] + tpv[st];
+                }
+                offs[0] = 0;
+                if (!bad) offs[k + 1] = forced_off[S];
+                shared_int[1] = k + 1;
             }
-        if (__syncthreads_or(bad)) { leave(kSweepFailed + HARP_CAND_INVALID, 0); continue; }
-        if (tid == 0) {
-            int64_t o = 0;
-            offs[0] = 0;
-            for (int k = 0; k < K; ++k) { o += tb.group_ndev[order[k]]; offs[k + 1] = int32_t(o); }
+            if (__syncthreads_or(bad)) { leave(kSweepFailed + HARP_CAND_INVALID, 0); continue; }
+            K = shared_int[1];
+        } else {
+            K = od.ord_G[c];
+            const int32_t *og = od.ord_group + int64_t(c) * od.G_max;
+            int bad = (S < 1 || S > S_max || K < 1 || K > od.G_max) ? 1 : 0;
+            if (!bad)
+                for (int k = tid; k < K; k += nthreads) {
+                    const int g = og[k];
+                    if (g < 0 || g >= tb.G) { bad = 1; continue; }
+                    for (int q = 0; q < k; ++q)
+                        if (og[q] == g) bad = 1;
+                    order[k] = uint16_t(g);
+                }
+            if (__syncthreads_or(bad)) { leave(kSweepFailed + HARP_CAND_INVALID, 0); continue; }
+            if (tid == 0) {
+                int64_t o = 0;
+                offs[0] = 0;
+                for (int k = 0; k < K; ++k) { o += tb.group_ndev[order[k]]; offs[k + 1] = int32_t(o); }
+            }
+            __syncthreads();
         }
-        __syncthreads();
         const int Dtot = offs[K];
         if (S > L || S < K || S > Dtot) { leave(kSweepFailed + HARP_CAND_INFEASIBLE, 0); continue; }
         if (Dtot <= kMeshGroupTable) {
@@ -937,8 +1060,12 @@ __device__ __forceinline__ void mesh_sweep_body(const TablesDev &tb, const OrdDe
                 for (int d = offs[k] + tid; d < offs[k + 1]; d += nthreads) group_at[d] = uint16_t(k);
         }
         auto h1_pass = [&](int64_t at) -> int64_t {
-            if constexpr (kFast) return mesh_h1_pass_fast(tb, m, offs, order, group_at, sums_lds, K, S, n_dev, at);
-            else return mesh_h1_pass(tb, m, offs, order, group_at, K, S, n_dev, at);
+            if constexpr (kFast) return mesh_h1_pass_fast(tb, m, offs, order, group_at, sums_lds, K, S, n_dev, at, fq, fo);
+            else return mesh_h1_pass(tb, m, offs, order, group_at, K, S, n_dev, at, fq, fo);
+        };
+        auto next_cap = [&](int64_t after) -> int64_t {
+            if constexpr (kForced) return mesh_next_cap_slots<kFast>(tb, S, forced_g, forced_q, after, &next_slot);
+            else return mesh_next_cap<kFast>(tb, order, K, after, &next_slot);
         };
         // thread 0 backtracks the pass just run; everyone copies the plan to this item's slot
         auto keep = [&](int64_t at, int64_t T) {
@@ -953,8 +1080,8 @@ __device__ __forceinline__ void mesh_sweep_body(const TablesDev &tb, const OrdDe
         };
         if (!kRest) {
             int64_t t_S;
-            if constexpr (kFast) t_S = mesh_pass_fast<false>(tb, m, offs, order, group_at, sums_lds, K, S, n_dev, 0);
-            else t_S = mesh_pass<false>(tb, m, offs, order, group_at, K, S, n_dev, 0);
+            if constexpr (kFast) t_S = mesh_pass_fast<false>(tb, m, offs, order, group_at, sums_lds, K, S, n_dev, 0, fq, fo);
+            else t_S = mesh_pass<false>(tb, m, offs, order, group_at, K, S, n_dev, 0, fq, fo);
             if (t_S == kInf) { leave(kSweepFailed + HARP_CAND_INFEASIBLE, 0); continue; }
             cap = t_S;
             int state = kSweepFailed + HARP_CAND_INFEASIBLE;
@@ -967,7 +1094,7 @@ __device__ __forceinline__ void mesh_sweep_body(const TablesDev &tb, const OrdDe
                     break;
                 }
                 if (tried >= max_caps) break;
-                const int64_t nb = mesh_next_cap<kFast>(tb, order, K, cap, &next_slot);
+                const int64_t nb = next_cap(cap);
                 if (nb == kInf) break;
                 cap = nb;
             }
@@ -976,7 +1103,7 @@ __device__ __forceinline__ void mesh_sweep_body(const TablesDev &tb, const OrdDe
         } else {
             int64_t best_T = kInf;
             for (int step = 0; tried < max_caps; ++step) {
-                const int64_t nb = mesh_next_cap<kFast>(tb, order, K, cap, &next_slot);
+                const int64_t nb = next_cap(cap);
                 if (nb == kInf || nb > t_E) break;
                 cap = nb;
                 ++tried;
@@ -995,11 +1122,14 @@ __device__ __forceinline__ void mesh_sweep_body(const TablesDev &tb, const OrdDe
     }
 }
 
-template <bool kFast, bool kRest>
-__global__ __launch_bounds__(kMeshMaxThreads) void k2_mesh_h1f1b_sweep(TablesDev tb, OrdDev od, int max_caps, int W,
+template <bool kFast, bool kRest, bool kForced>
+__global__ __launch_bounds__(kMeshMaxThreads) void k2_mesh_h1f1b_sweep(TablesDev tb, OrdDev od,
+                                                                       const int32_t *cand_group,
+                                                                       const int32_t *cand_tp, int max_caps, int W,
                                                                        unsigned char *slots, unsigned char *ws,
                                                                        size_t per_group, int64_t n_dev, int *ticket) {
-    mesh_sweep_body<kFast, kRest>(tb, od, max_caps, W, slots, ws, per_group, n_dev, ticket);
+    mesh_sweep_body<kFast, kRest, kForced>(tb, od, cand_group, cand_tp, max_caps, W, slots, ws, per_group, n_dev,
+                                           ticket);
 }
 
 // One wavefront per ordering: the best of its W + 1 kept plans goes to the outputs.
@@ -1011,12 +1141,18 @@ __global__ __launch_bounds__(256) void k2_mesh_sweep_pick(TablesDev tb, OrdDev o
     if (c >= od.C) return;
     const int S_max = od.S_max;
     int32_t *sp = out.splits + int64_t(c) * (S_max + 1), *df = out.dev_first + int64_t(c) * S_max;
-    int32_t *sg = stage_group + int64_t(c) * S_max, *stp = stage_tp + int64_t(c) * S_max;
+    // a batch of candidates (fixed slicing) has no slicing to report
+    int32_t *sg = stage_group ? stage_group + int64_t(c) * S_max : nullptr;
+    int32_t *stp = stage_tp ? stage_tp + int64_t(c) * S_max : nullptr;
     int32_t *wu = warmup + int64_t(c) * S_max;
     const SweepSlot opening = sweep_slot(slots, S_max, W, c, W);
     if (opening.head->state != kSweepPlan) {
         for (int s = lane; s <= S_max; s += 64) sp[s] = -1;
-        for (int s = lane; s < S_max; s += 64) { df[s] = -1; sg[s] = -1; stp[s] = -1; wu[s] = -1; }
+        for (int s = lane; s < S_max; s += 64) {
+            df[s] = -1; wu[s] = -1;
+            if (sg) sg[s] = -1;
+            if (stp) stp[s] = -1;
+        }
         if (lane == 0) {
             out.bottleneck[c] = kInf;
             out.iter_time[c] = kInf;
@@ -1038,8 +1174,8 @@ __global__ __launch_bounds__(256) void k2_mesh_sweep_pick(TablesDev tb, OrdDev o
     const int S = od.ord_S[c];
     for (int s = lane; s <= S_max; s += 64) sp[s] = s <= S ? b.cuts[s] : -1;
     for (int s = lane; s < S_max; s += 64) {
-        sg[s] = s < S ? int32_t(b.g[s]) : -1;
-        stp[s] = s < S ? tb.tp[b.k[s]] : -1;
+        if (sg) sg[s] = s < S ? int32_t(b.g[s]) : -1;
+        if (stp) stp[s] = s < S ? tb.tp[b.k[s]] : -1;
         df[s] = s < S ? b.first[s] : -1;
         wu[s] = s < S ? b.count[s] : -1;
     }
@@ -1117,7 +1253,10 @@ void launch_plan_mesh_h1f1b(const TablesDev &tb, const OrdDev &od, const int64_t
                            stage_group, stage_tp, warmup, slices, per_group, total_devices, ticket);
 }
 
-void launch_plan_mesh_h1f1b_sweep(const TablesDev &tb, const OrdDev &od, int max_caps, const PlansDev &out,
+// cand_group / cand_tp not null: the batch holds candidates with a fixed slicing (od.ord_S = their
+// stage counts), and stage_group / stage_tp may be null.
+void launch_plan_mesh_h1f1b_sweep(const TablesDev &tb, const OrdDev &od, const int32_t *cand_group,
+                                  const int32_t *cand_tp, int max_caps, const PlansDev &out,
                                   int32_t *stage_group, int32_t *stage_tp, int32_t *warmup, int64_t *t_max_out,
                                   int32_t *n_caps, bool fast32, void *ws, int n_groups, int threads, int W,
                                   int64_t total_devices, hipStream_t st) {
@@ -1130,13 +1269,17 @@ void launch_plan_mesh_h1f1b_sweep(const TablesDev &tb, const OrdDev &od, int max
     const size_t lds = fast32 ? 2 * size_t(tb.L + 1) * sizeof(int64_t) : 0;
     const int first_groups = n_groups < od.C ? n_groups : od.C;
     const dim3 block(threads);
+    const bool forced = cand_group != nullptr;
     hipLaunchKernelGGL(k2_mesh_clear, dim3(1), dim3(64), 0, st, ticket);
-#define HARP_SWEEP_LAUNCH(F)                                                                                  \
-    hipLaunchKernelGGL(HIP_KERNEL_NAME(k2_mesh_h1f1b_sweep<F, false>), dim3(first_groups), block, lds, st, tb, od, \
-                       max_caps, W, slots, slices, per_group, total_devices, ticket);                           \
-    hipLaunchKernelGGL(HIP_KERNEL_NAME(k2_mesh_h1f1b_sweep<F, true>), dim3(n_groups), block, lds, st, tb, od,    \
-                       max_caps, W, slots, slices, per_group, total_devices, ticket + 1)
-    if (fast32) { HARP_SWEEP_LAUNCH(true); } else { HARP_SWEEP_LAUNCH(false); }
+#define HARP_SWEEP_LAUNCH(F, X)                                                                                  \
+    hipLaunchKernelGGL(HIP_KERNEL_NAME(k2_mesh_h1f1b_sweep<F, false, X>), dim3(first_groups), block, lds, st, tb,  \
+                       od, cand_group, cand_tp, max_caps, W, slots, slices, per_group, total_devices, ticket);      \
+    hipLaunchKernelGGL(HIP_KERNEL_NAME(k2_mesh_h1f1b_sweep<F, true, X>), dim3(n_groups), block, lds, st, tb, od,    \
+                       cand_group, cand_tp, max_caps, W, slots, slices, per_group, total_devices, ticket + 1)
+    if (fast32 && forced) { HARP_SWEEP_LAUNCH(true, true); }
+    else if (fast32) { HARP_SWEEP_LAUNCH(true, false); }
+    else if (forced) { HARP_SWEEP_LAUNCH(false, true); }
+    else { HARP_SWEEP_LAUNCH(false, false); }
 #undef HARP_SWEEP_LAUNCH
     hipLaunchKernelGGL(k2_mesh_sweep_pick, dim3((od.C + 3) / 4), dim3(256), 0, st, tb, od, W, slots, out,
                        stage_group, stage_tp, warmup, t_max_out, n_caps);

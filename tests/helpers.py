@@ -152,6 +152,22 @@ def oracle_plan_mesh_h1f1b_sweep_threaded(tables, orders, max_caps=1 << 20, thre
     return out
 
 
+def oracle_plan_h1f1b_sweep_threaded(tables, cands, max_caps=1 << 20, threads=None):
+    """Oracle answers of the search over the cap for a batch of candidates (fixed slicing)."""
+    import os
+    from concurrent.futures import ThreadPoolExecutor
+
+    import oracle
+    threads = threads or min(16, len(os.sched_getaffinity(0)))
+    out = oracle.Plans(cands.C, cands.S_max)
+    out.warmup = np.full((cands.C, cands.S_max), -1, dtype=np.int32)
+    out.t_max = np.full(cands.C, oracle.INF, dtype=np.int64)
+    out.n_caps = np.zeros(cands.C, dtype=np.int32)
+    with ThreadPoolExecutor(threads) as ex:
+        list(ex.map(lambda c: oracle.plan_h1f1b_sweep_batch(tables, cands, max_caps, c, c + 1, out), range(cands.C)))
+    return out
+
+
 def assert_plans_equal(got, want, label=""):
     """Bit-exact comparison of every output array of a batch."""
     for name in ("status", "splits", "dev_first", "bottleneck", "iter_time"):

@@ -264,3 +264,56 @@ def test_h1f1b_full_stress_batch_properties(harp, ctx):
     assert (ost == 0).all() and (owu == got.warmup[idx]).all() and (ot == got.iter_time[idx]).all()
     print("stress: %d of %d feasible under H-1F1B counts at the exact search's caps (classic counts: %d)"
           % (ok.sum(), cands.C, (exact.status == oracle.OK).sum()))
+
+
+def _check_sweep(harp, ctx, problem, cands, label, max_caps=1 << 20):
+    from helpers import oracle_plan_h1f1b_sweep_threaded
+    want = oracle_plan_h1f1b_sweep_threaded(oracle.build_tables(problem), cands, max_caps)
+    fast32 = harp.Tables(ctx, problem).fast32
+    for path in [harp.PATH_GENERIC] + ([harp.PATH_FAST32] if fast32 else []):
+        tag = "%s (path %d)" % (label, path)
+        got, _ = harp.plan_h1f1b_sweep(ctx, problem, cands, max_caps, path)
+        assert_plans_equal(got, want, tag)
+        for name in ("warmup", "t_max", "n_caps"):
+            a, b = getattr(got, name), getattr(want, name)
+            if not (a == b).all():
+                bad = np.nonzero((a != b).reshape(a.shape[0], -1).any(axis=1))[0]
+                raise AssertionError("%s: %s differs at %d candidates, first %d: got %s want %s"
+                                     % (tag, name, bad.size, bad[0], a[bad[0]], b[bad[0]]))
+    return got, want
+
+
+def test_h1f1b_sweep_of_candidates(harp, ctx):
+    """The search over the cap for candidates with a fixed slicing (section 5.2.4 (2) around the
+    capped H-1F1B recurrence) against the oracle: plans, counts, chosen cap and caps tried."""
+    feasible = moved = 0
+    for seed in range(150):
+        w = W.random_small(seed)
+        cands = w.candidates()
+        got, want = _check_sweep(harp, ctx, w.problem, cands, "seed %d" % seed)
+        ok = want.status == oracle.OK
+        feasible += int(ok.sum())
+        mm, _ = harp.plan(ctx, w.problem, cands)
+        moved += int((want.t_max[ok] != mm.bottleneck[ok]).sum())
+        if seed % 10 == 0:
+            _check_sweep(harp, ctx, w.problem, cands, "seed %d, 2 caps" % seed, max_caps=2)
+    assert feasible > 500 and moved > 20
+    # malformed and infeasible candidates; an empty batch
+    p = simple_problem([5, 3, 8, 2, 7, 4], M=3, G=3, ndev=(2, 2, 1), tp=(1, 2), bw=np.full((3, 3), 2),
+                       act=[4, 9, 2, 7, 5, 3], params=[1] * 6, stash=[1] * 6, mem=[40])
+    lists = [[(0, 1), (0, 1), (1, 2)], [(0, 2), (1, 1), (2, 1)], [(0, 1), (1, 1), (0, 1)], [(0, 2), (0, 1)],
+             [(0, 3)], [(5, 1)], [(2, 1)] * 1 + [(1, 1)] * 2 + [(0, 1)] * 2 + [(0, 2)], [(1, 2)]]
+    cands = cands_from_lists(lists, S_max=7)
+    _, want = _check_sweep(harp, ctx, p, cands, "statuses")
+    assert {oracle.OK, oracle.INVALID} <= set(want.status)
+    got, _ = harp.plan_h1f1b_sweep(ctx, p, cands.slice(0, 0))
+    assert got.status.shape == (0,)
+    for name, n in (("tiny", 16), ("llama7b", 64), ("llama70b", 24)):
+        w = W.make(name)
+        cands = w.candidates(0, n)
+        got, want = _check_sweep(harp, ctx, w.problem, cands, name)
+        ok = want.status == oracle.OK
+        assert ok.any() and (name != "llama70b" or (want.status == oracle.INFEASIBLE).any())
+        at, _ = harp.plan_h1f1b(ctx, w.problem, cands, np.where(ok, want.t_max, -1))
+        for field in ("splits", "warmup", "iter_time"):
+            assert (getattr(at, field)[ok] == getattr(got, field)[ok]).all(), (name, field)
