@@ -358,6 +358,41 @@ def mesh_search(ctx, binding, torch, workloads, name, n_orders, reps, cpu_orders
                                             "kind": "oracle", "sample": "first %d orderings under a limit of %d caps, "
                                             "one ordering per thread, %.1f s wall; GPU answers under the same limit "
                                             "verified bit-exact" % (n_chk, limit, dt)}
+    # the same search for candidates of this workload (fixed slicing)
+    if sweep_orders:
+        cands = w.candidates(0, min(w.C, sweep_orders))
+        dcs = binding.DeviceCandidates(ctx, cands)
+        out_c = binding.DevicePlans(ctx, dcs.C, dcs.S_max)
+        wu_c = torch.empty((dcs.C, dcs.S_max), dtype=torch.int32, device=ctx.device)
+        tm_c = torch.empty(dcs.C, dtype=torch.int64, device=ctx.device)
+        nc_c = torch.empty(dcs.C, dtype=torch.int32, device=ctx.device)
+        ws_c = binding.h1f1b_sweep_workspace(ctx, tables, dcs)
+        ms_c = timed_ms(torch, lambda: binding.harp_plan_h1f1b_sweep_batch(ctx, tables, dcs, 1 << 20, out_c, wu_c, tm_c,
+                                                                           ws_c, nc_c), 1, warmup=0)
+        tried_c = nc_c.cpu().numpy()
+        res["candidate_sweep"] = {"kernel": "k2_mesh_h1f1b_sweep, fixed slicing (one harp_plan_h1f1b_sweep_batch call)",
+                                  "candidates": int(dcs.C), "ms_per_call": ms_c,
+                                  "mean_caps_tried": float(tried_c.mean()), "max_caps_tried": int(tried_c.max()),
+                                  "passes_per_s": float(tried_c.sum()) / (ms_c * 1e-3),
+                                  "feasible_fraction": float((out_c.to_host().status == 0).mean())}
+        if cpu_orders:
+            import oracle
+            from concurrent.futures import ThreadPoolExecutor
+            n_chk, limit = min(dcs.C, 16), 24
+            binding.harp_plan_h1f1b_sweep_batch(ctx, tables, dcs, limit, out_c, wu_c, tm_c, ws_c, nc_c)
+            torch.cuda.synchronize()
+            lim = out_c.to_host()
+            ot = oracle.build_tables(p)
+            with ThreadPoolExecutor(min(16, len(os.sched_getaffinity(0)))) as ex:
+                outs = list(ex.map(lambda c: oracle.plan_h1f1b_sweep_batch(ot, cands, limit, c, c + 1), range(n_chk)))
+            for c, want in enumerate(outs):
+                for name in ("status", "splits", "dev_first", "bottleneck", "iter_time"):
+                    if not (getattr(want, name)[c] == getattr(lim, name)[c]).all():
+                        raise SystemExit("GPU candidate sweep differs from the oracle in %s at candidate %d" % (name, c))
+                if want.t_max[c] != int(tm_c[c].item()) or want.n_caps[c] != int(nc_c[c].item()):
+                    raise SystemExit("GPU candidate sweep differs from the oracle in the cap chosen at candidate %d" % c)
+            res["candidate_sweep"]["check"] = ("first %d candidates under a limit of %d caps verified bit-exact "
+                                               "against the oracle" % (n_chk, limit))
     timed_ms(torch, lambda: binding.harp_plan_mesh_batch(ctx, tables, do, out, sg, st, ws), 1)   # restore sg, st
     if cpu_orders:
         import oracle
