@@ -163,7 +163,8 @@ SweepLayout sweep_layout(const harp_ctx *ctx, const harp_tables *t, const harp_o
     W = W < 1 ? 1 : (W > 32 ? 32 : W);
     s.W = int(W);
     s.groups = int(resident < C * W ? resident : C * W);
-    s.bytes = 256 + size_t(s.groups) * s.per_group + size_t(C) * size_t(W + 1) * plan_mesh_sweep_slot_bytes(od->S_max);
+    s.bytes = 256 + size_t(s.groups) * s.per_group + size_t(C) * size_t(W + 1) * plan_mesh_sweep_slot_bytes(od->S_max) +
+              ((size_t(C) * sizeof(int) + 255) & ~size_t(255));
     return s;
 }
 

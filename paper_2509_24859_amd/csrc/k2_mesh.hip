@@ -899,19 +899,19 @@ __device__ __forceinline__ int64_t mesh_next_cap_slots(const TablesDev &tb, int 
     return v == ~0ull ? kInf : int64_t(v);
 }
 
-// The search around the full recurrence (section 5.2.4 (2)) in three launches, so that the caps of
-// one ordering can be tried by several workgroups at once (the batched evaluation of 5.2.4 (3)):
-//  first:  one workgroup per ordering; the classic min-max pass gives the lower end t_S of the
-//          sweep (no cap below it admits a plan, and H-1F1B's counts are never below the classic
-//          ones); the caps are then taken in increasing order until one has a plan, which fixes
-//          t_E = ceil(T / B);
-//  rest:   W workgroups per ordering; each walks ALL later caps up to t_E (finding the next cap
-//          costs a few percent of a pass) and runs the H-1F1B pass on every W-th of them, keeping
-//          its best plan;
+// The search around the full recurrence (section 5.2.4 (2)), with the caps of one ordering shared
+// by W workgroups (the batched evaluation of 5.2.4 (3)).  The k-th candidate value at or above t_S
+// has index k whoever tries it, and walker j of an ordering tries the indices congruent to j.
+//  climb:  every walker runs the classic min-max pass for the lower end t_S (no cap below it admits
+//          a plan, and H-1F1B's counts are never below the classic ones), then walks the caps
+//          upwards, running the H-1F1B pass on its own indices until one has a plan; the lowest such
+//          index is kept as an atomic minimum, and a walker stops once it is above that minimum;
+//  open:   the walker with the lowest index hands its plan over; it fixes t_E = ceil(T / B);
+//  rest:   every walker walks ALL later caps up to t_E (finding the next cap costs a few percent
+//          of a pass) and runs the H-1F1B pass on its own indices, keeping its best plan;
 //  pick:   per ordering the smallest T = least sum + (B - 1) cap over the W + 1 kept plans, the
 //          lower cap on equal T; that is what trying the caps one after the other returns.
-// The k-th cap tried has index k whoever tries it, so the limit max_caps cuts the sweep at the
-// same cap for every W.
+// The limit max_caps cuts the sweep at the same cap for every W.
 struct SweepHead {
     int64_t T, cap;
     int32_t tried, state;    // state: kSweepNone, kSweepPlan, or kSweepFailed + a candidate status
@@ -952,8 +952,8 @@ __device__ __forceinline__ SweepSlot sweep_slot(unsigned char *slots, int S_max,
 template <bool kFast, bool kRest, bool kForced>
 __device__ __forceinline__ void mesh_sweep_body(const TablesDev &tb, const OrdDev &od, const int32_t *cand_group,
                                                 const int32_t *cand_tp, int max_caps, int W,
-                                                unsigned char *slots, unsigned char *ws, size_t per_group,
-                                                int64_t n_dev, int *ticket) {
+                                                unsigned char *slots, int *first_idx, unsigned char *ws,
+                                                size_t per_group, int64_t n_dev, int *ticket) {
     extern __shared__ __align__(16) unsigned char mesh_lds[];      // fast form: PP and PS (or Q), L + 1 entries each
     int64_t *sums_lds = reinterpret_cast<int64_t *>(mesh_lds);
     __shared__ int32_t offs[kMaxOrderGroups + 1];
@@ -972,7 +972,7 @@ __device__ __forceinline__ void mesh_sweep_body(const TablesDev &tb, const OrdDe
     const int tid = threadIdx.x, nthreads = blockDim.x;
     const MeshSlice m = mesh_slice(ws, per_group, L, n_dev);
     const int64_t m_cap = tb.M;
-    const int n_items = kRest ? od.C * W : od.C;
+    const int n_items = od.C * W;
     const uint8_t *fq = kForced ? forced_q : nullptr;
     const int32_t *fo = kForced ? forced_off : nullptr;
 
@@ -982,7 +982,7 @@ __device__ __forceinline__ void mesh_sweep_body(const TablesDev &tb, const OrdDe
         __syncthreads();
         const int item = shared_int[0];
         if (item >= n_items) break;
-        const int c = kRest ? item / W : item, j = kRest ? item - c * W : W;
+        const int c = item / W, j = item - c * W;
         const SweepSlot mine = sweep_slot(slots, S_max, W, c, j);
         const SweepSlot opening = sweep_slot(slots, S_max, W, c, W);
         auto leave = [&](int state, int tried) {
@@ -1079,19 +1079,30 @@ __device__ __forceinline__ void mesh_sweep_body(const TablesDev &tb, const OrdDe
             if (tid == 0) { mine.head->T = T; mine.head->cap = at; }
         };
         if (!kRest) {
+            // the climb from t_S to the first cap with a plan, shared by the W walkers of the
+            // ordering: each walks every cap and tries those with its own index modulo W; the lowest
+            // index found so far (first_idx, an atomic minimum) tells the others where to stop.  Every
+            // index below the final minimum has been tried by its walker and has no plan.
             int64_t t_S;
             if constexpr (kFast) t_S = mesh_pass_fast<false>(tb, m, offs, order, group_at, sums_lds, K, S, n_dev, 0, fq, fo);
             else t_S = mesh_pass<false>(tb, m, offs, order, group_at, K, S, n_dev, 0, fq, fo);
             if (t_S == kInf) { leave(kSweepFailed + HARP_CAND_INFEASIBLE, 0); continue; }
             cap = t_S;
             int state = kSweepFailed + HARP_CAND_INFEASIBLE;
-            for (;;) {
-                const int64_t sum = h1_pass(cap);
-                ++tried;
-                if (sum != kInf) {
-                    keep(cap, sum + (m_cap - 1) * cap);
-                    state = kSweepPlan;
-                    break;
+            for (int idx = 0;; ++idx) {
+                __syncthreads();
+                if (tid == 0) shared_int[1] = atomicAdd(&first_idx[c], 0);
+                __syncthreads();
+                if (idx > shared_int[1]) { state = kSweepNone; break; }        // a lower cap already has a plan
+                tried = idx + 1;
+                if (idx % W == j) {
+                    const int64_t sum = h1_pass(cap);
+                    if (sum != kInf) {
+                        keep(cap, sum + (m_cap - 1) * cap);
+                        if (tid == 0) atomicMin(&first_idx[c], idx);
+                        state = kSweepPlan;
+                        break;
+                    }
                 }
                 if (tried >= max_caps) break;
                 const int64_t nb = next_cap(cap);
@@ -1126,10 +1137,43 @@ template <bool kFast, bool kRest, bool kForced>
 __global__ __launch_bounds__(kMeshMaxThreads) void k2_mesh_h1f1b_sweep(TablesDev tb, OrdDev od,
                                                                        const int32_t *cand_group,
                                                                        const int32_t *cand_tp, int max_caps, int W,
-                                                                       unsigned char *slots, unsigned char *ws,
-                                                                       size_t per_group, int64_t n_dev, int *ticket) {
-    mesh_sweep_body<kFast, kRest, kForced>(tb, od, cand_group, cand_tp, max_caps, W, slots, ws, per_group, n_dev,
-                                           ticket);
+                                                                       unsigned char *slots, int *first_idx,
+                                                                       unsigned char *ws, size_t per_group,
+                                                                       int64_t n_dev, int *ticket) {
+    mesh_sweep_body<kFast, kRest, kForced>(tb, od, cand_group, cand_tp, max_caps, W, slots, first_idx, ws, per_group,
+                                           n_dev, ticket);
+}
+
+// Between the two launches, one wavefront per ordering: the walker that found the lowest cap with a
+// plan (index first_idx, walker first_idx mod W) hands its plan over as the opening of the sweep;
+// without one, the opening carries walker 0's verdict and count of caps tried.
+__global__ __launch_bounds__(256) void k2_mesh_sweep_open(OrdDev od, int W, unsigned char *slots,
+                                                          const int *first_idx) {
+    const int lane = threadIdx.x & 63;
+    const int c = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    if (c >= od.C) return;
+    const int S_max = od.S_max;
+    const SweepSlot opening = sweep_slot(slots, S_max, W, c, W);
+    const int f = first_idx[c];
+    const SweepSlot from = sweep_slot(slots, S_max, W, c, f == INT32_MAX ? 0 : f % W);
+    if (f != INT32_MAX) {
+        for (int s = lane; s <= S_max; s += 64) opening.cuts[s] = from.cuts[s];
+        for (int s = lane; s < S_max; s += 64) {
+            opening.first[s] = from.first[s]; opening.count[s] = from.count[s];
+            opening.g[s] = from.g[s]; opening.k[s] = from.k[s];
+        }
+    }
+    if (lane == 0) {
+        opening.head->T = from.head->T;
+        opening.head->cap = from.head->cap;
+        opening.head->tried = f == INT32_MAX ? from.head->tried : f + 1;
+        opening.head->state = from.head->state;
+    }
+}
+
+__global__ void k2_mesh_sweep_clear(int *first_idx, int C) {
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c < C) first_idx[c] = INT32_MAX;
 }
 
 // One wavefront per ordering: the best of its W + 1 kept plans goes to the outputs.
@@ -1260,22 +1304,25 @@ void launch_plan_mesh_h1f1b_sweep(const TablesDev &tb, const OrdDev &od, const i
                                   int32_t *stage_group, int32_t *stage_tp, int32_t *warmup, int64_t *t_max_out,
                                   int32_t *n_caps, bool fast32, void *ws, int n_groups, int threads, int W,
                                   int64_t total_devices, hipStream_t st) {
-    // layout: 256 bytes for the tickets, n_groups slices, then (W + 1) kept plans per ordering
+    // layout: 256 bytes for the tickets, n_groups slices, (W + 1) kept plans per ordering, one int per ordering
     int *ticket = static_cast<int *>(ws);
     unsigned char *slices = static_cast<unsigned char *>(ws) + 256;
     const size_t per_group = plan_mesh_ws_per_group(tb.L, od.S_max, total_devices);
     unsigned char *slots = slices + size_t(n_groups) * per_group;
+    int *first_idx = reinterpret_cast<int *>(slots + size_t(od.C) * size_t(W + 1) * sweep_slot_bytes(od.S_max));
     fast32 = fast32 && tb.L <= kMeshFastMaxL;
     const size_t lds = fast32 ? 2 * size_t(tb.L + 1) * sizeof(int64_t) : 0;
-    const int first_groups = n_groups < od.C ? n_groups : od.C;
     const dim3 block(threads);
     const bool forced = cand_group != nullptr;
     hipLaunchKernelGGL(k2_mesh_clear, dim3(1), dim3(64), 0, st, ticket);
+    hipLaunchKernelGGL(k2_mesh_sweep_clear, dim3((od.C + 255) / 256), dim3(256), 0, st, first_idx, od.C);
 #define HARP_SWEEP_LAUNCH(F, X)                                                                                  \
-    hipLaunchKernelGGL(HIP_KERNEL_NAME(k2_mesh_h1f1b_sweep<F, false, X>), dim3(first_groups), block, lds, st, tb,  \
-                       od, cand_group, cand_tp, max_caps, W, slots, slices, per_group, total_devices, ticket);      \
+    hipLaunchKernelGGL(HIP_KERNEL_NAME(k2_mesh_h1f1b_sweep<F, false, X>), dim3(n_groups), block, lds, st, tb, od,   \
+                       cand_group, cand_tp, max_caps, W, slots, first_idx, slices, per_group, total_devices, ticket); \
+    hipLaunchKernelGGL(k2_mesh_sweep_open, dim3((od.C + 3) / 4), dim3(256), 0, st, od, W, slots, first_idx);       \
     hipLaunchKernelGGL(HIP_KERNEL_NAME(k2_mesh_h1f1b_sweep<F, true, X>), dim3(n_groups), block, lds, st, tb, od,    \
-                       cand_group, cand_tp, max_caps, W, slots, slices, per_group, total_devices, ticket + 1)
+                       cand_group, cand_tp, max_caps, W, slots, first_idx, slices, per_group, total_devices,        \
+                       ticket + 1)
     if (fast32 && forced) { HARP_SWEEP_LAUNCH(true, true); }
     else if (fast32) { HARP_SWEEP_LAUNCH(true, false); }
     else if (forced) { HARP_SWEEP_LAUNCH(false, true); }
