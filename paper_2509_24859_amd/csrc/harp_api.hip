@@ -153,7 +153,9 @@ struct SweepLayout {
 SweepLayout sweep_layout(const harp_ctx *ctx, const harp_tables *t, const harp_orderings *od) {
     SweepLayout s;
     s.per_group = plan_mesh_ws_per_group(t->dev.L, od->S_max, t->total_devices);
-    s.threads = plan_mesh_threads(t->dev.L, t->total_devices, od->C, ctx->n_cu);
+    // up to 32 walkers share an ordering, so the batch fills the chip 32 times sooner than for one pass
+    const long long walkers = (long long)(od->C > 0 ? od->C : 1) * 32;
+    s.threads = plan_mesh_threads(t->dev.L, t->total_devices, int(walkers < (1 << 30) ? walkers : (1 << 30)), ctx->n_cu);
     long long resident = (long long)ctx->n_cu * (2048 / s.threads);
     const long long fit = (long long)((size_t(16) << 30) / (s.per_group ? s.per_group : 1));
     if (resident > fit) resident = fit;

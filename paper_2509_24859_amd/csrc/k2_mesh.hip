@@ -778,26 +778,29 @@ __global__ __launch_bounds__(kMeshMaxThreads) void k2_mesh_h1f1b(TablesDev tb, O
     mesh_h1_body<kFast>(tb, od, t_max, out, stage_group, stage_tp, warmup, ws, per_group, n_dev, ticket);
 }
 
-// The smallest candidate cap above b (section 5.2.4 (2)): candidate caps of an ordering are the
-// stage times of every listed group, usable degree and operator range, and the transfer times of
-// the inner cuts on the links the ordering can use (inside a group, and to the group after it).
-// A stage time grows with its end cut, so per (group, degree, start) a binary search finds the
-// first one above b; transfer times are looked at one by one.  Every thread takes part; kInf when
-// there is none.
-template <bool kFast>
-__device__ __forceinline__ int64_t mesh_next_cap(const TablesDev &tb, const uint16_t *order, int K, int64_t b,
-                                                 unsigned long long *slot) {
+// The smallest candidate cap above b (section 5.2.4 (2)).  Candidate caps are stage times of
+// (group, degree) rows over every operator range, and transfer times of the inner cuts on some
+// links; which rows and links is up to the caller (row_of(r, g, q) and link_of(r, g, h) return
+// false for entries to skip).  A stage time grows with its end cut, so per (row, start cut) the
+// first time above b is found by a binary search, or, when the caller lends a position array
+// (pos, one entry per (row, start cut), filled by a call with fresh = true), by moving the
+// position kept from the previous call forward: within one sweep b only rises, so the positions
+// only advance and a call costs about one table read per entry.  Transfer times are looked at one
+// by one.  Every thread takes part; kInf when there is none.
+template <bool kFast, typename RowFn, typename LinkFn>
+__device__ __forceinline__ int64_t next_cap_over(const TablesDev &tb, int n_rows, RowFn row_of, int n_links,
+                                                 LinkFn link_of, int64_t b, unsigned long long *slot,
+                                                 uint16_t *pos, bool fresh) {
     const int L = tb.L, tid = threadIdx.x, nthreads = blockDim.x;
     __syncthreads();
     if (tid == 0) *slot = ~0ull;
     __syncthreads();
     unsigned long long least = ~0ull;
-    const int n_rows = K * tb.n_tp;
     for (int x = tid; x < n_rows * L; x += nthreads) {
-        const int j = x % L, r = x / L, q = r % tb.n_tp, k = r / tb.n_tp;
-        const int g = order[k];
+        const int j = x % L, r = x / L;
+        int g, q;
+        if (!row_of(r, g, q)) continue;
         const int64_t tp = tb.tp[q];
-        if (tp > tb.group_ndev[g]) continue;
         const int shift = tb.tp_shift[q];
         const uint32_t *p32 = kFast ? tb.P32 + (int64_t(g) * tb.n_tp + q) * tb.pitch32 : nullptr;
         const int64_t *pf = tb.PF(tb.group_type[g]), *pr = tb.PR(g, q);
@@ -806,20 +809,31 @@ __device__ __forceinline__ int64_t mesh_next_cap(const TablesDev &tb, const uint
             const int64_t work = pf[i] - pf[j];
             return (shift >= 0 ? (work + tp - 1) >> shift : (work + tp - 1) / tp) + (pr[i] - pr[j]);
         };
-        if (time_to(L) <= b) continue;
-        int lo = j + 1, hi = L;                       // time_to(hi) > b
-        while (lo < hi) {
-            const int mid = (lo + hi) >> 1;
-            if (time_to(mid) > b) hi = mid; else lo = mid + 1;
+        int i;                                        // first end cut whose time is above b; L + 1: none
+        if (pos && !fresh) {
+            i = pos[x];
+            while (i <= L && time_to(i) <= b) ++i;
+        } else if (time_to(L) <= b) {
+            i = L + 1;
+        } else {
+            int lo = j + 1, hi = L;                   // time_to(hi) > b
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                if (time_to(mid) > b) hi = mid; else lo = mid + 1;
+            }
+            i = hi;
         }
-        const unsigned long long v = (unsigned long long)time_to(hi);
-        least = v < least ? v : least;
+        if (pos) pos[x] = uint16_t(i);
+        if (i <= L) {
+            const unsigned long long v = (unsigned long long)time_to(i);
+            least = v < least ? v : least;
+        }
     }
     if (L >= 2) {
-        for (int x = tid; x < K * 2 * (L - 1); x += nthreads) {
-            const int i = 1 + x % (L - 1), r = x / (L - 1), k = r >> 1;
-            if ((r & 1) && k + 1 >= K) continue;
-            const int g = order[k], h = (r & 1) ? order[k + 1] : g;
+        for (int x = tid; x < n_links * (L - 1); x += nthreads) {
+            const int i = 1 + x % (L - 1), r = x / (L - 1);
+            int g, h;
+            if (!link_of(r, g, h)) continue;
             int64_t v;
             if (kFast) {
                 v = tb.CM[(int64_t(g) * tb.G + h) * tb.pitch32 + i];
@@ -842,61 +856,43 @@ __device__ __forceinline__ int64_t mesh_next_cap(const TablesDev &tb, const uint
     return v == ~0ull ? kInf : int64_t(v);
 }
 
-// The same for a fixed slicing: the candidate values are the stage times of the slots (group and
-// degree of every stage given) and the transfer times on the links between consecutive slots.
+// Candidate caps of an ordering: the stage times of every listed group and usable degree, and the
+// transfer times on the links the ordering can use (inside a group, and to the group after it).
+template <bool kFast>
+__device__ __forceinline__ int64_t mesh_next_cap(const TablesDev &tb, const uint16_t *order, int K, int64_t b,
+                                                 unsigned long long *slot, uint16_t *pos, bool fresh) {
+    auto row_of = [&](int r, int &g, int &q) -> bool {
+        q = r % tb.n_tp;
+        g = order[r / tb.n_tp];
+        return tb.tp[q] <= tb.group_ndev[g];
+    };
+    auto link_of = [&](int r, int &g, int &h) -> bool {
+        const int k = r >> 1;
+        if ((r & 1) && k + 1 >= K) return false;
+        g = order[k];
+        h = (r & 1) ? order[k + 1] : g;
+        return true;
+    };
+    return next_cap_over<kFast>(tb, K * tb.n_tp, row_of, 2 * K, link_of, b, slot, pos, fresh);
+}
+
+// Candidate caps of a fixed slicing: the stage times of the slots (group and degree of every stage
+// given) and the transfer times on the links between consecutive slots.
 template <bool kFast>
 __device__ __forceinline__ int64_t mesh_next_cap_slots(const TablesDev &tb, int S, const uint16_t *stage_g,
-                                                       const uint8_t *stage_q, int64_t b, unsigned long long *slot) {
-    const int L = tb.L, tid = threadIdx.x, nthreads = blockDim.x;
-    __syncthreads();
-    if (tid == 0) *slot = ~0ull;
-    __syncthreads();
-    unsigned long long least = ~0ull;
-    for (int x = tid; x < S * L; x += nthreads) {
-        const int j = x % L, st = x / L, q = stage_q[st];
-        const int g = stage_g[st];
-        const int64_t tp = tb.tp[q];
-        const int shift = tb.tp_shift[q];
-        const uint32_t *p32 = kFast ? tb.P32 + (int64_t(g) * tb.n_tp + q) * tb.pitch32 : nullptr;
-        const int64_t *pf = tb.PF(tb.group_type[g]), *pr = tb.PR(g, q);
-        auto time_to = [&](int i) -> int64_t {
-            if (kFast) return int64_t((p32[i] + uint32_t(tp) - 1u - p32[j]) >> shift);
-            const int64_t work = pf[i] - pf[j];
-            return (shift >= 0 ? (work + tp - 1) >> shift : (work + tp - 1) / tp) + (pr[i] - pr[j]);
-        };
-        if (time_to(L) <= b) continue;
-        int lo = j + 1, hi = L;                       // time_to(hi) > b
-        while (lo < hi) {
-            const int mid = (lo + hi) >> 1;
-            if (time_to(mid) > b) hi = mid; else lo = mid + 1;
-        }
-        const unsigned long long v = (unsigned long long)time_to(hi);
-        least = v < least ? v : least;
-    }
-    if (L >= 2) {
-        for (int x = tid; x < (S - 1) * (L - 1); x += nthreads) {
-            const int i = 1 + x % (L - 1), st = x / (L - 1);
-            const int g = stage_g[st], h = stage_g[st + 1];
-            int64_t v;
-            if (kFast) {
-                v = tb.CM[(int64_t(g) * tb.G + h) * tb.pitch32 + i];
-            } else {
-                const int64_t link = tb.bw[int64_t(g) * tb.G + h];
-                v = (tb.act_bytes[i - 1] + link - 1) / link;
-            }
-            if (v > b && (unsigned long long)v < least) least = (unsigned long long)v;
-        }
-    }
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) {
-        const uint32_t lo = __shfl_xor(uint32_t(least), d, 64), hi = __shfl_xor(uint32_t(least >> 32), d, 64);
-        const unsigned long long o = ((unsigned long long)hi << 32) | lo;
-        least = o < least ? o : least;
-    }
-    if ((tid & 63) == 0 && least != ~0ull) atomicMin(slot, least);
-    __syncthreads();
-    const unsigned long long v = *slot;
-    return v == ~0ull ? kInf : int64_t(v);
+                                                       const uint8_t *stage_q, int64_t b, unsigned long long *slot,
+                                                       uint16_t *pos, bool fresh) {
+    auto row_of = [&](int r, int &g, int &q) -> bool {
+        g = stage_g[r];
+        q = stage_q[r];
+        return true;
+    };
+    auto link_of = [&](int r, int &g, int &h) -> bool {
+        g = stage_g[r];
+        h = stage_g[r + 1];
+        return true;
+    };
+    return next_cap_over<kFast>(tb, S, row_of, S - 1, link_of, b, slot, pos, fresh);
 }
 
 // The search around the full recurrence (section 5.2.4 (2)), with the caps of one ordering shared
@@ -953,9 +949,11 @@ template <bool kFast, bool kRest, bool kForced>
 __device__ __forceinline__ void mesh_sweep_body(const TablesDev &tb, const OrdDev &od, const int32_t *cand_group,
                                                 const int32_t *cand_tp, int max_caps, int W,
                                                 unsigned char *slots, int *first_idx, unsigned char *ws,
-                                                size_t per_group, int64_t n_dev, int *ticket) {
-    extern __shared__ __align__(16) unsigned char mesh_lds[];      // fast form: PP and PS (or Q), L + 1 entries each
+                                                size_t per_group, int64_t n_dev, int *ticket, size_t pos_bytes) {
+    // fast form: PP and PS (or Q), L + 1 entries each; then pos_bytes of cap positions
+    extern __shared__ __align__(16) unsigned char mesh_lds[];
     int64_t *sums_lds = reinterpret_cast<int64_t *>(mesh_lds);
+    uint16_t *pos_lds = reinterpret_cast<uint16_t *>(mesh_lds + (kFast ? 2 * size_t(tb.L + 1) * sizeof(int64_t) : 0));
     __shared__ int32_t offs[kMaxOrderGroups + 1];
     __shared__ uint16_t order[kMaxOrderGroups];
     __shared__ uint16_t group_at[kMeshGroupTable];
@@ -1063,9 +1061,15 @@ __device__ __forceinline__ void mesh_sweep_body(const TablesDev &tb, const OrdDe
             if constexpr (kFast) return mesh_h1_pass_fast(tb, m, offs, order, group_at, sums_lds, K, S, n_dev, at, fq, fo);
             else return mesh_h1_pass(tb, m, offs, order, group_at, K, S, n_dev, at, fq, fo);
         };
+        // positions of the candidate values, kept between calls when this item's rows fit in the array
+        const int cap_rows = kForced ? S : K * tb.n_tp;
+        uint16_t *pos = (L < 65535 && size_t(cap_rows) * size_t(L) * sizeof(uint16_t) <= pos_bytes) ? pos_lds : nullptr;
+        bool fresh = true;
         auto next_cap = [&](int64_t after) -> int64_t {
-            if constexpr (kForced) return mesh_next_cap_slots<kFast>(tb, S, forced_g, forced_q, after, &next_slot);
-            else return mesh_next_cap<kFast>(tb, order, K, after, &next_slot);
+            const bool first_call = fresh;
+            fresh = false;
+            if constexpr (kForced) return mesh_next_cap_slots<kFast>(tb, S, forced_g, forced_q, after, &next_slot, pos, first_call);
+            else return mesh_next_cap<kFast>(tb, order, K, after, &next_slot, pos, first_call);
         };
         // thread 0 backtracks the pass just run; everyone copies the plan to this item's slot
         auto keep = [&](int64_t at, int64_t T) {
@@ -1139,9 +1143,9 @@ __global__ __launch_bounds__(kMeshMaxThreads) void k2_mesh_h1f1b_sweep(TablesDev
                                                                        const int32_t *cand_tp, int max_caps, int W,
                                                                        unsigned char *slots, int *first_idx,
                                                                        unsigned char *ws, size_t per_group,
-                                                                       int64_t n_dev, int *ticket) {
+                                                                       int64_t n_dev, int *ticket, size_t pos_bytes) {
     mesh_sweep_body<kFast, kRest, kForced>(tb, od, cand_group, cand_tp, max_caps, W, slots, first_idx, ws, per_group,
-                                           n_dev, ticket);
+                                           n_dev, ticket, pos_bytes);
 }
 
 // Between the two launches, one wavefront per ordering: the walker that found the lowest cap with a
@@ -1311,18 +1315,25 @@ void launch_plan_mesh_h1f1b_sweep(const TablesDev &tb, const OrdDev &od, const i
     unsigned char *slots = slices + size_t(n_groups) * per_group;
     int *first_idx = reinterpret_cast<int *>(slots + size_t(od.C) * size_t(W + 1) * sweep_slot_bytes(od.S_max));
     fast32 = fast32 && tb.L <= kMeshFastMaxL;
-    const size_t lds = fast32 ? 2 * size_t(tb.L + 1) * sizeof(int64_t) : 0;
-    const dim3 block(threads);
     const bool forced = cand_group != nullptr;
+    // cap positions: one uint16 per (row, start cut), kept in LDS when the largest item's rows fit
+    // beside the static arrays in a workgroup's 64 KiB
+    const size_t sums = fast32 ? 2 * size_t(tb.L + 1) * sizeof(int64_t) : 0;
+    const size_t rows_max = forced ? size_t(od.S_max) : size_t(tb.G) * size_t(tb.n_tp);
+    size_t pos_bytes = (rows_max * size_t(tb.L) * sizeof(uint16_t) + 15) & ~size_t(15);
+    if (sums + pos_bytes > (size_t(40) << 10)) pos_bytes = 0;
+    const size_t lds = sums + pos_bytes;
+    const dim3 block(threads);
     hipLaunchKernelGGL(k2_mesh_clear, dim3(1), dim3(64), 0, st, ticket);
     hipLaunchKernelGGL(k2_mesh_sweep_clear, dim3((od.C + 255) / 256), dim3(256), 0, st, first_idx, od.C);
 #define HARP_SWEEP_LAUNCH(F, X)                                                                                  \
     hipLaunchKernelGGL(HIP_KERNEL_NAME(k2_mesh_h1f1b_sweep<F, false, X>), dim3(n_groups), block, lds, st, tb, od,   \
-                       cand_group, cand_tp, max_caps, W, slots, first_idx, slices, per_group, total_devices, ticket); \
+                       cand_group, cand_tp, max_caps, W, slots, first_idx, slices, per_group, total_devices, ticket, \
+                       pos_bytes);                                                                                \
     hipLaunchKernelGGL(k2_mesh_sweep_open, dim3((od.C + 3) / 4), dim3(256), 0, st, od, W, slots, first_idx);       \
     hipLaunchKernelGGL(HIP_KERNEL_NAME(k2_mesh_h1f1b_sweep<F, true, X>), dim3(n_groups), block, lds, st, tb, od,    \
                        cand_group, cand_tp, max_caps, W, slots, first_idx, slices, per_group, total_devices,        \
-                       ticket + 1)
+                       ticket + 1, pos_bytes)
     if (fast32 && forced) { HARP_SWEEP_LAUNCH(true, true); }
     else if (fast32) { HARP_SWEEP_LAUNCH(true, false); }
     else if (forced) { HARP_SWEEP_LAUNCH(false, true); }
