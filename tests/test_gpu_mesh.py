@@ -324,3 +324,29 @@ def test_mesh_h1f1b_sweep(harp, ctx):
         at, _ = harp.plan_mesh_h1f1b(ctx, w.problem, orders, np.where(ok, want.t_max, -1))
         for field in ("splits", "warmup", "iter_time", "stage_tp"):
             assert (getattr(at, field)[ok] == getattr(got, field)[ok]).all(), (name, field)
+
+
+def test_sweeps_degenerate_shapes(harp, ctx):
+    """Edge shapes for both searches over the cap: one stage, one operator per stage, one
+    microbatch (t_E = T, so every candidate value is tried), operators that cost nothing (caps of
+    zero, equal stage times at consecutive cuts), transfers that dominate every stage time."""
+    from test_gpu_h1f1b import _check_sweep as _check_candidate_sweep
+    rng = np.random.default_rng(77)
+    cases = []
+    for M in (1, 2, 7):
+        cases.append(simple_problem(rng.integers(1, 50, size=7), M=M, G=2, ndev=(2, 2), tp=(1, 2),
+                                    act=rng.integers(0, 300, size=7), bw=[[40, 3], [3, 30]],
+                                    params=rng.integers(0, 9, size=7), stash=rng.integers(0, 5, size=7), mem=[60]))
+    cases.append(simple_problem([0, 0, 5, 0, 0, 0, 3, 0], M=4, G=2, ndev=(2, 1), tp=(1, 2), act=[0, 4, 0, 0, 9, 0, 0, 0],
+                                bw=[[2, 1], [1, 2]], params=[1] * 8, stash=[1] * 8, mem=[30]))
+    cases.append(simple_problem([0] * 6, M=5, G=2, ndev=(1, 2), tp=(1, 2), act=[0] * 6, bw=np.ones((2, 2)), mem=[10]))
+    cases.append(simple_problem(rng.integers(1, 5, size=9), M=6, G=3, ndev=(1, 1, 1), act=rng.integers(500, 900, size=9),
+                                bw=np.ones((3, 3)), params=[2] * 9, stash=[3] * 9, mem=[80]))
+    for n, p in enumerate(cases):
+        G, L, D = int(p.G), int(p.L), int(p.group_ndev.sum())
+        lists = [(S, order) for order in ([*range(G)], [*range(G)][::-1], [0]) for S in (1, len(order), D, min(L, D))
+                 if len(order) <= S]
+        _check_sweep(harp, ctx, p, W.orderings_from_lists(lists, S_max=max(S for S, _ in lists)), "degenerate %d" % n)
+        slots = [[(g, 1) for g in range(G) for _ in range(int(p.group_ndev[g]))], [(0, 1)], [(g, 1) for g in range(G)],
+                 [(G - 1, int(p.tp_degrees[-1]) if p.group_ndev[G - 1] >= p.tp_degrees[-1] else 1), (0, 1)]]
+        _check_candidate_sweep(harp, ctx, p, cands_from_lists(slots), "degenerate candidates %d" % n)
