@@ -30,6 +30,16 @@
  *   D[s+1][i] = min_j max(D[s][j], time(s;j,i), comm(s;i))  over fitting j, lowest j on ties,
  * followed back from (S, L).
  *
+ * Built on the same tables and cost model, further down in this header: the exact optimum of the
+ * iteration-time model per candidate (harp_plan_exact_batch, section 5.2.4 (2)); the capped
+ * recurrence with the warm-up counts of the H-1F1B scheduler in the memory constraint and as an
+ * output (harp_plan_h1f1b_batch, harp_score_h1f1b; sections 4.1 and 5.2.3), and its search over
+ * the cap (harp_plan_h1f1b_sweep_batch); the planner over ORDERINGS of device groups that chooses
+ * every stage's devices inside the recurrence (harp_plan_mesh_batch, harp_plan_mesh_exact_batch,
+ * harp_plan_mesh_h1f1b_batch; eq. dp_general's device index) and the paper's search in full around
+ * it (harp_plan_mesh_h1f1b_sweep_batch); and the selection of the best plan of a batch
+ * (harp_argmin_batch).
+ *
  * Conventions.  Pointers marked DEVICE are device memory of the context's GPU, pointers marked
  * HOST are ordinary host memory.  The caller owns every buffer; the library allocates no device
  * memory.  Calls enqueue work on the given HIP stream (NULL = the default stream) and return
