@@ -326,6 +326,25 @@ def test_mesh_h1f1b_sweep(harp, ctx):
             assert (getattr(at, field)[ok] == getattr(got, field)[ok]).all(), (name, field)
 
 
+def test_mesh_h1f1b_sweep_in_the_benchmark_configuration(harp, ctx):
+    """256 llama70b-shaped orderings, the batch and launch configuration the benchmark times (eight
+    walkers per ordering), under a limit on the caps tried that the oracle can follow in seconds."""
+    w = W.make("llama70b")
+    orders = W.make_orderings(w.problem, w.seed, w.config_id, w.problem.G, w.S_max, 0, 256)
+    got, want = _check_sweep(harp, ctx, w.problem, orders, "llama70b, 40 caps", max_caps=40)
+    assert (want.status == oracle.OK).all() and (want.n_caps == 40).all()
+    # without the limit: what must hold at any size
+    full, _ = harp.plan_mesh_h1f1b_sweep(ctx, w.problem, orders)
+    mm, _ = harp.plan_mesh(ctx, w.problem, orders)
+    assert (full.status == oracle.OK).all() and (full.n_caps >= 40).all()
+    assert (full.iter_time <= got.iter_time).all()                 # more caps tried never lose
+    assert (full.t_max >= mm.bottleneck).all() and (full.bottleneck <= full.t_max).all()
+    # the answer is the recurrence's plan at the chosen cap
+    at, _ = harp.plan_mesh_h1f1b(ctx, w.problem, orders, full.t_max)
+    for field in ("splits", "stage_group", "stage_tp", "warmup", "iter_time", "bottleneck"):
+        assert (getattr(at, field) == getattr(full, field)).all(), field
+
+
 def test_sweeps_degenerate_shapes(harp, ctx):
     """Edge shapes for both searches over the cap: one stage, one operator per stage, one
     microbatch (t_E = T, so every candidate value is tried), operators that cost nothing (caps of
