@@ -1,5 +1,5 @@
 """Pins of the cost model itself: the DAG pipeline simulator (section 4.2.1) against the closed
-forms the paper proves (Lemma 1, Lemma 2, eq. result2h), the case study of section 2.2, and the
+forms the paper proves (Lemma 1, Lemma 2, eq. result2h), the case study of section 2.3, and the
 warm-up counts the H-1F1B oracle emits."""
 import math
 
@@ -40,7 +40,7 @@ def test_smallest_bubble_free_warmup_is_eq_result2h():
 def test_case_study_counts():
     # three balanced stages, slow first link (between half a stage time and a full one), fast
     # second link: the tailored {5, 2, 1} hides everything; Eager-1F1B's {5, 3, 1} and the classic
-    # {3, 2, 1} leave bubbles (section 2.2)
+    # {3, 2, 1} leave bubbles (section 2.3)
     f, b, c, B = [100] * 3, [200] * 3, [250, 0], 24
     model = dag_sim.cost_model(f, b, c, B)
     assert dag_sim.simulate(f, b, c, B, [5, 2, 1])[0] == model
