@@ -125,3 +125,22 @@ def test_a_c_program_links_and_calls_the_library(tmp_path):
     size, rc, msg = first.split(" ", 2)
     assert int(size) > 0 and int(rc) == binding.ERR_INVALID_ARG and msg == "null context"
     assert int(second) == 0
+
+
+def test_the_c_only_client_builds_against_the_library(tmp_path):
+    """tests/c_client/plan_tiny.c drives the hot path through the C ABI and the HIP runtime's C
+    interface alone (no Python, no torch).  Here it is compiled and linked with gcc; on a GPU machine it
+    prints "0 2 4 4 20 0" for the hand example and exits 0."""
+    import subprocess
+    from paper_2509_24859_amd import binding
+    _library()
+    if not os.path.exists("/opt/rocm/include/hip/hip_runtime_api.h"):
+        pytest.skip("no ROCm headers on this machine")
+    libdir, libname = os.path.dirname(binding.LIB_PATH), os.path.basename(binding.LIB_PATH)
+    exe = tmp_path / "plan_tiny"
+    r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), "-I", "/opt/rocm/include",
+                        os.path.join(ROOT, "tests", "c_client", "plan_tiny.c"), "-o", str(exe), "-L", libdir,
+                        "-l:" + libname, "-L", "/opt/rocm/lib", "-lamdhip64", "-Wl,-rpath," + libdir,
+                        "-Wl,-rpath,/opt/rocm/lib"], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    assert exe.exists()
