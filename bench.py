@@ -31,6 +31,7 @@ MEASURED_TRAFFIC_BYTES = {"stress": 3.394e9 + 1.795e9 + 0.254e9 + 0.344e9}
 # issued-instruction view of k2_fast on the same workload, from the same counter runs
 MEASURED_ISSUE = {"stress": {"valu_issue_utilisation": 0.686, "lanes_active_per_valu_instruction": 0.57,
                              "lds_bank_conflict_fraction": 0.12,
+                             "issued_lane_ops_frac_of_peak": 0.686 * 0.57,   # what the VALUs actually did
                              "source": "profiles/plan_batch_stress_pmc.txt (rocprofv3 --pmc, k2_fast)"}}
 
 
