@@ -147,7 +147,7 @@ int n_mesh_groups(const harp_ctx *ctx, int C, size_t per_group, int threads) {
 // compute units idle; its workspace holds the slices of the resident workgroups and W + 1 kept
 // plans per ordering.
 struct SweepLayout {
-    int threads, groups, W;
+    int threads, groups, W, W_climb;
     size_t per_group, bytes;
 };
 SweepLayout sweep_layout(const harp_ctx *ctx, const harp_tables *t, const harp_orderings *od) {
@@ -164,9 +164,15 @@ SweepLayout sweep_layout(const harp_ctx *ctx, const harp_tables *t, const harp_o
     long long W = resident / C;
     W = W < 1 ? 1 : (W > 32 ? 32 : W);
     s.W = int(W);
-    s.groups = int(resident < C * W ? resident : C * W);
-    s.bytes = 256 + size_t(s.groups) * s.per_group + size_t(C) * size_t(W + 1) * plan_mesh_sweep_slot_bytes(od->S_max) +
-              ((size_t(C) * sizeof(int) + 255) & ~size_t(255));
+    // the climb to the first cap with a plan is deep for a few orderings only (those whose memory
+    // fits once a larger cap has lowered the counts): it gets four times the walkers, drawn from
+    // the same ticket, so that workgroups that are done with easy orderings join the deep ones
+    long long Wc = 4 * resident / C;
+    Wc = Wc < W ? W : (Wc > 32 ? 32 : Wc);
+    s.W_climb = int(Wc);
+    s.groups = int(resident < C * Wc ? resident : C * Wc);
+    s.bytes = 256 + size_t(s.groups) * s.per_group + size_t(C) * size_t(Wc + 1) * plan_mesh_sweep_slot_bytes(od->S_max) +
+              ((size_t(C) * (sizeof(int64_t) + sizeof(int)) + 255) & ~size_t(255));
     return s;
 }
 
@@ -542,7 +548,7 @@ int harp_plan_mesh_h1f1b_sweep_batch(harp_ctx *ctx, harp_tables *t, const harp_o
     const OrdDev o = { od->C, od->G_max, od->S_max, od->ord_S, od->ord_G, od->ord_group };
     const PlansDev pl = { out->splits, out->dev_first, out->bottleneck, out->iter_time, out->status };
     launch_plan_mesh_h1f1b_sweep(t->dev, o, nullptr, nullptr, max_caps, pl, stage_group, stage_tp, warmup, t_max_out, n_caps,
-                                 use_fast(ctx, t), workspace, lay.groups, lay.threads, lay.W, t->total_devices,
+                                 use_fast(ctx, t), workspace, lay.groups, lay.threads, lay.W_climb, lay.W, t->total_devices,
                                  static_cast<hipStream_t>(hip_stream));
     e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(ctx, e, "launching the submesh H-1F1B sweep kernel");
@@ -579,7 +585,7 @@ int harp_plan_h1f1b_sweep_batch(harp_ctx *ctx, harp_tables *t, const harp_candid
     const OrdDev o = { cd->C, 1, cd->S_max, cd->cand_S, nullptr, nullptr };
     const PlansDev pl = { out->splits, out->dev_first, out->bottleneck, out->iter_time, out->status };
     launch_plan_mesh_h1f1b_sweep(t->dev, o, cd->cand_group, cd->cand_tp, max_caps, pl, nullptr, nullptr, warmup,
-                                 t_max_out, n_caps, use_fast(ctx, t), workspace, lay.groups, lay.threads, lay.W,
+                                 t_max_out, n_caps, use_fast(ctx, t), workspace, lay.groups, lay.threads, lay.W_climb, lay.W,
                                  t->total_devices, static_cast<hipStream_t>(hip_stream));
     e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(ctx, e, "launching the search over the cap");

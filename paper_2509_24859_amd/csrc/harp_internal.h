@@ -109,8 +109,8 @@ void launch_plan_mesh_h1f1b(const TablesDev &tb, const OrdDev &od, const int64_t
 void launch_plan_mesh_h1f1b_sweep(const TablesDev &tb, const OrdDev &od, const int32_t *cand_group,
                                   const int32_t *cand_tp, int max_caps, const PlansDev &out,
                                   int32_t *stage_group, int32_t *stage_tp, int32_t *warmup, int64_t *t_max_out,
-                                  int32_t *n_caps, bool fast32, void *ws, int n_groups, int threads, int W,
-                                  int64_t total_devices, hipStream_t st);
+                                  int32_t *n_caps, bool fast32, void *ws, int n_groups, int threads, int W_climb,
+                                  int W, int64_t total_devices, hipStream_t st);
 size_t plan_mesh_sweep_slot_bytes(int S_max);
 size_t plan_mesh_ws_per_group(int L, int S_max, int64_t total_devices);
 int plan_mesh_threads(int L, int64_t total_devices, int C, int n_cu);

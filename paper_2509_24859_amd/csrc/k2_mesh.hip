@@ -896,17 +896,19 @@ __device__ __forceinline__ int64_t mesh_next_cap_slots(const TablesDev &tb, int 
 }
 
 // The search around the full recurrence (section 5.2.4 (2)), with the caps of one ordering shared
-// by W workgroups (the batched evaluation of 5.2.4 (3)).  The k-th candidate value at or above t_S
-// has index k whoever tries it, and walker j of an ordering tries the indices congruent to j.
-//  climb:  every walker runs the classic min-max pass for the lower end t_S (no cap below it admits
-//          a plan, and H-1F1B's counts are never below the classic ones), then walks the caps
-//          upwards, running the H-1F1B pass on its own indices until one has a plan; the lowest such
-//          index is kept as an atomic minimum, and a walker stops once it is above that minimum;
+// by several workgroups (the batched evaluation of 5.2.4 (3)).  The k-th candidate value at or
+// above t_S has index k whoever tries it.
+//  lower:  one workgroup per ordering checks it, runs the classic min-max pass for the lower end
+//          t_S (no cap below it admits a plan, and H-1F1B's counts are never below the classic
+//          ones) and tries t_S itself, which has a plan for most orderings;
+//  climb:  for the others, W walkers per ordering walk the caps upwards from index 1, walker j
+//          running the H-1F1B pass on the indices congruent to j until one has a plan; the lowest
+//          such index is kept as an atomic minimum, and a walker stops once it is above it;
 //  open:   the walker with the lowest index hands its plan over; it fixes t_E = ceil(T / B);
-//  rest:   every walker walks ALL later caps up to t_E (finding the next cap costs a few percent
-//          of a pass) and runs the H-1F1B pass on its own indices, keeping its best plan;
-//  pick:   per ordering the smallest T = least sum + (B - 1) cap over the W + 1 kept plans, the
-//          lower cap on equal T; that is what trying the caps one after the other returns.
+//  rest:   W walkers per ordering walk ALL later caps up to t_E (finding the next cap costs a few
+//          percent of a pass) and run the H-1F1B pass on their own indices, keeping their best plan;
+//  pick:   per ordering the smallest T = least sum + (B - 1) cap over the kept plans, the lower cap
+//          on equal T; that is what trying the caps one after the other returns.
 // The limit max_caps cuts the sweep at the same cap for every W.
 struct SweepHead {
     int64_t T, cap;
@@ -945,11 +947,17 @@ __device__ __forceinline__ SweepSlot sweep_slot(unsigned char *slots, int S_max,
 // lists in cand_group / cand_tp): every stage's group and degree are given, so each stage has one
 // device offset and one degree, and the candidate values are those of the slots and of the links
 // between consecutive slots.
-template <bool kFast, bool kRest, bool kForced>
+// kPhase: kSweepLower (one item per ordering: validity and t_S), kSweepClimb, kSweepRest (W items per
+// ordering each).  Ws is the number of walker slots per ordering in the workspace (the largest W of
+// the phases); slot Ws holds the opening.
+constexpr int kSweepLower = 0, kSweepClimb = 1, kSweepRest = 2;
+template <bool kFast, int kPhase, bool kForced>
 __device__ __forceinline__ void mesh_sweep_body(const TablesDev &tb, const OrdDev &od, const int32_t *cand_group,
-                                                const int32_t *cand_tp, int max_caps, int W,
-                                                unsigned char *slots, int *first_idx, unsigned char *ws,
-                                                size_t per_group, int64_t n_dev, int *ticket, size_t pos_bytes) {
+                                                const int32_t *cand_tp, int max_caps, int W, int Ws,
+                                                unsigned char *slots, int *first_idx, int64_t *lower,
+                                                unsigned char *ws, size_t per_group, int64_t n_dev, int *ticket,
+                                                size_t pos_bytes) {
+    constexpr bool kRest = kPhase == kSweepRest;
     // fast form: PP and PS (or Q), L + 1 entries each; then pos_bytes of cap positions
     extern __shared__ __align__(16) unsigned char mesh_lds[];
     int64_t *sums_lds = reinterpret_cast<int64_t *>(mesh_lds);
@@ -981,13 +989,17 @@ __device__ __forceinline__ void mesh_sweep_body(const TablesDev &tb, const OrdDe
         const int item = shared_int[0];
         if (item >= n_items) break;
         const int c = item / W, j = item - c * W;
-        const SweepSlot mine = sweep_slot(slots, S_max, W, c, j);
-        const SweepSlot opening = sweep_slot(slots, S_max, W, c, W);
+        const SweepSlot opening = sweep_slot(slots, S_max, Ws, c, Ws);
+        const SweepSlot mine = kPhase == kSweepLower ? opening : sweep_slot(slots, S_max, Ws, c, j);
         auto leave = [&](int state, int tried) {
             if (tid == 0) { mine.head->T = kInf; mine.head->cap = kInf; mine.head->tried = tried; mine.head->state = state; }
         };
         int64_t cap = 0, t_E = kInf;
         int tried = 0;
+        if (kPhase == kSweepClimb) {
+            // the first launch found this ordering malformed or without any plan: nothing to climb
+            if (opening.head->state != kSweepNone) { leave(kSweepNone, 0); continue; }
+        }
         if (kRest) {
             // what the first launch found for this ordering (written before this kernel started)
             if (opening.head->state != kSweepPlan) { leave(kSweepNone, opening.head->tried); continue; }
@@ -1082,36 +1094,47 @@ __device__ __forceinline__ void mesh_sweep_body(const TablesDev &tb, const OrdDe
             }
             if (tid == 0) { mine.head->T = T; mine.head->cap = at; }
         };
-        if (!kRest) {
-            // the climb from t_S to the first cap with a plan, shared by the W walkers of the
-            // ordering: each walks every cap and tries those with its own index modulo W; the lowest
-            // index found so far (first_idx, an atomic minimum) tells the others where to stop.  Every
-            // index below the final minimum has been tried by its walker and has no plan.
+        if constexpr (kPhase == kSweepLower) {
+            // validity (checked above), the lower end of the sweep, and the cap of index 0 (t_S itself),
+            // which has a plan for most orderings: then the climb has nothing left to do
             int64_t t_S;
             if constexpr (kFast) t_S = mesh_pass_fast<false>(tb, m, offs, order, group_at, sums_lds, K, S, n_dev, 0, fq, fo);
             else t_S = mesh_pass<false>(tb, m, offs, order, group_at, K, S, n_dev, 0, fq, fo);
             if (t_S == kInf) { leave(kSweepFailed + HARP_CAND_INFEASIBLE, 0); continue; }
-            cap = t_S;
+            const int64_t sum = h1_pass(t_S);
+            if (sum != kInf) {
+                keep(t_S, sum + (m_cap - 1) * t_S);
+                if (tid == 0) { mine.head->tried = 1; mine.head->state = kSweepPlan; }
+            } else {
+                if (tid == 0) lower[c] = t_S;
+                leave(kSweepNone, 1);
+            }
+        } else if constexpr (kPhase == kSweepClimb) {
+            // the climb from t_S (index 0, tried without a plan by the first launch) to the first cap
+            // with a plan, shared by the W walkers of the ordering: each walks every cap and tries
+            // those whose index is congruent to its own; the lowest index found so far (first_idx, an
+            // atomic minimum) tells the others where to stop.  Every index below the final minimum
+            // has been tried by its walker and has no plan.
+            cap = lower[c];
+            tried = 1;
             int state = kSweepFailed + HARP_CAND_INFEASIBLE;
-            for (int idx = 0;; ++idx) {
+            for (int idx = 1;; ++idx) {
+                if (tried >= max_caps) break;
+                const int64_t nb = next_cap(cap);
+                if (nb == kInf) break;
+                cap = nb;
                 __syncthreads();
                 if (tid == 0) shared_int[1] = atomicAdd(&first_idx[c], 0);
                 __syncthreads();
                 if (idx > shared_int[1]) { state = kSweepNone; break; }        // a lower cap already has a plan
                 tried = idx + 1;
-                if (idx % W == j) {
-                    const int64_t sum = h1_pass(cap);
-                    if (sum != kInf) {
-                        keep(cap, sum + (m_cap - 1) * cap);
-                        if (tid == 0) atomicMin(&first_idx[c], idx);
-                        state = kSweepPlan;
-                        break;
-                    }
-                }
-                if (tried >= max_caps) break;
-                const int64_t nb = next_cap(cap);
-                if (nb == kInf) break;
-                cap = nb;
+                if ((idx - 1) % W != j) continue;
+                const int64_t sum = h1_pass(cap);
+                if (sum == kInf) continue;
+                keep(cap, sum + (m_cap - 1) * cap);
+                if (tid == 0) atomicMin(&first_idx[c], idx);
+                state = kSweepPlan;
+                break;
             }
             if (state != kSweepPlan) { leave(state, tried); continue; }
             if (tid == 0) { mine.head->tried = tried; mine.head->state = kSweepPlan; }
@@ -1137,29 +1160,32 @@ __device__ __forceinline__ void mesh_sweep_body(const TablesDev &tb, const OrdDe
     }
 }
 
-template <bool kFast, bool kRest, bool kForced>
+template <bool kFast, int kPhase, bool kForced>
 __global__ __launch_bounds__(kMeshMaxThreads) void k2_mesh_h1f1b_sweep(TablesDev tb, OrdDev od,
                                                                        const int32_t *cand_group,
                                                                        const int32_t *cand_tp, int max_caps, int W,
-                                                                       unsigned char *slots, int *first_idx,
-                                                                       unsigned char *ws, size_t per_group,
-                                                                       int64_t n_dev, int *ticket, size_t pos_bytes) {
-    mesh_sweep_body<kFast, kRest, kForced>(tb, od, cand_group, cand_tp, max_caps, W, slots, first_idx, ws, per_group,
-                                           n_dev, ticket, pos_bytes);
+                                                                       int Ws, unsigned char *slots, int *first_idx,
+                                                                       int64_t *lower, unsigned char *ws,
+                                                                       size_t per_group, int64_t n_dev, int *ticket,
+                                                                       size_t pos_bytes) {
+    mesh_sweep_body<kFast, kPhase, kForced>(tb, od, cand_group, cand_tp, max_caps, W, Ws, slots, first_idx, lower, ws,
+                                            per_group, n_dev, ticket, pos_bytes);
 }
 
-// Between the two launches, one wavefront per ordering: the walker that found the lowest cap with a
-// plan (index first_idx, walker first_idx mod W) hands its plan over as the opening of the sweep;
-// without one, the opening carries walker 0's verdict and count of caps tried.
-__global__ __launch_bounds__(256) void k2_mesh_sweep_open(OrdDev od, int W, unsigned char *slots,
+// After the climb, one wavefront per ordering that the climb had to work on: the walker that found
+// the lowest cap with a plan (index first_idx, walker (first_idx - 1) mod W) hands its plan over as
+// the opening of the sweep; without one, the opening carries walker 0's verdict and count of caps
+// tried.
+__global__ __launch_bounds__(256) void k2_mesh_sweep_open(OrdDev od, int W, int Ws, unsigned char *slots,
                                                           const int *first_idx) {
     const int lane = threadIdx.x & 63;
     const int c = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
     if (c >= od.C) return;
     const int S_max = od.S_max;
-    const SweepSlot opening = sweep_slot(slots, S_max, W, c, W);
+    const SweepSlot opening = sweep_slot(slots, S_max, Ws, c, Ws);
+    if (opening.head->state != kSweepNone) return;        // malformed, or no plan even with the classic counts
     const int f = first_idx[c];
-    const SweepSlot from = sweep_slot(slots, S_max, W, c, f == INT32_MAX ? 0 : f % W);
+    const SweepSlot from = sweep_slot(slots, S_max, Ws, c, f == INT32_MAX ? 0 : (f - 1) % W);
     if (f != INT32_MAX) {
         for (int s = lane; s <= S_max; s += 64) opening.cuts[s] = from.cuts[s];
         for (int s = lane; s < S_max; s += 64) {
@@ -1181,7 +1207,7 @@ __global__ void k2_mesh_sweep_clear(int *first_idx, int C) {
 }
 
 // One wavefront per ordering: the best of its W + 1 kept plans goes to the outputs.
-__global__ __launch_bounds__(256) void k2_mesh_sweep_pick(TablesDev tb, OrdDev od, int W, unsigned char *slots,
+__global__ __launch_bounds__(256) void k2_mesh_sweep_pick(TablesDev tb, OrdDev od, int W, int Ws, unsigned char *slots,
                                                           PlansDev out, int32_t *stage_group, int32_t *stage_tp,
                                                           int32_t *warmup, int64_t *t_max_out, int32_t *n_caps) {
     const int lane = threadIdx.x & 63;
@@ -1193,7 +1219,7 @@ __global__ __launch_bounds__(256) void k2_mesh_sweep_pick(TablesDev tb, OrdDev o
     int32_t *sg = stage_group ? stage_group + int64_t(c) * S_max : nullptr;
     int32_t *stp = stage_tp ? stage_tp + int64_t(c) * S_max : nullptr;
     int32_t *wu = warmup + int64_t(c) * S_max;
-    const SweepSlot opening = sweep_slot(slots, S_max, W, c, W);
+    const SweepSlot opening = sweep_slot(slots, S_max, Ws, c, Ws);
     if (opening.head->state != kSweepPlan) {
         for (int s = lane; s <= S_max; s += 64) sp[s] = -1;
         for (int s = lane; s < S_max; s += 64) {
@@ -1210,15 +1236,15 @@ __global__ __launch_bounds__(256) void k2_mesh_sweep_pick(TablesDev tb, OrdDev o
         }
         return;
     }
-    int best = W;
+    int best = Ws;
     int64_t best_T = opening.head->T, best_cap = opening.head->cap;
     for (int j = 0; j < W; ++j) {
-        const SweepHead *h = sweep_slot(slots, S_max, W, c, j).head;
+        const SweepHead *h = sweep_slot(slots, S_max, Ws, c, j).head;
         if (h->state == kSweepPlan && (h->T < best_T || (h->T == best_T && h->cap < best_cap))) {
             best = j; best_T = h->T; best_cap = h->cap;
         }
     }
-    const SweepSlot b = sweep_slot(slots, S_max, W, c, best);
+    const SweepSlot b = sweep_slot(slots, S_max, Ws, c, best);
     const int S = od.ord_S[c];
     for (int s = lane; s <= S_max; s += 64) sp[s] = s <= S ? b.cuts[s] : -1;
     for (int s = lane; s < S_max; s += 64) {
@@ -1234,7 +1260,7 @@ __global__ __launch_bounds__(256) void k2_mesh_sweep_pick(TablesDev tb, OrdDev o
         out.iter_time[c] = best_T;
         out.status[c] = HARP_CAND_OK;
         t_max_out[c] = best_cap;
-        if (n_caps) n_caps[c] = sweep_slot(slots, S_max, W, c, 0).head->tried;
+        if (n_caps) n_caps[c] = sweep_slot(slots, S_max, Ws, c, 0).head->tried;
     }
 }
 
@@ -1302,18 +1328,22 @@ void launch_plan_mesh_h1f1b(const TablesDev &tb, const OrdDev &od, const int64_t
 }
 
 // cand_group / cand_tp not null: the batch holds candidates with a fixed slicing (od.ord_S = their
-// stage counts), and stage_group / stage_tp may be null.
+// stage counts), and stage_group / stage_tp may be null.  W_climb and W walkers per ordering in the
+// climb and in the rest of the sweep.
 void launch_plan_mesh_h1f1b_sweep(const TablesDev &tb, const OrdDev &od, const int32_t *cand_group,
                                   const int32_t *cand_tp, int max_caps, const PlansDev &out,
                                   int32_t *stage_group, int32_t *stage_tp, int32_t *warmup, int64_t *t_max_out,
-                                  int32_t *n_caps, bool fast32, void *ws, int n_groups, int threads, int W,
-                                  int64_t total_devices, hipStream_t st) {
-    // layout: 256 bytes for the tickets, n_groups slices, (W + 1) kept plans per ordering, one int per ordering
+                                  int32_t *n_caps, bool fast32, void *ws, int n_groups, int threads, int W_climb,
+                                  int W, int64_t total_devices, hipStream_t st) {
+    // layout: 256 bytes for the tickets | n_groups slices | (Ws + 1) kept plans per ordering | t_S per
+    // ordering | index of the first cap with a plan per ordering
     int *ticket = static_cast<int *>(ws);
     unsigned char *slices = static_cast<unsigned char *>(ws) + 256;
     const size_t per_group = plan_mesh_ws_per_group(tb.L, od.S_max, total_devices);
+    const int Ws = W_climb > W ? W_climb : W;
     unsigned char *slots = slices + size_t(n_groups) * per_group;
-    int *first_idx = reinterpret_cast<int *>(slots + size_t(od.C) * size_t(W + 1) * sweep_slot_bytes(od.S_max));
+    int64_t *lower = reinterpret_cast<int64_t *>(slots + size_t(od.C) * size_t(Ws + 1) * sweep_slot_bytes(od.S_max));
+    int *first_idx = reinterpret_cast<int *>(lower + od.C);
     fast32 = fast32 && tb.L <= kMeshFastMaxL;
     const bool forced = cand_group != nullptr;
     // cap positions: one uint16 per (row, start cut), kept in LDS when the largest item's rows fit
@@ -1324,22 +1354,26 @@ void launch_plan_mesh_h1f1b_sweep(const TablesDev &tb, const OrdDev &od, const i
     if (sums + pos_bytes > (size_t(40) << 10)) pos_bytes = 0;
     const size_t lds = sums + pos_bytes;
     const dim3 block(threads);
+    auto grid_for = [&](long long items) { return dim3(unsigned(items < n_groups ? items : n_groups)); };
     hipLaunchKernelGGL(k2_mesh_clear, dim3(1), dim3(64), 0, st, ticket);
     hipLaunchKernelGGL(k2_mesh_sweep_clear, dim3((od.C + 255) / 256), dim3(256), 0, st, first_idx, od.C);
+#define HARP_SWEEP_PHASE(F, P, X, WALKERS, TICKET)                                                               \
+    hipLaunchKernelGGL(HIP_KERNEL_NAME(k2_mesh_h1f1b_sweep<F, P, X>), grid_for((long long)od.C * (WALKERS)), block,  \
+                       lds, st, tb, od, cand_group, cand_tp, max_caps, WALKERS, Ws, slots, first_idx, lower, slices, \
+                       per_group, total_devices, ticket + (TICKET), pos_bytes)
 #define HARP_SWEEP_LAUNCH(F, X)                                                                                  \
-    hipLaunchKernelGGL(HIP_KERNEL_NAME(k2_mesh_h1f1b_sweep<F, false, X>), dim3(n_groups), block, lds, st, tb, od,   \
-                       cand_group, cand_tp, max_caps, W, slots, first_idx, slices, per_group, total_devices, ticket, \
-                       pos_bytes);                                                                                \
-    hipLaunchKernelGGL(k2_mesh_sweep_open, dim3((od.C + 3) / 4), dim3(256), 0, st, od, W, slots, first_idx);       \
-    hipLaunchKernelGGL(HIP_KERNEL_NAME(k2_mesh_h1f1b_sweep<F, true, X>), dim3(n_groups), block, lds, st, tb, od,    \
-                       cand_group, cand_tp, max_caps, W, slots, first_idx, slices, per_group, total_devices,        \
-                       ticket + 1, pos_bytes)
+    HARP_SWEEP_PHASE(F, kSweepLower, X, 1, 0);                                                                    \
+    HARP_SWEEP_PHASE(F, kSweepClimb, X, W_climb, 1);                                                              \
+    hipLaunchKernelGGL(k2_mesh_sweep_open, dim3((od.C + 3) / 4), dim3(256), 0, st, od, W_climb, Ws, slots,        \
+                       first_idx);                                                                                \
+    HARP_SWEEP_PHASE(F, kSweepRest, X, W, 2)
     if (fast32 && forced) { HARP_SWEEP_LAUNCH(true, true); }
     else if (fast32) { HARP_SWEEP_LAUNCH(true, false); }
     else if (forced) { HARP_SWEEP_LAUNCH(false, true); }
     else { HARP_SWEEP_LAUNCH(false, false); }
 #undef HARP_SWEEP_LAUNCH
-    hipLaunchKernelGGL(k2_mesh_sweep_pick, dim3((od.C + 3) / 4), dim3(256), 0, st, tb, od, W, slots, out,
+#undef HARP_SWEEP_PHASE
+    hipLaunchKernelGGL(k2_mesh_sweep_pick, dim3((od.C + 3) / 4), dim3(256), 0, st, tb, od, W, Ws, slots, out,
                        stage_group, stage_tp, warmup, t_max_out, n_caps);
 }
 
