@@ -170,6 +170,7 @@ SweepLayout sweep_layout(const harp_ctx *ctx, const harp_tables *t, const harp_o
     long long Wc = 4 * resident / C;
     Wc = Wc < W ? W : (Wc > 32 ? 32 : Wc);
     s.W_climb = int(Wc);
+    s.W = int(Wc);        // the rest of the sweep as well: more, shorter items even out orderings with many caps
     s.groups = int(resident < C * Wc ? resident : C * Wc);
     s.bytes = 256 + size_t(s.groups) * s.per_group + size_t(C) * size_t(Wc + 1) * plan_mesh_sweep_slot_bytes(od->S_max) +
               ((size_t(C) * (sizeof(int64_t) + sizeof(int)) + 255) & ~size_t(255));
