@@ -66,23 +66,48 @@ __device__ __forceinline__ const int64_t *generic_pass(const TablesDev &tb, cons
             int64_t best = kInf;
             int best_j = INT32_MAX;
             if (!kCapped || cut <= time_cap) {
-                for (int j = s + lane; j < i; j += 64) {
-                    const int64_t dj = Dp[j];
-                    if (dj == kInf) continue;
-                    const int64_t need = (ppi - PP[j]) + n_inflight * (psi - PS[j]);
-                    if (need > cap) continue;
-                    const int64_t work = pfi - pf[j];
-                    const int64_t comp = shift >= 0 ? (work + tp - 1) >> shift : (work + tp - 1) / tp;
-                    const int64_t time = comp + (pri - pr[j]);
-                    int64_t val;
-                    if (kCapped) {
-                        if (time > time_cap) continue;
-                        val = dj + time;
-                    } else {
-                        val = time > dj ? time : dj;
-                        val = val > cut ? val : cut;
+                // previous cuts in runs of 64 from i - 1 downwards.  Both the memory need and the
+                // stage time never decrease as j moves down, so once the lowest j of a run does not
+                // fit, or its time alone is above the cap (capped form) or above the best value so
+                // far (min-max form: strictly, an equal value at a lower j still has to be seen),
+                // no lower j can be taken or can match, and the scan stops.
+                for (int top = i - 1; top >= s; top -= 64) {
+                    const int j = top - lane;
+                    if (j >= s) {
+                        const int64_t dj = Dp[j];
+                        const int64_t need = (ppi - PP[j]) + n_inflight * (psi - PS[j]);
+                        if (dj != kInf && need <= cap) {
+                            const int64_t work = pfi - pf[j];
+                            const int64_t comp = shift >= 0 ? (work + tp - 1) >> shift : (work + tp - 1) / tp;
+                            const int64_t time = comp + (pri - pr[j]);
+                            if (kCapped) {
+                                if (time <= time_cap && dj + time <= best) { best = dj + time; best_j = j; }
+                            } else {
+                                int64_t val = time > dj ? time : dj;
+                                val = val > cut ? val : cut;
+                                if (val <= best) { best = val; best_j = j; }       // j falls: the lower j keeps a tie
+                            }
+                        }
                     }
-                    if (val < best) { best = val; best_j = j; }
+                    const int low = top - 63 > s ? top - 63 : s;                    // lowest j of this run
+                    if (low == s) break;
+                    const int64_t need_low = (ppi - PP[low]) + n_inflight * (psi - PS[low]);
+                    if (need_low > cap) break;
+                    const int64_t work_low = pfi - pf[low];
+                    const int64_t time_low = (shift >= 0 ? (work_low + tp - 1) >> shift : (work_low + tp - 1) / tp) +
+                                             (pri - pr[low]);
+                    if (kCapped) {
+                        if (time_low > time_cap) break;
+                    } else {
+                        // the best value of the whole wave so far decides, so it is gathered here
+#pragma unroll
+                        for (int d = 32; d >= 1; d >>= 1) {
+                            const int64_t ov = __shfl_xor(best, d, 64);
+                            const int oj = __shfl_xor(best_j, d, 64);
+                            if (ov < best || (ov == best && oj < best_j)) { best = ov; best_j = oj; }
+                        }
+                        if (time_low > best) break;
+                    }
                 }
             }
 #pragma unroll
