@@ -344,17 +344,28 @@ __global__ __launch_bounds__(kThreads) void k2_generic_h1f1b(TablesDev tb, CandD
                     const int64_t pfi = pf[i], pri = pr[i], ppi = PP[i], psi = PS[i];
                     int64_t best = kInf;
                     int best_j = INT32_MAX, best_n = 0;
-                    for (int j = (i + 1 > j_lo ? i + 1 : j_lo) + lane; j <= j_hi; j += 64) {
-                        const int64_t h = w.H[j];
-                        if (h == kInf) continue;
-                        const int64_t work = pf[j] - pfi;
-                        const int64_t comp = shift >= 0 ? (work + tp - 1) >> shift : (work + tp - 1) / tp;
-                        const int64_t time = comp + (pr[j] - pri);
-                        if (time > cap_t) continue;
-                        const int n = w.NN[j];
-                        if ((PP[j] - ppi) + int64_t(n) * (PS[j] - psi) > capm) continue;
-                        const int64_t val = h + time;
-                        if (val < best) { best = val; best_j = j; best_n = n; }   // j rises within a lane
+                    // end cuts in runs of 64 upwards; the stage time and its memory need with a count of
+                    // one both grow with j, so once the highest cut of a run is above the cap or does
+                    // not fit, no higher cut can be taken
+                    for (int base = (i + 1 > j_lo ? i + 1 : j_lo); base <= j_hi; base += 64) {
+                        const int j = base + lane;
+                        if (j <= j_hi) {
+                            const int64_t h = w.H[j];
+                            const int64_t work = pf[j] - pfi;
+                            const int64_t comp = shift >= 0 ? (work + tp - 1) >> shift : (work + tp - 1) / tp;
+                            const int64_t time = comp + (pr[j] - pri);
+                            const int n = w.NN[j];
+                            if (h != kInf && time <= cap_t && (PP[j] - ppi) + int64_t(n) * (PS[j] - psi) <= capm &&
+                                h + time < best) {
+                                best = h + time; best_j = j; best_n = n;       // j rises within a lane
+                            }
+                        }
+                        const int high = base + 63 < j_hi ? base + 63 : j_hi;
+                        if (high == j_hi) break;
+                        const int64_t work_h = pf[high] - pfi;
+                        const int64_t time_h = (shift >= 0 ? (work_h + tp - 1) >> shift : (work_h + tp - 1) / tp) +
+                                               (pr[high] - pri);
+                        if (time_h > cap_t || (PP[high] - ppi) + (PS[high] - psi) > capm) break;
                     }
 #pragma unroll
                     for (int d = 32; d >= 1; d >>= 1) {
