@@ -976,3 +976,50 @@ def test_case_study_layer_shares_follow_the_flop_shares_at_fine_granularity():
             times = [2 * scale // flops[0], 3 * scale // flops[1], 3 * scale // flops[2]]
             assert b[0] == max(times) and abs(times[0] / times[1] - 1.65) < 0.005       # the table's 1.65 t
             assert out.bottleneck[0] < b[0] and list(sizes) == [1, 3, 4]
+
+
+def test_finer_layers_and_faster_links_never_hurt():
+    """Two trends of the paper's evaluation that hold exactly for the model: cutting every layer in
+    two (section 6.5, layer granularity) keeps every coarse plan available, so neither the smallest
+    bottleneck nor the optimum of the cost model can get worse; and raising bandwidths (section
+    6.4) shortens transfers, so they cannot get worse either.  Degree 1 throughout, where no
+    rounding depends on how a stage's operators are grouped."""
+    rng = np.random.default_rng(65)
+    checked = strictly_better = 0
+    for case in range(120):
+        L, G = int(rng.integers(3, 9)), int(rng.integers(1, 4))
+        T = int(rng.integers(1, 3))
+        fwd = rng.integers(2, 80, size=(T, L))
+        bwd = rng.integers(2, 80, size=(T, L))
+        params, stash = rng.integers(0, 30, size=L), rng.integers(0, 12, size=L)
+        act = rng.integers(0, 500, size=L)
+        bw = rng.integers(1, 30, size=(G, G))
+        bw = np.minimum(bw, bw.T)
+        mem = rng.integers(60, 400, size=T)
+        gtype = rng.integers(0, T, size=G)
+        ndev = rng.integers(1, 3, size=G)
+        M = int(rng.integers(1, 9))
+        coarse = simple_problem(np.zeros(L), M=M, T=T, G=G, ndev=ndev, gtype=gtype, fwd=fwd, bwd=bwd, params=params,
+                                stash=stash, act=act, mem=mem, bw=bw)
+        # every operator cut in two: the halves share its time and bytes, the new inner cut carries
+        # any amount of data, the old cut keeps its own
+        fa, ba = fwd // 2, bwd // 2
+        pa, sa = params // 2, stash // 2
+        fine = simple_problem(
+            np.zeros(2 * L), M=M, T=T, G=G, ndev=ndev, gtype=gtype,
+            fwd=np.stack([fa, fwd - fa], axis=2).reshape(T, 2 * L), bwd=np.stack([ba, bwd - ba], axis=2).reshape(T, 2 * L),
+            params=np.stack([pa, params - pa], axis=1).reshape(-1), stash=np.stack([sa, stash - sa], axis=1).reshape(-1),
+            act=np.stack([rng.integers(0, 500, size=L), act], axis=1).reshape(-1), mem=mem, bw=bw)
+        fast_links = dataclasses.replace(coarse, bw=coarse.bw * int(rng.integers(2, 5)))
+        slots = [(int(g), 1) for g in rng.permutation(G) for _ in range(int(ndev[g]))]
+        cands = cands_from_lists([slots[:S] for S in range(1, len(slots) + 1)])     # every prefix keeps groups adjacent
+        base, base_exact = plan(coarse, cands), plan_exact(coarse, cands)
+        for other in (fine, fast_links):
+            got, got_exact = plan(other, cands), plan_exact(other, cands)
+            ok = base.status == oracle.OK
+            assert (got.status[ok] == oracle.OK).all()
+            assert (got.bottleneck[ok] <= base.bottleneck[ok]).all()
+            assert (got_exact.iter_time[ok] <= base_exact.iter_time[ok]).all()
+            checked += int(ok.sum())
+            strictly_better += int((got_exact.iter_time[ok] < base_exact.iter_time[ok]).sum())
+    assert checked > 300 and strictly_better > 100
