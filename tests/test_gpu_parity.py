@@ -466,3 +466,23 @@ def test_stress_full_batch_properties_and_samples(harp, ctx):
     harp.harp_argmin_batch(ctx, w.C, out.iter_time, out.status, bt, bi)
     torch.cuda.synchronize()
     assert (int(bt.item()), int(bi.item())) == oracle.argmin_batch(got.iter_time, got.status)
+
+
+def test_case_study_of_the_paper_on_the_gpu(harp, ctx):
+    """Section 2.2, Table 1 (tests/golden/case_study_shares.txt): the kernels give the oracle's plans
+    for the table's two pipelines, whose 128-layer stage sizes follow the submeshes' FLOP shares."""
+    from helpers import read_golden
+    rows = read_golden(os.path.join(os.path.dirname(__file__), "golden", "case_study_shares.txt"))
+    for row in rows:
+        L, flops, layers = (part.split() for part in row.split("|"))
+        L, flops, layers = int(L[0]), [int(x) for x in flops], [int(x) for x in layers]
+        scale = flops[0] * flops[1]
+        fwd = np.array([[scale // f] * L for f in flops], dtype=np.int64)
+        p = simple_problem(np.zeros(L), M=8, T=3, G=3, ndev=(1, 1, 1), gtype=[0, 1, 2], fwd=fwd,
+                           bwd=np.zeros_like(fwd))
+        cands = cands_from_lists([[(0, 1), (1, 1), (2, 1)]])
+        want = oracle.plan_batch(oracle.build_tables(p), cands)
+        _plan_all_paths(harp, ctx, p, cands, want, "case study, %d layers" % L)
+        if L == 128:
+            sizes = np.diff(want.splits[0, :4])
+            assert max(abs(1000 * n / L - s) for n, s in zip(sizes, layers)) <= 12
