@@ -8,8 +8,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libharp_hip.so")
-SOURCES = ("harp_api.hip", "k1_tables.hip", "k2_generic.hip", "k2_fast.hip", "k2_exact.hip", "k2_h1f1b.hip", "k2_mesh.hip", "k3_score.hip", "k5_peaks.hip")
-HEADERS = ("harp_internal.h", "plan_common.h", "fast_common.h")
+SOURCES = ("harp_api.hip", "k1_tables.hip", "k2_generic.hip", "k2_fast.hip", "k2_exact.hip", "k2_h1f1b.hip", "k2_mesh.hip", "k2_sweep.hip", "k3_score.hip", "k5_peaks.hip")
+HEADERS = ("harp_internal.h", "plan_common.h", "fast_common.h", "mesh_passes.h")
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
