@@ -54,7 +54,7 @@ __device__ __forceinline__ void mesh_body(const TablesDev &tb, const OrdDev &od,
 
     // all threads: thread 0 backtracks into cuts/slot_*, the first wave scores them
     auto backtrack_and_score = [&](int K, int S, int64_t &bott, int64_t &total) {
-        if (tid == 0) mesh_backtrack(tb, m, offs, order, K, S, n_dev, cuts, slot_g, slot_k, slot_first);
+        if (tid == 0) mesh_backtrack<kFast>(tb, m, offs, order, K, S, n_dev, cuts, slot_g, slot_k, slot_first);
         __syncthreads();
         if (wave == 0) {
             int64_t b, t;
@@ -239,7 +239,7 @@ __device__ __forceinline__ void mesh_h1_body(const TablesDev &tb, const OrdDev &
         if constexpr (kFast) sum = mesh_h1_pass_fast(tb, m, offs, order, group_at, sums_lds, K, S, n_dev, cap);
         else sum = mesh_h1_pass(tb, m, offs, order, group_at, K, S, n_dev, cap);
         if (sum == kInf) { fail(HARP_CAND_INFEASIBLE); continue; }
-        if (tid == 0) mesh_h1_backtrack(tb, m, offs, order, K, S, n_dev, cap, cuts, slot_g, slot_k, slot_first, count);
+        if (tid == 0) mesh_h1_backtrack<kFast>(tb, m, offs, order, K, S, n_dev, cap, cuts, slot_g, slot_k, slot_first, count);
         __syncthreads();
         int32_t *sp = out.splits + int64_t(c) * (S_max + 1);
         int32_t *df = out.dev_first + int64_t(c) * S_max;

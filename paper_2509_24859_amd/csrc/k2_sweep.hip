@@ -317,7 +317,7 @@ __device__ __forceinline__ void mesh_sweep_body(const TablesDev &tb, const OrdDe
         // thread 0 backtracks the pass just run; everyone copies the plan to this item's slot
         auto keep = [&](int64_t at, int64_t T) {
             if (tid == 0)
-                mesh_h1_backtrack(tb, m, offs, order, K, S, n_dev, at, cuts, slot_g, slot_k, slot_first, count);
+                mesh_h1_backtrack<kFast>(tb, m, offs, order, K, S, n_dev, at, cuts, slot_g, slot_k, slot_first, count);
             __syncthreads();
             for (int s = tid; s <= S; s += nthreads) mine.cuts[s] = cuts[s];
             for (int s = tid; s < S; s += nthreads) {

@@ -137,7 +137,7 @@ __device__ __forceinline__ int64_t mesh_pass(const TablesDev &tb, const MeshSlic
 //  * four previous cuts per trip, all evaluated under predicates; entries below a stop cannot
 //    update (their time exceeds the best value or the cap, or they do not fit), so only the last
 //    entry of a trip decides whether the lane goes on.
-constexpr int kMeshFastMaxL = 4096;
+constexpr int kMeshFastMaxL = 4096;     // and below 8192, so that a cut fits the 13 bits of a packed back-pointer
 
 template <bool kCapped>
 __device__ __forceinline__ int64_t mesh_pass_fast(const TablesDev &tb, const MeshSlice &m, const int32_t *offs,
@@ -169,7 +169,7 @@ __device__ __forceinline__ int64_t mesh_pass_fast(const TablesDev &tb, const Mes
         const int d_lo = forced ? forced_off[s + 1] : (last ? Dtot : s + 1);
         const int d_hi = forced ? forced_off[s + 1] : (last ? Dtot : Dtot - (S - 1 - s));
         const int n_i = i_hi - i_lo + 1, n_d = d_hi - d_lo + 1;
-        uint32_t *arg_s = m.arg + size_t(s) * size_t(n_dev + 1) * W;
+        uint16_t *arg_s = reinterpret_cast<uint16_t *>(m.arg) + size_t(s) * size_t(n_dev + 1) * W;   // packed form
         for (int x = tid; x < n_i * n_d; x += nthreads) {
             const int i = i_lo + x % n_i, d2 = d_lo + x / n_i;
             int k = 0;
@@ -238,7 +238,7 @@ __device__ __forceinline__ int64_t mesh_pass_fast(const TablesDev &tb, const Mes
                 jq = uint32_t(best) & 0x7FFFFu;
             }
             Dn[size_t(d2) * W + i] = value;
-            arg_s[size_t(d2) * W + i] = (jq >> 3) | ((jq & 7u) << 16);
+            arg_s[size_t(d2) * W + i] = uint16_t(((jq >> 3) & 0x1FFFu) | ((jq & 7u) << 13));
         }
         ValT *tmp = Dp; Dp = Dn; Dn = tmp;
     }
@@ -248,6 +248,10 @@ __device__ __forceinline__ int64_t mesh_pass_fast(const TablesDev &tb, const Mes
 }
 
 // Thread 0: follows the back-pointers from (S, L, all devices).
+// kPacked: the back-pointers were written by a 32-bit pass (uint16: cut | degree index << 13, which
+// holds every cut of a sequence the 32-bit rows exist for), otherwise by an int64 pass (uint32:
+// cut | degree index << 16).
+template <bool kPacked>
 __device__ __forceinline__ void mesh_backtrack(const TablesDev &tb, const MeshSlice &m, const int32_t *offs,
                                                const uint16_t *order, int K, int S, int64_t n_dev, int32_t *cuts,
                                                uint16_t *slot_g, uint8_t *slot_k, int32_t *slot_first) {
@@ -255,9 +259,10 @@ __device__ __forceinline__ void mesh_backtrack(const TablesDev &tb, const MeshSl
     int i = L, d = offs[K];
     cuts[S] = L;
     for (int s = S; s >= 1; --s) {
-        const uint32_t a = m.arg[(size_t(s - 1) * size_t(n_dev + 1) + size_t(d)) * W + i];
-        int j = int(a & 0xFFFFu);
-        const int q = int(a >> 16) & 7;
+        const size_t at = (size_t(s - 1) * size_t(n_dev + 1) + size_t(d)) * W + i;
+        const uint32_t a = kPacked ? reinterpret_cast<const uint16_t *>(m.arg)[at] : m.arg[at];
+        int j = int(a & (kPacked ? 0x1FFFu : 0xFFFFu));
+        const int q = int(a >> (kPacked ? 13 : 16)) & 7;
         j = j < L ? j : L - 1;                      // a finite value only chains through cuts inside the row
         d -= tb.tp[q];
         d = d > 0 ? d : 0;
@@ -405,7 +410,7 @@ __device__ __forceinline__ int64_t mesh_h1_pass_fast(const TablesDev &tb, const 
         const int e_hi = forced ? Dtot - forced_off[S - s] : (whole ? Dtot : Dtot - (S - s));
         const int j_hi = L - (s - 1);
         const int n_i = i_hi - i_lo + 1, n_e = e_hi - e_lo + 1;
-        uint32_t *arg_s = m.arg + size_t(s - 1) * size_t(n_dev + 1) * W;
+        uint16_t *arg_s = reinterpret_cast<uint16_t *>(m.arg) + size_t(s - 1) * size_t(n_dev + 1) * W;   // packed form
         for (int x = tid; x < n_i * n_e; x += nthreads) {
             const int i = i_lo + x % n_i, e = e_lo + x / n_i;
             const int d0 = Dtot - e;                 // first device of the stage this step places
@@ -468,7 +473,7 @@ __device__ __forceinline__ int64_t mesh_h1_pass_fast(const TablesDev &tb, const 
             }
             Gn[size_t(e) * W + i] = best == kNone ? kNone : (((best >> 19) << 10) | uint64_t(best_n));
             const uint32_t jq = uint32_t(best) & 0x7FFFFu;
-            arg_s[size_t(e) * W + i] = (jq >> 3) | ((jq & 7u) << 16);
+            arg_s[size_t(e) * W + i] = uint16_t(((jq >> 3) & 0x1FFFu) | ((jq & 7u) << 13));
         }
         uint64_t *tg = Gp; Gp = Gn; Gn = tg;
     }
@@ -479,6 +484,7 @@ __device__ __forceinline__ int64_t mesh_h1_pass_fast(const TablesDev &tb, const 
 
 // Thread 0: follows the back-pointers of the H-1F1B form from (S, 0, all devices) and recomputes the
 // counts by eq. Ni along the plan, from the last stage backwards.
+template <bool kPacked>
 __device__ __forceinline__ void mesh_h1_backtrack(const TablesDev &tb, const MeshSlice &m, const int32_t *offs,
                                                   const uint16_t *order, int K, int S, int64_t n_dev, int64_t cap,
                                                   int32_t *cuts, uint16_t *slot_g, uint8_t *slot_k,
@@ -488,9 +494,10 @@ __device__ __forceinline__ void mesh_h1_backtrack(const TablesDev &tb, const Mes
     int i = 0, e = Dtot;
     for (int slot = 0; slot < S; ++slot) {
         const int s = S - slot;
-        const uint32_t a = m.arg[(size_t(s - 1) * size_t(n_dev + 1) + size_t(e)) * W + i];
-        int j = int(a & 0xFFFFu);
-        const int q = int(a >> 16) & 7;
+        const size_t at = (size_t(s - 1) * size_t(n_dev + 1) + size_t(e)) * W + i;
+        const uint32_t a = kPacked ? reinterpret_cast<const uint16_t *>(m.arg)[at] : m.arg[at];
+        int j = int(a & (kPacked ? 0x1FFFu : 0xFFFFu));
+        const int q = int(a >> (kPacked ? 13 : 16)) & 7;
         j = j <= L ? j : L;                     // a finite sum only chains through cuts inside the row
         const int d0 = Dtot - e;
         int k = 0;
