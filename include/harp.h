@@ -193,6 +193,23 @@ int harp_plan_batch(harp_ctx *ctx, harp_tables *tables, const harp_candidates *c
                     const harp_plans *out, void *workspace, size_t workspace_bytes,
                     void *hip_stream);
 
+/* harp_plan_batch for callers that cannot allocate device memory or hand over a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same inputs,
+ * outputs, statuses and kernel selection as harp_plan_batch; the planner workspace is a static
+ * device array of HARP_STATIC_SCRATCH_BYTES inside the library (every GPU the library is used on
+ * holds its own copy until the process ends; harp_create looks up its address).  The call
+ * allocates and frees nothing, on the device or through any library.  It runs with as many
+ * workgroups as the array has room for, so large batches are slower than with harp_plan_batch; a
+ * batch whose lists and reachability bands alone (about 4 (S_max + 3) bytes per candidate, plus one
+ * workgroup's back-pointer rows) exceed the array is refused with HARP_ERR_WORKSPACE and nothing
+ * is launched.  The tables must have been finalized (harp_tables_finalize) if the call is to stay
+ * free of host waits.  Every call on one GPU uses the same array: calls that overlap on one GPU
+ * (two streams, two contexts, two host threads) race; calls queued on one stream do not.  The
+ * array keeps the previous call's contents; the kernels clear the counters they rely on. */
+#define HARP_STATIC_SCRATCH_BYTES (32u << 20)
+int harp_plan_batch_static(harp_ctx *ctx, harp_tables *tables, const harp_candidates *cands,
+                           const harp_plans *out, void *hip_stream);
+
 /* The exact optimum of eq. gpipe_cost_model per candidate: the sweep over the stage-time cap t_max
  * of section 5.2.4 (2), between t_S (the smallest feasible cap, found by the min-max search of
  * harp_plan_batch, which this call runs first) and t_E = ceil(T(t_S) / B), with the capped

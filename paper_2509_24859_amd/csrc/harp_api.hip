@@ -16,8 +16,14 @@ struct harp_ctx {
     int n_cu;
     int plan_path;
     BuildHeader *pinned;   // host, pinned
+    unsigned char *scratch;   // this device's copy of the library's static scratch array
     char err[512];
 };
+
+// Planner workspace of harp_plan_batch_static.  In host code this name is only a handle for
+// hipGetSymbolAddress: harp_create asks for the device address once per context, with the
+// context's device current, and every later use goes through harp_ctx::scratch.
+static __device__ __align__(256) unsigned char scratch[HARP_STATIC_SCRATCH_BYTES];
 
 struct harp_tables {
     TablesDev dev;
@@ -134,6 +140,12 @@ int n_plan_groups(const harp_ctx *ctx, int C, bool fast, int L, int S_max) {
     return C < resident ? (C < 1 ? 1 : C) : resident;
 }
 
+// Workspace of the min-max planner on the path that will run, with `groups` workgroups.
+size_t plan_bytes_on_path(const harp_tables *t, const harp_candidates *cd, bool fast, int groups) {
+    if (fast) return plan_fast_ws_bytes(t->dev.L, cd->S_max, cd->C, groups) + 256;
+    return size_t(groups) * plan_generic_ws_per_group(t->dev.L, cd->S_max) + 256;
+}
+
 // Workgroups of the submesh planner: resident ones, fewer when their slices would pass 16 GiB.
 int n_mesh_groups(const harp_ctx *ctx, int C, size_t per_group, int threads) {
     long long n = (long long)ctx->n_cu * (2048 / threads);         // as many wavefronts as a CU holds
@@ -214,7 +226,14 @@ int harp_create(harp_ctx **out, int hip_device_ordinal) {
     ctx->n_cu = prop.multiProcessorCount;
     ctx->plan_path = HARP_PATH_AUTO;
     ctx->pinned = nullptr;
+    ctx->scratch = nullptr;
     ctx->err[0] = 0;
+    // each GPU holds its own copy of the static scratch array at its own address
+    if (hipGetSymbolAddress(reinterpret_cast<void **>(&ctx->scratch), HIP_SYMBOL(scratch)) != hipSuccess ||
+        !ctx->scratch) {
+        delete ctx;
+        return HARP_ERR_HIP;
+    }
     if (hipHostMalloc(reinterpret_cast<void **>(&ctx->pinned), sizeof(BuildHeader), hipHostMallocDefault) != hipSuccess) {
         delete ctx;
         return HARP_ERR_HIP;
@@ -369,6 +388,38 @@ int harp_plan_batch(harp_ctx *ctx, harp_tables *t, const harp_candidates *cd, co
     const int groups = n_plan_groups(ctx, cd->C, fast, t->dev.L, cd->S_max);
     if (fast) launch_plan_fast(t->dev, c, o, workspace, groups, static_cast<hipStream_t>(hip_stream));
     else launch_plan_generic(t->dev, c, o, workspace, groups, static_cast<hipStream_t>(hip_stream));
+    e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(ctx, e, "launching the planner kernel");
+    return HARP_OK;
+}
+
+int harp_plan_batch_static(harp_ctx *ctx, harp_tables *t, const harp_candidates *cd, const harp_plans *out,
+                           void *hip_stream) {
+    int rc = check_batch(ctx, t, cd);
+    if (rc != HARP_OK) return rc;
+    if (!out || (cd->C > 0 && (!out->splits || !out->dev_first || !out->bottleneck || !out->iter_time || !out->status)))
+        return fail(ctx, HARP_ERR_INVALID_ARG, "null output array");
+    if (ctx->plan_path == HARP_PATH_FAST32 && !t->fast32)
+        return fail(ctx, HARP_ERR_UNIMPLEMENTED, "the 32-bit path was requested but these tables do not allow it");
+    if (cd->C == 0) return HARP_OK;
+    // as many workgroups as the static array has room for, at most the resident number
+    const bool fast = use_fast(ctx, t);
+    int groups = n_plan_groups(ctx, cd->C, fast, t->dev.L, cd->S_max);
+    const size_t one = plan_bytes_on_path(t, cd, fast, 1);
+    if (one > size_t(HARP_STATIC_SCRATCH_BYTES))
+        return fail(ctx, HARP_ERR_WORKSPACE,
+                    "this batch needs at least %zu bytes of planner workspace, the static scratch array holds %zu: "
+                    "use harp_plan_batch with a caller-lent workspace, or split the batch",
+                    one, size_t(HARP_STATIC_SCRATCH_BYTES));
+    const size_t per_group = plan_bytes_on_path(t, cd, fast, 2) - one;
+    const size_t room = (size_t(HARP_STATIC_SCRATCH_BYTES) - one) / (per_group ? per_group : 1) + 1;
+    if (size_t(groups) > room) groups = int(room);
+    hipError_t e = hipSetDevice(ctx->device);
+    if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
+    const CandDev c = { cd->C, cd->S_max, cd->cand_S, cd->cand_group, cd->cand_tp };
+    const PlansDev o = { out->splits, out->dev_first, out->bottleneck, out->iter_time, out->status };
+    if (fast) launch_plan_fast(t->dev, c, o, ctx->scratch, groups, static_cast<hipStream_t>(hip_stream));
+    else launch_plan_generic(t->dev, c, o, ctx->scratch, groups, static_cast<hipStream_t>(hip_stream));
     e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(ctx, e, "launching the planner kernel");
     return HARP_OK;
