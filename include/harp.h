@@ -139,7 +139,9 @@ int harp_build_segment_costs(harp_ctx *ctx, const harp_problem *problem, void *t
 int harp_tables_finalize(harp_ctx *ctx, harp_tables *tables);
 
 /* 1 when the finalized tables allow the 32-bit fast path (all degrees powers of two, every time
- * below 2^31 us, L <= 1024, per-link cut table within 256 MiB), else 0. */
+ * below 2^31 us, L <= 1024, per-link cut table within 256 MiB), else 0.  A batch runs on it when
+ * its feasibility index (min(S_max, M, L) * T * n_tp rows of L + 1 16-bit entries) stays within
+ * 256 MiB as well. */
 int harp_tables_fast32(const harp_tables *tables);
 
 /* DEVICE pointers into the table buffer, for inspection: running sums indexed [row][i],
@@ -209,6 +211,16 @@ int harp_plan_batch(harp_ctx *ctx, harp_tables *tables, const harp_candidates *c
 #define HARP_STATIC_SCRATCH_BYTES (32u << 20)
 int harp_plan_batch_static(harp_ctx *ctx, harp_tables *tables, const harp_candidates *cands,
                            const harp_plans *out, void *hip_stream);
+
+/* Measurement support: harp_plan_batch with the work it does counted (an instrumented build of the
+ * same kernel; slower, same outputs).  work: DEVICE [4], receives the number of transitions
+ * (s, i, j) whose value max(D[s][j], time, comm) the kernel evaluated, the DP cells (s, i) it filled,
+ * the groups of four previous cuts it read, and the candidates that reached the recurrence (the
+ * others were rejected by the memory bounds of the pre-pass).  32-bit path only
+ * (HARP_ERR_UNIMPLEMENTED otherwise).  Everything else as harp_plan_batch. */
+int harp_plan_batch_count_work(harp_ctx *ctx, harp_tables *tables, const harp_candidates *cands,
+                               const harp_plans *out, void *workspace, size_t workspace_bytes,
+                               uint64_t *work, void *hip_stream);
 
 /* The exact optimum of eq. gpipe_cost_model per candidate: the sweep over the stage-time cap t_max
  * of section 5.2.4 (2), between t_S (the smallest feasible cap, found by the min-max search of

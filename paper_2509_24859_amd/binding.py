@@ -25,6 +25,7 @@ EXPORTS = (
     "harp_build_segment_costs", "harp_tables_finalize", "harp_tables_fast32", "harp_tables_pf",
     "harp_tables_pp", "harp_tables_ps", "harp_tables_pr", "harp_tables_release",
     "harp_set_plan_path", "harp_plan_workspace_bytes", "harp_plan_batch", "harp_plan_batch_static",
+    "harp_plan_batch_count_work",
     "harp_plan_exact_batch",
     "harp_plan_h1f1b_batch", "harp_score_h1f1b",
     "harp_plan_mesh_workspace_bytes", "harp_plan_mesh_batch", "harp_plan_mesh_exact_batch", "harp_plan_mesh_h1f1b_batch",
@@ -102,6 +103,7 @@ def load_library() -> C.CDLL:
     lib.harp_plan_workspace_bytes.argtypes = [vp, vp, C.POINTER(harp_candidates)]
     lib.harp_plan_workspace_bytes.restype = sz
     lib.harp_plan_batch.argtypes = [vp, vp, C.POINTER(harp_candidates), C.POINTER(harp_plans), vp, sz, vp]
+    lib.harp_plan_batch_count_work.argtypes = [vp, vp, C.POINTER(harp_candidates), C.POINTER(harp_plans), vp, sz, vp, vp]
     lib.harp_plan_batch_static.argtypes = [vp, vp, C.POINTER(harp_candidates), C.POINTER(harp_plans), vp]
     lib.harp_plan_exact_batch.argtypes = [vp, vp, C.POINTER(harp_candidates), C.POINTER(harp_plans), vp, vp, sz, vp]
     lib.harp_plan_h1f1b_batch.argtypes = [vp, vp, C.POINTER(harp_candidates), vp, C.POINTER(harp_plans), vp, vp, sz, vp]
@@ -325,6 +327,14 @@ def harp_plan_batch(ctx: Context, tables: Tables, dc: DeviceCandidates, out: Dev
                     workspace, stream=None):
     ctx.check(ctx.lib.harp_plan_batch(ctx.handle, tables.handle, C.byref(dc.c), C.byref(out.c),
                                       workspace.data_ptr(), workspace.numel(), _stream_handle(stream)))
+
+
+def harp_plan_batch_count_work(ctx: Context, tables: Tables, dc: DeviceCandidates, out: DevicePlans, workspace, work,
+                               stream=None):
+    """work: int64 device tensor of 4 entries (transitions, cells, groups of four, candidates planned)."""
+    ctx.check(ctx.lib.harp_plan_batch_count_work(ctx.handle, tables.handle, C.byref(dc.c), C.byref(out.c),
+                                                 workspace.data_ptr(), workspace.numel(), work.data_ptr(),
+                                                 _stream_handle(stream)))
 
 
 def harp_plan_batch_static(ctx: Context, tables: Tables, dc: DeviceCandidates, out: DevicePlans, stream=None):

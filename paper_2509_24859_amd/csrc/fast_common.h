@@ -79,26 +79,48 @@ inline size_t fast_arg_per_group(int L, int S_max) {
     return (b + 255) & ~size_t(255);
 }
 
-// Workspace: counters | live list [C] | dead list [C] | bands [S_max+1][C] | back-pointer slices.
+// Rows of the feasibility index (see k2_fast.hip): one per in-flight count n = 1 .. n_max, GPU type and
+// degree index; entry i is the lowest previous cut j such that operators [j, i) fit.
+inline int lo_n_max(int L, int S_max, int M) {
+    int n = S_max < M ? S_max : M;
+    return n < L ? n : L;
+}
+inline size_t lo_pitch(int L) { return (size_t(L) + 1 + 31) & ~size_t(31); }
+inline size_t lo_table_bytes(int L, int S_max, int M, int T, int n_tp) {
+    return size_t(lo_n_max(L, S_max, M)) * size_t(T) * size_t(n_tp) * lo_pitch(L) * sizeof(uint16_t);
+}
+
+// Workspace: counters | live list [C] | dead list [C] | bands [C][S_max+1] | feasibility index |
+// back-pointer slices (one per resident wavefront of k2_fast, one per workgroup of the other kernels).
 struct FastWorkspace {
     int *counts;
     int32_t *live_list;
     uint32_t *dead_list;
     uint32_t *bands;
+    uint16_t *lo_tab;
     unsigned char *arg;
     size_t total;
 };
 
-inline FastWorkspace carve(void *ws, int L, int S_max, int C, int n_groups) {
+struct FastShape {
+    int L, S_max, C, M, T, n_tp;
+};
+
+inline FastShape fast_shape(const TablesDev &tb, const CandDev &cd) {
+    return FastShape{tb.L, cd.S_max, cd.C, tb.M, tb.T, tb.n_tp};
+}
+
+inline FastWorkspace carve(void *ws, const FastShape &f, int n_slices) {
     auto up = [](size_t x) { return (x + 255) & ~size_t(255); };
     unsigned char *base = static_cast<unsigned char *>(ws);
     FastWorkspace w;
     size_t off = 0;
     w.counts = reinterpret_cast<int *>(base + off); off += 256;
-    w.live_list = reinterpret_cast<int32_t *>(base + off); off += up(size_t(C) * 4);
-    w.dead_list = reinterpret_cast<uint32_t *>(base + off); off += up(size_t(C) * 4);
-    w.bands = reinterpret_cast<uint32_t *>(base + off); off += up(size_t(C) * (S_max + 1) * 4);
-    w.arg = base + off; off += size_t(n_groups) * fast_arg_per_group(L, S_max);
+    w.live_list = reinterpret_cast<int32_t *>(base + off); off += up(size_t(f.C) * 4);
+    w.dead_list = reinterpret_cast<uint32_t *>(base + off); off += up(size_t(f.C) * 4);
+    w.bands = reinterpret_cast<uint32_t *>(base + off); off += up(size_t(f.C) * (f.S_max + 1) * 4);
+    w.lo_tab = reinterpret_cast<uint16_t *>(base + off); off += up(lo_table_bytes(f.L, f.S_max, f.M, f.T, f.n_tp));
+    w.arg = base + off; off += size_t(n_slices) * fast_arg_per_group(f.L, f.S_max);
     w.total = off;
     return w;
 }

@@ -134,16 +134,35 @@ int check_batch(harp_ctx *ctx, harp_tables *t, const harp_candidates *cd) {
     return finalize_tables(ctx, t);
 }
 
+// Workgroups of the planner kernels that work one candidate per workgroup.
 int n_plan_groups(const harp_ctx *ctx, int C, bool fast, int L, int S_max) {
     int resident = fast ? plan_fast_groups(L, S_max, ctx->n_cu) : ctx->n_cu * 8;
     if (resident < 1) resident = 1;
     return C < resident ? (C < 1 ? 1 : C) : resident;
 }
 
-// Workspace of the min-max planner on the path that will run, with `groups` workgroups.
-size_t plan_bytes_on_path(const harp_tables *t, const harp_candidates *cd, bool fast, int groups) {
-    if (fast) return plan_fast_ws_bytes(t->dev.L, cd->S_max, cd->C, groups) + 256;
-    return size_t(groups) * plan_generic_ws_per_group(t->dev.L, cd->S_max) + 256;
+// Back-pointer slices of the 32-bit path: one per resident wavefront of the min-max kernel (whole
+// workgroups of kFastWaves) or per workgroup of the kernels built on it, whichever is more.
+int n_fast_slices(const harp_ctx *ctx, int C, int L, int S_max) {
+    int want = plan_fast_waves(L, S_max, ctx->n_cu);
+    const int groups = plan_fast_groups(L, S_max, ctx->n_cu);
+    if (want < groups) want = groups;
+    if (want > C) want = C;
+    want = (want + kFastWaves - 1) / kFastWaves * kFastWaves;
+    return want < kFastWaves ? kFastWaves : want;
+}
+
+// Workspace of the min-max planner on the path that will run, with `units` slices (32-bit path) or
+// workgroups (int64 path).
+size_t plan_bytes_on_path(const harp_tables *t, const harp_candidates *cd, bool fast, int units) {
+    if (fast) return plan_fast_ws_bytes(t->dev, cd->S_max, cd->C, units) + 256;
+    return size_t(units) * plan_generic_ws_per_group(t->dev.L, cd->S_max) + 256;
+}
+
+// The 32-bit path keeps a feasibility index whose size grows with min(S_max, M) * T * n_tp * L;
+// batches for which it would pass the limit run on the int64 path.
+bool fast_batch_ok(const harp_tables *t, const harp_candidates *cd) {
+    return plan_fast_index_bytes(t->dev, cd->S_max) <= kFastIndexLimit;
 }
 
 // Workgroups of the submesh planner: resident ones, fewer when their slices would pass 16 GiB.
@@ -205,6 +224,9 @@ int check_orderings(harp_ctx *ctx, harp_tables *t, const harp_orderings *od) {
 
 bool use_fast(const harp_ctx *ctx, const harp_tables *t) {
     return t->fast32 && ctx->plan_path != HARP_PATH_GENERIC;
+}
+bool use_fast(const harp_ctx *ctx, const harp_tables *t, const harp_candidates *cd) {
+    return use_fast(ctx, t) && fast_batch_ok(t, cd);
 }
 
 }  // namespace
@@ -361,97 +383,123 @@ size_t harp_plan_workspace_bytes(harp_ctx *ctx, const harp_tables *t, const harp
                                  : plan_generic_h1f1b_ws_per_group(t->dev.L, cd->S_max);
     size_t gen = size_t(n_plan_groups(ctx, C, false, t->dev.L, cd->S_max)) * per_group;
     size_t fast = 0;
-    if (t->lim.want_fast)
-        fast = plan_fast_ws_bytes(t->dev.L, cd->S_max, C, n_plan_groups(ctx, C, true, t->dev.L, cd->S_max));
+    if (t->lim.want_fast && fast_batch_ok(t, cd))
+        fast = plan_fast_ws_bytes(t->dev, cd->S_max, C, n_fast_slices(ctx, C, t->dev.L, cd->S_max));
     return (gen > fast ? gen : fast) + 256;
 }
 
-int harp_plan_batch(harp_ctx *ctx, harp_tables *t, const harp_candidates *cd, const harp_plans *out,
-                    void *workspace, size_t workspace_bytes, void *hip_stream) {
+}  // extern "C"
+
+namespace {
+
+// What the candidate planners share: argument checks, the path that will run, and how many
+// workgroups and back-pointer slices the lent memory allows.
+struct PlanCall {
+    CandDev c;
+    PlansDev o;
+    bool fast;
+    int groups;      // workgroups of the one-candidate-per-workgroup kernels
+    int slices;      // back-pointer slices of the 32-bit path (>= groups, a multiple of kFastWaves)
+    hipStream_t st;
+};
+
+// limit_bytes: the memory at hand.  With shrink the unit count is cut down to what fits (the
+// static-scratch entry point); without, the full resident count must fit.
+int plan_prepare(harp_ctx *ctx, harp_tables *t, const harp_candidates *cd, const harp_plans *out,
+                 bool extra_null, const void *workspace, size_t limit_bytes, bool shrink, void *hip_stream,
+                 PlanCall &pc) {
     int rc = check_batch(ctx, t, cd);
     if (rc != HARP_OK) return rc;
-    if (!out || (cd->C > 0 && (!out->splits || !out->dev_first || !out->bottleneck || !out->iter_time || !out->status)))
-        return fail(ctx, HARP_ERR_INVALID_ARG, "null output array");
-    if (ctx->plan_path == HARP_PATH_FAST32 && !t->fast32)
-        return fail(ctx, HARP_ERR_UNIMPLEMENTED, "the 32-bit path was requested but these tables do not allow it");
+    if (!out || extra_null ||
+        (cd->C > 0 && (!out->splits || !out->dev_first || !out->bottleneck || !out->iter_time || !out->status)))
+        return fail(ctx, HARP_ERR_INVALID_ARG, "null array");
+    if (ctx->plan_path == HARP_PATH_FAST32 && !(t->fast32 && fast_batch_ok(t, cd)))
+        return fail(ctx, HARP_ERR_UNIMPLEMENTED,
+                    "the 32-bit path was requested but these tables or this batch do not allow it");
+    pc.c = CandDev{ cd->C, cd->S_max, cd->cand_S, cd->cand_group, cd->cand_tp };
+    pc.o = PlansDev{ out->splits, out->dev_first, out->bottleneck, out->iter_time, out->status };
+    pc.fast = use_fast(ctx, t, cd);
+    pc.groups = n_plan_groups(ctx, cd->C, pc.fast, t->dev.L, cd->S_max);
+    pc.slices = pc.fast ? n_fast_slices(ctx, cd->C, t->dev.L, cd->S_max) : pc.groups;
+    pc.st = static_cast<hipStream_t>(hip_stream);
     if (cd->C == 0) return HARP_OK;
-    const size_t need = harp_plan_workspace_bytes(ctx, t, cd);
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0)
         return fail(ctx, HARP_ERR_WORKSPACE, "workspace must be a 256-byte aligned device pointer");
-    if (workspace_bytes < need)
-        return fail(ctx, HARP_ERR_WORKSPACE, "workspace holds %zu bytes, %zu needed", workspace_bytes, need);
+    if (!shrink) {
+        const size_t need = harp_plan_workspace_bytes(ctx, t, cd);
+        if (limit_bytes < need)
+            return fail(ctx, HARP_ERR_WORKSPACE, "workspace holds %zu bytes, %zu needed", limit_bytes, need);
+    } else {
+        const int unit = pc.fast ? kFastWaves : 1;
+        const size_t least = plan_bytes_on_path(t, cd, pc.fast, unit);
+        if (least > limit_bytes)
+            return fail(ctx, HARP_ERR_WORKSPACE,
+                        "this batch needs at least %zu bytes of planner workspace, the static scratch array holds %zu: "
+                        "use harp_plan_batch with a caller-lent workspace, or split the batch", least, limit_bytes);
+        const size_t per_unit = plan_bytes_on_path(t, cd, pc.fast, 2 * unit) - least;
+        size_t room = ((limit_bytes - least) / (per_unit ? per_unit : 1) + 1) * size_t(unit);
+        if (size_t(pc.slices) > room) pc.slices = int(room);
+        if (pc.groups > pc.slices) pc.groups = pc.slices;
+    }
     hipError_t e = hipSetDevice(ctx->device);
     if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
-    const CandDev c = { cd->C, cd->S_max, cd->cand_S, cd->cand_group, cd->cand_tp };
-    const PlansDev o = { out->splits, out->dev_first, out->bottleneck, out->iter_time, out->status };
-    const bool fast = use_fast(ctx, t);
-    const int groups = n_plan_groups(ctx, cd->C, fast, t->dev.L, cd->S_max);
-    if (fast) launch_plan_fast(t->dev, c, o, workspace, groups, static_cast<hipStream_t>(hip_stream));
-    else launch_plan_generic(t->dev, c, o, workspace, groups, static_cast<hipStream_t>(hip_stream));
-    e = hipGetLastError();
+    return HARP_OK;
+}
+
+int plan_minmax(harp_ctx *ctx, harp_tables *t, const PlanCall &pc, void *ws, unsigned long long *work) {
+    if (pc.fast) launch_plan_fast(t->dev, pc.c, pc.o, ws, pc.slices, ctx->n_cu, work, pc.st);
+    else launch_plan_generic(t->dev, pc.c, pc.o, ws, pc.groups, pc.st);
+    const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(ctx, e, "launching the planner kernel");
     return HARP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int harp_plan_batch(harp_ctx *ctx, harp_tables *t, const harp_candidates *cd, const harp_plans *out,
+                    void *workspace, size_t workspace_bytes, void *hip_stream) {
+    PlanCall pc;
+    const int rc = plan_prepare(ctx, t, cd, out, false, workspace, workspace_bytes, false, hip_stream, pc);
+    if (rc != HARP_OK || cd->C == 0) return rc;
+    return plan_minmax(ctx, t, pc, workspace, nullptr);
 }
 
 int harp_plan_batch_static(harp_ctx *ctx, harp_tables *t, const harp_candidates *cd, const harp_plans *out,
                            void *hip_stream) {
-    int rc = check_batch(ctx, t, cd);
+    PlanCall pc;
+    const int rc = plan_prepare(ctx, t, cd, out, false, ctx ? ctx->scratch : nullptr,
+                                size_t(HARP_STATIC_SCRATCH_BYTES), true, hip_stream, pc);
+    if (rc != HARP_OK || cd->C == 0) return rc;
+    return plan_minmax(ctx, t, pc, ctx->scratch, nullptr);
+}
+
+int harp_plan_batch_count_work(harp_ctx *ctx, harp_tables *t, const harp_candidates *cd, const harp_plans *out,
+                               void *workspace, size_t workspace_bytes, uint64_t *work, void *hip_stream) {
+    PlanCall pc;
+    const int rc = plan_prepare(ctx, t, cd, out, work == nullptr, workspace, workspace_bytes, false, hip_stream, pc);
     if (rc != HARP_OK) return rc;
-    if (!out || (cd->C > 0 && (!out->splits || !out->dev_first || !out->bottleneck || !out->iter_time || !out->status)))
-        return fail(ctx, HARP_ERR_INVALID_ARG, "null output array");
-    if (ctx->plan_path == HARP_PATH_FAST32 && !t->fast32)
-        return fail(ctx, HARP_ERR_UNIMPLEMENTED, "the 32-bit path was requested but these tables do not allow it");
+    if (!pc.fast)
+        return fail(ctx, HARP_ERR_UNIMPLEMENTED, "work is counted on the 32-bit path only");
+    launch_clear_work(reinterpret_cast<unsigned long long *>(work), pc.st);
     if (cd->C == 0) return HARP_OK;
-    // as many workgroups as the static array has room for, at most the resident number
-    const bool fast = use_fast(ctx, t);
-    int groups = n_plan_groups(ctx, cd->C, fast, t->dev.L, cd->S_max);
-    const size_t one = plan_bytes_on_path(t, cd, fast, 1);
-    if (one > size_t(HARP_STATIC_SCRATCH_BYTES))
-        return fail(ctx, HARP_ERR_WORKSPACE,
-                    "this batch needs at least %zu bytes of planner workspace, the static scratch array holds %zu: "
-                    "use harp_plan_batch with a caller-lent workspace, or split the batch",
-                    one, size_t(HARP_STATIC_SCRATCH_BYTES));
-    const size_t per_group = plan_bytes_on_path(t, cd, fast, 2) - one;
-    const size_t room = (size_t(HARP_STATIC_SCRATCH_BYTES) - one) / (per_group ? per_group : 1) + 1;
-    if (size_t(groups) > room) groups = int(room);
-    hipError_t e = hipSetDevice(ctx->device);
-    if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
-    const CandDev c = { cd->C, cd->S_max, cd->cand_S, cd->cand_group, cd->cand_tp };
-    const PlansDev o = { out->splits, out->dev_first, out->bottleneck, out->iter_time, out->status };
-    if (fast) launch_plan_fast(t->dev, c, o, ctx->scratch, groups, static_cast<hipStream_t>(hip_stream));
-    else launch_plan_generic(t->dev, c, o, ctx->scratch, groups, static_cast<hipStream_t>(hip_stream));
-    e = hipGetLastError();
-    if (e != hipSuccess) return hip_fail(ctx, e, "launching the planner kernel");
-    return HARP_OK;
+    return plan_minmax(ctx, t, pc, workspace, reinterpret_cast<unsigned long long *>(work));
 }
 
 int harp_plan_exact_batch(harp_ctx *ctx, harp_tables *t, const harp_candidates *cd, const harp_plans *out,
                           int32_t *n_passes, void *workspace, size_t workspace_bytes, void *hip_stream) {
-    int rc = check_batch(ctx, t, cd);
-    if (rc != HARP_OK) return rc;
-    if (!out || (cd->C > 0 && (!out->splits || !out->dev_first || !out->bottleneck || !out->iter_time || !out->status)))
-        return fail(ctx, HARP_ERR_INVALID_ARG, "null output array");
-    if (ctx->plan_path == HARP_PATH_FAST32 && !t->fast32)
-        return fail(ctx, HARP_ERR_UNIMPLEMENTED, "the 32-bit path was requested but these tables do not allow it");
-    if (cd->C == 0) return HARP_OK;
-    const size_t need = harp_plan_workspace_bytes(ctx, t, cd);
-    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0)
-        return fail(ctx, HARP_ERR_WORKSPACE, "workspace must be a 256-byte aligned device pointer");
-    if (workspace_bytes < need)
-        return fail(ctx, HARP_ERR_WORKSPACE, "workspace holds %zu bytes, %zu needed", workspace_bytes, need);
-    hipError_t e = hipSetDevice(ctx->device);
-    if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
-    const CandDev c = { cd->C, cd->S_max, cd->cand_S, cd->cand_group, cd->cand_tp };
-    const PlansDev o = { out->splits, out->dev_first, out->bottleneck, out->iter_time, out->status };
-    const bool fast = use_fast(ctx, t);
-    const int groups = n_plan_groups(ctx, cd->C, fast, t->dev.L, cd->S_max);
-    if (fast) {
-        launch_plan_fast(t->dev, c, o, workspace, groups, static_cast<hipStream_t>(hip_stream));
-        launch_plan_exact(t->dev, c, o, n_passes, workspace, groups, static_cast<hipStream_t>(hip_stream));
+    PlanCall pc;
+    int rc = plan_prepare(ctx, t, cd, out, false, workspace, workspace_bytes, false, hip_stream, pc);
+    if (rc != HARP_OK || cd->C == 0) return rc;
+    if (pc.fast) {
+        rc = plan_minmax(ctx, t, pc, workspace, nullptr);
+        if (rc != HARP_OK) return rc;
+        launch_plan_exact(t->dev, pc.c, pc.o, n_passes, workspace, pc.groups, pc.st);
     } else {
-        launch_plan_generic_exact(t->dev, c, o, n_passes, workspace, groups, static_cast<hipStream_t>(hip_stream));
+        launch_plan_generic_exact(t->dev, pc.c, pc.o, n_passes, workspace, pc.groups, pc.st);
     }
-    e = hipGetLastError();
+    const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(ctx, e, "launching the exact-search kernels");
     return HARP_OK;
 }
@@ -459,28 +507,13 @@ int harp_plan_exact_batch(harp_ctx *ctx, harp_tables *t, const harp_candidates *
 int harp_plan_h1f1b_batch(harp_ctx *ctx, harp_tables *t, const harp_candidates *cd, const int64_t *t_max,
                           const harp_plans *out, int32_t *warmup, void *workspace, size_t workspace_bytes,
                           void *hip_stream) {
-    int rc = check_batch(ctx, t, cd);
-    if (rc != HARP_OK) return rc;
-    if (!out || (cd->C > 0 && (!out->splits || !out->dev_first || !out->bottleneck || !out->iter_time ||
-                               !out->status || !warmup || !t_max)))
-        return fail(ctx, HARP_ERR_INVALID_ARG, "null array");
-    if (ctx->plan_path == HARP_PATH_FAST32 && !t->fast32)
-        return fail(ctx, HARP_ERR_UNIMPLEMENTED, "the 32-bit path was requested but these tables do not allow it");
-    if (cd->C == 0) return HARP_OK;
-    const size_t need = harp_plan_workspace_bytes(ctx, t, cd);
-    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0)
-        return fail(ctx, HARP_ERR_WORKSPACE, "workspace must be a 256-byte aligned device pointer");
-    if (workspace_bytes < need)
-        return fail(ctx, HARP_ERR_WORKSPACE, "workspace holds %zu bytes, %zu needed", workspace_bytes, need);
-    hipError_t e = hipSetDevice(ctx->device);
-    if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
-    const CandDev c = { cd->C, cd->S_max, cd->cand_S, cd->cand_group, cd->cand_tp };
-    const PlansDev o = { out->splits, out->dev_first, out->bottleneck, out->iter_time, out->status };
-    const bool fast = use_fast(ctx, t);
-    const int groups = n_plan_groups(ctx, cd->C, fast, t->dev.L, cd->S_max);
-    if (fast) launch_plan_h1f1b(t->dev, c, t_max, o, warmup, workspace, groups, static_cast<hipStream_t>(hip_stream));
-    else launch_plan_generic_h1f1b(t->dev, c, t_max, o, warmup, workspace, groups, static_cast<hipStream_t>(hip_stream));
-    e = hipGetLastError();
+    PlanCall pc;
+    const int rc = plan_prepare(ctx, t, cd, out, cd && cd->C > 0 && (!warmup || !t_max), workspace, workspace_bytes,
+                                false, hip_stream, pc);
+    if (rc != HARP_OK || cd->C == 0) return rc;
+    if (pc.fast) launch_plan_h1f1b(t->dev, pc.c, t_max, pc.o, warmup, workspace, pc.groups, pc.st);
+    else launch_plan_generic_h1f1b(t->dev, pc.c, t_max, pc.o, warmup, workspace, pc.groups, pc.st);
+    const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(ctx, e, "launching the H-1F1B planner kernels");
     return HARP_OK;
 }

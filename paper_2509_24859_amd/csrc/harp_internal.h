@@ -85,7 +85,7 @@ void launch_plan_generic_exact(const TablesDev &tb, const CandDev &cd, const Pla
                                void *ws, int n_groups, hipStream_t st);
 size_t plan_generic_ws_per_group(int L, int S_max);
 void launch_plan_fast(const TablesDev &tb, const CandDev &cd, const PlansDev &out, void *ws,
-                      int n_groups, hipStream_t st);
+                      int n_slices, int n_cu, unsigned long long *work, hipStream_t st);
 void launch_plan_prepass(const TablesDev &tb, const CandDev &cd, void *ws, int n_groups, hipStream_t st);
 void launch_plan_h1f1b(const TablesDev &tb, const CandDev &cd, const int64_t *t_max, const PlansDev &out,
                        int32_t *warmup, void *ws, int n_groups, hipStream_t st);
@@ -114,8 +114,13 @@ void launch_plan_mesh_h1f1b_sweep(const TablesDev &tb, const OrdDev &od, const i
 size_t plan_mesh_sweep_slot_bytes(int S_max);
 size_t plan_mesh_ws_per_group(int L, int S_max, int64_t total_devices);
 int plan_mesh_threads(int L, int64_t total_devices, int C, int n_cu);
-size_t plan_fast_ws_bytes(int L, int S_max, int C, int n_groups);
+size_t plan_fast_ws_bytes(const TablesDev &tb, int S_max, int C, int n_slices);
+void launch_clear_work(unsigned long long *work, hipStream_t st);
+size_t plan_fast_index_bytes(const TablesDev &tb, int S_max);
 int plan_fast_groups(int L, int S_max, int n_cu);
+int plan_fast_waves(int L, int S_max, int n_cu);
+constexpr int kFastWaves = 4;           // wavefronts per workgroup of k2_fast; they share nothing
+constexpr size_t kFastIndexLimit = size_t(256) << 20;   // feasibility index of the 32-bit path
 void launch_plan_exact(const TablesDev &tb, const CandDev &cd, const PlansDev &out, int32_t *n_passes,
                        void *ws, int n_groups, hipStream_t st);
 void launch_score(const TablesDev &tb, const CandDev &cd, const int32_t *splits,

@@ -123,7 +123,7 @@ __device__ __forceinline__ void exact_body(const TablesDev &tb, const CandDev &c
                 sc[s].cm_row_shift = uint32_t((int64_t(g) * tb.G + g_next) * tb.pitch32) |
                                      (uint32_t(tb.tp_shift[k]) << 27);
             }
-            for (int s = tid; s <= S; s += nthreads) band[s] = bands[int64_t(s) * cd.C + c];
+            for (int s = tid; s <= S; s += nthreads) band[s] = bands[int64_t(c) * (S_max + 1) + s];
         }
         __syncthreads();
 
@@ -391,7 +391,7 @@ size_t exact_lds_bytes(int L, int S_max, size_t entry) {
 // bands and the min-max results in `out` are its inputs.
 void launch_plan_exact(const TablesDev &tb, const CandDev &cd, const PlansDev &out, int32_t *n_passes,
                        void *ws, int n_groups, hipStream_t st) {
-    const FastWorkspace w = carve(ws, tb.L, cd.S_max, cd.C, n_groups);
+    const FastWorkspace w = carve(ws, fast_shape(tb, cd), n_groups);
     hipLaunchKernelGGL(k2_exact, dim3(n_groups), dim3(kFastThreads), exact_lds_bytes(tb.L, cd.S_max, 8), st, tb,
                        cd, out, n_passes, w.counts, w.live_list, w.dead_list, w.bands, w.arg,
                        fast_arg_per_group(tb.L, cd.S_max), fast_row_len(tb.L));

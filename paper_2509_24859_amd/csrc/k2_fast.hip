@@ -1,4 +1,5 @@
-// Fast planner-search kernels for gfx950: reachability bands, 32-bit times, bounded scans, rows in LDS.
+// Fast planner-search kernels for gfx950: reachability bands, a feasibility index, 32-bit times,
+// bounded scans, one wavefront per candidate with its rows in LDS.
 //
 // Same recurrence as the generic kernel (paper section 5.2.3, eq. dp_general with the submesh of
 // each stage fixed by the candidate; constraints (i)-(iii)), same results bit for bit, but the
@@ -15,12 +16,19 @@
 //    B[0] > 0, or F[S] < L proves the candidate infeasible before any DP work.  (The bands are
 //    bounds, not exact sets: a candidate whose band is non-empty can still turn out infeasible,
 //    which the DP then reports.)  k2_band computes the two chains with one thread per candidate.
+//  * lo(s, i) depends on the stage only through its in-flight count n = min(S - s, M) and the memory
+//    of its submesh, tp devices of one GPU type.  The pre-pass therefore also writes a feasibility
+//    index of stage ranges per (count, GPU type, degree) into the workspace, once per call (the
+//    precomputed index of feasible stage-mesh pairs of section 5.2.4 (1), reduced to what this
+//    device model needs: one lower limit per end cut): row (n, type, k), entry i = the lowest j such
+//    that operators [j, i) fit.  A DP cell then knows its range of previous cuts from one 16-bit
+//    load, and the recurrence itself touches no byte count at all.
 //  * the stage time time(s; j, i) never decreases when j moves down.  Scanning j downwards from
 //    i-1, once time(s; j, i) exceeds the best value found so far no lower j can match or beat it,
 //    and the scan stops.  The stop uses a strict comparison and the update a non-strict one, so
 //    the lowest j among equal values is kept, as the recurrence demands.  Nothing is assumed
 //    about the previous DP row (it is not monotone when transfer times dominate); in the worst
-//    case the scan covers the whole band.
+//    case the scan covers the whole range.
 //
 // With tp a power of two and every time below 2^31 us (both checked by the table build), the
 // stage time is one subtraction and one shift on the fused 32-bit row
@@ -28,17 +36,19 @@
 // because ceil(a / tp) + b = ceil((a + tp b) / tp) for integers.  Transfer times come from the
 // per-link cut table built beside the rows.
 //
-// Mapping of k2_fast: one workgroup per live candidate at a time (persistent workgroups draw
-// from the list k2_band compacted through a shared counter), one lane per DP cell of the current stage's band (more trips
-// when the band is wider than the workgroup), lanes of a wave on consecutive cells so that LDS
-// reads of (D[j], P[j]) pairs are stride-1 or broadcast.  The previous DP row and the slot's P row
-// sit interleaved in LDS so that one 8-byte read feeds a transition.  What stage s+1 needs from
-// global memory (its slot's P row, the memory row, the cell's own cut time) is requested at the
-// top of stage s, lands in registers while stage s scans, and is committed to the other LDS buffer
-// before the single LDS-only barrier that ends the stage.  Values that are the same for the whole
-// workgroup are moved to scalar registers so that addressing runs on the scalar unit.  The lone
-// cell of the last stage is reduced across a wavefront with a lexicographic (value, j) minimum.
-// Back-pointers go to a per-workgroup slice of the caller's workspace as uint16.
+// Mapping of k2_fast: one wavefront per live candidate at a time (persistent wavefronts draw from
+// the list k2_band compacted through a shared counter; the wavefronts of a workgroup share nothing
+// and never meet at a barrier), one lane per DP cell of the current stage's band, 64 cells per
+// chunk.  The DP row and the stage's fused time row sit interleaved in LDS, one 8-byte entry per
+// cut, in a single buffer: chunks are taken from the top of the band downwards and a cell only
+// reads cuts below itself, so writing the new row over the old one never destroys a value that is
+// still needed, and the time row of the next stage replaces the current one once the stage is done
+// (its entries were requested from global memory before the stage's scans and wait in registers).
+// Previous cuts are scanned four per trip; a trip keeps the least of its four values and its own
+// position, and the lowest cut inside the winning trip is found once per cell afterwards.
+// Back-pointers are one byte each (distance to the previous cut) in an LDS arena while the
+// candidate's rows fit there, 16-bit in a per-wavefront slice of the workspace beyond that, so the
+// backtrack of most candidates never leaves the CU.
 #include "harp_internal.h"
 #include "fast_common.h"
 #include "plan_common.h"
@@ -59,18 +69,55 @@ namespace {
 // so everything the loops touch is staged in LDS first: the running sums PP and PS, the memory
 // cap of every (group, degree), and the workgroup's slot lists, read from global memory once,
 // coalesced, and stored slot-major so that the per-thread walks are conflict-free.  Bands are
-// written slot-major as well ([s][c]), which keeps the writes of a wave contiguous.
+// written candidate-major ([c][s]): the wavefront that later plans candidate c reads its row with
+// one coalesced load.
+//
+// The workgroups behind the candidates' ones build the feasibility index, one row each.
 constexpr int kBandCapTable = 1024;     // caps kept in LDS when G * n_tp is at most this
 constexpr uint16_t kBadSlot = 0xFFFFu;
 
 int band_threads(int S_max) { return S_max <= 64 ? 256 : (S_max <= 128 ? 128 : 64); }
 
+// One row of the feasibility index: for in-flight count n, GPU type t, degree index k and every cut
+// i, the lowest j with (PP[i] - PP[j]) + n (PS[i] - PS[j]) <= tp_k * type_mem[t].  The need is
+// monotone in j, so a binary search over the running sums finds it.
+__device__ __forceinline__ void lo_row(const TablesDev &tb, int row, int rows_per_n, uint16_t *lo_tab,
+                                       int pitch, int64_t *Q) {
+    const int L = tb.L;
+    const int n = row / rows_per_n + 1;
+    const int tk = row - (n - 1) * rows_per_n;
+    const int t = tk / tb.n_tp, k = tk - t * tb.n_tp;
+    const int64_t cap = int64_t(tb.tp[k]) * tb.type_mem[t];
+    const int64_t *gp = tb.PP(), *gs = tb.PS();
+    for (int i = threadIdx.x; i <= L; i += blockDim.x) Q[i] = gp[i] + int64_t(n) * gs[i];
+    __syncthreads();
+    uint16_t *dst = lo_tab + size_t(row) * pitch;
+    for (int i = threadIdx.x; i <= L; i += blockDim.x) {
+        const int64_t th = Q[i] - cap;
+        int a = -1, b = i;                      // Q[b] >= th holds at b = i; Q[a] < th (a = -1: none)
+        while (b - a > 1) {
+            const int m = (a + b) >> 1;
+            if (Q[m] >= th) b = m; else a = m;
+        }
+        dst[i] = (uint16_t)b;
+    }
+}
+
 __global__ __launch_bounds__(256) void k2_band(TablesDev tb, CandDev cd, int *counts, int32_t *live_list,
-                                               uint32_t *dead_list, uint32_t *bands, int caps_in_lds) {
+                                               uint32_t *dead_list, uint32_t *bands, int caps_in_lds,
+                                               int n_band_groups, uint16_t *lo_tab, int lo_pitch_e,
+                                               int lo_rows) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     const int L = tb.L, S_max = cd.S_max, C = cd.C;
     const int nthreads = blockDim.x, pitch = nthreads + 2;
     int64_t *PP = reinterpret_cast<int64_t *>(lds_raw);      // [L + 1]
+    if ((int)blockIdx.x >= n_band_groups) {
+        for (int row = blockIdx.x - n_band_groups; row < lo_rows; row += gridDim.x - n_band_groups) {
+            __syncthreads();
+            lo_row(tb, row, tb.T * tb.n_tp, lo_tab, lo_pitch_e, PP);
+        }
+        return;
+    }
     int64_t *PS = PP + (L + 1);                              // [L + 1]
     int64_t *caps = PS + (L + 1);                            // [G * n_tp] when caps_in_lds
     uint16_t *slots = reinterpret_cast<uint16_t *>(caps + (caps_in_lds ? tb.G * tb.n_tp : 0));  // [S_max][pitch]
@@ -99,6 +146,7 @@ __global__ __launch_bounds__(256) void k2_band(TablesDev tb, CandDev cd, int *co
     if (c >= C) return;
     const int S = cd.cand_S[c];
     const int R = L - S + 1;
+    uint32_t *my = bands + int64_t(c) * (S_max + 1);
     auto cap_of = [&](int g, int k) -> int64_t {
         return caps_in_lds ? caps[g * tb.n_tp + k] : int64_t(tb.tp[k]) * tb.type_mem[tb.group_type[g]];
     };
@@ -111,7 +159,7 @@ __global__ __launch_bounds__(256) void k2_band(TablesDev tb, CandDev cd, int *co
     int64_t used = 0;
     unsigned long long seen = 0;                      // groups already entered, when G <= 64
     int prev_g = -1, F = 0;
-    if (status == HARP_CAND_OK) bands[c] = 0;
+    if (status == HARP_CAND_OK) my[0] = 0;
     for (int s = 0; status == HARP_CAND_OK && s < S; ++s) {
         const uint16_t code = slots[s * pitch + cl];
         if (code == kBadSlot) { status = HARP_CAND_INVALID; break; }
@@ -142,13 +190,13 @@ __global__ __launch_bounds__(256) void k2_band(TablesDev tb, CandDev cd, int *co
             }
             F = a;
             if (F < s + 1 || (s == S - 1 && F != L)) feasible = false;
-            else bands[int64_t(s + 1) * C + c] = uint32_t(F) << 16;
+            else my[s + 1] = uint32_t(F) << 16;
         }
     }
     // backward chain: B[s] = smallest cut from which stage s can reach B[s+1]
     if (status == HARP_CAND_OK && feasible) {
         int B = L;
-        bands[int64_t(S) * C + c] |= uint32_t(L);
+        my[S] |= uint32_t(L);
         for (int s = S - 1; s >= 0; --s) {
             const uint16_t code = slots[s * pitch + cl];
             const int64_t n = (S - s) < tb.M ? (S - s) : tb.M;
@@ -161,10 +209,9 @@ __global__ __launch_bounds__(256) void k2_band(TablesDev tb, CandDev cd, int *co
                 if (qb - (PP[m] + n * PS[m]) <= cap) b = m; else a = m;
             }
             B = b;
-            uint32_t *w = bands + int64_t(s) * C + c;
-            const int hi = band_hi(*w);
+            const int hi = band_hi(my[s]);
             if (hi < B || (s == 0 && B != 0)) { feasible = false; break; }
-            *w = uint32_t(B) | (uint32_t(hi) << 16);
+            my[s] = uint32_t(B) | (uint32_t(hi) << 16);
         }
     }
     if (status == HARP_CAND_OK && !feasible) status = HARP_CAND_INFEASIBLE;
@@ -187,259 +234,427 @@ __global__ __launch_bounds__(256) void k2_band(TablesDev tb, CandDev cd, int *co
 }
 
 __global__ void k2_clear_count(int *counts) {
-    if (threadIdx.x < 8) counts[threadIdx.x] = 0;
+    if (threadIdx.x < 32) counts[threadIdx.x] = 0;
 }
 
-__global__ __launch_bounds__(kFastThreads) __attribute__((amdgpu_waves_per_eu(8, 8)))
-void k2_fast(TablesDev tb, CandDev cd, PlansDev out, int *counts, const int32_t *live_list,
-             const uint32_t *dead_list, const uint32_t *bands, unsigned char *arg_base, size_t arg_per_group,
-             int row_len) {
+__global__ void k2_clear_work(unsigned long long *work) {
+    if (threadIdx.x < 4) work[threadIdx.x] = 0;
+}
+
+// ---------------------------------------------------------------------------------- k2_fast
+
+constexpr int kPrefetchChunks = 4;      // chunks of the next stage's time row held in registers
+constexpr int kArgEscape = 255;         // one-byte back-pointer: distance too long, see the slice
+
+// wavefront-scope ordering of LDS traffic: one wavefront's LDS operations execute in order, so
+// this only keeps the compiler from moving accesses across the phases of a stage
+__device__ __forceinline__ void wave_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+__device__ __forceinline__ uint32_t umin2(uint32_t a, uint32_t b) { return a < b ? a : b; }
+
+struct FastArgs {
+    const uint32_t *bands;        // [C][S_max + 1]
+    const uint16_t *lo_tab;       // feasibility index
+    unsigned char *arg_base;      // back-pointer slices
+    size_t arg_per_wave;
+    unsigned long long *work;     // [4] transitions, cells, trips, candidates (counting build only)
+    int lo_pitch, row_len, lds_per_wave, arena_bytes;
+    uint32_t shift_packed;        // log2 of degree k in bits 4k .. 4k+3
+};
+
+// per-wavefront LDS slice: rows [row_len] | band [S_max+1] | slot [S_max] | aoff [S_max+1] |
+// cuts [S_max+1] | arena [arena_bytes]
+__host__ __device__ inline size_t fast_wave_fixed_bytes(int row_len, int S_max) {
+    return size_t(row_len) * sizeof(Pair) + size_t(S_max + 1) * 12 + size_t(S_max) * 4;
+}
+
+template <bool kCount>
+__global__ __launch_bounds__(kFastWaves * 64) void k2_fast(TablesDev tb, CandDev cd, PlansDev out, int *counts,
+                                                            const int32_t *live_list,
+                                                            const uint32_t *dead_list, FastArgs fa) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
 
     const int L = tb.L, S_max = cd.S_max;
-    const int tid = threadIdx.x, lane = tid & 63, nthreads = blockDim.x;
-    const int wave = uniform(tid >> 6);
-    // every LDS row has kPad spare entries in front, so that the group of four previous cuts
-    // ending at any j >= 0 can be read at fixed offsets without clamping
-    int64_t *Qb = reinterpret_cast<int64_t *>(lds_raw) + kPad;                        // [2][row_len]
-    Pair *rows = reinterpret_cast<Pair *>(lds_raw + size_t(row_len) * 16) + kPad;     // [2][row_len]
-    StageConst *sc = reinterpret_cast<StageConst *>(lds_raw + size_t(row_len) * 32);  // [S_max]
-    uint32_t *ticket = reinterpret_cast<uint32_t *>(sc + S_max);                       // [1]
-    uint32_t *band = ticket + 1;                                                       // [S_max + 1]
-    uint16_t *slot_g = reinterpret_cast<uint16_t *>(band + S_max + 1);                 // [S_max]
-    uint8_t *slot_k = reinterpret_cast<uint8_t *>(slot_g + S_max);                     // [S_max]
-    uint16_t *arg = reinterpret_cast<uint16_t *>(arg_base + size_t(blockIdx.x) * arg_per_group);
-    const int64_t *PP = tb.PP(), *PS = tb.PS();
+    const int lane = threadIdx.x & 63;
+    const int wave = uniform(threadIdx.x >> 6);
+    const int wave_id = blockIdx.x * kFastWaves + wave, n_waves = gridDim.x * kFastWaves;
+    unsigned char *mine = lds_raw + size_t(wave) * fa.lds_per_wave;
+    Pair *rows = reinterpret_cast<Pair *>(mine) + kPad;                                // [row_len]
+    uint32_t *band = reinterpret_cast<uint32_t *>(mine + size_t(fa.row_len) * sizeof(Pair));   // [S_max + 1]
+    uint32_t *slot = band + (S_max + 1);                                               // [S_max]
+    uint32_t *aoff = slot + S_max;                                                     // [S_max + 1]
+    int32_t *cuts = reinterpret_cast<int32_t *>(aoff + (S_max + 1));                   // [S_max + 1]
+    uint8_t *arena = reinterpret_cast<uint8_t *>(cuts + (S_max + 1));                  // [arena_bytes]
+    uint16_t *slice = reinterpret_cast<uint16_t *>(fa.arg_base + size_t(wave_id) * fa.arg_per_wave);
     const int n_live = counts[0], n_dead = counts[1];
     int *next_item = counts + 5;
-    const int64_t m_cap = tb.M;
+    const int m_cap = tb.M;
+    const int rows_per_n = tb.T * tb.n_tp;
+    unsigned long long n_trans = 0, n_cells = 0, n_trips = 0, n_cands = 0;
 
-    // candidates differ in stages and band widths, so workgroups draw them from a shared counter
+    // scalars of one stage, from the packed slot word  g | k << 12 | type << 16
+    struct Stage {
+        const uint32_t *p_row, *cm_row;
+        const uint16_t *lo;
+        int shift;
+    };
+    auto stage_of = [&](int s, int S) -> Stage {
+        const uint32_t w = (uint32_t)uniform((int)slot[s]);
+        const uint32_t wn = (uint32_t)uniform((int)slot[s + 1 < S ? s + 1 : s]);
+        const int g = int(w & 0xFFFu), k = int((w >> 12) & 7u), t = int(w >> 16);
+        const int gn = int(wn & 0xFFFu);
+        const int n = (S - s) < m_cap ? (S - s) : m_cap;
+        Stage st;
+        st.p_row = tb.P32 + (int64_t(g) * tb.n_tp + k) * tb.pitch32;
+        st.cm_row = tb.CM + (int64_t(g) * tb.G + gn) * tb.pitch32;
+        st.lo = fa.lo_tab + (int64_t(n - 1) * rows_per_n + t * tb.n_tp + k) * fa.lo_pitch;
+        st.shift = int((fa.shift_packed >> (4 * k)) & 15u);
+        return st;
+    };
+
+    // candidates differ in stages and band widths, so wavefronts draw them from a shared counter
     for (;;) {
-        __syncthreads();   // the previous candidate's tail has finished with LDS
-        if (tid == 0) *ticket = (uint32_t)atomicAdd(next_item, 1);
-        __syncthreads();
-        const int n = uniform((int)*ticket);
+        // Every lane takes part in the draw (only the first adds one).  A draw under `if (lane == 0)`
+        // would sit right behind the lane-0 stores that end the previous candidate; the compiler
+        // joins two such branches, and the other lanes then reach the broadcast below on their own,
+        // ahead of lane 0 and without a ticket.
+        wave_sync();
+        const int n = uniform(atomicAdd(next_item, lane == 0 ? 1 : 0));
         if (n >= n_live) break;
-        const int c = live_list[n];
-        const int S = cd.cand_S[c];
+        const int c = uniform(live_list[n]);
+        const int S = uniform(cd.cand_S[c]);
+        wave_sync();              // the previous candidate's tail has finished with LDS
         {
             const int32_t *grp = cd.cand_group + int64_t(c) * S_max;
             const int32_t *tpv = cd.cand_tp + int64_t(c) * S_max;
             int32_t *df = out.dev_first + int64_t(c) * S_max;
-            for (int s = tid; s < S; s += nthreads) {
+            const uint32_t *bd = fa.bands + int64_t(c) * (S_max + 1);
+            for (int s = lane; s < S; s += 64) {
                 const int g = grp[s], k = tp_index(tb, tpv[s]);
-                const int g_next = s + 1 < S ? grp[s + 1] : g;
-                slot_g[s] = (uint16_t)g;
-                slot_k[s] = (uint8_t)k;
-                sc[s].cap = int64_t(tb.tp[k]) * tb.type_mem[tb.group_type[g]];
-                sc[s].p_row = uint32_t((int64_t(g) * tb.n_tp + k) * tb.pitch32);
-                sc[s].cm_row_shift = uint32_t((int64_t(g) * tb.G + g_next) * tb.pitch32) |
-                                     (uint32_t(tb.tp_shift[k]) << 27);
+                slot[s] = uint32_t(g) | (uint32_t(k) << 12) | (uint32_t(tb.group_type[g]) << 16);
                 // first device of the slot: its group's base plus the degrees of the group's
                 // earlier slots (they are adjacent; the pre-pass has checked that)
                 int32_t first = tb.group_base[g];
                 for (int q = s - 1; q >= 0 && grp[q] == g; --q) first += tpv[q];
                 df[s] = first;
             }
-            for (int s = S + tid; s < S_max; s += nthreads) df[s] = -1;
-            for (int s = tid; s <= S; s += nthreads) band[s] = bands[int64_t(s) * cd.C + c];
-        }
-        __syncthreads();
-        int32_t *sp = out.splits + int64_t(c) * (S_max + 1);
-        bool dead = false;
-        if (S >= 2) {
-            // prologue: rows of stage 0 over [0, F[1]] and the thread's own cut time of stage 0
-            uint32_t cut_i = 0;
-            {
-                const uint32_t *p32 = tb.P32 + (uint32_t)uniform((int)sc[0].p_row);
-                const uint32_t *cm = tb.CM + ((uint32_t)uniform((int)sc[0].cm_row_shift) & kRowMask);
-                const int64_t n0 = S < m_cap ? S : m_cap;
-                const uint32_t b1 = (uint32_t)uniform((int)band[1]);
-                for (int j = tid; j <= band_hi(b1); j += nthreads) {
-                    rows[j].p = p32[j];
-                    Qb[j] = PP[j] + n0 * PS[j];
+            for (int s = S + lane; s < S_max; s += 64) df[s] = -1;
+            // bands, and where the back-pointers of each stage start: running sum of the widths of
+            // rows 1 .. S-1 (the last row has the single cell L, kept in a register)
+            uint32_t carry = 0;
+            for (int s0 = 0; s0 <= S; s0 += 64) {
+                const int s = s0 + lane;
+                uint32_t b = 0, wdt = 0;
+                if (s <= S) { b = bd[s]; band[s] = b; }
+                if (s >= 1 && s < S) wdt = uint32_t(band_hi(b) - band_lo(b) + 1);
+                uint32_t inc = wdt;
+#pragma unroll
+                for (int d = 1; d < 64; d <<= 1) {
+                    const uint32_t o = __shfl_up(inc, d, 64);
+                    if (lane >= d) inc += o;
                 }
-                if (band_lo(b1) + tid <= band_hi(b1)) cut_i = cm[band_lo(b1) + tid];
-                if (tid < 3) rows[-1 - tid].d = kInf32;   // below cut 0: never a predecessor
-                if (tid == 0) rows[0].d = 0;
+                // aoff[s - 1] = offset of stage s - 1, whose cells are row s
+                if (s >= 1 && s <= S) aoff[s - 1] = carry + inc - wdt;
+                carry += __shfl(inc, 63, 64);
             }
-            lds_barrier();
+        }
+        wave_sync();
+        int32_t *sp = out.splits + int64_t(c) * (S_max + 1);
+        uint32_t final_v = 0;
+        if (S >= 2) {
+            // prologue: time row of stage 0 over [0, F[1]]; row 0 of the DP is the single cut 0
+            Stage cur = stage_of(0, S);
+            {
+                const int top = band_hi((uint32_t)uniform((int)band[1]));
+                for (int j = lane; j <= top; j += 64) rows[j].p = cur.p_row[j];
+                if (lane == 0) rows[0].d = 0;
+            }
+            // first work item: the top chunk of stage 0
+            uint32_t cut_c = 0;
+            int lo_c = 0;
+            {
+                const uint32_t b1 = (uint32_t)uniform((int)band[1]);
+                const int il = band_lo(b1), ih = band_hi(b1);
+                const int i = il + ((ih - il) & ~63) + lane;
+                if (i <= ih) { cut_c = cur.cm_row[i]; lo_c = cur.lo[i]; }
+            }
+            wave_sync();
 
-            int cur = 0;
-            const int wave_first = wave * 64;
             for (int s = 0; s < S - 1; ++s) {
+                const uint32_t b0 = (uint32_t)uniform((int)band[s]);
                 const uint32_t b1 = (uint32_t)uniform((int)band[s + 1]);
                 const uint32_t b2 = (uint32_t)uniform((int)band[s + 2]);
-                const int il = band_lo(b1), ih = band_hi(b1);     // cells: row s + 1
-                const int top_n = band_hi(b2);                    // stage s+1 reads its rows up to here
-                // a wave whose lanes own neither a cell nor a staged entry only keeps the barrier
-                if (il + wave_first > top_n && wave != 0) {
-                    lds_barrier();
-                    cur ^= 1;
-                    continue;
-                }
-                const uint32_t rs = (uint32_t)uniform((int)sc[s].cm_row_shift);
-                const int shift = int(rs >> 27);
-                const uint32_t tp = 1u << shift;
-                const int64_t cap = uniform64(sc[s].cap);
-                const uint32_t b0 = (uint32_t)uniform((int)band[s]);
                 const int jl = band_lo(b0), jh = band_hi(b0);     // predecessors: row s
-                const uint32_t *cm_s = tb.CM + (rs & kRowMask);
-                const Pair *prev = rows + cur * row_len;
-                Pair *next = rows + (cur ^ 1) * row_len;
-                const int64_t *Q = Qb + cur * row_len;
-                int64_t *Qn = Qb + (cur ^ 1) * row_len;
-                const uint32_t *p32_n = tb.P32 + (uint32_t)uniform((int)sc[s + 1].p_row);
-                const uint32_t *cm_n = tb.CM + ((uint32_t)uniform((int)sc[s + 1].cm_row_shift) & kRowMask);
-                const bool next_has_cut = s + 2 < S;
+                const int il = band_lo(b1), ih = band_hi(b1);     // cells: row s + 1
+                const int top_n = band_hi(b2);                    // stage s+1 reads its time row up to here
+                const int shift = cur.shift;
+                const uint32_t tp = 1u << shift;
+                const Stage nxt = stage_of(s + 1, S);
+                const bool nxt_is_last = s + 2 == S;
+                const uint32_t a0 = (uint32_t)uniform((int)aoff[s]);
+                const bool arg_in_lds = a0 + uint32_t(ih - il + 1) <= uint32_t(fa.arena_bytes);
 
-                // requests for stage s+1: entry jn of its rows, and this thread's own cut time
-                const int jn = il + tid;
-                uint32_t p_n = 0, cut_n = 0;
-                int64_t pp_n = 0, ps_n = 0;
-                if (jn <= top_n) { p_n = p32_n[jn]; pp_n = PP[jn]; ps_n = PS[jn]; }
-                if (next_has_cut && band_lo(b2) + tid <= top_n) cut_n = cm_n[band_lo(b2) + tid];
+                // requests for the time row of stage s+1: entries [il, top_n], first chunks in registers
+                uint32_t pn[kPrefetchChunks];
+#pragma unroll
+                for (int q = 0; q < kPrefetchChunks; ++q) {
+                    const int j = il + q * 64 + lane;
+                    pn[q] = j <= top_n ? nxt.p_row[j] : 0u;
+                }
 
-                // One DP cell: scan the fitting previous cuts of the band downwards, four per trip.
-                // Fitting cuts are j >= lo with Q[lo] >= Q[i] - cap (memory need is monotone in
-                // j), so an entry counts while its Q passes the threshold, a plain predicate;
-                // entries below the band hold D = infinity and never win.  Entries below a stop
-                // cannot update (their time exceeds the best value), so only the last entry of a
-                // trip decides whether the lane goes on.  Returns the back-pointer.
-                auto cell = [&](int i, uint32_t cut) -> int {
-                    const int64_t th = Q[i] - cap;
-                    const uint32_t xi = prev[i].p + tp - 1;
+                for (int q = (ih - il) >> 6; q >= 0; --q) {
+                    const int i = il + q * 64 + lane;
+                    // requests for the next work item: the chunk below, or the top chunk of the next stage
+                    uint32_t cut_n = 0;
+                    int lo_n = 0;
+                    if (q > 0) {
+                        cut_n = cur.cm_row[i - 64];
+                        lo_n = cur.lo[i - 64];
+                    } else if (!nxt_is_last) {
+                        const int i2l = band_lo(b2);
+                        const int i2 = i2l + ((top_n - i2l) & ~63) + lane;
+                        if (i2 <= top_n) { cut_n = nxt.cm_row[i2]; lo_n = nxt.lo[i2]; }
+                    }
+
+                    // One DP cell: the previous cuts that fit are lo .. hi; four per trip, downwards.
+                    // A trip keeps the least of its four values; ties between trips go to the lower
+                    // one.  Entries below a stop cannot match the best value (their stage time alone
+                    // exceeds it), so only the last entry of a trip decides whether the lane goes on.
                     uint32_t best = kInf32;
                     int best_j = 0;
-                    int j = (i - 1) < jh ? (i - 1) : jh;
-                    bool more = j >= jl;
-                    while (more) {
-                        const Pair *pe = prev + (j - 3);
-                        const int64_t *pq = Q + (j - 3);
-                        const Pair e3 = pe[0], e2 = pe[1], e1 = pe[2], e0 = pe[3];
-                        const int64_t q3 = pq[0], q2 = pq[1], q1 = pq[2], q0 = pq[3];
-                        uint32_t tj;
-#define HARP_STEP(E, QV, JJ)                                                   \
-    {                                                                          \
-        tj = (xi - (E).p) >> shift;                                            \
-        const uint32_t v = umax3((E).d, tj, cut);                              \
-        const bool upd = ((QV) >= th) & (v <= best);                           \
-        best = upd ? v : best;                                                 \
-        best_j = upd ? (JJ) : best_j;                                          \
-    }
-                        HARP_STEP(e0, q0, j)
-                        HARP_STEP(e1, q1, j - 1)
-                        HARP_STEP(e2, q2, j - 2)
-                        HARP_STEP(e3, q3, j - 3)
-#undef HARP_STEP
-                        more = ((j - 3) > jl) & (q3 >= th) & (tj <= best);
-                        j -= 4;
+                    if (i <= ih) {
+                        const int hi = (i - 1) < jh ? (i - 1) : jh;
+                        const int lo = lo_c > jl ? lo_c : jl;
+                        const uint32_t xi = rows[i].p + tp - 1;
+                        const uint32_t cut = cut_c;
+                        int bt = hi;
+                        int j = hi;
+                        while (j - 3 >= lo) {
+                            const Pair *pe = rows + (j - 3);
+                            const Pair e3 = pe[0], e2 = pe[1], e1 = pe[2], e0 = pe[3];
+                            const uint32_t t3 = (xi - e3.p) >> shift;
+                            const uint32_t v0 = umax3(e0.d, (xi - e0.p) >> shift, cut);
+                            const uint32_t v1 = umax3(e1.d, (xi - e1.p) >> shift, cut);
+                            const uint32_t v2 = umax3(e2.d, (xi - e2.p) >> shift, cut);
+                            const uint32_t v3 = umax3(e3.d, t3, cut);
+                            const uint32_t m = umin2(umin2(v0, v1), umin2(v2, v3));
+                            const bool upd = m <= best;
+                            best = upd ? m : best;
+                            bt = upd ? j : bt;
+                            if (kCount) { n_trans += 4; ++n_trips; }
+                            j = t3 > best ? lo - 1 : j - 4;
+                        }
+                        // what is left of the range: at most three cuts, j .. lo
+                        {
+                            const Pair *pe = rows + (j - 3);
+                            const Pair e2 = pe[1], e1 = pe[2], e0 = pe[3];
+                            const uint32_t v0 = j >= lo ? umax3(e0.d, (xi - e0.p) >> shift, cut) : kInf32;
+                            const uint32_t v1 = j - 1 >= lo ? umax3(e1.d, (xi - e1.p) >> shift, cut) : kInf32;
+                            const uint32_t v2 = j - 2 >= lo ? umax3(e2.d, (xi - e2.p) >> shift, cut) : kInf32;
+                            const uint32_t m = umin2(umin2(v0, v1), v2);
+                            const bool upd = (m <= best) & (j >= lo);
+                            best = upd ? m : best;
+                            bt = upd ? j : bt;
+                            if (kCount) { n_trans += j >= lo ? uint32_t(j - lo + 1) : 0u; n_trips += j >= lo; ++n_cells; }
+                        }
+                        // the lowest cut of the winning trip that attains the best value
+                        {
+                            const Pair *pw = rows + (bt - 3);
+                            const Pair w3 = pw[0], w2 = pw[1], w1 = pw[2];
+                            const uint32_t u1 = umax3(w1.d, (xi - w1.p) >> shift, cut);
+                            const uint32_t u2 = umax3(w2.d, (xi - w2.p) >> shift, cut);
+                            const uint32_t u3 = umax3(w3.d, (xi - w3.p) >> shift, cut);
+                            best_j = bt;
+                            best_j = ((u1 == best) & (bt - 1 >= lo)) ? bt - 1 : best_j;
+                            best_j = ((u2 == best) & (bt - 2 >= lo)) ? bt - 2 : best_j;
+                            best_j = ((u3 == best) & (bt - 3 >= lo)) ? bt - 3 : best_j;
+                            best_j = best == kInf32 ? i - 1 : best_j;      // no previous cut fits: any value
+                        }
                     }
-                    next[i].d = best;
-                    return best_j;
-                };
-                const int i0 = il + tid;
-                int first_j = 0;
-                if (i0 <= ih) first_j = cell(i0, cut_i);
-                // a band wider than the workgroup takes more trips; their cut times come straight
-                // from the table
-                for (int i = i0 + nthreads; i <= ih; i += nthreads)
-                    arg[s * row_len + i] = (uint16_t)cell(i, cm_s[i]);
-                if (tid < 3) next[il - 1 - tid].d = kInf32;     // below the band of row s + 1
+                    wave_sync();      // every lane has read what it needs of the old row
+                    if (i <= ih) {
+                        rows[i].d = best;
+                        const int rel = i - 1 - best_j;
+                        const uint32_t at = a0 + uint32_t(i - il);
+                        if (arg_in_lds) {
+                            arena[at] = (uint8_t)(rel < kArgEscape ? rel : kArgEscape);
+                            if (rel >= kArgEscape) slice[at] = (uint16_t)best_j;
+                        } else {
+                            slice[at] = (uint16_t)best_j;
+                        }
+                    }
+                    wave_sync();
+                    cut_c = cut_n;
+                    lo_c = lo_n;
+                }
 
-                // commit the staged entries of stage s+1, then let the back-pointer go
-                const int64_t n1 = (S - s - 1) < m_cap ? (S - s - 1) : m_cap;
-                if (jn <= top_n) {
-                    next[jn].p = p_n;
-                    Qn[jn] = pp_n + n1 * ps_n;
+                // the time row of stage s+1 takes the place of this stage's
+#pragma unroll
+                for (int q = 0; q < kPrefetchChunks; ++q) {
+                    const int j = il + q * 64 + lane;
+                    if (j <= top_n) rows[j].p = pn[q];
                 }
-                for (int j = jn + nthreads; j <= top_n; j += nthreads) {
-                    next[j].p = p32_n[j];
-                    Qn[j] = PP[j] + n1 * PS[j];
-                }
-                // the cut time requested above must have landed before the next stage issues its own
-                // requests: vector memory returns in order, so a wait placed at its first use inside
-                // the next scan would also wait for those
-                asm volatile("" : "+v"(cut_n));
-                cut_i = cut_n;
-                if (i0 <= ih) arg[s * row_len + i0] = (uint16_t)first_j;
-                lds_barrier();
-                cur ^= 1;
+                for (int j = il + kPrefetchChunks * 64 + lane; j <= top_n; j += 64) rows[j].p = nxt.p_row[j];
+                wave_sync();
+                cur = nxt;
             }
             // the last stage has the single cell i = L: lanes over j, lexicographic reduction
+            int last_j;
             {
                 const int s = S - 1;
-                if (wave == 0) {
-                    const int shift = int((uint32_t)uniform((int)sc[s].cm_row_shift) >> 27);
-                    const uint32_t tp = 1u << shift;
-                    const int64_t cap = uniform64(sc[s].cap);
-                    const uint32_t b0 = (uint32_t)uniform((int)band[s]);
-                    const Pair *prev = rows + cur * row_len;
-                    const int64_t *Q = Qb + cur * row_len;
-                    const int64_t th = Q[L] - cap;
-                    const uint32_t xi = prev[L].p + tp - 1;
-                    const int hi = (L - 1) < band_hi(b0) ? (L - 1) : band_hi(b0);
-                    uint32_t best = kInf32;
-                    int best_j = INT32_MAX;
-                    for (int j = band_lo(b0) + lane; j <= hi; j += 64) {
-                        if (Q[j] < th) continue;
-                        const Pair e = prev[j];
-                        const uint32_t tj = (xi - e.p) >> shift;
-                        const uint32_t v = e.d > tj ? e.d : tj;
-                        if (v < best) { best = v; best_j = j; }   // j rises within a lane
-                    }
-#pragma unroll
-                    for (int d = 32; d >= 1; d >>= 1) {
-                        const uint32_t ov = __shfl_xor(best, d, 64);
-                        const int oj = __shfl_xor(best_j, d, 64);
-                        if (ov < best || (ov == best && oj < best_j)) { best = ov; best_j = oj; }
-                    }
-                    if (lane == 0) arg[s * row_len + L] = (uint16_t)(best == kInf32 ? 0xFFFFu : best_j);
+                const uint32_t b0 = (uint32_t)uniform((int)band[s]);
+                const int shift = cur.shift;
+                const uint32_t xi = rows[L].p + (1u << shift) - 1;
+                const int lo_L = uniform((int)cur.lo[L]);
+                const int lo = lo_L > band_lo(b0) ? lo_L : band_lo(b0);
+                const int hi = (L - 1) < band_hi(b0) ? (L - 1) : band_hi(b0);
+                uint32_t best = kInf32;
+                int best_j = INT32_MAX;
+                for (int j = lo + lane; j <= hi; j += 64) {
+                    const Pair e = rows[j];
+                    const uint32_t tj = (xi - e.p) >> shift;
+                    const uint32_t v = e.d > tj ? e.d : tj;
+                    if (v < best) { best = v; best_j = j; }   // j rises within a lane
+                    if (kCount) ++n_trans;
                 }
-                __syncthreads();          // back-pointers of every wave are visible to thread 0
-                if (arg[s * row_len + L] == 0xFFFFu) dead = true;   // L <= 1024, so no cut has this value
+                if (kCount && lane == 0) { ++n_cells; ++n_cands; }
+#pragma unroll
+                for (int d = 32; d >= 1; d >>= 1) {
+                    const uint32_t ov = __shfl_xor(best, d, 64);
+                    const int oj = __shfl_xor(best_j, d, 64);
+                    if (ov < best || (ov == best && oj < best_j)) { best = ov; best_j = oj; }
+                }
+                final_v = (uint32_t)uniform((int)best);
+                last_j = uniform(best_j);
             }
-            if (!dead && tid == 0) {
-                int b = L;
-                sp[S] = L;
-                for (int s = S - 1; s >= 0; --s) { b = arg[s * row_len + b]; sp[s] = b; }
+            if (final_v == kInf32) {          // the bands were bounds: the recurrence found no plan
+                write_failed_wave(out, c, S_max, HARP_CAND_INFEASIBLE, lane);
+                continue;
             }
-        } else if (tid == 0) {
-            sp[0] = 0;    // one stage holds every operator; the pre-pass has checked that it fits
-            sp[1] = L;
-        }
-        if (dead) {
-            write_failed(out, c, S_max, HARP_CAND_INFEASIBLE);
-            continue;
-        }
-        for (int s = S + 1 + tid; s <= S_max; s += nthreads) sp[s] = -1;
-        __syncthreads();              // the cuts written by thread 0 are read by the first wave
-        if (wave == 0) {
-            int64_t bott, iter;
-            const int st = wave_score_partition(tb, S, slot_g, slot_k, sp, lane, bott, iter);
+            // backtrack along the back-pointers
             if (lane == 0) {
-                out.bottleneck[c] = bott;
-                out.iter_time[c] = iter;
-                out.status[c] = st;
+                int b = last_j;
+                cuts[S] = L;
+                cuts[S - 1] = b;
+                for (int s = S - 2; s >= 0; --s) {
+                    const uint32_t b1 = band[s + 1];
+                    const uint32_t a0 = aoff[s];
+                    const uint32_t at = a0 + uint32_t(b - band_lo(b1));
+                    if (a0 + uint32_t(band_hi(b1) - band_lo(b1) + 1) <= uint32_t(fa.arena_bytes)) {
+                        const int rel = arena[at];
+                        b = rel == kArgEscape ? int(slice[at]) : b - 1 - rel;
+                    } else {
+                        b = slice[at];
+                    }
+                    cuts[s] = b;
+                }
+            }
+            wave_sync();
+        } else {
+            // one stage holds every operator; the pre-pass has checked that it fits
+            if (lane == 0) { cuts[0] = 0; cuts[1] = L; }
+            if (kCount && lane == 0) ++n_cands;
+            wave_sync();
+        }
+        for (int s = lane; s <= S_max; s += 64) sp[s] = s <= S ? cuts[s] : -1;
+        // score of the plan (section 5.2.2): sum of (t + 2c) + (M - 1) bottleneck, lanes over stages
+        {
+            uint32_t worst = 0;
+            int64_t single = 0;
+            for (int s = lane; s < S; s += 64) {
+                const uint32_t w = slot[s], wn = slot[s + 1 < S ? s + 1 : s];
+                const int g = int(w & 0xFFFu), k = int((w >> 12) & 7u), gn = int(wn & 0xFFFu);
+                const int shift = int((fa.shift_packed >> (4 * k)) & 15u);
+                const uint32_t *p = tb.P32 + (int64_t(g) * tb.n_tp + k) * tb.pitch32;
+                const int j = cuts[s], i = cuts[s + 1];
+                const uint32_t t = (p[i] + (1u << shift) - 1u - p[j]) >> shift;
+                const uint32_t cu = s < S - 1 ? tb.CM[(int64_t(g) * tb.G + gn) * tb.pitch32 + i] : 0u;
+                const uint32_t m = t > cu ? t : cu;
+                worst = worst > m ? worst : m;
+                single += int64_t(t) + 2 * int64_t(cu);
+            }
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) {
+                const uint32_t ow = __shfl_xor(worst, d, 64);
+                single += __shfl_xor(single, d, 64);
+                worst = worst > ow ? worst : ow;
+            }
+            if (lane == 0) {
+                out.bottleneck[c] = int64_t(worst);
+                out.iter_time[c] = single + int64_t(m_cap - 1) * int64_t(worst);
+                out.status[c] = HARP_CAND_OK;
             }
         }
     }
     // candidates the pre-pass rejected: no plan to report
-    for (int n = blockIdx.x; n < n_dead; n += gridDim.x) {
+    for (int n = wave_id; n < n_dead; n += n_waves) {
         const uint32_t e = dead_list[n];
-        write_failed(out, int(e & ((1u << kDeadStatusShift) - 1u)), S_max, int(e >> kDeadStatusShift));
+        write_failed_wave(out, int(e & ((1u << kDeadStatusShift) - 1u)), S_max, int(e >> kDeadStatusShift), lane);
+    }
+    if (kCount) {
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) {
+            n_trans += __shfl_xor(n_trans, d, 64);
+            n_cells += __shfl_xor(n_cells, d, 64);
+            n_trips += __shfl_xor(n_trips, d, 64);
+            n_cands += __shfl_xor(n_cands, d, 64);
+        }
+        if (lane == 0) {
+            atomicAdd(&fa.work[0], n_trans);
+            atomicAdd(&fa.work[1], n_cells);
+            atomicAdd(&fa.work[2], n_trips);
+            atomicAdd(&fa.work[3], n_cands);
+        }
     }
 }
 
+struct FastLaunch {
+    int waves_per_cu, lds_per_wave, arena_bytes;
+};
+
+// LDS split: the wavefronts that fit beside each other on a CU, and what is left of their share
+// for one-byte back-pointers.  Eight wavefronts per SIMD is the hardware limit; below four per
+// SIMD the arena gives way first.
+FastLaunch fast_launch_shape(int L, int S_max) {
+    const size_t lds_cu = size_t(160) << 10;
+    const size_t fixed = (fast_wave_fixed_bytes(fast_row_len(L), S_max) + 15) & ~size_t(15);
+    FastLaunch f;
+    int waves = 16;                                  // target: four per SIMD, the rest of the LDS as arena
+    while (waves > kFastWaves && fixed * waves > lds_cu) waves -= kFastWaves;
+    size_t share = (lds_cu / waves - 128) & ~size_t(15);    // a little under an even split: allocation granules
+    if (share < fixed) share = fixed;                // very long rows: one workgroup per CU at most
+    f.waves_per_cu = waves;
+    f.lds_per_wave = int(share);
+    f.arena_bytes = int(share - fixed);
+    return f;
+}
 
 }  // namespace
 
-size_t plan_fast_ws_bytes(int L, int S_max, int C, int n_groups) {
-    return carve(nullptr, L, S_max, C, n_groups).total;
+size_t plan_fast_ws_bytes(const TablesDev &tb, int S_max, int C, int n_slices) {
+    const FastShape f{tb.L, S_max, C, tb.M, tb.T, tb.n_tp};
+    return carve(nullptr, f, n_slices).total;
 }
 
-// Workgroups that can be resident at once: bounded by threads (2048 per CU) and LDS (160 KiB).
+size_t plan_fast_index_bytes(const TablesDev &tb, int S_max) {
+    return lo_table_bytes(tb.L, S_max, tb.M, tb.T, tb.n_tp);
+}
+
+void launch_clear_work(unsigned long long *work, hipStream_t st) {
+    hipLaunchKernelGGL(k2_clear_work, dim3(1), dim3(64), 0, st, work);
+}
+
+// Wavefronts of k2_fast that can be resident at once.
+int plan_fast_waves(int L, int S_max, int n_cu) {
+    return fast_launch_shape(L, S_max).waves_per_cu * n_cu;
+}
+
+// Workgroups of the other 32-bit kernels that can be resident at once: bounded by threads (2048
+// per CU) and LDS (160 KiB).
 int plan_fast_groups(int L, int S_max, int n_cu) {
     const int by_threads = 2048 / kFastThreads;
     int by_lds = int((size_t(160) << 10) / (fast_lds_bytes(L, S_max) + 64));
@@ -449,25 +664,53 @@ int plan_fast_groups(int L, int S_max, int n_cu) {
 }
 
 // Pre-pass shared by every 32-bit planner entry point: clears the counters, checks the slot lists,
-// computes the reachability bands and compacts the live and dead lists.
-void launch_plan_prepass(const TablesDev &tb, const CandDev &cd, void *ws, int n_groups, hipStream_t st) {
-    const FastWorkspace w = carve(ws, tb.L, cd.S_max, cd.C, n_groups);
+// computes the reachability bands, compacts the live and dead lists, and writes the feasibility
+// index.
+void launch_plan_prepass(const TablesDev &tb, const CandDev &cd, void *ws, int n_slices, hipStream_t st) {
+    const FastWorkspace w = carve(ws, fast_shape(tb, cd), n_slices);
     hipLaunchKernelGGL(k2_clear_count, dim3(1), dim3(64), 0, st, w.counts);
     const int caps_in_lds = tb.G * tb.n_tp <= kBandCapTable ? 1 : 0;
     const int bt = band_threads(cd.S_max);
     const size_t band_lds = size_t(tb.L + 1) * 16 + (caps_in_lds ? size_t(tb.G) * tb.n_tp * 8 : 0) +
                             size_t(cd.S_max) * (bt + 2) * 2;
-    hipLaunchKernelGGL(k2_band, dim3((cd.C + bt - 1) / bt), dim3(bt), band_lds, st, tb, cd, w.counts,
-                       w.live_list, w.dead_list, w.bands, caps_in_lds);
+    const int n_band_groups = (cd.C + bt - 1) / bt;
+    const long long lo_rows = (long long)lo_n_max(tb.L, cd.S_max, tb.M) * tb.T * tb.n_tp;
+    const int n_lo_groups = int(lo_rows < 65536 ? lo_rows : 65536);
+    hipLaunchKernelGGL(k2_band, dim3(n_band_groups + n_lo_groups), dim3(bt), band_lds, st, tb, cd, w.counts,
+                       w.live_list, w.dead_list, w.bands, caps_in_lds, n_band_groups, w.lo_tab,
+                       int(lo_pitch(tb.L)), int(lo_rows));
 }
 
+// n_slices: back-pointer slices in the workspace; k2_fast runs with at most that many wavefronts.
 void launch_plan_fast(const TablesDev &tb, const CandDev &cd, const PlansDev &out, void *ws,
-                      int n_groups, hipStream_t st) {
-    const FastWorkspace w = carve(ws, tb.L, cd.S_max, cd.C, n_groups);
-    launch_plan_prepass(tb, cd, ws, n_groups, st);
-    hipLaunchKernelGGL(k2_fast, dim3(n_groups), dim3(kFastThreads), fast_lds_bytes(tb.L, cd.S_max), st, tb,
-                       cd, out, w.counts, w.live_list, w.dead_list, w.bands, w.arg,
-                       fast_arg_per_group(tb.L, cd.S_max), fast_row_len(tb.L));
+                      int n_slices, int n_cu, unsigned long long *work, hipStream_t st) {
+    const FastWorkspace w = carve(ws, fast_shape(tb, cd), n_slices);
+    launch_plan_prepass(tb, cd, ws, n_slices, st);
+    const FastLaunch shape = fast_launch_shape(tb.L, cd.S_max);
+    // whole workgroups only: every wavefront of the grid owns a slice (n_slices >= kFastWaves)
+    int n_groups = shape.waves_per_cu * n_cu / kFastWaves;
+    if (n_groups > n_slices / kFastWaves) n_groups = n_slices / kFastWaves;
+    if (n_groups > (cd.C + kFastWaves - 1) / kFastWaves) n_groups = (cd.C + kFastWaves - 1) / kFastWaves;
+    if (n_groups < 1) n_groups = 1;
+    FastArgs fa;
+    fa.bands = w.bands;
+    fa.lo_tab = w.lo_tab;
+    fa.arg_base = w.arg;
+    fa.arg_per_wave = fast_arg_per_group(tb.L, cd.S_max);
+    fa.work = work;
+    fa.lo_pitch = int(lo_pitch(tb.L));
+    fa.row_len = fast_row_len(tb.L);
+    fa.lds_per_wave = shape.lds_per_wave;
+    fa.arena_bytes = shape.arena_bytes;
+    fa.shift_packed = 0;
+    for (int k = 0; k < tb.n_tp; ++k) fa.shift_packed |= uint32_t(tb.tp_shift[k] & 15) << (4 * k);
+    const size_t lds = size_t(kFastWaves) * shape.lds_per_wave;
+    if (work)
+        hipLaunchKernelGGL(k2_fast<true>, dim3(n_groups), dim3(kFastWaves * 64), lds, st, tb, cd, out, w.counts,
+                           w.live_list, w.dead_list, fa);
+    else
+        hipLaunchKernelGGL(k2_fast<false>, dim3(n_groups), dim3(kFastWaves * 64), lds, st, tb, cd, out, w.counts,
+                           w.live_list, w.dead_list, fa);
 }
 
 }  // namespace harp

@@ -127,7 +127,7 @@ __device__ __forceinline__ void h1f1b_body(const TablesDev &tb, const CandDev &c
                 df[s] = first;
             }
             for (int s = S + tid; s < S_max; s += nthreads) df[s] = -1;
-            for (int s = tid; s <= S; s += nthreads) band[s] = bands[int64_t(s) * cd.C + c];
+            for (int s = tid; s <= S; s += nthreads) band[s] = bands[int64_t(c) * (S_max + 1) + s];
             // behind the last stage: no operators left, nothing launched yet; the last stage itself
             // adds delta(0) = 1
             if (tid == 0) { rows[L].h = 0; rows[L].nn = 1; }
@@ -331,7 +331,7 @@ size_t h1f1b_lds_bytes(int L, int S_max, size_t entry) {
 // launch_plan_prepass) and then the two instantiations.
 void launch_plan_h1f1b(const TablesDev &tb, const CandDev &cd, const int64_t *t_max, const PlansDev &out,
                        int32_t *warmup, void *ws, int n_groups, hipStream_t st) {
-    const FastWorkspace w = carve(ws, tb.L, cd.S_max, cd.C, n_groups);
+    const FastWorkspace w = carve(ws, fast_shape(tb, cd), n_groups);
     launch_plan_prepass(tb, cd, ws, n_groups, st);
     const int row_len = h1f1b_row_len(tb.L);
     hipLaunchKernelGGL(k2_h1f1b, dim3(n_groups), dim3(kFastThreads), h1f1b_lds_bytes(tb.L, cd.S_max, 8), st, tb,

@@ -60,6 +60,19 @@ __device__ __forceinline__ void write_failed(const PlansDev &out, int c, int S_m
     }
 }
 
+// One wavefront (all 64 lanes): outputs of a candidate without a plan.
+__device__ __forceinline__ void write_failed_wave(const PlansDev &out, int c, int S_max, int status, int lane) {
+    int32_t *sp = out.splits + int64_t(c) * (S_max + 1);
+    int32_t *df = out.dev_first + int64_t(c) * S_max;
+    for (int s = lane; s <= S_max; s += 64) sp[s] = -1;
+    for (int s = lane; s < S_max; s += 64) df[s] = -1;
+    if (lane == 0) {
+        out.bottleneck[c] = kInf;
+        out.iter_time[c] = kInf;
+        out.status[c] = status;
+    }
+}
+
 // One wavefront (all 64 lanes, uniform arguments): the cost model of the paper's section 5.2.2
 // for the partition sp[0..S]:  sum_s (t_s + 2 c_s) + (M - 1) max_s max(t_s, c_s), after checking
 // that the cuts rise strictly from 0 to L and that every stage fits in memory (eq. mem_cons).
