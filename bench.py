@@ -20,19 +20,36 @@ if ROOT not in sys.path:
 
 # int32 VALU peak of one MI355X: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz lane-operations per second
 ALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
-# accounting convention for one transition of the dense recurrence: 13 int64 operations
-# (time: 2 sub, add, shift, add; memory: 2 sub, mul, add, compare; combine: 2 max, 1 min-select),
-# each counted as two 32-bit lane-operations
-LANE_OPS_PER_TRANSITION = 26
-# HBM bytes per launch of the planner kernel on the stress workload, from rocprofv3 counters
-# (profiles/plan_batch_stress_pmc.txt: FETCH_SIZE + WRITE_SIZE of k2_band and k2_fast, each scaled by
-# a plain copy's reading)
-MEASURED_TRAFFIC_BYTES = {"stress": 3.394e9 + 1.795e9 + 0.254e9 + 0.344e9}
-# issued-instruction view of k2_fast on the same workload, from the same counter runs
-MEASURED_ISSUE = {"stress": {"valu_issue_utilisation": 0.686, "lanes_active_per_valu_instruction": 0.57,
-                             "lds_bank_conflict_fraction": 0.12,
-                             "issued_lane_ops_frac_of_peak": 0.686 * 0.57,   # what the VALUs actually did
-                             "source": "profiles/plan_batch_stress_pmc.txt (rocprofv3 --pmc, k2_fast)"}}
+# Accounting convention for one transition (s, i, j) of the recurrence: 13 integer operations (time:
+# 2 sub, add, shift, add; memory: 2 sub, mul, add, compare; combine: 2 max, 1 min-select).  On the int64
+# path each is a 64-bit operation = two 32-bit lane-operations (26 per transition); on the 32-bit path,
+# which the table build has proven exact for the problem, each is one lane-operation (13).
+LANE_OPS_PER_TRANSITION = {"int64": 26, "u32": 13}
+# sources of the planner kernel; counter-derived figures in profiles/ are quoted only while these are unchanged
+KERNEL_SOURCES = ("k2_fast.hip", "fast_common.h", "plan_common.h", "harp_internal.h")
+COUNTER_FILE = os.path.join(ROOT, "profiles", "plan_batch_stress_counters.json")
+
+
+def kernel_source_hash():
+    import hashlib
+    h = hashlib.sha256()
+    for name in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_2509_24859_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def counter_figures(workload, full_batch):
+    """HBM traffic and the issued-instruction view of the planner launch from the rocprofv3 counter runs
+    recorded in profiles/ - quoted only when they were taken on this workload with the kernel sources as
+    they are now (the record carries their hash); otherwise None, never a stale number."""
+    if not full_batch or not os.path.exists(COUNTER_FILE):
+        return None, None
+    with open(COUNTER_FILE) as f:
+        rec = json.load(f)
+    if rec.get("workload") != workload or rec.get("kernel_source_hash") != kernel_source_hash():
+        return None, None
+    return rec.get("traffic_bytes_per_call"), rec.get("issued")
 
 
 def cpu_baseline(w, cands, gpu_plans, budget_candidates):
@@ -445,6 +462,66 @@ def mesh_search(ctx, binding, torch, workloads, name, n_orders, reps, cpu_orders
     return res
 
 
+def minmax_config(ctx, binding, torch, workloads, name, reps, with_cpu):
+    """One workload through the min-max path on its own: time per harp_plan_batch, rates by the fixed
+    formulas of the dense recurrence, the work the kernel actually did (counted by the instrumented
+    build of the same kernel), and the oracle beside it: single-thread rate on the first min(C, 1024)
+    candidates, then every host thread over the whole batch, which also verifies every plan bit for bit
+    (the stress batch is verified on a prefix here; the GPU test suite covers all of it)."""
+    import numpy as np
+
+    w = workloads.make(name)
+    cands = w.candidates()
+    cells, trans = workloads.dense_counts(w.problem.L, cands.cand_S)
+    tables = binding.Tables(ctx, w.problem)
+    dc = binding.DeviceCandidates(ctx, cands)
+    out = binding.DevicePlans(ctx, dc.C, dc.S_max)
+    ws = binding.plan_workspace(ctx, tables, dc)
+    ms = timed_ms(torch, lambda: binding.harp_plan_batch(ctx, tables, dc, out, ws), reps, warmup=2)
+    got = out.to_host()
+    res = {"L": w.problem.L, "candidates": dc.C, "S_max": dc.S_max, "plan_kernel_ms": ms,
+           "plans_per_s": dc.C / (ms * 1e-3), "cells_per_s": float(cells.sum()) / (ms * 1e-3),
+           "dense_transitions_per_s": float(trans.sum()) / (ms * 1e-3),
+           "feasible_fraction": float((got.status == 0).mean()), "path": "u32" if tables.fast32 else "int64"}
+    if tables.fast32:
+        work = torch.zeros(4, dtype=torch.int64, device=ctx.device)
+        binding.harp_plan_batch_count_work(ctx, tables, dc, out, ws, work)
+        torch.cuda.synchronize()
+        ev, cl, tr, nc = (int(x) for x in work.cpu().numpy())
+        res["evaluated"] = {"transitions": ev, "cells": cl, "groups_of_four": tr, "candidates_planned": nc}
+        res["alu_frac"] = ev * LANE_OPS_PER_TRANSITION["u32"] / (ms * 1e-3) / ALU_PEAK_LANE_OPS
+    if with_cpu:
+        import oracle
+        from concurrent.futures import ThreadPoolExecutor
+        cores = min(16, len(os.sched_getaffinity(0)))
+        ot = oracle.build_tables(w.problem)
+        n1 = min(dc.C, 1024)
+        one = oracle.Plans(n1, cands.S_max)
+        sub = cands.slice(0, n1)
+        t0 = time.perf_counter()
+        oracle.plan_batch(ot, sub, 0, n1, one)
+        dt1 = time.perf_counter() - t0
+        # all host threads: the whole batch when that is a few seconds of work, else a prefix
+        n_all = dc.C if float(trans.sum()) < 4e10 else max(n1, int(dc.C * 4e10 / float(trans.sum())))
+        allc = cands.slice(0, n_all)
+        want = oracle.Plans(n_all, cands.S_max)
+        step = max(1, min(16, n_all // (cores * 4) or 1))
+        t0 = time.perf_counter()
+        with ThreadPoolExecutor(cores) as ex:
+            list(ex.map(lambda lo: oracle.plan_batch(ot, allc, lo, min(lo + step, n_all), want), range(0, n_all, step)))
+        dta = time.perf_counter() - t0
+        for field in ("status", "splits", "dev_first", "bottleneck", "iter_time"):
+            if not (getattr(want, field) == getattr(got, field)[:n_all]).all():
+                raise SystemExit("GPU plans differ from the oracle in %s on workload %s" % (field, name))
+        res["cpu_baseline"] = {
+            "kind": "oracle", "single_thread_transitions_per_s": float(trans[:n1].sum()) / dt1,
+            "single_thread_sample": "first %d candidates, %.2f s" % (n1, dt1),
+            "all_core_plans_per_s": n_all / dta, "all_core_transitions_per_s": float(trans[:n_all].sum()) / dta,
+            "cores": cores, "all_core_sample": "%d of %d candidates, %.2f s wall" % (n_all, dc.C, dta),
+            "verified": "GPU plans of those %d candidates bit-exact against the oracle" % n_all}
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -455,6 +532,7 @@ def main():
     ap.add_argument("--candidates", type=int, default=0, help="use only the first N candidates")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-peaks", action="store_true", help="skip the VALU and copy micro-benchmarks")
+    ap.add_argument("--no-configs", action="store_true", help="skip the per-workload table (all five configs)")
     ap.add_argument("--cpu-candidates", type=int, default=0)
     ap.add_argument("--tables-L", type=int, default=1 << 20,
                     help="operators of the table-build streaming measurement (0 = skip)")
@@ -466,6 +544,8 @@ def main():
     ap.add_argument("--h1f1b-reps", type=int, default=3,
                     help="timed calls of the H-1F1B recurrence at the exact search's caps (0 = skip)")
     ap.add_argument("--h1f1b-cpu-candidates", type=int, default=1024)
+    ap.add_argument("--h1f1b-workload", default="finegrained",
+                    help="second workload for the H-1F1B recurrence, one where most candidates stay feasible ('' = skip)")
     ap.add_argument("--mesh-workload", default="llama70b")
     ap.add_argument("--mesh-orderings", type=int, default=4096,
                     help="group orderings for the submesh-in-recurrence planner (0 = skip)")
@@ -506,6 +586,7 @@ def main():
     ctx.set_plan_path(path)
     fast = tables.fast32 and path != binding.PATH_GENERIC
     kernel = "k2_band + k2_fast (one harp_plan_batch call)" if fast else "k2_generic"
+    width = "u32" if fast else "int64"
 
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
           for _ in range(args.steps)]
@@ -538,6 +619,21 @@ def main():
     per_step = sorted(a.elapsed_time(b) for a, b in ev)
     kernel_ms = sum(per_step) / args.steps
     got = out.to_host()
+    # the work the planner launch actually does, counted once by the instrumented build of the same kernel
+    evaluated = None
+    if fast:
+        work = torch.zeros(4, dtype=torch.int64, device=ctx.device)
+        check = binding.DevicePlans(ctx, dc.C, dc.S_max)
+        binding.harp_plan_batch_count_work(ctx, tables, dc, check, ws, work)
+        torch.cuda.synchronize()
+        same = check.to_host()
+        for field in ("status", "splits", "dev_first", "bottleneck", "iter_time"):
+            if not (getattr(same, field) == getattr(got, field)).all():
+                raise SystemExit("the counting build of the planner kernel gives different plans (%s)" % field)
+        n_ev, n_cl, n_tr, n_pl = (int(x) for x in work.cpu().numpy())
+        evaluated = {"transitions": n_ev, "cells": n_cl, "groups_of_four": n_tr, "candidates_planned": n_pl,
+                     "fraction_of_dense_transitions": n_ev / n_trans, "fraction_of_dense_cells": n_cl / n_cells}
+        del check
     # the other kernels of a step, each on its own (enqueue to enqueue, HIP events)
     parts = {"tables_build_ms": timed_ms(torch, tables.rebuild, 20),
              "argmin_ms": timed_ms(torch, lambda: binding.harp_argmin_batch(ctx, dc.C, out.iter_time, out.status,
@@ -548,8 +644,21 @@ def main():
     s2 = torch.empty(dc.C, dtype=torch.int32, device=ctx.device)
     parts["score_ms"] = timed_ms(torch, lambda: binding.harp_score_1f1b(ctx, tables, dc, out.splits, b2, t2, s2), 10)
     del b2, t2, s2
-    achieved = n_trans * LANE_OPS_PER_TRANSITION / (kernel_ms * 1e-3)
-    traffic = MEASURED_TRAFFIC_BYTES.get(args.workload) if C == w.C and fast else None
+    ops = LANE_OPS_PER_TRANSITION[width]
+    dense_rate = n_trans * 26 / (kernel_ms * 1e-3)
+    traffic, issued = counter_figures(args.workload, C == w.C and fast)
+    if evaluated is not None:
+        achieved = evaluated["transitions"] * ops / (kernel_ms * 1e-3)
+        note = ("achieved = transitions the kernel evaluated in one launch (counted by the instrumented build of the "
+                "same kernel, harp_plan_batch_count_work) x %d lane-ops / mean time of one harp_plan_batch (HIP events "
+                "on the launch stream); %d = the 13 operations of a transition, each one 32-bit lane-op on this path "
+                "(26 when they are 64-bit).  dense_equivalent_rate prices every transition of the dense recurrence, "
+                "most of which the bands and bounded scans never evaluate: work delivered, not a fraction of anything"
+                % (ops, ops))
+    else:
+        achieved = dense_rate
+        note = ("int64 path: no evaluated-transition count; achieved = dense-recurrence transitions x 26 lane-ops / "
+                "mean kernel time, an upper figure (the monotone stops skip part of them)")
     result = {
         "metric": "candidate plans/sec (and DP cells/sec) on 1 MI355X",
         "value": C * args.steps / elapsed,
@@ -582,13 +691,15 @@ def main():
             "bound": "alu", "kernel": kernel,
             "achieved": achieved / 1e12, "peak": ALU_PEAK_LANE_OPS / 1e12, "unit": "T int32 lane-op/s",
             "frac": achieved / ALU_PEAK_LANE_OPS, "traffic": traffic,
-            "issued": MEASURED_ISSUE.get(args.workload) if C == w.C and fast else None,
-            "note": "achieved = dense-recurrence transitions per launch x 26 lane-ops / mean kernel time "
-                    "(HIP events on the launch stream around harp_plan_batch); the kernels evaluate far fewer "
-                    "transitions than the dense count (reachability bands, bounded scans), so this is work "
-                    "delivered, not instructions issued: VALU issue utilisation is 69% (profiles/)",
+            "lane_ops_per_transition": ops, "evaluated": evaluated,
+            "dense_equivalent_rate": dense_rate / 1e12,
+            "issued": issued,
+            "counters_from": (os.path.relpath(COUNTER_FILE, ROOT) if traffic is not None or issued is not None else None),
+            "note": note,
         },
     }
+    if evaluated is not None:
+        result["roofline"]["evaluated_x26_over_peak"] = evaluated["transitions"] * 26 / (kernel_ms * 1e-3) / ALU_PEAK_LANE_OPS
     if not args.no_peaks:
         peaks = measured_peaks(ctx, binding, torch)
         result["measured_peaks"] = peaks
@@ -608,9 +719,28 @@ def main():
         result["h1f1b"] = h1f1b_search(ctx, binding, torch, w, tables, dc, cands, result.pop("_exact_caps"),
                                        args.h1f1b_reps, 0 if args.no_cpu_baseline else args.h1f1b_cpu_candidates)
     result.pop("_exact_caps", None)
+    if args.h1f1b_reps and args.exact_reps and args.h1f1b_workload and args.h1f1b_workload != args.workload:
+        # the same recurrence where most candidates stay feasible under H-1F1B's counts
+        w2 = workloads.make(args.h1f1b_workload)
+        c2 = w2.candidates()
+        t2 = binding.Tables(ctx, w2.problem)
+        if t2.fast32:
+            d2 = binding.DeviceCandidates(ctx, c2)
+            o2 = binding.DevicePlans(ctx, d2.C, d2.S_max)
+            binding.harp_plan_batch(ctx, t2, d2, o2, binding.plan_workspace(ctx, t2, d2))
+            torch.cuda.synchronize()
+            e2 = exact_search(ctx, binding, torch, w2, t2, d2, c2, o2.to_host(), 1, 0)
+            leg = h1f1b_search(ctx, binding, torch, w2, t2, d2, c2, e2.pop("_caps"), args.h1f1b_reps,
+                               0 if args.no_cpu_baseline else args.h1f1b_cpu_candidates)
+            leg["workload"] = "%s: L=%d, %d candidates" % (w2.name, w2.problem.L, d2.C)
+            result["h1f1b_feasible_workload"] = leg
     if args.mesh_orderings:
         result["mesh"] = mesh_search(ctx, binding, torch, workloads, args.mesh_workload, args.mesh_orderings, 2,
                                      0 if args.no_cpu_baseline else args.mesh_cpu_orderings, args.mesh_sweep_orderings)
+    if not args.no_configs:
+        # all five workloads through the min-max path, the oracle beside each
+        result["configs"] = {name: minmax_config(ctx, binding, torch, workloads, name, 20 if name != "stress" else 5,
+                                                 not args.no_cpu_baseline) for name in workloads.ORDER}
     if not args.no_cpu_baseline:
         # about 20 core-seconds of oracle work at 1-5 ns per dense transition
         budget = args.cpu_candidates or max(64, int(1.6e10 / max(1.0, n_trans / C)))
