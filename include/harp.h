@@ -9,7 +9,7 @@
  * subclusters of section 5.2.1 together with the submesh choice of section 5.2.2, hoisted out of
  * the DP into the batch dimension).  For every candidate the library finds the partition of the
  * operators into S contiguous non-empty stages with the smallest feasible bottleneck t_max
- * (section 5.2.3, constraints (i)-(iii); section 5.2.4 (2), "smallest feasible value t_S") and
+ * (section 5.2.3, constraints (i)-(iii); the lower end t_S of the cap range of section 5.2.4 (2)) and
  * scores it with the iteration-time model of section 5.2.2 (eq. gpipe_cost_model).
  *
  * All quantities are integers: times in microseconds, sizes in bytes, bandwidths in bytes per
@@ -265,7 +265,9 @@ size_t harp_plan_mesh_workspace_bytes(harp_ctx *ctx, harp_tables *tables, const 
  * out as for harp_plan_batch (rows of length S_max + 1 / S_max); stage_group, stage_tp: DEVICE
  * [C][S_max], the slicing found (-1 beyond S or without a plan).  HARP_CAND_INVALID: S outside
  * 1..S_max, ord_G outside 1..G_max, a group id out of range or listed twice; HARP_CAND_INFEASIBLE:
- * S > L, S < ord_G, S > devices, or no plan fits in memory.  At most 65535 devices.
+ * S > L, S < ord_G, S > devices, or no plan fits in memory.  At most 65535 devices, and
+ * (devices + 1) x (L + 1) below 2^31 (HARP_ERR_SHAPE otherwise; also for the other entry points
+ * with a device index).
  * Asynchronous on `hip_stream`, except that the first use of a view finalizes it. */
 int harp_plan_mesh_batch(harp_ctx *ctx, harp_tables *tables, const harp_orderings *orders,
                          const harp_plans *out, int32_t *stage_group, int32_t *stage_tp,
@@ -344,7 +346,9 @@ int harp_plan_h1f1b_sweep_batch(harp_ctx *ctx, harp_tables *tables, const harp_c
  *   delta(c_cut; t_max) = 1 if 2 c_cut <= floor(t_max / 64), else 1 + ceil((2 c_cut - floor(t_max / 64)) / t_max)
  *   N(last stage) = 1,  N(stage s) = min(M, delta(cut behind s) + N(stage s + 1))        (eq. Ni)
  *   a state keeps the continuation of least sum (lowest end cut among equal sums) and its N.
- * t_max: DEVICE [C] (negative: no plan).  warmup: DEVICE [C][S_max], receives N per stage, -1 beyond
+ * t_max: DEVICE [C] (negative: no plan; above min(2^47 - 1, INT64_MAX / (3 L + M)), beyond which
+ * sum + (M - 1) t_max could leave int64: the candidate is HARP_CAND_INVALID; the same bound holds
+ * for every entry point that takes a cap).  warmup: DEVICE [C][S_max], receives N per stage, -1 beyond
  * S and for candidates without a plan.  out as for harp_plan_batch, with bottleneck = the plan's own
  * largest stage or transfer time (<= t_max[c]) and iter_time = least sum + (M - 1) t_max[c], the
  * T(t_max) of section 5.2.3; HARP_CAND_INFEASIBLE when no partition satisfies (i)-(iii) under the

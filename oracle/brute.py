@@ -648,3 +648,28 @@ def sweep_h1f1b(p, S: int, S_max: int, grp, tp, max_caps: int = 1 << 20):
         if T < best[4]:
             best = (0, cap, cuts, counts, T)
     return best + (tried,)
+
+
+def subcluster_order(p):
+    """Order of the subclusters by the heuristic of section 5.2.1, as a check of the product's
+    pre-filter: a group goes before another when its devices have more memory per unit of compute
+    throughput, throughput of a GPU type = 1 / (its forward+backward time over the whole model);
+    equal ratios keep the lower group id first.  Written as the definition: exact fractions, and a
+    selection that asks, for every position, which remaining group no other remaining group beats."""
+    from fractions import Fraction
+
+    def ratio(g):
+        t = int(p.group_type[g])
+        time = sum(int(x) for x in p.fwd_us[t]) + sum(int(x) for x in p.bwd_us[t])
+        if time == 0:
+            return Fraction(0)                       # infinite throughput: no memory per unit of it
+        return Fraction(int(p.type_mem_bytes[t])) / Fraction(1, time)
+
+    left = list(range(p.G))
+    out = []
+    while left:
+        pick = next(g for g in left
+                    if all(ratio(g) > ratio(h) or (ratio(g) == ratio(h) and g <= h) for h in left))
+        out.append(pick)
+        left.remove(pick)
+    return out

@@ -508,6 +508,16 @@ static int64_t h1f1b_delta(int64_t c, int64_t t_max)
 /* One candidate under the cap t_max.  G and N are (S+1) x (L+1) tables: G[s][i] = least sum for
  * operators i..L-1 on the last s slots, N[s][i] = warm-up count of the first of those stages.
  * Ties keep the lowest end cut j of the first stage.  Returns the status; fills the outputs. */
+/* Caps the capped entry points accept: below 2^47 us like every time of an accepted problem, and
+ * small enough that a sum of at most 3 L terms plus (M - 1) caps stays inside int64 (magnitudes,
+ * reading R13); a larger cap makes the candidate INVALID. */
+static int cap_out_of_range(const oracle_problem *p, int64_t t_max)
+{
+    const int64_t by_sum = INT64_MAX / (3 * (int64_t)p->L + (int64_t)p->M);
+    const int64_t limit = by_sum < ((int64_t)1 << 47) - 1 ? by_sum : ((int64_t)1 << 47) - 1;
+    return t_max > limit;
+}
+
 static int plan_h1f1b_one(const tables_view *v, int S, int S_max, const int32_t *grp, const int32_t *tp,
                           int64_t t_max, int64_t *G, int64_t *N, int32_t *arg, int32_t *splits,
                           int32_t *dev_first, int32_t *warmup, int64_t *bott, int64_t *iter)
@@ -517,6 +527,7 @@ static int plan_h1f1b_one(const tables_view *v, int S, int S_max, const int32_t 
     fill_failed(S_max, splits, dev_first, bott, iter);
     for (int s = 0; s < S_max; ++s) warmup[s] = -1;
     if (!candidate_valid(p, S, S_max, grp, tp)) return CAND_INVALID;
+    if (cap_out_of_range(p, t_max)) return CAND_INVALID;
     if (S > L || t_max < 0) return CAND_INFEASIBLE;
     const size_t W = (size_t)(L + 1);
     for (size_t x = 0; x < (size_t)(S + 1) * W; ++x) { G[x] = ORACLE_INF; N[x] = 0; arg[x] = -1; }
@@ -617,6 +628,7 @@ int oracle_score_h1f1b(const oracle_problem *p, const int64_t *PF, const int64_t
         int ok = sp[0] == 0 && sp[S] == L;
         for (int s = 0; s < S && ok; ++s) ok = sp[s + 1] > sp[s];
         if (!ok) continue;
+        if (cap_out_of_range(p, t_max[c])) continue;
         status[c] = CAND_INFEASIBLE;
         if (t_max[c] < 0) continue;
         int64_t n = 0, sum = 0, worst = 0;
@@ -931,6 +943,7 @@ int oracle_plan_mesh_h1f1b_batch(const oracle_problem *p, const int64_t *PF, con
             m.O[k + 1] = m.O[k] + p->group_ndev[og[k]];
         }
         if (!ok) continue;
+        if (cap_out_of_range(p, cap)) continue;
         status[c] = CAND_INFEASIBLE;
         const int64_t Dtot = m.O[K];
         if (S > L || S < K || S > Dtot || cap < 0) continue;

@@ -222,6 +222,11 @@ int check_orderings(harp_ctx *ctx, harp_tables *t, const harp_orderings *od) {
     return finalize_tables(ctx, t);
 }
 
+// The kernels with a device index address their state with 32-bit products of these two.
+bool mesh_index_fits(const harp_tables *t) {
+    return (t->total_devices + 1) * (int64_t(t->dev.L) + 1) < (int64_t(1) << 31);
+}
+
 bool use_fast(const harp_ctx *ctx, const harp_tables *t) {
     return t->fast32 && ctx->plan_path != HARP_PATH_GENERIC;
 }
@@ -546,6 +551,7 @@ int plan_mesh_common(harp_ctx *ctx, harp_tables *t, const harp_orderings *od, co
         return fail(ctx, HARP_ERR_UNIMPLEMENTED, "the 32-bit path was requested but these tables do not allow it");
     if (od->C == 0) return HARP_OK;
     if (t->total_devices > 65535) return fail(ctx, HARP_ERR_SHAPE, "the submesh planner handles at most 65535 devices");
+    if (!mesh_index_fits(t)) return fail(ctx, HARP_ERR_SHAPE, "(devices + 1) x (L + 1) must stay below 2^31 for the kernels with a device index");
     const size_t per_group = plan_mesh_ws_per_group(t->dev.L, od->S_max, t->total_devices);
     const int threads = plan_mesh_threads(t->dev.L, t->total_devices, od->C, ctx->n_cu);
     const int groups = n_mesh_groups(ctx, od->C, per_group, threads);
@@ -589,6 +595,7 @@ int harp_plan_mesh_h1f1b_batch(harp_ctx *ctx, harp_tables *t, const harp_orderin
         return fail(ctx, HARP_ERR_UNIMPLEMENTED, "the 32-bit path was requested but these tables do not allow it");
     if (od->C == 0) return HARP_OK;
     if (t->total_devices > 65535) return fail(ctx, HARP_ERR_SHAPE, "the submesh planner handles at most 65535 devices");
+    if (!mesh_index_fits(t)) return fail(ctx, HARP_ERR_SHAPE, "(devices + 1) x (L + 1) must stay below 2^31 for the kernels with a device index");
     const size_t per_group = plan_mesh_ws_per_group(t->dev.L, od->S_max, t->total_devices);
     const int threads = plan_mesh_threads(t->dev.L, t->total_devices, od->C, ctx->n_cu);
     const int groups = n_mesh_groups(ctx, od->C, per_group, threads);
@@ -622,6 +629,7 @@ int harp_plan_mesh_h1f1b_sweep_batch(harp_ctx *ctx, harp_tables *t, const harp_o
         return fail(ctx, HARP_ERR_UNIMPLEMENTED, "the 32-bit path was requested but these tables do not allow it");
     if (od->C == 0) return HARP_OK;
     if (t->total_devices > 65535) return fail(ctx, HARP_ERR_SHAPE, "the submesh planner handles at most 65535 devices");
+    if (!mesh_index_fits(t)) return fail(ctx, HARP_ERR_SHAPE, "(devices + 1) x (L + 1) must stay below 2^31 for the kernels with a device index");
     const SweepLayout lay = sweep_layout(ctx, t, od);
     const size_t need = lay.bytes;
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0)
@@ -659,6 +667,7 @@ int harp_plan_h1f1b_sweep_batch(harp_ctx *ctx, harp_tables *t, const harp_candid
         return fail(ctx, HARP_ERR_UNIMPLEMENTED, "the 32-bit path was requested but these tables do not allow it");
     if (cd->C == 0) return HARP_OK;
     if (t->total_devices > 65535) return fail(ctx, HARP_ERR_SHAPE, "the search over the cap handles at most 65535 devices");
+    if (!mesh_index_fits(t)) return fail(ctx, HARP_ERR_SHAPE, "(devices + 1) x (L + 1) must stay below 2^31 for the kernels with a device index");
     const harp_orderings shape = { cd->C, 1, cd->S_max, nullptr, nullptr, nullptr };
     const SweepLayout lay = sweep_layout(ctx, t, &shape);
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0)

@@ -309,6 +309,7 @@ __global__ __launch_bounds__(kThreads) void k2_generic_h1f1b(TablesDev tb, CandD
         const int32_t *tpv = cd.cand_tp + int64_t(c) * S_max;
         int32_t *wu = warmup + int64_t(c) * S_max;
         int status = load_and_check_slots(tb, S, S_max, grp, tpv, slots);
+        if (status == HARP_CAND_OK && cap_out_of_range(tb, cap_t)) status = HARP_CAND_INVALID;
         if (status == HARP_CAND_OK && (S > L || cap_t < 0)) status = HARP_CAND_INFEASIBLE;
         const int64_t *Gp = w.G0;
         if (status == HARP_CAND_OK) {

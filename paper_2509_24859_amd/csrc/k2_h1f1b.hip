@@ -104,8 +104,8 @@ __device__ __forceinline__ void h1f1b_body(const TablesDev &tb, const CandDev &c
         int32_t *sp = out.splits + int64_t(c) * (S_max + 1);
         int32_t *df = out.dev_first + int64_t(c) * S_max;
         int32_t *wu = warmup + int64_t(c) * S_max;
-        if (cap64 < 0) {              // no time fits under a negative cap
-            write_failed(out, c, S_max, HARP_CAND_INFEASIBLE);
+        if (cap64 < 0 || cap_out_of_range(tb, cap64)) {   // no time fits under a negative cap; too large a cap is refused
+            write_failed(out, c, S_max, cap64 < 0 ? HARP_CAND_INFEASIBLE : HARP_CAND_INVALID);
             for (int s = tid; s < S_max; s += nthreads) wu[s] = -1;
             continue;
         }
@@ -295,7 +295,8 @@ __device__ __forceinline__ void h1f1b_body(const TablesDev &tb, const CandDev &c
         for (int n = blockIdx.x; n < n_dead; n += gridDim.x) {
             const uint32_t e = dead_list[n];
             const int c = int(e & ((1u << kDeadStatusShift) - 1u));
-            write_failed(out, c, S_max, int(e >> kDeadStatusShift));
+            const int st = cap_out_of_range(tb, t_max[c]) ? HARP_CAND_INVALID : int(e >> kDeadStatusShift);
+            write_failed(out, c, S_max, st);
             for (int s = tid; s < S_max; s += nthreads) warmup[int64_t(c) * S_max + s] = -1;
         }
     }

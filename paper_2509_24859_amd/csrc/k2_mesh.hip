@@ -223,6 +223,7 @@ __device__ __forceinline__ void mesh_h1_body(const TablesDev &tb, const OrdDev &
                 order[k] = uint16_t(g);
             }
         if (__syncthreads_or(bad)) { fail(HARP_CAND_INVALID); continue; }
+        if (cap_out_of_range(tb, cap)) { fail(HARP_CAND_INVALID); continue; }
         if (tid == 0) {
             int64_t o = 0;
             offs[0] = 0;

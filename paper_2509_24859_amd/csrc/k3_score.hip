@@ -58,6 +58,7 @@ __global__ __launch_bounds__(64) void k3_score_h1f1b(TablesDev tb, CandDev cd, c
                 if (sp[s + 1] <= sp[s]) invalid = 1;
             if (__any(invalid)) st = HARP_CAND_INVALID;
         }
+        if (st == HARP_CAND_OK && cap_out_of_range(tb, cap)) st = HARP_CAND_INVALID;
         int64_t worst = 0, sum = 0;
         if (st == HARP_CAND_OK) {
             int over = cap < 0 ? 1 : 0;

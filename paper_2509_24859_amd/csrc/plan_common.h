@@ -47,6 +47,14 @@ __device__ __forceinline__ int load_and_check_slots(const TablesDev &tb, int S, 
     return HARP_CAND_OK;
 }
 
+// Largest cap t_max the capped entry points accept: below 2^47 us like every time of an accepted
+// problem, and small enough that a sum of at most 3 L terms plus (M - 1) caps stays inside int64.
+__device__ __forceinline__ bool cap_out_of_range(const TablesDev &tb, int64_t cap) {
+    const int64_t by_sum = INT64_MAX / (3 * int64_t(tb.L) + int64_t(tb.M));
+    const int64_t limit = by_sum < kTimeLimit - 1 ? by_sum : kTimeLimit - 1;
+    return cap > limit;
+}
+
 // All threads of the workgroup: outputs of a candidate without a plan.
 __device__ __forceinline__ void write_failed(const PlansDev &out, int c, int S_max, int status) {
     int32_t *sp = out.splits + int64_t(c) * (S_max + 1);

@@ -191,6 +191,28 @@ def test_exact_empty_batch(harp, ctx):
     assert got.status.shape == (0,) and n_passes.shape == (0,)
 
 
+def test_exact_full_finegrained_batch_both_paths_and_sample(harp, ctx):
+    """The whole fine-grained batch (65,536 candidates) through the exact search on both kernel paths,
+    which share no search code: identical plans and pass counts; and a sample spread over the batch
+    against the oracle's full increasing sweep (which does about 6 candidates a second on 16 host
+    threads, so the oracle itself cannot cover the batch)."""
+    w = W.make("finegrained")
+    cands = w.candidates()
+    fast, n_fast, _ = harp.plan_exact(ctx, w.problem, cands, harp.PATH_FAST32)
+    gen, n_gen, _ = harp.plan_exact(ctx, w.problem, cands, harp.PATH_GENERIC)
+    assert_plans_equal(fast, gen, "finegrained exact, 32-bit against int64 path")
+    assert (n_fast == n_gen).all()
+    idx = (np.arange(48, dtype=np.int64) * 1361) % w.C
+    want = oracle_plan_exact_threaded(oracle.build_tables(w.problem), cands.take(idx))
+
+    class _Sub:
+        pass
+    sub = _Sub()
+    for name in ("status", "splits", "dev_first", "bottleneck", "iter_time"):
+        setattr(sub, name, getattr(fast, name)[idx])
+    assert_plans_equal(sub, want, "finegrained exact sample")
+
+
 def test_exact_full_stress_batch_properties(harp, ctx):
     """The whole stress batch in the launch configuration the benchmark times: what must hold for
     every candidate whatever its size."""

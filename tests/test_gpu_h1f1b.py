@@ -241,6 +241,30 @@ def test_h1f1b_scorer_on_arbitrary_partitions(harp, ctx):
     assert set(st) == {oracle.OK, oracle.INFEASIBLE, oracle.INVALID}
 
 
+def test_caps_beyond_the_accepted_range_are_invalid(harp, ctx):
+    """The largest accepted cap gives a plan with an exact iteration time; one more, or INT64_MAX passed
+    as "no cap", makes the candidate INVALID on every entry point that takes a cap, on both paths and
+    in the oracle (sum + (M - 1) t_max would otherwise leave int64)."""
+    w = W.make("llama7b")
+    p = w.problem
+    top = min(2 ** 47 - 1, (2 ** 63 - 1) // (3 * p.L + p.M))
+    cands = w.candidates(0, 8)
+    cands.cand_group[7, 0] = p.G + 3                      # malformed whatever the cap
+    caps = np.array([top, top + 1, 2 ** 63 - 1, 2 ** 62, top, -1, top - 1, top + 1], dtype=np.int64)
+    got, want, dev_tables = _check(harp, ctx, p, cands, caps, "caps at the limit")
+    assert list(want.status) == [0, 2, 2, 2, 0, 1, 0, 2]
+    splits = oracle.plan_batch(oracle.build_tables(p), cands).splits       # each candidate's own min-max cuts
+    wu, b, t, st = oracle.score_h1f1b(oracle.build_tables(p), cands, splits, caps)
+    gwu, gb, gt, gst = _score(harp, ctx, dev_tables, cands, splits, caps)
+    assert (gst == st).all() and (gwu == wu).all() and (gb == b).all() and (gt == t).all()
+    assert list(st) == [0, 2, 2, 2, 0, 1, 0, 2]
+    # a candidate the memory bounds reject keeps INVALID under such a cap (32-bit path: rejected by the pre-pass)
+    tight = simple_problem([5] * 6, M=2, ndev=(4,), tp=(1,), params=[10] * 6, mem=[15])
+    tc = cands_from_lists([same_slot(2), same_slot(2)])
+    _, tw, _ = _check(harp, ctx, tight, tc, np.array([100, 2 ** 63 - 1], dtype=np.int64), "rejected by memory")
+    assert list(tw.status) == [1, 2]
+
+
 def test_h1f1b_full_stress_batch_properties(harp, ctx):
     """The whole stress batch at the caps the exact search found, in the launch configuration the
     benchmark times: what must hold for every candidate whatever its size."""

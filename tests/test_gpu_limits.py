@@ -155,6 +155,30 @@ def test_argument_errors_of_the_newer_entry_points(harp, ctx):
     assert (out.to_host().status == -7).all()          # nothing ran
 
 
+def test_device_index_larger_than_32_bits_is_refused(harp, ctx):
+    """The kernels with a device index address (devices + 1) x (L + 1) states per stage with 32-bit
+    products: a problem beyond that is refused on the host with a shape error (it would need tens of
+    GB of workspace anyway), never run with a wrapped index."""
+    import torch
+    L = 60000
+    p = simple_problem(np.ones(L, dtype=np.int64), M=2, G=1, ndev=(40000,), tp=(1,))
+    tables = harp.Tables(ctx, p)
+    orders = W.Orderings(1, 1, 2, np.array([2], dtype=np.int32), np.array([1], dtype=np.int32),
+                         np.zeros((1, 1), dtype=np.int32))
+    do = harp.DeviceOrderings(ctx, orders)
+    out = harp.DevicePlans(ctx, 1, 2)
+    out.poison()
+    sg = torch.zeros((1, 2), dtype=torch.int32, device=ctx.device)
+    ws = torch.empty(1 << 20, dtype=torch.uint8, device=ctx.device)
+    for call in (lambda: harp.harp_plan_mesh_batch(ctx, tables, do, out, sg, sg.clone(), ws),
+                 lambda: harp.harp_plan_mesh_exact_batch(ctx, tables, do, out, sg, sg.clone(), ws)):
+        with pytest.raises(harp.HarpError) as e:
+            call()
+        assert e.value.code == harp.ERR_SHAPE and "2^31" in str(e.value)
+    torch.cuda.synchronize()
+    assert (out.to_host().status == -7).all()
+
+
 def test_calls_on_a_caller_stream_and_back_to_back(harp, ctx):
     """Every entry point enqueues on the stream it is given; calls queued back to back on one stream
     with one workspace (each after the other, no host synchronisation in between) give the same

@@ -225,6 +225,12 @@ def test_mesh_h1f1b_full_recurrence(harp, ctx):
         orders = W.make_orderings(p, seed, 5, 1, max(top, p.G), 0, 6)
         caps = np.array([0, 1, 2 ** 31 - 1, 2 ** 31, 2 ** 32 + 5, 2 ** 40], dtype=np.int64)[:orders.C]
         _check_h1(harp, ctx, p, orders, caps, "edge caps, seed %d" % seed)
+    # caps beyond the accepted range: INVALID, as for the candidate form
+    w = W.make("tiny")
+    orders = W.make_orderings(w.problem, w.seed, w.config_id, w.problem.G, w.S_max, 0, 4)
+    caps = np.array([2 ** 47 - 1, 2 ** 47, 2 ** 63 - 1, 10 ** 6], dtype=np.int64)
+    _, want = _check_h1(harp, ctx, w.problem, orders, caps, "caps at the limit")
+    assert list(want.status[1:3]) == [oracle.INVALID, oracle.INVALID] and want.status[0] != oracle.INVALID
     for name, n in (("tiny", 16), ("llama7b", 128), ("llama70b", 48)):
         w = W.make(name)
         orders = W.make_orderings(w.problem, w.seed, w.config_id, w.problem.G, w.S_max, 0, n)

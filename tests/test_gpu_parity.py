@@ -468,6 +468,56 @@ def test_stress_full_batch_properties_and_samples(harp, ctx):
     assert (int(bt.item()), int(bi.item())) == oracle.argmin_batch(got.iter_time, got.status)
 
 
+@pytest.fixture(scope="module")
+def stress_full(harp, ctx):
+    """The whole stress batch planned once on each path, in the launch configuration bench.py times."""
+    import torch
+    w = W.make("stress")
+    cands = w.candidates()
+    tables = harp.Tables(ctx, w.problem)
+    dc = harp.DeviceCandidates(ctx, cands)
+    out = harp.DevicePlans(ctx, dc.C, dc.S_max)
+    ws = harp.plan_workspace(ctx, tables, dc)
+    plans = {}
+    for path in (harp.PATH_FAST32, harp.PATH_GENERIC):
+        out.poison()
+        ctx.set_plan_path(path)
+        try:
+            harp.harp_plan_batch(ctx, tables, dc, out, ws)
+            torch.cuda.synchronize()
+        finally:
+            ctx.set_plan_path(harp.PATH_AUTO)
+        plans[path] = out.to_host()
+    return w, cands, plans
+
+
+def test_stress_full_batch_both_paths_agree(harp, stress_full):
+    """All 262,144 candidates: the int64 kernel (dense scans, no bands, no index) and the 32-bit
+    kernel share no device code beyond the scorer and must give the same plans."""
+    _, _, plans = stress_full
+    assert_plans_equal(plans[harp.PATH_FAST32], plans[harp.PATH_GENERIC], "stress, 32-bit against int64 path")
+
+
+@pytest.mark.parametrize("quarter", range(4))
+def test_stress_full_batch_against_oracle(harp, stress_full, quarter):
+    """All 262,144 candidates of the stress batch against the oracle, a quarter of the batch per case
+    (about 25 s of oracle time on 16 host threads each).  Includes the candidates that pass the
+    memory bounds of the pre-pass and are found infeasible by the recurrence."""
+    w, cands, plans = stress_full
+    n = w.C // 4
+    lo, hi = quarter * n, (quarter + 1) * n if quarter < 3 else w.C
+    want = oracle_plan_threaded(oracle.build_tables(w.problem), cands.slice(lo, hi))
+    got = plans[harp.PATH_FAST32]
+
+    class _Sub:
+        pass
+    sub = _Sub()
+    for name in ("status", "splits", "dev_first", "bottleneck", "iter_time"):
+        setattr(sub, name, getattr(got, name)[lo:hi])
+    assert_plans_equal(sub, want, "stress candidates %d..%d" % (lo, hi))
+    assert (want.status == oracle.INFEASIBLE).any() and (want.status == oracle.OK).any()
+
+
 def test_case_study_of_the_paper_on_the_gpu(harp, ctx):
     """Section 2.2, Table 1 (tests/golden/case_study_shares.txt): the kernels give the oracle's plans
     for the table's two pipelines, whose 128-layer stage sizes follow the submeshes' FLOP shares."""
