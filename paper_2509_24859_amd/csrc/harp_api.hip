@@ -326,7 +326,6 @@ int harp_build_segment_costs(harp_ctx *ctx, const harp_problem *p, void *table_b
 
     const int64_t tp_max = p->tp_degrees[p->n_tp - 1];
     const int64_t num_mul = int64_t(p->ar_count) * 2 * (tp_max - 1);
-    t->lim.elem_max = ((int64_t(1) << 62) - 1) / p->L;
     t->lim.act_max = num_mul > 0 ? INT64_MAX / num_mul : INT64_MAX;
     t->lim.bw_max = INT64_MAX / tp_max;
     t->lim.mem_max = INT64_MAX / tp_max;

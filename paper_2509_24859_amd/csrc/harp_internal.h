@@ -64,9 +64,9 @@ struct PlansDev {
     int32_t *status;
 };
 
-// limits derived on the host for the element-wise magnitude guard
+// limits derived on the host for the magnitude guard (products that must stay inside int64; sums are
+// checked where they are formed)
 struct BuildLimits {
-    int64_t elem_max;   // every time/byte input and every all-reduce time must be <= this
     int64_t act_max;    // act_bytes bound so that the all-reduce numerator fits
     int64_t bw_max;     // bandwidth bound so that tp * bw fits
     int64_t mem_max;    // device memory bound so that tp * mem fits

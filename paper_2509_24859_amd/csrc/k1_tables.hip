@@ -35,6 +35,17 @@ __device__ __forceinline__ int64_t ceil_div_inv(int64_t a, int64_t b, double inv
     return q + (r != 0 ? 1 : 0);
 }
 
+// Sum of two non-negative 64-bit values, with the sticky overflow note of the table build: `over`
+// collects the upper halves of every sum formed, so its top bit says that some running sum reached
+// 2^63.  The first sum to do so has operands below 2^63 and cannot wrap, and since all terms are
+// non-negative a partial sum reaches 2^63 exactly when its row's total does: the verdict is the exact
+// one, whatever the order in which the scan adds.
+__device__ __forceinline__ int64_t add_checked(int64_t a, int64_t b, unsigned int &over) {
+    const unsigned long long s = (unsigned long long)a + (unsigned long long)b;
+    over |= (unsigned int)(s >> 32);
+    return (int64_t)s;
+}
+
 // Value of element l of table row r, with the checks that belong to the inputs it touches.
 struct RowSource {
     const int64_t *a;     // first addend
@@ -79,27 +90,23 @@ __device__ __forceinline__ int64_t row_value(const RowSource &s, int64_t l, cons
     if (x < 0) { bad = 1; x = 0; }
     if (s.is_ar) {
         if ((unsigned long long)x > act_seen) act_seen = (unsigned long long)x;
-        if (x > lim.act_max || x > lim.elem_max) { ovf = 1; x = 0; }
+        if (x > lim.act_max) { ovf |= 0x80000000u; x = 0; }     // the numerator ar_count 2 (tp - 1) act would leave int64
         if (s.num_mul == 0) return 0;
-        int64_t v = ceil_div_inv(s.num_mul * x, s.den, s.inv_den);
-        if (v > lim.elem_max) { ovf = 1; v = 0; }
-        return v;
+        return ceil_div_inv(s.num_mul * x, s.den, s.inv_den);
     }
-    if (x > lim.elem_max) { ovf = 1; x = 0; }
     if (s.b) {
         int64_t y = s.b[l];
         if (y < 0) { bad = 1; y = 0; }
-        if (y > lim.elem_max) { ovf = 1; y = 0; }
-        x += y;
+        x = add_checked(x, y, ovf);
     }
     return x;
 }
 
-__device__ __forceinline__ int64_t wave_inclusive_scan(int64_t v, int lane) {
+__device__ __forceinline__ int64_t wave_inclusive_scan(int64_t v, int lane, unsigned int &over) {
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) {
         int64_t up = __shfl_up(v, d, 64);
-        if (lane >= d) v += up;
+        if (lane >= d) v = add_checked(v, up, over);
     }
     return v;
 }
@@ -107,7 +114,7 @@ __device__ __forceinline__ int64_t wave_inclusive_scan(int64_t v, int lane) {
 __device__ __forceinline__ void report(BuildHeader *h, unsigned int bad, unsigned int ovf,
                                        unsigned long long act_seen, bool track_act) {
     if (__any(bad) && (threadIdx.x & 63) == 0) atomicOr(&h->bad_arg, 1u);
-    if (__any(ovf) && (threadIdx.x & 63) == 0) atomicOr(&h->overflow, 1u);
+    if (__any(ovf >> 31) && (threadIdx.x & 63) == 0) atomicOr(&h->overflow, 1u);
     if (track_act) atomicMax(&h->max_act, act_seen);
 }
 
@@ -124,7 +131,7 @@ __global__ __launch_bounds__(kScanThreads) void k1_chunk_sums(TablesDev tb, Buil
         if (base + q < tb.L) sum += row_value(src, base + q, lim, bad, ovf, act_seen);
     __shared__ int64_t part[kScanThreads / 64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    int64_t inc = wave_inclusive_scan(sum, lane);
+    int64_t inc = wave_inclusive_scan(sum, lane, ovf);
     if (lane == 63) part[wave] = inc;
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -132,7 +139,8 @@ __global__ __launch_bounds__(kScanThreads) void k1_chunk_sums(TablesDev tb, Buil
         for (int w = 0; w < kScanThreads / 64; ++w) t += part[w];
         tb.chunk_sums[int64_t(r) * n_chunks + chunk] = t;
     }
-    // values are checked again by the last launch; nothing to report here
+    // values and sums inside a chunk are checked again by the last launch, sums across chunks by
+    // the next one; nothing to report here
 }
 
 // Launch 2: exclusive scan of the chunk sums of each row, in place.
@@ -141,21 +149,24 @@ __global__ __launch_bounds__(kScanThreads) void k1_scan_chunk_sums(TablesDev tb,
     __shared__ int64_t part[kScanThreads / 64];
     __shared__ int64_t carry_s;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    unsigned int over = 0;
     if (threadIdx.x == 0) carry_s = 0;
     __syncthreads();
     for (int base = 0; base < n_chunks; base += kScanThreads) {
         int idx = base + threadIdx.x;
         int64_t v = idx < n_chunks ? row[idx] : 0;
-        int64_t inc = wave_inclusive_scan(v, lane);
+        int64_t inc = wave_inclusive_scan(v, lane, over);
         if (lane == 63) part[wave] = inc;
         __syncthreads();
         int64_t off = carry_s;
-        for (int w = 0; w < wave; ++w) off += part[w];
-        if (idx < n_chunks) row[idx] = off + inc - v;
+        for (int w = 0; w < wave; ++w) off = add_checked(off, part[w], over);
+        const int64_t upto = add_checked(off, inc, over);       // the last thread's is the row's total so far
+        if (idx < n_chunks) row[idx] = upto - v;
         __syncthreads();
-        if (threadIdx.x == kScanThreads - 1) carry_s = off + inc;
+        if (threadIdx.x == kScanThreads - 1) carry_s = upto;
         __syncthreads();
     }
+    report(tb.header, 0, over, 0, false);
 }
 
 // Launch 3: scan each chunk, add the chunk's offset, write the table row (entry i = l + 1).
@@ -170,21 +181,21 @@ __global__ __launch_bounds__(kScanThreads) void k1_scan_rows(TablesDev tb, Build
 #pragma unroll
     for (int q = 0; q < kScanItems; ++q) {
         v[q] = (base + q < tb.L) ? row_value(src, base + q, lim, bad, ovf, act_seen) : 0;
-        sum += v[q];
+        sum = add_checked(sum, v[q], ovf);
     }
     __shared__ int64_t part[kScanThreads / 64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    int64_t inc = wave_inclusive_scan(sum, lane);
+    int64_t inc = wave_inclusive_scan(sum, lane, ovf);
     if (lane == 63) part[wave] = inc;
     __syncthreads();
     int64_t run = (n_chunks > 1) ? tb.chunk_sums[int64_t(r) * n_chunks + chunk] : 0;
-    for (int w = 0; w < wave; ++w) run += part[w];
-    run += inc - sum;
+    for (int w = 0; w < wave; ++w) run = add_checked(run, part[w], ovf);
+    run = add_checked(run, inc - sum, ovf);
     int64_t *out = tb.rows + int64_t(r) * tb.pitch;
     if (chunk == 0 && threadIdx.x == 0) out[0] = 0;
 #pragma unroll
     for (int q = 0; q < kScanItems; ++q) {
-        run += v[q];
+        run = add_checked(run, v[q], ovf);
         if (base + q < tb.L) out[base + q + 1] = run;
     }
     unsigned long long wave_act = act_seen;
@@ -227,7 +238,7 @@ __device__ __forceinline__ ActRun load_act_run(const TablesDev &tb, const BuildL
         int64_t x = (base + q < tb.L) ? tb.act_bytes[base + q] : 0;
         if (x < 0) { bad = 1; x = 0; }
         if ((unsigned long long)x > act_seen) act_seen = (unsigned long long)x;
-        if (x > lim.act_max || x > lim.elem_max) { ovf = 1; x = 0; }
+        if (x > lim.act_max) { ovf |= 0x80000000u; x = 0; }
         a.x[q] = x;
         a.narrow = a.narrow && x < (int64_t(1) << 32);
         a.xd[q] = (double)(uint32_t)x;
@@ -263,17 +274,15 @@ __device__ __forceinline__ int64_t ar_value(const ArRow &r, const ActRun &a, int
     } else {
         v = ceil_div_inv(r.mul * a.x[q], r.den, r.inv);
     }
-    if (v > lim.elem_max) { ovf = 1; v = 0; }
     return v;
 }
 
 // The common case of an all-reduce row, all four values at once: narrow operands (see ar_row), a
-// divisor not below the multiplier (so the quotient stays below 2^32) and an element bound of at
-// least 2^32 (so no value can trip it).  ceil(p / d) = floor((p + d - 1) / d); the sum p + d - 1 is
+// divisor not below the multiplier (so the quotient stays below 2^32).  ceil(p / d) = floor((p + d - 1) / d); the sum p + d - 1 is
 // exact in a double, the product with 1 / d is within 1 of the quotient, and the exact remainder
 // from one fused multiply-add corrects it.
 __device__ __forceinline__ bool ar_tight(const ArRow &r, bool all_narrow, const BuildLimits &lim) {
-    return r.fast && all_narrow && r.den >= r.mul && lim.elem_max >= (int64_t(1) << 32);
+    return r.fast && all_narrow && r.den >= r.mul;
 }
 
 __device__ __forceinline__ void ar_values_tight(const ArRow &r, const ActRun &a, uint32_t v[kWaveItems]) {
@@ -431,17 +440,17 @@ __global__ __launch_bounds__(kScanThreads) void k1_long_scan(TablesDev tb, Build
 #pragma unroll
                 for (int q = 0; q < kWaveItems; ++q) {
                     v[q] = long_value(tb, src, arr, a, q, base, lim, bad, ovf);
-                    sum += v[q];
+                    sum = add_checked(sum, v[q], ovf);
                 }
                 same_mul = -1;
             }
-            const int64_t inc = wave_inclusive_scan(sum, lane);
-            int64_t acc = start + inc - sum;
+            const int64_t inc = wave_inclusive_scan(sum, lane, ovf);
+            int64_t acc = add_checked(start, inc - sum, ovf);
             // a lane holds four consecutive entries; passing them through the wavefront's LDS tile
             // turns four 8-byte stores at a 32-byte stride into four fully contiguous 512-byte stores
 #pragma unroll
             for (int q = 0; q < kWaveItems; ++q) {
-                acc += v[q];
+                acc = add_checked(acc, v[q], ovf);
                 tile[lane * kWaveItems + q] = acc;
             }
         }
@@ -474,7 +483,9 @@ __global__ __launch_bounds__(256) void k1_finalize(TablesDev tb, BuildLimits lim
         int64_t b = tb.bw[e];
         if (b < 1) atomicOr(&bad_s, 1u);
         else {
-            if (b > lim.bw_max) atomicOr(&ovf_s, 1u);
+            // tp * bandwidth is formed for a group's own link only (the all-reduce time), degrees above 1
+            const bool own = e / tb.G == e % tb.G;
+            if (own && tb.n_tp > 1 && b > lim.bw_max) atomicOr(&ovf_s, 1u);
             atomicMin(&min_bw_s, (unsigned long long)b);
         }
     }
@@ -502,7 +513,7 @@ __global__ __launch_bounds__(256) void k1_finalize(TablesDev tb, BuildLimits lim
     if (groups_ok) {
         for (int q = threadIdx.x; q < tb.G * tb.n_tp; q += blockDim.x) {
             int g = q / tb.n_tp, k = q - g * tb.n_tp;
-            // sums are bounded by L * elem_max <= 2^62 each, so these additions cannot wrap
+            // both totals are below 2^63 unless the build has already noted an overflow
             unsigned long long work = (unsigned long long)tb.PF(tb.group_type[g])[L];
             unsigned long long ar = (unsigned long long)tb.PR(g, k)[L];
             unsigned long long whole = work + ar;

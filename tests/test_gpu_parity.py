@@ -154,6 +154,79 @@ def test_build_verdicts(harp, ctx):
     assert not t.fast32                      # times beyond 32 bits: only the int64 path
 
 
+def _verdict_cases():
+    """Problems on both sides of every magnitude limit (all sums, products and times that must stay
+    inside int64 or below 2^47 us): (label, problem)."""
+    top = (1 << 63) - 1
+    cases = []
+
+    def add(label, p):
+        cases.append((label, p))
+    # largest stage time any plan can see: below 2^47
+    add("time 2^47 - 1", simple_problem([1 << 46, (1 << 46) - 1], ndev=(2,)))
+    add("time 2^47", simple_problem([1 << 46, 1 << 46], ndev=(2,)))
+    # a long sequence (chunk-major build): the iteration-time bound worst x (3 L + M) decides
+    long_costs = np.zeros(300001, dtype=np.int64)
+    long_costs[123456] = ((1 << 63) - 1) // (3 * 300001 + 1)
+    add("one huge operator among 300,001, at the limit", simple_problem(long_costs, ndev=(2,)))
+    long_costs = long_costs.copy()
+    long_costs[299999] = 1
+    add("one huge operator among 300,001, beyond", simple_problem(long_costs, ndev=(2,)))
+    # iteration time: worst x (3 L + M) inside int64
+    w = 1 << 40
+    m_ok = top // w - 3 * 2
+    add("iteration time at the limit", simple_problem([w - 1, 1], M=int(m_ok), ndev=(2,)))
+    add("iteration time beyond", simple_problem([w - 1, 1], M=int(m_ok) + 1, ndev=(2,)))
+    # parameter bytes: the running sum may pass 2^62 but not 2^63
+    add("parameters 1.5 x 2^62", simple_problem([1, 1], ndev=(2,), params=[3 << 60, 3 << 60]))
+    add("parameters 2^63", simple_problem([1, 1], ndev=(2,), params=[1 << 62, 1 << 62]))
+    add("parameters 2^63 over chunks", simple_problem(np.ones(3000, dtype=np.int64), ndev=(2,),
+                                                      params=[1 << 62] + [0] * 2998 + [1 << 62]))
+    add("parameters 2^63 - 1 over chunks", simple_problem(np.ones(3000, dtype=np.int64), ndev=(2,),
+                                                          params=[1 << 62] + [0] * 2998 + [(1 << 62) - 1]))
+    # memory need with the in-flight count: PP + min(M, L) PS
+    ps = 1 << 40
+    add("need at the limit", simple_problem([1, 1], M=8, ndev=(2,), params=[top - 2 * 2 * ps, 0], stash=[ps, ps]))
+    add("need beyond", simple_problem([1, 1], M=8, ndev=(2,), params=[top - 2 * 2 * ps + 1, 0], stash=[ps, ps]))
+    # degree x device memory
+    add("tp x memory at the limit", simple_problem([1, 1], ndev=(8,), tp=(1, 8), mem=[top // 8]))
+    add("tp x memory beyond", simple_problem([1, 1], ndev=(8,), tp=(1, 8), mem=[top // 8 + 1]))
+    # all-reduce numerator ar_count 2 (tp - 1) act, with links fast enough that every time stays small
+    fast = [[1 << 50]]
+    lim = top // (4 * 2 * 7)
+    add("all-reduce numerator at the limit", simple_problem([1, 1], ndev=(8,), tp=(1, 8), act=[lim, 5], bw=fast))
+    add("all-reduce numerator beyond", simple_problem([1, 1], ndev=(8,), tp=(1, 8), act=[lim + 1, 5], bw=fast))
+    add("large act without tensor parallelism", simple_problem([1, 1], ndev=(8,), tp=(1,), act=[lim + 1, 5], bw=fast))
+    # degree x bandwidth of a group's own link; other links may be as fast as they like
+    two = lambda own, other: [[own, other], [other, own]]
+    add("tp x own link at the limit", simple_problem([1, 1], G=2, ndev=(8, 8), tp=(1, 8), act=[9, 9], bw=two(top // 8, 7)))
+    add("tp x own link beyond", simple_problem([1, 1], G=2, ndev=(8, 8), tp=(1, 8), act=[9, 9], bw=two(top // 8 + 1, 7)))
+    add("other links beyond int64 / tp", simple_problem([1, 1], G=2, ndev=(8, 8), tp=(1, 8), act=[9, 9], bw=two(7, top)))
+    add("own link beyond int64 / tp without tensor parallelism",
+        simple_problem([1, 1], G=2, ndev=(8, 8), tp=(1,), act=[9, 9], bw=two(top, 7)))
+    return cases
+
+
+def test_build_verdicts_are_the_oracles_at_every_limit(harp, ctx):
+    """The library's verdict on magnitudes equals the oracle's 128-bit check on both sides of every
+    limit, and accepted problems give the oracle's tables."""
+    seen = set()
+    for label, p in _verdict_cases():
+        rc = oracle.Tables(p).rc
+        seen.add(rc)
+        if rc == 0:
+            tables = harp.Tables(ctx, p)
+            want = oracle.build_tables(p)
+            PF, PP, PS, PR = tables.host_copies()
+            assert (PF == want.PF).all() and (PP == want.PP).all() and (PS == want.PS).all() and (PR == want.PR).all(), label
+        else:
+            assert rc == oracle.ERR_OVERFLOW, label
+            with pytest.raises(harp.HarpError) as e:
+                harp.Tables(ctx, p)
+            assert e.value.code == harp.ERR_OVERFLOW, label
+    assert seen == {0, oracle.ERR_OVERFLOW}
+
+
 # ------------------------------------------------------------------ planner (a2-a4)
 
 def test_plan_tiny_all_paths(harp, ctx):
