@@ -2,9 +2,11 @@
 //
 // Paper section 5.2.3 (eq. dp_general with the submesh of every stage fixed by the candidate,
 // constraints (i)-(iii)) evaluated exactly as stated: for every stage s and every end cut i, all
-// previous cuts j are tried.  One workgroup works on one candidate at a time; one wavefront owns
-// one DP cell and its 64 lanes stride over j, then reduce (value, j) lexicographically across the
-// wave, which keeps the lowest j among equal values.  Rows of D and the back-pointers live in a
+// previous cuts j that can matter are tried.  One workgroup works on one candidate at a time; one lane
+// owns one DP cell of the current stage and walks j downwards from i - 1 until the stage no longer
+// fits in memory or its time alone rules every lower j out, keeping the lowest j among equal values
+// (no reachability bands, no feasibility index, no 32-bit rows: this path shares none of the fast
+// kernel's pruning).  Rows of D and the back-pointers live in a
 // per-workgroup slice of the caller's workspace (L2-resident at the sizes of interest).  This path
 // accepts any degree (division when it is not a power of two) and any L up to 65535; the 32-bit
 // path in k2_fast.hip is the fast one.
@@ -39,87 +41,82 @@ __device__ __forceinline__ GenericSlice generic_slice(unsigned char *ws, size_t 
 // (section 5.2.3 with constraints (i), (ii)), D[s+1][i] = min_j D[s][j] + time + 2 comm over
 // time <= cap, cells with comm > cap unreachable.  Both keep the lowest j among equal values.
 // Returns the row that holds D[S][.].
+// Sequences of up to kGenericLdsL operators keep the six rows a stage reads (the two memory sums, the
+// stage's compute and all-reduce sums, the two DP rows) in LDS; longer ones read them from global
+// memory (L2).  Same arithmetic either way.
+constexpr int kGenericLdsL = 1279;      // 6 x 1280 x 8 B = 60 KB
+
+size_t generic_lds_bytes(int L) { return L <= kGenericLdsL ? size_t(6) * (L + 1) * sizeof(int64_t) : 0; }
+
 template <bool kCapped>
 __device__ __forceinline__ const int64_t *generic_pass(const TablesDev &tb, const SlotInfo &slots, int S,
                                                        const GenericSlice &w, int64_t time_cap) {
+    extern __shared__ __align__(16) unsigned char generic_lds[];
     const int L = tb.L;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const bool rows_in_lds = L <= kGenericLdsL;
+    int64_t *stage = reinterpret_cast<int64_t *>(generic_lds);       // [6][L + 1] when rows_in_lds
     const int64_t *PP = tb.PP(), *PS = tb.PS();
-    for (int i = threadIdx.x; i <= L; i += kThreads) w.D0[i] = (i == 0) ? 0 : kInf;
-    __syncthreads();
     int64_t *Dp = w.D0, *Dn = w.D1;
+    __syncthreads();                          // an earlier pass is done with the rows
+    if (rows_in_lds) {
+        for (int i = threadIdx.x; i <= L; i += kThreads) { stage[i] = PP[i]; stage[(L + 1) + i] = PS[i]; }
+        PP = stage;
+        PS = stage + (L + 1);
+        Dp = stage + 4 * (L + 1);
+        Dn = stage + 5 * (L + 1);
+    }
+    for (int i = threadIdx.x; i <= L; i += kThreads) Dp[i] = (i == 0) ? 0 : kInf;
+    __syncthreads();
     for (int s = 0; s < S; ++s) {
         const int g = slots.g[s], k = slots.k[s];
         const int64_t tp = tb.tp[k];
         const int shift = tb.tp_shift[k];
         const int t = tb.group_type[g];
         const int64_t *pf = tb.PF(t), *pr = tb.PR(g, k);
+        if (rows_in_lds) {
+            int64_t *spf = stage + 2 * (L + 1), *spr = stage + 3 * (L + 1);
+            for (int i = threadIdx.x; i <= L; i += kThreads) { spf[i] = pf[i]; spr[i] = pr[i]; }
+            __syncthreads();                  // (the barrier that ended the previous stage lets these be overwritten)
+            pf = spf;
+            pr = spr;
+        }
         const int64_t n_inflight = (S - s) < tb.M ? (S - s) : tb.M;
         const int64_t cap = tp * tb.type_mem[t];
         const bool last = (s == S - 1);
         const int64_t link = last ? 1 : tb.bw[int64_t(g) * tb.G + slots.g[s + 1]];
         const int i_lo = last ? L : s + 1, i_hi = L - (S - 1 - s);
         uint16_t *arg_row = w.arg + size_t(s) * (L + 1);
-        for (int i = i_lo + wave; i <= i_hi; i += kWaves) {
+        for (int i = i_lo + int(threadIdx.x); i <= i_hi; i += kThreads) {
             const int64_t cut = last ? 0 : (tb.act_bytes[i - 1] + link - 1) / link;
             const int64_t pfi = pf[i], pri = pr[i], ppi = PP[i], psi = PS[i];
             int64_t best = kInf;
-            int best_j = INT32_MAX;
+            int best_j = 0;
             if (!kCapped || cut <= time_cap) {
-                // previous cuts in runs of 64 from i - 1 downwards.  Both the memory need and the
-                // stage time never decrease as j moves down, so once the lowest j of a run does not
-                // fit, or its time alone is above the cap (capped form) or above the best value so
-                // far (min-max form: strictly, an equal value at a lower j still has to be seen),
-                // no lower j can be taken or can match, and the scan stops.
-                for (int top = i - 1; top >= s; top -= 64) {
-                    const int j = top - lane;
-                    if (j >= s) {
-                        const int64_t dj = Dp[j];
-                        const int64_t need = (ppi - PP[j]) + n_inflight * (psi - PS[j]);
-                        if (dj != kInf && need <= cap) {
-                            const int64_t work = pfi - pf[j];
-                            const int64_t comp = shift >= 0 ? (work + tp - 1) >> shift : (work + tp - 1) / tp;
-                            const int64_t time = comp + (pri - pr[j]);
-                            if (kCapped) {
-                                if (time <= time_cap && dj + time <= best) { best = dj + time; best_j = j; }
-                            } else {
-                                int64_t val = time > dj ? time : dj;
-                                val = val > cut ? val : cut;
-                                if (val <= best) { best = val; best_j = j; }       // j falls: the lower j keeps a tie
-                            }
-                        }
-                    }
-                    const int low = top - 63 > s ? top - 63 : s;                    // lowest j of this run
-                    if (low == s) break;
-                    const int64_t need_low = (ppi - PP[low]) + n_inflight * (psi - PS[low]);
-                    if (need_low > cap) break;
-                    const int64_t work_low = pfi - pf[low];
-                    const int64_t time_low = (shift >= 0 ? (work_low + tp - 1) >> shift : (work_low + tp - 1) / tp) +
-                                             (pri - pr[low]);
+                // previous cuts from i - 1 downwards.  Both the memory need and the stage time never
+                // decrease as j moves down, so once a cut does not fit, or its time alone is above
+                // the cap (capped form) or above the best value so far (min-max form: strictly, an
+                // equal value at a lower j still has to be seen), no lower j can be taken or can
+                // match, and the scan stops.
+                for (int j = i - 1; j >= s; --j) {
+                    const int64_t need = (ppi - PP[j]) + n_inflight * (psi - PS[j]);
+                    if (need > cap) break;
+                    const int64_t work = pfi - pf[j];
+                    const int64_t comp = shift >= 0 ? (work + tp - 1) >> shift : (work + tp - 1) / tp;
+                    const int64_t time = comp + (pri - pr[j]);
+                    if (time > (kCapped ? time_cap : best)) break;
+                    const int64_t dj = Dp[j];
+                    if (dj == kInf) continue;
                     if (kCapped) {
-                        if (time_low > time_cap) break;
+                        if (dj + time <= best) { best = dj + time; best_j = j; }   // j falls: the lower j keeps a tie
                     } else {
-                        // the best value of the whole wave so far decides, so it is gathered here
-#pragma unroll
-                        for (int d = 32; d >= 1; d >>= 1) {
-                            const int64_t ov = __shfl_xor(best, d, 64);
-                            const int oj = __shfl_xor(best_j, d, 64);
-                            if (ov < best || (ov == best && oj < best_j)) { best = ov; best_j = oj; }
-                        }
-                        if (time_low > best) break;
+                        int64_t val = time > dj ? time : dj;
+                        val = val > cut ? val : cut;
+                        if (val <= best) { best = val; best_j = j; }
                     }
                 }
             }
-#pragma unroll
-            for (int d = 32; d >= 1; d >>= 1) {
-                const int64_t ov = __shfl_xor(best, d, 64);
-                const int oj = __shfl_xor(best_j, d, 64);
-                if (ov < best || (ov == best && oj < best_j)) { best = ov; best_j = oj; }
-            }
-            if (lane == 0) {
-                Dn[i] = (kCapped && best != kInf) ? best + 2 * cut : best;
-                arg_row[i] = (uint16_t)(best == kInf ? 0 : best_j);
-            }
+            Dn[i] = (kCapped && best != kInf) ? best + 2 * cut : best;
+            arg_row[i] = (uint16_t)best_j;
         }
         __syncthreads();
         int64_t *tmp = Dp; Dp = Dn; Dn = tmp;
@@ -456,13 +453,13 @@ size_t plan_generic_ws_per_group(int L, int S_max) {
 
 void launch_plan_generic(const TablesDev &tb, const CandDev &cd, const PlansDev &out, void *ws,
                          int n_groups, hipStream_t st) {
-    hipLaunchKernelGGL(k2_generic, dim3(n_groups), dim3(kThreads), 0, st, tb, cd, out,
+    hipLaunchKernelGGL(k2_generic, dim3(n_groups), dim3(kThreads), generic_lds_bytes(tb.L), st, tb, cd, out,
                        static_cast<unsigned char *>(ws), plan_generic_ws_per_group(tb.L, cd.S_max));
 }
 
 void launch_plan_generic_exact(const TablesDev &tb, const CandDev &cd, const PlansDev &out, int32_t *n_passes,
                                void *ws, int n_groups, hipStream_t st) {
-    hipLaunchKernelGGL(k2_generic_exact, dim3(n_groups), dim3(kThreads), 0, st, tb, cd, out, n_passes,
+    hipLaunchKernelGGL(k2_generic_exact, dim3(n_groups), dim3(kThreads), generic_lds_bytes(tb.L), st, tb, cd, out, n_passes,
                        static_cast<unsigned char *>(ws), plan_generic_ws_per_group(tb.L, cd.S_max));
 }
 
