@@ -68,9 +68,10 @@ namespace {
 // Every probe of the searches is a dependent load and every candidate walks its slot list twice,
 // so everything the loops touch is staged in LDS first: the running sums PP and PS, the memory
 // cap of every (group, degree), and the workgroup's slot lists, read from global memory once,
-// coalesced, and stored slot-major so that the per-thread walks are conflict-free.  Bands are
-// written candidate-major ([c][s]): the wavefront that later plans candidate c reads its row with
-// one coalesced load.
+// coalesced, and stored slot-major so that the per-thread walks are conflict-free.  The two chains
+// leave their limits in LDS tiles as well, and the workgroup writes the bands of its candidates as
+// one contiguous run, candidate-major ([c][s]): the wavefront that later plans candidate c reads
+// its row with one coalesced load.
 //
 // The workgroups behind the candidates' ones build the feasibility index, one row each.
 constexpr int kBandCapTable = 1024;     // caps kept in LDS when G * n_tp is at most this
@@ -120,8 +121,11 @@ __global__ __launch_bounds__(256) void k2_band(TablesDev tb, CandDev cd, int *co
     }
     int64_t *PS = PP + (L + 1);                              // [L + 1]
     int64_t *caps = PS + (L + 1);                            // [G * n_tp] when caps_in_lds
-    uint16_t *slots = reinterpret_cast<uint16_t *>(caps + (caps_in_lds ? tb.G * tb.n_tp : 0));  // [S_max][pitch]
+    // slot codes, replaced stage by stage by the lower band limits B[s]; and the upper limits F[s]
+    uint16_t *slots = reinterpret_cast<uint16_t *>(caps + (caps_in_lds ? tb.G * tb.n_tp : 0));  // [S_max + 1][pitch]
+    uint16_t *ftile = slots + (S_max + 1) * pitch;                                               // [S_max + 1][pitch]
     const int c0 = blockIdx.x * nthreads;
+    const int n_here = (C - c0) < nthreads ? (C - c0) : nthreads;
     {
         const int64_t *gp = tb.PP(), *gs = tb.PS();
         for (int i = threadIdx.x; i <= L; i += nthreads) { PP[i] = gp[i]; PS[i] = gs[i]; }
@@ -131,7 +135,6 @@ __global__ __launch_bounds__(256) void k2_band(TablesDev tb, CandDev cd, int *co
                 caps[q] = int64_t(tb.tp[k]) * tb.type_mem[tb.group_type[g]];
             }
         // slot lists of this workgroup's candidates: (group << 3) | degree index, or kBadSlot
-        const int n_here = (C - c0) < nthreads ? (C - c0) : nthreads;
         const int32_t *grp = cd.cand_group + int64_t(c0) * S_max;
         const int32_t *tpv = cd.cand_tp + int64_t(c0) * S_max;
         for (int idx = threadIdx.x; idx < n_here * S_max; idx += nthreads) {
@@ -143,10 +146,9 @@ __global__ __launch_bounds__(256) void k2_band(TablesDev tb, CandDev cd, int *co
     }
     __syncthreads();
     const int cl = threadIdx.x, c = c0 + cl;
-    if (c >= C) return;
-    const int S = cd.cand_S[c];
+    const bool mine = c < C;
+    const int S = mine ? cd.cand_S[c] : 0;
     const int R = L - S + 1;
-    uint32_t *my = bands + int64_t(c) * (S_max + 1);
     auto cap_of = [&](int g, int k) -> int64_t {
         return caps_in_lds ? caps[g * tb.n_tp + k] : int64_t(tb.tp[k]) * tb.type_mem[tb.group_type[g]];
     };
@@ -159,7 +161,7 @@ __global__ __launch_bounds__(256) void k2_band(TablesDev tb, CandDev cd, int *co
     int64_t used = 0;
     unsigned long long seen = 0;                      // groups already entered, when G <= 64
     int prev_g = -1, F = 0;
-    if (status == HARP_CAND_OK) my[0] = 0;
+    ftile[cl] = 0;
     for (int s = 0; status == HARP_CAND_OK && s < S; ++s) {
         const uint16_t code = slots[s * pitch + cl];
         if (code == kBadSlot) { status = HARP_CAND_INVALID; break; }
@@ -190,13 +192,14 @@ __global__ __launch_bounds__(256) void k2_band(TablesDev tb, CandDev cd, int *co
             }
             F = a;
             if (F < s + 1 || (s == S - 1 && F != L)) feasible = false;
-            else my[s + 1] = uint32_t(F) << 16;
+            else ftile[(s + 1) * pitch + cl] = (uint16_t)F;
         }
     }
-    // backward chain: B[s] = smallest cut from which stage s can reach B[s+1]
+    // backward chain: B[s] = smallest cut from which stage s can reach B[s+1]; B[s] takes the place of
+    // the slot code of stage s, which is no longer needed
     if (status == HARP_CAND_OK && feasible) {
         int B = L;
-        my[S] |= uint32_t(L);
+        slots[S * pitch + cl] = (uint16_t)L;
         for (int s = S - 1; s >= 0; --s) {
             const uint16_t code = slots[s * pitch + cl];
             const int64_t n = (S - s) < tb.M ? (S - s) : tb.M;
@@ -209,28 +212,38 @@ __global__ __launch_bounds__(256) void k2_band(TablesDev tb, CandDev cd, int *co
                 if (qb - (PP[m] + n * PS[m]) <= cap) b = m; else a = m;
             }
             B = b;
-            const int hi = band_hi(my[s]);
+            const int hi = ftile[s * pitch + cl];
             if (hi < B || (s == 0 && B != 0)) { feasible = false; break; }
-            my[s] = uint32_t(B) | (uint32_t(hi) << 16);
+            slots[s * pitch + cl] = (uint16_t)B;
         }
     }
     if (status == HARP_CAND_OK && !feasible) status = HARP_CAND_INFEASIBLE;
 
     // append to the live or the dead list with one atomic per wave and list: lanes rank themselves
     const int lane = threadIdx.x & 63;
-    const bool alive = status == HARP_CAND_OK;
-    const unsigned long long here = __ballot(1), live_m = __ballot(alive), dead_m = here & ~live_m;
+    const bool alive = mine && status == HARP_CAND_OK;
+    const unsigned long long here = __ballot(mine), live_m = __ballot(alive), dead_m = here & ~live_m;
     const int leader = __ffsll((long long)here) - 1;
     int base_live = 0, base_dead = 0;
-    if (lane == leader) {
-        if (live_m) base_live = atomicAdd(&counts[0], __popcll(live_m));
-        if (dead_m) base_dead = atomicAdd(&counts[1], __popcll(dead_m));
+    if (here != 0) {
+        if (lane == leader) {
+            if (live_m) base_live = atomicAdd(&counts[0], __popcll(live_m));
+            if (dead_m) base_dead = atomicAdd(&counts[1], __popcll(dead_m));
+        }
+        base_live = __shfl(base_live, leader, 64);
+        base_dead = __shfl(base_dead, leader, 64);
+        const unsigned long long below = (1ull << lane) - 1ull;
+        if (alive) live_list[base_live + __popcll(live_m & below)] = c;
+        else if (mine) dead_list[base_dead + __popcll(dead_m & below)] = uint32_t(c) | (uint32_t(status) << kDeadStatusShift);
     }
-    base_live = __shfl(base_live, leader, 64);
-    base_dead = __shfl(base_dead, leader, 64);
-    const unsigned long long below = (1ull << lane) - 1ull;
-    if (alive) live_list[base_live + __popcll(live_m & below)] = c;
-    else dead_list[base_dead + __popcll(dead_m & below)] = uint32_t(c) | (uint32_t(status) << kDeadStatusShift);
+    // the bands of the workgroup's candidates leave LDS as one contiguous run of rows (rows of
+    // candidates without bands carry whatever the tiles held: nobody reads them)
+    __syncthreads();
+    uint32_t *dst = bands + int64_t(c0) * (S_max + 1);
+    for (int e = threadIdx.x; e < n_here * (S_max + 1); e += nthreads) {
+        const int cand = e / (S_max + 1), s = e - cand * (S_max + 1);
+        dst[e] = uint32_t(slots[s * pitch + cand]) | (uint32_t(ftile[s * pitch + cand]) << 16);
+    }
 }
 
 __global__ void k2_clear_count(int *counts) {
@@ -262,20 +275,26 @@ struct FastArgs {
     unsigned char *arg_base;      // back-pointer slices
     size_t arg_per_wave;
     unsigned long long *work;     // [4] transitions, cells, trips, candidates (counting build only)
-    int lo_pitch, row_len, lds_per_wave, arena_bytes;
+    int lo_pitch, lds_per_wave;
+    int wide_pass;                // 1: the pass over the candidates the first pass found too wide for its LDS share
     uint32_t shift_packed;        // log2 of degree k in bits 4k .. 4k+3
 };
 
-// per-wavefront LDS slice: rows [row_len] | band [S_max+1] | slot [S_max] | aoff [S_max+1] |
-// cuts [S_max+1] | arena [arena_bytes]
-__host__ __device__ inline size_t fast_wave_fixed_bytes(int row_len, int S_max) {
-    return size_t(row_len) * sizeof(Pair) + size_t(S_max + 1) * 12 + size_t(S_max) * 4;
+// per-wavefront LDS slice: band [S_max+1] | slot [S_max] | aoff [S_max+1] | cuts [S_max+1] | row entries
+// of the candidate's widest stage | arena (the rest)
+__host__ __device__ inline size_t fast_wave_small_bytes(int S_max) {
+    return (size_t(S_max + 1) * 12 + size_t(S_max) * 4 + 15) & ~size_t(15);
+}
+// bytes of row entries for a stage that reads `span` cuts: kPad spare entries in front, so that the
+// group of four previous cuts ending at any cut of the stage can be read without clamping
+__host__ __device__ inline size_t fast_row_bytes(int span) {
+    return (size_t(span + kPad) * sizeof(Pair) + 15) & ~size_t(15);
 }
 
 template <bool kCount>
 __global__ __launch_bounds__(kFastWaves * 64) void k2_fast(TablesDev tb, CandDev cd, PlansDev out, int *counts,
                                                             const int32_t *live_list,
-                                                            const uint32_t *dead_list, FastArgs fa) {
+                                                            uint32_t *dead_list, FastArgs fa) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
 
     const int L = tb.L, S_max = cd.S_max;
@@ -283,15 +302,18 @@ __global__ __launch_bounds__(kFastWaves * 64) void k2_fast(TablesDev tb, CandDev
     const int wave = uniform(threadIdx.x >> 6);
     const int wave_id = blockIdx.x * kFastWaves + wave, n_waves = gridDim.x * kFastWaves;
     unsigned char *mine = lds_raw + size_t(wave) * fa.lds_per_wave;
-    Pair *rows = reinterpret_cast<Pair *>(mine) + kPad;                                // [row_len]
-    uint32_t *band = reinterpret_cast<uint32_t *>(mine + size_t(fa.row_len) * sizeof(Pair));   // [S_max + 1]
+    uint32_t *band = reinterpret_cast<uint32_t *>(mine);                               // [S_max + 1]
     uint32_t *slot = band + (S_max + 1);                                               // [S_max]
     uint32_t *aoff = slot + S_max;                                                     // [S_max + 1]
     int32_t *cuts = reinterpret_cast<int32_t *>(aoff + (S_max + 1));                   // [S_max + 1]
-    uint8_t *arena = reinterpret_cast<uint8_t *>(cuts + (S_max + 1));                  // [arena_bytes]
+    const int small_bytes = int(fast_wave_small_bytes(S_max));
+    // row entries: entry of cut j of the stage whose lowest cut is `base` sits at rows0[j - base]
+    Pair *rows0 = reinterpret_cast<Pair *>(mine + small_bytes) + kPad;
     uint16_t *slice = reinterpret_cast<uint16_t *>(fa.arg_base + size_t(wave_id) * fa.arg_per_wave);
-    const int n_live = counts[0], n_dead = counts[1];
-    int *next_item = counts + 5;
+    // first pass: the live list; second pass: the candidates the first one queued behind the dead list
+    const int n_dead = counts[1];
+    const int n_live = fa.wide_pass ? counts[8] : counts[0];
+    int *next_item = counts + (fa.wide_pass ? 9 : 5);
     const int m_cap = tb.M;
     const int rows_per_n = tb.T * tb.n_tp;
     unsigned long long n_trans = 0, n_cells = 0, n_trips = 0, n_cands = 0;
@@ -325,7 +347,7 @@ __global__ __launch_bounds__(kFastWaves * 64) void k2_fast(TablesDev tb, CandDev
         wave_sync();
         const int n = uniform(atomicAdd(next_item, lane == 0 ? 1 : 0));
         if (n >= n_live) break;
-        const int c = uniform(live_list[n]);
+        const int c = uniform(fa.wide_pass ? int(dead_list[n_dead + n]) : live_list[n]);
         const int S = uniform(cd.cand_S[c]);
         wave_sync();              // the previous candidate's tail has finished with LDS
         {
@@ -363,6 +385,27 @@ __global__ __launch_bounds__(kFastWaves * 64) void k2_fast(TablesDev tb, CandDev
             }
         }
         wave_sync();
+        // LDS of this candidate: row entries for its widest stage (stage s reads the cuts B[s] .. F[s+1]),
+        // the rest of the wavefront's share for back-pointers.  A candidate whose widest stage does
+        // not fit the share is queued for the second pass, which runs with a share sized for L.
+        int span = 0;
+        for (int s = lane; s < S; s += 64) {
+            const int w = band_hi(band[s + 1]) - band_lo(band[s]) + 1;
+            span = w > span ? w : span;
+        }
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) {
+            const int o = __shfl_xor(span, d, 64);
+            span = o > span ? o : span;
+        }
+        span = uniform(span);
+        const int row_bytes = int(fast_row_bytes(span));
+        if (small_bytes + row_bytes > fa.lds_per_wave) {
+            if (lane == 0) dead_list[n_dead + atomicAdd(&counts[8], 1)] = uint32_t(c);
+            continue;
+        }
+        uint8_t *arena = reinterpret_cast<uint8_t *>(mine) + small_bytes + row_bytes;
+        const uint32_t arena_bytes = uint32_t(fa.lds_per_wave - small_bytes - row_bytes);
         int32_t *sp = out.splits + int64_t(c) * (S_max + 1);
         uint32_t final_v = 0;
         if (S >= 2) {
@@ -370,8 +413,8 @@ __global__ __launch_bounds__(kFastWaves * 64) void k2_fast(TablesDev tb, CandDev
             Stage cur = stage_of(0, S);
             {
                 const int top = band_hi((uint32_t)uniform((int)band[1]));
-                for (int j = lane; j <= top; j += 64) rows[j].p = cur.p_row[j];
-                if (lane == 0) rows[0].d = 0;
+                for (int j = lane; j <= top; j += 64) rows0[j].p = cur.p_row[j];
+                if (lane == 0) rows0[0].d = 0;
             }
             // first work item: the top chunk of stage 0
             uint32_t cut_c = 0;
@@ -396,7 +439,8 @@ __global__ __launch_bounds__(kFastWaves * 64) void k2_fast(TablesDev tb, CandDev
                 const Stage nxt = stage_of(s + 1, S);
                 const bool nxt_is_last = s + 2 == S;
                 const uint32_t a0 = (uint32_t)uniform((int)aoff[s]);
-                const bool arg_in_lds = a0 + uint32_t(ih - il + 1) <= uint32_t(fa.arena_bytes);
+                const bool arg_in_lds = a0 + uint32_t(ih - il + 1) <= arena_bytes;
+                Pair *rows = rows0 - jl;          // this stage's entries: cut j at rows[j], from B[s] on
 
                 // requests for the time row of stage s+1: entries [il, top_n], first chunks in registers
                 uint32_t pn[kPrefetchChunks];
@@ -492,14 +536,29 @@ __global__ __launch_bounds__(kFastWaves * 64) void k2_fast(TablesDev tb, CandDev
                     lo_c = lo_n;
                 }
 
-                // the time row of stage s+1 takes the place of this stage's
+                // The time row of stage s+1 takes the place of this stage's, and the entries move down
+                // to start at B[s+1]: chunk by chunk upwards, every lane reading its old DP value before
+                // any lane writes (a chunk lands at or below its old place and never on a chunk that is
+                // still to be read).
+                Pair *rows_n = rows0 - il;
 #pragma unroll
                 for (int q = 0; q < kPrefetchChunks; ++q) {
                     const int j = il + q * 64 + lane;
-                    if (j <= top_n) rows[j].p = pn[q];
+                    uint32_t d_keep = 0;
+                    if (j <= ih) d_keep = rows[j].d;
+                    wave_sync();
+                    if (j <= top_n) rows_n[j] = Pair{d_keep, pn[q]};
+                    wave_sync();
                 }
-                for (int j = il + kPrefetchChunks * 64 + lane; j <= top_n; j += 64) rows[j].p = nxt.p_row[j];
-                wave_sync();
+                for (int j0 = il + kPrefetchChunks * 64; j0 <= top_n; j0 += 64) {
+                    const int j = j0 + lane;
+                    uint32_t d_keep = 0, p_new = 0;
+                    if (j <= ih) d_keep = rows[j].d;
+                    if (j <= top_n) p_new = nxt.p_row[j];
+                    wave_sync();
+                    if (j <= top_n) rows_n[j] = Pair{d_keep, p_new};
+                    wave_sync();
+                }
                 cur = nxt;
             }
             // the last stage has the single cell i = L: lanes over j, lexicographic reduction
@@ -508,6 +567,7 @@ __global__ __launch_bounds__(kFastWaves * 64) void k2_fast(TablesDev tb, CandDev
                 const int s = S - 1;
                 const uint32_t b0 = (uint32_t)uniform((int)band[s]);
                 const int shift = cur.shift;
+                const Pair *rows = rows0 - band_lo(b0);
                 const uint32_t xi = rows[L].p + (1u << shift) - 1;
                 const int lo_L = uniform((int)cur.lo[L]);
                 const int lo = lo_L > band_lo(b0) ? lo_L : band_lo(b0);
@@ -544,7 +604,7 @@ __global__ __launch_bounds__(kFastWaves * 64) void k2_fast(TablesDev tb, CandDev
                     const uint32_t b1 = band[s + 1];
                     const uint32_t a0 = aoff[s];
                     const uint32_t at = a0 + uint32_t(b - band_lo(b1));
-                    if (a0 + uint32_t(band_hi(b1) - band_lo(b1) + 1) <= uint32_t(fa.arena_bytes)) {
+                    if (a0 + uint32_t(band_hi(b1) - band_lo(b1) + 1) <= arena_bytes) {
                         const int rel = arena[at];
                         b = rel == kArgEscape ? int(slice[at]) : b - 1 - rel;
                     } else {
@@ -591,7 +651,7 @@ __global__ __launch_bounds__(kFastWaves * 64) void k2_fast(TablesDev tb, CandDev
         }
     }
     // candidates the pre-pass rejected: no plan to report
-    for (int n = wave_id; n < n_dead; n += n_waves) {
+    for (int n = wave_id; n < n_dead && !fa.wide_pass; n += n_waves) {
         const uint32_t e = dead_list[n];
         write_failed_wave(out, int(e & ((1u << kDeadStatusShift) - 1u)), S_max, int(e >> kDeadStatusShift), lane);
     }
@@ -613,24 +673,32 @@ __global__ __launch_bounds__(kFastWaves * 64) void k2_fast(TablesDev tb, CandDev
 }
 
 struct FastLaunch {
-    int waves_per_cu, lds_per_wave, arena_bytes;
+    int waves_per_cu, lds_per_wave;
+    bool second_pass;        // some candidate of this shape may not fit the first pass's share
+    int wide_waves_per_cu, wide_lds_per_wave;
 };
 
-// LDS split: the wavefronts that fit beside each other on a CU, and what is left of their share
-// for one-byte back-pointers.  Measured on the 512-operator workload: 16 resident wavefronts per CU
-// (10 KB each, 5 KB of it arena) plan the batch in 6.1 ms, 24 (6.5 KB, 1.5 KB arena) in 5.2 ms, 28 in
-// 5.3 ms: occupancy is worth more than keeping every back-pointer on the CU.
+// LDS split.  A wavefront's share holds its small per-candidate arrays, the row entries of the
+// candidate's widest stage and, in what is left, one-byte back-pointers.  Measured on the
+// 512-operator workload with rows sized for L: 16 resident wavefronts per CU plan the batch in
+// 6.1 ms, 24 in 5.2 ms, 28 in 5.3 ms, so the first pass runs 24 per CU (six per SIMD); a candidate
+// whose widest stage does not fit that share goes to a second pass whose share is sized for a
+// stage over the whole sequence (launched only when L makes that possible).
 FastLaunch fast_launch_shape(int L, int S_max) {
     const size_t lds_cu = size_t(160) << 10;
-    const size_t fixed = (fast_wave_fixed_bytes(fast_row_len(L), S_max) + 15) & ~size_t(15);
+    const size_t small = fast_wave_small_bytes(S_max);
+    const size_t widest = small + fast_row_bytes(L + 1);
     FastLaunch f;
-    int waves = 24;                                  // six per SIMD keep the vector units busy; what is left of the LDS is arena
-    while (waves > kFastWaves && fixed * waves > lds_cu) waves -= kFastWaves;
-    size_t share = (lds_cu / waves - 128) & ~size_t(15);    // a little under an even split: allocation granules
-    if (share < fixed) share = fixed;                // very long rows: one workgroup per CU at most
+    int waves = 24;
+    while (waves > kFastWaves && (small + fast_row_bytes(8)) * waves > lds_cu) waves -= kFastWaves;
     f.waves_per_cu = waves;
-    f.lds_per_wave = int(share);
-    f.arena_bytes = int(share - fixed);
+    f.lds_per_wave = int((lds_cu / waves - 128) & ~size_t(15));     // a little under an even split: allocation granules
+    f.second_pass = widest > size_t(f.lds_per_wave);
+    int wide = 24;
+    while (wide > kFastWaves && (widest + 128) * wide > lds_cu) wide -= kFastWaves;
+    f.wide_waves_per_cu = wide;
+    f.wide_lds_per_wave = int((lds_cu / wide - 128) & ~size_t(15));
+    if (size_t(f.wide_lds_per_wave) < widest) f.wide_lds_per_wave = int(widest);
     return f;
 }
 
@@ -673,7 +741,7 @@ void launch_plan_prepass(const TablesDev &tb, const CandDev &cd, void *ws, int n
     const int caps_in_lds = tb.G * tb.n_tp <= kBandCapTable ? 1 : 0;
     const int bt = band_threads(cd.S_max);
     const size_t band_lds = size_t(tb.L + 1) * 16 + (caps_in_lds ? size_t(tb.G) * tb.n_tp * 8 : 0) +
-                            size_t(cd.S_max) * (bt + 2) * 2;
+                            size_t(cd.S_max + 1) * (bt + 2) * 2 * 2;
     const int n_band_groups = (cd.C + bt - 1) / bt;
     const long long lo_rows = (long long)lo_n_max(tb.L, cd.S_max, tb.M) * tb.T * tb.n_tp;
     const int n_lo_groups = int(lo_rows < 65536 ? lo_rows : 65536);
@@ -688,11 +756,6 @@ void launch_plan_fast(const TablesDev &tb, const CandDev &cd, const PlansDev &ou
     const FastWorkspace w = carve(ws, fast_shape(tb, cd), n_slices);
     launch_plan_prepass(tb, cd, ws, n_slices, st);
     const FastLaunch shape = fast_launch_shape(tb.L, cd.S_max);
-    // whole workgroups only: every wavefront of the grid owns a slice (n_slices >= kFastWaves)
-    int n_groups = shape.waves_per_cu * n_cu / kFastWaves;
-    if (n_groups > n_slices / kFastWaves) n_groups = n_slices / kFastWaves;
-    if (n_groups > (cd.C + kFastWaves - 1) / kFastWaves) n_groups = (cd.C + kFastWaves - 1) / kFastWaves;
-    if (n_groups < 1) n_groups = 1;
     FastArgs fa;
     fa.bands = w.bands;
     fa.lo_tab = w.lo_tab;
@@ -700,18 +763,25 @@ void launch_plan_fast(const TablesDev &tb, const CandDev &cd, const PlansDev &ou
     fa.arg_per_wave = fast_arg_per_group(tb.L, cd.S_max);
     fa.work = work;
     fa.lo_pitch = int(lo_pitch(tb.L));
-    fa.row_len = fast_row_len(tb.L);
-    fa.lds_per_wave = shape.lds_per_wave;
-    fa.arena_bytes = shape.arena_bytes;
     fa.shift_packed = 0;
     for (int k = 0; k < tb.n_tp; ++k) fa.shift_packed |= uint32_t(tb.tp_shift[k] & 15) << (4 * k);
-    const size_t lds = size_t(kFastWaves) * shape.lds_per_wave;
-    if (work)
-        hipLaunchKernelGGL(k2_fast<true>, dim3(n_groups), dim3(kFastWaves * 64), lds, st, tb, cd, out, w.counts,
-                           w.live_list, w.dead_list, fa);
-    else
-        hipLaunchKernelGGL(k2_fast<false>, dim3(n_groups), dim3(kFastWaves * 64), lds, st, tb, cd, out, w.counts,
-                           w.live_list, w.dead_list, fa);
+    for (int pass = 0; pass < (shape.second_pass ? 2 : 1); ++pass) {
+        const int per_cu = pass ? shape.wide_waves_per_cu : shape.waves_per_cu;
+        fa.lds_per_wave = pass ? shape.wide_lds_per_wave : shape.lds_per_wave;
+        fa.wide_pass = pass;
+        // whole workgroups only: every wavefront of the grid owns a slice (n_slices >= kFastWaves)
+        int n_groups = per_cu * n_cu / kFastWaves;
+        if (n_groups > n_slices / kFastWaves) n_groups = n_slices / kFastWaves;
+        if (n_groups > (cd.C + kFastWaves - 1) / kFastWaves) n_groups = (cd.C + kFastWaves - 1) / kFastWaves;
+        if (n_groups < 1) n_groups = 1;
+        const size_t lds = size_t(kFastWaves) * fa.lds_per_wave;
+        if (work)
+            hipLaunchKernelGGL(k2_fast<true>, dim3(n_groups), dim3(kFastWaves * 64), lds, st, tb, cd, out, w.counts,
+                               w.live_list, w.dead_list, fa);
+        else
+            hipLaunchKernelGGL(k2_fast<false>, dim3(n_groups), dim3(kFastWaves * 64), lds, st, tb, cd, out, w.counts,
+                               w.live_list, w.dead_list, fa);
+    }
 }
 
 }  // namespace harp
