@@ -80,14 +80,16 @@ inline size_t fast_arg_per_group(int L, int S_max) {
 }
 
 // Rows of the feasibility index (see k2_fast.hip): one per in-flight count n = 1 .. n_max, GPU type and
-// degree index; entry i is the lowest previous cut j such that operators [j, i) fit.
+// degree index.  Two tables of that many rows, one after the other: entry i of a row of the first
+// is the lowest previous cut j such that operators [j, i) fit, entry j of a row of the second the
+// highest cut i such that they do.
 inline int lo_n_max(int L, int S_max, int M) {
     int n = S_max < M ? S_max : M;
     return n < L ? n : L;
 }
 inline size_t lo_pitch(int L) { return (size_t(L) + 1 + 31) & ~size_t(31); }
 inline size_t lo_table_bytes(int L, int S_max, int M, int T, int n_tp) {
-    return size_t(lo_n_max(L, S_max, M)) * size_t(T) * size_t(n_tp) * lo_pitch(L) * sizeof(uint16_t);
+    return 2 * size_t(lo_n_max(L, S_max, M)) * size_t(T) * size_t(n_tp) * lo_pitch(L) * sizeof(uint16_t);
 }
 
 // Workspace: counters | live list [C] | dead list [C] | bands [C][S_max+1] | feasibility index |

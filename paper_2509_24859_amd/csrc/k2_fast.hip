@@ -60,79 +60,80 @@ using namespace fastdp;
 namespace {
 
 
+// Feasibility index, one workgroup per row (n, GPU type t, degree index k): for every cut i the
+// lowest j such that operators [j, i) fit, lo, and for every cut j the highest i such that [j, i)
+// fit, hi; "fit" is (PP[i] - PP[j]) + n (PS[i] - PS[j]) <= tp_k * type_mem[t] (eq. mem_cons with n
+// micro-batches in flight).  The need is monotone in both ends, so each entry is one binary
+// search over Q = PP + n PS, which the workgroup keeps in LDS.
+__global__ __launch_bounds__(256) void k2_index(TablesDev tb, uint16_t *lo_tab, uint16_t *hi_tab, int pitch,
+                                                int n_rows) {
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    int64_t *Q = reinterpret_cast<int64_t *>(lds_raw);       // [L + 1]
+    const int L = tb.L, rows_per_n = tb.T * tb.n_tp;
+    const int64_t *gp = tb.PP(), *gs = tb.PS();
+    for (int row = blockIdx.x; row < n_rows; row += gridDim.x) {
+        const int n = row / rows_per_n + 1;
+        const int tk = row - (n - 1) * rows_per_n;
+        const int t = tk / tb.n_tp, k = tk - t * tb.n_tp;
+        const int64_t cap = int64_t(tb.tp[k]) * tb.type_mem[t];
+        __syncthreads();
+        for (int i = threadIdx.x; i <= L; i += blockDim.x) Q[i] = gp[i] + int64_t(n) * gs[i];
+        __syncthreads();
+        uint16_t *lo = lo_tab + size_t(row) * pitch, *hi = hi_tab + size_t(row) * pitch;
+        for (int i = threadIdx.x; i <= L; i += blockDim.x) {
+            const int64_t q = Q[i];
+            int a = -1, b = i;                  // Q[b] >= q - cap holds at b = i; Q[a] < q - cap (a = -1: none)
+            while (b - a > 1) {
+                const int m = (a + b) >> 1;
+                if (Q[m] >= q - cap) b = m; else a = m;
+            }
+            lo[i] = (uint16_t)b;
+            a = i, b = L + 1;                   // Q[a] - q <= cap holds at a = i; Q[b] - q > cap (b = L + 1: none)
+            while (b - a > 1) {
+                const int m = (a + b) >> 1;
+                if (Q[m] - q <= cap) a = m; else b = m;
+            }
+            hi[i] = (uint16_t)a;
+        }
+    }
+}
+
 // Pre-pass, one thread per candidate: checks the slot list and computes the reachability band
-// [B[s], F[s]] of every DP row from the memory constraint alone (two chains of binary searches
-// over the running sums).  Candidates that pass go to the live list; malformed ones and those
-// proven infeasible go to the dead list with their status.
+// [B[s], F[s]] of every DP row from the memory constraint alone.  With the feasibility index in
+// place each link of the two chains is one lookup:
+//   F[s+1] = min(hi(n_s, type_s, k_s)[F[s]], top_s),     B[s] = max(lo(n_s, type_s, k_s)[B[s+1]], s),
+// top_s being the last cut that leaves one operator to every later stage.  Candidates that pass go
+// to the live list; malformed ones and those proven infeasible go to the dead list with their
+// status.
 //
-// Every probe of the searches is a dependent load and every candidate walks its slot list twice,
-// so everything the loops touch is staged in LDS first: the running sums PP and PS, the memory
-// cap of every (group, degree), and the workgroup's slot lists, read from global memory once,
-// coalesced, and stored slot-major so that the per-thread walks are conflict-free.  The two chains
-// leave their limits in LDS tiles as well, and the workgroup writes the bands of its candidates as
-// one contiguous run, candidate-major ([c][s]): the wavefront that later plans candidate c reads
-// its row with one coalesced load.
-//
-// The workgroups behind the candidates' ones build the feasibility index, one row each.
-constexpr int kBandCapTable = 1024;     // caps kept in LDS when G * n_tp is at most this
+// Every candidate walks its slot list twice, so the workgroup's slot lists are read from global
+// memory once, coalesced, and kept in LDS slot-major (conflict-free per-thread walks).  The two
+// chains leave their limits in LDS tiles as well, and the workgroup writes the bands of its
+// candidates as one contiguous run, candidate-major ([c][s]): the wavefront that later plans
+// candidate c reads its row with one coalesced load.
+constexpr int kBandTypeTable = 2048;    // GPU type and size of every group kept in LDS when G is at most this
 constexpr uint16_t kBadSlot = 0xFFFFu;
 
 int band_threads(int S_max) { return S_max <= 64 ? 256 : (S_max <= 128 ? 128 : 64); }
 
-// One row of the feasibility index: for in-flight count n, GPU type t, degree index k and every cut
-// i, the lowest j with (PP[i] - PP[j]) + n (PS[i] - PS[j]) <= tp_k * type_mem[t].  The need is
-// monotone in j, so a binary search over the running sums finds it.
-__device__ __forceinline__ void lo_row(const TablesDev &tb, int row, int rows_per_n, uint16_t *lo_tab,
-                                       int pitch, int64_t *Q) {
-    const int L = tb.L;
-    const int n = row / rows_per_n + 1;
-    const int tk = row - (n - 1) * rows_per_n;
-    const int t = tk / tb.n_tp, k = tk - t * tb.n_tp;
-    const int64_t cap = int64_t(tb.tp[k]) * tb.type_mem[t];
-    const int64_t *gp = tb.PP(), *gs = tb.PS();
-    for (int i = threadIdx.x; i <= L; i += blockDim.x) Q[i] = gp[i] + int64_t(n) * gs[i];
-    __syncthreads();
-    uint16_t *dst = lo_tab + size_t(row) * pitch;
-    for (int i = threadIdx.x; i <= L; i += blockDim.x) {
-        const int64_t th = Q[i] - cap;
-        int a = -1, b = i;                      // Q[b] >= th holds at b = i; Q[a] < th (a = -1: none)
-        while (b - a > 1) {
-            const int m = (a + b) >> 1;
-            if (Q[m] >= th) b = m; else a = m;
-        }
-        dst[i] = (uint16_t)b;
-    }
-}
-
 __global__ __launch_bounds__(256) void k2_band(TablesDev tb, CandDev cd, int *counts, int32_t *live_list,
-                                               uint32_t *dead_list, uint32_t *bands, int caps_in_lds,
-                                               int n_band_groups, uint16_t *lo_tab, int lo_pitch_e,
-                                               int lo_rows) {
+                                               uint32_t *dead_list, uint32_t *bands, int types_in_lds,
+                                               const uint16_t *lo_tab, const uint16_t *hi_tab, int idx_pitch) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     const int L = tb.L, S_max = cd.S_max, C = cd.C;
     const int nthreads = blockDim.x, pitch = nthreads + 2;
-    int64_t *PP = reinterpret_cast<int64_t *>(lds_raw);      // [L + 1]
-    if ((int)blockIdx.x >= n_band_groups) {
-        for (int row = blockIdx.x - n_band_groups; row < lo_rows; row += gridDim.x - n_band_groups) {
-            __syncthreads();
-            lo_row(tb, row, tb.T * tb.n_tp, lo_tab, lo_pitch_e, PP);
-        }
-        return;
-    }
-    int64_t *PS = PP + (L + 1);                              // [L + 1]
-    int64_t *caps = PS + (L + 1);                            // [G * n_tp] when caps_in_lds
     // slot codes, replaced stage by stage by the lower band limits B[s]; and the upper limits F[s]
-    uint16_t *slots = reinterpret_cast<uint16_t *>(caps + (caps_in_lds ? tb.G * tb.n_tp : 0));  // [S_max + 1][pitch]
-    uint16_t *ftile = slots + (S_max + 1) * pitch;                                               // [S_max + 1][pitch]
+    uint16_t *slots = reinterpret_cast<uint16_t *>(lds_raw);        // [S_max + 1][pitch]
+    uint16_t *ftile = slots + (S_max + 1) * pitch;                  // [S_max + 1][pitch]
+    int32_t *gtype = reinterpret_cast<int32_t *>(ftile + (S_max + 1) * pitch);   // [G] when types_in_lds
+    int32_t *gndev = gtype + tb.G;                                               // [G] when types_in_lds
     const int c0 = blockIdx.x * nthreads;
     const int n_here = (C - c0) < nthreads ? (C - c0) : nthreads;
     {
-        const int64_t *gp = tb.PP(), *gs = tb.PS();
-        for (int i = threadIdx.x; i <= L; i += nthreads) { PP[i] = gp[i]; PS[i] = gs[i]; }
-        if (caps_in_lds)
-            for (int q = threadIdx.x; q < tb.G * tb.n_tp; q += nthreads) {
-                const int g = q / tb.n_tp, k = q - g * tb.n_tp;
-                caps[q] = int64_t(tb.tp[k]) * tb.type_mem[tb.group_type[g]];
+        if (types_in_lds)
+            for (int g = threadIdx.x; g < tb.G; g += nthreads) {
+                gtype[g] = tb.group_type[g];
+                gndev[g] = tb.group_ndev[g];
             }
         // slot lists of this workgroup's candidates: (group << 3) | degree index, or kBadSlot
         const int32_t *grp = cd.cand_group + int64_t(c0) * S_max;
@@ -149,8 +150,10 @@ __global__ __launch_bounds__(256) void k2_band(TablesDev tb, CandDev cd, int *co
     const bool mine = c < C;
     const int S = mine ? cd.cand_S[c] : 0;
     const int R = L - S + 1;
-    auto cap_of = [&](int g, int k) -> int64_t {
-        return caps_in_lds ? caps[g * tb.n_tp + k] : int64_t(tb.tp[k]) * tb.type_mem[tb.group_type[g]];
+    // row of the index for a stage with n micro-batches in flight on degree index k of group g
+    auto index_row = [&](int n, int g, int k) -> size_t {
+        const int t = types_in_lds ? gtype[g] : tb.group_type[g];
+        return size_t(((n - 1) * tb.T + t) * tb.n_tp + k) * idx_pitch;
     };
 
     int status = HARP_CAND_OK;
@@ -178,19 +181,12 @@ __global__ __launch_bounds__(256) void k2_band(TablesDev tb, CandDev cd, int *co
             prev_g = g;
         }
         used += tb.tp[k];
-        if (used > tb.group_ndev[g]) status = HARP_CAND_INVALID;
+        if (used > (types_in_lds ? gndev[g] : tb.group_ndev[g])) status = HARP_CAND_INVALID;
         if (feasible) {
-            const int64_t n = (S - s) < tb.M ? (S - s) : tb.M;
-            const int64_t cap = cap_of(g, k);
-            const int64_t q0 = PP[F] + n * PS[F];
+            const int n = (S - s) < tb.M ? (S - s) : tb.M;
+            const int reach = hi_tab[index_row(n, g, k) + F];
             const int top = (s == S - 1) ? L : s + R;
-            int a = F, b = top;                               // need(F, a) <= cap always holds
-            if ((PP[b] + n * PS[b]) - q0 <= cap) a = b;
-            while (b - a > 1) {
-                const int m = (a + b) >> 1;
-                if ((PP[m] + n * PS[m]) - q0 <= cap) a = m; else b = m;
-            }
-            F = a;
+            F = reach < top ? reach : top;
             if (F < s + 1 || (s == S - 1 && F != L)) feasible = false;
             else ftile[(s + 1) * pitch + cl] = (uint16_t)F;
         }
@@ -202,16 +198,9 @@ __global__ __launch_bounds__(256) void k2_band(TablesDev tb, CandDev cd, int *co
         slots[S * pitch + cl] = (uint16_t)L;
         for (int s = S - 1; s >= 0; --s) {
             const uint16_t code = slots[s * pitch + cl];
-            const int64_t n = (S - s) < tb.M ? (S - s) : tb.M;
-            const int64_t cap = cap_of(code >> 3, code & 7);
-            const int64_t qb = PP[B] + n * PS[B];
-            int a = s, b = B;                                 // need(b, B) <= cap holds at b = B
-            if (qb - (PP[a] + n * PS[a]) <= cap) b = a;
-            while (b - a > 1) {
-                const int m = (a + b) >> 1;
-                if (qb - (PP[m] + n * PS[m]) <= cap) b = m; else a = m;
-            }
-            B = b;
+            const int n = (S - s) < tb.M ? (S - s) : tb.M;
+            const int from = lo_tab[index_row(n, code >> 3, code & 7) + B];
+            B = from > s ? from : s;
             const int hi = ftile[s * pitch + cl];
             if (hi < B || (s == 0 && B != 0)) { feasible = false; break; }
             slots[s * pitch + cl] = (uint16_t)B;
@@ -738,16 +727,17 @@ int plan_fast_groups(int L, int S_max, int n_cu) {
 void launch_plan_prepass(const TablesDev &tb, const CandDev &cd, void *ws, int n_slices, hipStream_t st) {
     const FastWorkspace w = carve(ws, fast_shape(tb, cd), n_slices);
     hipLaunchKernelGGL(k2_clear_count, dim3(1), dim3(64), 0, st, w.counts);
-    const int caps_in_lds = tb.G * tb.n_tp <= kBandCapTable ? 1 : 0;
+    const long long idx_rows = (long long)lo_n_max(tb.L, cd.S_max, tb.M) * tb.T * tb.n_tp;
+    const int idx_pitch = int(lo_pitch(tb.L));
+    hipLaunchKernelGGL(k2_index, dim3(unsigned(idx_rows < 65536 ? idx_rows : 65536)), dim3(256),
+                       size_t(tb.L + 1) * 8, st, tb, w.lo_tab, w.lo_tab + idx_rows * idx_pitch, idx_pitch,
+                       int(idx_rows));
+    const int types_in_lds = tb.G <= kBandTypeTable ? 1 : 0;
     const int bt = band_threads(cd.S_max);
-    const size_t band_lds = size_t(tb.L + 1) * 16 + (caps_in_lds ? size_t(tb.G) * tb.n_tp * 8 : 0) +
-                            size_t(cd.S_max + 1) * (bt + 2) * 2 * 2;
-    const int n_band_groups = (cd.C + bt - 1) / bt;
-    const long long lo_rows = (long long)lo_n_max(tb.L, cd.S_max, tb.M) * tb.T * tb.n_tp;
-    const int n_lo_groups = int(lo_rows < 65536 ? lo_rows : 65536);
-    hipLaunchKernelGGL(k2_band, dim3(n_band_groups + n_lo_groups), dim3(bt), band_lds, st, tb, cd, w.counts,
-                       w.live_list, w.dead_list, w.bands, caps_in_lds, n_band_groups, w.lo_tab,
-                       int(lo_pitch(tb.L)), int(lo_rows));
+    const size_t band_lds = size_t(cd.S_max + 1) * (bt + 2) * 2 * 2 + (types_in_lds ? size_t(tb.G) * 8 : 0);
+    hipLaunchKernelGGL(k2_band, dim3((cd.C + bt - 1) / bt), dim3(bt), band_lds, st, tb, cd, w.counts,
+                       w.live_list, w.dead_list, w.bands, types_in_lds, w.lo_tab,
+                       w.lo_tab + idx_rows * idx_pitch, idx_pitch);
 }
 
 // n_slices: back-pointer slices in the workspace; k2_fast runs with at most that many wavefronts.
