@@ -227,11 +227,16 @@ bool mesh_index_fits(const harp_tables *t) {
     return (t->total_devices + 1) * (int64_t(t->dev.L) + 1) < (int64_t(1) << 31);
 }
 
-bool use_fast(const harp_ctx *ctx, const harp_tables *t) {
-    return t->fast32 && ctx->plan_path != HARP_PATH_GENERIC;
+// The 32-bit tables serve the min-max planner up to kFastMaxL operators; the kernels that keep
+// whole rows in LDS (exact search, H-1F1B, the submesh planners) stop at kFastRowsMaxL.
+bool fast_allowed(const harp_tables *t, bool whole_rows) {
+    return t->fast32 && (!whole_rows || t->dev.L <= kFastRowsMaxL);
 }
-bool use_fast(const harp_ctx *ctx, const harp_tables *t, const harp_candidates *cd) {
-    return use_fast(ctx, t) && fast_batch_ok(t, cd);
+bool use_fast_rows(const harp_ctx *ctx, const harp_tables *t) {
+    return fast_allowed(t, true) && ctx->plan_path != HARP_PATH_GENERIC;
+}
+bool use_fast(const harp_ctx *ctx, const harp_tables *t, const harp_candidates *cd, bool whole_rows) {
+    return fast_allowed(t, whole_rows) && ctx->plan_path != HARP_PATH_GENERIC && fast_batch_ok(t, cd);
 }
 
 }  // namespace
@@ -410,19 +415,19 @@ struct PlanCall {
 // limit_bytes: the memory at hand.  With shrink the unit count is cut down to what fits (the
 // static-scratch entry point); without, the full resident count must fit.
 int plan_prepare(harp_ctx *ctx, harp_tables *t, const harp_candidates *cd, const harp_plans *out,
-                 bool extra_null, const void *workspace, size_t limit_bytes, bool shrink, void *hip_stream,
-                 PlanCall &pc) {
+                 bool extra_null, bool whole_rows, const void *workspace, size_t limit_bytes, bool shrink,
+                 void *hip_stream, PlanCall &pc) {
     int rc = check_batch(ctx, t, cd);
     if (rc != HARP_OK) return rc;
     if (!out || extra_null ||
         (cd->C > 0 && (!out->splits || !out->dev_first || !out->bottleneck || !out->iter_time || !out->status)))
         return fail(ctx, HARP_ERR_INVALID_ARG, "null array");
-    if (ctx->plan_path == HARP_PATH_FAST32 && !(t->fast32 && fast_batch_ok(t, cd)))
+    if (ctx->plan_path == HARP_PATH_FAST32 && !(fast_allowed(t, whole_rows) && fast_batch_ok(t, cd)))
         return fail(ctx, HARP_ERR_UNIMPLEMENTED,
                     "the 32-bit path was requested but these tables or this batch do not allow it");
     pc.c = CandDev{ cd->C, cd->S_max, cd->cand_S, cd->cand_group, cd->cand_tp };
     pc.o = PlansDev{ out->splits, out->dev_first, out->bottleneck, out->iter_time, out->status };
-    pc.fast = use_fast(ctx, t, cd);
+    pc.fast = use_fast(ctx, t, cd, whole_rows);
     pc.groups = n_plan_groups(ctx, cd->C, pc.fast, t->dev.L, cd->S_max);
     pc.slices = pc.fast ? n_fast_slices(ctx, cd->C, t->dev.L, cd->S_max) : pc.groups;
     pc.st = static_cast<hipStream_t>(hip_stream);
@@ -465,7 +470,7 @@ extern "C" {
 int harp_plan_batch(harp_ctx *ctx, harp_tables *t, const harp_candidates *cd, const harp_plans *out,
                     void *workspace, size_t workspace_bytes, void *hip_stream) {
     PlanCall pc;
-    const int rc = plan_prepare(ctx, t, cd, out, false, workspace, workspace_bytes, false, hip_stream, pc);
+    const int rc = plan_prepare(ctx, t, cd, out, false, false, workspace, workspace_bytes, false, hip_stream, pc);
     if (rc != HARP_OK || cd->C == 0) return rc;
     return plan_minmax(ctx, t, pc, workspace, nullptr);
 }
@@ -473,7 +478,7 @@ int harp_plan_batch(harp_ctx *ctx, harp_tables *t, const harp_candidates *cd, co
 int harp_plan_batch_static(harp_ctx *ctx, harp_tables *t, const harp_candidates *cd, const harp_plans *out,
                            void *hip_stream) {
     PlanCall pc;
-    const int rc = plan_prepare(ctx, t, cd, out, false, ctx ? ctx->scratch : nullptr,
+    const int rc = plan_prepare(ctx, t, cd, out, false, false, ctx ? ctx->scratch : nullptr,
                                 size_t(HARP_STATIC_SCRATCH_BYTES), true, hip_stream, pc);
     if (rc != HARP_OK || cd->C == 0) return rc;
     return plan_minmax(ctx, t, pc, ctx->scratch, nullptr);
@@ -482,7 +487,8 @@ int harp_plan_batch_static(harp_ctx *ctx, harp_tables *t, const harp_candidates 
 int harp_plan_batch_count_work(harp_ctx *ctx, harp_tables *t, const harp_candidates *cd, const harp_plans *out,
                                void *workspace, size_t workspace_bytes, uint64_t *work, void *hip_stream) {
     PlanCall pc;
-    const int rc = plan_prepare(ctx, t, cd, out, work == nullptr, workspace, workspace_bytes, false, hip_stream, pc);
+    const int rc = plan_prepare(ctx, t, cd, out, work == nullptr, false, workspace, workspace_bytes, false, hip_stream,
+                                pc);
     if (rc != HARP_OK) return rc;
     if (!pc.fast)
         return fail(ctx, HARP_ERR_UNIMPLEMENTED, "work is counted on the 32-bit path only");
@@ -494,7 +500,7 @@ int harp_plan_batch_count_work(harp_ctx *ctx, harp_tables *t, const harp_candida
 int harp_plan_exact_batch(harp_ctx *ctx, harp_tables *t, const harp_candidates *cd, const harp_plans *out,
                           int32_t *n_passes, void *workspace, size_t workspace_bytes, void *hip_stream) {
     PlanCall pc;
-    int rc = plan_prepare(ctx, t, cd, out, false, workspace, workspace_bytes, false, hip_stream, pc);
+    int rc = plan_prepare(ctx, t, cd, out, false, true, workspace, workspace_bytes, false, hip_stream, pc);
     if (rc != HARP_OK || cd->C == 0) return rc;
     if (pc.fast) {
         rc = plan_minmax(ctx, t, pc, workspace, nullptr);
@@ -512,8 +518,8 @@ int harp_plan_h1f1b_batch(harp_ctx *ctx, harp_tables *t, const harp_candidates *
                           const harp_plans *out, int32_t *warmup, void *workspace, size_t workspace_bytes,
                           void *hip_stream) {
     PlanCall pc;
-    const int rc = plan_prepare(ctx, t, cd, out, cd && cd->C > 0 && (!warmup || !t_max), workspace, workspace_bytes,
-                                false, hip_stream, pc);
+    const int rc = plan_prepare(ctx, t, cd, out, cd && cd->C > 0 && (!warmup || !t_max), true, workspace,
+                                workspace_bytes, false, hip_stream, pc);
     if (rc != HARP_OK || cd->C == 0) return rc;
     if (pc.fast) launch_plan_h1f1b(t->dev, pc.c, t_max, pc.o, warmup, workspace, pc.groups, pc.st);
     else launch_plan_generic_h1f1b(t->dev, pc.c, t_max, pc.o, warmup, workspace, pc.groups, pc.st);
@@ -563,7 +569,7 @@ int plan_mesh_common(harp_ctx *ctx, harp_tables *t, const harp_orderings *od, co
     if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
     const OrdDev o = { od->C, od->G_max, od->S_max, od->ord_S, od->ord_G, od->ord_group };
     const PlansDev pl = { out->splits, out->dev_first, out->bottleneck, out->iter_time, out->status };
-    launch_plan_mesh(t->dev, o, pl, stage_group, stage_tp, n_passes, exact, use_fast(ctx, t), workspace, groups,
+    launch_plan_mesh(t->dev, o, pl, stage_group, stage_tp, n_passes, exact, use_fast_rows(ctx, t), workspace, groups,
                      threads, t->total_devices,
                      static_cast<hipStream_t>(hip_stream));
     e = hipGetLastError();
@@ -607,7 +613,7 @@ int harp_plan_mesh_h1f1b_batch(harp_ctx *ctx, harp_tables *t, const harp_orderin
     if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
     const OrdDev o = { od->C, od->G_max, od->S_max, od->ord_S, od->ord_G, od->ord_group };
     const PlansDev pl = { out->splits, out->dev_first, out->bottleneck, out->iter_time, out->status };
-    launch_plan_mesh_h1f1b(t->dev, o, t_max, pl, stage_group, stage_tp, warmup, use_fast(ctx, t), workspace, groups,
+    launch_plan_mesh_h1f1b(t->dev, o, t_max, pl, stage_group, stage_tp, warmup, use_fast_rows(ctx, t), workspace, groups,
                            threads, t->total_devices, static_cast<hipStream_t>(hip_stream));
     e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(ctx, e, "launching the submesh H-1F1B kernel");
@@ -640,7 +646,7 @@ int harp_plan_mesh_h1f1b_sweep_batch(harp_ctx *ctx, harp_tables *t, const harp_o
     const OrdDev o = { od->C, od->G_max, od->S_max, od->ord_S, od->ord_G, od->ord_group };
     const PlansDev pl = { out->splits, out->dev_first, out->bottleneck, out->iter_time, out->status };
     launch_plan_mesh_h1f1b_sweep(t->dev, o, nullptr, nullptr, max_caps, pl, stage_group, stage_tp, warmup, t_max_out, n_caps,
-                                 use_fast(ctx, t), workspace, lay.groups, lay.threads, lay.W_climb, lay.W, t->total_devices,
+                                 use_fast_rows(ctx, t), workspace, lay.groups, lay.threads, lay.W_climb, lay.W, t->total_devices,
                                  static_cast<hipStream_t>(hip_stream));
     e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(ctx, e, "launching the submesh H-1F1B sweep kernel");
@@ -678,7 +684,7 @@ int harp_plan_h1f1b_sweep_batch(harp_ctx *ctx, harp_tables *t, const harp_candid
     const OrdDev o = { cd->C, 1, cd->S_max, cd->cand_S, nullptr, nullptr };
     const PlansDev pl = { out->splits, out->dev_first, out->bottleneck, out->iter_time, out->status };
     launch_plan_mesh_h1f1b_sweep(t->dev, o, cd->cand_group, cd->cand_tp, max_caps, pl, nullptr, nullptr, warmup,
-                                 t_max_out, n_caps, use_fast(ctx, t), workspace, lay.groups, lay.threads, lay.W_climb, lay.W,
+                                 t_max_out, n_caps, use_fast_rows(ctx, t), workspace, lay.groups, lay.threads, lay.W_climb, lay.W,
                                  t->total_devices, static_cast<hipStream_t>(hip_stream));
     e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(ctx, e, "launching the search over the cap");

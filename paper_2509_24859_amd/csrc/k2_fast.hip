@@ -435,8 +435,11 @@ __global__ __launch_bounds__(kFastWaves * 64) void k2_fast(TablesDev tb, CandDev
                 uint32_t pn[kPrefetchChunks];
 #pragma unroll
                 for (int q = 0; q < kPrefetchChunks; ++q) {
-                    const int j = il + q * 64 + lane;
-                    pn[q] = j <= top_n ? nxt.p_row[j] : 0u;
+                    pn[q] = 0u;
+                    if (il + q * 64 <= top_n) {       // most stages are a chunk or two wide
+                        const int j = il + q * 64 + lane;
+                        if (j <= top_n) pn[q] = nxt.p_row[j];
+                    }
                 }
 
                 for (int q = (ih - il) >> 6; q >= 0; --q) {
@@ -532,6 +535,7 @@ __global__ __launch_bounds__(kFastWaves * 64) void k2_fast(TablesDev tb, CandDev
                 Pair *rows_n = rows0 - il;
 #pragma unroll
                 for (int q = 0; q < kPrefetchChunks; ++q) {
+                    if (il + q * 64 > top_n) break;
                     const int j = il + q * 64 + lane;
                     uint32_t d_keep = 0;
                     if (j <= ih) d_keep = rows[j].d;

@@ -19,23 +19,31 @@ def ctx(harp):
     c.close()
 
 
+ROWS_MAX_L = 1024      # the 32-bit exact, H-1F1B and submesh kernels keep whole rows in LDS
+
+
 def _all_entry_points(harp, ctx, p, cands, label, exact=True):
     tables = oracle.build_tables(p)
     want = oracle_plan_threaded(tables, cands)
     fast32 = harp.Tables(ctx, p).fast32
     paths = [harp.PATH_GENERIC] + ([harp.PATH_FAST32] if fast32 else [])
+    row_paths = [harp.PATH_GENERIC] + ([harp.PATH_FAST32] if fast32 and p.L <= ROWS_MAX_L else [])
     for path in paths:
         got, _ = harp.plan(ctx, p, cands, path)
         assert_plans_equal(got, want, "%s min-max path %d" % (label, path))
     caps = np.where(want.status == oracle.OK, want.bottleneck // 8 * 9, 3).astype(np.int64)
     want_h = oracle_plan_h1f1b_threaded(tables, cands, caps)
-    for path in paths:
+    for path in row_paths:
         got, _ = harp.plan_h1f1b(ctx, p, cands, caps, path)
         assert_plans_equal(got, want_h, "%s H-1F1B path %d" % (label, path))
         assert (got.warmup == want_h.warmup).all()
+    if fast32 and p.L > ROWS_MAX_L:          # asked for by name where it does not exist: an error, no fallback
+        with pytest.raises(harp.HarpError) as e:
+            harp.plan_h1f1b(ctx, p, cands, caps, harp.PATH_FAST32)
+        assert e.value.code == harp.ERR_UNIMPLEMENTED
     if exact:
         want_e = oracle_plan_exact_threaded(tables, cands)
-        for path in paths:
+        for path in row_paths:
             got, _, _ = harp.plan_exact(ctx, p, cands, path)
             assert_plans_equal(got, want_e, "%s exact path %d" % (label, path))
     return want, fast32
@@ -78,8 +86,10 @@ def test_every_operator_its_own_stage(harp, ctx):
 
 
 def test_longest_sequence_of_the_32_bit_path_and_beyond(harp, ctx):
+    """L = 1024 is the last length with 32-bit kernels behind every entry point, 4096 the last for
+    the min-max planner; past each limit the int64 path takes over with the same results."""
     rng = np.random.default_rng(43)
-    for L, expect_fast in ((1024, True), (1025, False), (3000, False)):
+    for L, expect_fast in ((1024, True), (1025, True), (4096, True), (4097, False)):
         G = 3
         bw = rng.integers(20, 4000, size=(G, G))
         # many microbatches keep [t_S, t_E] narrow, so that the oracle's sweep stays in seconds

@@ -306,6 +306,24 @@ def test_plan_wide_bands(harp, ctx):
         assert harp.PATH_FAST32 in ran
 
 
+def test_plan_sequence_of_4096_operators(harp, ctx):
+    """The longest sequence the 32-bit min-max path takes (the stress workload's cluster with 4,096
+    operators): with tight memory the bands are narrow and every candidate is planned in the first
+    pass of the kernel; with loose memory the widest stage spans hundreds of cuts more than a
+    wavefront's first-pass share of LDS holds, so candidates go through the second pass."""
+    for scale, n in ((2.4, 24), (8.0, 6)):
+        p = W.long_sequence(4096, seed=3)
+        p.type_mem_bytes = (p.type_mem_bytes * scale).astype(np.int64)
+        cands = W.make_candidates(p, 3, 77, p.G, 48, 0, n)
+        print("L = 4096, memory x %.1f" % scale, flush=True)
+        want = oracle_plan_threaded(oracle.build_tables(p), cands)
+        assert (want.status == oracle.OK).any()
+        _, ran = _plan_all_paths(harp, ctx, p, cands, want, "L=4096 memory x%.1f" % scale)
+        assert harp.PATH_FAST32 in ran
+        if scale < 3:
+            assert (want.status == oracle.INFEASIBLE).any()
+
+
 def test_plan_adversarial_rows(harp, ctx):
     """Inputs built to break shortcuts: huge transfers on some cuts (non-monotone DP rows), zero
     cost operators (long runs of ties), memory that only fits one-operator stages."""
