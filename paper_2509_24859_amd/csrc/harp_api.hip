@@ -154,15 +154,17 @@ int n_fast_slices(const harp_ctx *ctx, int C, int L, int S_max) {
 
 // Workspace of the min-max planner on the path that will run, with `units` slices (32-bit path) or
 // workgroups (int64 path).
-size_t plan_bytes_on_path(const harp_tables *t, const harp_candidates *cd, bool fast, int units) {
-    if (fast) return plan_fast_ws_bytes(t->dev, cd->S_max, cd->C, units) + 256;
-    return size_t(units) * plan_generic_ws_per_group(t->dev.L, cd->S_max) + 256;
+// The pre-pass keeps a feasibility index whose size grows with min(S_max, M) * T * n_tp * L; batches
+// for which it would pass the limit run on the int64 path without bands.
+bool fast_batch_ok(const harp_tables *t, const harp_candidates *cd) {
+    return t->dev.L <= kIndexMaxL && plan_fast_index_bytes(t->dev, cd->S_max) <= kFastIndexLimit;
 }
 
-// The 32-bit path keeps a feasibility index whose size grows with min(S_max, M) * T * n_tp * L;
-// batches for which it would pass the limit run on the int64 path.
-bool fast_batch_ok(const harp_tables *t, const harp_candidates *cd) {
-    return plan_fast_index_bytes(t->dev, cd->S_max) <= kFastIndexLimit;
+size_t plan_bytes_on_path(const harp_tables *t, const harp_candidates *cd, bool fast, int units) {
+    if (fast) return plan_fast_ws_bytes(t->dev, cd->S_max, cd->C, units) + 256;
+    // int64 path: the pre-pass area (lists, bands, index) when the index fits, then the workgroups' slices
+    const size_t prepass = fast_batch_ok(t, cd) ? plan_fast_ws_bytes(t->dev, cd->S_max, cd->C, 0) : 0;
+    return prepass + size_t(units) * plan_generic_ws_per_group(t->dev.L, cd->S_max) + 256;
 }
 
 // Workgroups of the submesh planner: resident ones, fewer when their slices would pass 16 GiB.
@@ -391,6 +393,7 @@ size_t harp_plan_workspace_bytes(harp_ctx *ctx, const harp_tables *t, const harp
                                  ? plan_generic_ws_per_group(t->dev.L, cd->S_max)
                                  : plan_generic_h1f1b_ws_per_group(t->dev.L, cd->S_max);
     size_t gen = size_t(n_plan_groups(ctx, C, false, t->dev.L, cd->S_max)) * per_group;
+    if (fast_batch_ok(t, cd)) gen += plan_fast_ws_bytes(t->dev, cd->S_max, C, 0);
     size_t fast = 0;
     if (t->lim.want_fast && fast_batch_ok(t, cd))
         fast = plan_fast_ws_bytes(t->dev, cd->S_max, C, n_fast_slices(ctx, C, t->dev.L, cd->S_max));
@@ -407,6 +410,7 @@ struct PlanCall {
     CandDev c;
     PlansDev o;
     bool fast;
+    bool banded;     // int64 path: the min-max planner runs behind the pre-pass (the index fits)
     int groups;      // workgroups of the one-candidate-per-workgroup kernels
     int slices;      // back-pointer slices of the 32-bit path (>= groups, a multiple of kFastWaves)
     hipStream_t st;
@@ -428,6 +432,7 @@ int plan_prepare(harp_ctx *ctx, harp_tables *t, const harp_candidates *cd, const
     pc.c = CandDev{ cd->C, cd->S_max, cd->cand_S, cd->cand_group, cd->cand_tp };
     pc.o = PlansDev{ out->splits, out->dev_first, out->bottleneck, out->iter_time, out->status };
     pc.fast = use_fast(ctx, t, cd, whole_rows);
+    pc.banded = !pc.fast && fast_batch_ok(t, cd);
     pc.groups = n_plan_groups(ctx, cd->C, pc.fast, t->dev.L, cd->S_max);
     pc.slices = pc.fast ? n_fast_slices(ctx, cd->C, t->dev.L, cd->S_max) : pc.groups;
     pc.st = static_cast<hipStream_t>(hip_stream);
@@ -457,7 +462,7 @@ int plan_prepare(harp_ctx *ctx, harp_tables *t, const harp_candidates *cd, const
 
 int plan_minmax(harp_ctx *ctx, harp_tables *t, const PlanCall &pc, void *ws, unsigned long long *work) {
     if (pc.fast) launch_plan_fast(t->dev, pc.c, pc.o, ws, pc.slices, ctx->n_cu, work, pc.st);
-    else launch_plan_generic(t->dev, pc.c, pc.o, ws, pc.groups, pc.st);
+    else launch_plan_generic(t->dev, pc.c, pc.o, ws, pc.groups, pc.banded, pc.st);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(ctx, e, "launching the planner kernel");
     return HARP_OK;

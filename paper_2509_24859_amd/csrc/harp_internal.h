@@ -81,7 +81,7 @@ constexpr int kLongL = 1 << 18;        // from here on the table build runs chun
 
 void launch_build(const TablesDev &tb, const BuildLimits &lim, hipStream_t st);
 void launch_plan_generic(const TablesDev &tb, const CandDev &cd, const PlansDev &out, void *ws,
-                         int n_groups, hipStream_t st);
+                         int n_groups, bool banded, hipStream_t st);
 void launch_plan_generic_exact(const TablesDev &tb, const CandDev &cd, const PlansDev &out, int32_t *n_passes,
                                void *ws, int n_groups, hipStream_t st);
 size_t plan_generic_ws_per_group(int L, int S_max);
@@ -121,7 +121,8 @@ size_t plan_fast_index_bytes(const TablesDev &tb, int S_max);
 int plan_fast_groups(int L, int S_max, int n_cu);
 int plan_fast_waves(int L, int S_max, int n_cu);
 constexpr int kFastWaves = 4;           // wavefronts per workgroup of k2_fast; they share nothing
-constexpr size_t kFastIndexLimit = size_t(256) << 20;   // feasibility index of the 32-bit path
+constexpr size_t kFastIndexLimit = size_t(256) << 20;   // feasibility index of the pre-pass
+constexpr int kIndexMaxL = 16383;       // its build keeps one 8-byte sum per cut in LDS (128 KB)
 void launch_plan_exact(const TablesDev &tb, const CandDev &cd, const PlansDev &out, int32_t *n_passes,
                        void *ws, int n_groups, hipStream_t st);
 void launch_score(const TablesDev &tb, const CandDev &cd, const int32_t *splits,

@@ -5,12 +5,21 @@
 // previous cuts j that can matter are tried.  One workgroup works on one candidate at a time; one lane
 // owns one DP cell of the current stage and walks j downwards from i - 1 until the stage no longer
 // fits in memory or its time alone rules every lower j out, keeping the lowest j among equal values
-// (no reachability bands, no feasibility index, no 32-bit rows: this path shares none of the fast
+// (no reachability bands, no feasibility index, no 32-bit rows: k2_generic shares none of the fast
 // kernel's pruning).  Rows of D and the back-pointers live in a
 // per-workgroup slice of the caller's workspace (L2-resident at the sizes of interest).  This path
 // accepts any degree (division when it is not a power of two) and any L up to 65535; the 32-bit
 // path in k2_fast.hip is the fast one.
+//
+// k2_banded is the min-max planner of this path when the batch's feasibility index fits its limit
+// (it does unless L, the in-flight counts and the degree list are all large): same int64
+// arithmetic, but it runs behind the pre-pass of k2_fast.hip, which needs nothing but the memory
+// sums, and so works on the reachability bands only and reads each cell's lowest fitting previous
+// cut from the index instead of evaluating eq. mem_cons per transition.  The rows it keeps in LDS
+// are a third of the unbanded kernel's per candidate, so several times as many candidates are in
+// flight per CU.
 #include "harp_internal.h"
+#include "fast_common.h"
 #include "plan_common.h"
 
 namespace harp {
@@ -172,6 +181,175 @@ __global__ __launch_bounds__(kThreads) void k2_generic(TablesDev tb, CandDev cd,
                 out.status[c] = st;
             }
         }
+    }
+}
+
+// ---------------------------------------------------------------------------------- k2_banded
+
+constexpr int kBandedThreads = 128;
+constexpr int kBandedLdsL = 2047;       // 4 rows x 2048 x 8 B = 64 KB: stage sums and DP rows in LDS up to here
+
+size_t banded_lds_bytes(int L) { return L <= kBandedLdsL ? size_t(4) * (L + 1) * sizeof(int64_t) : 0; }
+
+// The min-max recurrence of one live candidate over its bands: row s + 1 has the cells
+// B[s+1] .. F[s+1], cell i tries the previous cuts max(lo(i), B[s]) .. min(i - 1, F[s]) downwards,
+// lo(i) from the feasibility index.  The scan stops as in the unbanded kernel once the stage time
+// alone exceeds the best value (strictly; the update is non-strict, so the lowest j among equal
+// values is kept).  The last stage has the single cell L: its previous cuts are spread over the
+// threads and reduced.  Returns D[S][L] to every thread; back-pointers are in w.arg.
+__device__ __forceinline__ int64_t banded_pass(const TablesDev &tb, const SlotInfo &slots, int S,
+                                               const uint32_t *band, const uint16_t *lo_tab, int lo_pitch,
+                                               const GenericSlice &w, int64_t *red_v, int *red_j) {
+    extern __shared__ __align__(16) unsigned char generic_lds[];
+    const int L = tb.L;
+    const bool rows_in_lds = L <= kBandedLdsL;
+    int64_t *stage = reinterpret_cast<int64_t *>(generic_lds);       // [4][L + 1] when rows_in_lds
+    int64_t *Dp = w.D0, *Dn = w.D1;
+    if (rows_in_lds) {
+        Dp = stage + 2 * (L + 1);
+        Dn = stage + 3 * (L + 1);
+    }
+    if (threadIdx.x == 0) Dp[0] = 0;          // row 0 is the single cut 0 (its band)
+    const int rows_per_n = tb.T * tb.n_tp;
+    for (int s = 0; s < S; ++s) {
+        const int g = slots.g[s], k = slots.k[s];
+        const int64_t tp = tb.tp[k];
+        const int shift = tb.tp_shift[k];
+        const int t = tb.group_type[g];
+        const int64_t *pf = tb.PF(t), *pr = tb.PR(g, k);
+        const uint32_t b0 = band[s], b1 = band[s + 1];
+        const int jl = fastdp::band_lo(b0), jh = fastdp::band_hi(b0);      // previous cuts: row s
+        const int il = fastdp::band_lo(b1), ih = fastdp::band_hi(b1);      // cells: row s + 1
+        __syncthreads();                      // row s is complete, the previous stage's sums are free
+        if (rows_in_lds) {
+            int64_t *spf = stage, *spr = stage + (L + 1);
+            for (int i = jl + int(threadIdx.x); i <= ih; i += kBandedThreads) { spf[i] = pf[i]; spr[i] = pr[i]; }
+            __syncthreads();
+            pf = spf;
+            pr = spr;
+        }
+        const int n_inflight = (S - s) < tb.M ? (S - s) : tb.M;
+        const uint16_t *lo_row = lo_tab + (size_t(n_inflight - 1) * rows_per_n + size_t(t) * tb.n_tp + k) * lo_pitch;
+        const bool last = (s == S - 1);
+        uint16_t *arg_row = w.arg + size_t(s) * (L + 1);
+        if (!last) {
+            const int64_t link = tb.bw[int64_t(g) * tb.G + slots.g[s + 1]];
+            for (int i = il + int(threadIdx.x); i <= ih; i += kBandedThreads) {
+                const int64_t cut = (tb.act_bytes[i - 1] + link - 1) / link;
+                const int64_t pfi = pf[i] + tp - 1, pri = pr[i];
+                const int lo_i = lo_row[i];
+                const int lo = lo_i > jl ? lo_i : jl;
+                const int hi = (i - 1) < jh ? (i - 1) : jh;
+                int64_t best = kInf;
+                int best_j = i - 1;
+                for (int j = hi; j >= lo; --j) {
+                    const int64_t work = pfi - pf[j];
+                    const int64_t comp = shift >= 0 ? work >> shift : work / tp;
+                    const int64_t time = comp + (pri - pr[j]);
+                    if (time > best) break;
+                    const int64_t dj = Dp[j];
+                    int64_t val = time > dj ? time : dj;      // dj = kInf (unreachable cut) stays kInf
+                    val = val > cut ? val : cut;
+                    if (val <= best && dj != kInf) { best = val; best_j = j; }
+                }
+                Dn[i] = best;
+                arg_row[i] = (uint16_t)best_j;
+            }
+        } else {
+            // cell L: threads over the previous cuts, then the least value and the lowest cut among equals
+            const int64_t pfi = pf[L] + tp - 1, pri = pr[L];
+            const int lo_i = lo_row[L];
+            const int lo = lo_i > jl ? lo_i : jl;
+            const int hi = (L - 1) < jh ? (L - 1) : jh;
+            int64_t best = kInf;
+            int best_j = INT32_MAX;
+            for (int j = lo + int(threadIdx.x); j <= hi; j += kBandedThreads) {
+                const int64_t work = pfi - pf[j];
+                const int64_t comp = shift >= 0 ? work >> shift : work / tp;
+                const int64_t time = comp + (pri - pr[j]);
+                const int64_t dj = Dp[j];
+                const int64_t val = time > dj ? time : dj;
+                if (val < best) { best = val; best_j = j; }      // j rises within a thread
+            }
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) {
+                const int64_t ov = __shfl_xor(best, d, 64);
+                const int oj = __shfl_xor(best_j, d, 64);
+                if (ov < best || (ov == best && oj < best_j)) { best = ov; best_j = oj; }
+            }
+            if ((threadIdx.x & 63) == 0) { red_v[threadIdx.x >> 6] = best; red_j[threadIdx.x >> 6] = best_j; }
+            __syncthreads();
+            if (threadIdx.x == 0) {
+                for (int q = 1; q < kBandedThreads / 64; ++q)
+                    if (red_v[q] < best || (red_v[q] == best && red_j[q] < best_j)) { best = red_v[q]; best_j = red_j[q]; }
+                red_v[0] = best;
+                arg_row[L] = (uint16_t)(best == kInf ? L - 1 : best_j);
+            }
+            __syncthreads();
+            return red_v[0];
+        }
+        int64_t *tmp = Dp; Dp = Dn; Dn = tmp;
+    }
+    return kInf;          // S >= 1: the last stage returns above
+}
+
+__global__ __launch_bounds__(kBandedThreads) void k2_banded(TablesDev tb, CandDev cd, PlansDev out, int *counts,
+                                                             const int32_t *live_list, const uint32_t *dead_list,
+                                                             const uint32_t *bands, const uint16_t *lo_tab,
+                                                             int lo_pitch, unsigned char *ws, size_t ws_per_group) {
+    __shared__ SlotInfo slots;
+    __shared__ uint32_t band[kMaxStages + 1];
+    __shared__ int64_t red_v[kBandedThreads / 64];
+    __shared__ int red_j[kBandedThreads / 64];
+    __shared__ int ticket;
+    const int L = tb.L, S_max = cd.S_max;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const GenericSlice w = generic_slice(ws, ws_per_group, L);
+    const int n_live = counts[0], n_dead = counts[1];
+
+    // candidates differ in stages and band widths: workgroups draw them from a shared counter
+    for (;;) {
+        __syncthreads();   // previous candidate's tail is done with the shared state
+        if (threadIdx.x == 0) ticket = atomicAdd(&counts[5], 1);
+        __syncthreads();
+        const int n = ticket;
+        if (n >= n_live) break;
+        const int c = live_list[n];
+        const int S = cd.cand_S[c];
+        const int32_t *grp = cd.cand_group + int64_t(c) * S_max;
+        const int32_t *tpv = cd.cand_tp + int64_t(c) * S_max;
+        // the pre-pass has checked the slot list; this fills the slot arrays and the first devices
+        const int status = load_and_check_slots(tb, S, S_max, grp, tpv, slots);
+        if (status != HARP_CAND_OK) {
+            write_failed(out, c, S_max, status);
+            continue;
+        }
+        for (int s = threadIdx.x; s <= S; s += kBandedThreads) band[s] = bands[int64_t(c) * (S_max + 1) + s];
+        __syncthreads();
+        if (banded_pass(tb, slots, S, band, lo_tab, lo_pitch, w, red_v, red_j) == kInf) {
+            write_failed(out, c, S_max, HARP_CAND_INFEASIBLE);      // the bands were bounds only
+            continue;
+        }
+        int32_t *sp = out.splits + int64_t(c) * (S_max + 1);
+        if (threadIdx.x == 0) generic_backtrack(w, S, L, sp);
+        for (int s = S + 1 + threadIdx.x; s <= S_max; s += kBandedThreads) sp[s] = -1;
+        int32_t *df = out.dev_first + int64_t(c) * S_max;
+        for (int s = threadIdx.x; s < S_max; s += kBandedThreads) df[s] = s < S ? slots.dev_first[s] : -1;
+        __syncthreads();              // the cuts written by thread 0 are read by the first wave
+        if (wave == 0) {
+            int64_t bott, iter;
+            const int st = wave_score_partition(tb, S, slots.g, slots.k, sp, lane, bott, iter);
+            if (lane == 0) {
+                out.bottleneck[c] = bott;
+                out.iter_time[c] = iter;
+                out.status[c] = st;
+            }
+        }
+    }
+    // candidates the pre-pass rejected: no plan to report
+    for (int n = blockIdx.x; n < n_dead; n += gridDim.x) {
+        const uint32_t e = dead_list[n];
+        write_failed(out, int(e & ((1u << fastdp::kDeadStatusShift) - 1u)), S_max, int(e >> fastdp::kDeadStatusShift));
     }
 }
 
@@ -451,10 +629,20 @@ size_t plan_generic_ws_per_group(int L, int S_max) {
     return (b + 255) & ~size_t(255);
 }
 
+// banded: the workspace starts with the pre-pass area (plan_fast_ws_bytes with no slices) and the
+// workgroups' slices follow it.
 void launch_plan_generic(const TablesDev &tb, const CandDev &cd, const PlansDev &out, void *ws,
-                         int n_groups, hipStream_t st) {
-    hipLaunchKernelGGL(k2_generic, dim3(n_groups), dim3(kThreads), generic_lds_bytes(tb.L), st, tb, cd, out,
-                       static_cast<unsigned char *>(ws), plan_generic_ws_per_group(tb.L, cd.S_max));
+                         int n_groups, bool banded, hipStream_t st) {
+    if (!banded) {
+        hipLaunchKernelGGL(k2_generic, dim3(n_groups), dim3(kThreads), generic_lds_bytes(tb.L), st, tb, cd, out,
+                           static_cast<unsigned char *>(ws), plan_generic_ws_per_group(tb.L, cd.S_max));
+        return;
+    }
+    const fastdp::FastWorkspace w = fastdp::carve(ws, fastdp::fast_shape(tb, cd), 0);
+    launch_plan_prepass(tb, cd, ws, 0, st);
+    hipLaunchKernelGGL(k2_banded, dim3(n_groups), dim3(kBandedThreads), banded_lds_bytes(tb.L), st, tb, cd, out,
+                       w.counts, w.live_list, w.dead_list, w.bands, w.lo_tab, int(fastdp::lo_pitch(tb.L)),
+                       static_cast<unsigned char *>(ws) + w.total, plan_generic_ws_per_group(tb.L, cd.S_max));
 }
 
 void launch_plan_generic_exact(const TablesDev &tb, const CandDev &cd, const PlansDev &out, int32_t *n_passes,
