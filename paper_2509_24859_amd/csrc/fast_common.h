@@ -74,9 +74,17 @@ inline size_t fast_lds_bytes(int L, int S_max) {
     return (b + 15) & ~size_t(15);
 }
 
-inline size_t fast_arg_per_group(int L, int S_max) {
+// Back-pointer slice of one wavefront (k2_fast) or workgroup (the kernels built on it): a 16-bit
+// entry per DP cell, followed by the one-byte entries k2_fast uses for cells whose back-pointers
+// leave LDS (distance to the previous cut; the 16-bit entry holds the cut itself when the distance
+// does not fit a byte).
+inline size_t fast_arg_u16_bytes(int L, int S_max) {
     size_t b = size_t(S_max) * fast_row_len(L) * sizeof(uint16_t);
     return (b + 255) & ~size_t(255);
+}
+inline size_t fast_arg_per_group(int L, int S_max) {
+    size_t b = size_t(S_max) * fast_row_len(L);
+    return fast_arg_u16_bytes(L, S_max) + ((b + 255) & ~size_t(255));
 }
 
 // Rows of the feasibility index (see k2_fast.hip): one per in-flight count n = 1 .. n_max, GPU type and

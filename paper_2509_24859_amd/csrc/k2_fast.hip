@@ -247,6 +247,8 @@ __global__ void k2_clear_work(unsigned long long *work) {
 
 constexpr int kPrefetchChunks = 4;      // chunks of the next stage's time row held in registers
 constexpr int kArgEscape = 255;         // one-byte back-pointer: distance too long, see the slice
+constexpr uint32_t kArgBias = 1u << 16;     // keeps (stage offset - lowest cut of the row) positive
+constexpr uint32_t kArgInLds = 1u << 31;    // flag on that word: the stage's back-pointers are in the LDS arena
 
 // wavefront-scope ordering of LDS traffic: one wavefront's LDS operations execute in order, so
 // this only keeps the compiler from moving accesses across the phases of a stage
@@ -263,6 +265,7 @@ struct FastArgs {
     const uint16_t *lo_tab;       // feasibility index
     unsigned char *arg_base;      // back-pointer slices
     size_t arg_per_wave;
+    size_t arg_u8_off;            // where a slice's one-byte entries start
     unsigned long long *work;     // [4] transitions, cells, trips, candidates (counting build only)
     int lo_pitch, lds_per_wave;
     int wide_pass;                // 1: the pass over the candidates the first pass found too wide for its LDS share
@@ -299,6 +302,7 @@ __global__ __launch_bounds__(kFastWaves * 64) void k2_fast(TablesDev tb, CandDev
     // row entries: entry of cut j of the stage whose lowest cut is `base` sits at rows0[j - base]
     Pair *rows0 = reinterpret_cast<Pair *>(mine + small_bytes) + kPad;
     uint16_t *slice = reinterpret_cast<uint16_t *>(fa.arg_base + size_t(wave_id) * fa.arg_per_wave);
+    uint8_t *slice8 = reinterpret_cast<uint8_t *>(slice) + fa.arg_u8_off;
     // first pass: the live list; second pass: the candidates the first one queued behind the dead list
     const int n_dead = counts[1];
     const int n_live = fa.wide_pass ? counts[8] : counts[0];
@@ -368,8 +372,9 @@ __global__ __launch_bounds__(kFastWaves * 64) void k2_fast(TablesDev tb, CandDev
                     const uint32_t o = __shfl_up(inc, d, 64);
                     if (lane >= d) inc += o;
                 }
-                // aoff[s - 1] = offset of stage s - 1, whose cells are row s
-                if (s >= 1 && s <= S) aoff[s - 1] = carry + inc - wdt;
+                // aoff[s - 1] = where the back-pointer of cut 0 of row s would sit (stage s - 1 writes
+                // row s): the stage's offset less the row's lowest cut, biased to stay positive
+                if (s >= 1 && s <= S) aoff[s - 1] = carry + inc - wdt + kArgBias - uint32_t(band_lo(b));
                 carry += __shfl(inc, 63, 64);
             }
         }
@@ -395,6 +400,12 @@ __global__ __launch_bounds__(kFastWaves * 64) void k2_fast(TablesDev tb, CandDev
         }
         uint8_t *arena = reinterpret_cast<uint8_t *>(mine) + small_bytes + row_bytes;
         const uint32_t arena_bytes = uint32_t(fa.lds_per_wave - small_bytes - row_bytes);
+        // stages whose back-pointers fit the arena (offset + width within it) are flagged once
+        for (int s = lane; s + 1 < S; s += 64) {
+            const uint32_t end = aoff[s] - kArgBias + uint32_t(band_hi(band[s + 1])) + 1u;
+            if (end <= arena_bytes) aoff[s] |= kArgInLds;
+        }
+        wave_sync();
         int32_t *sp = out.splits + int64_t(c) * (S_max + 1);
         uint32_t final_v = 0;
         if (S >= 2) {
@@ -427,8 +438,9 @@ __global__ __launch_bounds__(kFastWaves * 64) void k2_fast(TablesDev tb, CandDev
                 const uint32_t tp = 1u << shift;
                 const Stage nxt = stage_of(s + 1, S);
                 const bool nxt_is_last = s + 2 == S;
-                const uint32_t a0 = (uint32_t)uniform((int)aoff[s]);
-                const bool arg_in_lds = a0 + uint32_t(ih - il + 1) <= arena_bytes;
+                const uint32_t a_word = (uint32_t)uniform((int)aoff[s]);
+                const bool arg_in_lds = (a_word & kArgInLds) != 0;
+                const uint32_t a0 = (a_word & ~kArgInLds) - kArgBias;       // + cut = index of the cut's back-pointer
                 Pair *rows = rows0 - jl;          // this stage's entries: cut j at rows[j], from B[s] on
 
                 // requests for the time row of stage s+1: entries [il, top_n], first chunks in registers
@@ -515,13 +527,12 @@ __global__ __launch_bounds__(kFastWaves * 64) void k2_fast(TablesDev tb, CandDev
                     if (i <= ih) {
                         rows[i].d = best;
                         const int rel = i - 1 - best_j;
-                        const uint32_t at = a0 + uint32_t(i - il);
-                        if (arg_in_lds) {
-                            arena[at] = (uint8_t)(rel < kArgEscape ? rel : kArgEscape);
-                            if (rel >= kArgEscape) slice[at] = (uint16_t)best_j;
-                        } else {
-                            slice[at] = (uint16_t)best_j;
-                        }
+                        const uint32_t at = a0 + uint32_t(i);
+                        // one byte per cell, in LDS while the candidate's rows fit the arena
+                        const uint8_t code = (uint8_t)(rel < kArgEscape ? rel : kArgEscape);
+                        if (arg_in_lds) arena[at] = code;
+                        else slice8[at] = code;
+                        if (rel >= kArgEscape) slice[at] = (uint16_t)best_j;
                     }
                     wave_sync();
                     cut_c = cut_n;
@@ -594,15 +605,12 @@ __global__ __launch_bounds__(kFastWaves * 64) void k2_fast(TablesDev tb, CandDev
                 cuts[S] = L;
                 cuts[S - 1] = b;
                 for (int s = S - 2; s >= 0; --s) {
-                    const uint32_t b1 = band[s + 1];
-                    const uint32_t a0 = aoff[s];
-                    const uint32_t at = a0 + uint32_t(b - band_lo(b1));
-                    if (a0 + uint32_t(band_hi(b1) - band_lo(b1) + 1) <= arena_bytes) {
-                        const int rel = arena[at];
-                        b = rel == kArgEscape ? int(slice[at]) : b - 1 - rel;
-                    } else {
-                        b = slice[at];
-                    }
+                    const uint32_t a_word = aoff[s];
+                    const uint32_t at = (a_word & ~kArgInLds) - kArgBias + uint32_t(b);
+                    int rel;
+                    if (a_word & kArgInLds) rel = arena[at];
+                    else rel = slice8[at];
+                    b = rel == kArgEscape ? int(slice[at]) : b - 1 - rel;
                     cuts[s] = b;
                 }
             }
@@ -755,6 +763,7 @@ void launch_plan_fast(const TablesDev &tb, const CandDev &cd, const PlansDev &ou
     fa.lo_tab = w.lo_tab;
     fa.arg_base = w.arg;
     fa.arg_per_wave = fast_arg_per_group(tb.L, cd.S_max);
+    fa.arg_u8_off = fast_arg_u16_bytes(tb.L, cd.S_max);
     fa.work = work;
     fa.lo_pitch = int(lo_pitch(tb.L));
     fa.shift_packed = 0;
