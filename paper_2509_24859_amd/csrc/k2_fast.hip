@@ -20,9 +20,11 @@
 //    of its submesh, tp devices of one GPU type.  The pre-pass therefore also writes a feasibility
 //    index of stage ranges per (count, GPU type, degree) into the workspace, once per call (the
 //    precomputed index of feasible stage-mesh pairs of section 5.2.4 (1), reduced to what this
-//    device model needs: one lower limit per end cut): row (n, type, k), entry i = the lowest j such
-//    that operators [j, i) fit.  A DP cell then knows its range of previous cuts from one 16-bit
-//    load, and the recurrence itself touches no byte count at all.
+//    device model needs: one lower limit per end cut and one upper limit per start cut): row
+//    (n, type, k), entry i = the lowest j such that operators [j, i) fit, and in a second table
+//    entry j = the highest i such that they do.  A DP cell then knows its range of previous cuts
+//    from one 16-bit load, the recurrence itself touches no byte count at all, and each link of
+//    the band chains above is one lookup.
 //  * the stage time time(s; j, i) never decreases when j moves down.  Scanning j downwards from
 //    i-1, once time(s; j, i) exceeds the best value found so far no lower j can match or beat it,
 //    and the scan stops.  The stop uses a strict comparison and the update a non-strict one, so
@@ -46,9 +48,12 @@
 // (its entries were requested from global memory before the stage's scans and wait in registers).
 // Previous cuts are scanned four per trip; a trip keeps the least of its four values and its own
 // position, and the lowest cut inside the winning trip is found once per cell afterwards.
-// Back-pointers are one byte each (distance to the previous cut) in an LDS arena while the
-// candidate's rows fit there, 16-bit in a per-wavefront slice of the workspace beyond that, so the
-// backtrack of most candidates never leaves the CU.
+// The buffer is band-relative: the entry of cut j of stage s sits at offset j - B[s], and the buffer
+// is sized for the candidate's widest stage, not for L; a candidate whose widest stage does not fit
+// the wavefront's share of LDS is queued for a second pass with a share sized for L.
+// Back-pointers are one byte each (distance to the previous cut; 255 refers to a 16-bit entry in
+// the wavefront's slice of the workspace): in an LDS arena while the candidate's rows fit there, so
+// that the backtrack of most candidates never leaves the CU, in the slice beyond that.
 #include "harp_internal.h"
 #include "fast_common.h"
 #include "plan_common.h"
