@@ -498,17 +498,37 @@ __global__ __launch_bounds__(256) void k1_finalize(TablesDev tb, BuildLimits lim
         int t = tb.group_type[g];
         if (t < 0 || t >= tb.T || tb.group_ndev[g] < 1) atomicOr(&bad_s, 1u);
     }
+    // first device of every group: exclusive running sum of the group sizes.  Each thread takes a run
+    // of consecutive groups, the runs' totals are scanned in LDS, and no load waits on a store.
+    __shared__ long long run_total[256];
+    const int per = (tb.G + 255) / 256;
+    const int g_begin = threadIdx.x * per, g_end = (g_begin + per) < tb.G ? (g_begin + per) : tb.G;
+    long long mine = 0;
+    for (int g = g_begin; g < g_end; ++g) {
+        const int n = tb.group_ndev[g];
+        mine += n > 0 ? n : 0;
+    }
+    run_total[threadIdx.x] = mine;
     __syncthreads();
     const bool groups_ok = (bad_s == 0);
-    if (threadIdx.x == 0) {
-        int64_t base = 0;
-        for (int g = 0; g < tb.G; ++g) {
-            tb.group_base[g] = (int32_t)base;
-            int n = tb.group_ndev[g];
+    for (int d = 1; d < 256; d <<= 1) {
+        const long long add = threadIdx.x >= d ? run_total[threadIdx.x - d] : 0;
+        __syncthreads();
+        run_total[threadIdx.x] += add;
+        __syncthreads();
+    }
+    {
+        long long base = run_total[threadIdx.x] - mine;           // devices before this thread's run
+        for (int g = g_begin; g < g_end; ++g) {
+            tb.group_base[g] = (int32_t)(base > INT32_MAX ? 0 : base);
+            const int n = tb.group_ndev[g];
             base += n > 0 ? n : 0;
-            if (base > INT32_MAX) { atomicOr(&ovf_s, 1u); base = 0; }
         }
-        tb.header->total_devices = base;
+        if (threadIdx.x == 255) {
+            // more devices than an int32 numbers: the problem is refused, the bases are not used
+            if (run_total[255] > INT32_MAX) atomicOr(&ovf_s, 1u);
+            tb.header->total_devices = run_total[255] > INT32_MAX ? 0 : run_total[255];
+        }
     }
     if (groups_ok) {
         for (int q = threadIdx.x; q < tb.G * tb.n_tp; q += blockDim.x) {
