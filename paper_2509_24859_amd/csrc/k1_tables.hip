@@ -310,8 +310,22 @@ __device__ __forceinline__ int64_t long_value(const TablesDev &tb, const RowSour
 // Order in which the long kernels walk the table rows: the fixed rows first, then the all-reduce
 // rows degree-major, so that groups whose own link has the same speed (the usual case: subclusters
 // of one GPU type) come one after the other with identical constants, and a row that equals the
-// one before it is stored again without being recomputed.
-__device__ __forceinline__ int long_row_order(const TablesDev &tb, int x) {
+// one before it is stored again without being recomputed.  The gridDim.y parts of a launch take
+// consecutive stretches of this order.  (Dealing the fixed rows, the ones that read their values
+// from memory, evenly over the parts was measured and is slower: 0.45 against 0.40 ms per build.)
+struct LongPart {
+    int x_begin, x_end;     // walk positions of this part
+};
+
+__device__ __forceinline__ LongPart long_part(const TablesDev &tb) {
+    const int n_rows = tb.n_rows();
+    LongPart lp;
+    lp.x_begin = int(int64_t(n_rows) * blockIdx.y / gridDim.y);
+    lp.x_end = int(int64_t(n_rows) * (blockIdx.y + 1) / gridDim.y);
+    return lp;
+}
+
+__device__ __forceinline__ int long_row_order(const TablesDev &tb, const LongPart &, int x) {
     const int n_fixed = tb.T + 2;
     if (x < n_fixed) return x;
     const int e = x - n_fixed;
@@ -319,7 +333,7 @@ __device__ __forceinline__ int long_row_order(const TablesDev &tb, int x) {
     return n_fixed + g * tb.n_tp + k;
 }
 
-// Row constants of the table rows a workgroup walks (positions x_begin .. x_end - 1 of the order
+// Row constants of the table rows a workgroup walks (its part of the order
 // above), worked out once per workgroup (each needs a link bandwidth from memory and a reciprocal)
 // and kept in LDS.  The array is dynamic LDS sized for the workgroup's share of this problem's rows:
 // a fixed array for the largest case would leave room for two workgroups per CU only.
@@ -329,22 +343,51 @@ struct LongRow {
 };
 constexpr int kLongRowsInLds = 512;     // rows per workgroup beyond which the constants are recomputed per use
 
-__device__ __forceinline__ void stage_long_rows(const TablesDev &tb, LongRow *rows_lds, int x_begin, int x_end) {
+// What the walk needs first of a row, 8 bytes: the table row it is, and whether it is an all-reduce
+// row of the tight form with the same multiplier and divisor as the row walked just before it.  Most
+// rows of a cluster are (groups of one GPU type share their link speed), and for those the walk
+// reads nothing else.
+struct LongRowKey {
+    int32_t r;
+    int32_t same_as_previous;
+};
+
+__device__ __forceinline__ bool ar_tight_row(const LongRow &lr) {
+    return lr.src.is_ar && lr.arr.fast && lr.arr.den >= lr.arr.mul;
+}
+
+// Dynamic LDS of the long kernels: the workgroup's row constants, then their keys.
+__device__ __forceinline__ LongRowKey *long_row_keys(LongRow *rows_lds, int x_begin, int x_end) {
+    return reinterpret_cast<LongRowKey *>(rows_lds + (x_end - x_begin));
+}
+
+__device__ __forceinline__ void stage_long_rows(const TablesDev &tb, LongRow *rows_lds, const LongPart &lp) {
+    const int x_begin = lp.x_begin, x_end = lp.x_end;
     if (x_end - x_begin <= kLongRowsInLds) {
+        LongRowKey *keys = long_row_keys(rows_lds, x_begin, x_end);
         for (int x = x_begin + threadIdx.x; x < x_end; x += blockDim.x) {
-            const int r = long_row_order(tb, x);
+            const int r = long_row_order(tb, lp, x);
             rows_lds[x - x_begin].src = row_source(tb, r);
             rows_lds[x - x_begin].arr = ar_row(rows_lds[x - x_begin].src);
+            keys[x - x_begin].r = r;
+        }
+        __syncthreads();
+        for (int x = x_begin + threadIdx.x; x < x_end; x += blockDim.x) {
+            bool same = false;
+            if (x > x_begin) {
+                const LongRow &a = rows_lds[x - x_begin], &b = rows_lds[x - 1 - x_begin];
+                same = ar_tight_row(a) && ar_tight_row(b) && a.arr.mul == b.arr.mul && a.arr.den == b.arr.den;
+            }
+            keys[x - x_begin].same_as_previous = same ? 1 : 0;
         }
     }
     __syncthreads();
 }
 
-__device__ __forceinline__ LongRow long_row(const TablesDev &tb, const LongRow *rows_lds, int x_begin, int x_end,
-                                            int x) {
-    if (x_end - x_begin <= kLongRowsInLds) return rows_lds[x - x_begin];
+__device__ __forceinline__ LongRow long_row(const TablesDev &tb, const LongRow *rows_lds, const LongPart &lp, int x) {
+    if (lp.x_end - lp.x_begin <= kLongRowsInLds) return rows_lds[x - lp.x_begin];
     LongRow lr;
-    lr.src = row_source(tb, long_row_order(tb, x));
+    lr.src = row_source(tb, long_row_order(tb, lp, x));
     lr.arr = ar_row(lr.src);
     return lr;
 }
@@ -353,14 +396,17 @@ __device__ __forceinline__ LongRow long_row(const TablesDev &tb, const LongRow *
 __global__ __launch_bounds__(kScanThreads) void k1_long_sums(TablesDev tb, BuildLimits lim, int n_runs) {
     extern __shared__ __align__(16) unsigned char long_lds[];
     LongRow *rows_lds = reinterpret_cast<LongRow *>(long_lds);
-    const int n_rows = tb.n_rows();
     // the rows are split over gridDim.y workgroups so that enough wavefronts are in flight
-    const int x_begin = int(int64_t(n_rows) * blockIdx.y / gridDim.y);
-    const int x_end = int(int64_t(n_rows) * (blockIdx.y + 1) / gridDim.y);
-    stage_long_rows(tb, rows_lds, x_begin, x_end);
+    const LongPart lp = long_part(tb);
+    const int x_begin = lp.x_begin, x_end = lp.x_end;
+    stage_long_rows(tb, rows_lds, lp);
+    const bool keyed = x_end - x_begin <= kLongRowsInLds;
+    const LongRowKey *keys = long_row_keys(rows_lds, x_begin, x_end);
     const int lane = threadIdx.x & 63;
-    const int run = blockIdx.x * (kScanThreads / 64) + (threadIdx.x >> 6);
-    if (run >= n_runs) return;
+    // a wavefront takes every (gridDim.x * wavefronts per workgroup)-th run, so that the row constants
+    // staged above serve several runs
+    for (int run = blockIdx.x * (kScanThreads / 64) + (threadIdx.x >> 6); run < n_runs;
+         run += gridDim.x * (kScanThreads / 64)) {
     const int64_t base = int64_t(run) * kWaveChunk + int64_t(lane) * kWaveItems;
     unsigned int bad = 0, ovf = 0;
     unsigned long long act_seen = 0;
@@ -368,8 +414,15 @@ __global__ __launch_bounds__(kScanThreads) void k1_long_sums(TablesDev tb, Build
     const bool all_narrow = __all(a.narrow);
     int64_t same_mul = -1, same_den = -1, same_sum = 0;     // the all-reduce row computed last
     for (int x = x_begin; x < x_end; ++x) {
-        const int r = long_row_order(tb, x);
-        const LongRow lr = long_row(tb, rows_lds, x_begin, x_end, x);
+        if (keyed) {
+            const LongRowKey key = keys[x - x_begin];
+            if (key.same_as_previous && all_narrow) {       // the row before it took the tight form: same sum
+                if (lane == 0) tb.chunk_sums[int64_t(key.r) * n_runs + run] = same_sum;
+                continue;
+            }
+        }
+        const int r = long_row_order(tb, lp, x);
+        const LongRow lr = long_row(tb, rows_lds, lp, x);
         const RowSource &src = lr.src;
         const ArRow &arr = lr.arr;
         int64_t sum = 0;
@@ -393,6 +446,7 @@ __global__ __launch_bounds__(kScanThreads) void k1_long_sums(TablesDev tb, Build
         }
         if (lane == 0) tb.chunk_sums[int64_t(r) * n_runs + run] = sum;
     }
+    }
     // values are checked again by the scan launch; nothing to report here
 }
 
@@ -400,58 +454,67 @@ __global__ __launch_bounds__(kScanThreads) void k1_long_sums(TablesDev tb, Build
 __global__ __launch_bounds__(kScanThreads) void k1_long_scan(TablesDev tb, BuildLimits lim, int n_runs) {
     extern __shared__ __align__(16) unsigned char long_lds[];
     LongRow *rows_lds = reinterpret_cast<LongRow *>(long_lds);
-    const int n_rows = tb.n_rows();
     // the rows are split over gridDim.y workgroups so that enough wavefronts are in flight
-    const int x_begin = int(int64_t(n_rows) * blockIdx.y / gridDim.y);
-    const int x_end = int(int64_t(n_rows) * (blockIdx.y + 1) / gridDim.y);
-    stage_long_rows(tb, rows_lds, x_begin, x_end);
+    const LongPart lp = long_part(tb);
+    const int x_begin = lp.x_begin, x_end = lp.x_end;
+    stage_long_rows(tb, rows_lds, lp);
     __shared__ int64_t tiles[kScanThreads / 64][kWaveChunk];
+    const bool keyed = x_end - x_begin <= kLongRowsInLds;
+    const LongRowKey *keys = long_row_keys(rows_lds, x_begin, x_end);
     const int lane = threadIdx.x & 63;
-    const int run = blockIdx.x * (kScanThreads / 64) + (threadIdx.x >> 6);
-    if (run >= n_runs) return;
     int64_t *tile = tiles[threadIdx.x >> 6];
-    const int64_t base = int64_t(run) * kWaveChunk + int64_t(lane) * kWaveItems;
     unsigned int bad = 0, ovf = 0;
     unsigned long long act_seen = 0;
+    for (int run = blockIdx.x * (kScanThreads / 64) + (threadIdx.x >> 6); run < n_runs;
+         run += gridDim.x * (kScanThreads / 64)) {
+    const int64_t base = int64_t(run) * kWaveChunk + int64_t(lane) * kWaveItems;
     const ActRun a = load_act_run(tb, lim, base, bad, ovf, act_seen);
     const bool all_narrow = __all(a.narrow);
     int64_t same_mul = -1, same_den = -1, same_start = -1;  // what the LDS tile currently holds
     for (int x = x_begin; x < x_end; ++x) {
-        const int r = long_row_order(tb, x);
-        const LongRow lr = long_row(tb, rows_lds, x_begin, x_end, x);
-        const RowSource &src = lr.src;
-        const ArRow &arr = lr.arr;
+        LongRowKey key;
+        if (keyed) key = keys[x - x_begin];
+        else { key.r = long_row_order(tb, lp, x); key.same_as_previous = 0; }
+        const int r = key.r;
         int64_t *out = tb.rows + int64_t(r) * tb.pitch;
         if (run == 0 && lane == 0) out[0] = 0;
         const int64_t start = tb.chunk_sums[int64_t(r) * n_runs + run];   // sum of the row before this run
-        const bool tight = src.is_ar && ar_tight(arr, all_narrow, lim);
-        // rows of groups with the same link speed and degree are identical: the tile already holds them
-        const bool reuse = tight && arr.mul == same_mul && arr.den == same_den && start == same_start;
+        // rows of groups with the same link speed and degree are identical: when the row walked just
+        // before this one took the tight form with the same constants and started from the same sum,
+        // the tile already holds this row (the key says so without a look at the row's constants)
+        bool reuse = key.same_as_previous && all_narrow && same_mul >= 0 && start == same_start;
         if (!reuse) {
-            int64_t v[kWaveItems];
-            int64_t sum = 0;
-            if (tight) {
-                uint32_t v32[kWaveItems];
-                ar_values_tight(arr, a, v32);
+            const LongRow lr = long_row(tb, rows_lds, lp, x);
+            const RowSource &src = lr.src;
+            const ArRow &arr = lr.arr;
+            const bool tight = src.is_ar && ar_tight(arr, all_narrow, lim);
+            reuse = tight && arr.mul == same_mul && arr.den == same_den && start == same_start;
+            if (!reuse) {
+                int64_t v[kWaveItems];
+                int64_t sum = 0;
+                if (tight) {
+                    uint32_t v32[kWaveItems];
+                    ar_values_tight(arr, a, v32);
 #pragma unroll
-                for (int q = 0; q < kWaveItems; ++q) { v[q] = v32[q]; sum += v32[q]; }
-                same_mul = arr.mul; same_den = arr.den; same_start = start;
-            } else {
+                    for (int q = 0; q < kWaveItems; ++q) { v[q] = v32[q]; sum += v32[q]; }
+                    same_mul = arr.mul; same_den = arr.den; same_start = start;
+                } else {
+#pragma unroll
+                    for (int q = 0; q < kWaveItems; ++q) {
+                        v[q] = long_value(tb, src, arr, a, q, base, lim, bad, ovf);
+                        sum = add_checked(sum, v[q], ovf);
+                    }
+                    same_mul = -1;
+                }
+                const int64_t inc = wave_inclusive_scan(sum, lane, ovf);
+                int64_t acc = add_checked(start, inc - sum, ovf);
+                // a lane holds four consecutive entries; passing them through the wavefront's LDS tile
+                // turns four 8-byte stores at a 32-byte stride into four fully contiguous 512-byte stores
 #pragma unroll
                 for (int q = 0; q < kWaveItems; ++q) {
-                    v[q] = long_value(tb, src, arr, a, q, base, lim, bad, ovf);
-                    sum = add_checked(sum, v[q], ovf);
+                    acc = add_checked(acc, v[q], ovf);
+                    tile[lane * kWaveItems + q] = acc;
                 }
-                same_mul = -1;
-            }
-            const int64_t inc = wave_inclusive_scan(sum, lane, ovf);
-            int64_t acc = add_checked(start, inc - sum, ovf);
-            // a lane holds four consecutive entries; passing them through the wavefront's LDS tile
-            // turns four 8-byte stores at a 32-byte stride into four fully contiguous 512-byte stores
-#pragma unroll
-            for (int q = 0; q < kWaveItems; ++q) {
-                acc = add_checked(acc, v[q], ovf);
-                tile[lane * kWaveItems + q] = acc;
             }
         }
         const int64_t first = int64_t(run) * kWaveChunk;
@@ -461,6 +524,7 @@ __global__ __launch_bounds__(kScanThreads) void k1_long_scan(TablesDev tb, Build
             const int64_t val = tile[e];
             if (first + e < tb.L) out[first + e + 1] = val;
         }
+    }
     }
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) {
@@ -606,10 +670,13 @@ void launch_build(const TablesDev &tb, const BuildLimits &lim, hipStream_t st) {
     hipLaunchKernelGGL(k1_clear_header, dim3(1), dim3(64), 0, st, tb.header);
     if (tb.L >= kLongL) {
         const int n_runs = (tb.L + kWaveChunk - 1) / kWaveChunk;
-        const int groups = (n_runs + kScanThreads / 64 - 1) / (kScanThreads / 64);
+        // workgroups walk several runs each (their row constants are staged once), never more of them
+        // than half of what covers the sequence with one run per wavefront
+        int groups = (n_runs + kScanThreads / 64 - 1) / (kScanThreads / 64);
+        if (groups > 512) groups = (groups + 1) / 2;
         const int row_parts = n_rows >= 32 ? 4 : 1;
         const int rows_per_part = (n_rows + row_parts - 1) / row_parts + 1;
-        const size_t row_lds = rows_per_part <= kLongRowsInLds ? size_t(rows_per_part) * sizeof(LongRow) : 16;
+        const size_t row_lds = rows_per_part <= kLongRowsInLds ? size_t(rows_per_part) * (sizeof(LongRow) + sizeof(LongRowKey)) : 16;
         hipLaunchKernelGGL(k1_long_sums, dim3(groups, row_parts), dim3(kScanThreads), row_lds, st, tb, lim, n_runs);
         hipLaunchKernelGGL(k1_scan_chunk_sums, dim3(n_rows), dim3(kScanThreads), 0, st, tb, n_runs);
         hipLaunchKernelGGL(k1_long_scan, dim3(groups, row_parts), dim3(kScanThreads), row_lds, st, tb, lim, n_runs);
