@@ -250,7 +250,7 @@ __global__ void k2_clear_work(unsigned long long *work) {
 
 // ---------------------------------------------------------------------------------- k2_fast
 
-constexpr int kPrefetchChunks = 4;      // chunks of the next stage's time row held in registers
+constexpr int kPrefetchChunks = 2;      // chunks of the next stage's time row held in registers
 constexpr int kArgEscape = 255;         // one-byte back-pointer: distance too long, see the slice
 constexpr uint32_t kArgBias = 1u << 16;     // keeps (stage offset - lowest cut of the row) positive
 constexpr uint32_t kArgInLds = 1u << 31;    // flag on that word: the stage's back-pointers are in the LDS arena
