@@ -160,6 +160,58 @@ __global__ __launch_bounds__(kArgminThreads) void k4_argmin(int32_t C, const int
     }
 }
 
+// Large batches: the same selection by many workgroups and two atomics.  The least time first (signed
+// 64-bit minimum), then the lowest index that attains it (unsigned 32-bit minimum: the initial
+// 0xFFFFFFFF reads back as -1 when no candidate qualifies).
+constexpr int kArgminWideThreads = 256;
+constexpr int kArgminWideItems = 8;
+constexpr int kArgminWideFrom = 1 << 15;      // batches below this take the one-workgroup kernel
+
+__global__ void k4_argmin_open(int64_t *best_time, int32_t *best_index) {
+    if (threadIdx.x == 0) { *best_time = kInf; *best_index = -1; }
+}
+
+__global__ __launch_bounds__(kArgminWideThreads) void k4_argmin_time(int32_t C, const int64_t *iter_time,
+                                                                      const int32_t *status, int64_t *best_time) {
+    int64_t best = kInf;
+    const int stride = gridDim.x * kArgminWideThreads;
+    int c = blockIdx.x * kArgminWideThreads + threadIdx.x;
+    for (; c + (kArgminWideItems - 1) * stride < C; c += kArgminWideItems * stride) {
+        int32_t st[kArgminWideItems];
+        int64_t v[kArgminWideItems];
+#pragma unroll
+        for (int u = 0; u < kArgminWideItems; ++u) { st[u] = status[c + u * stride]; v[u] = iter_time[c + u * stride]; }
+#pragma unroll
+        for (int u = 0; u < kArgminWideItems; ++u)
+            if (st[u] == HARP_CAND_OK && v[u] < best) best = v[u];
+    }
+    for (; c < C; c += stride)
+        if (status[c] == HARP_CAND_OK && iter_time[c] < best) best = iter_time[c];
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        const int64_t o = __shfl_xor(best, d, 64);
+        best = o < best ? o : best;
+    }
+    if ((threadIdx.x & 63) == 0 && best != kInf) atomicMin(reinterpret_cast<long long *>(best_time), (long long)best);
+}
+
+__global__ __launch_bounds__(kArgminWideThreads) void k4_argmin_index(int32_t C, const int64_t *iter_time,
+                                                                       const int32_t *status, const int64_t *best_time,
+                                                                       int32_t *best_index) {
+    const int64_t want = *best_time;
+    if (want == kInf) return;                 // no candidate qualifies: the index stays -1
+    uint32_t bi = 0xFFFFFFFFu;
+    const int stride = gridDim.x * kArgminWideThreads;
+    for (int c = blockIdx.x * kArgminWideThreads + threadIdx.x; c < C; c += stride)
+        if (iter_time[c] == want && status[c] == HARP_CAND_OK && uint32_t(c) < bi) bi = uint32_t(c);
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        const uint32_t o = __shfl_xor(bi, d, 64);
+        bi = o < bi ? o : bi;
+    }
+    if ((threadIdx.x & 63) == 0 && bi != 0xFFFFFFFFu) atomicMin(reinterpret_cast<unsigned int *>(best_index), bi);
+}
+
 }  // namespace
 
 void launch_score(const TablesDev &tb, const CandDev &cd, const int32_t *splits,
@@ -181,7 +233,16 @@ void launch_score_h1f1b(const TablesDev &tb, const CandDev &cd, const int32_t *s
 
 void launch_argmin(int32_t C, const int64_t *iter_time, const int32_t *status, int64_t *best_time,
                    int32_t *best_index, hipStream_t st) {
-    hipLaunchKernelGGL(k4_argmin, dim3(1), dim3(kArgminThreads), 0, st, C, iter_time, status,
+    if (C < kArgminWideFrom) {
+        hipLaunchKernelGGL(k4_argmin, dim3(1), dim3(kArgminThreads), 0, st, C, iter_time, status,
+                           best_time, best_index);
+        return;
+    }
+    int groups = (C + kArgminWideThreads * kArgminWideItems - 1) / (kArgminWideThreads * kArgminWideItems);
+    if (groups > 2048) groups = 2048;
+    hipLaunchKernelGGL(k4_argmin_open, dim3(1), dim3(64), 0, st, best_time, best_index);
+    hipLaunchKernelGGL(k4_argmin_time, dim3(groups), dim3(kArgminWideThreads), 0, st, C, iter_time, status, best_time);
+    hipLaunchKernelGGL(k4_argmin_index, dim3(groups), dim3(kArgminWideThreads), 0, st, C, iter_time, status,
                        best_time, best_index);
 }
 

@@ -484,7 +484,7 @@ def test_score_parity_on_arbitrary_partitions(harp, ctx):
 def test_argmin_parity(harp, ctx):
     import torch
     rng = np.random.default_rng(3)
-    for n in (0, 1, 63, 64, 1000, 70001):
+    for n in (0, 1, 63, 64, 1000, 32767, 32768, 70001, 600011):   # one workgroup below 2^15, many from there on
         it = rng.integers(10, 50, size=n).astype(np.int64)
         st = rng.integers(0, 3, size=n).astype(np.int32)
         for status in (st, np.ones(n, dtype=np.int32)):
