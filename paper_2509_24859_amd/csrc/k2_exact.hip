@@ -62,8 +62,9 @@ constexpr int64_t kNarrowLimit = int64_t(1) << 31;   // sums below this run in 3
 template <typename SumT>
 __device__ __forceinline__ void exact_body(const TablesDev &tb, const CandDev &cd, const PlansDev &out,
                                            int32_t *n_passes, int *counts, const int32_t *live_list,
-                                           uint32_t *dead_list, const uint32_t *bands,
-                                           unsigned char *arg_base, size_t arg_per_group, int row_len) {
+                                           uint32_t *dead_list, const uint32_t *bands, const uint16_t *lo_tab,
+                                           int lo_pitch, unsigned char *arg_base, size_t arg_per_group,
+                                           int row_len) {
     using Pair = typename SumTraits<SumT>::Entry;
     constexpr SumT kInfSum = SumTraits<SumT>::inf;
     constexpr bool kWide = sizeof(SumT) == 8;
@@ -72,17 +73,19 @@ __device__ __forceinline__ void exact_body(const TablesDev &tb, const CandDev &c
     const int L = tb.L, S_max = cd.S_max;
     const int tid = threadIdx.x, lane = tid & 63, nthreads = blockDim.x;
     const int wave = uniform(tid >> 6);
-    int64_t *Qb = reinterpret_cast<int64_t *>(lds_raw) + kPad;                        // [2][row_len]
-    Pair *rows = reinterpret_cast<Pair *>(lds_raw + size_t(row_len) * 16) + kPad;     // [2][row_len]
-    StageConst *sc = reinterpret_cast<StageConst *>(lds_raw + size_t(row_len) * (16 + 2 * sizeof(Pair)));  // [S_max]
+    Pair *rows = reinterpret_cast<Pair *>(lds_raw) + kPad;                             // [2][row_len]
+    StageConst *sc = reinterpret_cast<StageConst *>(lds_raw + size_t(row_len) * (2 * sizeof(Pair)));      // [S_max]
     uint64_t *scal = reinterpret_cast<uint64_t *>(sc + S_max);                         // [2]
     uint32_t *band = reinterpret_cast<uint32_t *>(scal + 2);                           // [S_max + 1]
     int32_t *trial = reinterpret_cast<int32_t *>(band + S_max + 1);                    // [S_max + 1]
     int32_t *kept = trial + S_max + 1;                                                 // [S_max + 1]
     uint16_t *slot_g = reinterpret_cast<uint16_t *>(kept + S_max + 1);                 // [S_max]
     uint8_t *slot_k = reinterpret_cast<uint8_t *>(slot_g + S_max);                     // [S_max]
+    // element offset of each stage's row of the feasibility index (lowest fitting previous cut per cut)
+    uint32_t *lo_off = reinterpret_cast<uint32_t *>(lds_raw + ((size_t(row_len) * (2 * sizeof(Pair)) +
+                                                               size_t(S_max) * sizeof(StageConst) + 16 +
+                                                               size_t(S_max + 1) * 12 + size_t(S_max) * 3 + 3) & ~size_t(3)));
     uint16_t *arg = reinterpret_cast<uint16_t *>(arg_base + size_t(blockIdx.x) * arg_per_group);
-    const int64_t *PP = tb.PP(), *PS = tb.PS();
     const int n_dead = counts[1];
     const int n_items = kWide ? counts[2] : counts[0];
     const int64_t m_cap = tb.M;
@@ -122,6 +125,9 @@ __device__ __forceinline__ void exact_body(const TablesDev &tb, const CandDev &c
                 sc[s].p_row = uint32_t((int64_t(g) * tb.n_tp + k) * tb.pitch32);
                 sc[s].cm_row_shift = uint32_t((int64_t(g) * tb.G + g_next) * tb.pitch32) |
                                      (uint32_t(tb.tp_shift[k]) << 27);
+                const int n_inflight = int((S - s) < m_cap ? (S - s) : m_cap);
+                lo_off[s] = uint32_t((int64_t(n_inflight - 1) * tb.T * tb.n_tp + int64_t(tb.group_type[g]) * tb.n_tp + k) *
+                                     lo_pitch);
             }
             for (int s = tid; s <= S; s += nthreads) band[s] = bands[int64_t(c) * (S_max + 1) + s];
         }
@@ -134,16 +140,14 @@ __device__ __forceinline__ void exact_body(const TablesDev &tb, const CandDev &c
             const uint32_t tcap = (uint32_t)uniform((int)(uint32_t)t_cap64);
             // ---- one capped pass
             uint32_t cut_i = 0;
+            int lo_i = 0;
             {
                 const uint32_t *p32 = tb.P32 + (uint32_t)uniform((int)sc[0].p_row);
                 const uint32_t *cm = tb.CM + ((uint32_t)uniform((int)sc[0].cm_row_shift) & kRowMask);
-                const int64_t n0 = S < m_cap ? S : m_cap;
+                const uint16_t *lo0 = lo_tab + (uint32_t)uniform((int)lo_off[0]);
                 const uint32_t b1 = (uint32_t)uniform((int)band[1]);
-                for (int j = tid; j <= band_hi(b1); j += nthreads) {
-                    rows[j].p = p32[j];
-                    Qb[j] = PP[j] + n0 * PS[j];
-                }
-                if (band_lo(b1) + tid <= band_hi(b1)) cut_i = cm[band_lo(b1) + tid];
+                for (int j = tid; j <= band_hi(b1); j += nthreads) rows[j].p = p32[j];
+                if (band_lo(b1) + tid <= band_hi(b1)) { cut_i = cm[band_lo(b1) + tid]; lo_i = lo0[band_lo(b1) + tid]; }
                 // below cut 0: never a predecessor; the time read there must stay small
                 if (tid < 3) { rows[-1 - tid].d = kInfSum; rows[-1 - tid].p = 0xFFFFFFFFu; }
                 if (tid == 0) rows[0].d = 0;
@@ -165,54 +169,55 @@ __device__ __forceinline__ void exact_body(const TablesDev &tb, const CandDev &c
                 const uint32_t rs = (uint32_t)uniform((int)sc[s].cm_row_shift);
                 const int shift = int(rs >> 27);
                 const uint32_t tp = 1u << shift;
-                const int64_t cap = uniform64(sc[s].cap);
                 const uint32_t b0 = (uint32_t)uniform((int)band[s]);
                 const int jl = band_lo(b0), jh = band_hi(b0);     // predecessors: row s
                 const uint32_t *cm_s = tb.CM + (rs & kRowMask);
+                const uint16_t *lo_s = lo_tab + (uint32_t)uniform((int)lo_off[s]);
+                const uint16_t *lo_n_row = lo_tab + (uint32_t)uniform((int)lo_off[s + 1]);
                 const Pair *prev = rows + cur * row_len;
                 Pair *next = rows + (cur ^ 1) * row_len;
-                const int64_t *Q = Qb + cur * row_len;
-                int64_t *Qn = Qb + (cur ^ 1) * row_len;
                 const uint32_t *p32_n = tb.P32 + (uint32_t)uniform((int)sc[s + 1].p_row);
                 const uint32_t *cm_n = tb.CM + ((uint32_t)uniform((int)sc[s + 1].cm_row_shift) & kRowMask);
                 const bool next_has_cut = s + 2 < S;
 
                 const int jn = il + tid;
                 uint32_t p_n = 0, cut_n = 0;
-                int64_t pp_n = 0, ps_n = 0;
-                if (jn <= top_n) { p_n = p32_n[jn]; pp_n = PP[jn]; ps_n = PS[jn]; }
-                if (next_has_cut && band_lo(b2) + tid <= top_n) cut_n = cm_n[band_lo(b2) + tid];
+                int lo_n = 0;
+                if (jn <= top_n) p_n = p32_n[jn];
+                if (band_lo(b2) + tid <= top_n) {       // the first cell this thread has in row s + 2
+                    if (next_has_cut) cut_n = cm_n[band_lo(b2) + tid];
+                    lo_n = lo_n_row[band_lo(b2) + tid];
+                }
 
-                // One cell: least sum over the previous cuts that fit in memory and under the cap,
-                // scanned downwards four per trip.  Both limits are monotone in j, so the last
-                // entry of a trip decides whether the lane goes on.  Equal sums keep the lowest j.
-                auto cell = [&](int i, uint32_t cut) -> int {
-                    const int64_t th = Q[i] - cap;
+                // One cell: least sum over the previous cuts that fit in memory (from the feasibility
+                // index: cuts lo .. i - 1) and under the cap, scanned downwards four per trip.  The
+                // stage time never decreases as j moves down, so the last entry of a trip decides
+                // whether the lane goes on.  Equal sums keep the lowest j.
+                auto cell = [&](int i, uint32_t cut, int lo_idx) -> int {
+                    const int lo = lo_idx > jl ? lo_idx : jl;
                     const uint32_t xi = prev[i].p + tp - 1;
                     SumT best = kInfSum;
                     int best_j = 0;
                     int j = (i - 1) < jh ? (i - 1) : jh;
-                    bool more = (j >= jl) & (cut <= tcap);
+                    bool more = (j >= lo) & (cut <= tcap);
                     while (more) {
                         const Pair *pe = prev + (j - 3);
-                        const int64_t *pq = Q + (j - 3);
                         const Pair e3 = pe[0], e2 = pe[1], e1 = pe[2], e0 = pe[3];
-                        const int64_t q3 = pq[0], q2 = pq[1], q1 = pq[2], q0 = pq[3];
                         uint32_t tj;
-#define HARP_STEP(E, QV, JJ)                                                   \
+#define HARP_STEP(E, K)                                                        \
     {                                                                          \
         tj = (xi - (E).p) >> shift;                                            \
         const SumT v = (E).d + tj;                                             \
-        const bool upd = ((QV) >= th) & (tj <= tcap) & (v <= best);            \
+        const bool upd = (j - (K) >= lo) & (tj <= tcap) & (v <= best);         \
         best = upd ? v : best;                                                 \
-        best_j = upd ? (JJ) : best_j;                                          \
+        best_j = upd ? j - (K) : best_j;                                       \
     }
-                        HARP_STEP(e0, q0, j)
-                        HARP_STEP(e1, q1, j - 1)
-                        HARP_STEP(e2, q2, j - 2)
-                        HARP_STEP(e3, q3, j - 3)
+                        HARP_STEP(e0, 0)
+                        HARP_STEP(e1, 1)
+                        HARP_STEP(e2, 2)
+                        HARP_STEP(e3, 3)
 #undef HARP_STEP
-                        more = ((j - 3) > jl) & (q3 >= th) & (tj <= tcap);
+                        more = ((j - 3) > lo) & (tj <= tcap);
                         j -= 4;
                     }
                     const uint64_t total = uint64_t(best) + 2ull * cut;
@@ -221,25 +226,19 @@ __device__ __forceinline__ void exact_body(const TablesDev &tb, const CandDev &c
                 };
                 const int i0 = il + tid;
                 int first_j = 0;
-                if (i0 <= ih) first_j = cell(i0, cut_i);
+                if (i0 <= ih) first_j = cell(i0, cut_i, lo_i);
                 for (int i = i0 + nthreads; i <= ih; i += nthreads)
-                    arg[s * row_len + i] = (uint16_t)cell(i, cm_s[i]);
+                    arg[s * row_len + i] = (uint16_t)cell(i, cm_s[i], lo_s[i]);
                 if (tid < 3) {                                  // below the band of row s + 1
                     next[il - 1 - tid].d = kInfSum;
                     next[il - 1 - tid].p = 0xFFFFFFFFu;
                 }
 
-                const int64_t n1 = (S - s - 1) < m_cap ? (S - s - 1) : m_cap;
-                if (jn <= top_n) {
-                    next[jn].p = p_n;
-                    Qn[jn] = pp_n + n1 * ps_n;
-                }
-                for (int j = jn + nthreads; j <= top_n; j += nthreads) {
-                    next[j].p = p32_n[j];
-                    Qn[j] = PP[j] + n1 * PS[j];
-                }
+                if (jn <= top_n) next[jn].p = p_n;
+                for (int j = jn + nthreads; j <= top_n; j += nthreads) next[j].p = p32_n[j];
                 asm volatile("" : "+v"(cut_n));
                 cut_i = cut_n;
+                lo_i = lo_n;
                 if (i0 <= ih) arg[s * row_len + i0] = (uint16_t)first_j;
                 lds_barrier();
                 cur ^= 1;
@@ -249,17 +248,15 @@ __device__ __forceinline__ void exact_body(const TablesDev &tb, const CandDev &c
                 const int s = S - 1;
                 const int shift = int((uint32_t)uniform((int)sc[s].cm_row_shift) >> 27);
                 const uint32_t tp = 1u << shift;
-                const int64_t cap = uniform64(sc[s].cap);
                 const uint32_t b0 = (uint32_t)uniform((int)band[s]);
                 const Pair *prev = rows + cur * row_len;
-                const int64_t *Q = Qb + cur * row_len;
-                const int64_t th = Q[L] - cap;
                 const uint32_t xi = prev[L].p + tp - 1;
                 const int hi = (L - 1) < band_hi(b0) ? (L - 1) : band_hi(b0);
+                const int lo_L = uniform((int)lo_tab[size_t((uint32_t)uniform((int)lo_off[s])) + L]);
+                const int lo = lo_L > band_lo(b0) ? lo_L : band_lo(b0);
                 unsigned long long best = kInfSum;
                 int best_j = INT32_MAX;
-                for (int j = band_lo(b0) + lane; j <= hi; j += 64) {
-                    if (Q[j] < th) continue;
+                for (int j = lo + lane; j <= hi; j += 64) {
                     const uint32_t tj = (xi - prev[j].p) >> shift;
                     const unsigned long long v = (unsigned long long)prev[j].d + tj;
                     if (tj <= tcap && v < best) { best = v; best_j = j; }   // j rises within a lane
@@ -365,23 +362,24 @@ __device__ __forceinline__ void exact_body(const TablesDev &tb, const CandDev &c
 
 __global__ __launch_bounds__(kFastThreads) __attribute__((amdgpu_waves_per_eu(8, 8)))
 void k2_exact(TablesDev tb, CandDev cd, PlansDev out, int32_t *n_passes, int *counts, const int32_t *live_list,
-              uint32_t *dead_list, const uint32_t *bands, unsigned char *arg_base, size_t arg_per_group,
-              int row_len) {
-    exact_body<uint32_t>(tb, cd, out, n_passes, counts, live_list, dead_list, bands, arg_base, arg_per_group,
-                         row_len);
+              uint32_t *dead_list, const uint32_t *bands, const uint16_t *lo_tab, int lo_pitch,
+              unsigned char *arg_base, size_t arg_per_group, int row_len) {
+    exact_body<uint32_t>(tb, cd, out, n_passes, counts, live_list, dead_list, bands, lo_tab, lo_pitch, arg_base,
+                         arg_per_group, row_len);
 }
 
 __global__ __launch_bounds__(kFastThreads)
 void k2_exact_wide(TablesDev tb, CandDev cd, PlansDev out, int32_t *n_passes, int *counts,
-                   const int32_t *live_list, uint32_t *dead_list, const uint32_t *bands,
-                   unsigned char *arg_base, size_t arg_per_group, int row_len) {
-    exact_body<uint64_t>(tb, cd, out, n_passes, counts, live_list, dead_list, bands, arg_base, arg_per_group,
-                         row_len);
+                   const int32_t *live_list, uint32_t *dead_list, const uint32_t *bands, const uint16_t *lo_tab,
+                   int lo_pitch, unsigned char *arg_base, size_t arg_per_group, int row_len) {
+    exact_body<uint64_t>(tb, cd, out, n_passes, counts, live_list, dead_list, bands, lo_tab, lo_pitch, arg_base,
+                         arg_per_group, row_len);
 }
 
 size_t exact_lds_bytes(int L, int S_max, size_t entry) {
-    size_t b = size_t(fast_row_len(L)) * (16 + 2 * entry) + size_t(S_max) * sizeof(StageConst) + 16 +
+    size_t b = size_t(fast_row_len(L)) * (2 * entry) + size_t(S_max) * sizeof(StageConst) + 16 +
                size_t(S_max + 1) * 12 + size_t(S_max) * 3;
+    b = ((b + 3) & ~size_t(3)) + size_t(S_max) * 4;         // + the stages' index-row offsets
     return (b + 15) & ~size_t(15);
 }
 
@@ -393,10 +391,10 @@ void launch_plan_exact(const TablesDev &tb, const CandDev &cd, const PlansDev &o
                        void *ws, int n_groups, hipStream_t st) {
     const FastWorkspace w = carve(ws, fast_shape(tb, cd), n_groups);
     hipLaunchKernelGGL(k2_exact, dim3(n_groups), dim3(kFastThreads), exact_lds_bytes(tb.L, cd.S_max, 8), st, tb,
-                       cd, out, n_passes, w.counts, w.live_list, w.dead_list, w.bands, w.arg,
+                       cd, out, n_passes, w.counts, w.live_list, w.dead_list, w.bands, w.lo_tab, int(lo_pitch(tb.L)), w.arg,
                        fast_arg_per_group(tb.L, cd.S_max), fast_row_len(tb.L));
     hipLaunchKernelGGL(k2_exact_wide, dim3(n_groups), dim3(kFastThreads), exact_lds_bytes(tb.L, cd.S_max, 16),
-                       st, tb, cd, out, n_passes, w.counts, w.live_list, w.dead_list, w.bands, w.arg,
+                       st, tb, cd, out, n_passes, w.counts, w.live_list, w.dead_list, w.bands, w.lo_tab, int(lo_pitch(tb.L)), w.arg,
                        fast_arg_per_group(tb.L, cd.S_max), fast_row_len(tb.L));
 }
 
