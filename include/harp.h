@@ -203,10 +203,11 @@ int harp_plan_batch(harp_ctx *ctx, harp_tables *tables, const harp_candidates *c
  * device array of HARP_STATIC_SCRATCH_BYTES inside the library (every GPU the library is used on
  * holds its own copy until the process ends; harp_create looks up its address).  The call
  * allocates and frees nothing, on the device or through any library.  It runs with as many
- * workgroups as the array has room for, so large batches are slower than with harp_plan_batch; a
- * batch whose lists and reachability bands alone (about 4 (S_max + 3) bytes per candidate, plus one
- * workgroup's back-pointer rows) exceed the array is refused with HARP_ERR_WORKSPACE and nothing
- * is launched.  The tables must have been finalized (harp_tables_finalize) if the call is to stay
+ * wavefronts (32-bit path, in fours) or workgroups (int64 path) as the array has room for, so large
+ * batches are slower than with harp_plan_batch; a batch whose lists and reachability bands (about
+ * 4 (S_max + 3) bytes per candidate), feasibility index (4 min(S_max, M, L) T n_tp (L + 1) bytes)
+ * and the back-pointer slices of four wavefronts or one workgroup exceed the array is refused with
+ * HARP_ERR_WORKSPACE and nothing is launched.  The tables must have been finalized (harp_tables_finalize) if the call is to stay
  * free of host waits.  Every call on one GPU uses the same array: calls that overlap on one GPU
  * (two streams, two contexts, two host threads) race; calls queued on one stream do not.  The
  * array keeps the previous call's contents; the kernels clear the counters they rely on. */
