@@ -144,3 +144,23 @@ def test_the_c_only_client_builds_against_the_library(tmp_path):
                         "-Wl,-rpath,/opt/rocm/lib"], capture_output=True, text=True)
     assert r.returncode == 0, r.stderr
     assert exe.exists()
+
+
+def test_recorded_counters_belong_to_the_current_kernel_sources():
+    """bench.py quotes HBM traffic and issued instructions from the rocprofv3 record in profiles/ only
+    while the record's hash of the planner kernel sources matches the tree; a source edit without a
+    new counter run would silently turn those fields into null."""
+    import json
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    sys.path.insert(0, root)
+    import bench
+    with open(bench.COUNTER_FILE) as f:
+        rec = json.load(f)
+    assert rec["workload"] == "stress"
+    assert rec["kernel_source_hash"] == bench.kernel_source_hash()
+    traffic, issued = bench.counter_figures("stress", True)
+    assert 0.28e9 < traffic < 1.5e9                # above the algorithmic bytes, within the budget set for it
+    assert 0.5 < issued["k2_fast_valu_issue_utilisation"] <= 1.0
+    assert bench.counter_figures("tiny", True) == (None, None)       # another workload: nothing to quote
+    assert bench.counter_figures("stress", False) == (None, None)    # part of the batch: nothing to quote
