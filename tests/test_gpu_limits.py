@@ -104,6 +104,29 @@ def test_longest_sequence_of_the_32_bit_path_and_beyond(harp, ctx):
         assert fast32 == expect_fast and (want.status == oracle.OK).any()
 
 
+def test_sequences_beyond_the_feasibility_index(harp, ctx):
+    """The pre-pass builds its index of fitting ranges for sequences of up to 16,383 operators and up to
+    256 MiB; beyond either limit the int64 planner runs without bands (the dense kernel), with the
+    same results."""
+    rng = np.random.default_rng(47)
+    # (L, T, degrees, M, S_max): the first is too long for the index, the second makes it too large
+    for L, T, tp, M, S_max in ((17000, 2, (1, 2), 40, 4), (12000, 8, (1, 2, 4, 8, 16, 32, 64, 128), 100, 100)):
+        G = 3
+        bw = rng.integers(20, 4000, size=(G, G))
+        p = simple_problem(np.zeros(L), M=M, T=T, G=G, ndev=(128, 128, 128), tp=tp,
+                           fwd=rng.integers(1, 200, size=(T, L)), bwd=rng.integers(1, 300, size=(T, L)),
+                           act=rng.integers(0, 10**6, size=L), params=rng.integers(1, 10**5, size=L),
+                           stash=rng.integers(0, 10**3, size=L), gtype=rng.integers(0, T, size=G),
+                           mem=[int(6e8)] * T, bw=np.minimum(bw, bw.T))
+        slots = [[(0, 1), (1, 2), (2, 1)], [(2, 2), (0, 1), (0, 1), (1, 1)], [(1, 1), (1, 1)], [(0, 2)] * 3 + [(1, 1)]]
+        cands = cands_from_lists(slots[:3] if L > 16383 else slots, S_max=S_max)
+        print("L = %d, S_max = %d" % (L, S_max), flush=True)
+        want = oracle_plan_threaded(oracle.build_tables(p), cands)
+        assert not harp.Tables(ctx, p).fast32 and (want.status == oracle.OK).any()
+        got, _ = harp.plan(ctx, p, cands, harp.PATH_GENERIC)
+        assert_plans_equal(got, want, "L = %d without the index" % L)
+
+
 def test_argument_errors_of_the_newer_entry_points(harp, ctx):
     """Every planner entry point refuses a short or misaligned workspace, null arrays and shapes
     beyond its limits with an error code, and launches nothing."""
