@@ -448,6 +448,95 @@ def test_empty_batch_and_argument_errors(harp, ctx):
     assert e.value.code == harp.ERR_INVALID_ARG
 
 
+def _bands_from_the_memory_constraint(p, S, groups, degrees):
+    """Per DP row s the lowest cut from which stages s .. S-1 can still hold the rest and the highest
+    cut that s stages can reach, by exhaustive set propagation over eq. mem_cons (non-empty stages,
+    classic in-flight counts min(S - s, M)); None when some row has no cut left."""
+    L = p.L
+    PP = np.concatenate([[0], np.cumsum(p.param_bytes)]).astype(object)
+    PS = np.concatenate([[0], np.cumsum(p.stash_bytes)]).astype(object)
+
+    def fits(s, j, i):
+        n = min(S - s, p.M)
+        cap = int(degrees[s]) * int(p.type_mem_bytes[p.group_type[groups[s]]])
+        return (PP[i] - PP[j]) + n * (PS[i] - PS[j]) <= cap
+
+    reach = [{0}]
+    for s in range(S):
+        last = L - (S - 1 - s)                      # leaves an operator to every later stage
+        reach.append({i for j in reach[s] for i in range(j + 1, last + 1) if fits(s, j, i)})
+    done = [set() for _ in range(S + 1)]
+    done[S] = {L}
+    for s in range(S - 1, -1, -1):
+        done[s] = {j for j in range(s, L) for i in done[s + 1] if j < i and fits(s, j, i)}
+    if any(not r for r in reach) or any(not d for d in done) or L not in reach[S] or 0 not in done[0]:
+        return None
+    rows = [(min(done[s]), max(reach[s])) for s in range(S + 1)]
+    return None if any(lo > hi for lo, hi in rows) else rows
+
+
+def test_counted_work_matches_the_bands_of_the_memory_constraint(harp, ctx):
+    """harp_plan_batch_count_work: same plans as harp_plan_batch; the cells it reports are exactly the
+    cells of the reachability bands (worked out here by exhaustive propagation of eq. mem_cons), the
+    candidates it reports are those with a band in every row, and the transitions lie between one
+    per cell with a fitting predecessor and all fitting predecessors inside the bands."""
+    import torch
+    cases = [W.make("tiny"), W.make("llama7b")] + [W.random_small(seed, odd_degrees=False) for seed in range(40)]
+    checked = 0
+    for w in cases:
+        p = w.problem
+        cands = w.candidates(0, min(w.C, 96))
+        tables = harp.Tables(ctx, p)
+        if not tables.fast32:
+            continue
+        dc = harp.DeviceCandidates(ctx, cands)
+        out, out2 = harp.DevicePlans(ctx, dc.C, dc.S_max), harp.DevicePlans(ctx, dc.C, dc.S_max)
+        ws = harp.plan_workspace(ctx, tables, dc)
+        work = torch.full((4,), -7, dtype=torch.int64, device=ctx.device)
+        out.poison(); out2.poison()
+        harp.harp_plan_batch(ctx, tables, dc, out, ws)
+        harp.harp_plan_batch_count_work(ctx, tables, dc, out2, ws, work)
+        torch.cuda.synchronize()
+        assert_plans_equal(out2.to_host(), out.to_host(), "%s counted launch" % w.name)
+        transitions, cells, groups_of_four, planned = (int(x) for x in work.cpu().numpy())
+        want_cells = want_planned = most = least = 0
+        PP = np.concatenate([[0], np.cumsum(p.param_bytes)]).astype(object)
+        PS = np.concatenate([[0], np.cumsum(p.stash_bytes)]).astype(object)
+        statuses = oracle.plan_batch(oracle.build_tables(p), cands).status
+        for c in range(cands.C):
+            S = int(cands.cand_S[c])
+            if statuses[c] == oracle.INVALID:
+                continue
+            rows = _bands_from_the_memory_constraint(p, S, cands.cand_group[c], cands.cand_tp[c])
+            if rows is None:
+                continue
+            want_planned += 1
+            if S == 1:                              # one stage holds everything: no recurrence, no cells
+                continue
+            for s in range(S):                      # stage s fills row s + 1 from row s
+                (jl, jh), (il, ih) = rows[s], rows[s + 1]
+                n = min(S - s, p.M)
+                cap = int(cands.cand_tp[c][s]) * int(p.type_mem_bytes[p.group_type[cands.cand_group[c][s]]])
+                for i in range(il, ih + 1):
+                    fitting = sum(1 for j in range(jl, min(i - 1, jh) + 1)
+                                  if (PP[i] - PP[j]) + n * (PS[i] - PS[j]) <= cap)
+                    want_cells += 1
+                    most += fitting
+                    least += 1 if fitting else 0
+        assert (cells, planned) == (want_cells, want_planned), w.name
+        assert least <= transitions <= most and 4 * groups_of_four >= transitions, w.name
+        checked += want_planned
+    assert checked > 200
+    # the int64 path has no counting build
+    ctx.set_plan_path(harp.PATH_GENERIC)
+    try:
+        with pytest.raises(harp.HarpError) as e:
+            harp.harp_plan_batch_count_work(ctx, tables, dc, out2, ws, work)
+        assert e.value.code == harp.ERR_UNIMPLEMENTED
+    finally:
+        ctx.set_plan_path(harp.PATH_AUTO)
+
+
 # ------------------------------------------------------------------ scorer and selection
 
 def test_score_parity_on_arbitrary_partitions(harp, ctx):
