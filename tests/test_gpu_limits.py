@@ -104,6 +104,40 @@ def test_longest_sequence_of_the_32_bit_path_and_beyond(harp, ctx):
         assert fast32 == expect_fast and (want.status == oracle.OK).any()
 
 
+def test_many_device_groups(harp, ctx):
+    """More than 64 groups (the pre-pass checks re-entered groups against the slot list instead of a
+    bit mask) and more than 2,048 (group types and sizes are read from memory, not LDS; the per-link
+    table of the 32-bit path is out of reach, so only the int64 path runs)."""
+    rng = np.random.default_rng(48)
+    for G, L in ((100, 150), (2100, 60)):
+        T = 3
+        bw = rng.integers(5, 3000, size=(G, G))
+        p = simple_problem(np.zeros(L), M=6, T=T, G=G, ndev=rng.integers(1, 3, size=G) * 2, tp=(1, 2),
+                           fwd=rng.integers(1, 900, size=(T, L)), bwd=rng.integers(1, 900, size=(T, L)),
+                           act=rng.integers(0, 10**5, size=L), params=rng.integers(1, 10**4, size=L),
+                           stash=rng.integers(0, 10**3, size=L), gtype=rng.integers(0, T, size=G),
+                           mem=[int(6e4 * L / 150), int(4e4 * L / 150), int(3e4 * L / 150)], bw=np.minimum(bw, bw.T))
+        lists = []
+        for n in range(40):
+            S = int(rng.integers(2, 50))
+            order = rng.permutation(G)[:S]
+            lists.append([(int(g), int(rng.integers(1, 3))) for g in order])
+        a, b = int(rng.integers(0, G)), int(rng.integers(0, G - 1))
+        b += b >= a
+        lists.append([(a, 1), (b, 1), (a, 1)])                      # a group left and entered again
+        lists.append([(a, 1)] * (int(p.group_ndev[a]) + 1))         # more devices than the group has
+        lists.append([(G - 1, 2), (0, 1), (G - 2, 1), (G - 2, 1)])
+        cands = cands_from_lists(lists)
+        want = oracle_plan_threaded(oracle.build_tables(p), cands)
+        assert list(want.status[40:42]) == [oracle.INVALID, oracle.INVALID]
+        assert (want.status == oracle.OK).sum() >= 10 and (want.status == oracle.INFEASIBLE).sum() >= 5
+        fast32 = harp.Tables(ctx, p).fast32
+        assert fast32 == (G == 100)
+        for path in [harp.PATH_GENERIC] + ([harp.PATH_FAST32] if fast32 else []):
+            got, _ = harp.plan(ctx, p, cands, path)
+            assert_plans_equal(got, want, "%d groups path %d" % (G, path))
+
+
 def test_sequences_beyond_the_feasibility_index(harp, ctx):
     """The pre-pass builds its index of fitting ranges for sequences of up to 16,383 operators and up to
     256 MiB; beyond either limit the int64 planner runs without bands (the dense kernel), with the
