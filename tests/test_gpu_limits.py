@@ -119,7 +119,7 @@ def test_many_device_groups(harp, ctx):
                            mem=[int(6e4 * L / 150), int(4e4 * L / 150), int(3e4 * L / 150)], bw=np.minimum(bw, bw.T))
         lists = []
         for n in range(40):
-            S = int(rng.integers(2, 50))
+            S = int(rng.integers(2, 101 if G == 100 else 50))      # up to 100 stages: the pre-pass's 128-thread shape
             order = rng.permutation(G)[:S]
             lists.append([(int(g), int(rng.integers(1, 3))) for g in order])
         a, b = int(rng.integers(0, G)), int(rng.integers(0, G - 1))
