@@ -553,6 +553,34 @@ def test_h1f1b_counts_enter_the_memory_constraint():
         assert oracle.plan_h1f1b_batch(oracle.build_tables(p), cands, [cap]).status[0] == st
 
 
+def test_caps_are_accepted_up_to_the_stated_bound():
+    """A cap is accepted up to min(2^47 - 1, INT64_MAX / (3 L + M)), the bound under which the sum of at
+    most 3 L terms and (M - 1) caps stays inside int64; one more makes the candidate invalid, in the
+    planner and in the scorer alike, and the bound itself still gives the arithmetic it promises."""
+    p = _chain_problem([750, 0], 1000)
+    cands = cands_from_lists([[(0, 1), (1, 1), (2, 1)]])
+    tables = oracle.build_tables(p)
+    by_sum = (2 ** 63 - 1) // (3 * p.L + p.M)
+    assert by_sum > 2 ** 47 - 1                      # a short sequence: the time limit is the one that binds
+    top = 2 ** 47 - 1
+    at = oracle.plan_h1f1b_batch(tables, cands, [top])
+    # three operators of 1000 us, transfers of 750 and 0 us: sum of (t + 2 c) = 4500
+    assert at.status[0] == oracle.OK and int(at.iter_time[0]) == 4500 + (p.M - 1) * top
+    assert oracle.plan_h1f1b_batch(tables, cands, [top + 1]).status[0] == oracle.INVALID
+    splits = at.splits
+    assert oracle.score_h1f1b(tables, cands, splits, [top])[3][0] == oracle.OK
+    assert oracle.score_h1f1b(tables, cands, splits, [top + 1])[3][0] == oracle.INVALID
+    # many microbatches: now the sum bound binds, below the time limit
+    p = _chain_problem([750, 0], 1000, M=2 ** 20)
+    tables = oracle.build_tables(p)
+    by_sum = (2 ** 63 - 1) // (3 * p.L + p.M)
+    assert by_sum < 2 ** 47 - 1
+    at = oracle.plan_h1f1b_batch(tables, cands, [by_sum])
+    assert at.status[0] == oracle.OK
+    assert int(at.iter_time[0]) == 4500 + (p.M - 1) * by_sum < 2 ** 63
+    assert oracle.plan_h1f1b_batch(tables, cands, [by_sum + 1]).status[0] == oracle.INVALID
+
+
 def test_h1f1b_recurrence_against_its_twin_and_exhaustive_enumeration():
     n = below = 0
     for seed in range(400):
