@@ -581,6 +581,39 @@ def test_caps_are_accepted_up_to_the_stated_bound():
     assert oracle.plan_h1f1b_batch(tables, cands, [by_sum + 1]).status[0] == oracle.INVALID
 
 
+def test_h1f1b_scorer_on_arbitrary_partitions():
+    """oracle.score_h1f1b on partitions that no planner chose (every partition of small problems, at
+    caps around the partition's own largest time) against eq. Ni and the cost model evaluated from
+    the raw inputs: counts, bottleneck, iteration time, and which of the three statuses."""
+    seen = {oracle.OK: 0, oracle.INFEASIBLE: 0}
+    for seed in range(150):
+        w = W.random_small(seed, L_max=8, S_cap=4)
+        p, cands = w.problem, w.candidates()
+        tables = oracle.build_tables(p)
+        for c in range(cands.C):
+            S, grp, tp = int(cands.cand_S[c]), cands.cand_group[c], cands.cand_tp[c]
+            if not brute.valid(p, S, cands.S_max, grp, tp) or S > p.L:
+                continue
+            one = cands.slice(c, c + 1)
+            for cuts in brute.partitions(p.L, S):
+                worst = max(max(brute.stage_time(p, int(grp[s]), int(tp[s]), cuts[s], cuts[s + 1]),
+                                0 if s == S - 1 else brute.cut_time(p, int(grp[s]), int(grp[s + 1]), cuts[s + 1]))
+                            for s in range(S))
+                for cap in {max(worst - 1, 0), worst, 2 * worst + 3}:
+                    splits = np.full((1, cands.S_max + 1), -1, dtype=np.int32)
+                    splits[0, :S + 1] = cuts
+                    wu, b, t, st = oracle.score_h1f1b(tables, one, splits, [cap])
+                    want = brute.h1f1b_evaluate(p, S, grp, tp, list(cuts), cap)
+                    if want is None:
+                        assert st[0] == oracle.INFEASIBLE and t[0] == oracle.INF and (wu[0] == -1).all()
+                    else:
+                        counts, total = want
+                        assert st[0] == oracle.OK and list(wu[0, :S]) == counts, (seed, c, cuts, cap)
+                        assert b[0] == worst and t[0] == total + (p.M - 1) * cap
+                    seen[int(st[0])] += 1
+    assert seen[oracle.OK] > 2000 and seen[oracle.INFEASIBLE] > 2000
+
+
 def test_h1f1b_recurrence_against_its_twin_and_exhaustive_enumeration():
     n = below = 0
     for seed in range(400):
