@@ -585,7 +585,8 @@ def main():
     path = {"auto": binding.PATH_AUTO, "generic": binding.PATH_GENERIC, "fast32": binding.PATH_FAST32}[args.path]
     ctx.set_plan_path(path)
     fast = tables.fast32 and path != binding.PATH_GENERIC
-    kernel = "k2_band + k2_fast (one harp_plan_batch call)" if fast else "k2_generic"
+    kernel = ("k2_band + k2_fast (one harp_plan_batch call)" if fast
+              else "k2_band + k2_banded (int64; k2_generic when the feasibility index does not fit)")
     width = "u32" if fast else "int64"
 
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))

@@ -512,7 +512,7 @@ int harp_plan_exact_batch(harp_ctx *ctx, harp_tables *t, const harp_candidates *
         if (rc != HARP_OK) return rc;
         launch_plan_exact(t->dev, pc.c, pc.o, n_passes, workspace, pc.groups, pc.st);
     } else {
-        launch_plan_generic_exact(t->dev, pc.c, pc.o, n_passes, workspace, pc.groups, pc.st);
+        launch_plan_generic_exact(t->dev, pc.c, pc.o, n_passes, workspace, pc.groups, pc.banded, pc.st);
     }
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(ctx, e, "launching the exact-search kernels");

@@ -83,7 +83,7 @@ void launch_build(const TablesDev &tb, const BuildLimits &lim, hipStream_t st);
 void launch_plan_generic(const TablesDev &tb, const CandDev &cd, const PlansDev &out, void *ws,
                          int n_groups, bool banded, hipStream_t st);
 void launch_plan_generic_exact(const TablesDev &tb, const CandDev &cd, const PlansDev &out, int32_t *n_passes,
-                               void *ws, int n_groups, hipStream_t st);
+                               void *ws, int n_groups, bool banded, hipStream_t st);
 size_t plan_generic_ws_per_group(int L, int S_max);
 void launch_plan_fast(const TablesDev &tb, const CandDev &cd, const PlansDev &out, void *ws,
                       int n_slices, int n_cu, unsigned long long *work, hipStream_t st);

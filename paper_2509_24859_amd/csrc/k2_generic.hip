@@ -191,15 +191,20 @@ constexpr int kBandedLdsL = 2047;       // 4 rows x 2048 x 8 B = 64 KB: stage su
 
 size_t banded_lds_bytes(int L) { return L <= kBandedLdsL ? size_t(4) * (L + 1) * sizeof(int64_t) : 0; }
 
-// The min-max recurrence of one live candidate over its bands: row s + 1 has the cells
+// One pass of the recurrence of one live candidate over its bands, in either form of generic_pass
+// (kCapped = false: min-max; true: least sum under the cap time_cap): row s + 1 has the cells
 // B[s+1] .. F[s+1], cell i tries the previous cuts max(lo(i), B[s]) .. min(i - 1, F[s]) downwards,
 // lo(i) from the feasibility index.  The scan stops as in the unbanded kernel once the stage time
-// alone exceeds the best value (strictly; the update is non-strict, so the lowest j among equal
-// values is kept).  The last stage has the single cell L: its previous cuts are spread over the
-// threads and reduced.  Returns D[S][L] to every thread; back-pointers are in w.arg.
+// alone exceeds the best value (min-max form: strictly; the update is non-strict, so the lowest j
+// among equal values is kept) or the cap (capped form).  The bands come from eq. mem_cons alone, so
+// they bound the plans of every cap.  The last stage has the single cell L: its previous cuts are
+// spread over the threads and reduced.  Returns D[S][L] to every thread; back-pointers are in w.arg.
+template <bool kCapped>
 __device__ __forceinline__ int64_t banded_pass(const TablesDev &tb, const SlotInfo &slots, int S,
                                                const uint32_t *band, const uint16_t *lo_tab, int lo_pitch,
-                                               const GenericSlice &w, int64_t *red_v, int *red_j) {
+                                               const GenericSlice &w, int64_t time_cap, int64_t *red_v,
+                                               int *red_j) {
+    const int nthreads = blockDim.x;
     extern __shared__ __align__(16) unsigned char generic_lds[];
     const int L = tb.L;
     const bool rows_in_lds = L <= kBandedLdsL;
@@ -209,6 +214,7 @@ __device__ __forceinline__ int64_t banded_pass(const TablesDev &tb, const SlotIn
         Dp = stage + 2 * (L + 1);
         Dn = stage + 3 * (L + 1);
     }
+    __syncthreads();                          // an earlier pass is done with the rows
     if (threadIdx.x == 0) Dp[0] = 0;          // row 0 is the single cut 0 (its band)
     const int rows_per_n = tb.T * tb.n_tp;
     for (int s = 0; s < S; ++s) {
@@ -223,7 +229,7 @@ __device__ __forceinline__ int64_t banded_pass(const TablesDev &tb, const SlotIn
         __syncthreads();                      // row s is complete, the previous stage's sums are free
         if (rows_in_lds) {
             int64_t *spf = stage, *spr = stage + (L + 1);
-            for (int i = jl + int(threadIdx.x); i <= ih; i += kBandedThreads) { spf[i] = pf[i]; spr[i] = pr[i]; }
+            for (int i = jl + int(threadIdx.x); i <= ih; i += nthreads) { spf[i] = pf[i]; spr[i] = pr[i]; }
             __syncthreads();
             pf = spf;
             pr = spr;
@@ -234,7 +240,7 @@ __device__ __forceinline__ int64_t banded_pass(const TablesDev &tb, const SlotIn
         uint16_t *arg_row = w.arg + size_t(s) * (L + 1);
         if (!last) {
             const int64_t link = tb.bw[int64_t(g) * tb.G + slots.g[s + 1]];
-            for (int i = il + int(threadIdx.x); i <= ih; i += kBandedThreads) {
+            for (int i = il + int(threadIdx.x); i <= ih; i += nthreads) {
                 const int64_t cut = (tb.act_bytes[i - 1] + link - 1) / link;
                 const int64_t pfi = pf[i] + tp - 1, pri = pr[i];
                 const int lo_i = lo_row[i];
@@ -242,17 +248,24 @@ __device__ __forceinline__ int64_t banded_pass(const TablesDev &tb, const SlotIn
                 const int hi = (i - 1) < jh ? (i - 1) : jh;
                 int64_t best = kInf;
                 int best_j = i - 1;
-                for (int j = hi; j >= lo; --j) {
-                    const int64_t work = pfi - pf[j];
-                    const int64_t comp = shift >= 0 ? work >> shift : work / tp;
-                    const int64_t time = comp + (pri - pr[j]);
-                    if (time > best) break;
-                    const int64_t dj = Dp[j];
-                    int64_t val = time > dj ? time : dj;      // dj = kInf (unreachable cut) stays kInf
-                    val = val > cut ? val : cut;
-                    if (val <= best && dj != kInf) { best = val; best_j = j; }
+                if (!kCapped || cut <= time_cap) {
+                    for (int j = hi; j >= lo; --j) {
+                        const int64_t work = pfi - pf[j];
+                        const int64_t comp = shift >= 0 ? work >> shift : work / tp;
+                        const int64_t time = comp + (pri - pr[j]);
+                        if (time > (kCapped ? time_cap : best)) break;
+                        const int64_t dj = Dp[j];
+                        if (dj == kInf) continue;                 // an unreachable cut
+                        if (kCapped) {
+                            if (dj + time <= best) { best = dj + time; best_j = j; }   // j falls: the lower j keeps a tie
+                        } else {
+                            int64_t val = time > dj ? time : dj;
+                            val = val > cut ? val : cut;
+                            if (val <= best) { best = val; best_j = j; }
+                        }
+                    }
                 }
-                Dn[i] = best;
+                Dn[i] = (kCapped && best != kInf) ? best + 2 * cut : best;
                 arg_row[i] = (uint16_t)best_j;
             }
         } else {
@@ -263,12 +276,13 @@ __device__ __forceinline__ int64_t banded_pass(const TablesDev &tb, const SlotIn
             const int hi = (L - 1) < jh ? (L - 1) : jh;
             int64_t best = kInf;
             int best_j = INT32_MAX;
-            for (int j = lo + int(threadIdx.x); j <= hi; j += kBandedThreads) {
+            for (int j = lo + int(threadIdx.x); j <= hi; j += nthreads) {
                 const int64_t work = pfi - pf[j];
                 const int64_t comp = shift >= 0 ? work >> shift : work / tp;
                 const int64_t time = comp + (pri - pr[j]);
                 const int64_t dj = Dp[j];
-                const int64_t val = time > dj ? time : dj;
+                if (dj == kInf || (kCapped && time > time_cap)) continue;
+                const int64_t val = kCapped ? dj + time : (time > dj ? time : dj);
                 if (val < best) { best = val; best_j = j; }      // j rises within a thread
             }
 #pragma unroll
@@ -280,7 +294,7 @@ __device__ __forceinline__ int64_t banded_pass(const TablesDev &tb, const SlotIn
             if ((threadIdx.x & 63) == 0) { red_v[threadIdx.x >> 6] = best; red_j[threadIdx.x >> 6] = best_j; }
             __syncthreads();
             if (threadIdx.x == 0) {
-                for (int q = 1; q < kBandedThreads / 64; ++q)
+                for (int q = 1; q < nthreads / 64; ++q)
                     if (red_v[q] < best || (red_v[q] == best && red_j[q] < best_j)) { best = red_v[q]; best_j = red_j[q]; }
                 red_v[0] = best;
                 arg_row[L] = (uint16_t)(best == kInf ? L - 1 : best_j);
@@ -326,7 +340,7 @@ __global__ __launch_bounds__(kBandedThreads) void k2_banded(TablesDev tb, CandDe
         }
         for (int s = threadIdx.x; s <= S; s += kBandedThreads) band[s] = bands[int64_t(c) * (S_max + 1) + s];
         __syncthreads();
-        if (banded_pass(tb, slots, S, band, lo_tab, lo_pitch, w, red_v, red_j) == kInf) {
+        if (banded_pass<false>(tb, slots, S, band, lo_tab, lo_pitch, w, 0, red_v, red_j) == kInf) {
             write_failed(out, c, S_max, HARP_CAND_INFEASIBLE);      // the bands were bounds only
             continue;
         }
@@ -439,6 +453,116 @@ __global__ __launch_bounds__(kThreads) void k2_generic_exact(TablesDev tb, CandD
             out.status[c] = HARP_CAND_OK;
             if (n_passes) n_passes[c] = passes;
         }
+    }
+}
+
+// The same search behind the pre-pass: the min-max pass and every capped pass run over the
+// candidate's reachability bands with their ranges of previous cuts from the feasibility index
+// (banded_pass); the walk over the caps is the one above.
+__global__ __launch_bounds__(kBandedThreads) void k2_banded_exact(TablesDev tb, CandDev cd, PlansDev out,
+                                                                   int32_t *n_passes, int *counts,
+                                                                   const int32_t *live_list, const uint32_t *dead_list,
+                                                                   const uint32_t *bands, const uint16_t *lo_tab,
+                                                                   int lo_pitch, unsigned char *ws, size_t ws_per_group) {
+    __shared__ SlotInfo slots;
+    __shared__ uint32_t band[kMaxStages + 1];
+    __shared__ int32_t trial[kMaxStages + 1], kept[kMaxStages + 1];
+    __shared__ int64_t scored[2];
+    __shared__ int64_t red_v[kBandedThreads / 64];
+    __shared__ int red_j[kBandedThreads / 64];
+    __shared__ int ticket;
+    const int L = tb.L, S_max = cd.S_max;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const GenericSlice w = generic_slice(ws, ws_per_group, L);
+    const int64_t m_cap = tb.M;
+    const int n_live = counts[0], n_dead = counts[1];
+
+    // all threads: bottleneck and total of the cuts in trial[], by the cost model itself
+    auto score_trial = [&](int S, int64_t &bott, int64_t &total) {
+        __syncthreads();              // the cuts written by thread 0 are read by the first wave
+        if (wave == 0) {
+            int64_t b, t;
+            wave_score_partition(tb, S, slots.g, slots.k, trial, lane, b, t);
+            if (lane == 0) { scored[0] = b; scored[1] = t; }
+        }
+        __syncthreads();
+        bott = scored[0];
+        total = scored[1];
+    };
+
+    for (;;) {
+        __syncthreads();
+        if (threadIdx.x == 0) ticket = atomicAdd(&counts[5], 1);
+        __syncthreads();
+        const int n = ticket;
+        if (n >= n_live) break;
+        const int c = live_list[n];
+        const int S = cd.cand_S[c];
+        const int32_t *grp = cd.cand_group + int64_t(c) * S_max;
+        const int32_t *tpv = cd.cand_tp + int64_t(c) * S_max;
+        int status = load_and_check_slots(tb, S, S_max, grp, tpv, slots);
+        for (int s = threadIdx.x; s <= S && status == HARP_CAND_OK; s += kBandedThreads)
+            band[s] = bands[int64_t(c) * (S_max + 1) + s];
+        __syncthreads();
+        if (status == HARP_CAND_OK &&
+            banded_pass<false>(tb, slots, S, band, lo_tab, lo_pitch, w, 0, red_v, red_j) == kInf)
+            status = HARP_CAND_INFEASIBLE;
+        if (status != HARP_CAND_OK) {
+            write_failed(out, c, S_max, status);
+            if (threadIdx.x == 0 && n_passes) n_passes[c] = 0;
+            continue;
+        }
+        if (threadIdx.x == 0) generic_backtrack(w, S, L, trial);
+        int64_t t_S, best_T, best_b;
+        score_trial(S, t_S, best_T);
+        best_b = t_S;
+        for (int s = threadIdx.x; s <= S; s += kBandedThreads) kept[s] = trial[s];
+        int passes = 0;
+        int64_t cap = t_S;
+        while (S >= 2) {
+            const int64_t sum = banded_pass<true>(tb, slots, S, band, lo_tab, lo_pitch, w, cap, red_v, red_j);
+            if (sum == kInf) break;   // cannot happen at or above t_S
+            if (threadIdx.x == 0) generic_backtrack(w, S, L, trial);
+            int64_t b, T;
+            score_trial(S, b, T);
+            ++passes;
+            if (T < best_T || (T == best_T && b <= best_b)) {   // equal totals: the lower cap; equal caps: the capped plan
+                best_T = T;
+                best_b = b;
+                for (int s = threadIdx.x; s <= S; s += kBandedThreads) kept[s] = trial[s];
+            }
+            if (passes >= (1 << 20) || b > cap) break;           // cannot happen: the cap falls with every pass
+            int64_t next_cap;
+            if (passes == 1) {
+                next_cap = (best_T + m_cap - 1) / m_cap;
+            } else {
+                next_cap = b - 1;
+                if (m_cap > 1) {
+                    const int64_t bound = (best_T - sum) / (m_cap - 1);
+                    next_cap = next_cap < bound ? next_cap : bound;
+                }
+            }
+            if (next_cap <= t_S) break;
+            cap = next_cap;
+        }
+        __syncthreads();
+        int32_t *sp = out.splits + int64_t(c) * (S_max + 1);
+        for (int s = threadIdx.x; s <= S_max; s += kBandedThreads) sp[s] = s <= S ? kept[s] : -1;
+        int32_t *df = out.dev_first + int64_t(c) * S_max;
+        for (int s = threadIdx.x; s < S_max; s += kBandedThreads) df[s] = s < S ? slots.dev_first[s] : -1;
+        if (threadIdx.x == 0) {
+            out.bottleneck[c] = best_b;
+            out.iter_time[c] = best_T;
+            out.status[c] = HARP_CAND_OK;
+            if (n_passes) n_passes[c] = passes;
+        }
+    }
+    // candidates the pre-pass rejected: no plan to report
+    for (int n = blockIdx.x; n < n_dead; n += gridDim.x) {
+        const uint32_t e = dead_list[n];
+        const int c = int(e & ((1u << fastdp::kDeadStatusShift) - 1u));
+        write_failed(out, c, S_max, int(e >> fastdp::kDeadStatusShift));
+        if (threadIdx.x == 0 && n_passes) n_passes[c] = 0;
     }
 }
 
@@ -646,7 +770,16 @@ void launch_plan_generic(const TablesDev &tb, const CandDev &cd, const PlansDev 
 }
 
 void launch_plan_generic_exact(const TablesDev &tb, const CandDev &cd, const PlansDev &out, int32_t *n_passes,
-                               void *ws, int n_groups, hipStream_t st) {
+                               void *ws, int n_groups, bool banded, hipStream_t st) {
+    if (banded) {
+        const fastdp::FastWorkspace w = fastdp::carve(ws, fastdp::fast_shape(tb, cd), 0);
+        launch_plan_prepass(tb, cd, ws, 0, st);
+        hipLaunchKernelGGL(k2_banded_exact, dim3(n_groups), dim3(kBandedThreads), banded_lds_bytes(tb.L), st, tb, cd,
+                           out, n_passes, w.counts, w.live_list, w.dead_list, w.bands, w.lo_tab,
+                           int(fastdp::lo_pitch(tb.L)), static_cast<unsigned char *>(ws) + w.total,
+                           plan_generic_ws_per_group(tb.L, cd.S_max));
+        return;
+    }
     hipLaunchKernelGGL(k2_generic_exact, dim3(n_groups), dim3(kThreads), generic_lds_bytes(tb.L), st, tb, cd, out, n_passes,
                        static_cast<unsigned char *>(ws), plan_generic_ws_per_group(tb.L, cd.S_max));
 }
