@@ -91,7 +91,7 @@ void launch_plan_prepass(const TablesDev &tb, const CandDev &cd, void *ws, int n
 void launch_plan_h1f1b(const TablesDev &tb, const CandDev &cd, const int64_t *t_max, const PlansDev &out,
                        int32_t *warmup, void *ws, int n_groups, hipStream_t st);
 void launch_plan_generic_h1f1b(const TablesDev &tb, const CandDev &cd, const int64_t *t_max, const PlansDev &out,
-                               int32_t *warmup, void *ws, int n_groups, hipStream_t st);
+                               int32_t *warmup, void *ws, int n_groups, bool banded, hipStream_t st);
 size_t plan_generic_h1f1b_ws_per_group(int L, int S_max);
 void launch_score_h1f1b(const TablesDev &tb, const CandDev &cd, const int32_t *splits, const int64_t *t_max,
                         int32_t *warmup, int64_t *bottleneck, int64_t *iter_time, int32_t *status,

@@ -736,6 +736,160 @@ __global__ __launch_bounds__(kThreads) void k2_generic_h1f1b(TablesDev tb, CandD
 
 }  // namespace
 
+// The same recurrence behind the pre-pass.  The bands of the classic counts bound it from outside
+// (H-1F1B's counts are never below the classic ones, so a stage that does not fit with the classic
+// count does not fit at all): slot `slot` has the start cuts B[slot] .. F[slot], and a start cut i
+// takes the end cuts max(i + 1, B[slot+1]) .. min(hi(i), F[slot+1]) upwards, hi(i) the highest end
+// cut that fits with the classic count, from the feasibility index.  One lane per start cut; the
+// scan stops at the cap (the stage time grows with the end cut).
+__global__ __launch_bounds__(kBandedThreads) void k2_banded_h1f1b(TablesDev tb, CandDev cd, const int64_t *t_max,
+                                                                   PlansDev out, int32_t *warmup, int *counts,
+                                                                   const int32_t *live_list, const uint32_t *dead_list,
+                                                                   const uint32_t *bands, const uint16_t *hi_tab,
+                                                                   int idx_pitch, unsigned char *ws,
+                                                                   size_t ws_per_group) {
+    __shared__ SlotInfo slots;
+    __shared__ uint32_t band[kMaxStages + 1];
+    __shared__ int32_t trial[kMaxStages + 1], count[kMaxStages];
+    __shared__ int ticket;
+    const int L = tb.L, S_max = cd.S_max;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const H1Slice w = h1_slice(ws, ws_per_group, L);
+    const int64_t *PP = tb.PP(), *PS = tb.PS();
+    const int64_t m_cap = tb.M;
+    const int n_live = counts[0], n_dead = counts[1];
+    const int rows_per_n = tb.T * tb.n_tp;
+
+    for (;;) {
+        __syncthreads();
+        if (threadIdx.x == 0) ticket = atomicAdd(&counts[5], 1);
+        __syncthreads();
+        const int n = ticket;
+        if (n >= n_live) break;
+        const int c = live_list[n];
+        const int S = cd.cand_S[c];
+        const int64_t cap_t = t_max[c];
+        const int32_t *grp = cd.cand_group + int64_t(c) * S_max;
+        const int32_t *tpv = cd.cand_tp + int64_t(c) * S_max;
+        int32_t *wu = warmup + int64_t(c) * S_max;
+        int status = load_and_check_slots(tb, S, S_max, grp, tpv, slots);
+        if (status == HARP_CAND_OK && cap_out_of_range(tb, cap_t)) status = HARP_CAND_INVALID;
+        if (status == HARP_CAND_OK && cap_t < 0) status = HARP_CAND_INFEASIBLE;
+        const int64_t *Gp = w.G0;
+        if (status == HARP_CAND_OK) {
+            for (int s = threadIdx.x; s <= S; s += kBandedThreads) band[s] = bands[int64_t(c) * (S_max + 1) + s];
+            if (threadIdx.x == 0) { w.G0[L] = 0; w.N0[L] = 0; }      // row S is the single cut L
+            int64_t *Gn = w.G1;
+            int32_t *Np = w.N0, *Nn = w.N1;
+            int64_t *Gcur = w.G0;
+            for (int slot = S - 1; slot >= 0; --slot) {
+                const int g = slots.g[slot], k = slots.k[slot];
+                const int64_t tp = tb.tp[k];
+                const int shift = tb.tp_shift[k];
+                const int t = tb.group_type[g];
+                const int64_t *pf = tb.PF(t), *pr = tb.PR(g, k);
+                const int64_t capm = tp * tb.type_mem[t];
+                const bool last = (slot == S - 1);
+                const int64_t link = last ? 1 : tb.bw[int64_t(g) * tb.G + slots.g[slot + 1]];
+                __syncthreads();                            // the previous slot's rows and the bands are complete
+                const uint32_t b0 = band[slot], b1 = band[slot + 1];
+                const int il = fastdp::band_lo(b0), ih = fastdp::band_hi(b0);      // start cuts of this slot
+                const int jl = fastdp::band_lo(b1), jh = fastdp::band_hi(b1);      // its end cuts
+                const int n_classic = int((S - slot) < m_cap ? (S - slot) : m_cap);
+                const uint16_t *hi_row = hi_tab + (size_t(n_classic - 1) * rows_per_n + size_t(t) * tb.n_tp + k) * idx_pitch;
+                // the row handed over by the slots behind, made ready for this slot's transitions
+                for (int j = jl + int(threadIdx.x); j <= jh; j += kBandedThreads) {
+                    const int64_t cut = last ? 0 : (tb.act_bytes[j - 1] + link - 1) / link;
+                    const int64_t rest = Gcur[j];
+                    w.H[j] = (rest == kInf || cut > cap_t) ? kInf : rest + 2 * cut;
+                    const int64_t x = 2 * cut - (cap_t >> 6);
+                    const int64_t nn = 1 + (x > 0 ? 1 : 0) + (x > cap_t ? 1 : 0) + Np[j];
+                    w.NN[j] = int32_t(nn < m_cap ? nn : m_cap);
+                }
+                __syncthreads();
+                uint16_t *arg_row = w.arg + size_t(slot) * (L + 1);
+                for (int i = il + int(threadIdx.x); i <= ih; i += kBandedThreads) {
+                    const int64_t pfi = pf[i], pri = pr[i], ppi = PP[i], psi = PS[i];
+                    const int reach = hi_row[i];
+                    const int first = (i + 1) > jl ? (i + 1) : jl;
+                    const int end = reach < jh ? reach : jh;
+                    int64_t best = kInf;
+                    int best_j = 0, best_n = 0;
+                    for (int j = first; j <= end; ++j) {
+                        const int64_t work = pf[j] - pfi;
+                        const int64_t comp = shift >= 0 ? (work + tp - 1) >> shift : (work + tp - 1) / tp;
+                        const int64_t time = comp + (pr[j] - pri);
+                        if (time > cap_t) break;
+                        const int64_t h = w.H[j];
+                        const int nn = w.NN[j];
+                        if (h != kInf && (PP[j] - ppi) + int64_t(nn) * (PS[j] - psi) <= capm && h + time < best) {
+                            best = h + time; best_j = j; best_n = nn;          // j rises: the lowest end cut keeps a tie
+                        }
+                    }
+                    Gn[i] = best;
+                    Nn[i] = best_n;
+                    arg_row[i] = (uint16_t)best_j;
+                }
+                int64_t *tg = Gcur; Gcur = Gn; Gn = tg;
+                int32_t *tn = Np; Np = Nn; Nn = tn;
+            }
+            __syncthreads();
+            Gp = Gcur;
+            if (Gp[0] == kInf) status = HARP_CAND_INFEASIBLE;
+        }
+        if (status != HARP_CAND_OK) {
+            write_failed(out, c, S_max, status);
+            for (int s = threadIdx.x; s < S_max; s += kBandedThreads) wu[s] = -1;
+            continue;
+        }
+        const int64_t sum = Gp[0];
+        if (threadIdx.x == 0) {
+            int b = 0;
+            for (int slot = 0; slot < S; ++slot) { trial[slot] = b; b = w.arg[size_t(slot) * (L + 1) + b]; }
+            trial[S] = b;
+            // counts by eq. Ni along the plan, from the last stage backwards
+            int64_t nn = 0;
+            for (int slot = S - 1; slot >= 0; --slot) {
+                int64_t cut = 0;
+                if (slot < S - 1) {
+                    const int64_t link = tb.bw[int64_t(slots.g[slot]) * tb.G + slots.g[slot + 1]];
+                    cut = (tb.act_bytes[trial[slot + 1] - 1] + link - 1) / link;
+                }
+                const int64_t x = 2 * cut - (cap_t >> 6);
+                nn += 1 + (x > 0 ? 1 : 0) + (x > cap_t ? 1 : 0);
+                nn = nn < m_cap ? nn : m_cap;
+                count[slot] = int32_t(nn);
+            }
+        }
+        __syncthreads();
+        int32_t *sp = out.splits + int64_t(c) * (S_max + 1);
+        for (int s = threadIdx.x; s <= S_max; s += kBandedThreads) sp[s] = s <= S ? trial[s] : -1;
+        int32_t *df = out.dev_first + int64_t(c) * S_max;
+        for (int s = threadIdx.x; s < S_max; s += kBandedThreads) {
+            df[s] = s < S ? slots.dev_first[s] : -1;
+            wu[s] = s < S ? count[s] : -1;
+        }
+        if (wave == 0) {
+            int64_t bott, iter;
+            wave_score_partition(tb, S, slots.g, slots.k, trial, lane, bott, iter);   // the plan's own bottleneck
+            if (lane == 0) {
+                out.bottleneck[c] = bott;
+                out.iter_time[c] = sum + (m_cap - 1) * cap_t;
+                out.status[c] = HARP_CAND_OK;
+            }
+        }
+    }
+    // candidates the pre-pass rejected: no plan; a cap outside the accepted range is the caller's mistake first
+    for (int n = blockIdx.x; n < n_dead; n += gridDim.x) {
+        const uint32_t e = dead_list[n];
+        const int c = int(e & ((1u << fastdp::kDeadStatusShift) - 1u));
+        int status = int(e >> fastdp::kDeadStatusShift);
+        if (status == HARP_CAND_INFEASIBLE && cap_out_of_range(tb, t_max[c])) status = HARP_CAND_INVALID;
+        write_failed(out, c, S_max, status);
+        for (int s = threadIdx.x; s < S_max; s += kBandedThreads) warmup[int64_t(c) * S_max + s] = -1;
+    }
+}
+
 size_t plan_generic_h1f1b_ws_per_group(int L, int S_max) {
     size_t b = size_t(3) * (L + 1) * sizeof(int64_t) + size_t(3) * (L + 1) * sizeof(int32_t) +
                size_t(S_max) * (L + 1) * sizeof(uint16_t);
@@ -743,7 +897,17 @@ size_t plan_generic_h1f1b_ws_per_group(int L, int S_max) {
 }
 
 void launch_plan_generic_h1f1b(const TablesDev &tb, const CandDev &cd, const int64_t *t_max, const PlansDev &out,
-                               int32_t *warmup, void *ws, int n_groups, hipStream_t st) {
+                               int32_t *warmup, void *ws, int n_groups, bool banded, hipStream_t st) {
+    if (banded) {
+        const fastdp::FastWorkspace w = fastdp::carve(ws, fastdp::fast_shape(tb, cd), 0);
+        launch_plan_prepass(tb, cd, ws, 0, st);
+        const long long idx_rows = (long long)fastdp::lo_n_max(tb.L, cd.S_max, tb.M) * tb.T * tb.n_tp;
+        const int idx_pitch = int(fastdp::lo_pitch(tb.L));
+        hipLaunchKernelGGL(k2_banded_h1f1b, dim3(n_groups), dim3(kBandedThreads), 0, st, tb, cd, t_max, out, warmup,
+                           w.counts, w.live_list, w.dead_list, w.bands, w.lo_tab + idx_rows * idx_pitch, idx_pitch,
+                           static_cast<unsigned char *>(ws) + w.total, plan_generic_h1f1b_ws_per_group(tb.L, cd.S_max));
+        return;
+    }
     hipLaunchKernelGGL(k2_generic_h1f1b, dim3(n_groups), dim3(kThreads), 0, st, tb, cd, t_max, out, warmup,
                        static_cast<unsigned char *>(ws), plan_generic_h1f1b_ws_per_group(tb.L, cd.S_max));
 }
