@@ -11,13 +11,13 @@
 // accepts any degree (division when it is not a power of two) and any L up to 65535; the 32-bit
 // path in k2_fast.hip is the fast one.
 //
-// k2_banded is the min-max planner of this path when the batch's feasibility index fits its limit
-// (it does unless L, the in-flight counts and the degree list are all large): same int64
-// arithmetic, but it runs behind the pre-pass of k2_fast.hip, which needs nothing but the memory
-// sums, and so works on the reachability bands only and reads each cell's lowest fitting previous
-// cut from the index instead of evaluating eq. mem_cons per transition.  The rows it keeps in LDS
-// are a third of the unbanded kernel's per candidate, so several times as many candidates are in
-// flight per CU.
+// k2_banded, k2_banded_exact and k2_banded_h1f1b are the planners of this path when the batch's
+// feasibility index fits its limits (it does unless L, the in-flight counts and the degree list are
+// all large): same int64 arithmetic, but they run behind the pre-pass of k2_fast.hip, which needs
+// nothing but the memory sums, and so work on the reachability bands only and read each cell's
+// range of fitting cuts from the index instead of evaluating eq. mem_cons per transition.  The rows
+// k2_banded keeps in LDS are a third of the unbanded kernel's per candidate, so several times as
+// many candidates are in flight per CU.
 #include "harp_internal.h"
 #include "fast_common.h"
 #include "plan_common.h"
