@@ -141,9 +141,9 @@ int harp_tables_finalize(harp_ctx *ctx, harp_tables *tables);
 /* 1 when the finalized tables allow the 32-bit fast path (all degrees powers of two, every time
  * below 2^31 us, L <= 4096, per-link cut table within 256 MiB), else 0.  A batch runs on it when
  * its feasibility index (two tables of min(S_max, M, L) * T * n_tp rows of L + 1 16-bit entries)
- * stays within 256 MiB as well.  The min-max planner uses it for every such L; the exact search,
- * the H-1F1B planner and the submesh planners, whose 32-bit kernels keep whole rows in LDS, use it
- * up to L = 1024 and run on the int64 path beyond. */
+ * stays within 256 MiB as well.  The min-max planner and the exact search use it for every such L;
+ * the H-1F1B planner and the submesh planners, whose 32-bit kernels keep whole rows of several
+ * arrays in LDS, use it up to L = 1024 and run on the int64 path beyond. */
 int harp_tables_fast32(const harp_tables *tables);
 
 /* DEVICE pointers into the table buffer, for inspection: running sums indexed [row][i],

@@ -230,7 +230,7 @@ bool mesh_index_fits(const harp_tables *t) {
 }
 
 // The 32-bit tables serve the min-max planner up to kFastMaxL operators; the kernels that keep
-// whole rows in LDS (exact search, H-1F1B, the submesh planners) stop at kFastRowsMaxL.
+// whole rows of several arrays in LDS (H-1F1B, the submesh planners) stop at kFastRowsMaxL.
 bool fast_allowed(const harp_tables *t, bool whole_rows) {
     return t->fast32 && (!whole_rows || t->dev.L <= kFastRowsMaxL);
 }
@@ -505,7 +505,8 @@ int harp_plan_batch_count_work(harp_ctx *ctx, harp_tables *t, const harp_candida
 int harp_plan_exact_batch(harp_ctx *ctx, harp_tables *t, const harp_candidates *cd, const harp_plans *out,
                           int32_t *n_passes, void *workspace, size_t workspace_bytes, void *hip_stream) {
     PlanCall pc;
-    int rc = plan_prepare(ctx, t, cd, out, false, true, workspace, workspace_bytes, false, hip_stream, pc);
+    // (the exact search's two rows of 8- or 16-byte entries fit LDS for every L of the 32-bit tables)
+    int rc = plan_prepare(ctx, t, cd, out, false, false, workspace, workspace_bytes, false, hip_stream, pc);
     if (rc != HARP_OK || cd->C == 0) return rc;
     if (pc.fast) {
         rc = plan_minmax(ctx, t, pc, workspace, nullptr);

@@ -10,8 +10,8 @@ namespace harp {
 
 constexpr int kMaxTp = HARP_MAX_TP_DEGREES;
 constexpr int kMaxStages = 256;        // S_max accepted by plan/score
-constexpr int kFastMaxL = 4096;        // 32-bit tables and the min-max planner on them (band-relative rows in LDS)
-constexpr int kFastRowsMaxL = 1024;    // 32-bit kernels that keep whole rows in LDS: exact search, H-1F1B, submesh
+constexpr int kFastMaxL = 4096;        // 32-bit tables, the min-max planner and the exact search on them
+constexpr int kFastRowsMaxL = 1024;    // 32-bit kernels that keep whole rows of several arrays in LDS: H-1F1B, submesh
 constexpr size_t kFastCutTableLimit = size_t(256) << 20;
 constexpr int64_t kInf = INT64_MAX;
 constexpr int64_t kTimeLimit = int64_t(1) << 47;

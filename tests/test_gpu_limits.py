@@ -19,7 +19,7 @@ def ctx(harp):
     c.close()
 
 
-ROWS_MAX_L = 1024      # the 32-bit exact, H-1F1B and submesh kernels keep whole rows in LDS
+ROWS_MAX_L = 1024      # the 32-bit H-1F1B and submesh kernels keep whole rows of several arrays in LDS
 
 
 def _all_entry_points(harp, ctx, p, cands, label, exact=True):
@@ -43,9 +43,15 @@ def _all_entry_points(harp, ctx, p, cands, label, exact=True):
         assert e.value.code == harp.ERR_UNIMPLEMENTED
     if exact:
         want_e = oracle_plan_exact_threaded(tables, cands)
-        for path in row_paths:
+        for path in paths:
             got, _, _ = harp.plan_exact(ctx, p, cands, path)
             assert_plans_equal(got, want_e, "%s exact path %d" % (label, path))
+    elif fast32:
+        # too long for the oracle's sweep to stay in seconds: the two arithmetic paths against each other
+        a, _, _ = harp.plan_exact(ctx, p, cands, harp.PATH_GENERIC)
+        b, _, _ = harp.plan_exact(ctx, p, cands, harp.PATH_FAST32)
+        assert_plans_equal(b, a, "%s exact, 32-bit against int64" % label)
+        assert ((a.iter_time <= want.iter_time) | (want.status != oracle.OK)).all()
     return want, fast32
 
 
@@ -87,9 +93,10 @@ def test_every_operator_its_own_stage(harp, ctx):
 
 def test_longest_sequence_of_the_32_bit_path_and_beyond(harp, ctx):
     """L = 1024 is the last length with 32-bit kernels behind every entry point, 4096 the last for
-    the min-max planner; past each limit the int64 path takes over with the same results."""
+    the min-max planner and the exact search; past each limit the int64 path takes over with the same
+    results."""
     rng = np.random.default_rng(43)
-    for L, expect_fast in ((1024, True), (1025, True), (4096, True), (4097, False)):
+    for L, expect_fast in ((1024, True), (1025, True), (2048, True), (4096, True), (4097, False)):
         G = 3
         bw = rng.integers(20, 4000, size=(G, G))
         # many microbatches keep [t_S, t_E] narrow, so that the oracle's sweep stays in seconds
@@ -100,7 +107,7 @@ def test_longest_sequence_of_the_32_bit_path_and_beyond(harp, ctx):
                            mem=[int(4e7), int(3e7)], bw=np.minimum(bw, bw.T))
         cands = W.make_candidates(p, L, 91, G, 6, 0, 6 if L > 2000 else 16)
         print("L = %d" % L, flush=True)
-        want, fast32 = _all_entry_points(harp, ctx, p, cands, "L = %d" % L, exact=(L <= 1025))
+        want, fast32 = _all_entry_points(harp, ctx, p, cands, "L = %d" % L, exact=(L <= 2048))
         assert fast32 == expect_fast and (want.status == oracle.OK).any()
 
 
