@@ -16,9 +16,10 @@
 // The row handed from slot sigma+1 to slot sigma is stored ready for use: entry j holds the
 // suffix sum plus twice the transfer time of the cut at j (infinity when that transfer exceeds the
 // cap) and the count the stage in front of j would have, so a transition is one stage time, one
-// memory test and one add.  Scans run upwards in j (the stage time grows with j and stops the scan
-// at the cap; so does the stage's memory need at the smallest possible count), with a strict
-// comparison, which keeps the lowest j among equal sums.
+// memory test and one add.  Scans run upwards in j with a strict comparison, which keeps the lowest j
+// among equal sums; the stage time grows with j and stops the scan at the cap, and the scan ends at
+// the highest end cut that fits with the slot's classic count (from the pre-pass's feasibility
+// index: a larger count cannot fit where the classic one does not).
 //
 // Sums are 32-bit while they stay below 2^31 - 1 - cap, so that a stored sum plus any admissible
 // stage time cannot reach infinity (2^31); a candidate for which some cell would exceed that is
@@ -58,8 +59,9 @@ template <typename SumT>
 __device__ __forceinline__ void h1f1b_body(const TablesDev &tb, const CandDev &cd, const int64_t *t_max,
                                            const PlansDev &out, int32_t *warmup, int *counts,
                                            const int32_t *live_list, uint32_t *dead_list,
-                                           const uint32_t *bands, unsigned char *arg_base,
-                                           size_t arg_per_group, int row_len, int arg_pitch) {
+                                           const uint32_t *bands, const uint16_t *hi_tab, int idx_pitch,
+                                           unsigned char *arg_base, size_t arg_per_group, int row_len,
+                                           int arg_pitch) {
     using Entry = typename H1Traits<SumT>::Entry;
     constexpr SumT kInfSum = H1Traits<SumT>::inf;
     constexpr bool kWide = sizeof(SumT) == 8;
@@ -78,6 +80,10 @@ __device__ __forceinline__ void h1f1b_body(const TablesDev &tb, const CandDev &c
     uint32_t *flags = reinterpret_cast<uint32_t *>(trial + S_max + 1);                 // [2]: ticket, overflow
     uint16_t *slot_g = reinterpret_cast<uint16_t *>(flags + 2);                        // [S_max]
     uint8_t *slot_k = reinterpret_cast<uint8_t *>(slot_g + S_max);                     // [S_max]
+    // element offset of each slot's row of the feasibility index: the highest end cut that fits with the
+    // classic count of the slot, an outer bound for H-1F1B's (its counts are never below the classic ones)
+    uint32_t *hi_off = reinterpret_cast<uint32_t *>(
+        lds_raw + ((size_t(reinterpret_cast<unsigned char *>(slot_k + S_max) - lds_raw) + 3) & ~size_t(3)));   // [S_max]
     uint16_t *arg = reinterpret_cast<uint16_t *>(arg_base + size_t(blockIdx.x) * arg_per_group);
     const int n_dead = counts[1];
     const int n_items = kWide ? counts[2] : counts[0];
@@ -125,6 +131,9 @@ __device__ __forceinline__ void h1f1b_body(const TablesDev &tb, const CandDev &c
                 int32_t first = tb.group_base[g];
                 for (int q = s - 1; q >= 0 && grp[q] == g; --q) first += tpv[q];
                 df[s] = first;
+                const int n_classic = int((S - s) < m_cap ? (S - s) : m_cap);
+                hi_off[s] = uint32_t((int64_t(n_classic - 1) * tb.T * tb.n_tp + int64_t(tb.group_type[g]) * tb.n_tp + k) *
+                                     idx_pitch);
             }
             for (int s = S + tid; s < S_max; s += nthreads) df[s] = -1;
             for (int s = tid; s <= S; s += nthreads) band[s] = bands[int64_t(c) * (S_max + 1) + s];
@@ -164,6 +173,7 @@ __device__ __forceinline__ void h1f1b_body(const TablesDev &tb, const CandDev &c
             const int shift = int(rsv >> 27);
             const uint32_t tp = 1u << shift;
             const int64_t capm = uniform64(sc[slot].cap);
+            const uint16_t *hi_row = hi_tab + (uint32_t)uniform((int)hi_off[slot]);
             const uint32_t *pr_cur = prow + pcur * row_len;
             uint32_t *pr_next = prow + (pcur ^ 1) * row_len;
             const Entry *prev = rows + cur * row_len;
@@ -186,10 +196,12 @@ __device__ __forceinline__ void h1f1b_body(const TablesDev &tb, const CandDev &c
                 uint32_t best_n = 0;
                 int best_j = 0;
                 int j = (i + 1) > jl ? (i + 1) : jl;
-                bool more = j <= jh;
+                // end cuts beyond the classic count's reach cannot fit with a larger count either
+                const int reach = hi_row[i];
+                const int end = reach < jh ? reach : jh;
+                bool more = j <= end;
                 while (more) {
                     uint32_t tj = 0;
-                    int64_t least = 0;
 #pragma unroll
                     for (int u = 0; u < 4; ++u) {
                         // entries behind the band (up to kTail behind L) hold an infinite sum; what
@@ -198,15 +210,14 @@ __device__ __forceinline__ void h1f1b_body(const TablesDev &tb, const CandDev &c
                         const MemPair mj = mem[j + u];
                         tj = (pr_cur[j + u] + tp - 1 - xi) >> shift;
                         const int64_t dpp = mj.pp - mi.pp, dps = mj.ps - mi.ps;
-                        least = dpp + dps;                                   // need at the smallest count
                         const bool fits = dpp + int64_t(e.nn) * dps <= capm;
                         const SumT v = e.h + tj;
-                        const bool upd = fits & (tj <= tcap) & (v < best) & ((j + u) <= jh);
+                        const bool upd = fits & (tj <= tcap) & (v < best) & ((j + u) <= end);
                         best = upd ? v : best;
                         best_n = upd ? e.nn : best_n;
                         best_j = upd ? (j + u) : best_j;
                     }
-                    more = ((j + 4) <= jh) & (tj <= tcap) & (least <= capm);
+                    more = ((j + 4) <= end) & (tj <= tcap);
                     j += 4;
                 }
                 arg[slot * arg_pitch + i] = (uint16_t)best_j;
@@ -304,17 +315,17 @@ __device__ __forceinline__ void h1f1b_body(const TablesDev &tb, const CandDev &c
 
 __global__ __launch_bounds__(kFastThreads) __attribute__((amdgpu_waves_per_eu(8, 8)))
 void k2_h1f1b(TablesDev tb, CandDev cd, const int64_t *t_max, PlansDev out, int32_t *warmup, int *counts,
-              const int32_t *live_list, uint32_t *dead_list, const uint32_t *bands, unsigned char *arg_base,
-              size_t arg_per_group, int row_len, int arg_pitch) {
-    h1f1b_body<uint32_t>(tb, cd, t_max, out, warmup, counts, live_list, dead_list, bands, arg_base,
+              const int32_t *live_list, uint32_t *dead_list, const uint32_t *bands, const uint16_t *hi_tab,
+              int idx_pitch, unsigned char *arg_base, size_t arg_per_group, int row_len, int arg_pitch) {
+    h1f1b_body<uint32_t>(tb, cd, t_max, out, warmup, counts, live_list, dead_list, bands, hi_tab, idx_pitch, arg_base,
                          arg_per_group, row_len, arg_pitch);
 }
 
 __global__ __launch_bounds__(kFastThreads)
 void k2_h1f1b_wide(TablesDev tb, CandDev cd, const int64_t *t_max, PlansDev out, int32_t *warmup, int *counts,
-                   const int32_t *live_list, uint32_t *dead_list, const uint32_t *bands,
-                   unsigned char *arg_base, size_t arg_per_group, int row_len, int arg_pitch) {
-    h1f1b_body<uint64_t>(tb, cd, t_max, out, warmup, counts, live_list, dead_list, bands, arg_base,
+                   const int32_t *live_list, uint32_t *dead_list, const uint32_t *bands, const uint16_t *hi_tab,
+                   int idx_pitch, unsigned char *arg_base, size_t arg_per_group, int row_len, int arg_pitch) {
+    h1f1b_body<uint64_t>(tb, cd, t_max, out, warmup, counts, live_list, dead_list, bands, hi_tab, idx_pitch, arg_base,
                          arg_per_group, row_len, arg_pitch);
 }
 
@@ -323,6 +334,7 @@ int h1f1b_row_len(int L) { return (L + 1 + kTail + 7) / 8 * 8; }
 size_t h1f1b_lds_bytes(int L, int S_max, size_t entry) {
     size_t b = size_t(h1f1b_row_len(L)) * (sizeof(MemPair) + 2 * entry + 8) + size_t(S_max) * sizeof(StageConst) +
                16 + size_t(S_max + 1) * 8 + 8 + size_t(S_max) * 3;
+    b = ((b + 3) & ~size_t(3)) + size_t(S_max) * 4;         // + the slots' index-row offsets
     return (b + 15) & ~size_t(15);
 }
 
@@ -335,11 +347,13 @@ void launch_plan_h1f1b(const TablesDev &tb, const CandDev &cd, const int64_t *t_
     const FastWorkspace w = carve(ws, fast_shape(tb, cd), n_groups);
     launch_plan_prepass(tb, cd, ws, n_groups, st);
     const int row_len = h1f1b_row_len(tb.L);
+    const int idx_pitch = int(lo_pitch(tb.L));
+    const uint16_t *hi_tab = w.lo_tab + (long long)lo_n_max(tb.L, cd.S_max, tb.M) * tb.T * tb.n_tp * idx_pitch;
     hipLaunchKernelGGL(k2_h1f1b, dim3(n_groups), dim3(kFastThreads), h1f1b_lds_bytes(tb.L, cd.S_max, 8), st, tb,
-                       cd, t_max, out, warmup, w.counts, w.live_list, w.dead_list, w.bands, w.arg,
+                       cd, t_max, out, warmup, w.counts, w.live_list, w.dead_list, w.bands, hi_tab, idx_pitch, w.arg,
                        fast_arg_per_group(tb.L, cd.S_max), row_len, fast_row_len(tb.L));
     hipLaunchKernelGGL(k2_h1f1b_wide, dim3(n_groups), dim3(kFastThreads), h1f1b_lds_bytes(tb.L, cd.S_max, 16),
-                       st, tb, cd, t_max, out, warmup, w.counts, w.live_list, w.dead_list, w.bands, w.arg,
+                       st, tb, cd, t_max, out, warmup, w.counts, w.live_list, w.dead_list, w.bands, hi_tab, idx_pitch, w.arg,
                        fast_arg_per_group(tb.L, cd.S_max), row_len, fast_row_len(tb.L));
 }
 
