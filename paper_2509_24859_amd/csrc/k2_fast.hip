@@ -143,11 +143,25 @@ __global__ __launch_bounds__(256) void k2_band(TablesDev tb, CandDev cd, int *co
         // slot lists of this workgroup's candidates: (group << 3) | degree index, or kBadSlot
         const int32_t *grp = cd.cand_group + int64_t(c0) * S_max;
         const int32_t *tpv = cd.cand_tp + int64_t(c0) * S_max;
-        for (int idx = threadIdx.x; idx < n_here * S_max; idx += nthreads) {
-            const int cl = idx / S_max, s = idx - cl * S_max;
-            const int g = grp[idx];
-            const int k = tp_index(tb, tpv[idx]);
-            slots[s * pitch + cl] = (g < 0 || g >= tb.G || k < 0) ? kBadSlot : (uint16_t)((g << 3) | k);
+        // four loads in flight per thread: the loop is bound by their latency
+        const int n_slots = n_here * S_max;
+        for (int idx0 = threadIdx.x; idx0 < n_slots; idx0 += 4 * nthreads) {
+            int g4[4], t4[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int idx = idx0 + u * nthreads;
+                g4[u] = idx < n_slots ? grp[idx] : 0;
+                t4[u] = idx < n_slots ? tpv[idx] : 0;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int idx = idx0 + u * nthreads;
+                if (idx < n_slots) {
+                    const int cl = idx / S_max, s = idx - cl * S_max;
+                    const int g = g4[u], k = tp_index(tb, t4[u]);
+                    slots[s * pitch + cl] = (g < 0 || g >= tb.G || k < 0) ? kBadSlot : (uint16_t)((g << 3) | k);
+                }
+            }
         }
     }
     __syncthreads();
