@@ -77,7 +77,7 @@ bool problem_shape_ok(const harp_problem *p) {
 Layout make_layout(const harp_problem *p) {
     Layout y;
     const size_t L1 = size_t(p->L) + 1;
-    y.pitch = (int64_t)align_up(L1, 8);
+    y.pitch = (int64_t)align_up(L1, 16);
     y.pitch32 = (int64_t)align_up(L1, 16);
     y.n_chunks = (p->L + 255) / 256;     // scan scratch sized for the finest chunking (one wavefront)
     const size_t n_rows = size_t(p->T) + 2 + size_t(p->G) * p->n_tp;

@@ -143,28 +143,49 @@ __global__ __launch_bounds__(kScanThreads) void k1_chunk_sums(TablesDev tb, Buil
     // the next one; nothing to report here
 }
 
-// Launch 2: exclusive scan of the chunk sums of each row, in place.
+// Launch 2: exclusive scan of the chunk sums of each row, in place.  A thread takes a stretch of
+// consecutive sums - in registers when there are at most kSumsInRegs of them, so that the row is
+// read in one round trip and written in one - and the stretches' totals are scanned over the
+// workgroup.
+constexpr int kSumsInRegs = 16;
+
 __global__ __launch_bounds__(kScanThreads) void k1_scan_chunk_sums(TablesDev tb, int n_chunks) {
     int64_t *row = tb.chunk_sums + int64_t(blockIdx.x) * n_chunks;
     __shared__ int64_t part[kScanThreads / 64];
-    __shared__ int64_t carry_s;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int per = (n_chunks + kScanThreads - 1) / kScanThreads;
+    const int begin = threadIdx.x * per;
+    const int end = begin + per < n_chunks ? begin + per : n_chunks;    // below begin for the idle threads
     unsigned int over = 0;
-    if (threadIdx.x == 0) carry_s = 0;
+    int64_t vals[kSumsInRegs];
+    int64_t mine = 0;
+    if (per <= kSumsInRegs) {
+#pragma unroll
+        for (int q = 0; q < kSumsInRegs; ++q) vals[q] = begin + q < end ? row[begin + q] : 0;
+#pragma unroll
+        for (int q = 0; q < kSumsInRegs; ++q) mine = add_checked(mine, vals[q], over);
+    } else {
+        for (int i = begin; i < end; ++i) mine = add_checked(mine, row[i], over);
+    }
+    const int64_t inc = wave_inclusive_scan(mine, lane, over);
+    if (lane == 63) part[wave] = inc;
     __syncthreads();
-    for (int base = 0; base < n_chunks; base += kScanThreads) {
-        int idx = base + threadIdx.x;
-        int64_t v = idx < n_chunks ? row[idx] : 0;
-        int64_t inc = wave_inclusive_scan(v, lane, over);
-        if (lane == 63) part[wave] = inc;
-        __syncthreads();
-        int64_t off = carry_s;
-        for (int w = 0; w < wave; ++w) off = add_checked(off, part[w], over);
-        const int64_t upto = add_checked(off, inc, over);       // the last thread's is the row's total so far
-        if (idx < n_chunks) row[idx] = upto - v;
-        __syncthreads();
-        if (threadIdx.x == kScanThreads - 1) carry_s = upto;
-        __syncthreads();
+    int64_t off = 0;
+    for (int w = 0; w < wave; ++w) off = add_checked(off, part[w], over);
+    add_checked(off, inc, over);                                        // the last thread's is the row's total
+    int64_t before = off + (inc - mine);                                // sum of everything before this stretch
+    if (per <= kSumsInRegs) {
+#pragma unroll
+        for (int q = 0; q < kSumsInRegs; ++q) {
+            if (begin + q < end) row[begin + q] = before;
+            before += vals[q];
+        }
+    } else {
+        for (int i = begin; i < end; ++i) {
+            const int64_t v = row[i];
+            row[i] = before;
+            before += v;
+        }
     }
     report(tb.header, 0, over, 0, false);
 }
@@ -219,6 +240,7 @@ __global__ __launch_bounds__(kScanThreads) void k1_scan_rows(TablesDev tb, Build
 // multiply-add gives the remainder that corrects it.  What is left is the 8-byte store per table
 // entry, i.e. the HBM write stream.
 
+typedef long long i64x2 __attribute__((ext_vector_type(2)));
 constexpr int kWaveItems = 4;
 constexpr int kWaveChunk = 64 * kWaveItems;
 
@@ -295,6 +317,32 @@ __device__ __forceinline__ void ar_values_tight(const ArRow &r, const ActRun &a,
         quo += rem < 0.0 ? -1.0 : (rem >= r.den_d ? 1.0 : 0.0);
         v[q] = r.mul == 0 ? 0u : (uint32_t)quo;
     }
+}
+
+// Raw values of one thread's four operators of a row that reads memory (a fixed row: fwd + bwd of
+// a type, parameter bytes, stash bytes), loaded ahead of their use; zero beyond L.
+constexpr int kRowsInFlight = 2;
+struct MemRow {
+    int64_t a[kWaveItems], b[kWaveItems];
+};
+
+__device__ __forceinline__ MemRow load_mem_row(const RowSource &s, int64_t base, int64_t L) {
+    MemRow w;
+#pragma unroll
+    for (int q = 0; q < kWaveItems; ++q) {
+        const bool in = base + q < L;
+        w.a[q] = in ? s.a[base + q] : 0;
+        w.b[q] = (in && s.b) ? s.b[base + q] : 0;
+    }
+    return w;
+}
+
+// the checks and the sum of row_value for a fixed row, on values already loaded
+__device__ __forceinline__ int64_t mem_row_value(const MemRow &w, int q, unsigned int &bad, unsigned int &ovf) {
+    int64_t x = w.a[q], y = w.b[q];
+    if (x < 0) { bad = 1; x = 0; }
+    if (y < 0) { bad = 1; y = 0; }
+    return add_checked(x, y, ovf);
 }
 
 // value q of row r for this thread: all-reduce rows from the staged run, the others from memory
@@ -413,7 +461,29 @@ __global__ __launch_bounds__(kScanThreads) void k1_long_sums(TablesDev tb, Build
     const ActRun a = load_act_run(tb, lim, base, bad, ovf, act_seen);
     const bool all_narrow = __all(a.narrow);
     int64_t same_mul = -1, same_den = -1, same_sum = 0;     // the all-reduce row computed last
-    for (int x = x_begin; x < x_end; ++x) {
+    // the rows that read their values from memory come first in the order: their loads are issued
+    // kRowsInFlight rows at a time, so that a run waits for memory once per batch, not once per row
+    const int n_fixed = tb.T + 2;
+    const int m_end = x_end < n_fixed ? x_end : n_fixed;
+    int x_from = x_begin;
+    for (int x0 = x_begin; x0 < m_end; x0 += kRowsInFlight) {
+        MemRow w[kRowsInFlight];
+#pragma unroll
+        for (int u = 0; u < kRowsInFlight; ++u)
+            if (x0 + u < m_end) w[u] = load_mem_row(long_row(tb, rows_lds, lp, x0 + u).src, base, tb.L);
+#pragma unroll
+        for (int u = 0; u < kRowsInFlight; ++u) {
+            if (x0 + u >= m_end) break;
+            int64_t sum = 0;
+#pragma unroll
+            for (int q = 0; q < kWaveItems; ++q) sum += mem_row_value(w[u], q, bad, ovf);
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) sum += __shfl_xor(sum, d, 64);
+            if (lane == 0) tb.chunk_sums[int64_t(x0 + u) * n_runs + run] = sum;
+        }
+        x_from = m_end;
+    }
+    for (int x = x_from; x < x_end; ++x) {
         if (keyed) {
             const LongRowKey key = keys[x - x_begin];
             if (key.same_as_previous && all_narrow) {       // the row before it took the tight form: same sum
@@ -458,7 +528,7 @@ __global__ __launch_bounds__(kScanThreads) void k1_long_scan(TablesDev tb, Build
     const LongPart lp = long_part(tb);
     const int x_begin = lp.x_begin, x_end = lp.x_end;
     stage_long_rows(tb, rows_lds, lp);
-    __shared__ int64_t tiles[kScanThreads / 64][kWaveChunk];
+    __shared__ __align__(16) int64_t tiles[kScanThreads / 64][kWaveChunk + 2];
     const bool keyed = x_end - x_begin <= kLongRowsInLds;
     const LongRowKey *keys = long_row_keys(rows_lds, x_begin, x_end);
     const int lane = threadIdx.x & 63;
@@ -477,7 +547,6 @@ __global__ __launch_bounds__(kScanThreads) void k1_long_scan(TablesDev tb, Build
         else { key.r = long_row_order(tb, lp, x); key.same_as_previous = 0; }
         const int r = key.r;
         int64_t *out = tb.rows + int64_t(r) * tb.pitch;
-        if (run == 0 && lane == 0) out[0] = 0;
         const int64_t start = tb.chunk_sums[int64_t(r) * n_runs + run];   // sum of the row before this run
         // rows of groups with the same link speed and degree are identical: when the row walked just
         // before this one took the tight form with the same constants and started from the same sum,
@@ -513,17 +582,24 @@ __global__ __launch_bounds__(kScanThreads) void k1_long_scan(TablesDev tb, Build
 #pragma unroll
                 for (int q = 0; q < kWaveItems; ++q) {
                     acc = add_checked(acc, v[q], ovf);
-                    tile[lane * kWaveItems + q] = acc;
+                    tile[lane * kWaveItems + q + 1] = acc;
                 }
+                if (lane == 0) tile[0] = start;
             }
         }
+        // the wavefront stores entries first .. first + 255 of the row (entry first is the sum before
+        // the run, so a row's leading zero comes from run 0), 16 bytes per lane: rows start on 128-byte
+        // lines and so does every run, and a store instruction covers eight whole lines
         const int64_t first = int64_t(run) * kWaveChunk;
 #pragma unroll
-        for (int q = 0; q < kWaveItems; ++q) {
-            const int e = q * 64 + lane;
-            const int64_t val = tile[e];
-            if (first + e < tb.L) out[first + e + 1] = val;
+        for (int h = 0; h < 2; ++h) {
+            const int e = h * 128 + 2 * lane;
+            const i64x2 val = *reinterpret_cast<const i64x2 *>(&tile[e]);
+            if (first + e + 1 <= tb.L) __builtin_nontemporal_store(val, reinterpret_cast<i64x2 *>(&out[first + e]));
+            else if (first + e <= tb.L) out[first + e] = val.x;
         }
+        // a sequence that ends with a full run: its last entry lies one past the last window
+        if (first + kWaveChunk == tb.L && lane == 0) out[tb.L] = tile[kWaveChunk];
     }
     }
 #pragma unroll
@@ -535,102 +611,143 @@ __global__ __launch_bounds__(kScanThreads) void k1_long_scan(TablesDev tb, Build
 }
 
 // Launch 4 (one workgroup): checks of the small arrays, device numbering of the groups, the
-// magnitude verdict, and whether the 32-bit fast path may be used.
+// magnitude verdict, and whether the 32-bit fast path may be used.  The kernel is a chain of
+// dependent memory round trips and little else, so everything whose address depends on nothing -
+// each thread's first element of every array, the all-reduce totals, what thread 0 needs at the end -
+// is loaded before the first wait; only the work totals (their row is the group's type) come second.
 __global__ __launch_bounds__(256) void k1_finalize(TablesDev tb, BuildLimits lim) {
     __shared__ unsigned int bad_s, ovf_s;
     __shared__ unsigned long long min_bw_s;
     __shared__ long long worst_s, worst32_s;
-    if (threadIdx.x == 0) { bad_s = 0; ovf_s = 0; min_bw_s = ~0ull; worst_s = 0; worst32_s = 0; }
-    __syncthreads();
+    __shared__ long long wave_total[4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int L = tb.L;
-    for (int64_t e = threadIdx.x; e < int64_t(tb.G) * tb.G; e += blockDim.x) {
-        int64_t b = tb.bw[e];
-        if (b < 1) atomicOr(&bad_s, 1u);
+    const int64_t n_links = int64_t(tb.G) * tb.G;
+    const int n_pairs = tb.G * tb.n_tp;
+    const int per = (tb.G + 255) / 256;                 // consecutive groups per thread for the numbering
+    const int g_begin = tid * per, g_end = (g_begin + per) < tb.G ? (g_begin + per) : tb.G;
+
+    const int64_t bw0 = tid < n_links ? tb.bw[tid] : 1;
+    const int64_t mem0 = tid < tb.T ? tb.type_mem[tid] : 0;
+    int type0 = 0, ndev0 = 1;
+    if (tid < tb.G) { type0 = tb.group_type[tid]; ndev0 = tb.group_ndev[tid]; }
+    const int first_ndev = g_begin < g_end ? tb.group_ndev[g_begin] : 0;
+    int pair_type = 0;
+    unsigned long long pair_ar = 0;
+    if (tid < n_pairs) {
+        const int g = tid / tb.n_tp, k = tid - g * tb.n_tp;
+        pair_type = tb.group_type[g];
+        pair_ar = (unsigned long long)tb.PR(g, k)[L];
+    }
+    unsigned int h_bad = 0, h_ovf = 0;
+    unsigned long long h_act = 0;
+    long long pp = 0, ps = 0;
+    if (tid == 0) {
+        const BuildHeader *h = tb.header;
+        h_bad = h->bad_arg; h_ovf = h->overflow; h_act = h->max_act;
+        pp = tb.PP()[L]; ps = tb.PS()[L];
+        bad_s = 0; ovf_s = 0; min_bw_s = ~0ull; worst_s = 0; worst32_s = 0;
+    }
+    __syncthreads();
+
+    unsigned int bad = 0, ovf = 0;
+    unsigned long long min_bw = ~0ull;
+    for (int64_t e = tid; e < n_links; e += blockDim.x) {
+        const int64_t b = e == tid ? bw0 : tb.bw[e];
+        if (b < 1) bad = 1;
         else {
             // tp * bandwidth is formed for a group's own link only (the all-reduce time), degrees above 1
             const bool own = e / tb.G == e % tb.G;
-            if (own && tb.n_tp > 1 && b > lim.bw_max) atomicOr(&ovf_s, 1u);
-            atomicMin(&min_bw_s, (unsigned long long)b);
+            if (own && tb.n_tp > 1 && b > lim.bw_max) ovf = 1;
+            if ((unsigned long long)b < min_bw) min_bw = (unsigned long long)b;
         }
     }
-    for (int t = threadIdx.x; t < tb.T; t += blockDim.x) {
-        int64_t m = tb.type_mem[t];
-        if (m < 0) atomicOr(&bad_s, 1u);
-        else if (m > lim.mem_max) atomicOr(&ovf_s, 1u);
+    for (int t = tid; t < tb.T; t += blockDim.x) {
+        const int64_t m = t == tid ? mem0 : tb.type_mem[t];
+        if (m < 0) bad = 1;
+        else if (m > lim.mem_max) ovf = 1;
     }
-    for (int g = threadIdx.x; g < tb.G; g += blockDim.x) {
-        int t = tb.group_type[g];
-        if (t < 0 || t >= tb.T || tb.group_ndev[g] < 1) atomicOr(&bad_s, 1u);
+    for (int g = tid; g < tb.G; g += blockDim.x) {
+        const int t = g == tid ? type0 : tb.group_type[g];
+        const int n = g == tid ? ndev0 : tb.group_ndev[g];
+        if (t < 0 || t >= tb.T || n < 1) bad = 1;
     }
+    if (bad) atomicOr(&bad_s, 1u);
+    if (ovf) atomicOr(&ovf_s, 1u);
+    if (min_bw != ~0ull) atomicMin(&min_bw_s, min_bw);
+
     // first device of every group: exclusive running sum of the group sizes.  Each thread takes a run
-    // of consecutive groups, the runs' totals are scanned in LDS, and no load waits on a store.
-    __shared__ long long run_total[256];
-    const int per = (tb.G + 255) / 256;
-    const int g_begin = threadIdx.x * per, g_end = (g_begin + per) < tb.G ? (g_begin + per) : tb.G;
+    // of consecutive groups; the runs' totals are scanned per wavefront and over the four wavefronts.
     long long mine = 0;
     for (int g = g_begin; g < g_end; ++g) {
-        const int n = tb.group_ndev[g];
+        const int n = g == g_begin ? first_ndev : tb.group_ndev[g];
         mine += n > 0 ? n : 0;
     }
-    run_total[threadIdx.x] = mine;
+    long long upto = mine;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const long long up = __shfl_up(upto, d, 64);
+        if (lane >= d) upto += up;
+    }
+    if (lane == 63) wave_total[wave] = upto;
     __syncthreads();
     const bool groups_ok = (bad_s == 0);
-    for (int d = 1; d < 256; d <<= 1) {
-        const long long add = threadIdx.x >= d ? run_total[threadIdx.x - d] : 0;
-        __syncthreads();
-        run_total[threadIdx.x] += add;
-        __syncthreads();
+    long long all_devices = 0;
+    for (int w = 0; w < 4; ++w) {
+        if (w < wave) upto += wave_total[w];
+        all_devices += wave_total[w];
     }
     {
-        long long base = run_total[threadIdx.x] - mine;           // devices before this thread's run
+        long long base = upto - mine;                               // devices before this thread's run
         for (int g = g_begin; g < g_end; ++g) {
             tb.group_base[g] = (int32_t)(base > INT32_MAX ? 0 : base);
-            const int n = tb.group_ndev[g];
+            const int n = g == g_begin ? first_ndev : tb.group_ndev[g];
             base += n > 0 ? n : 0;
         }
-        if (threadIdx.x == 255) {
+        if (tid == 255) {
             // more devices than an int32 numbers: the problem is refused, the bases are not used
-            if (run_total[255] > INT32_MAX) atomicOr(&ovf_s, 1u);
-            tb.header->total_devices = run_total[255] > INT32_MAX ? 0 : run_total[255];
+            if (all_devices > INT32_MAX) atomicOr(&ovf_s, 1u);
+            tb.header->total_devices = all_devices > INT32_MAX ? 0 : all_devices;
         }
     }
     if (groups_ok) {
-        for (int q = threadIdx.x; q < tb.G * tb.n_tp; q += blockDim.x) {
-            int g = q / tb.n_tp, k = q - g * tb.n_tp;
+        long long worst = 0, worst32 = 0;
+        for (int q = tid; q < n_pairs; q += blockDim.x) {
+            const int g = q / tb.n_tp, k = q - g * tb.n_tp;
             // both totals are below 2^63 unless the build has already noted an overflow
-            unsigned long long work = (unsigned long long)tb.PF(tb.group_type[g])[L];
-            unsigned long long ar = (unsigned long long)tb.PR(g, k)[L];
-            unsigned long long whole = work + ar;
-            long long w = whole >= (unsigned long long)kTimeLimit ? kTimeLimit : (long long)whole;
-            atomicMax(&worst_s, w);
-            unsigned long long tp = (unsigned long long)tb.tp[k];
-            unsigned long long fused = (ar < (1ull << 40)) ? work + tp * ar + tp - 1 : ~0ull;
-            long long f = fused >= (unsigned long long)kTimeLimit ? kTimeLimit : (long long)fused;
-            atomicMax(&worst32_s, f);
+            const unsigned long long work = (unsigned long long)tb.PF(q == tid ? pair_type : tb.group_type[g])[L];
+            const unsigned long long ar = q == tid ? pair_ar : (unsigned long long)tb.PR(g, k)[L];
+            const unsigned long long whole = work + ar;
+            const long long w = whole >= (unsigned long long)kTimeLimit ? kTimeLimit : (long long)whole;
+            worst = w > worst ? w : worst;
+            const unsigned long long tp = (unsigned long long)tb.tp[k];
+            const unsigned long long fused = (ar < (1ull << 40)) ? work + tp * ar + tp - 1 : ~0ull;
+            const long long f = fused >= (unsigned long long)kTimeLimit ? kTimeLimit : (long long)fused;
+            worst32 = f > worst32 ? f : worst32;
         }
+        if (tid < n_pairs) { atomicMax(&worst_s, worst); atomicMax(&worst32_s, worst32); }
     }
     __syncthreads();
-    if (threadIdx.x == 0) {
+    if (tid == 0) {
         BuildHeader *h = tb.header;
-        unsigned int bad = bad_s | h->bad_arg, ovf = ovf_s | h->overflow;
+        unsigned int bad_all = bad_s | h_bad, ovf_all = ovf_s | h_ovf;
         long long worst = worst_s, cut_worst = 0;
-        if (!bad) {
-            cut_worst = (long long)((h->max_act + min_bw_s - 1ull) / min_bw_s);
+        if (!bad_all) {
+            cut_worst = (long long)((h_act + min_bw_s - 1ull) / min_bw_s);
             if (cut_worst > worst) worst = cut_worst;
-            if (worst >= kTimeLimit) ovf = 1;
-            else if (worst > INT64_MAX / (3ll * L + tb.M)) ovf = 1;
+            if (worst >= kTimeLimit) ovf_all = 1;
+            else if (worst > INT64_MAX / (3ll * L + tb.M)) ovf_all = 1;
             // memory need of any segment with any in-flight count
             long long n_max = tb.M < L ? tb.M : L;
-            long long pp = tb.PP()[L], ps = tb.PS()[L];
-            if (ps > (INT64_MAX - pp) / n_max) ovf = 1;
+            if (ps > (INT64_MAX - pp) / n_max) ovf_all = 1;
         }
         bool pow2 = true;
         for (int k = 0; k < tb.n_tp; ++k) pow2 = pow2 && tb.tp_shift[k] >= 0;
         const long long lim32 = 1ll << 31;
-        h->bad_arg = bad;
-        h->overflow = ovf;
+        h->bad_arg = bad_all;
+        h->overflow = ovf_all;
         h->worst_time = worst;
-        h->fast32 = (!bad && !ovf && lim.want_fast && pow2 && worst32_s < lim32 && cut_worst < lim32) ? 1u : 0u;
+        h->fast32 = (!bad_all && !ovf_all && lim.want_fast && pow2 && worst32_s < lim32 && cut_worst < lim32) ? 1u : 0u;
     }
 }
 
