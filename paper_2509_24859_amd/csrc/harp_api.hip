@@ -511,7 +511,7 @@ int harp_plan_exact_batch(harp_ctx *ctx, harp_tables *t, const harp_candidates *
     if (pc.fast) {
         rc = plan_minmax(ctx, t, pc, workspace, nullptr);
         if (rc != HARP_OK) return rc;
-        launch_plan_exact(t->dev, pc.c, pc.o, n_passes, workspace, pc.groups, pc.st);
+        launch_plan_exact(t->dev, pc.c, pc.o, n_passes, workspace, pc.groups, pc.slices, ctx->n_cu, pc.st);
     } else {
         launch_plan_generic_exact(t->dev, pc.c, pc.o, n_passes, workspace, pc.groups, pc.banded, pc.st);
     }

@@ -124,7 +124,7 @@ constexpr int kFastWaves = 4;           // wavefronts per workgroup of k2_fast; 
 constexpr size_t kFastIndexLimit = size_t(256) << 20;   // feasibility index of the pre-pass
 constexpr int kIndexMaxL = 16383;       // its build keeps one 8-byte sum per cut in LDS (128 KB)
 void launch_plan_exact(const TablesDev &tb, const CandDev &cd, const PlansDev &out, int32_t *n_passes,
-                       void *ws, int n_groups, hipStream_t st);
+                       void *ws, int n_groups, int n_slices, int n_cu, hipStream_t st);
 void launch_score(const TablesDev &tb, const CandDev &cd, const int32_t *splits,
                   int64_t *bottleneck, int64_t *iter_time, int32_t *status, hipStream_t st);
 void launch_valu_int32(int blocks, int iters, uint32_t *sink, hipStream_t st);
