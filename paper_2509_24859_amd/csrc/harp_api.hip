@@ -527,7 +527,7 @@ int harp_plan_h1f1b_batch(harp_ctx *ctx, harp_tables *t, const harp_candidates *
     const int rc = plan_prepare(ctx, t, cd, out, cd && cd->C > 0 && (!warmup || !t_max), true, workspace,
                                 workspace_bytes, false, hip_stream, pc);
     if (rc != HARP_OK || cd->C == 0) return rc;
-    if (pc.fast) launch_plan_h1f1b(t->dev, pc.c, t_max, pc.o, warmup, workspace, pc.groups, pc.st);
+    if (pc.fast) launch_plan_h1f1b(t->dev, pc.c, t_max, pc.o, warmup, workspace, pc.groups, pc.slices, ctx->n_cu, pc.st);
     else launch_plan_generic_h1f1b(t->dev, pc.c, t_max, pc.o, warmup, workspace, pc.groups, pc.banded, pc.st);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(ctx, e, "launching the H-1F1B planner kernels");

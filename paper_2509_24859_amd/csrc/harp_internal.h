@@ -89,7 +89,7 @@ void launch_plan_fast(const TablesDev &tb, const CandDev &cd, const PlansDev &ou
                       int n_slices, int n_cu, unsigned long long *work, hipStream_t st);
 void launch_plan_prepass(const TablesDev &tb, const CandDev &cd, void *ws, int n_groups, hipStream_t st);
 void launch_plan_h1f1b(const TablesDev &tb, const CandDev &cd, const int64_t *t_max, const PlansDev &out,
-                       int32_t *warmup, void *ws, int n_groups, hipStream_t st);
+                       int32_t *warmup, void *ws, int n_groups, int n_slices, int n_cu, hipStream_t st);
 void launch_plan_generic_h1f1b(const TablesDev &tb, const CandDev &cd, const int64_t *t_max, const PlansDev &out,
                                int32_t *warmup, void *ws, int n_groups, bool banded, hipStream_t st);
 size_t plan_generic_h1f1b_ws_per_group(int L, int S_max);

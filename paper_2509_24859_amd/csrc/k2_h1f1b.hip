@@ -10,9 +10,12 @@
 // (t + 2c) under the cap and carries the warm-up count of its first stage as determined by the
 // continuation that attained the least sum.  Counts never exceed the number of microbatches.
 //
-// Mapping: as in the min-max kernel, one workgroup per live candidate at a time, one lane per cell
+// Mapping: one wavefront per live candidate at a time (64-thread workgroups), one lane per cell
 // of the current slot's reachability band (the bands of the pre-pass were computed with the classic
-// 1F1B counts, which are never larger than H-1F1B's, so they remain outer bounds), rows in LDS.
+// 1F1B counts, which are never larger than H-1F1B's, so they remain outer bounds), rows in LDS that
+// hold the cuts one slot touches; a candidate whose widest slot does not fit the wavefront's LDS
+// share is queued for a second launch with one 256-thread workgroup per candidate and rows over the
+// whole sequence, which is also the form the 64-bit instantiation has.
 // The row handed from slot sigma+1 to slot sigma is stored ready for use: entry j holds the
 // suffix sum plus twice the transfer time of the cut at j (infinity when that transfer exceeds the
 // cap) and the count the stage in front of j would have, so a transition is one stage time, one
@@ -54,8 +57,26 @@ __device__ __forceinline__ uint32_t h1f1b_delta(uint32_t c, int64_t cap) {
     return 1u + (x > 0 ? 1u : 0u) + (x > cap ? 1u : 0u);
 }
 
-// counts: [0] live, [1] dead, [2] queued for 64-bit sums, [6] and [7] tickets of the two kernels.
-template <typename SumT>
+// LDS in front of the rows: per-slot constants, two scalars, band and trial cuts, two flags,
+// index-row offsets, the plan's deltas, slot lists
+__host__ __device__ inline size_t h1f1b_small_bytes(int S_max) {
+    const size_t b = size_t(S_max) * sizeof(StageConst) + 16 + size_t(S_max + 1) * 8 + 8 + size_t(S_max) * 11;
+    return (b + 15) & ~size_t(15);
+}
+// bytes per cut of the rows in LDS when every row is sized for one slot: one row of memory sums, two
+// of entries, one of times
+__host__ __device__ inline size_t h1f1b_cut_bytes(size_t entry) { return sizeof(MemPair) + 2 * entry + 4; }
+
+// counts: [0] live, [1] dead, [2] queued for 64-bit sums, [6] and [7] tickets of the 32- and 64-bit
+// kernels, [10] candidates queued for rows over the whole sequence, [11] next item of that list.
+// Both queues sit in the unused tail of the dead list, the 64-bit one from its front, the other from
+// its back.
+//
+// kMode 0: a workgroup per candidate, LDS rows with an entry for every cut.  kMode 1: a wavefront
+// per candidate (64-thread workgroups), LDS rows that hold the cuts one slot touches (a slot's cells
+// and continuations: B[slot] .. F[slot+1]), sized for the candidate's widest slot; a candidate that
+// does not fit is queued.  kMode 2: as 0, on the candidates queued by 1.
+template <typename SumT, int kMode>
 __device__ __forceinline__ void h1f1b_body(const TablesDev &tb, const CandDev &cd, const int64_t *t_max,
                                            const PlansDev &out, int32_t *warmup, int *counts,
                                            const int32_t *live_list, uint32_t *dead_list,
@@ -65,37 +86,45 @@ __device__ __forceinline__ void h1f1b_body(const TablesDev &tb, const CandDev &c
     using Entry = typename H1Traits<SumT>::Entry;
     constexpr SumT kInfSum = H1Traits<SumT>::inf;
     constexpr bool kWide = sizeof(SumT) == 8;
+    constexpr bool kBandRows = kMode == 1;
     extern __shared__ __align__(16) unsigned char lds_raw[];
 
     const int L = tb.L, S_max = cd.S_max;
     const int tid = threadIdx.x, lane = tid & 63, nthreads = blockDim.x;
     const int wave = uniform(tid >> 6);
-    MemPair *mem = reinterpret_cast<MemPair *>(lds_raw);                               // [row_len]
-    Entry *rows = reinterpret_cast<Entry *>(mem + row_len);                            // [2][row_len]
-    uint32_t *prow = reinterpret_cast<uint32_t *>(rows + 2 * row_len);                 // [2][row_len]
-    StageConst *sc = reinterpret_cast<StageConst *>(prow + 2 * row_len);               // [S_max]
+    StageConst *sc = reinterpret_cast<StageConst *>(lds_raw);                          // [S_max]
     uint64_t *scal = reinterpret_cast<uint64_t *>(sc + S_max);                         // [2]
     uint32_t *band = reinterpret_cast<uint32_t *>(scal + 2);                           // [S_max + 1]
     int32_t *trial = reinterpret_cast<int32_t *>(band + S_max + 1);                    // [S_max + 1]
     uint32_t *flags = reinterpret_cast<uint32_t *>(trial + S_max + 1);                 // [2]: ticket, overflow
-    uint16_t *slot_g = reinterpret_cast<uint16_t *>(flags + 2);                        // [S_max]
-    uint8_t *slot_k = reinterpret_cast<uint8_t *>(slot_g + S_max);                     // [S_max]
     // element offset of each slot's row of the feasibility index: the highest end cut that fits with the
     // classic count of the slot, an outer bound for H-1F1B's (its counts are never below the classic ones)
-    uint32_t *hi_off = reinterpret_cast<uint32_t *>(
-        lds_raw + ((size_t(reinterpret_cast<unsigned char *>(slot_k + S_max) - lds_raw) + 3) & ~size_t(3)));   // [S_max]
+    uint32_t *hi_off = flags + 2;                                                      // [S_max]
+    uint32_t *deltas = hi_off + S_max;                                                 // [S_max]
+    uint16_t *slot_g = reinterpret_cast<uint16_t *>(deltas + S_max);                   // [S_max]
+    uint8_t *slot_k = reinterpret_cast<uint8_t *>(slot_g + S_max);                     // [S_max]
+    // Rows of row_len entries.  Whole-sequence form: one row of memory sums, two of entries, two of
+    // times; entry x of a row is cut x.  Slot-sized form: a row's entry 0 is the lowest cut of the
+    // slot it serves, and the memory sums and times of the slot in front take the place of this
+    // slot's once its cells are done (one wavefront: its LDS operations execute in order).
+    MemPair *mem0 = reinterpret_cast<MemPair *>(lds_raw + h1f1b_small_bytes(S_max));
+    MemPair *mem1 = mem0;
+    Entry *rows0 = reinterpret_cast<Entry *>(mem1 + row_len);
+    Entry *rows1 = rows0 + row_len;
+    uint32_t *prow0 = reinterpret_cast<uint32_t *>(rows1 + row_len);
+    uint32_t *prow1 = kBandRows ? prow0 : prow0 + row_len;
     uint16_t *arg = reinterpret_cast<uint16_t *>(arg_base + size_t(blockIdx.x) * arg_per_group);
     const int n_dead = counts[1];
-    const int n_items = kWide ? counts[2] : counts[0];
-    int *next_item = counts + (kWide ? 7 : 6);
+    const int n_items = kWide ? counts[2] : kMode == 2 ? counts[10] : counts[0];
+    int *next_item = counts + (kWide ? 7 : kMode == 2 ? 11 : 6);
     const int64_t m_cap = tb.M;
+    const int64_t *PP = tb.PP(), *PS = tb.PS();
 
     // the running sums of parameter and stash bytes are the same for every candidate
-    {
-        const int64_t *PP = tb.PP(), *PS = tb.PS();
-        for (int j = tid; j <= L; j += nthreads) mem[j] = MemPair{PP[j], PS[j]};
-        for (int j = L + 1 + tid; j < row_len; j += nthreads) mem[j] = MemPair{0, 0};
-        for (int j = L + 1 + tid; j < row_len; j += nthreads) { prow[j] = 0; prow[row_len + j] = 0; }
+    if (!kBandRows) {
+        for (int j = tid; j <= L; j += nthreads) mem0[j] = MemPair{PP[j], PS[j]};
+        for (int j = L + 1 + tid; j < row_len; j += nthreads) mem0[j] = MemPair{0, 0};
+        for (int j = L + 1 + tid; j < row_len; j += nthreads) { prow0[j] = 0; prow1[j] = 0; }
     }
 
     for (;;) {
@@ -104,7 +133,7 @@ __device__ __forceinline__ void h1f1b_body(const TablesDev &tb, const CandDev &c
         __syncthreads();
         const int n = uniform((int)flags[0]);
         if (n >= n_items) break;
-        const int c = kWide ? int(dead_list[n_dead + n]) : live_list[n];
+        const int c = kWide ? int(dead_list[n_dead + n]) : kMode == 2 ? int(dead_list[cd.C - 1 - n]) : live_list[n];
         const int S = cd.cand_S[c];
         const int64_t cap64 = t_max[c];
         int32_t *sp = out.splits + int64_t(c) * (S_max + 1);
@@ -137,19 +166,44 @@ __device__ __forceinline__ void h1f1b_body(const TablesDev &tb, const CandDev &c
             }
             for (int s = S + tid; s < S_max; s += nthreads) df[s] = -1;
             for (int s = tid; s <= S; s += nthreads) band[s] = bands[int64_t(c) * (S_max + 1) + s];
-            // behind the last stage: no operators left, nothing launched yet; the last stage itself
-            // adds delta(0) = 1
-            if (tid == 0) { rows[L].h = 0; rows[L].nn = 1; }
-            if (tid >= 1 && tid <= kTail) rows[L + tid].h = kInfSum;
         }
         // stored sums stay this small, so that adding an admissible stage time cannot reach infinity
         const uint64_t limit = kWide ? uint64_t(kInfSum) - 1 : uint64_t(kInfSum) - 1 - tcap;
         __syncthreads();          // slot constants and bands are in LDS
-        // prologue: the fused time row of the last slot over its cells and its single continuation
+        if (kBandRows) {
+            // a slot touches its cells and its continuations, B[slot] .. F[slot+1], and up to kTail
+            // entries behind them
+            int span = 0;
+            for (int s = tid; s < S; s += nthreads) {
+                const int w = band_hi(band[s + 1]) - (s == 0 ? 0 : band_lo(band[s])) + 1;
+                span = w > span ? w : span;
+            }
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) {
+                const int o = __shfl_xor(span, d, 64);
+                span = o > span ? o : span;
+            }
+            if (uniform(span) + kTail > row_len) {
+                if (tid == 0) dead_list[cd.C - 1 - atomicAdd(&counts[10], 1)] = uint32_t(c);
+                continue;
+            }
+        }
+        // prologue: behind the last stage no operators are left and nothing is launched yet (the last
+        // stage itself adds delta(0) = 1); the fused time row of the last slot over its cells and its
+        // single continuation
         {
             const int il0 = (S == 1) ? 0 : band_lo((uint32_t)uniform((int)band[S - 1]));
+            Entry *row_S = rows0 - (kBandRows ? L : 0);
+            if (tid == 0) { row_S[L].h = 0; row_S[L].nn = 1; }
+            if (tid >= 1 && tid <= kTail) row_S[L + tid].h = kInfSum;
             const uint32_t *p32 = tb.P32 + (uint32_t)uniform((int)sc[S - 1].p_row);
-            for (int x = il0 + tid; x <= L; x += nthreads) prow[x] = p32[x];
+            uint32_t *pr = prow0 - (kBandRows ? il0 : 0);
+            for (int x = il0 + tid; x <= L; x += nthreads) pr[x] = p32[x];
+            if (kBandRows) {
+                MemPair *mm = mem0 - il0;
+                for (int x = il0 + tid; x <= L + kTail - 1; x += nthreads)
+                    mm[x] = x <= L ? MemPair{PP[x], PS[x]} : MemPair{0, 0};
+            }
         }
         lds_barrier();
         int cur = 0, pcur = 0;
@@ -174,10 +228,14 @@ __device__ __forceinline__ void h1f1b_body(const TablesDev &tb, const CandDev &c
             const uint32_t tp = 1u << shift;
             const int64_t capm = uniform64(sc[slot].cap);
             const uint16_t *hi_row = hi_tab + (uint32_t)uniform((int)hi_off[slot]);
-            const uint32_t *pr_cur = prow + pcur * row_len;
-            uint32_t *pr_next = prow + (pcur ^ 1) * row_len;
-            const Entry *prev = rows + cur * row_len;
-            Entry *next = rows + (cur ^ 1) * row_len;
+            // rows of this slot start at its lowest cell il, the row of continuations at jl, the rows
+            // staged for the slot in front at nl
+            const uint32_t *pr_cur = (pcur ? prow1 : prow0) - (kBandRows ? il : 0);
+            uint32_t *pr_next = (pcur ? prow0 : prow1) - (kBandRows ? nl : 0);
+            const MemPair *mem = (pcur ? mem1 : mem0) - (kBandRows ? il : 0);
+            MemPair *mem_next = (pcur ? mem0 : mem1) - (kBandRows ? nl : 0);
+            const Entry *prev = (cur ? rows1 : rows0) - (kBandRows ? jl : 0);
+            Entry *next = (cur ? rows0 : rows1) - (kBandRows ? il : 0);
             // the cut in front of this slot's stage (between slot - 1 and slot)
             const uint32_t *cm_front = stage_next ? tb.CM + ((uint32_t)uniform((int)sc[slot - 1].cm_row_shift) & kRowMask)
                                                   : nullptr;
@@ -238,6 +296,10 @@ __device__ __forceinline__ void h1f1b_body(const TablesDev &tb, const CandDev &c
                 if (tid < kTail) next[ih + 1 + tid].h = kInfSum;     // behind the band
                 if (xn <= ih) pr_next[xn] = p_n;
                 for (int x = xn + nthreads; x <= ih; x += nthreads) pr_next[x] = p32_n[x];
+                if (kBandRows) {
+                    for (int x = xn; x <= ih + kTail - 1; x += nthreads)
+                        mem_next[x] = x <= L ? MemPair{PP[x], PS[x]} : MemPair{0, 0};
+                }
             }
             lds_barrier();
             cur ^= 1;
@@ -276,7 +338,7 @@ __device__ __forceinline__ void h1f1b_body(const TablesDev &tb, const CandDev &c
                 const uint32_t cu = s < S - 1 ? tb.CM[(rsl & kRowMask) + uint32_t(i)] : 0u;
                 const uint32_t m = t > cu ? t : cu;
                 w = w > m ? w : m;
-                prow[s] = s < S - 1 ? h1f1b_delta(cu, cap64) : 1u;     // prow is free now: the deltas
+                deltas[s] = s < S - 1 ? h1f1b_delta(cu, cap64) : 1u;
             }
 #pragma unroll
             for (int d = 32; d >= 1; d >>= 1) {
@@ -293,7 +355,7 @@ __device__ __forceinline__ void h1f1b_body(const TablesDev &tb, const CandDev &c
         if (tid == 0) {
             uint32_t nrun = 0;
             for (int s = S - 1; s >= 0; --s) {
-                nrun += prow[s];
+                nrun += deltas[s];
                 nrun = nrun < uint32_t(m_cap) ? nrun : uint32_t(m_cap);
                 wu[s] = int32_t(nrun);
             }
@@ -302,7 +364,7 @@ __device__ __forceinline__ void h1f1b_body(const TablesDev &tb, const CandDev &c
         for (int s = S + tid; s < S_max; s += nthreads) wu[s] = -1;
     }
     // candidates the pre-pass rejected: no plan to report
-    if (!kWide) {
+    if (!kWide && kMode != 2) {
         for (int n = blockIdx.x; n < n_dead; n += gridDim.x) {
             const uint32_t e = dead_list[n];
             const int c = int(e & ((1u << kDeadStatusShift) - 1u));
@@ -313,48 +375,66 @@ __device__ __forceinline__ void h1f1b_body(const TablesDev &tb, const CandDev &c
     }
 }
 
-__global__ __launch_bounds__(kFastThreads) __attribute__((amdgpu_waves_per_eu(8, 8)))
-void k2_h1f1b(TablesDev tb, CandDev cd, const int64_t *t_max, PlansDev out, int32_t *warmup, int *counts,
-              const int32_t *live_list, uint32_t *dead_list, const uint32_t *bands, const uint16_t *hi_tab,
-              int idx_pitch, unsigned char *arg_base, size_t arg_per_group, int row_len, int arg_pitch) {
-    h1f1b_body<uint32_t>(tb, cd, t_max, out, warmup, counts, live_list, dead_list, bands, hi_tab, idx_pitch, arg_base,
-                         arg_per_group, row_len, arg_pitch);
-}
-
-__global__ __launch_bounds__(kFastThreads)
-void k2_h1f1b_wide(TablesDev tb, CandDev cd, const int64_t *t_max, PlansDev out, int32_t *warmup, int *counts,
-                   const int32_t *live_list, uint32_t *dead_list, const uint32_t *bands, const uint16_t *hi_tab,
-                   int idx_pitch, unsigned char *arg_base, size_t arg_per_group, int row_len, int arg_pitch) {
-    h1f1b_body<uint64_t>(tb, cd, t_max, out, warmup, counts, live_list, dead_list, bands, hi_tab, idx_pitch, arg_base,
-                         arg_per_group, row_len, arg_pitch);
-}
+#define HARP_H1F1B_KERNEL(NAME, BOUNDS, SUM, MODE)                                                                  \
+    __global__ BOUNDS void NAME(TablesDev tb, CandDev cd, const int64_t *t_max, PlansDev out, int32_t *warmup,     \
+                                int *counts, const int32_t *live_list, uint32_t *dead_list, const uint32_t *bands, \
+                                const uint16_t *hi_tab, int idx_pitch, unsigned char *arg_base,                    \
+                                size_t arg_per_group, int row_len, int arg_pitch) {                                \
+        h1f1b_body<SUM, MODE>(tb, cd, t_max, out, warmup, counts, live_list, dead_list, bands, hi_tab, idx_pitch,  \
+                              arg_base, arg_per_group, row_len, arg_pitch);                                        \
+    }
+HARP_H1F1B_KERNEL(k2_h1f1b, __launch_bounds__(64), uint32_t, 1)
+HARP_H1F1B_KERNEL(k2_h1f1b_rows, __launch_bounds__(kFastThreads) __attribute__((amdgpu_waves_per_eu(8, 8))), uint32_t, 2)
+HARP_H1F1B_KERNEL(k2_h1f1b_wide, __launch_bounds__(kFastThreads), uint64_t, 0)
+#undef HARP_H1F1B_KERNEL
 
 int h1f1b_row_len(int L) { return (L + 1 + kTail + 7) / 8 * 8; }
 
+// whole-sequence rows: one of memory sums, two of entries, two of times
 size_t h1f1b_lds_bytes(int L, int S_max, size_t entry) {
-    size_t b = size_t(h1f1b_row_len(L)) * (sizeof(MemPair) + 2 * entry + 8) + size_t(S_max) * sizeof(StageConst) +
-               16 + size_t(S_max + 1) * 8 + 8 + size_t(S_max) * 3;
-    b = ((b + 3) & ~size_t(3)) + size_t(S_max) * 4;         // + the slots' index-row offsets
-    return (b + 15) & ~size_t(15);
+    return h1f1b_small_bytes(S_max) + size_t(h1f1b_row_len(L)) * (sizeof(MemPair) + 2 * entry + 8);
 }
 
 }  // namespace
 
 // Runs the pre-pass itself (launch_plan_fast's first two kernels are shared through
-// launch_plan_prepass) and then the two instantiations.
+// launch_plan_prepass) and then the three instantiations.  n_groups: resident 256-thread workgroups;
+// n_slices: back-pointer slices in the workspace (the wavefront-per-candidate launch runs at most
+// that many).
 void launch_plan_h1f1b(const TablesDev &tb, const CandDev &cd, const int64_t *t_max, const PlansDev &out,
-                       int32_t *warmup, void *ws, int n_groups, hipStream_t st) {
+                       int32_t *warmup, void *ws, int n_groups, int n_slices, int n_cu, hipStream_t st) {
     const FastWorkspace w = carve(ws, fast_shape(tb, cd), n_groups);
     launch_plan_prepass(tb, cd, ws, n_groups, st);
     const int row_len = h1f1b_row_len(tb.L);
     const int idx_pitch = int(lo_pitch(tb.L));
     const uint16_t *hi_tab = w.lo_tab + (long long)lo_n_max(tb.L, cd.S_max, tb.M) * tb.T * tb.n_tp * idx_pitch;
-    hipLaunchKernelGGL(k2_h1f1b, dim3(n_groups), dim3(kFastThreads), h1f1b_lds_bytes(tb.L, cd.S_max, 8), st, tb,
-                       cd, t_max, out, warmup, w.counts, w.live_list, w.dead_list, w.bands, hi_tab, idx_pitch, w.arg,
-                       fast_arg_per_group(tb.L, cd.S_max), row_len, fast_row_len(tb.L));
-    hipLaunchKernelGGL(k2_h1f1b_wide, dim3(n_groups), dim3(kFastThreads), h1f1b_lds_bytes(tb.L, cd.S_max, 16),
-                       st, tb, cd, t_max, out, warmup, w.counts, w.live_list, w.dead_list, w.bands, hi_tab, idx_pitch, w.arg,
-                       fast_arg_per_group(tb.L, cd.S_max), row_len, fast_row_len(tb.L));
+    const size_t per_group = fast_arg_per_group(tb.L, cd.S_max);
+    const int arg_pitch = fast_row_len(tb.L);
+    // Wavefronts per CU of the first launch and the row entries their LDS share leaves: as many
+    // wavefronts as hold rows for the whole sequence, between 16 and 24 (measured on the 512-operator
+    // workload, where such rows would leave 7: 12 per CU 14.2 ms, 16 12.7, 20 14.1, 24 16.9 - the
+    // smaller the share, the more candidates leave for the second launch; on the 160-operator one,
+    // where 22 fit: 16 per CU 2.2 ms, 20 2.0).
+    const size_t small = h1f1b_small_bytes(cd.S_max);
+    int per_cu = int((size_t(160) << 10) / (small + size_t(row_len) * h1f1b_cut_bytes(8) + 128));
+    per_cu = per_cu < 16 ? 16 : (per_cu > 24 ? 24 : per_cu);
+    const size_t share = ((size_t(160) << 10) / per_cu - 128) & ~size_t(15);
+    int entries = share > small + h1f1b_cut_bytes(8) * 16 ? int((share - small) / h1f1b_cut_bytes(8)) & ~1 : 16;
+    if (entries > row_len) entries = row_len;
+    int n_waves = per_cu * n_cu;
+    if (n_waves > n_slices) n_waves = n_slices;
+    if (n_waves > cd.C) n_waves = cd.C;
+    if (n_waves < 1) n_waves = 1;
+    hipLaunchKernelGGL(k2_h1f1b, dim3(n_waves), dim3(64), small + size_t(entries) * h1f1b_cut_bytes(8), st, tb, cd,
+                       t_max, out, warmup, w.counts, w.live_list, w.dead_list, w.bands, hi_tab, idx_pitch, w.arg,
+                       per_group, entries, arg_pitch);
+    if (entries < row_len)
+        hipLaunchKernelGGL(k2_h1f1b_rows, dim3(n_groups), dim3(kFastThreads), h1f1b_lds_bytes(tb.L, cd.S_max, 8),
+                           st, tb, cd, t_max, out, warmup, w.counts, w.live_list, w.dead_list, w.bands, hi_tab,
+                           idx_pitch, w.arg, per_group, row_len, arg_pitch);
+    hipLaunchKernelGGL(k2_h1f1b_wide, dim3(n_groups), dim3(kFastThreads), h1f1b_lds_bytes(tb.L, cd.S_max, 16), st,
+                       tb, cd, t_max, out, warmup, w.counts, w.live_list, w.dead_list, w.bands, hi_tab, idx_pitch,
+                       w.arg, per_group, row_len, arg_pitch);
 }
 
 }  // namespace harp
