@@ -187,7 +187,7 @@ size_t harp_plan_workspace_bytes(harp_ctx *ctx, const harp_tables *tables,
                                  const harp_candidates *cands);
 
 /* The search itself (section 5.2.3 recurrence per candidate, back-pointers, backtrack, and the
- * score of section 5.2.2), one workgroup per candidate.  A candidate is HARP_CAND_INVALID when
+ * score of section 5.2.2), one wavefront or workgroup per candidate.  A candidate is HARP_CAND_INVALID when
  * S is outside 1..S_max, a group id or degree is not allowed, a group's slots are not adjacent
  * or use more devices than the group has; HARP_CAND_INFEASIBLE when S > L or no partition fits
  * in memory.  workspace: DEVICE, 256-byte aligned, >= harp_plan_workspace_bytes; contents are
