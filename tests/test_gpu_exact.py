@@ -213,6 +213,21 @@ def test_exact_full_finegrained_batch_both_paths_and_sample(harp, ctx):
     assert_plans_equal(sub, want, "finegrained exact sample")
 
 
+def test_exact_stress_sample_both_paths(harp, ctx):
+    """Every 16th candidate of the stress batch through the exact search on both kernel paths, which
+    share no search code: identical plans and pass counts.  About one candidate in sixteen there has
+    a stage too wide for a wavefront's share of LDS and takes the 32-bit path's second launch, and
+    candidates of every width meet the int64 kernels."""
+    w = W.make("stress")
+    idx = np.arange(0, w.C, 16, dtype=np.int64)
+    cands = w.candidates().take(idx)
+    fast, n_fast, _ = harp.plan_exact(ctx, w.problem, cands, harp.PATH_FAST32)
+    gen, n_gen, _ = harp.plan_exact(ctx, w.problem, cands, harp.PATH_GENERIC)
+    assert_plans_equal(fast, gen, "stress exact, 32-bit against int64 path")
+    assert (n_fast == n_gen).all()
+    assert (fast.status == oracle.OK).sum() > 8000
+
+
 def test_exact_full_stress_batch_properties(harp, ctx):
     """The whole stress batch in the launch configuration the benchmark times: what must hold for
     every candidate whatever its size."""

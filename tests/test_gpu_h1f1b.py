@@ -265,6 +265,23 @@ def test_caps_beyond_the_accepted_range_are_invalid(harp, ctx):
     assert list(tw.status) == [1, 2]
 
 
+def test_h1f1b_stress_sample_both_paths(harp, ctx):
+    """Every 16th candidate of the stress batch, at the caps the exact search finds, through the
+    H-1F1B recurrence on both kernel paths, which share no code: identical plans and warm-up counts.
+    A third of these candidates have a slot too wide for a wavefront's share of LDS and take the
+    32-bit path's second launch."""
+    w = W.make("stress")
+    idx = np.arange(0, w.C, 16, dtype=np.int64)
+    cands = w.candidates().take(idx)
+    exact, _, _ = harp.plan_exact(ctx, w.problem, cands)
+    caps = np.where(exact.status == oracle.OK, exact.bottleneck, 0).astype(np.int64)
+    fast, _ = harp.plan_h1f1b(ctx, w.problem, cands, caps, harp.PATH_FAST32)
+    gen, _ = harp.plan_h1f1b(ctx, w.problem, cands, caps, harp.PATH_GENERIC)
+    assert_plans_equal(fast, gen, "stress H-1F1B, 32-bit against int64 path")
+    assert (fast.warmup == gen.warmup).all()
+    assert (fast.status == oracle.OK).any() and (fast.status != oracle.OK).any()
+
+
 def test_h1f1b_full_stress_batch_properties(harp, ctx):
     """The whole stress batch at the caps the exact search found, in the launch configuration the
     benchmark times: what must hold for every candidate whatever its size."""
