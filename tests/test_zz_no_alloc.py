@@ -6,6 +6,8 @@ the array (the second with a smaller batch of another shape, so that whatever th
 behind is still there), on both kernel paths; it must not allocate device memory; and it must refuse
 a batch whose workspace cannot fit.
 """
+import gc
+
 import numpy as np
 import pytest
 
@@ -51,9 +53,15 @@ def test_static_scratch_matches_workspace_entry_point(harp, ctx, path_name):
             out = harp.DevicePlans(ctx, dc.C, dc.S_max)
             out.poison()
             torch.cuda.synchronize()
-            before = torch.cuda.memory_allocated(ctx.device)
-            harp.harp_plan_batch_static(ctx, tables, dc, out)
-            assert torch.cuda.memory_allocated(ctx.device) == before     # nothing came from torch's allocator
+            # no collection of earlier tests' garbage (which would free tensors) between the two readings
+            gc.collect()
+            gc.disable()
+            try:
+                before = torch.cuda.memory_allocated(ctx.device)
+                harp.harp_plan_batch_static(ctx, tables, dc, out)
+                assert torch.cuda.memory_allocated(ctx.device) == before     # nothing came from torch's allocator
+            finally:
+                gc.enable()
             torch.cuda.synchronize()
             assert_plans_equal(out.to_host(), want, "%s static, path %s" % (name, path_name))
     finally:
