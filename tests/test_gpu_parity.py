@@ -80,8 +80,10 @@ def test_tables_match_oracle_long_rows(harp, ctx):
 def test_tables_match_oracle_operator_level(harp, ctx):
     """The long-sequence problem of the streaming measurement at a length the oracle finishes in
     seconds: 300,001 operators = 1,171 full wavefront runs and a ragged tail, 138 rows, built by
-    the chunk-major kernels; and 100,003 operators, built by the row-parallel ones."""
-    for L in (300001, 100003):
+    the chunk-major kernels; 262,144, their shortest sequence, which ends with a full run (the last
+    table entry then lies one past the last run's window of stores); and 100,003 operators, built by
+    the row-parallel ones."""
+    for L in (300001, 262144, 100003):
         _check_operator_level(harp, ctx, L)
     # groups whose own links differ (every third one alike): the chunk-major kernels reuse a row only
     # when the one walked just before it has the same link speed and degree
