@@ -90,6 +90,23 @@ def test_tables_match_oracle_operator_level(harp, ctx):
     _check_operator_level(harp, ctx, 270001, own_links=lambda g: 400_000 - 1000 * (g % 3) - (17 * g if g > 20 else 0))
 
 
+def test_tables_beyond_a_million_operators(harp, ctx):
+    """1,100,003 operators, 7 table rows: more than 4,096 runs of 256 operators per row, so a thread of
+    the scan over the run sums takes more sums than it keeps in registers; and few enough rows that a
+    launch has a single row part."""
+    rng = np.random.default_rng(77)
+    L = 1_100_003
+    fwd = rng.integers(1, 3000, size=(1, L))
+    p = simple_problem(np.zeros(L), M=4, T=1, G=2, ndev=(4, 4), tp=(1, 2), fwd=fwd, bwd=2 * fwd,
+                       params=rng.integers(0, 1 << 22, size=L), stash=rng.integers(0, 1 << 18, size=L),
+                       act=rng.integers(0, 1 << 26, size=L), bw=[[40000, 125], [125, 35000]])
+    want = oracle.build_tables(p)
+    tables = harp.Tables(ctx, p)
+    PF, PP, PS, PR = tables.host_copies()
+    assert (PF == want.PF).all() and (PP == want.PP).all() and (PS == want.PS).all()
+    assert (PR == want.PR).all()
+
+
 def _check_operator_level(harp, ctx, L, own_links=None):
     p = W.long_sequence(L)
     if own_links is not None:
