@@ -223,6 +223,13 @@ def _verdict_cases():
     add("other links beyond int64 / tp", simple_problem([1, 1], G=2, ndev=(8, 8), tp=(1, 8), act=[9, 9], bw=two(7, top)))
     add("own link beyond int64 / tp without tensor parallelism",
         simple_problem([1, 1], G=2, ndev=(8, 8), tp=(1,), act=[9, 9], bw=two(top, 7)))
+    # the slowest of 400 links (20 groups) decides the largest transfer time
+    slow = np.full((20, 20), 1 << 20, dtype=np.int64)
+    slow[19, 18] = slow[18, 19] = 1
+    add("transfer over the slowest of 400 links at the limit",
+        simple_problem([1, 1], G=20, ndev=(1,) * 20, act=[(1 << 47) - 1, 5], bw=slow))
+    add("transfer over the slowest of 400 links beyond",
+        simple_problem([1, 1], G=20, ndev=(1,) * 20, act=[1 << 47, 5], bw=slow))
     return cases
 
 
