@@ -373,7 +373,10 @@ int harp_score_h1f1b(harp_ctx *ctx, harp_tables *tables, const harp_candidates *
 /* Scores caller-chosen partitions with eq. gpipe_cost_model (section 5.2.2):
  * splits DEVICE [C][S_max+1].  Status HARP_CAND_INVALID when the candidate is malformed or its
  * cuts are not strictly increasing from 0 to L; HARP_CAND_INFEASIBLE when a stage does not fit
- * in memory; times are HARP_INF unless the status is HARP_CAND_OK. */
+ * in memory; times are HARP_INF unless the status is HARP_CAND_OK.  Kernel selection as for
+ * harp_plan_batch (harp_set_plan_path; the kernel for the 32-bit rows takes S_max <= 64, larger
+ * batches run on the int64 one; identical results; HARP_ERR_UNIMPLEMENTED when HARP_PATH_FAST32 is
+ * set and the tables have no 32-bit rows). */
 int harp_score_1f1b(harp_ctx *ctx, harp_tables *tables, const harp_candidates *cands,
                     const int32_t *splits, int64_t *bottleneck, int64_t *iter_time,
                     int32_t *status, void *hip_stream);

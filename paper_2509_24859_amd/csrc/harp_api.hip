@@ -731,7 +731,10 @@ int harp_score_1f1b(harp_ctx *ctx, harp_tables *t, const harp_candidates *cd, co
     hipError_t e = hipSetDevice(ctx->device);
     if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
     const CandDev c = { cd->C, cd->S_max, cd->cand_S, cd->cand_group, cd->cand_tp };
-    launch_score(t->dev, c, splits, bottleneck, iter_time, status, static_cast<hipStream_t>(hip_stream));
+    if (ctx->plan_path == HARP_PATH_FAST32 && !t->fast32)
+        return fail(ctx, HARP_ERR_UNIMPLEMENTED, "these tables have no 32-bit rows");
+    launch_score(t->dev, c, splits, bottleneck, iter_time, status, t->fast32 && ctx->plan_path != HARP_PATH_GENERIC,
+                 ctx->n_cu, static_cast<hipStream_t>(hip_stream));
     e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(ctx, e, "launching the scorer kernel");
     return HARP_OK;

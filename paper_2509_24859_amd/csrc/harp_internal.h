@@ -126,7 +126,8 @@ constexpr int kIndexMaxL = 16383;       // its build keeps one 8-byte sum per cu
 void launch_plan_exact(const TablesDev &tb, const CandDev &cd, const PlansDev &out, int32_t *n_passes,
                        void *ws, int n_groups, int n_slices, int n_cu, hipStream_t st);
 void launch_score(const TablesDev &tb, const CandDev &cd, const int32_t *splits,
-                  int64_t *bottleneck, int64_t *iter_time, int32_t *status, hipStream_t st);
+                  int64_t *bottleneck, int64_t *iter_time, int32_t *status, bool fast32, int n_cu,
+                  hipStream_t st);
 void launch_valu_int32(int blocks, int iters, uint32_t *sink, hipStream_t st);
 void launch_argmin(int32_t C, const int64_t *iter_time, const int32_t *status, int64_t *best_time,
                    int32_t *best_index, hipStream_t st);

@@ -2,6 +2,11 @@
 //
 // k3_score: iteration time of caller-chosen partitions under the cost model of the paper's
 // section 5.2.2 (eq. gpipe_cost_model), one wavefront per candidate, lanes over stages.
+// k3_score_fast is the same for tables with the 32-bit rows and at most 64 stages: the work is a
+// few gathers per candidate, so the kernel is a chain of memory round trips, and this form has
+// three of them where the general one has seven (everything whose address depends on nothing is
+// loaded first, for the next candidate while the current one is worked; the slot list is checked in
+// registers; stage and transfer times come from the fused 32-bit rows, without divisions).
 // k4_argmin: final selection of section 5.2.3 (the min over evaluated candidates), lowest
 // candidate index on ties.  Both are O(C S) bytes of streaming work.
 #include "harp_internal.h"
@@ -26,6 +31,121 @@ __global__ __launch_bounds__(64) void k3_score(TablesDev tb, CandDev cd, const i
             st = wave_score_partition(tb, S, slots.g, slots.k, splits + int64_t(c) * (S_max + 1),
                                       threadIdx.x, bott, iter);
         if (threadIdx.x == 0) {
+            bottleneck[c] = bott;
+            iter_time[c] = iter;
+            status[c] = st;
+        }
+    }
+}
+
+constexpr int kScoreWaves = 4;       // independent wavefronts per workgroup of k3_score_fast
+
+__global__ __launch_bounds__(kScoreWaves * 64) void k3_score_fast(TablesDev tb, CandDev cd, const int32_t *splits,
+                                                                  int64_t *bottleneck, int64_t *iter_time,
+                                                                  int32_t *status, uint32_t shift_packed) {
+    const int lane = threadIdx.x & 63;
+    const int wave_id = blockIdx.x * kScoreWaves + (threadIdx.x >> 6), n_waves = gridDim.x * kScoreWaves;
+    const int S_max = cd.S_max, L = tb.L;
+    const int64_t *PP = tb.PP(), *PS = tb.PS();
+    // what a candidate's work starts from: its stage count and, lane s, slot s and the cuts s, s + 1
+    struct First { int S, g, tp, j, i; };
+    auto load_first = [&](int c) -> First {
+        First f{0, -1, 0, 0, 0};
+        if (c < cd.C) {
+            f.S = cd.cand_S[c];
+            if (lane < S_max) {
+                f.g = cd.cand_group[int64_t(c) * S_max + lane];
+                f.tp = cd.cand_tp[int64_t(c) * S_max + lane];
+                f.j = splits[int64_t(c) * (S_max + 1) + lane];
+                f.i = splits[int64_t(c) * (S_max + 1) + lane + 1];
+            }
+        }
+        return f;
+    };
+    First next = load_first(wave_id);
+    for (int c = wave_id; c < cd.C; c += n_waves) {
+        const First f = next;
+        next = load_first(c + n_waves);
+        const int S = __builtin_amdgcn_readfirstlane(f.S);
+        const int g = f.g, j = f.j, i = f.i;
+        int st = HARP_CAND_OK;
+        int64_t bott = kInf, iter = kInf;
+        const bool mine = lane < S;
+        int k = -1;
+        for (int q = 0; q < tb.n_tp; ++q)
+            if (tb.tp[q] == f.tp) k = q;
+        // Second round trip: everything the checks and the score read, requested at once with indices
+        // forced into range (a candidate that fails a check ignores what comes back).
+        const int g_next = __shfl_down(g, 1, 64);
+        const bool slot_ok = g >= 0 && g < tb.G && k >= 0;
+        const int gs = slot_ok ? g : 0, ks = slot_ok ? k : 0;
+        const int gn = (g_next >= 0 && g_next < tb.G) ? g_next : 0;
+        const int is = i < 0 ? 0 : (i > L ? L : i), js = j < 0 ? 0 : (j > L ? L : j);
+        const int ndev = tb.group_ndev[gs];
+        const int type = tb.group_type[gs];
+        const uint32_t *p = tb.P32 + (int64_t(gs) * tb.n_tp + ks) * tb.pitch32;
+        const uint32_t pi = p[is], pj = p[js];
+        const uint32_t cut_here = tb.CM[(int64_t(gs) * tb.G + gn) * tb.pitch32 + is];
+        const int64_t dpp = PP[is] - PP[js], dps = PS[is] - PS[js];
+        if (S < 1 || S > S_max) {
+            st = HARP_CAND_INVALID;
+        } else if (__any(mine && !slot_ok)) {
+            st = HARP_CAND_INVALID;
+        } else {
+            // runs of slots on one group: a group must not be entered twice, nor give more devices than it has
+            const int g_prev = __shfl_up(g, 1, 64);
+            const bool start = mine && (lane == 0 || g_prev != g);
+            const unsigned long long starts = __ballot(start);
+            int bad = 0;
+            for (unsigned long long m = starts; m != 0; m &= m - 1) {
+                const int q = __ffsll((long long)m) - 1;
+                const int gq = __builtin_amdgcn_readlane(g, q);
+                if (start && q < lane && gq == g) bad = 1;
+            }
+            long long upto = mine ? f.tp : 0;              // devices of slots 0 .. lane
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                const long long o = __shfl_up(upto, d, 64);
+                if (lane >= d) upto += o;
+            }
+            const unsigned long long later = lane < 63 ? starts >> (lane + 1) : 0ull;
+            const int end = later != 0 ? lane + __ffsll((long long)later) - 1 : S - 1;    // last slot of this run
+            const long long upto_end = __shfl(upto, end, 64);
+            const long long before = __shfl_up(upto, 1, 64);
+            if (start && upto_end - (lane > 0 ? before : 0) > ndev) bad = 1;
+            if (__any(bad)) st = HARP_CAND_INVALID;
+        }
+        if (st == HARP_CAND_OK) {
+            // the cuts rise strictly from 0 to L
+            int invalid = (lane == 0 && j != 0) || (lane == S - 1 && i != L) || (mine && i <= j);
+            if (__any(invalid)) st = HARP_CAND_INVALID;
+        }
+        if (st == HARP_CAND_OK) {
+            uint32_t time = 0, cu = 0;
+            int unfit = 0;
+            if (mine) {
+                const int shift = int((shift_packed >> (4 * k)) & 15u);
+                if (lane < S - 1) cu = cut_here;
+                const int64_t n_inflight = (S - lane) < tb.M ? (S - lane) : tb.M;
+                if (dpp + n_inflight * dps > int64_t(f.tp) * tb.type_mem[type]) unfit = 1;
+                time = (pi + (1u << shift) - 1u - pj) >> shift;
+            }
+            if (__any(unfit)) {
+                st = HARP_CAND_INFEASIBLE;
+            } else {
+                uint32_t worst = time > cu ? time : cu;
+                int64_t single = int64_t(time) + 2 * int64_t(cu);
+#pragma unroll
+                for (int d = 32; d >= 1; d >>= 1) {
+                    const uint32_t ow = __shfl_xor(worst, d, 64);
+                    single += __shfl_xor(single, d, 64);
+                    worst = worst > ow ? worst : ow;
+                }
+                bott = int64_t(worst);
+                iter = single + int64_t(tb.M - 1) * int64_t(worst);
+            }
+        }
+        if (lane == 0) {
             bottleneck[c] = bott;
             iter_time[c] = iter;
             status[c] = st;
@@ -214,9 +334,21 @@ __global__ __launch_bounds__(kArgminWideThreads) void k4_argmin_index(int32_t C,
 
 }  // namespace
 
+// fast32: the tables have the 32-bit rows and the caller has not asked for the int64 kernels.
 void launch_score(const TablesDev &tb, const CandDev &cd, const int32_t *splits,
-                  int64_t *bottleneck, int64_t *iter_time, int32_t *status, hipStream_t st) {
+                  int64_t *bottleneck, int64_t *iter_time, int32_t *status, bool fast32, int n_cu,
+                  hipStream_t st) {
     if (cd.C == 0) return;
+    if (fast32 && cd.S_max <= 64) {
+        uint32_t shift_packed = 0;
+        for (int k = 0; k < tb.n_tp; ++k) shift_packed |= uint32_t(tb.tp_shift[k] & 15) << (4 * k);
+        int groups = n_cu * (32 / kScoreWaves);                  // as many wavefronts as the chip holds
+        const int want = (cd.C + kScoreWaves - 1) / kScoreWaves;
+        if (groups > want) groups = want;
+        hipLaunchKernelGGL(k3_score_fast, dim3(groups), dim3(kScoreWaves * 64), 0, st, tb, cd, splits, bottleneck,
+                           iter_time, status, shift_packed);
+        return;
+    }
     const int groups = cd.C < (1 << 20) ? cd.C : (1 << 20);
     hipLaunchKernelGGL(k3_score, dim3(groups), dim3(64), 0, st, tb, cd, splits, bottleneck,
                        iter_time, status);

@@ -588,12 +588,74 @@ def test_score_parity_on_arbitrary_partitions(harp, ctx):
         b = torch.full((n,), -7, dtype=torch.int64, device=ctx.device)
         t = torch.full((n,), -7, dtype=torch.int64, device=ctx.device)
         st = torch.full((n,), -7, dtype=torch.int32, device=ctx.device)
-        harp.harp_score_1f1b(ctx, tables, dc, sp, b, t, st)
-        torch.cuda.synchronize()
-        assert (st.cpu().numpy() == want[2]).all()
-        assert (b.cpu().numpy() == want[0]).all() and (t.cpu().numpy() == want[1]).all()
+        for path in (harp.PATH_AUTO, harp.PATH_GENERIC):        # the kernel for the 32-bit tables, the int64 one
+            b.fill_(-7); t.fill_(-7); st.fill_(-7)
+            ctx.set_plan_path(path)
+            try:
+                harp.harp_score_1f1b(ctx, tables, dc, sp, b, t, st)
+                torch.cuda.synchronize()
+            finally:
+                ctx.set_plan_path(harp.PATH_AUTO)
+            assert (st.cpu().numpy() == want[2]).all()
+            assert (b.cpu().numpy() == want[0]).all() and (t.cpu().numpy() == want[1]).all()
         seen |= set(int(x) for x in np.unique(want[2]))
     assert seen == {0, 1, 2}
+
+
+def test_score_checks_the_slot_lists_on_both_paths(harp, ctx):
+    """The scorer's own checks of a candidate (stage count, group ids, degrees, a group entered twice,
+    more devices than a group has) and of a partition, on the kernel for the 32-bit tables and on the
+    int64 one, against the oracle; S_max = 64 and 65 (the first kernel takes at most 64 stages)."""
+    import torch
+    rng = np.random.default_rng(12)
+    L = 90
+    p = simple_problem(np.zeros(L), M=5, T=2, G=4, ndev=(4, 2, 8, 4), tp=(1, 2, 4),
+                       fwd=rng.integers(1, 500, size=(2, L)), bwd=rng.integers(1, 900, size=(2, L)),
+                       act=rng.integers(0, 10**5, size=L), params=rng.integers(0, 1000, size=L),
+                       stash=rng.integers(0, 100, size=L), gtype=[0, 1, 1, 0], mem=[30000, 20000],
+                       bw=[[900, 7, 9, 5], [7, 800, 6, 4], [9, 6, 700, 3], [5, 4, 3, 950]])
+    lists = [
+        [(0, 2), (0, 2), (1, 1), (2, 4)],           # fine
+        [(0, 2), (1, 1), (0, 2)],                   # group 0 entered twice
+        [(1, 1), (1, 1), (1, 1)],                   # three devices of a group of two
+        [(2, 4), (2, 4), (3, 1)],                   # exactly the devices of group 2
+        [(2, 4), (2, 4), (2, 1)],                   # one too many
+        [(0, 3), (1, 1)],                           # a degree that is not allowed
+        [(4, 1), (1, 1)],                           # a group that does not exist
+        [(-1, 1), (1, 1)],
+        [(3, 4)],                                   # a single stage
+        [(3, 1), (3, 1), (3, 1), (3, 1), (0, 1), (0, 1), (0, 1), (0, 1), (2, 2), (2, 2), (2, 2), (2, 2), (1, 2)],
+    ]
+    for S_max in (64, 65):
+        cands = cands_from_lists(lists * 3, S_max=S_max)
+        cands.cand_S[len(lists)] = 0                # no stage
+        cands.cand_S[len(lists) + 3] = S_max + 1    # more stages than the arrays hold
+        n = cands.C
+        splits = np.full((n, S_max + 1), -1, dtype=np.int32)
+        for c in range(n):
+            S = int(cands.cand_S[c])
+            if 1 <= S <= S_max:
+                cut = np.sort(rng.choice(np.arange(1, L), size=S - 1, replace=False))
+                splits[c, :S + 1] = [0, *cut, L]
+        splits[2 * len(lists), 1] = 0               # a fine slot list with cuts that do not rise
+        want = oracle.score_1f1b(oracle.build_tables(p), cands, splits)
+        assert set(int(x) for x in np.unique(want[2])) == {0, 1, 2} or set(int(x) for x in np.unique(want[2])) == {0, 2}
+        tables = harp.Tables(ctx, p)
+        assert tables.fast32
+        dc = harp.DeviceCandidates(ctx, cands)
+        sp = torch.from_numpy(splits).to(ctx.device)
+        for path in (harp.PATH_AUTO, harp.PATH_GENERIC):
+            b = torch.full((n,), -7, dtype=torch.int64, device=ctx.device)
+            t = torch.full((n,), -7, dtype=torch.int64, device=ctx.device)
+            st = torch.full((n,), -7, dtype=torch.int32, device=ctx.device)
+            ctx.set_plan_path(path)
+            try:
+                harp.harp_score_1f1b(ctx, tables, dc, sp, b, t, st)
+                torch.cuda.synchronize()
+            finally:
+                ctx.set_plan_path(harp.PATH_AUTO)
+            assert (st.cpu().numpy() == want[2]).all(), (S_max, path, st.cpu().numpy(), want[2])
+            assert (b.cpu().numpy() == want[0]).all() and (t.cpu().numpy() == want[1]).all(), (S_max, path)
 
 
 def test_argmin_parity(harp, ctx):
