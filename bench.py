@@ -28,6 +28,7 @@ LANE_OPS_PER_TRANSITION = {"int64": 26, "u32": 13}
 # sources of the planner kernel; counter-derived figures in profiles/ are quoted only while these are unchanged
 KERNEL_SOURCES = ("k2_fast.hip", "fast_common.h", "plan_common.h", "harp_internal.h")
 COUNTER_FILE = os.path.join(ROOT, "profiles", "plan_batch_stress_counters.json")
+TABLES_COUNTER_FILE = os.path.join(ROOT, "profiles", "tables_streaming_counters.json")
 
 
 def kernel_source_hash():
@@ -50,6 +51,21 @@ def counter_figures(workload, full_batch):
     if rec.get("workload") != workload or rec.get("kernel_source_hash") != kernel_source_hash():
         return None, None
     return rec.get("traffic_bytes_per_call"), rec.get("issued")
+
+
+def tables_traffic(L):
+    """HBM traffic of one table build from the rocprofv3 counter runs recorded in profiles/, quoted only
+    for the length they were taken at and while the kernel source is what it was then."""
+    import hashlib
+    if not os.path.exists(TABLES_COUNTER_FILE):
+        return None
+    with open(TABLES_COUNTER_FILE) as f:
+        rec = json.load(f)
+    with open(os.path.join(ROOT, "paper_2509_24859_amd", "csrc", "k1_tables.hip"), "rb") as f:
+        now = hashlib.sha256(f.read()).hexdigest()[:16]
+    if rec.get("L") != L or rec.get("kernel_source_hash") != now:
+        return None
+    return rec.get("traffic_bytes_per_build")
 
 
 def cpu_baseline(w, cands, gpu_plans, budget_candidates):
@@ -126,7 +142,8 @@ def tables_streaming(ctx, binding, workloads, torch, L, reps=10):
     rate = bytes_alg / (ms * 1e-3)
     return {"kernel": "k1 (chunk sums, chunk-sum scan, row scan, finalize)", "L": p.L, "rows": n_rows,
             "algorithmic_bytes": bytes_alg, "ms_per_build": ms, "bound": "hbm",
-            "achieved": rate / 1e9, "peak": 8000.0, "unit": "GB/s", "frac": rate / 8e12}
+            "achieved": rate / 1e9, "peak": 8000.0, "unit": "GB/s", "frac": rate / 8e12,
+            "traffic": tables_traffic(p.L)}
 
 
 def measured_peaks(ctx, binding, torch):

@@ -164,3 +164,15 @@ def test_recorded_counters_belong_to_the_current_kernel_sources():
     assert 0.5 < issued["k2_fast_valu_issue_utilisation"] <= 1.0
     assert bench.counter_figures("tiny", True) == (None, None)       # another workload: nothing to quote
     assert bench.counter_figures("stress", False) == (None, None)    # part of the batch: nothing to quote
+
+
+def test_recorded_table_build_counters_belong_to_the_current_kernel_source():
+    """The same for the table build: its HBM traffic is quoted from profiles/ only for the length the
+    counters were taken at and while k1_tables.hip is unchanged."""
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    sys.path.insert(0, root)
+    import bench
+    traffic = bench.tables_traffic(1 << 20)
+    assert traffic is not None and 1.317e9 < traffic < 1.7e9      # above the algorithmic bytes, one re-read of the inputs
+    assert bench.tables_traffic(1 << 19) is None
