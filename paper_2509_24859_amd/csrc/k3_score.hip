@@ -86,7 +86,12 @@ __global__ __launch_bounds__(kScoreWaves * 64) void k3_score_fast(TablesDev tb, 
         const uint32_t *p = tb.P32 + (int64_t(gs) * tb.n_tp + ks) * tb.pitch32;
         const uint32_t pi = p[is], pj = p[js];
         const uint32_t cut_here = tb.CM[(int64_t(gs) * tb.G + gn) * tb.pitch32 + is];
-        const int64_t dpp = PP[is] - PP[js], dps = PS[is] - PS[js];
+        // the running sums at a stage's lower cut are those at the upper cut of the stage before it
+        // (cut 0, where they are 0, for the first): when the cuts are not a partition the candidate is
+        // refused and the difference is not used
+        const int64_t pp_i = PP[is], ps_i = PS[is];
+        const int64_t pp_up = __shfl_up(pp_i, 1, 64), ps_up = __shfl_up(ps_i, 1, 64);
+        const int64_t dpp = pp_i - (lane > 0 ? pp_up : 0), dps = ps_i - (lane > 0 ? ps_up : 0);
         if (S < 1 || S > S_max) {
             st = HARP_CAND_INVALID;
         } else if (__any(mine && !slot_ok)) {
