@@ -240,6 +240,12 @@ __device__ __forceinline__ void exact_body(const TablesDev &tb, const CandDev &c
 
             int cur = 0;
             const int wave_first = wave * 64;
+            // Cuts of the previous row with a finite sum lie in [fin_lo, fin_hi] (a wavefront per
+            // candidate keeps track; the workgroup forms use the whole band).  Under a cap most of a
+            // band is out of reach - its cells are infinite - and a scan that starts above fin_hi or
+            // runs below fin_lo would only read infinite sums: clamping the scans to the finite range
+            // changes no value and ends them at once for cells the cap has cut off.
+            int fin_lo = 0, fin_hi = 0;
             for (int s = 0; s < S - 1; ++s) {
                 const uint32_t b1 = (uint32_t)uniform((int)band[s + 1]);
                 const uint32_t b2 = (uint32_t)uniform((int)band[s + 2]);
@@ -255,6 +261,9 @@ __device__ __forceinline__ void exact_body(const TablesDev &tb, const CandDev &c
                 const uint32_t tp = 1u << shift;
                 const uint32_t b0 = (uint32_t)uniform((int)band[s]);
                 const int jl = band_lo(b0), jh = band_hi(b0);     // predecessors: row s
+                const int jl_f = kBandRows && fin_lo > jl ? fin_lo : jl;
+                const int jh_f = kBandRows && fin_hi < jh ? fin_hi : jh;
+                int my_lo = INT32_MAX, my_hi = -1;                 // this lane's cells of row s + 1 with a finite sum
                 const uint32_t *cm_s = tb.CM + (rs & kRowMask);
                 const uint16_t *lo_s = lo_tab + (uint32_t)uniform((int)lo_off[s]);
                 const uint16_t *lo_n_row = lo_tab + (uint32_t)uniform((int)lo_off[s + 1]);
@@ -293,11 +302,11 @@ __device__ __forceinline__ void exact_body(const TablesDev &tb, const CandDev &c
                 // stage time never decreases as j moves down, so the last entry of a trip decides
                 // whether the lane goes on.  Equal sums keep the lowest j.
                 auto cell = [&](int i, uint32_t cut, int lo_idx) -> int {
-                    const int lo = lo_idx > jl ? lo_idx : jl;
+                    const int lo = lo_idx > jl_f ? lo_idx : jl_f;
                     const uint32_t xi = prev[i].p + tp - 1;
                     SumT best = kInfSum;
                     int best_j = 0;
-                    int j = (i - 1) < jh ? (i - 1) : jh;
+                    int j = (i - 1) < jh_f ? (i - 1) : jh_f;
                     bool more = (j >= lo) & (cut <= tcap);
                     while (more) {
                         const Pair *pe = prev + (j - 3);
@@ -320,7 +329,10 @@ __device__ __forceinline__ void exact_body(const TablesDev &tb, const CandDev &c
                         j -= 4;
                     }
                     const uint64_t total = uint64_t(best) + 2ull * cut;
-                    next[i].d = (best >= kInfSum || total > uint64_t(limit)) ? kInfSum : SumT(total);
+                    const bool finite = !(best >= kInfSum || total > uint64_t(limit));
+                    next[i].d = finite ? SumT(total) : kInfSum;
+                    my_lo = finite && i < my_lo ? i : my_lo;
+                    my_hi = finite && i > my_hi ? i : my_hi;
                     return best >= kInfSum ? i - 1 : best_j;        // no previous cut: any value, a short one
                 };
                 const int i0 = il + tid;
@@ -339,6 +351,16 @@ __device__ __forceinline__ void exact_body(const TablesDev &tb, const CandDev &c
                 cut_i = cut_n;
                 lo_i = lo_n;
                 if (i0 <= ih) put_arg(i0, first_j);
+                if (kBandRows) {
+#pragma unroll
+                    for (int d = 32; d >= 1; d >>= 1) {
+                        const int ol = __shfl_xor(my_lo, d, 64), oh = __shfl_xor(my_hi, d, 64);
+                        my_lo = ol < my_lo ? ol : my_lo;
+                        my_hi = oh > my_hi ? oh : my_hi;
+                    }
+                    fin_hi = uniform(my_hi);
+                    fin_lo = fin_hi < 0 ? L + 1 : uniform(my_lo);      // no finite cell: an empty range
+                }
                 lds_barrier();
                 cur ^= 1;
             }
@@ -350,9 +372,13 @@ __device__ __forceinline__ void exact_body(const TablesDev &tb, const CandDev &c
                 const uint32_t b0 = (uint32_t)uniform((int)band[s]);
                 const Pair *prev = (cur ? buf1 : buf0) - (kBandRows ? band_lo(b0) : 0);
                 const uint32_t xi = prev[L].p + tp - 1;
-                const int hi = (L - 1) < band_hi(b0) ? (L - 1) : band_hi(b0);
+                int hi = (L - 1) < band_hi(b0) ? (L - 1) : band_hi(b0);
                 const int lo_L = uniform((int)lo_tab[size_t((uint32_t)uniform((int)lo_off[s])) + L]);
-                const int lo = lo_L > band_lo(b0) ? lo_L : band_lo(b0);
+                int lo = lo_L > band_lo(b0) ? lo_L : band_lo(b0);
+                if (kBandRows && S > 1) {
+                    hi = fin_hi < hi ? fin_hi : hi;
+                    lo = fin_lo > lo ? fin_lo : lo;
+                }
                 unsigned long long best = kInfSum;
                 int best_j = INT32_MAX;
                 for (int j = lo + lane; j <= hi; j += 64) {
