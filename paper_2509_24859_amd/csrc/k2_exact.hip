@@ -263,7 +263,7 @@ __device__ __forceinline__ void exact_body(const TablesDev &tb, const CandDev &c
                 const int jl = band_lo(b0), jh = band_hi(b0);     // predecessors: row s
                 const int jl_f = kBandRows && fin_lo > jl ? fin_lo : jl;
                 const int jh_f = kBandRows && fin_hi < jh ? fin_hi : jh;
-                int my_lo = INT32_MAX, my_hi = -1;                 // this lane's cells of row s + 1 with a finite sum
+                int new_lo = INT32_MAX, new_hi = -1;               // cells of row s + 1 with a finite sum (wavefront form)
                 const uint32_t *cm_s = tb.CM + (rs & kRowMask);
                 const uint16_t *lo_s = lo_tab + (uint32_t)uniform((int)lo_off[s]);
                 const uint16_t *lo_n_row = lo_tab + (uint32_t)uniform((int)lo_off[s + 1]);
@@ -331,8 +331,17 @@ __device__ __forceinline__ void exact_body(const TablesDev &tb, const CandDev &c
                     const uint64_t total = uint64_t(best) + 2ull * cut;
                     const bool finite = !(best >= kInfSum || total > uint64_t(limit));
                     next[i].d = finite ? SumT(total) : kInfSum;
-                    my_lo = finite && i < my_lo ? i : my_lo;
-                    my_hi = finite && i > my_hi ? i : my_hi;
+                    if (kBandRows) {
+                        // lanes hold consecutive cells from i - tid on: the lowest and the highest lane with
+                        // a finite sum bound this round's cells
+                        const unsigned long long fm = __ballot(finite);
+                        if (fm != 0) {
+                            const int base = uniform(i - tid);
+                            const int lo_r = base + __ffsll((long long)fm) - 1, hi_r = base + 63 - __clzll((long long)fm);
+                            new_lo = lo_r < new_lo ? lo_r : new_lo;
+                            new_hi = hi_r > new_hi ? hi_r : new_hi;
+                        }
+                    }
                     return best >= kInfSum ? i - 1 : best_j;        // no previous cut: any value, a short one
                 };
                 const int i0 = il + tid;
@@ -352,14 +361,9 @@ __device__ __forceinline__ void exact_body(const TablesDev &tb, const CandDev &c
                 lo_i = lo_n;
                 if (i0 <= ih) put_arg(i0, first_j);
                 if (kBandRows) {
-#pragma unroll
-                    for (int d = 32; d >= 1; d >>= 1) {
-                        const int ol = __shfl_xor(my_lo, d, 64), oh = __shfl_xor(my_hi, d, 64);
-                        my_lo = ol < my_lo ? ol : my_lo;
-                        my_hi = oh > my_hi ? oh : my_hi;
-                    }
-                    fin_hi = uniform(my_hi);
-                    fin_lo = fin_hi < 0 ? L + 1 : uniform(my_lo);      // no finite cell: an empty range
+                    // lane 0 has a cell in every round that any lane has one in: its copy is complete
+                    fin_hi = uniform(new_hi);
+                    fin_lo = fin_hi < 0 ? L + 1 : uniform(new_lo);     // no finite cell: an empty range
                 }
                 lds_barrier();
                 cur ^= 1;

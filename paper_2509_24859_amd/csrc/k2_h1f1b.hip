@@ -208,11 +208,18 @@ __device__ __forceinline__ void h1f1b_body(const TablesDev &tb, const CandDev &c
         lds_barrier();
         int cur = 0, pcur = 0;
         const int wave_first = wave * 64;
+        // Continuations with a finite sum lie in [fin_lo, fin_hi] (a wavefront per candidate keeps
+        // track; the workgroup forms use the whole band): scans are clamped to that range, which
+        // changes no value, and a row without a finite sum ends the candidate - no plan - at once.
+        int fin_lo = L, fin_hi = L;
         for (int slot = S - 1; slot >= 0; --slot) {
             const uint32_t b0 = (uint32_t)uniform((int)band[slot]);
             const uint32_t b1 = (uint32_t)uniform((int)band[slot + 1]);
             const int il = slot == 0 ? 0 : band_lo(b0), ih = slot == 0 ? 0 : band_hi(b0);   // cells
             const int jl = band_lo(b1), jh = band_hi(b1);                                     // continuations
+            const int jl_f = kBandRows && fin_lo > jl ? fin_lo : jl;
+            const int jh_f = kBandRows && fin_hi < jh ? fin_hi : jh;
+            int new_lo = INT32_MAX, new_hi = -1;        // cells of this slot with a finite sum (wavefront form)
             // what the slot in front will read of its own time row: its cells and this slot's cells
             const int nl = slot >= 2 ? band_lo((uint32_t)uniform((int)band[slot - 1])) : 0;
             const bool stage_next = slot >= 1;
@@ -253,10 +260,10 @@ __device__ __forceinline__ void h1f1b_body(const TablesDev &tb, const CandDev &c
                 SumT best = kInfSum;
                 uint32_t best_n = 0;
                 int best_j = 0;
-                int j = (i + 1) > jl ? (i + 1) : jl;
+                int j = (i + 1) > jl_f ? (i + 1) : jl_f;
                 // end cuts beyond the classic count's reach cannot fit with a larger count either
                 const int reach = hi_row[i];
-                const int end = reach < jh ? reach : jh;
+                const int end = reach < jh_f ? reach : jh_f;
                 bool more = j <= end;
                 while (more) {
                     uint32_t tj = 0;
@@ -284,13 +291,34 @@ __device__ __forceinline__ void h1f1b_body(const TablesDev &tb, const CandDev &c
                     const uint64_t total = uint64_t(best) + 2ull * cf;
                     const bool reach = (best < kInfSum) & (cf <= tcap);
                     if (reach & (total > limit)) flags[1] = 1;        // needs 64-bit sums
-                    next[i].h = (reach & (total <= limit)) ? SumT(total) : kInfSum;
+                    const bool finite = reach & (total <= limit);
+                    next[i].h = finite ? SumT(total) : kInfSum;
+                    if (kBandRows) {
+                        // lanes hold consecutive cells from i - tid on: the lowest and the highest lane with
+                        // a finite sum bound this round's cells
+                        const unsigned long long fm = __ballot(finite);
+                        if (fm != 0) {
+                            const int base = uniform(i - tid);
+                            const int lo_r = base + __ffsll((long long)fm) - 1, hi_r = base + 63 - __clzll((long long)fm);
+                            new_lo = lo_r < new_lo ? lo_r : new_lo;
+                            new_hi = hi_r > new_hi ? hi_r : new_hi;
+                        }
+                    }
                     const uint32_t nn = h1f1b_delta(cf, cap64) + best_n;
                     next[i].nn = nn < uint32_t(m_cap) ? nn : uint32_t(m_cap);
                 } else {
                     scal[0] = uint64_t(best);
                 }
                 first_trip = false;
+            }
+            if (kBandRows && stage_next) {
+                // lane 0 has a cell in every round that any lane has one in: its copy is complete
+                fin_lo = uniform(new_lo);
+                fin_hi = uniform(new_hi);
+                if (fin_hi < 0) {                                    // nothing can be continued from here
+                    if (tid == 0) scal[0] = uint64_t(kInfSum);
+                    break;
+                }
             }
             if (stage_next) {
                 if (tid < kTail) next[ih + 1 + tid].h = kInfSum;     // behind the band
