@@ -57,10 +57,10 @@ __device__ __forceinline__ uint32_t h1f1b_delta(uint32_t c, int64_t cap) {
     return 1u + (x > 0 ? 1u : 0u) + (x > cap ? 1u : 0u);
 }
 
-// LDS in front of the rows: per-slot constants, two scalars, band and trial cuts, two flags,
-// index-row offsets, the plan's deltas, slot lists
+// LDS in front of the rows: per-slot constants, two scalars, band and trial cuts, two flags, the
+// wavefronts' ranges of finite sums, index-row offsets, the plan's deltas, slot lists
 __host__ __device__ inline size_t h1f1b_small_bytes(int S_max) {
-    const size_t b = size_t(S_max) * sizeof(StageConst) + 16 + size_t(S_max + 1) * 8 + 8 + size_t(S_max) * 11;
+    const size_t b = size_t(S_max) * sizeof(StageConst) + 16 + size_t(S_max + 1) * 8 + 8 + 64 + size_t(S_max) * 11;
     return (b + 15) & ~size_t(15);
 }
 // bytes per cut of the rows in LDS when every row is sized for one slot: one row of memory sums, two
@@ -99,7 +99,8 @@ __device__ __forceinline__ void h1f1b_body(const TablesDev &tb, const CandDev &c
     uint32_t *flags = reinterpret_cast<uint32_t *>(trial + S_max + 1);                 // [2]: ticket, overflow
     // element offset of each slot's row of the feasibility index: the highest end cut that fits with the
     // classic count of the slot, an outer bound for H-1F1B's (its counts are never below the classic ones)
-    uint32_t *hi_off = flags + 2;                                                      // [S_max]
+    int32_t *fin_w = reinterpret_cast<int32_t *>(flags + 2);                           // [2][4][2]: per slot parity and wavefront, lowest and highest cell with a finite sum
+    uint32_t *hi_off = reinterpret_cast<uint32_t *>(fin_w + 16);                       // [S_max]
     uint32_t *deltas = hi_off + S_max;                                                 // [S_max]
     uint16_t *slot_g = reinterpret_cast<uint16_t *>(deltas + S_max);                   // [S_max]
     uint8_t *slot_k = reinterpret_cast<uint8_t *>(slot_g + S_max);                     // [S_max]
@@ -208,24 +209,49 @@ __device__ __forceinline__ void h1f1b_body(const TablesDev &tb, const CandDev &c
         lds_barrier();
         int cur = 0, pcur = 0;
         const int wave_first = wave * 64;
-        // Continuations with a finite sum lie in [fin_lo, fin_hi] (a wavefront per candidate keeps
-        // track; the workgroup forms use the whole band): scans are clamped to that range, which
-        // changes no value, and a row without a finite sum ends the candidate - no plan - at once.
+        // Continuations with a finite sum lie in [fin_lo, fin_hi]: scans are clamped to that range,
+        // which changes no value, and a row without a finite sum ends the candidate - no plan - at
+        // once.  Every wavefront keeps the range of its own cells (one ballot per round of cells); a
+        // workgroup's wavefronts exchange theirs through LDS at the barrier that ends a slot.
         int fin_lo = L, fin_hi = L;
+        auto end_of_slot = [&](int slot, int new_lo, int new_hi) -> bool {      // true: no continuation is left
+            if (!kBandRows && lane == 0) {
+                fin_w[((slot & 1) * 4 + wave) * 2] = new_lo;
+                fin_w[((slot & 1) * 4 + wave) * 2 + 1] = new_hi;
+            }
+            lds_barrier();
+            if (slot == 0) return false;
+            if (kBandRows) {
+                // lane 0 has a cell in every round that any lane has one in: its copy is complete
+                fin_lo = uniform(new_lo);
+                fin_hi = uniform(new_hi);
+            } else {
+                int lo = INT32_MAX, hi = -1;
+                for (int w = 0; w < int(nthreads >> 6); ++w) {
+                    const int wl = fin_w[((slot & 1) * 4 + w) * 2], wh = fin_w[((slot & 1) * 4 + w) * 2 + 1];
+                    lo = wl < lo ? wl : lo;
+                    hi = wh > hi ? wh : hi;
+                }
+                fin_lo = uniform(lo);
+                fin_hi = uniform(hi);
+            }
+            if (fin_hi < 0 && tid == 0) scal[0] = uint64_t(kInfSum);
+            return fin_hi < 0;
+        };
         for (int slot = S - 1; slot >= 0; --slot) {
             const uint32_t b0 = (uint32_t)uniform((int)band[slot]);
             const uint32_t b1 = (uint32_t)uniform((int)band[slot + 1]);
             const int il = slot == 0 ? 0 : band_lo(b0), ih = slot == 0 ? 0 : band_hi(b0);   // cells
             const int jl = band_lo(b1), jh = band_hi(b1);                                     // continuations
-            const int jl_f = kBandRows && fin_lo > jl ? fin_lo : jl;
-            const int jh_f = kBandRows && fin_hi < jh ? fin_hi : jh;
-            int new_lo = INT32_MAX, new_hi = -1;        // cells of this slot with a finite sum (wavefront form)
+            const int jl_f = fin_lo > jl ? fin_lo : jl;
+            const int jh_f = fin_hi < jh ? fin_hi : jh;
+            int new_lo = INT32_MAX, new_hi = -1;        // this wavefront's cells with a finite sum
             // what the slot in front will read of its own time row: its cells and this slot's cells
             const int nl = slot >= 2 ? band_lo((uint32_t)uniform((int)band[slot - 1])) : 0;
             const bool stage_next = slot >= 1;
             // a wave whose lanes own neither a cell nor a staged entry only keeps the barrier
             if (il + wave_first > ih && (!stage_next || nl + wave_first > ih)) {
-                lds_barrier();
+                if (end_of_slot(slot, INT32_MAX, -1)) break;
                 cur ^= 1;
                 pcur ^= 1;
                 continue;
@@ -293,12 +319,12 @@ __device__ __forceinline__ void h1f1b_body(const TablesDev &tb, const CandDev &c
                     if (reach & (total > limit)) flags[1] = 1;        // needs 64-bit sums
                     const bool finite = reach & (total <= limit);
                     next[i].h = finite ? SumT(total) : kInfSum;
-                    if (kBandRows) {
-                        // lanes hold consecutive cells from i - tid on: the lowest and the highest lane with
+                    {
+                        // lanes hold consecutive cells from i - lane on: the lowest and the highest lane with
                         // a finite sum bound this round's cells
                         const unsigned long long fm = __ballot(finite);
                         if (fm != 0) {
-                            const int base = uniform(i - tid);
+                            const int base = uniform(i - lane);
                             const int lo_r = base + __ffsll((long long)fm) - 1, hi_r = base + 63 - __clzll((long long)fm);
                             new_lo = lo_r < new_lo ? lo_r : new_lo;
                             new_hi = hi_r > new_hi ? hi_r : new_hi;
@@ -311,15 +337,6 @@ __device__ __forceinline__ void h1f1b_body(const TablesDev &tb, const CandDev &c
                 }
                 first_trip = false;
             }
-            if (kBandRows && stage_next) {
-                // lane 0 has a cell in every round that any lane has one in: its copy is complete
-                fin_lo = uniform(new_lo);
-                fin_hi = uniform(new_hi);
-                if (fin_hi < 0) {                                    // nothing can be continued from here
-                    if (tid == 0) scal[0] = uint64_t(kInfSum);
-                    break;
-                }
-            }
             if (stage_next) {
                 if (tid < kTail) next[ih + 1 + tid].h = kInfSum;     // behind the band
                 if (xn <= ih) pr_next[xn] = p_n;
@@ -329,7 +346,7 @@ __device__ __forceinline__ void h1f1b_body(const TablesDev &tb, const CandDev &c
                         mem_next[x] = x <= L ? MemPair{PP[x], PS[x]} : MemPair{0, 0};
                 }
             }
-            lds_barrier();
+            if (end_of_slot(slot, new_lo, new_hi)) break;
             cur ^= 1;
             pcur ^= 1;
         }
@@ -411,7 +428,7 @@ __device__ __forceinline__ void h1f1b_body(const TablesDev &tb, const CandDev &c
         h1f1b_body<SUM, MODE>(tb, cd, t_max, out, warmup, counts, live_list, dead_list, bands, hi_tab, idx_pitch,  \
                               arg_base, arg_per_group, row_len, arg_pitch);                                        \
     }
-HARP_H1F1B_KERNEL(k2_h1f1b, __launch_bounds__(64), uint32_t, 1)
+HARP_H1F1B_KERNEL(k2_h1f1b, __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(5, 5))), uint32_t, 1)
 HARP_H1F1B_KERNEL(k2_h1f1b_rows, __launch_bounds__(kFastThreads) __attribute__((amdgpu_waves_per_eu(8, 8))), uint32_t, 2)
 HARP_H1F1B_KERNEL(k2_h1f1b_wide, __launch_bounds__(kFastThreads), uint64_t, 0)
 #undef HARP_H1F1B_KERNEL
