@@ -456,13 +456,13 @@ void launch_plan_h1f1b(const TablesDev &tb, const CandDev &cd, const int64_t *t_
     const size_t per_group = fast_arg_per_group(tb.L, cd.S_max);
     const int arg_pitch = fast_row_len(tb.L);
     // Wavefronts per CU of the first launch and the row entries their LDS share leaves: as many
-    // wavefronts as hold rows for the whole sequence, between 16 and 24 (measured on the 512-operator
-    // workload, where such rows would leave 7: 12 per CU 14.2 ms, 16 12.7, 20 14.1, 24 16.9 - the
+    // wavefronts as hold rows for the whole sequence, between 14 and 24 (measured on the 512-operator
+    // workload, where such rows would leave 7: 10 per CU 8.9 ms, 12 7.7, 14 7.6, 16 7.9, 20 10.4 - the
     // smaller the share, the more candidates leave for the second launch; on the 160-operator one,
     // where 22 fit: 16 per CU 2.2 ms, 20 2.0).
     const size_t small = h1f1b_small_bytes(cd.S_max);
     int per_cu = int((size_t(160) << 10) / (small + size_t(row_len) * h1f1b_cut_bytes(8) + 128));
-    per_cu = per_cu < 16 ? 16 : (per_cu > 24 ? 24 : per_cu);
+    per_cu = per_cu < 14 ? 14 : (per_cu > 24 ? 24 : per_cu);
     const size_t share = ((size_t(160) << 10) / per_cu - 128) & ~size_t(15);
     int entries = share > small + h1f1b_cut_bytes(8) * 16 ? int((share - small) / h1f1b_cut_bytes(8)) & ~1 : 16;
     if (entries > row_len) entries = row_len;
